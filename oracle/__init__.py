@@ -1,0 +1,274 @@
+"""CPU oracle for the ZeroQuant-HERO W8A8 layer forward (numpy front-end).
+
+TEST INFRASTRUCTURE, NOT PRODUCT CODE: only ``tests/``, ``__graft_entry__.smoke()`` and
+the ``cpu_baseline`` leg of ``bench.py`` may import this package.  It never imports the
+HIP library or its binding, and the HIP library never imports it.
+
+The arithmetic lives in ``hero_oracle.cpp`` (plain C++17, one loop nest per equation of
+the paper); this file only marshals numpy arrays into it.  ``layer.py`` chains the
+operators into the paper's attention + MLP flow and holds the offline preparation
+(calibration, scale folding, weight quantization).
+
+16-bit floats are carried as ``numpy.uint16`` bit patterns (numpy has no bfloat16).
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "hero_oracle.cpp")
+_LIB = os.path.join(_HERE, "libhero_oracle.so")
+
+I8, U8, I32, F16, BF16, F32 = range(6)
+EPI_RAW_I32, EPI_DEQUANT, EPI_DEQUANT_GELU, EPI_REQUANT, EPI_GELU_REQUANT = range(5)
+MASK_NONE, MASK_PADDING, MASK_CAUSAL = range(3)
+
+
+def build(force: bool = False) -> str:
+    """Compile the C++ oracle with g++ (no intrinsics, no fast-math, no contraction)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["g++", "-O2", "-std=c++17", "-fopenmp", "-ffp-contract=off", "-fPIC", "-shared",
+               "-Wall", "-o", _LIB, _SRC]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(build())
+        _lib.orc_f32_to_bf16.restype = C.c_uint16
+        _lib.orc_f32_to_bf16.argtypes = [C.c_float]
+        _lib.orc_bf16_to_f32.restype = C.c_float
+        _lib.orc_bf16_to_f32.argtypes = [C.c_uint16]
+        _lib.orc_f32_to_f16.restype = C.c_uint16
+        _lib.orc_f32_to_f16.argtypes = [C.c_float]
+        _lib.orc_f16_to_f32.restype = C.c_float
+        _lib.orc_f16_to_f32.argtypes = [C.c_uint16]
+        _lib.orc_gelu.restype = C.c_double
+        _lib.orc_gelu.argtypes = [C.c_double]
+        _lib.orc_num_threads.restype = C.c_int
+    return _lib
+
+
+def _p(a):
+    """Pointer to a C-contiguous numpy array (None -> NULL)."""
+    if a is None:
+        return None
+    assert a.flags["C_CONTIGUOUS"], "oracle arrays must be C-contiguous"
+    return a.ctypes.data_as(C.c_void_p)
+
+
+def _i64(x):
+    return C.c_int64(int(x))
+
+
+def num_threads() -> int:
+    return int(lib().orc_num_threads())
+
+
+# ------------------------------------------------------------------ 16-bit formats
+def f32_to_bf16(x: np.ndarray) -> np.ndarray:
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    y = np.empty(x.shape, np.uint16)
+    lib().orc_f32_to_bf16_n(_p(x), _i64(x.size), _p(y))
+    return y
+
+
+def bf16_to_f32(h: np.ndarray) -> np.ndarray:
+    h = np.ascontiguousarray(h, dtype=np.uint16)
+    return (h.astype(np.uint32) << 16).view(np.float32).reshape(h.shape)
+
+
+def f32_to_f16(x: np.ndarray) -> np.ndarray:
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    y = np.empty(x.shape, np.uint16)
+    lib().orc_f32_to_f16_n(_p(x), _i64(x.size), _p(y))
+    return y
+
+
+def f16_to_f32(h: np.ndarray) -> np.ndarray:
+    h = np.ascontiguousarray(h, dtype=np.uint16)
+    y = np.empty(h.shape, np.float32)
+    lib().orc_f16_to_f32_n(_p(h), _i64(h.size), _p(y))
+    return y
+
+
+def hp_to_f32(h: np.ndarray, dt: int) -> np.ndarray:
+    """Decode a stored activation (uint16 bit patterns or float32) to float32."""
+    if dt == F32:
+        return np.asarray(h, dtype=np.float32)
+    if dt == BF16:
+        return bf16_to_f32(h)
+    return f16_to_f32(h)
+
+
+_NP_OF = {I8: np.int8, U8: np.uint8, I32: np.int32, F16: np.uint16, BF16: np.uint16, F32: np.float32}
+
+
+# ------------------------------------------------------------------ O1 / O2
+def quant_twq(x: np.ndarray):
+    """Token-wise dynamic quantization (paper Sec. 2.1, TWQ)."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    M, D = x.shape
+    q = np.empty((M, D), np.int8)
+    s = np.empty((M,), np.float32)
+    lib().orc_quant_twq(_p(x), _i64(M), _i64(D), _p(q), _p(s))
+    return q, s
+
+
+def quant_static(x: np.ndarray, scale) -> np.ndarray:
+    """FWQ (``scale`` a length-D vector) or SQ (``scale`` a python float) quantization."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    M, D = x.shape
+    q = np.empty((M, D), np.int8)
+    if np.ndim(scale) == 0:
+        lib().orc_quant_static(_p(x), _i64(M), _i64(D), None, C.c_float(float(scale)), _p(q))
+    else:
+        cs = np.ascontiguousarray(scale, dtype=np.float32)
+        assert cs.shape == (D,)
+        lib().orc_quant_static(_p(x), _i64(M), _i64(D), _p(cs), C.c_float(0.0), _p(q))
+    return q
+
+
+def weight_quant(W: np.ndarray):
+    """Column-wise weight quantization; W is [K, N]; returns codes [N, K] and scales [N]."""
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    K, N = W.shape
+    Wt = np.empty((N, K), np.int8)
+    s = np.empty((N,), np.float32)
+    lib().orc_weight_quant(_p(W), _i64(K), _i64(N), _p(Wt), _p(s))
+    return Wt, s
+
+
+# ------------------------------------------------------------------ O3 / O4
+def gemm_i32(A: np.ndarray, Bt: np.ndarray) -> np.ndarray:
+    A = np.ascontiguousarray(A, np.int8)
+    Bt = np.ascontiguousarray(Bt, np.int8)
+    M, K = A.shape
+    N, K2 = Bt.shape
+    assert K == K2
+    Cm = np.empty((M, N), np.int32)
+    lib().orc_gemm_i32(_p(A), _i64(K), _p(Bt), _i64(K), _i64(M), _i64(N), _i64(K), _p(Cm))
+    return Cm
+
+
+def gemm_i64(A: np.ndarray, Bt: np.ndarray) -> np.ndarray:
+    A = np.ascontiguousarray(A, np.int8)
+    Bt = np.ascontiguousarray(Bt, np.int8)
+    M, K = A.shape
+    N, _ = Bt.shape
+    Cm = np.empty((M, N), np.int64)
+    lib().orc_gemm_i64(_p(A), _i64(K), _p(Bt), _i64(K), _i64(M), _i64(N), _i64(K), _p(Cm))
+    return Cm
+
+
+def int8_gemm(A, Bt, *, a_row_scale=None, b_col_scale=None, bias=None, residual=None, res_dt=BF16,
+              epi=EPI_RAW_I32, out_col_scale=None, c_dt=I32) -> np.ndarray:
+    """GeMM^quant with its fused epilogue (paper Sec. 2.2.2 / 2.2.3)."""
+    A = np.ascontiguousarray(A, np.int8)
+    Bt = np.ascontiguousarray(Bt, np.int8)
+    M, K = A.shape
+    N, K2 = Bt.shape
+    assert K == K2
+    f32 = lambda a: None if a is None else np.ascontiguousarray(a, np.float32)
+    a_row_scale, b_col_scale, bias, out_col_scale = map(f32, (a_row_scale, b_col_scale, bias, out_col_scale))
+    if residual is not None:
+        residual = np.ascontiguousarray(residual, _NP_OF[res_dt])
+        assert residual.shape == (M, N)
+    Cm = np.empty((M, N), _NP_OF[c_dt])
+    rc = lib().orc_int8_gemm(_p(A), _i64(K), _p(a_row_scale), _p(Bt), _i64(K), _p(b_col_scale), _p(bias),
+                             _p(residual), C.c_int(res_dt), _i64(N), C.c_int(epi), _p(out_col_scale),
+                             _p(Cm), C.c_int(c_dt), _i64(N), _i64(M), _i64(N), _i64(K))
+    if rc != 0:
+        raise ValueError("oracle int8_gemm: invalid epilogue / dtype combination")
+    return Cm
+
+
+# ------------------------------------------------------------------ O5
+def ln_quant(x, x_dt, x_row_scale, r, r_dt, r_col_scale, gamma, beta, eps, y_hp_dt=None):
+    """LN^quant: LayerNorm of the sum of the inputs, token-wise quantized output."""
+    x = np.ascontiguousarray(x, _NP_OF[x_dt])
+    M, D = x.shape
+    f32 = lambda a: None if a is None else np.ascontiguousarray(a, np.float32)
+    x_row_scale, r_col_scale, gamma, beta = map(f32, (x_row_scale, r_col_scale, gamma, beta))
+    if r is not None:
+        r = np.ascontiguousarray(r, _NP_OF[r_dt])
+        assert r.shape == (M, D)
+    y_q = np.empty((M, D), np.int8)
+    y_s = np.empty((M,), np.float32)
+    y_hp = None if y_hp_dt is None else np.empty((M, D), _NP_OF[y_hp_dt])
+    rc = lib().orc_ln_quant(_p(x), C.c_int(x_dt), _p(x_row_scale), _p(r), C.c_int(r_dt if r is not None else 0),
+                            _p(r_col_scale), _p(gamma), _p(beta), C.c_float(eps), _i64(M), _i64(D),
+                            _p(y_q), _p(y_s), _p(y_hp), C.c_int(y_hp_dt if y_hp_dt is not None else 0))
+    if rc != 0:
+        raise ValueError("oracle ln_quant: missing scale for an INT8 input")
+    return y_q, y_s, y_hp
+
+
+# ------------------------------------------------------------------ O6
+def _strides(a: np.ndarray):
+    """Element strides of a 4-d array as an int64[4] ctypes array."""
+    assert a.ndim == 4
+    st = [s // a.itemsize for s in a.strides]
+    return (C.c_int64 * 4)(*st)
+
+
+def int8_attn(q, k, v, *, qk_scale, p_scale, out_col_scale, out_scale_is_scalar=False,
+              mask=MASK_NONE, kv_len=None, out_dt=I8, dump_p=False):
+    """INT8 attention.  q [B,Sq,H,Dh], k/v [B,Skv,H,Dh] int8 (any strides, unit channel stride)."""
+    B, Sq, H, Dh = q.shape
+    Skv = k.shape[1]
+    ocs = np.ascontiguousarray(out_col_scale, np.float32).reshape(-1)
+    if kv_len is not None:
+        kv_len = np.ascontiguousarray(kv_len, np.int32)
+    out = np.empty((B * Sq, H * Dh), _NP_OF[out_dt])
+    pd = np.zeros((B, H, Sq, Skv), np.uint8) if dump_p else None
+    base = lambda a: C.c_void_p(a.ctypes.data)
+    rc = lib().orc_int8_attn(base(q), _strides(q), base(k), _strides(k), base(v), _strides(v),
+                             _i64(B), _i64(H), _i64(Sq), _i64(Skv), _i64(Dh),
+                             C.c_float(qk_scale), C.c_float(p_scale), _p(ocs), C.c_int(int(out_scale_is_scalar)),
+                             C.c_int(mask), _p(kv_len), _p(out), C.c_int(out_dt), _i64(H * Dh), _p(pd))
+    if rc != 0:
+        raise ValueError("oracle int8_attn: invalid arguments")
+    return (out, pd) if dump_p else out
+
+
+# ------------------------------------------------------------------ BF16 side
+def bf16_gemm(A, Wt, bias=None, residual=None, gelu=False) -> np.ndarray:
+    A = np.ascontiguousarray(A, np.uint16)
+    Wt = np.ascontiguousarray(Wt, np.uint16)
+    M, K = A.shape
+    N, _ = Wt.shape
+    if bias is not None:
+        bias = np.ascontiguousarray(bias, np.float32)
+    if residual is not None:
+        residual = np.ascontiguousarray(residual, np.uint16)
+    Cm = np.empty((M, N), np.uint16)
+    lib().orc_bf16_gemm(_p(A), _i64(K), _p(Wt), _i64(K), _p(bias), _p(residual), _i64(N), C.c_int(int(gelu)),
+                        _p(Cm), _i64(N), _i64(M), _i64(N), _i64(K))
+    return Cm
+
+
+def bf16_attn(q, k, v, *, scale, mask=MASK_NONE, kv_len=None) -> np.ndarray:
+    B, Sq, H, Dh = q.shape
+    Skv = k.shape[1]
+    if kv_len is not None:
+        kv_len = np.ascontiguousarray(kv_len, np.int32)
+    out = np.empty((B * Sq, H * Dh), np.uint16)
+    base = lambda a: C.c_void_p(a.ctypes.data)
+    lib().orc_bf16_attn(base(q), _strides(q), base(k), _strides(k), base(v), _strides(v),
+                        _i64(B), _i64(H), _i64(Sq), _i64(Skv), _i64(Dh), C.c_float(scale),
+                        C.c_int(mask), _p(kv_len), _p(out), _i64(H * Dh))
+    return out
+
+
+def gelu(x: float) -> float:
+    return float(lib().orc_gelu(float(x)))

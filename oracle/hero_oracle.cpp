@@ -1,0 +1,424 @@
+// CPU oracle for the ZeroQuant-HERO W8A8 layer operators.
+//
+// TEST INFRASTRUCTURE, NOT PRODUCT CODE.  Only the test-suite, the smoke check and
+// the benchmark's cpu_baseline leg may build, load or call this file.  It shares no
+// code, header, table or helper with the HIP library; every routine is the paper's
+// definition written out in the plainest way (one loop nest per equation, fp64 for
+// LayerNorm / softmax / GELU, exact integers for the contractions), so that it can be
+// checked against the paper by eye.  All pointers are HOST pointers.
+//
+// Conventions (paper Sec. 2.1 only says "symmetric uniform INT8"; the rest is this
+// build's reading, listed with its reasons in the design document):
+//   * codes in [-127,127]; round half to even; IEEE fp32 division by the scale;
+//   * dynamic scale = absmax / 127.0f; an all-zero row gets scale 1.0f;
+//   * softmax codes are unsigned 0..255 with zero-point 0 (Sec. 2.2.2: softmax
+//     output is "asymmetric" because it has no negative values).
+//
+// Parity pins live in tests/test_oracle_*.py (brute force, closed forms, invariants,
+// numpy/scipy/torch library routines).  No function here is "parity unpinned".
+
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <vector>
+#include <algorithm>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+extern "C" {
+
+enum { ORC_I8 = 0, ORC_U8 = 1, ORC_I32 = 2, ORC_F16 = 3, ORC_BF16 = 4, ORC_F32 = 5 };
+enum { ORC_EPI_RAW_I32 = 0, ORC_EPI_DEQUANT = 1, ORC_EPI_DEQUANT_GELU = 2,
+       ORC_EPI_REQUANT = 3, ORC_EPI_GELU_REQUANT = 4 };
+enum { ORC_MASK_NONE = 0, ORC_MASK_PADDING = 1, ORC_MASK_CAUSAL = 2 };
+
+// ---------------------------------------------------------------------------------
+// 16-bit float formats (storage only).  Round to nearest, ties to even.
+// ---------------------------------------------------------------------------------
+static inline uint32_t f32_bits(float f) { uint32_t u; std::memcpy(&u, &f, 4); return u; }
+static inline float bits_f32(uint32_t u) { float f; std::memcpy(&f, &u, 4); return f; }
+
+uint16_t orc_f32_to_bf16(float f) {
+    uint32_t u = f32_bits(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);  // NaN
+    uint32_t lsb = (u >> 16) & 1u;
+    u += 0x7fffu + lsb;
+    return (uint16_t)(u >> 16);
+}
+float orc_bf16_to_f32(uint16_t h) { return bits_f32((uint32_t)h << 16); }
+
+uint16_t orc_f32_to_f16(float f) {
+    // Through the exact value: find the nearest binary16 by scaling into an integer
+    // number of half-precision ulps and rounding that integer half-to-even in fp64.
+    uint32_t u = f32_bits(f);
+    uint16_t sign = (uint16_t)((u >> 16) & 0x8000u);
+    double a = std::fabs((double)f);
+    if (std::isnan(f)) return (uint16_t)(sign | 0x7e00u);
+    if (a >= 65520.0) return (uint16_t)(sign | 0x7c00u);        // rounds to infinity
+    if (a < std::ldexp(1.0, -14)) {                              // subnormal: ulp = 2^-24
+        double n = std::nearbyint(a * std::ldexp(1.0, 24));      // 0..1024
+        return (uint16_t)(sign | (uint16_t)n);                   // 1024 == smallest normal
+    }
+    int e; std::frexp(a, &e);                                    // a = m * 2^e, m in [0.5,1)
+    int E = e - 1;                                               // a in [2^E, 2^(E+1))
+    double n = std::nearbyint(a * std::ldexp(1.0, 10 - E));      // 1024..2048
+    if (n >= 2048.0) { n = 1024.0; E += 1; }
+    return (uint16_t)(sign | (uint16_t)(((E + 15) << 10) + ((int)n - 1024)));
+}
+float orc_f16_to_f32(uint16_t h) {
+    int s = (h >> 15) & 1, e = (h >> 10) & 0x1f, m = h & 0x3ff;
+    double v;
+    if (e == 0) v = std::ldexp((double)m, -24);
+    else if (e == 31) v = m ? NAN : INFINITY;
+    else v = std::ldexp((double)(m + 1024), e - 25);
+    return (float)(s ? -v : v);
+}
+
+void orc_f32_to_bf16_n(const float* x, int64_t n, uint16_t* y) { for (int64_t i = 0; i < n; ++i) y[i] = orc_f32_to_bf16(x[i]); }
+void orc_f32_to_f16_n(const float* x, int64_t n, uint16_t* y) { for (int64_t i = 0; i < n; ++i) y[i] = orc_f32_to_f16(x[i]); }
+void orc_f16_to_f32_n(const uint16_t* x, int64_t n, float* y) { for (int64_t i = 0; i < n; ++i) y[i] = orc_f16_to_f32(x[i]); }
+
+static inline float load_hp(const void* p, int dt, int64_t idx) {
+    if (dt == ORC_BF16) return orc_bf16_to_f32(((const uint16_t*)p)[idx]);
+    if (dt == ORC_F16) return orc_f16_to_f32(((const uint16_t*)p)[idx]);
+    return ((const float*)p)[idx];
+}
+static inline void store_hp(void* p, int dt, int64_t idx, float v) {
+    if (dt == ORC_BF16) ((uint16_t*)p)[idx] = orc_f32_to_bf16(v);
+    else if (dt == ORC_F16) ((uint16_t*)p)[idx] = orc_f32_to_f16(v);
+    else ((float*)p)[idx] = v;
+}
+
+// ---------------------------------------------------------------------------------
+// O1.  The quantization primitive (Sec. 2.1, "symmetric uniform INT8").
+// ---------------------------------------------------------------------------------
+static inline int8_t sat_i8(float r) {          // r already rounded to an integer value
+    if (r > 127.0f) return 127;
+    if (r < -127.0f) return -127;
+    return (int8_t)r;
+}
+static inline int8_t quant_code(float x, float s) {
+    volatile float qf = x / s;                  // IEEE fp32 division, kept in fp32
+    return sat_i8(std::nearbyintf(qf));         // default rounding mode: half to even
+}
+static inline float dyn_scale(float absmax) {
+    if (absmax == 0.0f) return 1.0f;
+    volatile float s = absmax / 127.0f;
+    return s;
+}
+
+// Token-wise quantization (TWQ, Sec. 2.1): X = S_x X_int8, S_x in R^{n x 1}, computed
+// on the fly from each row's absolute maximum.
+void orc_quant_twq(const float* x, int64_t M, int64_t D, int8_t* q, float* s) {
+    for (int64_t i = 0; i < M; ++i) {
+        float amax = 0.0f;
+        for (int64_t j = 0; j < D; ++j) amax = std::max(amax, std::fabs(x[i * D + j]));
+        float sc = dyn_scale(amax);
+        s[i] = sc;
+        for (int64_t j = 0; j < D; ++j) q[i * D + j] = quant_code(x[i * D + j], sc);
+    }
+}
+
+// Feature-wise (FWQ, S_x in R^{1 x d}) and static (SQ, scalar S_x) quantization with
+// calibrated scales (Sec. 2.1).  col_scale == NULL selects the scalar.
+void orc_quant_static(const float* x, int64_t M, int64_t D, const float* col_scale,
+                      float scalar_scale, int8_t* q) {
+    for (int64_t i = 0; i < M; ++i)
+        for (int64_t j = 0; j < D; ++j)
+            q[i * D + j] = quant_code(x[i * D + j], col_scale ? col_scale[j] : scalar_scale);
+}
+
+// O2.  Column-wise weight quantization (Sec. 2.1: W = W_int8 Diag(S_w), S_w in
+// R^{1 x m}).  W is the mathematical [K][N] matrix, row-major; the codes are written
+// "column-major", i.e. Wt[n][k], each output column's K values contiguous.
+void orc_weight_quant(const float* W, int64_t K, int64_t N, int8_t* Wt, float* s) {
+    for (int64_t n = 0; n < N; ++n) {
+        float amax = 0.0f;
+        for (int64_t k = 0; k < K; ++k) amax = std::max(amax, std::fabs(W[k * N + n]));
+        float sc = dyn_scale(amax);
+        s[n] = sc;
+        for (int64_t k = 0; k < K; ++k) Wt[n * K + k] = quant_code(W[k * N + n], sc);
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// O3.  The integer contraction  acc[i][j] = sum_k A[i][k] * Bt[j][k].
+// ---------------------------------------------------------------------------------
+void orc_gemm_i32(const int8_t* A, int64_t lda, const int8_t* Bt, int64_t ldb,
+                  int64_t M, int64_t N, int64_t K, int32_t* C) {
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < M; ++i)
+        for (int64_t j = 0; j < N; ++j) {
+            int32_t acc = 0;
+            for (int64_t k = 0; k < K; ++k)
+                acc += (int32_t)A[i * lda + k] * (int32_t)Bt[j * ldb + k];
+            C[i * N + j] = acc;
+        }
+}
+// Same sum carried in 64 bits: shows that the 32-bit one never wrapped.
+void orc_gemm_i64(const int8_t* A, int64_t lda, const int8_t* Bt, int64_t ldb,
+                  int64_t M, int64_t N, int64_t K, int64_t* C) {
+    for (int64_t i = 0; i < M; ++i)
+        for (int64_t j = 0; j < N; ++j) {
+            int64_t acc = 0;
+            for (int64_t k = 0; k < K; ++k)
+                acc += (int64_t)A[i * lda + k] * (int64_t)Bt[j * ldb + k];
+            C[i * N + j] = acc;
+        }
+}
+
+// GELU, exact erf form (the paper only names "GELU", Sec. 2.2.3), in fp64.
+double orc_gelu(double x) { return 0.5 * x * (1.0 + std::erf(x / std::sqrt(2.0))); }
+
+// ---------------------------------------------------------------------------------
+// O4.  GeMM^quant: INT8 GEMM with dequantization and the static FWQ/SQ scales fused
+// behind it (Sec. 2.2.2, the paragraph on fusing dequantization and scaling factors
+// into the INT8 GeMM, and the "Round(GeMM^quant(...))" equation; Sec. 2.2.3 for
+// GELU^quant).  fp32 arithmetic in one fixed order:
+//     t = float(acc);  t = t * a_row_scale[i];  y = fma(t, b_col_scale[j], bias[j])
+// DEQUANT:       y (+ residual) -> bf16/f16/f32
+// DEQUANT_GELU:  GELU(y) -> bf16/f16/f32
+// REQUANT:       sat(rne(y)) -> i8           (the folded scale makes this a bare Round)
+// GELU_REQUANT:  sat(rne(GELU(y) / out_col_scale[j])) -> i8
+// Returns 0, or -1 on an invalid combination.
+// ---------------------------------------------------------------------------------
+int orc_int8_gemm(const int8_t* A, int64_t lda, const float* a_row_scale,
+                  const int8_t* Bt, int64_t ldb, const float* b_col_scale,
+                  const float* bias, const void* residual, int res_dt, int64_t ldr,
+                  int epi, const float* out_col_scale,
+                  void* C, int c_dt, int64_t ldc, int64_t M, int64_t N, int64_t K) {
+    if (epi == ORC_EPI_RAW_I32 && c_dt != ORC_I32) return -1;
+    if ((epi == ORC_EPI_REQUANT || epi == ORC_EPI_GELU_REQUANT) && c_dt != ORC_I8) return -1;
+    if ((epi == ORC_EPI_DEQUANT || epi == ORC_EPI_DEQUANT_GELU) &&
+        !(c_dt == ORC_F16 || c_dt == ORC_BF16 || c_dt == ORC_F32)) return -1;
+    if (epi == ORC_EPI_GELU_REQUANT && !out_col_scale) return -1;
+    if (epi != ORC_EPI_RAW_I32 && !b_col_scale) return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < M; ++i)
+        for (int64_t j = 0; j < N; ++j) {
+            int32_t acc = 0;
+            for (int64_t k = 0; k < K; ++k)
+                acc += (int32_t)A[i * lda + k] * (int32_t)Bt[j * ldb + k];
+            if (epi == ORC_EPI_RAW_I32) { ((int32_t*)C)[i * ldc + j] = acc; continue; }
+            volatile float t = (float)acc;
+            if (a_row_scale) t = t * a_row_scale[i];
+            volatile float y = std::fmaf(t, b_col_scale[j], bias ? bias[j] : 0.0f);
+            switch (epi) {
+            case ORC_EPI_DEQUANT: {
+                float o = y;
+                if (residual) { volatile float r = y + load_hp(residual, res_dt, i * ldr + j); o = r; }
+                store_hp(C, c_dt, i * ldc + j, o);
+                break; }
+            case ORC_EPI_DEQUANT_GELU:
+                store_hp(C, c_dt, i * ldc + j, (float)orc_gelu((double)y));
+                break;
+            case ORC_EPI_REQUANT:
+                ((int8_t*)C)[i * ldc + j] = sat_i8(std::nearbyintf(y));
+                break;
+            case ORC_EPI_GELU_REQUANT:
+                ((int8_t*)C)[i * ldc + j] = quant_code((float)orc_gelu((double)y), out_col_scale[j]);
+                break;
+            }
+        }
+    return 0;
+}
+
+// ---------------------------------------------------------------------------------
+// O5.  LN^quant (Sec. 2.2.2 last equation of the quantized attention flow and the
+// paragraph after the W_o fold; Sec. 2.2.3 last equation): LayerNorm of the SUM of its
+// inputs, output token-wise quantized.
+//   x: i8 [M,D] with a per-row (TWQ) scale, or bf16/f16/f32 without a scale
+//   r: optional second addend: i8 with a per-column (FWQ) scale, or bf16/f16/f32
+//   gamma == NULL: no LayerNorm, the sum itself is quantized per token
+// Sum, mean, biased variance and the normalised value in fp64; the result is cast to
+// fp32 once and the TWQ primitive runs in fp32.
+// ---------------------------------------------------------------------------------
+int orc_ln_quant(const void* x, int x_dt, const float* x_row_scale,
+                 const void* r, int r_dt, const float* r_col_scale,
+                 const float* gamma, const float* beta, float eps,
+                 int64_t M, int64_t D,
+                 int8_t* y_q, float* y_scale, void* y_hp, int y_hp_dt) {
+    if (x_dt == ORC_I8 && !x_row_scale) return -1;
+    if (r && r_dt == ORC_I8 && !r_col_scale) return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < M; ++i) {
+        std::vector<double> s(D);
+        std::vector<float> y32(D);
+        for (int64_t j = 0; j < D; ++j) {
+            double v = (x_dt == ORC_I8)
+                ? (double)x_row_scale[i] * (double)((const int8_t*)x)[i * D + j]
+                : (double)load_hp(x, x_dt, i * D + j);
+            if (r) v += (r_dt == ORC_I8)
+                ? (double)r_col_scale[j] * (double)((const int8_t*)r)[i * D + j]
+                : (double)load_hp(r, r_dt, i * D + j);
+            s[j] = v;
+        }
+        if (gamma) {
+            double mu = 0.0;
+            for (int64_t j = 0; j < D; ++j) mu += s[j];
+            mu /= (double)D;
+            double var = 0.0;
+            for (int64_t j = 0; j < D; ++j) var += (s[j] - mu) * (s[j] - mu);
+            var /= (double)D;
+            double rstd = 1.0 / std::sqrt(var + (double)eps);
+            for (int64_t j = 0; j < D; ++j)
+                y32[j] = (float)((s[j] - mu) * rstd * (double)gamma[j] + (beta ? (double)beta[j] : 0.0));
+        } else {
+            for (int64_t j = 0; j < D; ++j) y32[j] = (float)s[j];
+        }
+        float amax = 0.0f;
+        for (int64_t j = 0; j < D; ++j) amax = std::max(amax, std::fabs(y32[j]));
+        float sc = dyn_scale(amax);
+        y_scale[i] = sc;
+        for (int64_t j = 0; j < D; ++j) {
+            y_q[i * D + j] = quant_code(y32[j], sc);
+            if (y_hp) store_hp(y_hp, y_hp_dt, i * D + j, y32[j]);
+        }
+    }
+    return 0;
+}
+
+// ---------------------------------------------------------------------------------
+// O6.  INT8 attention (Sec. 2.2.2, quantized flow, lines A, Softmax^quant, X_attn;
+// and d~ = S_q S_k / sqrt(d)).  Per (batch, head):
+//   acc_qk[i][k] exact;  a = float(acc_qk) * d~  (fp32, A is never quantized);
+//   keys outside the mask are left out;  p = softmax(a) in fp64;
+//   P_u8 = sat_[0,255](rne(float(p) / S_p));  acc_pv[i][e] = sum_k P_u8 * V[k][e] exact;
+//   INT8 out:  sat(rne(float(acc_pv) * c[j])),  c[j] = S_p S_v / S_attn[j],  j = h*Dh+e
+//   bf16/f16/f32 out:  float(acc_pv) * c[0]     (c[0] = S_p S_v)
+// Strides are in elements, ordered (batch, position, head, channel).
+// Mask: key k is visible to query i iff  k < kv_len[b] (when kv_len != NULL) and, for
+// CAUSAL, k <= i + (kvlen_b - Sq), i.e. the last query sees the last valid key.
+// A query with no visible key outputs 0.  p_dump (optional) receives the codes
+// [B,H,Sq,Skv].
+// ---------------------------------------------------------------------------------
+int orc_int8_attn(const int8_t* q, const int64_t* qs, const int8_t* k, const int64_t* ks,
+                  const int8_t* v, const int64_t* vs,
+                  int64_t B, int64_t H, int64_t Sq, int64_t Skv, int64_t Dh,
+                  float qk_scale, float p_scale, const float* out_col_scale, int out_scale_is_scalar,
+                  int mask, const int32_t* kv_len,
+                  void* out, int out_dt, int64_t ldo, uint8_t* p_dump) {
+    if (out_dt == ORC_I8 && out_scale_is_scalar == 0 && !out_col_scale) return -1;
+    if (mask == ORC_MASK_PADDING && !kv_len) return -1;
+#pragma omp parallel for schedule(dynamic) collapse(2)
+    for (int64_t b = 0; b < B; ++b)
+        for (int64_t h = 0; h < H; ++h) {
+            int64_t len = kv_len ? std::min<int64_t>(kv_len[b], Skv) : Skv;
+            std::vector<float> a(Skv);
+            std::vector<double> p(Skv);
+            std::vector<int32_t> codes(Skv);
+            for (int64_t i = 0; i < Sq; ++i) {
+                int64_t last = len - 1;                              // last visible key
+                if (mask == ORC_MASK_CAUSAL) last = std::min<int64_t>(last, i + (len - Sq));
+                int64_t nvis = last + 1;
+                const int8_t* qi = q + b * qs[0] + i * qs[1] + h * qs[2];
+                for (int64_t kk = 0; kk < nvis; ++kk) {
+                    const int8_t* kr = k + b * ks[0] + kk * ks[1] + h * ks[2];
+                    int32_t acc = 0;
+                    for (int64_t e = 0; e < Dh; ++e) acc += (int32_t)qi[e * qs[3]] * (int32_t)kr[e * ks[3]];
+                    volatile float t = (float)acc * qk_scale;
+                    a[kk] = t;
+                }
+                for (int64_t kk = 0; kk < Skv; ++kk) codes[kk] = 0;
+                if (nvis > 0) {
+                    double m = a[0];
+                    for (int64_t kk = 1; kk < nvis; ++kk) m = std::max(m, (double)a[kk]);
+                    double l = 0.0;
+                    for (int64_t kk = 0; kk < nvis; ++kk) { p[kk] = std::exp((double)a[kk] - m); l += p[kk]; }
+                    for (int64_t kk = 0; kk < nvis; ++kk) {
+                        volatile float pf = (float)(p[kk] / l);
+                        volatile float qf = pf / p_scale;
+                        float rr = std::nearbyintf(qf);
+                        codes[kk] = rr > 255.0f ? 255 : (rr < 0.0f ? 0 : (int32_t)rr);
+                    }
+                }
+                if (p_dump)
+                    for (int64_t kk = 0; kk < Skv; ++kk)
+                        p_dump[((b * H + h) * Sq + i) * Skv + kk] = (uint8_t)codes[kk];
+                for (int64_t e = 0; e < Dh; ++e) {
+                    int32_t acc = 0;
+                    for (int64_t kk = 0; kk < nvis; ++kk)
+                        acc += codes[kk] * (int32_t)v[b * vs[0] + kk * vs[1] + h * vs[2] + e * vs[3]];
+                    int64_t j = h * Dh + e;
+                    int64_t o = (b * Sq + i) * ldo + j;
+                    float c = out_scale_is_scalar ? out_col_scale[0] : out_col_scale[j];
+                    volatile float y = (float)acc * c;
+                    if (out_dt == ORC_I8) ((int8_t*)out)[o] = sat_i8(std::nearbyintf(y));
+                    else store_hp(out, out_dt, o, y);
+                }
+            }
+        }
+    return 0;
+}
+
+// ---------------------------------------------------------------------------------
+// BF16 side of a switched module (Sec. 2.3, Table 1: a module marked with a cross runs
+// in FP16/BF16).  Operands are bf16 values; the sums are carried in fp64 and rounded
+// to bf16 once at the end, so this is the value any correct fp32-accumulating kernel
+// must approach.
+//   C = act(A W + bias) (+ residual),  A [M,K] bf16, Wt [N][K] bf16, C bf16.
+// ---------------------------------------------------------------------------------
+int orc_bf16_gemm(const uint16_t* A, int64_t lda, const uint16_t* Wt, int64_t ldb,
+                  const float* bias, const uint16_t* residual, int64_t ldr, int gelu,
+                  uint16_t* C, int64_t ldc, int64_t M, int64_t N, int64_t K) {
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < M; ++i)
+        for (int64_t j = 0; j < N; ++j) {
+            double acc = 0.0;
+            for (int64_t kk = 0; kk < K; ++kk)
+                acc += (double)orc_bf16_to_f32(A[i * lda + kk]) * (double)orc_bf16_to_f32(Wt[j * ldb + kk]);
+            if (bias) acc += (double)bias[j];
+            if (gelu) acc = orc_gelu(acc);
+            if (residual) acc += (double)orc_bf16_to_f32(residual[i * ldr + j]);
+            C[i * ldc + j] = orc_f32_to_bf16((float)acc);
+        }
+    return 0;
+}
+
+// BF16 attention core: softmax(Q K^T * scale) V in fp64 on bf16 inputs, bf16 out.
+// Same strides and mask rules as orc_int8_attn.
+int orc_bf16_attn(const uint16_t* q, const int64_t* qs, const uint16_t* k, const int64_t* ks,
+                  const uint16_t* v, const int64_t* vs,
+                  int64_t B, int64_t H, int64_t Sq, int64_t Skv, int64_t Dh, float scale,
+                  int mask, const int32_t* kv_len, uint16_t* out, int64_t ldo) {
+#pragma omp parallel for schedule(dynamic) collapse(2)
+    for (int64_t b = 0; b < B; ++b)
+        for (int64_t h = 0; h < H; ++h) {
+            int64_t len = kv_len ? std::min<int64_t>(kv_len[b], Skv) : Skv;
+            std::vector<double> p(Skv);
+            for (int64_t i = 0; i < Sq; ++i) {
+                int64_t last = len - 1;
+                if (mask == ORC_MASK_CAUSAL) last = std::min<int64_t>(last, i + (len - Sq));
+                int64_t nvis = last + 1;
+                double m = -INFINITY;
+                for (int64_t kk = 0; kk < nvis; ++kk) {
+                    double acc = 0.0;
+                    for (int64_t e = 0; e < Dh; ++e)
+                        acc += (double)orc_bf16_to_f32(q[b * qs[0] + i * qs[1] + h * qs[2] + e * qs[3]]) *
+                               (double)orc_bf16_to_f32(k[b * ks[0] + kk * ks[1] + h * ks[2] + e * ks[3]]);
+                    p[kk] = acc * (double)scale;
+                    m = std::max(m, p[kk]);
+                }
+                double l = 0.0;
+                for (int64_t kk = 0; kk < nvis; ++kk) { p[kk] = std::exp(p[kk] - m); l += p[kk]; }
+                for (int64_t e = 0; e < Dh; ++e) {
+                    double acc = 0.0;
+                    for (int64_t kk = 0; kk < nvis; ++kk)
+                        acc += p[kk] * (double)orc_bf16_to_f32(v[b * vs[0] + kk * vs[1] + h * vs[2] + e * vs[3]]);
+                    out[(b * Sq + i) * ldo + h * Dh + e] = orc_f32_to_bf16(nvis > 0 ? (float)(acc / l) : 0.0f);
+                }
+            }
+        }
+    return 0;
+}
+
+int orc_num_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+}  // extern "C"

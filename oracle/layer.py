@@ -1,0 +1,276 @@
+"""Oracle: the paper's layer dataflow, offline preparation and the unquantized model.
+
+TEST INFRASTRUCTURE (see ``oracle/__init__.py``).  Written from the equations of
+Sec. 2.2.2 (attention module), Sec. 2.2.3 (MLP module) and Sec. 2.3 / Table 1 (modes),
+in the paper's notation:
+
+    X_in,int8 S_in  --QKV-->  X_{q,k,v},int8 (SQ)  --attention-->  X_attn,int8 S_attn (FWQ)
+    --W_o-->  X_o,int8 S_o (FWQ)  --LN^quant(X_in, X_o)-->  X_mid,int8 S_mid (TWQ)
+    --W_1, GELU^quant-->  A_int8 S_a (FWQ)  --W_2-->  X_2,int8 S_x2 (FWQ)
+    --LN^quant(X_mid, X_2)-->  X_out,int8 S_out (TWQ)
+
+The pre-LN (GPT) variant, the bias, the masks and the KV cache are not in the paper; the
+readings taken are listed in the design document.  Everything numeric is done by the C++
+operators in ``hero_oracle.cpp``; numpy fp64 is used for the unquantized model, the
+calibration statistics and the scale folding.
+"""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+
+import oracle as O
+
+POST_LN, PRE_LN = 0, 1
+# One bit per switchable module (Table 1 columns after "Embedding"); 1 = INT8, 0 = BF16.
+M_QKV, M_ATTN, M_ATTN_OUT, M_FC1, M_FC2 = 1, 2, 4, 8, 16
+MODE_M3 = M_QKV | M_ATTN | M_ATTN_OUT | M_FC1 | M_FC2
+MODE_M2 = M_QKV | M_ATTN | M_ATTN_OUT | M_FC1
+MODE_M1 = M_QKV | M_FC1
+S_P = np.float32(1.0 / 255.0)
+
+
+# ------------------------------------------------------------------ unquantized model (fp64)
+def _gelu64(x):
+    from scipy.special import erf
+    return 0.5 * x * (1.0 + erf(x / math.sqrt(2.0)))
+
+
+def _ln64(x, g, b, eps):
+    mu = x.mean(axis=1, keepdims=True)
+    var = ((x - mu) ** 2).mean(axis=1, keepdims=True)
+    return (x - mu) / np.sqrt(var + eps) * g + b
+
+
+def _visible(mask, i, Sq, length):
+    last = length - 1
+    if mask == O.MASK_CAUSAL:
+        last = min(last, i + (length - Sq))
+    return last + 1
+
+
+def fp64_attention(q, k, v, B, Sq, Skv, H, Dh, mask, kv_len):
+    """softmax(Q K^T / sqrt(Dh)) V per (batch, head); q [B*Sq, d], k/v [B*Skv, d]."""
+    out = np.zeros((B * Sq, H * Dh))
+    for b in range(B):
+        length = Skv if kv_len is None else min(int(kv_len[b]), Skv)
+        for h in range(H):
+            qs = q[b * Sq:(b + 1) * Sq, h * Dh:(h + 1) * Dh]
+            ks = k[b * Skv:(b + 1) * Skv, h * Dh:(h + 1) * Dh]
+            vs = v[b * Skv:(b + 1) * Skv, h * Dh:(h + 1) * Dh]
+            a = qs @ ks.T / math.sqrt(Dh)
+            for i in range(Sq):
+                n = _visible(mask, i, Sq, length)
+                if n <= 0:
+                    continue
+                e = np.exp(a[i, :n] - a[i, :n].max())
+                out[b * Sq + i, h * Dh:(h + 1) * Dh] = (e / e.sum()) @ vs[:n]
+    return out
+
+
+def fp64_layer(p, x, shape, B, S, kv_len=None):
+    """The unquantized layer (Sec. 2.2.2 first equation block, Sec. 2.2.3 first block).
+    x: [B*S, d] float64, the layer input (post-LN: already normalised; pre-LN: the
+    residual stream).  Returns every intermediate the calibration needs."""
+    d, H, Dh = shape.d, shape.H, shape.Dh
+    P = {k_: np.asarray(v_, np.float64) for k_, v_ in p.items()}
+    t = {}
+    xin = _ln64(x, P["ln1_g"], P["ln1_b"], shape.eps) if shape.arch == PRE_LN else x
+    qkv = xin @ P["w_qkv"] + P["b_qkv"]
+    t["q"], t["k"], t["v"] = qkv[:, :d], qkv[:, d:2 * d], qkv[:, 2 * d:]
+    t["attn"] = fp64_attention(t["q"], t["k"], t["v"], B, S, S, H, Dh, shape.mask, kv_len)
+    t["o"] = t["attn"] @ P["w_o"] + P["b_o"]
+    if shape.arch == POST_LN:
+        mid = _ln64(x + t["o"], P["ln1_g"], P["ln1_b"], shape.eps)
+        x1 = mid @ P["w_1"] + P["b_1"]
+    else:
+        mid = x + t["o"]
+        x1 = _ln64(mid, P["ln2_g"], P["ln2_b"], shape.eps) @ P["w_1"] + P["b_1"]
+    t["mid"] = mid
+    t["a"] = _gelu64(x1)
+    t["x2"] = t["a"] @ P["w_2"] + P["b_2"]
+    t["out"] = _ln64(mid + t["x2"], P["ln2_g"], P["ln2_b"], shape.eps) if shape.arch == POST_LN else mid + t["x2"]
+    return t
+
+
+# ------------------------------------------------------------------ calibration + preparation
+def _absmax_scale(a, axis=None):
+    """Static scale = absmax / 127 over the calibration tokens (no truncation, Sec. 3
+    discussion); a zero range gets scale 1."""
+    m = np.abs(a).max(axis=axis)
+    s = np.where(m == 0.0, 127.0, m) / 127.0
+    return np.float32(s) if axis is None else s.astype(np.float32)
+
+
+def calibrate(p, x_calib, shape, B, S, kv_len=None):
+    """Static scales from a forward pass of the unquantized layer on calibration tokens:
+    SQ scalars for X_q, X_k, X_v; FWQ vectors for X_attn, X_o, A, X_2; S_p = 1/255."""
+    t = fp64_layer(p, np.asarray(x_calib, np.float64), shape, B, S, kv_len)
+    sc = {"S_q": _absmax_scale(t["q"]), "S_k": _absmax_scale(t["k"]), "S_v": _absmax_scale(t["v"]),
+          "S_attn": _absmax_scale(t["attn"], 0), "S_o": _absmax_scale(t["o"], 0),
+          "S_a": _absmax_scale(t["a"], 0), "S_x2": _absmax_scale(t["x2"], 0), "S_p": S_P}
+    return sc, t["out"]
+
+
+def _bf16(a):
+    return O.f32_to_bf16(np.asarray(a, np.float32))
+
+
+def prepare(p, sc, shape, mode=MODE_M3):
+    """Fold the static scales into the weights, then quantize column-wise (Sec. 2.2.2:
+    W~_q = W_q / S_q and W~_o = S_attn W_o / S_o;  Sec. 2.2.3: W~_2 = S_a W_2 / S_x2).
+    Biases fold with the output scale.  Folding is done in fp64, cast to fp32 once, then
+    quantized.  BF16 modules keep the unfolded weights cast to bf16, stored [N][K]."""
+    d = shape.d
+    P = {k_: np.asarray(v_, np.float64) for k_, v_ in p.items()}
+    w = {"mode": mode, "S_p": sc["S_p"]}
+    # --- QKV (always INT8 in Table 1).  INT8 attention consumes SQ codes, so S_{q,k,v}
+    # are folded; a BF16 attention consumes dequantized values, so nothing is folded.
+    if mode & M_ATTN:
+        div = np.concatenate([np.full(d, float(sc["S_q"])), np.full(d, float(sc["S_k"])), np.full(d, float(sc["S_v"]))])
+    else:
+        div = np.ones(3 * d)
+    w["wq_qkv"], w["s_qkv"] = O.weight_quant((P["w_qkv"] / div).astype(np.float32))
+    w["b_qkv"] = (P["b_qkv"] / div).astype(np.float32)
+    w["qk_scale"] = np.float32(float(sc["S_q"]) * float(sc["S_k"]) / math.sqrt(shape.Dh))
+    w["bf16_qk_scale"] = np.float32(1.0 / math.sqrt(shape.Dh))
+    # attention output scale: FWQ codes when W_o is INT8, plain values when it is BF16
+    pv = float(sc["S_p"]) * float(sc["S_v"])
+    w["attn_out_scale"] = (pv / sc["S_attn"].astype(np.float64)).astype(np.float32)
+    w["attn_out_scalar"] = np.array([pv], np.float32)
+    # --- attention output linear
+    post = shape.arch == POST_LN
+    if mode & M_ATTN_OUT:
+        wo = sc["S_attn"].astype(np.float64)[:, None] * P["w_o"]
+        bo = P["b_o"]
+        if post:
+            wo = wo / sc["S_o"].astype(np.float64)[None, :]
+            bo = bo / sc["S_o"].astype(np.float64)
+        w["wq_o"], w["s_o_w"] = O.weight_quant(wo.astype(np.float32))
+        w["b_o"] = bo.astype(np.float32)
+    else:
+        w["wb_o"] = _bf16(P["w_o"].T.copy())
+        w["b_o"] = P["b_o"].astype(np.float32)
+    w["S_o"] = sc["S_o"]
+    # --- FC1 (always INT8 in Table 1); GELU^quant divides by S_a, nothing to fold
+    w["wq_1"], w["s_1"] = O.weight_quant(P["w_1"].astype(np.float32))
+    w["b_1"] = P["b_1"].astype(np.float32)
+    w["S_a"] = sc["S_a"]
+    # --- FC2
+    if mode & M_FC2:
+        w2 = sc["S_a"].astype(np.float64)[:, None] * P["w_2"]
+        b2 = P["b_2"]
+        if post:
+            w2 = w2 / sc["S_x2"].astype(np.float64)[None, :]
+            b2 = b2 / sc["S_x2"].astype(np.float64)
+        w["wq_2"], w["s_2_w"] = O.weight_quant(w2.astype(np.float32))
+        w["b_2"] = b2.astype(np.float32)
+    else:
+        w["wb_2"] = _bf16(P["w_2"].T.copy())
+        w["b_2"] = P["b_2"].astype(np.float32)
+    w["S_x2"] = sc["S_x2"]
+    for k_ in ("ln1_g", "ln1_b", "ln2_g", "ln2_b"):
+        w[k_] = np.asarray(p[k_], np.float32)
+    return w
+
+
+# ------------------------------------------------------------------ the quantized layer
+def _heads(a2d, B, S, H, Dh, part, parts=3):
+    """[B*S, parts*H*Dh] buffer -> strided [B,S,H,Dh] view of one of its column blocks."""
+    return a2d.reshape(B, S, parts, H, Dh)[:, :, part]
+
+
+def layer_fwd(w, shape, B, S, *, x_q=None, x_s=None, h=None, kv_len=None, cache=None, trace=None):
+    """One W8A8 layer.  POST_LN: input (x_q int8 [T,d], x_s f32 [T]) -> (out_q, out_s).
+    PRE_LN: input h (bf16 bit patterns [T,d]) -> new h.  ``cache`` (PRE_LN only) is a dict
+    {k, v: int8 [B,H,Smax,Dh]}; the S new key/value rows are written at positions
+    kv_len[b]-S .. kv_len[b]-1 and attention runs over the cache.  ``trace`` (a dict)
+    receives every intermediate."""
+    d, H, Dh, mode = shape.d, shape.H, shape.Dh, w["mode"]
+    T = B * S
+    tr = trace if trace is not None else {}
+    post = shape.arch == POST_LN
+    if not (mode & M_QKV and mode & M_FC1):
+        raise ValueError("QKV and FC1 are INT8 in every mode of Table 1")
+    if (mode & M_ATTN_OUT) and not (mode & M_ATTN):
+        raise ValueError("an INT8 attention-output linear needs INT8 attention in front of it")
+    if post:
+        xin_q, xin_s = x_q, x_s
+    else:
+        xin_q, xin_s, _ = O.ln_quant(h, O.BF16, None, None, 0, None, w["ln1_g"], w["ln1_b"], shape.eps)
+    tr["xin_q"], tr["xin_s"] = xin_q, xin_s
+    # ---- QKV GeMM^quant; the bare Round of the folded weights when attention is INT8
+    if mode & M_ATTN:
+        qkv = O.int8_gemm(xin_q, w["wq_qkv"], a_row_scale=xin_s, b_col_scale=w["s_qkv"], bias=w["b_qkv"],
+                          epi=O.EPI_REQUANT, c_dt=O.I8)
+    else:
+        qkv = O.int8_gemm(xin_q, w["wq_qkv"], a_row_scale=xin_s, b_col_scale=w["s_qkv"], bias=w["b_qkv"],
+                          epi=O.EPI_DEQUANT, c_dt=O.BF16)
+    tr["qkv"] = qkv
+    qv = _heads(qkv, B, S, H, Dh, 0)
+    if cache is not None:
+        kn, vn = _heads(qkv, B, S, H, Dh, 1), _heads(qkv, B, S, H, Dh, 2)
+        for b in range(B):
+            p0 = int(kv_len[b]) - S
+            cache["k"][b, :, p0:p0 + S, :] = kn[b].transpose(1, 0, 2)
+            cache["v"][b, :, p0:p0 + S, :] = vn[b].transpose(1, 0, 2)
+        kv, vv = cache["k"].transpose(0, 2, 1, 3), cache["v"].transpose(0, 2, 1, 3)   # [B,Smax,H,Dh] views
+        mask = shape.mask
+    else:
+        kv, vv = _heads(qkv, B, S, H, Dh, 1), _heads(qkv, B, S, H, Dh, 2)
+        mask = shape.mask
+    # ---- attention
+    if mode & M_ATTN:
+        to_i8 = bool(mode & M_ATTN_OUT)
+        attn = O.int8_attn(qv, kv, vv, qk_scale=float(w["qk_scale"]), p_scale=float(w["S_p"]),
+                           out_col_scale=w["attn_out_scale"] if to_i8 else w["attn_out_scalar"],
+                           out_scale_is_scalar=not to_i8, mask=mask, kv_len=kv_len,
+                           out_dt=O.I8 if to_i8 else O.BF16)
+    else:
+        attn = O.bf16_attn(qv, kv, vv, scale=float(w["bf16_qk_scale"]), mask=mask, kv_len=kv_len)
+    tr["attn"] = attn
+    # ---- attention output linear, then (post-LN) LN^quant of the two addends
+    if post:
+        if mode & M_ATTN_OUT:
+            xo = O.int8_gemm(attn, w["wq_o"], b_col_scale=w["s_o_w"], bias=w["b_o"], epi=O.EPI_REQUANT, c_dt=O.I8)
+            mid_q, mid_s, mid_hp = O.ln_quant(xin_q, O.I8, xin_s, xo, O.I8, w["S_o"], w["ln1_g"], w["ln1_b"], shape.eps)
+        else:
+            xo = O.bf16_gemm(attn, w["wb_o"], bias=w["b_o"])
+            mid_q, mid_s, mid_hp = O.ln_quant(xin_q, O.I8, xin_s, xo, O.BF16, None, w["ln1_g"], w["ln1_b"], shape.eps)
+        tr["xo"] = xo
+    else:
+        if mode & M_ATTN_OUT:
+            h1 = O.int8_gemm(attn, w["wq_o"], b_col_scale=w["s_o_w"], bias=w["b_o"], residual=h, res_dt=O.BF16,
+                             epi=O.EPI_DEQUANT, c_dt=O.BF16)
+        else:
+            h1 = O.bf16_gemm(attn, w["wb_o"], bias=w["b_o"], residual=h)
+        tr["h1"] = h1
+        mid_q, mid_s, _ = O.ln_quant(h1, O.BF16, None, None, 0, None, w["ln2_g"], w["ln2_b"], shape.eps)
+    tr["mid_q"], tr["mid_s"] = mid_q, mid_s
+    # ---- FC1 + GELU^quant
+    if mode & M_FC2:
+        a = O.int8_gemm(mid_q, w["wq_1"], a_row_scale=mid_s, b_col_scale=w["s_1"], bias=w["b_1"],
+                        epi=O.EPI_GELU_REQUANT, out_col_scale=w["S_a"], c_dt=O.I8)
+    else:
+        a = O.int8_gemm(mid_q, w["wq_1"], a_row_scale=mid_s, b_col_scale=w["s_1"], bias=w["b_1"],
+                        epi=O.EPI_DEQUANT_GELU, c_dt=O.BF16)
+    tr["a"] = a
+    # ---- FC2 and the closing LN^quant (post-LN) or residual add (pre-LN)
+    if post:
+        if mode & M_FC2:
+            x2 = O.int8_gemm(a, w["wq_2"], b_col_scale=w["s_2_w"], bias=w["b_2"], epi=O.EPI_REQUANT, c_dt=O.I8)
+            out_q, out_s, _ = O.ln_quant(mid_q, O.I8, mid_s, x2, O.I8, w["S_x2"], w["ln2_g"], w["ln2_b"], shape.eps)
+        else:
+            x2 = O.bf16_gemm(a, w["wb_2"], bias=w["b_2"])
+            out_q, out_s, _ = O.ln_quant(mid_q, O.I8, mid_s, x2, O.BF16, None, w["ln2_g"], w["ln2_b"], shape.eps)
+        tr["x2"] = x2
+        tr["out_q"], tr["out_s"] = out_q, out_s
+        return out_q, out_s
+    if mode & M_FC2:
+        h2 = O.int8_gemm(a, w["wq_2"], b_col_scale=w["s_2_w"], bias=w["b_2"], residual=h1, res_dt=O.BF16,
+                         epi=O.EPI_DEQUANT, c_dt=O.BF16)
+    else:
+        h2 = O.bf16_gemm(a, w["wb_2"], bias=w["b_2"], residual=h1)
+    tr["h2"] = h2
+    return h2
