@@ -1,0 +1,228 @@
+/* hero.h -- C ABI of libhero: the W8A8 transformer-layer forward of ZeroQuant-HERO
+ * (arXiv 2310.17723) for AMD MI355X (gfx950).
+ *
+ * Common rules for every entry point
+ *   - All data pointers are DEVICE pointers owned by the caller, 16-byte aligned, valid
+ *     until the work enqueued by the call has finished.  Nothing is retained afterwards.
+ *   - The library allocates no device memory and keeps no state between calls.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *     enqueue work; they never synchronise with the host.
+ *   - Arguments are validated on the host BEFORE anything is launched; on error nothing
+ *     has been enqueued and a non-zero hero_status is returned.  No exceptions cross the ABI.
+ *   - Sizes and strides are int64_t, in ELEMENTS.  Outputs must not alias inputs unless
+ *     the entry point says so.
+ *   - Numeric conventions (paper Sec. 2.1, "symmetric uniform INT8"): codes lie in
+ *     [-127,127]; rounding is to nearest, ties to even; a quantization divides by the
+ *     scale with IEEE fp32 division; a dynamic scale is absmax/127 (1.0 for an all-zero
+ *     row).  Integer contractions are exact in int32.
+ */
+#ifndef HERO_H
+#define HERO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    HERO_OK = 0,
+    HERO_ERR_NULL = 1,        /* a required pointer is NULL                           */
+    HERO_ERR_SHAPE = 2,       /* a size is negative / inconsistent                    */
+    HERO_ERR_ALIGN = 3,       /* a pointer or leading dimension breaks 16-byte rule   */
+    HERO_ERR_UNSUPPORTED = 4, /* valid request this build has no kernel for           */
+    HERO_ERR_WORKSPACE = 5,   /* workspace missing or too small                       */
+    HERO_ERR_LAUNCH = 6       /* the HIP runtime refused a launch                     */
+} hero_status;
+
+typedef enum { HERO_I8 = 0, HERO_U8 = 1, HERO_I32 = 2, HERO_F16 = 3, HERO_BF16 = 4, HERO_F32 = 5 } hero_dtype;
+
+typedef enum {
+    HERO_EPI_RAW_I32 = 0,      /* C = acc                                   (int32)        */
+    HERO_EPI_DEQUANT = 1,      /* C = y (+ residual)                        (f16/bf16)     */
+    HERO_EPI_DEQUANT_GELU = 2, /* C = GELU(y)                               (f16/bf16)     */
+    HERO_EPI_REQUANT = 3,      /* C = sat(rne(y))                           (int8)         */
+    HERO_EPI_GELU_REQUANT = 4  /* C = sat(rne(GELU(y) / out_col_scale[j]))  (int8)         */
+} hero_epilogue;
+
+typedef enum { HERO_MASK_NONE = 0, HERO_MASK_PADDING = 1, HERO_MASK_CAUSAL = 2 } hero_mask;
+
+const char* hero_strerror(hero_status s);
+
+/* LN^quant: LayerNorm of the SUM of its inputs with a token-wise (TWQ) INT8 output.
+ * Paper: Sec. 2.1 (TWQ is computed on the fly and fused into LayerNorm), Sec. 2.2.2 last
+ * line of the quantized attention flow  S_out X_out,int8 = LN^quant(S_in X_in,int8, X_o,int8 S_o),
+ * Sec. 2.2.3 last line of the quantized MLP flow.
+ *
+ *   s[i][j] = x[i][j] * x_row_scale[i] + r[i][j] * r_col_scale[j]
+ *   y       = (s - mean_j s) / sqrt(var_j s + eps) * gamma[j] + beta[j]     (biased variance)
+ *   y_scale[i] = max_j |y[i][j]| / 127 ;  y_q[i][j] = sat(rne(y[i][j] / y_scale[i]))
+ *
+ *   x        [M,D] row-major.  HERO_I8 with x_row_scale[M] (TWQ), or HERO_BF16/HERO_F16
+ *            with x_row_scale == NULL.
+ *   r        optional second addend [M,D] (NULL = none): HERO_I8 with r_col_scale[D] (FWQ),
+ *            or HERO_BF16/HERO_F16 with r_col_scale == NULL.
+ *   gamma, beta  f32[D].  gamma == NULL: no LayerNorm, the sum itself is quantized per
+ *            token (then beta must be NULL too).  beta may be NULL (= 0).
+ *   y_q [M,D] int8 and y_scale[M] f32 are always written.
+ *   y_hp     optional [M,D] copy of y in y_hp_dt (HERO_BF16/HERO_F16) for a BF16 consumer.
+ * Constraints: D % 16 == 0, 16 <= D <= 16384.  M == 0 is a no-op.
+ * Statistics are fp32 (mean, then variance about the mean) with the row held in registers.
+ */
+hero_status hero_ln_quant(const void* x, hero_dtype x_dt, const float* x_row_scale,
+                          const void* r, hero_dtype r_dt, const float* r_col_scale,
+                          const float* gamma, const float* beta, float eps,
+                          int64_t M, int64_t D,
+                          int8_t* y_q, float* y_scale, void* y_hp, hero_dtype y_hp_dt, void* stream);
+
+/* GeMM^quant: INT8 x INT8 -> INT32 GEMM with the dequantization and the static FWQ/SQ
+ * scales fused behind it.  Paper: Sec. 2.1 (Y = XW, column-wise weight scales, weights in
+ * column-major format), Sec. 2.2.2 (dequantization and pre-determined scales fused into
+ * the INT8 GeMM; X_q,int8 = Round(GeMM^quant(X_in,int8, W_q,int8, S_in, S_q)) once S_q is
+ * folded into the weight), Sec. 2.2.3 (GELU^quant).
+ *
+ *   acc[i][j] = sum_k A[i][k] * Bt[j][k]                      exact int32
+ *   t = float(acc);  t = t * a_row_scale[i]  (skipped if NULL);
+ *   y = fma(t, b_col_scale[j], bias[j])      (bias NULL = 0)   -- this order, fp32
+ *   then the epilogue `epi` (see hero_epilogue).  GELU is the exact erf form.
+ *
+ *   A   [M,K] int8 row-major, leading dimension lda.
+ *   Bt  [N,K] int8, K contiguous (the paper's column-major W[K,N]), leading dimension ldb.
+ *   residual  optional [M,N] HERO_BF16/HERO_F16 (DEQUANT only), leading dimension ldr; added
+ *       in fp32 before the final rounding.  C may alias residual when ldc == ldr and the
+ *       dtypes match (in-place residual stream).
+ *   out_col_scale[N]  required for GELU_REQUANT (the FWQ scale S_a), ignored otherwise.
+ *   C   [M,N] in c_dt, leading dimension ldc: HERO_I32 (RAW), HERO_F16/HERO_BF16 (DEQUANT*),
+ *       HERO_I8 (REQUANT*).  Other pairs -> HERO_ERR_UNSUPPORTED.
+ * Constraints: K % 16 == 0, K >= 16; lda, ldb multiples of 16; ldc*sizeof(C elem) and
+ * ldr*2 multiples of 16 bytes... see hero_int8_gemm in the source for the exact checks;
+ * M, N arbitrary (>= 0; zero is a no-op).
+ */
+hero_status hero_int8_gemm(const int8_t* A, int64_t lda, const float* a_row_scale,
+                           const int8_t* Bt, int64_t ldb, const float* b_col_scale,
+                           const float* bias, const void* residual, hero_dtype res_dt, int64_t ldr,
+                           hero_epilogue epi, const float* out_col_scale,
+                           void* C, hero_dtype c_dt, int64_t ldc,
+                           int64_t M, int64_t N, int64_t K, void* stream);
+
+/* INT8 attention: QK^T, Softmax^quant, PV.  Paper: Sec. 2.2.2 quantized flow
+ *   A = S_q S_k X_q,int8 X_k,int8^T / sqrt(d)   (not quantized; d~ = S_q S_k / sqrt(d))
+ *   S_p P_int8 = Softmax^quant(A)               (unsigned codes: softmax has no negatives)
+ *   X_attn,int8 S_attn = S_p S_v P_int8 X_v,int8
+ * Per (batch b, head h), query i, key k, channel e (j = h*Dh + e):
+ *   a[i][k]  = float(sum_e q k) * qk_scale                 keys outside the mask are left out
+ *   p        = softmax_k(a)   (fp32);   P[i][k] = sat_[0,255](rne(p / p_scale))
+ *   acc[i][e]= sum_k P[i][k] * v[k][e]                     exact int32
+ *   out_dt == HERO_I8 :  out[b*Sq+i][j] = sat(rne(float(acc) * out_col_scale[j]))
+ *   out_dt == HERO_BF16/HERO_F16 :  out = float(acc) * out_col_scale[0]   (out_scale_is_scalar = 1)
+ *
+ *   q [B,Sq,H,Dh], k/v [B,Skv,H,Dh] int8 given by a base pointer and 4 element strides in
+ *   the order (batch, position, head, channel); the channel stride must be 1 and the
+ *   others multiples of 16, so the operands can be views into a fused [T,3d] QKV buffer
+ *   or a [B,H,Smax,Dh] KV cache.
+ *   mask: key k is visible to query i iff k < kv_len[b] (when kv_len != NULL; required for
+ *   HERO_MASK_PADDING) and, for HERO_MASK_CAUSAL, k <= i + (len_b - Sq) with len_b =
+ *   min(kv_len[b], Skv) (or Skv): the last query sees the last valid key.  A query that
+ *   sees no key outputs 0.
+ *   out [B*Sq, H*Dh] row-major with leading dimension ldo.
+ * Constraints: Dh in {64, 128}; B, H, Sq, Skv >= 0 (zero is a no-op).
+ * The softmax is normalised BEFORE it is quantized, as the equation says, so the kernel
+ * makes two passes over the keys (row max and sum first, codes and PV second).
+ */
+hero_status hero_int8_attn(const int8_t* q, const int64_t q_strides[4],
+                           const int8_t* k, const int64_t k_strides[4],
+                           const int8_t* v, const int64_t v_strides[4],
+                           int64_t B, int64_t H, int64_t Sq, int64_t Skv, int64_t Dh,
+                           float qk_scale, float p_scale, const float* out_col_scale, int out_scale_is_scalar,
+                           hero_mask mask, const int32_t* kv_len,
+                           void* out, hero_dtype out_dt, int64_t ldo, void* stream);
+
+/* ---- one transformer layer (Sec. 2.2.2 + 2.2.3 chained, Sec. 2.3 / Table 1 modes) ---- */
+
+typedef enum { HERO_ARCH_POST_LN = 0, HERO_ARCH_PRE_LN = 1 } hero_arch;
+
+/* mode_mask: one bit per switchable module of Table 1; set = INT8, clear = BF16. */
+enum { HERO_M_QKV = 1, HERO_M_ATTN = 2, HERO_M_ATTN_OUT = 4, HERO_M_FC1 = 8, HERO_M_FC2 = 16 };
+#define HERO_MODE_M3 (HERO_M_QKV | HERO_M_ATTN | HERO_M_ATTN_OUT | HERO_M_FC1 | HERO_M_FC2)
+#define HERO_MODE_M2 (HERO_M_QKV | HERO_M_ATTN | HERO_M_ATTN_OUT | HERO_M_FC1)
+#define HERO_MODE_M1 (HERO_M_QKV | HERO_M_FC1)
+
+typedef struct {
+    int32_t arch;       /* hero_arch                                          */
+    int32_t d, H, Dh, f; /* hidden width, heads, head width (H*Dh == d), FFN width */
+    float eps;          /* LayerNorm epsilon                                  */
+    int32_t mask;       /* hero_mask                                          */
+    uint32_t mode_mask; /* HERO_M_* bits; QKV and FC1 must be set (Table 1)   */
+} hero_layer_desc;
+
+/* Prepared (folded, column-quantized) parameters, all device pointers.  INT8 weights are
+ * [N][K] (K contiguous); *_s are their f32 column scales; biases are f32 and already
+ * folded with the output scale where the output is requantized.  A BF16 module takes its
+ * weight in *_bf16 ([N][K] bf16, unfolded) and ignores the INT8 fields. */
+typedef struct {
+    const int8_t* w_qkv; const float* w_qkv_s; const float* b_qkv;          /* [3d][d] */
+    const int8_t* w_o;   const float* w_o_s;   const float* b_o;            /* [d][d]  */
+    const int8_t* w_1;   const float* w_1_s;   const float* b_1;            /* [f][d]  */
+    const int8_t* w_2;   const float* w_2_s;   const float* b_2;            /* [d][f]  */
+    const void* w_o_bf16; const void* w_2_bf16;                             /* BF16 modules */
+    const float* ln1_g; const float* ln1_b; const float* ln2_g; const float* ln2_b;
+    const float* S_o;   /* [d] FWQ scale of X_o  (POST_LN, INT8 attention-output)      */
+    const float* S_x2;  /* [d] FWQ scale of X_2  (POST_LN, INT8 FC2)                   */
+    const float* S_a;   /* [f] FWQ scale of A = GELU(X_1) (INT8 FC2)                   */
+    const float* attn_out_scale; /* [d] S_p S_v / S_attn[j] (INT8 attention-output) or
+                                    1 float S_p S_v (BF16 attention-output)            */
+    float qk_scale;     /* d~ = S_q S_k / sqrt(Dh)  (INT8 attention) or 1/sqrt(Dh) (BF16) */
+    float p_scale;      /* S_p                                                         */
+} hero_layer_weights;
+
+typedef struct {
+    int64_t B, S;            /* sequences and new tokens per sequence; T = B*S rows    */
+    /* POST_LN: TWQ input and output */
+    const int8_t* x_q; const float* x_scale;     /* [T,d] int8, [T] f32               */
+    int8_t* out_q;     float* out_scale;         /* [T,d] int8, [T] f32               */
+    /* PRE_LN: BF16 residual stream, updated IN PLACE */
+    void* h;                                     /* [T,d] bf16                        */
+    const int32_t* kv_len;   /* [B] visible keys per sequence INCLUDING this call's S tokens;
+                                NULL = S for every sequence (no cache, no padding)     */
+    /* optional INT8 KV cache [B,H,Smax,Dh] (PRE_LN or POST_LN): this call's K/V codes are
+       written at positions kv_len[b]-S .. kv_len[b]-1 and attention reads the cache.   */
+    int8_t* k_cache; int8_t* v_cache; int64_t Smax;
+} hero_layer_io;
+
+/* Bytes of scratch hero_layer_fwd needs for T = B*S rows of this layer. */
+size_t hero_layer_workspace_bytes(const hero_layer_desc* desc, int64_t B, int64_t S);
+
+/* One W8A8 layer: enqueues LN^quant, the four GeMM^quant, the attention and (POST_LN) the
+ * closing LN^quant on `stream`, with no host synchronisation.  Paper: Sec. 2.2.2, 2.2.3,
+ * Sec. 2.3 Table 1.  `workspace` is device scratch of at least
+ * hero_layer_workspace_bytes() bytes, 256-byte aligned, owned by the caller; its contents
+ * are undefined afterwards.  Supported mode masks: QKV and FC1 set; ATTN_OUT set only if
+ * ATTN is set (an INT8 output linear behind a BF16 attention would need the stand-alone
+ * quantization kernel the method removes). */
+hero_status hero_layer_fwd(const hero_layer_desc* desc, const hero_layer_weights* w, const hero_layer_io* io,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
+/* BF16 side of a switched module (Sec. 2.3, Table 1): C = act(A Wt^T + bias) (+ residual).
+ * A [M,K] bf16 (lda), Wt [N][K] bf16 (ldb), bias f32[N] or NULL, residual [M,N] bf16 or
+ * NULL (ldr; C may alias it), gelu != 0 applies erf-GELU before the residual, C [M,N] bf16
+ * (ldc).  fp32 accumulation.  Constraints: K % 32 == 0; lda, ldb, ldc, ldr multiples of 8. */
+hero_status hero_bf16_gemm(const void* A, int64_t lda, const void* Wt, int64_t ldb,
+                           const float* bias, const void* residual, int64_t ldr, int gelu,
+                           void* C, int64_t ldc, int64_t M, int64_t N, int64_t K, void* stream);
+
+/* BF16 attention core softmax(q k^T * scale) v with the same operand description and mask
+ * rules as hero_int8_attn (strides multiples of 8 elements); out [B*Sq, H*Dh] bf16. */
+hero_status hero_bf16_attn(const void* q, const int64_t q_strides[4],
+                           const void* k, const int64_t k_strides[4],
+                           const void* v, const int64_t v_strides[4],
+                           int64_t B, int64_t H, int64_t Sq, int64_t Skv, int64_t Dh, float scale,
+                           hero_mask mask, const int32_t* kv_len, void* out, int64_t ldo, void* stream);
+
+/* Library build identification: target architecture string, e.g. "gfx950". */
+const char* hero_build_arch(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HERO_H */

@@ -1,0 +1,197 @@
+"""ctypes binding of libhero.so: same names as the C ABI, torch tensors in place of raw
+pointers.  Argument marshalling only."""
+from __future__ import annotations
+
+import ctypes as C
+
+import torch
+
+# enums of include/hero.h
+I8, U8, I32, F16, BF16, F32 = range(6)
+EPI_RAW_I32, EPI_DEQUANT, EPI_DEQUANT_GELU, EPI_REQUANT, EPI_GELU_REQUANT = range(5)
+MASK_NONE, MASK_PADDING, MASK_CAUSAL = range(3)
+ARCH_POST_LN, ARCH_PRE_LN = 0, 1
+M_QKV, M_ATTN, M_ATTN_OUT, M_FC1, M_FC2 = 1, 2, 4, 8, 16
+MODE_M3 = M_QKV | M_ATTN | M_ATTN_OUT | M_FC1 | M_FC2
+MODE_M2 = M_QKV | M_ATTN | M_ATTN_OUT | M_FC1
+MODE_M1 = M_QKV | M_FC1
+
+_DT = {torch.int8: I8, torch.uint8: U8, torch.int32: I32, torch.float16: F16, torch.bfloat16: BF16,
+       torch.float32: F32}
+
+vp, i64, f32, i32 = C.c_void_p, C.c_int64, C.c_float, C.c_int
+
+
+class LayerDesc(C.Structure):
+    _fields_ = [("arch", C.c_int32), ("d", C.c_int32), ("H", C.c_int32), ("Dh", C.c_int32), ("f", C.c_int32),
+                ("eps", C.c_float), ("mask", C.c_int32), ("mode_mask", C.c_uint32)]
+
+
+class LayerWeights(C.Structure):
+    _fields_ = [(n, vp) for n in (
+        "w_qkv", "w_qkv_s", "b_qkv", "w_o", "w_o_s", "b_o", "w_1", "w_1_s", "b_1", "w_2", "w_2_s", "b_2",
+        "w_o_bf16", "w_2_bf16", "ln1_g", "ln1_b", "ln2_g", "ln2_b", "S_o", "S_x2", "S_a", "attn_out_scale")] + \
+        [("qk_scale", C.c_float), ("p_scale", C.c_float)]
+
+
+class LayerIO(C.Structure):
+    _fields_ = [("B", i64), ("S", i64), ("x_q", vp), ("x_scale", vp), ("out_q", vp), ("out_scale", vp),
+                ("h", vp), ("kv_len", vp), ("k_cache", vp), ("v_cache", vp), ("Smax", i64)]
+
+
+SYMBOLS = {
+    "hero_strerror": (C.c_char_p, [i32]),
+    "hero_build_arch": (C.c_char_p, []),
+    "hero_ln_quant": (i32, [vp, i32, vp, vp, i32, vp, vp, vp, f32, i64, i64, vp, vp, vp, i32, vp]),
+    "hero_int8_gemm": (i32, [vp, i64, vp, vp, i64, vp, vp, vp, i32, i64, i32, vp, vp, i32, i64, i64, i64, i64, vp]),
+    "hero_int8_attn": (i32, [vp, C.POINTER(i64), vp, C.POINTER(i64), vp, C.POINTER(i64), i64, i64, i64, i64, i64,
+                             f32, f32, vp, i32, i32, vp, vp, i32, i64, vp]),
+    "hero_layer_workspace_bytes": (C.c_size_t, [C.POINTER(LayerDesc), i64, i64]),
+    "hero_layer_fwd": (i32, [C.POINTER(LayerDesc), C.POINTER(LayerWeights), C.POINTER(LayerIO), vp, C.c_size_t, vp]),
+    "hero_bf16_gemm": (i32, [vp, i64, vp, i64, vp, vp, i64, i32, vp, i64, i64, i64, i64, vp]),
+    "hero_bf16_attn": (i32, [vp, C.POINTER(i64), vp, C.POINTER(i64), vp, C.POINTER(i64), i64, i64, i64, i64, i64,
+                             f32, i32, vp, vp, i64, vp]),
+}
+
+
+class HeroError(RuntimeError):
+    def __init__(self, status: int, msg: str):
+        super().__init__(f"libhero: {msg} (status {status})")
+        self.status = status
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream(stream=None):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+def _strides4(t):
+    assert t.dim() == 4
+    return (i64 * 4)(*t.stride())
+
+
+class Hero:
+    def __init__(self, path: str):
+        self.lib = C.CDLL(path)
+        for name, (res, args) in SYMBOLS.items():
+            fn = getattr(self.lib, name)      # AttributeError if the library lacks the symbol
+            fn.restype, fn.argtypes = res, args
+
+    # ------------------------------------------------------------------ helpers
+    def strerror(self, status: int) -> str:
+        return self.lib.hero_strerror(status).decode()
+
+    def build_arch(self) -> str:
+        return self.lib.hero_build_arch().decode()
+
+    def _check(self, status: int):
+        if status != 0:
+            raise HeroError(status, self.strerror(status))
+
+    # ------------------------------------------------------------------ LN^quant
+    def hero_ln_quant(self, x, x_row_scale=None, r=None, r_col_scale=None, gamma=None, beta=None, eps=1e-5,
+                      y_hp_dtype=None, y_q=None, y_scale=None, y_hp=None, stream=None):
+        """Returns (y_q int8 [M,D], y_scale f32 [M], y_hp or None)."""
+        M, D = x.shape
+        dev = x.device
+        y_q = torch.empty((M, D), dtype=torch.int8, device=dev) if y_q is None else y_q
+        y_scale = torch.empty((M,), dtype=torch.float32, device=dev) if y_scale is None else y_scale
+        if y_hp is None and y_hp_dtype is not None:
+            y_hp = torch.empty((M, D), dtype=y_hp_dtype, device=dev)
+        for t in (x, r):
+            assert t is None or t.is_contiguous()
+        st = self.lib.hero_ln_quant(_ptr(x), _DT[x.dtype], _ptr(x_row_scale), _ptr(r),
+                                    _DT[r.dtype] if r is not None else 0, _ptr(r_col_scale), _ptr(gamma), _ptr(beta),
+                                    float(eps), M, D, _ptr(y_q), _ptr(y_scale), _ptr(y_hp),
+                                    _DT[y_hp.dtype] if y_hp is not None else 0, _stream(stream))
+        self._check(st)
+        return y_q, y_scale, y_hp
+
+    # ------------------------------------------------------------------ GeMM^quant
+    def hero_int8_gemm(self, A, Bt, a_row_scale=None, b_col_scale=None, bias=None, residual=None,
+                       epi=EPI_RAW_I32, out_col_scale=None, out_dtype=torch.int32, C_out=None, stream=None):
+        """A [M,K] int8, Bt [N,K] int8 (row strides may exceed K).  Returns C [M,N]."""
+        M, K = A.shape
+        N = Bt.shape[0]
+        assert Bt.shape[1] == K and A.stride(1) == 1 and Bt.stride(1) == 1
+        if C_out is None:
+            C_out = torch.empty((M, N), dtype=out_dtype, device=A.device)
+        assert C_out.stride(1) == 1
+        st = self.lib.hero_int8_gemm(_ptr(A), A.stride(0) if M > 1 else max(K, A.stride(0)), _ptr(a_row_scale),
+                                     _ptr(Bt), Bt.stride(0) if N > 1 else max(K, Bt.stride(0)), _ptr(b_col_scale),
+                                     _ptr(bias), _ptr(residual),
+                                     _DT[residual.dtype] if residual is not None else 0,
+                                     residual.stride(0) if residual is not None else 0, int(epi), _ptr(out_col_scale),
+                                     _ptr(C_out), _DT[C_out.dtype], C_out.stride(0), M, N, K, _stream(stream))
+        self._check(st)
+        return C_out
+
+    # ------------------------------------------------------------------ INT8 attention
+    def hero_int8_attn(self, q, k, v, qk_scale, p_scale, out_col_scale, out_scale_is_scalar=False,
+                       mask=MASK_NONE, kv_len=None, out_dtype=torch.int8, out=None, stream=None):
+        """q [B,Sq,H,Dh], k/v [B,Skv,H,Dh] int8 views (unit channel stride).  Returns [B*Sq, H*Dh]."""
+        B, Sq, H, Dh = q.shape
+        Skv = k.shape[1]
+        if out is None:
+            out = torch.empty((B * Sq, H * Dh), dtype=out_dtype, device=q.device)
+        st = self.lib.hero_int8_attn(_ptr(q), _strides4(q), _ptr(k), _strides4(k), _ptr(v), _strides4(v),
+                                     B, H, Sq, Skv, Dh, float(qk_scale), float(p_scale), _ptr(out_col_scale),
+                                     int(bool(out_scale_is_scalar)), int(mask), _ptr(kv_len), _ptr(out),
+                                     _DT[out.dtype], out.stride(0), _stream(stream))
+        self._check(st)
+        return out
+
+    # ------------------------------------------------------------------ BF16 side
+    def hero_bf16_gemm(self, A, Wt, bias=None, residual=None, gelu=False, C_out=None, stream=None):
+        M, K = A.shape
+        N = Wt.shape[0]
+        if C_out is None:
+            C_out = torch.empty((M, N), dtype=torch.bfloat16, device=A.device)
+        st = self.lib.hero_bf16_gemm(_ptr(A), A.stride(0), _ptr(Wt), Wt.stride(0), _ptr(bias), _ptr(residual),
+                                     residual.stride(0) if residual is not None else 0, int(bool(gelu)),
+                                     _ptr(C_out), C_out.stride(0), M, N, K, _stream(stream))
+        self._check(st)
+        return C_out
+
+    def hero_bf16_attn(self, q, k, v, scale, mask=MASK_NONE, kv_len=None, out=None, stream=None):
+        B, Sq, H, Dh = q.shape
+        Skv = k.shape[1]
+        if out is None:
+            out = torch.empty((B * Sq, H * Dh), dtype=torch.bfloat16, device=q.device)
+        st = self.lib.hero_bf16_attn(_ptr(q), _strides4(q), _ptr(k), _strides4(k), _ptr(v), _strides4(v),
+                                     B, H, Sq, Skv, Dh, float(scale), int(mask), _ptr(kv_len), _ptr(out),
+                                     out.stride(0), _stream(stream))
+        self._check(st)
+        return out
+
+    # ------------------------------------------------------------------ layer
+    def layer_desc(self, arch, d, H, Dh, f, eps, mask, mode_mask=MODE_M3) -> LayerDesc:
+        return LayerDesc(int(arch), int(d), int(H), int(Dh), int(f), float(eps), int(mask), int(mode_mask))
+
+    def layer_weights(self, tensors: dict, qk_scale: float, p_scale: float) -> LayerWeights:
+        """tensors: device tensors keyed by the field names of hero_layer_weights; the dict
+        must stay alive while the struct is in use."""
+        w = LayerWeights()
+        for name, _ in LayerWeights._fields_:
+            if name in ("qk_scale", "p_scale"):
+                continue
+            t = tensors.get(name)
+            setattr(w, name, None if t is None else t.data_ptr())
+        w.qk_scale, w.p_scale = float(qk_scale), float(p_scale)
+        return w
+
+    def hero_layer_workspace_bytes(self, desc: LayerDesc, B: int, S: int) -> int:
+        return int(self.lib.hero_layer_workspace_bytes(C.byref(desc), B, S))
+
+    def hero_layer_fwd(self, desc, weights, B, S, workspace, *, x_q=None, x_scale=None, out_q=None, out_scale=None,
+                       h=None, kv_len=None, k_cache=None, v_cache=None, stream=None):
+        io = LayerIO(B, S, *(None if t is None else t.data_ptr() for t in (x_q, x_scale, out_q, out_scale, h, kv_len,
+                                                                            k_cache, v_cache)),
+                     k_cache.shape[2] if k_cache is not None else 0)
+        st = self.lib.hero_layer_fwd(C.byref(desc), C.byref(weights), C.byref(io), _ptr(workspace),
+                                     workspace.numel() * workspace.element_size(), _stream(stream))
+        self._check(st)

@@ -1,0 +1,72 @@
+// Shared device/host helpers of libhero (gfx950 only).  Not part of the public ABI.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "../../include/hero.h"
+
+#define HERO_WAVE 64
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v2i __attribute__((ext_vector_type(2)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef short v8s __attribute__((ext_vector_type(8)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+
+static inline bool hero_aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+static inline hero_status hero_launch_status() {
+    return hipGetLastError() == hipSuccess ? HERO_OK : HERO_ERR_LAUNCH;
+}
+
+// ---- 16-bit float storage (round to nearest even) -------------------------------------
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+__device__ __forceinline__ float f16_bits_to_f32(uint32_t h) {
+    return (float)__builtin_bit_cast(_Float16, (unsigned short)h);
+}
+__device__ __forceinline__ uint32_t f32_to_f16_bits(float f) {
+    return (uint32_t)__builtin_bit_cast(unsigned short, (_Float16)f);      // v_cvt_f16_f32: RNE
+}
+template <int DT> __device__ __forceinline__ float hp_to_f32(uint32_t h) {
+    return DT == HERO_BF16 ? bf16_bits_to_f32(h) : f16_bits_to_f32(h);
+}
+template <int DT> __device__ __forceinline__ uint32_t f32_to_hp(float f) {
+    return DT == HERO_BF16 ? f32_to_bf16_bits(f) : f32_to_f16_bits(f);
+}
+
+// ---- the quantization primitive ---------------------------------------------------------
+// code = sat_[-127,127](rne(x / s)) with IEEE fp32 division (never a reciprocal multiply).
+__device__ __forceinline__ int quant_code_div(float x, float s) {
+    float q = __builtin_rintf(__fdiv_rn(x, s));
+    q = fminf(fmaxf(q, -127.0f), 127.0f);
+    return (int)q;
+}
+// sat(rne(y)) for an already scaled value.
+__device__ __forceinline__ int round_sat_i8(float y) {
+    float q = __builtin_rintf(y);
+    q = fminf(fmaxf(q, -127.0f), 127.0f);
+    return (int)q;
+}
+__device__ __forceinline__ uint32_t pack4_i8(int a, int b, int c, int d) {
+    return (uint32_t)(a & 0xff) | ((uint32_t)(b & 0xff) << 8) | ((uint32_t)(c & 0xff) << 16) | ((uint32_t)d << 24);
+}
+// erf-form GELU in fp32.
+__device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752440f)); }
+
+// ---- wave reductions (64 lanes) ---------------------------------------------------------
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+    return v;
+}

@@ -1,0 +1,263 @@
+// hero_int8_attn: INT8 attention, QK^T -> Softmax^quant -> PV (paper Sec. 2.2.2, quantized
+// attention flow: A = d~ X_q,int8 X_k,int8^T is NOT quantized, S_p P_int8 = Softmax^quant(A)
+// with unsigned codes, X_attn,int8 S_attn = S_p S_v P_int8 X_v,int8).
+//
+// The softmax is normalised before it is quantized, so the row maximum and the row sum
+// must be known before the first code is produced: the kernel streams the keys twice
+// (pass 1: QK^T, row max / row sum; pass 2: QK^T again, codes, PV).  A and P never leave
+// the chip.
+//
+// Layout.  A block owns 128 queries of one (batch, head); each of its 4 waves owns 32.
+// Scores are computed TRANSPOSED, S^T = K Q^T (v_mfma_i32_32x32x32_i8 with the key
+// fragment as first operand), so lane l holds query l % 32 and the keys 8g + 4(l/32) + t
+// of a 32-key step in accumulator register 4g + t: a query's row statistics need one
+// exchange between lanes l and l^32, and the 16 codes a lane produces are already the
+// second-operand fragment of the PV MFMA (O^T = V^T P^T) provided V^T is stored in LDS with
+// the same key order, which the V staging does.
+// The matrix cores multiply signed bytes; codes are 0..255, so P-128 is fed and
+// 128 * colsum(V) (one extra MFMA against a vector of ones) is added back, exact in int32.
+#include "hero_common.h"
+
+namespace {
+
+constexpr int BQ = 128;   // queries per block
+constexpr int BKV = 64;   // keys per LDS tile
+
+struct AttnArgs {
+    const int8_t* q; const int8_t* k; const int8_t* v;
+    int64_t qs[4], ks[4], vs[4];
+    int B, H, Sq, Skv;
+    float qk_scale, p_scale;
+    const float* out_col_scale; int scale_is_scalar;
+    int mask; const int32_t* kv_len;
+    void* out; int64_t ldo;
+};
+
+template <int DH, int ODT>
+__global__ __launch_bounds__(256) void int8_attn_kernel(AttnArgs a) {
+    constexpr int KLD = DH + 16;        // sK row stride (bytes)
+    constexpr int VLD = BKV + 16;       // sVt row stride (bytes)
+    constexpr int DS = DH / 32;         // 32-wide steps over the head dimension
+    __shared__ __attribute__((aligned(16))) int8_t sK[BKV * KLD];
+    __shared__ __attribute__((aligned(16))) int8_t sVt[DH * VLD];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int hh = lane >> 5, ql = lane & 31;
+    const int b = blockIdx.z, h = blockIdx.y, q0 = blockIdx.x * BQ;
+    const int len = a.kv_len ? min(max(a.kv_len[b], 0), a.Skv) : a.Skv;
+    const int shift = len - a.Sq;                       // causal: key k visible iff k <= i + shift
+    const int qi = q0 + wave * 32 + ql;                 // this lane's query
+    int nvis = len;
+    if (a.mask == HERO_MASK_CAUSAL) nvis = min(len, qi + shift + 1);
+    nvis = max(nvis, 0);
+    // keys any query of the block can see -> number of key tiles
+    int kmax = len;
+    if (a.mask == HERO_MASK_CAUSAL) kmax = min(len, min(q0 + BQ, a.Sq) + shift);
+    const int ntiles = (max(kmax, 0) + BKV - 1) / BKV;
+
+    // ---- Q fragments (second MFMA operand), kept in registers -----------------------------
+    v4i qf[DS];
+    {
+        const int8_t* qp = a.q + (int64_t)b * a.qs[0] + (int64_t)min(qi, a.Sq - 1) * a.qs[1] + (int64_t)h * a.qs[2];
+#pragma unroll
+        for (int d = 0; d < DS; ++d) qf[d] = *reinterpret_cast<const v4i*>(qp + d * 32 + hh * 16);
+    }
+    const int8_t* kbase = a.k + (int64_t)b * a.ks[0] + (int64_t)h * a.ks[2];
+    const int8_t* vbase = a.v + (int64_t)b * a.vs[0] + (int64_t)h * a.vs[2];
+
+    auto stage_k = [&](int tile) {
+        constexpr int UNITS = BKV * (DH / 16) / 256;
+#pragma unroll
+        for (int u = 0; u < UNITS; ++u) {
+            int idx = tid + u * 256, row = idx / (DH / 16), ch = idx % (DH / 16);
+            int key = min(tile * BKV + row, a.Skv - 1);
+            v4i w = *reinterpret_cast<const v4i*>(kbase + (int64_t)key * a.ks[1] + ch * 16);
+            *reinterpret_cast<v4i*>(&sK[row * KLD + ch * 16]) = w;
+        }
+    };
+    auto stage_v = [&](int tile) {
+        constexpr int UNITS = BKV * (DH / 16) / 256;
+#pragma unroll
+        for (int u = 0; u < UNITS; ++u) {
+            int idx = tid + u * 256, row = idx / (DH / 16), ch = idx % (DH / 16);
+            int key = min(tile * BKV + row, a.Skv - 1);
+            v4i w = *reinterpret_cast<const v4i*>(vbase + (int64_t)key * a.vs[1] + ch * 16);
+            // key row = 32*kb + 8g + 4hh' + t  ->  position 32*kb + 16hh' + 4g + t
+            int r32 = row & 31;
+            int pos = (row & 32) + ((r32 >> 2) & 1) * 16 + (r32 >> 3) * 4 + (r32 & 3);
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+                sVt[(ch * 16 + e) * VLD + pos] = (int8_t)(w[e >> 2] >> (8 * (e & 3)));
+        }
+    };
+    // S^T for the 32-key step s of the staged tile
+    auto scores = [&](int s) {
+        v16i acc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] = 0;
+#pragma unroll
+        for (int d = 0; d < DS; ++d) {
+            v4i kf = *reinterpret_cast<const v4i*>(&sK[(s * 32 + ql) * KLD + d * 32 + hh * 16]);
+            acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(kf, qf[d], acc, 0, 0, 0);
+        }
+        return acc;
+    };
+
+    // ---- pass 1: row max and row sum ------------------------------------------------------------
+    float m = -INFINITY, l = 0.0f;
+    for (int tile = 0; tile < ntiles; ++tile) {
+        __syncthreads();
+        stage_k(tile);
+        __syncthreads();
+#pragma unroll
+        for (int s = 0; s < BKV / 32; ++s) {
+            v16i acc = scores(s);
+            float av[16];
+            float tmax = -INFINITY;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                int key = tile * BKV + s * 32 + (r >> 2) * 8 + hh * 4 + (r & 3);
+                float x = (float)acc[r] * a.qk_scale;
+                av[r] = key < nvis ? x : -INFINITY;
+                tmax = fmaxf(tmax, av[r]);
+            }
+            tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+            if (tmax > -INFINITY) {                      // same decision in both lanes of a query
+                float mn = fmaxf(m, tmax);
+                float sum = 0.0f;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) sum += __expf(av[r] - mn);     // exp(-inf) = 0
+                l = l * __expf(m - mn) + sum;
+                m = mn;
+            }
+        }
+    }
+    l += __shfl_xor(l, 32);
+    const float inv_l = l > 0.0f ? 1.0f / l : 0.0f;
+    const float inv_ps = 1.0f / a.p_scale;
+
+    // ---- pass 2: codes and PV --------------------------------------------------------------------
+    v16i o[DS], cs[DS];
+#pragma unroll
+    for (int c = 0; c < DS; ++c)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { o[c][r] = 0; cs[c][r] = 0; }
+    const v4i ones = {0x01010101, 0x01010101, 0x01010101, 0x01010101};
+    for (int tile = 0; tile < ntiles; ++tile) {
+        __syncthreads();
+        stage_k(tile);
+        stage_v(tile);
+        __syncthreads();
+#pragma unroll
+        for (int s = 0; s < BKV / 32; ++s) {
+            v16i acc = scores(s);
+            v4i pf;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                int code[4];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    int r = 4 * g + t;
+                    int key = tile * BKV + s * 32 + g * 8 + hh * 4 + t;
+                    float x = (float)acc[r] * a.qk_scale;
+                    float e = key < nvis ? __expf(x - m) : 0.0f;
+                    float c = __builtin_rintf(e * inv_l * inv_ps);
+                    c = fminf(fmaxf(c, 0.0f), 255.0f);
+                    code[t] = (int)c - 128;
+                }
+                pf[g] = (int)pack4_i8(code[0], code[1], code[2], code[3]);
+            }
+#pragma unroll
+            for (int c = 0; c < DS; ++c) {
+                v4i vf = *reinterpret_cast<const v4i*>(&sVt[(c * 32 + ql) * VLD + s * 32 + hh * 16]);
+                o[c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(vf, pf, o[c], 0, 0, 0);
+                cs[c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(vf, ones, cs[c], 0, 0, 0);
+            }
+        }
+    }
+
+    // ---- output: lane holds query ql, channels 32c + 8g + 4hh + t -----------------------------------
+    if (qi >= a.Sq) return;
+    const int64_t orow = ((int64_t)b * a.Sq + qi) * a.ldo + (int64_t)h * DH;
+#pragma unroll
+    for (int c = 0; c < DS; ++c)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int e0 = c * 32 + g * 8 + hh * 4;
+            float y[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                int val = o[c][4 * g + t] + 128 * cs[c][4 * g + t];
+                float sc = a.scale_is_scalar ? a.out_col_scale[0] : a.out_col_scale[h * DH + e0 + t];
+                y[t] = (float)val * sc;
+            }
+            if (ODT == HERO_I8) {
+                *reinterpret_cast<uint32_t*>((int8_t*)a.out + orow + e0) =
+                    pack4_i8(round_sat_i8(y[0]), round_sat_i8(y[1]), round_sat_i8(y[2]), round_sat_i8(y[3]));
+            } else {
+                uint32_t h0 = f32_to_hp<ODT>(y[0]), h1 = f32_to_hp<ODT>(y[1]), h2 = f32_to_hp<ODT>(y[2]), h3 = f32_to_hp<ODT>(y[3]);
+                v2i w = {(int)(h0 | (h1 << 16)), (int)(h2 | (h3 << 16))};
+                *reinterpret_cast<v2i*>((uint16_t*)a.out + orow + e0) = w;
+            }
+        }
+}
+
+__global__ void zero_rows_kernel(int8_t* out, int64_t bytes) {
+    int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 16;
+    if (i < bytes) *reinterpret_cast<v4i*>(out + i) = v4i{0, 0, 0, 0};
+}
+
+template <int DH>
+hero_status launch(const AttnArgs& a, hero_dtype out_dt, hipStream_t st) {
+    dim3 grid((a.Sq + BQ - 1) / BQ, a.H, a.B), block(256);
+    if (out_dt == HERO_I8) hipLaunchKernelGGL((int8_attn_kernel<DH, HERO_I8>), grid, block, 0, st, a);
+    else if (out_dt == HERO_BF16) hipLaunchKernelGGL((int8_attn_kernel<DH, HERO_BF16>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((int8_attn_kernel<DH, HERO_F16>), grid, block, 0, st, a);
+    return hero_launch_status();
+}
+
+}  // namespace
+
+extern "C" hero_status hero_int8_attn(const int8_t* q, const int64_t q_strides[4],
+                                      const int8_t* k, const int64_t k_strides[4],
+                                      const int8_t* v, const int64_t v_strides[4],
+                                      int64_t B, int64_t H, int64_t Sq, int64_t Skv, int64_t Dh,
+                                      float qk_scale, float p_scale, const float* out_col_scale, int out_scale_is_scalar,
+                                      hero_mask mask, const int32_t* kv_len,
+                                      void* out, hero_dtype out_dt, int64_t ldo, void* stream) {
+    if (B < 0 || H < 0 || Sq < 0 || Skv < 0) return HERO_ERR_SHAPE;
+    if (Dh != 64 && Dh != 128) return HERO_ERR_UNSUPPORTED;
+    if (out_dt != HERO_I8 && out_dt != HERO_BF16 && out_dt != HERO_F16) return HERO_ERR_UNSUPPORTED;
+    if (mask != HERO_MASK_NONE && mask != HERO_MASK_PADDING && mask != HERO_MASK_CAUSAL) return HERO_ERR_UNSUPPORTED;
+    if (B == 0 || H == 0 || Sq == 0) return HERO_OK;
+    if (!out || !out_col_scale || !q_strides || !k_strides || !v_strides) return HERO_ERR_NULL;
+    if (Skv > 0 && (!q || !k || !v)) return HERO_ERR_NULL;
+    if (mask == HERO_MASK_PADDING && !kv_len) return HERO_ERR_NULL;
+    if (out_dt != HERO_I8 && !out_scale_is_scalar) return HERO_ERR_UNSUPPORTED;
+    if (!(p_scale > 0.0f)) return HERO_ERR_SHAPE;
+    if (ldo < H * Dh) return HERO_ERR_SHAPE;
+    if (B > 65535 || H > 65535 || Sq > 0x7fffffffLL || Skv > 0x7fffffffLL) return HERO_ERR_SHAPE;
+    const int64_t* ss[3] = {q_strides, k_strides, v_strides};
+    for (int t = 0; t < 3; ++t) {
+        if (ss[t][3] != 1) return HERO_ERR_UNSUPPORTED;
+        if (ss[t][0] % 16 || ss[t][1] % 16 || ss[t][2] % 16) return HERO_ERR_ALIGN;
+    }
+    const int64_t o_elem = out_dt == HERO_I8 ? 1 : 2;
+    if ((ldo * o_elem) % 16 != 0 || !hero_aligned16(out) || !hero_aligned16(q) || !hero_aligned16(k) || !hero_aligned16(v))
+        return HERO_ERR_ALIGN;
+    AttnArgs a;
+    a.q = q; a.k = k; a.v = v;
+    for (int t = 0; t < 4; ++t) { a.qs[t] = q_strides[t]; a.ks[t] = k_strides[t]; a.vs[t] = v_strides[t]; }
+    a.B = (int)B; a.H = (int)H; a.Sq = (int)Sq; a.Skv = (int)Skv;
+    a.qk_scale = qk_scale; a.p_scale = p_scale; a.out_col_scale = out_col_scale; a.scale_is_scalar = out_scale_is_scalar;
+    a.mask = (int)mask; a.kv_len = kv_len; a.out = out; a.ldo = ldo;
+    hipStream_t st = (hipStream_t)stream;
+    if (Skv == 0) {     // no keys at all: every query outputs 0
+        const int64_t bytes = B * Sq * ldo * o_elem;                 // a multiple of 16 (ldo rule)
+        const int64_t blocks = (bytes / 16 + 255) / 256;
+        if (blocks > 0x7fffffffLL) return HERO_ERR_SHAPE;
+        hipLaunchKernelGGL(zero_rows_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (int8_t*)out, bytes);
+        return hero_launch_status();
+    }
+    return Dh == 64 ? launch<64>(a, out_dt, st) : launch<128>(a, out_dt, st);
+}

@@ -1,0 +1,67 @@
+"""Comparison helpers for the GPU-vs-oracle parity tests (tolerance classes of the
+benchmark contract: bit-exact integers, +-1 LSB on <= 0.1 % for LayerNorm / softmax / GELU
+fused paths, 2e-2 relative for 16-bit float outputs)."""
+import numpy as np
+import torch
+
+
+def to_np(t):
+    """Device tensor -> numpy; 16-bit floats come back as uint16 bit patterns."""
+    t = t.detach().cpu()
+    if t.dtype in (torch.bfloat16, torch.float16):
+        return t.view(torch.int16).numpy().view(np.uint16)
+    return t.numpy()
+
+
+def dev(a, dtype=None):
+    """numpy -> cuda tensor; uint16 arrays are reinterpreted as `dtype` (bf16/f16)."""
+    if a is None:
+        return None
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).view(dtype or torch.bfloat16).cuda()
+    return torch.from_numpy(a).cuda()
+
+
+def assert_exact(got, ref, what=""):
+    got, ref = np.asarray(got), np.asarray(ref)
+    assert got.shape == ref.shape, (what, got.shape, ref.shape)
+    bad = np.flatnonzero(got.ravel() != ref.ravel())
+    assert bad.size == 0, f"{what}: {bad.size} of {got.size} differ, first at {bad[:5]}: " \
+                          f"{got.ravel()[bad[:5]]} vs {ref.ravel()[bad[:5]]}"
+
+
+def assert_codes(got, ref, what="", max_frac=1e-3):
+    """INT8 codes: |diff| <= 1 everywhere, differing on at most max_frac of the elements."""
+    d = np.abs(got.astype(np.int32) - ref.astype(np.int32))
+    assert d.max() <= 1, f"{what}: max code difference {d.max()} at {np.unravel_index(d.argmax(), d.shape)}"
+    frac = np.count_nonzero(d) / d.size
+    assert frac <= max_frac, f"{what}: {frac:.2e} of the codes differ by 1 LSB (limit {max_frac:.0e})"
+    return frac
+
+
+def assert_scales(got, ref, what="", rtol=1e-5):
+    assert np.allclose(got, ref, rtol=rtol, atol=0), f"{what}: scales differ, max rel " \
+        f"{np.max(np.abs(got - ref) / np.abs(ref)):.2e}"
+
+
+def rel_err(got_f32, ref_f32):
+    """max_i |g - o| / max(|o_i|, rms(o)): the 16-bit float output tolerance."""
+    g, o = got_f32.astype(np.float64), ref_f32.astype(np.float64)
+    rms = np.sqrt(np.mean(o * o)) + 1e-30
+    return float(np.max(np.abs(g - o) / np.maximum(np.abs(o), rms)))
+
+
+def upload_weights(hero, w):
+    """Oracle-prepared layer parameters (oracle.layer.prepare) -> device hero_layer_weights.
+    Returns (struct, keepalive dict of device tensors)."""
+    from paper_2310_17723_amd import binding as HB
+    mode = w["mode"]
+    names = {"w_qkv": "wq_qkv", "w_qkv_s": "s_qkv", "b_qkv": "b_qkv", "w_o": "wq_o", "w_o_s": "s_o_w", "b_o": "b_o",
+             "w_1": "wq_1", "w_1_s": "s_1", "b_1": "b_1", "w_2": "wq_2", "w_2_s": "s_2_w", "b_2": "b_2",
+             "w_o_bf16": "wb_o", "w_2_bf16": "wb_2", "ln1_g": "ln1_g", "ln1_b": "ln1_b", "ln2_g": "ln2_g",
+             "ln2_b": "ln2_b", "S_o": "S_o", "S_x2": "S_x2", "S_a": "S_a"}
+    t = {k: dev(w[v]) for k, v in names.items() if v in w}
+    t["attn_out_scale"] = dev(w["attn_out_scale"] if mode & HB.M_ATTN_OUT else w["attn_out_scalar"])
+    qk = float(w["qk_scale"] if mode & HB.M_ATTN else w["bf16_qk_scale"])
+    return hero.layer_weights(t, qk, float(w["S_p"])), t

@@ -1,0 +1,251 @@
+"""GPU parity: each HIP entry point against the CPU oracle, element by element, on the
+same seeded inputs, at sizes that span several tiles and a ragged tail.  All calls go
+through the C ABI (ctypes binding)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+from oracle import layer as OL
+from paper_2310_17723_amd import binding as HB
+from paper_2310_17723_amd import synth
+from parity import assert_codes, assert_exact, assert_scales, dev, rel_err, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+# ============================================================ LN^quant
+def _ln_inputs(seed, M, D):
+    g = synth.rng(seed)
+    xq = g.integers(-127, 128, (M, D), dtype=np.int8)
+    rq = g.integers(-127, 128, (M, D), dtype=np.int8)
+    xs = g.uniform(0.005, 0.05, M).astype(np.float32)
+    rc = g.uniform(0.001, 0.02, D).astype(np.float32)
+    gam = (1 + 0.1 * g.standard_normal(D)).astype(np.float32)
+    bet = (0.02 * g.standard_normal(D)).astype(np.float32)
+    hb = O.f32_to_bf16(synth.activations(seed, synth.small(synth.CONFIGS[3], d=D), M))
+    return xq, rq, xs, rc, gam, bet, hb
+
+
+@pytest.mark.parametrize("M,D", [(37, 768), (130, 1024), (67, 4096), (9, 48), (21, 8192), (300, 1536)])
+def test_ln_quant_int8_pair(hero, M, D):
+    """Post-LN form: TWQ INT8 input + FWQ INT8 second addend (Sec. 2.2.2 last line)."""
+    xq, rq, xs, rc, gam, bet, _ = _ln_inputs(100 + D, M, D)
+    rq_o, rs_o, _ = O.ln_quant(xq, O.I8, xs, rq, O.I8, rc, gam, bet, 1e-12)
+    q, s, _ = hero.hero_ln_quant(dev(xq), dev(xs), dev(rq), dev(rc), dev(gam), dev(bet), 1e-12)
+    assert_scales(to_np(s), rs_o, "y_scale")
+    assert_codes(to_np(q), rq_o, "y_q")
+
+
+@pytest.mark.parametrize("M,D", [(131, 4096), (40, 1024), (17, 512), (5, 16)])
+def test_ln_quant_bf16_single_and_hp_copy(hero, M, D):
+    """Pre-LN form: one bf16 input; also the bf16 copy of y and a bf16 second addend."""
+    xq, rq, xs, rc, gam, bet, hb = _ln_inputs(200 + D, M, D)
+    rq_o, rs_o, hp_o = O.ln_quant(hb, O.BF16, None, None, 0, None, gam, bet, 1e-5, y_hp_dt=O.BF16)
+    q, s, hp = hero.hero_ln_quant(dev(hb), None, None, None, dev(gam), dev(bet), 1e-5, y_hp_dtype=torch.bfloat16)
+    assert_scales(to_np(s), rs_o)
+    assert_codes(to_np(q), rq_o, "y_q")
+    assert rel_err(O.bf16_to_f32(to_np(hp)), O.bf16_to_f32(hp_o)) <= 2e-2
+    # INT8 x + bf16 addend (a BF16 module feeding the LayerNorm), f16 copy of y
+    rb = O.f32_to_bf16(synth.rng(3).standard_normal((M, D)).astype(np.float32))
+    rq_o, rs_o, hp_o = O.ln_quant(xq, O.I8, xs, rb, O.BF16, None, gam, None, 1e-5, y_hp_dt=O.F16)
+    q, s, hp = hero.hero_ln_quant(dev(xq), dev(xs), dev(rb), None, dev(gam), None, 1e-5, y_hp_dtype=torch.float16)
+    assert_scales(to_np(s), rs_o)
+    assert_codes(to_np(q), rq_o)
+    assert rel_err(O.f16_to_f32(to_np(hp)), O.f16_to_f32(hp_o)) <= 2e-2
+
+
+def test_ln_quant_pure_per_token_quant_is_bit_exact(hero):
+    """gamma == NULL: no float reduction besides absmax, so scales and codes are exact."""
+    M, D = 150, 1024
+    _, _, _, _, _, _, hb = _ln_inputs(7, M, D)
+    hb[3] = 0                                                     # an all-zero row: scale 1, codes 0
+    rq_o, rs_o, _ = O.ln_quant(hb, O.BF16, None, None, 0, None, None, None, 0.0)
+    q, s, _ = hero.hero_ln_quant(dev(hb), None, None, None, None, None, 0.0)
+    assert_exact(to_np(s), rs_o, "scale")
+    assert_exact(to_np(q), rq_o, "codes")
+    assert to_np(s)[3] == 1.0 and not to_np(q)[3].any()
+    hf = O.f32_to_f16(O.bf16_to_f32(hb))
+    rq_o, rs_o, _ = O.ln_quant(hf, O.F16, None, None, 0, None, None, None, 0.0)
+    q, s, _ = hero.hero_ln_quant(dev(hf, torch.float16), None, None, None, None, None, 0.0)
+    assert_exact(to_np(s), rs_o)
+    assert_exact(to_np(q), rq_o)
+
+
+def test_ln_quant_rejects_bad_arguments(hero):
+    x = torch.zeros((4, 40), dtype=torch.int8, device="cuda")
+    with pytest.raises(HB.HeroError) as e:
+        hero.hero_ln_quant(x, torch.ones(4, device="cuda"))
+    assert e.value.status == 4                                    # D % 16 != 0
+    x = torch.zeros((4, 64), dtype=torch.int8, device="cuda")
+    with pytest.raises(HB.HeroError) as e:
+        hero.hero_ln_quant(x, None)
+    assert e.value.status == 1                                    # INT8 input without a row scale
+    q, s, _ = hero.hero_ln_quant(x[:0], torch.ones(0, device="cuda"))     # empty: no-op
+    assert q.shape == (0, 64)
+
+
+# ============================================================ GeMM^quant
+GEMM_SHAPES = [(128, 128, 64), (200, 200, 256), (512, 384, 1024), (77, 1000, 192), (1, 64, 4096), (300, 72, 768)]
+
+
+@pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
+def test_gemm_raw_int32_bit_exact(hero, M, N, K):
+    c = synth.gemm_case(300 + M, M, K, N)
+    ref = O.gemm_i32(c["A"], c["Bt"])
+    got = hero.hero_int8_gemm(dev(c["A"]), dev(c["Bt"]))
+    assert_exact(to_np(got), ref, "acc")
+
+
+def test_gemm_one_hot_probes_operand_layout(hero):
+    """A one-hot A row picks single weight entries: fails on any mistake in the MFMA
+    operand or accumulator lane mapping."""
+    M, N, K = 160, 192, 128
+    g = synth.rng(5)
+    Bt = g.integers(-127, 128, (N, K), dtype=np.int8)
+    A = np.zeros((M, K), np.int8)
+    ks = g.integers(0, K, M)
+    A[np.arange(M), ks] = 1
+    got = to_np(hero.hero_int8_gemm(dev(A), dev(Bt)))
+    assert_exact(got, Bt[:, ks].T.astype(np.int32))
+    # extreme magnitude: K = 16384 of 127 * -127
+    A = np.full((3, 16384), 127, np.int8)
+    Bt = np.full((5, 16384), -127, np.int8)
+    assert (to_np(hero.hero_int8_gemm(dev(A), dev(Bt))) == -127 * 127 * 16384).all()
+
+
+@pytest.mark.parametrize("outlier", [False, True])
+@pytest.mark.parametrize("M,N,K", GEMM_SHAPES[1:4])
+def test_gemm_requant_and_dequant_bit_exact(hero, M, N, K, outlier):
+    """REQUANT / DEQUANT: pure fp32 arithmetic on exact integers in a pinned order."""
+    c = synth.gemm_case(400 + M, M, K, N, outlier_rows=outlier)
+    A, Bt, rs, cs, bias = c["A"], c["Bt"], c["a_row_scale"], c["b_col_scale"], c["bias"]
+    dA, dB, drs, dcs, db = map(dev, (A, Bt, rs, cs, bias))
+    for dt, tdt in ((O.F16, torch.float16), (O.BF16, torch.bfloat16)):
+        ref = O.int8_gemm(A, Bt, a_row_scale=rs, b_col_scale=cs, bias=bias, epi=O.EPI_DEQUANT, c_dt=dt)
+        got = hero.hero_int8_gemm(dA, dB, drs, dcs, db, epi=HB.EPI_DEQUANT, out_dtype=tdt)
+        assert_exact(to_np(got), ref, f"dequant {dt}")
+    # static output scale folded into the column scale (the paper's bare Round)
+    y = O.int8_gemm(A, Bt, a_row_scale=rs, b_col_scale=cs, bias=bias, epi=O.EPI_DEQUANT, c_dt=O.F32)
+    s_out = np.float32(np.abs(y[~np.isin(np.arange(M), np.argsort(rs)[-max(1, M // 100):])]).max() / 127)
+    cs2, b2 = (cs / s_out).astype(np.float32), (bias / s_out).astype(np.float32)
+    ref = O.int8_gemm(A, Bt, a_row_scale=rs, b_col_scale=cs2, bias=b2, epi=O.EPI_REQUANT, c_dt=O.I8)
+    got = hero.hero_int8_gemm(dA, dB, drs, dev(cs2), dev(b2), epi=HB.EPI_REQUANT, out_dtype=torch.int8)
+    assert_exact(to_np(got), ref, "requant")
+    if outlier:
+        assert (np.abs(ref) == 127).sum() > 0                     # saturation is exercised
+    # no row scale, no bias (FWQ input whose scale is folded into the weight)
+    ref = O.int8_gemm(A, Bt, b_col_scale=cs2 * np.float32(0.01), epi=O.EPI_REQUANT, c_dt=O.I8)
+    got = hero.hero_int8_gemm(dA, dB, None, dev(cs2 * np.float32(0.01)), None, epi=HB.EPI_REQUANT, out_dtype=torch.int8)
+    assert_exact(to_np(got), ref, "requant no row scale")
+    # residual add (in place: C aliases the residual)
+    res = O.f32_to_bf16(synth.rng(9).standard_normal((M, N)).astype(np.float32))
+    ref = O.int8_gemm(A, Bt, a_row_scale=rs, b_col_scale=cs, bias=bias, residual=res, res_dt=O.BF16,
+                      epi=O.EPI_DEQUANT, c_dt=O.BF16)
+    dres = dev(res)
+    got = hero.hero_int8_gemm(dA, dB, drs, dcs, db, residual=dres, epi=HB.EPI_DEQUANT, C_out=dres)
+    assert_exact(to_np(got), ref, "dequant + residual in place")
+
+
+@pytest.mark.parametrize("M,N,K", [(256, 512, 256), (130, 200, 768)])
+def test_gemm_gelu_epilogues(hero, M, N, K):
+    """GELU^quant (Sec. 2.2.3): fp32 erf on the GPU vs fp64 in the oracle -> +-1 LSB class."""
+    c = synth.gemm_case(500 + M, M, K, N)
+    A, Bt, rs, cs, bias = c["A"], c["Bt"], c["a_row_scale"], c["b_col_scale"], c["bias"]
+    cs = (cs * np.float32(30.0 / np.sqrt(K))).astype(np.float32)      # pre-activations of a few units
+    g = O.int8_gemm(A, Bt, a_row_scale=rs, b_col_scale=cs, bias=bias, epi=O.EPI_DEQUANT_GELU, c_dt=O.F32)
+    s_a = (np.abs(g).max(axis=0) / 127).astype(np.float32)
+    ref = O.int8_gemm(A, Bt, a_row_scale=rs, b_col_scale=cs, bias=bias, epi=O.EPI_GELU_REQUANT, out_col_scale=s_a, c_dt=O.I8)
+    got = hero.hero_int8_gemm(dev(A), dev(Bt), dev(rs), dev(cs), dev(bias), epi=HB.EPI_GELU_REQUANT,
+                              out_col_scale=dev(s_a), out_dtype=torch.int8)
+    assert_codes(to_np(got), ref, "gelu requant")
+    refb = O.int8_gemm(A, Bt, a_row_scale=rs, b_col_scale=cs, bias=bias, epi=O.EPI_DEQUANT_GELU, c_dt=O.BF16)
+    gotb = hero.hero_int8_gemm(dev(A), dev(Bt), dev(rs), dev(cs), dev(bias), epi=HB.EPI_DEQUANT_GELU, out_dtype=torch.bfloat16)
+    assert rel_err(O.bf16_to_f32(to_np(gotb)), O.bf16_to_f32(refb)) <= 2e-2
+
+
+def test_gemm_strided_operands_and_errors(hero):
+    """Leading dimensions larger than the logical width; invalid combinations are refused."""
+    M, N, K = 96, 80, 128
+    c = synth.gemm_case(600, M, K + 64, N + 16)
+    A_full, B_full = dev(c["A"]), dev(c["Bt"])
+    A, Bt = A_full[:, :K], B_full[:N, :K]
+    Cbuf = torch.full((M, N + 48), -7, dtype=torch.int32, device="cuda")
+    hero.hero_int8_gemm(A, Bt, C_out=Cbuf[:, :N])
+    assert_exact(to_np(Cbuf[:, :N]), O.gemm_i32(c["A"][:, :K], c["Bt"][:N, :K]))
+    assert (to_np(Cbuf[:, N:]) == -7).all()                        # nothing written past N
+    with pytest.raises(HB.HeroError) as e:
+        hero.hero_int8_gemm(A, Bt, epi=HB.EPI_REQUANT, out_dtype=torch.int8)     # no column scale
+    assert e.value.status == 1
+    with pytest.raises(HB.HeroError) as e:
+        hero.hero_int8_gemm(A, Bt, None, torch.ones(N, device="cuda"), epi=HB.EPI_REQUANT, out_dtype=torch.float16)
+    assert e.value.status == 4
+    with pytest.raises(HB.HeroError) as e:
+        hero.hero_int8_gemm(A_full[:, :K - 16], B_full[:N, :K - 16])             # K % 64 != 0
+    assert e.value.status == 4
+
+
+# ============================================================ INT8 attention
+def _attn_case(seed, B, Sq, Skv, H, Dh):
+    g = synth.rng(seed)
+    # q/k/v codes with the spread of SQ-quantized N(0,1)-ish activations (|code| mostly < 60)
+    mk = lambda s: np.clip(np.rint(g.standard_normal(s) * 30), -127, 127).astype(np.int8)
+    q, k, v = mk((B, Sq, H, Dh)), mk((B, Skv, H, Dh)), mk((B, Skv, H, Dh))
+    qk_scale = np.float32(4.0 / (30 * 30 * np.sqrt(Dh)) / np.sqrt(Dh) * 6)       # logits of a few units
+    cs = g.uniform(0.8, 1.2, H * Dh).astype(np.float32) * np.float32(1.0 / (255 * 30) * 127 / 2.5)
+    return q, k, v, float(qk_scale), cs
+
+
+ATTN_SHAPES = [(2, 200, 200, 2, 64), (1, 128, 128, 3, 128), (2, 77, 300, 2, 64), (1, 513, 513, 1, 128)]
+
+
+@pytest.mark.parametrize("mask", [O.MASK_NONE, O.MASK_PADDING, O.MASK_CAUSAL])
+@pytest.mark.parametrize("B,Sq,Skv,H,Dh", ATTN_SHAPES)
+def test_int8_attn_matches_oracle(hero, B, Sq, Skv, H, Dh, mask):
+    q, k, v, qk_scale, cs = _attn_case(700 + Sq + Dh, B, Sq, Skv, H, Dh)
+    kv_len = None
+    if mask == O.MASK_PADDING:
+        kv_len = np.int32([Skv - 3, 0][:B]) if B == 2 else np.int32([Skv // 2 + 1])
+    if mask == O.MASK_CAUSAL and Sq != Skv:
+        kv_len = np.int32([Skv, Skv - 50][:B])
+    ref = O.int8_attn(q, k, v, qk_scale=qk_scale, p_scale=float(OL.S_P), out_col_scale=cs, mask=mask, kv_len=kv_len)
+    got = hero.hero_int8_attn(dev(q), dev(k), dev(v), qk_scale, float(OL.S_P), dev(cs), mask=mask, kv_len=dev(kv_len))
+    assert np.abs(ref).max() > 40                                  # the case is not degenerate
+    assert_codes(to_np(got), ref, "X_attn")
+    # 16-bit float output (the consumer is a BF16 attention-output linear)
+    sc = np.float32([cs[0]])
+    refb = O.int8_attn(q, k, v, qk_scale=qk_scale, p_scale=float(OL.S_P), out_col_scale=sc, out_scale_is_scalar=True,
+                       mask=mask, kv_len=kv_len, out_dt=O.BF16)
+    gotb = hero.hero_int8_attn(dev(q), dev(k), dev(v), qk_scale, float(OL.S_P), dev(sc), out_scale_is_scalar=True,
+                               mask=mask, kv_len=dev(kv_len), out_dtype=torch.bfloat16)
+    assert rel_err(O.bf16_to_f32(to_np(gotb)), O.bf16_to_f32(refb)) <= 2e-2
+
+
+def test_int8_attn_strided_views_cache_and_decode(hero):
+    """Operands as views into a fused [T,3d] buffer and a [B,H,Smax,Dh] cache; one-query decode."""
+    B, S, H, Dh = 3, 70, 2, 64
+    d = H * Dh
+    g = synth.rng(800)
+    qkv = np.clip(np.rint(g.standard_normal((B * S, 3 * d)) * 30), -127, 127).astype(np.int8)
+    _, _, _, qk_scale, cs = _attn_case(801, 1, 1, 1, H, Dh)
+    qv, kv, vv = (OL._heads(qkv, B, S, H, Dh, i) for i in range(3))
+    ref = O.int8_attn(qv, kv, vv, qk_scale=qk_scale, p_scale=float(OL.S_P), out_col_scale=cs, mask=O.MASK_CAUSAL)
+    dq = dev(qkv).view(B, S, 3, H, Dh)
+    got = hero.hero_int8_attn(dq[:, :, 0], dq[:, :, 1], dq[:, :, 2], qk_scale, float(OL.S_P), dev(cs), mask=HB.MASK_CAUSAL)
+    assert_codes(to_np(got), ref, "fused-buffer views")
+    Smax = 96
+    kc = np.zeros((B, H, Smax, Dh), np.int8)
+    vc = np.zeros((B, H, Smax, Dh), np.int8)
+    kc[:, :, :S], vc[:, :, :S] = kv.transpose(0, 2, 1, 3), vv.transpose(0, 2, 1, 3)
+    lens = np.int32([S, S - 9, 1])
+    q1 = np.ascontiguousarray(qv[:, -1:, :, :])
+    ref = O.int8_attn(q1, kc.transpose(0, 2, 1, 3), vc.transpose(0, 2, 1, 3), qk_scale=qk_scale, p_scale=float(OL.S_P),
+                      out_col_scale=cs, mask=O.MASK_PADDING, kv_len=lens)
+    dk, dv = dev(kc), dev(vc)
+    got = hero.hero_int8_attn(dev(q1), dk.permute(0, 2, 1, 3), dv.permute(0, 2, 1, 3), qk_scale, float(OL.S_P), dev(cs),
+                              mask=HB.MASK_PADDING, kv_len=dev(lens))
+    assert_codes(to_np(got), ref, "decode against the cache", max_frac=3e-3)    # 384 outputs: 1 flip = 0.26 %
+    # no keys at all -> zeros
+    z = hero.hero_int8_attn(dev(q1), dk.permute(0, 2, 1, 3)[:, :0], dv.permute(0, 2, 1, 3)[:, :0], qk_scale,
+                            float(OL.S_P), dev(cs))
+    assert not to_np(z).any()
