@@ -1,0 +1,319 @@
+#!/usr/bin/env python3
+"""Benchmark of the W8A8 layer forward (libhero) on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload bert-large|gpt-prefill|gpt-decode|bert-base]
+
+One "step" is one pass of the whole hot path -- every layer of the workload's stack, each
+layer = LN^quant, QKV / O / FC1 / FC2 GeMM^quant, INT8 attention -- over one batch of
+seeded synthetic input that is already resident in HBM.  Prints ONE JSON line:
+  value     W8A8 layer tokens/s = tokens x layers / second
+  roofline  the dominant kernel (the FC1 GeMM^quant with its GELU^quant epilogue) timed
+            alone with HIP events on the same stream, against the dense INT8 MFMA peak
+  cpu_baseline  the CPU oracle timed on a bounded slice of the same workload
+Extra keys report the stand-alone GEMM sweep (TOP/s) and the fused LN+quant kernel (GB/s).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_INT8_TOPS = 5000.0      # MI355X dense INT8 MFMA, TOP/s
+PEAK_HBM_GBS = 8000.0        # MI355X HBM3E, GB/s
+
+WORKLOADS = {"bert-base": 0, "bert-large": 2, "gpt-prefill": 3, "gpt-decode": 4}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def time_gpu(fn, iters, warmup=3):
+    import torch
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / iters      # ms per call
+
+
+class Stack:
+    """Device-resident prepared weights + activations of one workload."""
+
+    def __init__(self, hero, shape, seed, mode, layers=None):
+        import torch
+        from paper_2310_17723_amd import binding as HB, prep, synth
+        self.hero, self.shape, self.mode = hero, shape, mode
+        self.layers = shape.layers if layers is None else layers
+        dev = torch.device("cuda")
+        B, S, d = shape.B, shape.S, shape.d
+        self.T = B * S
+        post = shape.arch == synth.POST_LN
+        decode = shape.cache_len > 0
+        # ---- calibration input: a small batch of the same distribution, propagated
+        # through the UNQUANTIZED stack layer by layer (Sec. 3: forward pass only)
+        Sc = min(S if not decode else 128, 256)
+        Bc = 2
+        xc = torch.from_numpy(synth.activations(seed, shape, Bc * Sc, stream=1)).to(dev).double()
+        emb = synth.embedding_ln_params(seed, shape)
+        self.emb = {k: torch.from_numpy(v).to(dev) for k, v in emb.items()}
+        if post:
+            xc = torch.nn.functional.layer_norm(xc, (d,), self.emb["g"].double(), self.emb["b"].double(), shape.eps)
+        cal_mask = shape.mask if not decode else HB.MASK_CAUSAL
+        self.desc = hero.layer_desc(shape.arch, d, shape.H, shape.Dh, shape.f, shape.eps, shape.mask, mode)
+        self.weights, self.keep = [], []
+        for l in range(self.layers):
+            p = {k: torch.from_numpy(v).to(dev) for k, v in synth.layer_params(seed, shape, l).items()}
+            sc, xc = prep.calibrate(p, xc, shape.arch, shape.H, shape.Dh, shape.eps,
+                                    cal_mask if cal_mask != HB.MASK_PADDING else HB.MASK_NONE, Bc, Sc)
+            t, qk, ps = prep.prepare(p, sc, shape.arch, d, shape.Dh, mode)
+            self.keep.append(t)
+            self.weights.append(hero.layer_weights(t, qk, ps))
+            del p
+        # ---- inputs, resident in HBM
+        h0 = torch.from_numpy(synth.activations(seed, shape, self.T)).to(dev)
+        self.kv_len = None
+        if shape.mask == HB.MASK_PADDING and not decode:
+            self.kv_len = torch.from_numpy(synth.kv_lengths(seed, shape)).to(dev)
+        self.ws = torch.empty(hero.hero_layer_workspace_bytes(self.desc, B, S), dtype=torch.uint8, device=dev)
+        if post:
+            self.x0_q, self.x0_s, _ = hero.hero_ln_quant(h0.to(torch.bfloat16), None, None, None, self.emb["g"],
+                                                         self.emb["b"], shape.eps)
+            self.buf = [(torch.empty_like(self.x0_q), torch.empty_like(self.x0_s)) for _ in range(2)]
+        else:
+            self.h0 = h0.to(torch.bfloat16)
+            self.h = torch.empty_like(self.h0)
+        self.caches = None
+        if decode:
+            Smax = shape.cache_len + shape.steps
+            self.Smax = Smax
+            self.caches = []
+            for l in range(self.layers):
+                kc = torch.from_numpy(synth.int8_codes(seed, (B, shape.H, Smax, shape.Dh), stream=2 * l)).to(dev)
+                vc = torch.from_numpy(synth.int8_codes(seed, (B, shape.H, Smax, shape.Dh), stream=2 * l + 1)).to(dev)
+                self.caches.append((kc, vc))
+            # kv_len for every decode step, precomputed: the caller owns the counter
+            self.kv_steps = torch.stack([torch.full((B,), shape.cache_len + t + 1, dtype=torch.int32)
+                                         for t in range(shape.steps)]).to(dev)
+        torch.cuda.synchronize()
+
+    def step(self):
+        """One pass of the whole stack.  Decode: `steps` tokens, each through every layer."""
+        hero, sh = self.hero, self.shape
+        B, S = sh.B, sh.S
+        if sh.arch == 0:
+            xq, xs = self.x0_q, self.x0_s
+            for l in range(self.layers):
+                oq, os_ = self.buf[l & 1]
+                hero.hero_layer_fwd(self.desc, self.weights[l], B, S, self.ws, x_q=xq, x_scale=xs, out_q=oq,
+                                    out_scale=os_, kv_len=self.kv_len)
+                xq, xs = oq, os_
+        elif self.caches is None:
+            self.h.copy_(self.h0)
+            for l in range(self.layers):
+                hero.hero_layer_fwd(self.desc, self.weights[l], B, S, self.ws, h=self.h)
+        else:
+            for t in range(sh.steps):
+                self.h.copy_(self.h0)
+                for l in range(self.layers):
+                    kc, vc = self.caches[l]
+                    hero.hero_layer_fwd(self.desc, self.weights[l], B, 1, self.ws, h=self.h, kv_len=self.kv_steps[t],
+                                        k_cache=kc, v_cache=vc)
+
+    def tokens_layers_per_step(self):
+        sh = self.shape
+        return self.T * self.layers * (sh.steps if self.caches is not None else 1)
+
+
+def fc1_roofline(hero, shape, seed, iters=20):
+    """The dominant kernel alone: FC1 GeMM^quant + GELU^quant at the workload's shape."""
+    import torch
+    from paper_2310_17723_amd import binding as HB, synth
+    M, K, N = shape.B * shape.S, shape.d, shape.f
+    c = synth.gemm_case(seed, M, K, N)
+    A, Bt = torch.from_numpy(c["A"]).cuda(), torch.from_numpy(c["Bt"]).cuda()
+    rs, cs, bias = (torch.from_numpy(c[k]).cuda() for k in ("a_row_scale", "b_col_scale", "bias"))
+    cs = cs * (30.0 / K ** 0.5)
+    sa = torch.full((N,), 0.03, dtype=torch.float32, device="cuda")
+    out = torch.empty((M, N), dtype=torch.int8, device="cuda")
+    fn = lambda: hero.hero_int8_gemm(A, Bt, rs, cs, bias, epi=HB.EPI_GELU_REQUANT, out_col_scale=sa, C_out=out)
+    ms = time_gpu(fn, iters)
+    ops = 2.0 * M * N * K
+    tops = ops / (ms * 1e-3) / 1e12
+    return {"bound": "mfma", "kernel": "int8_gemm_kernel<GELU_REQUANT> (FC1)", "shape_mnk": [M, N, K],
+            "achieved": round(tops, 2), "peak": PEAK_INT8_TOPS, "unit": "TOP/s", "frac": round(tops / PEAK_INT8_TOPS, 4),
+            "avg_launch_us": round(ms * 1e3, 2), "ops_per_launch": ops, "traffic": None}
+
+
+def gemm_sweep(hero, seed, iters=10):
+    import torch
+    from paper_2310_17723_amd import binding as HB, synth
+    rows = []
+    for (K, N) in synth.GEMM_KN:
+        for M in synth.GEMM_M:
+            c = synth.gemm_case(seed, M, K, N)
+            A, Bt = torch.from_numpy(c["A"]).cuda(), torch.from_numpy(c["Bt"]).cuda()
+            rs, cs, bias = (torch.from_numpy(c[k]).cuda() for k in ("a_row_scale", "b_col_scale", "bias"))
+            for name, epi, dt in (("fp16", HB.EPI_DEQUANT, torch.float16), ("int8", HB.EPI_REQUANT, torch.int8)):
+                out = torch.empty((M, N), dtype=dt, device="cuda")
+                ms = time_gpu(lambda: hero.hero_int8_gemm(A, Bt, rs, cs, bias, epi=epi, C_out=out), iters)
+                tops = 2.0 * M * N * K / (ms * 1e-3) / 1e12
+                rows.append({"M": M, "K": K, "N": N, "out": name, "us": round(ms * 1e3, 2), "tops": round(tops, 1),
+                             "frac_peak": round(tops / PEAK_INT8_TOPS, 4)})
+    return rows
+
+
+def ln_bandwidth(hero, T, D, iters=40, nbuf=8):
+    """Fused LN + per-token quant on rotating buffers (working set >> the 256 MB cache)."""
+    import torch
+    g = torch.Generator(device="cuda").manual_seed(1)
+    sets = []
+    for _ in range(nbuf):
+        x = torch.randint(-127, 128, (T, D), dtype=torch.int8, device="cuda", generator=g)
+        r = torch.randint(-127, 128, (T, D), dtype=torch.int8, device="cuda", generator=g)
+        xs = torch.rand(T, device="cuda", generator=g) * 0.04 + 0.01
+        sets.append((x, r, xs, torch.empty_like(x), torch.empty(T, device="cuda")))
+    rc = torch.rand(D, device="cuda", generator=g) * 0.02 + 0.001
+    gam = torch.ones(D, device="cuda")
+    bet = torch.zeros(D, device="cuda")
+    i = [0]
+
+    def fn():
+        x, r, xs, yq, ys = sets[i[0] % nbuf]
+        i[0] += 1
+        hero.hero_ln_quant(x, xs, r, rc, gam, bet, 1e-12, y_q=yq, y_scale=ys)
+    ms = time_gpu(fn, iters, warmup=nbuf)
+    bytes_ = T * (3 * D + 8)
+    gbs = bytes_ / (ms * 1e-3) / 1e9
+    return {"T": T, "D": D, "form": "int8+int8->int8", "us": round(ms * 1e3, 2), "bytes_per_launch": bytes_,
+            "gbs": round(gbs, 1), "frac_hbm": round(gbs / PEAK_HBM_GBS, 4), "working_set_mb": nbuf * bytes_ // 2 ** 20}
+
+
+def cpu_baseline(shape, seed, mode_name):
+    """The oracle, as it stands, on a bounded slice: one sequence through one layer."""
+    import oracle as O
+    from oracle import layer as OL
+    from paper_2310_17723_amd import synth
+    decode = shape.cache_len > 0
+    B, S = (1, min(shape.S, 512)) if not decode else (2, 1)
+    sh = synth.small(shape, B=B, S=S)
+    p = synth.layer_params(seed, sh, 0)
+    emb = synth.embedding_ln_params(seed, sh)
+    Sc = 64
+    xc = synth.activations(seed, sh, 2 * Sc, stream=1).astype(np.float64)
+    if sh.arch == synth.POST_LN:
+        xc = OL._ln64(xc, emb["g"].astype(np.float64), emb["b"].astype(np.float64), sh.eps)
+    cal = synth.small(sh, mask=synth.MASK_NONE if sh.mask == synth.MASK_PADDING else sh.mask)
+    sc, _ = OL.calibrate(p, xc, cal, 2, Sc)
+    w = OL.prepare(p, sc, sh, OL.MODE_M3)
+    h0 = synth.activations(seed, sh, B * S)
+    t0 = time.perf_counter()
+    if sh.arch == synth.POST_LN:
+        xq, xs, _ = O.ln_quant(h0, O.F32, None, None, 0, None, emb["g"], emb["b"], sh.eps)
+        kv = np.full(B, S, np.int32) if sh.mask == synth.MASK_PADDING else None
+        OL.layer_fwd(w, sh, B, S, x_q=xq, x_s=xs, kv_len=kv)
+        sample = f"1 sequence x {S} tokens through 1 layer of {shape.name}"
+    elif not decode:
+        OL.layer_fwd(w, sh, B, S, h=O.f32_to_bf16(h0))
+        sample = f"1 sequence x {S} tokens through 1 layer of {shape.name}"
+    else:
+        Smax = shape.cache_len + 1
+        cache = {"k": synth.int8_codes(seed, (B, sh.H, Smax, sh.Dh), 0), "v": synth.int8_codes(seed, (B, sh.H, Smax, sh.Dh), 1)}
+        OL.layer_fwd(w, sh, B, 1, h=O.f32_to_bf16(h0), kv_len=np.full(B, Smax, np.int32), cache=cache)
+        sample = f"{B} sequences x 1 decode token (cache {shape.cache_len}) through 1 layer of {shape.name}"
+    dt = time.perf_counter() - t0
+    return {"value": round(B * S / dt, 2), "unit": "layer-tokens/s", "cores": O.num_threads(), "kind": "oracle",
+            "sample": sample, "seconds": round(dt, 2)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--workload", default="bert-large", choices=sorted(WORKLOADS))
+    ap.add_argument("--mode", default="M3", choices=["M1", "M2", "M3"])
+    ap.add_argument("--layers", type=int, default=None, help="override the stack depth")
+    ap.add_argument("--seed", type=int, default=2310)
+    ap.add_argument("--no-extras", action="store_true", help="skip the GEMM sweep / LN / CPU legs")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the path shards without exchange along tokens; "
+              "no collective is built) -- run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2310_17723_amd as pkg
+    from paper_2310_17723_amd import binding as HB, synth
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    hero = pkg.load()                     # raises if libhero.so is missing: no fallback
+    shape = synth.CONFIGS[WORKLOADS[args.workload]]
+    mode = {"M1": HB.MODE_M1, "M2": HB.MODE_M2, "M3": HB.MODE_M3}[args.mode]
+    decode = shape.cache_len > 0
+    steps = args.steps if args.steps is not None else (1 if decode else 10)
+    warmup = args.warmup if args.warmup is not None else (1 if decode else 3)
+
+    log(f"[bench] preparing {shape.name} ({args.mode}) ...")
+    st = Stack(hero, shape, args.seed, mode, args.layers)
+    log("[bench] warm-up")
+    for _ in range(warmup):
+        st.step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        st.step()
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    ms_per_step = e0.elapsed_time(e1) / steps
+    tl = st.tokens_layers_per_step()
+    value = tl / (ms_per_step * 1e-3)
+
+    rec = {
+        "metric": "W8A8 layer tokens/s", "value": round(value, 1), "unit": "layer-tokens/s",
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+        "config": {"workload": shape.name, "arch": "post-LN" if shape.arch == 0 else "pre-LN", "mode": args.mode,
+                   "layers": st.layers, "batch": shape.B, "seq_len": shape.S, "hidden": shape.d, "heads": shape.H,
+                   "ffn": shape.f, "tokens_per_step": st.T * (shape.steps if decode else 1),
+                   "mask": ["none", "padding", "causal"][shape.mask]},
+        "stack_tokens_per_s": round(value / st.layers, 1),
+        "us_per_layer": round(ms_per_step * 1e3 / (st.layers * (shape.steps if decode else 1)), 2),
+        "wall_ms_timed_region": round(wall_ms, 2),
+    }
+    if st.kv_len is not None:
+        real = int(st.kv_len.sum().item())
+        rec["real_token_fraction"] = round(real / st.T, 4)
+    log("[bench] dominant kernel alone (FC1 GeMM^quant + GELU^quant)")
+    rec["roofline"] = fc1_roofline(hero, shape, args.seed)
+    if not args.no_extras:
+        log("[bench] LN^quant bandwidth")
+        Tln = max(st.T, 16384)
+        rec["ln_quant"] = ln_bandwidth(hero, Tln, shape.d)
+        log("[bench] GEMM sweep")
+        rec["gemm_sweep"] = gemm_sweep(hero, args.seed)
+        del st
+        torch.cuda.empty_cache()
+        log("[bench] CPU oracle baseline")
+        rec["cpu_baseline"] = cpu_baseline(shape, args.seed, args.mode)
+    print(json.dumps(rec), flush=True)
+
+
+if __name__ == "__main__":
+    main()

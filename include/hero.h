@@ -95,9 +95,8 @@ hero_status hero_ln_quant(const void* x, hero_dtype x_dt, const float* x_row_sca
  *   out_col_scale[N]  required for GELU_REQUANT (the FWQ scale S_a), ignored otherwise.
  *   C   [M,N] in c_dt, leading dimension ldc: HERO_I32 (RAW), HERO_F16/HERO_BF16 (DEQUANT*),
  *       HERO_I8 (REQUANT*).  Other pairs -> HERO_ERR_UNSUPPORTED.
- * Constraints: K % 16 == 0, K >= 16; lda, ldb multiples of 16; ldc*sizeof(C elem) and
- * ldr*2 multiples of 16 bytes... see hero_int8_gemm in the source for the exact checks;
- * M, N arbitrary (>= 0; zero is a no-op).
+ * Constraints: K % 64 == 0; lda, ldb multiples of 16; ldc, ldr multiples of 4; base
+ * pointers 16-byte aligned; M, N arbitrary (>= 0; zero is a no-op); M < 2^23.
  */
 hero_status hero_int8_gemm(const int8_t* A, int64_t lda, const float* a_row_scale,
                            const int8_t* Bt, int64_t ldb, const float* b_col_scale,

@@ -31,6 +31,10 @@ __device__ __forceinline__ float f16_bits_to_f32(uint32_t h) {
     return (float)__builtin_bit_cast(_Float16, (unsigned short)h);
 }
 __device__ __forceinline__ uint32_t f32_to_f16_bits(float f) {
+    // The value is first rounded to fp32 and then to fp16.  The empty asm keeps the
+    // compiler from merging a preceding multiply/fma with the conversion into one
+    // mixed-precision instruction, which would round only once.
+    asm volatile("" : "+v"(f));
     return (uint32_t)__builtin_bit_cast(unsigned short, (_Float16)f);      // v_cvt_f16_f32: RNE
 }
 template <int DT> __device__ __forceinline__ float hp_to_f32(uint32_t h) {

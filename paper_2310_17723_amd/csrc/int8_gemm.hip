@@ -220,10 +220,9 @@ extern "C" hero_status hero_int8_gemm(const int8_t* A, int64_t lda, const float*
         if (epi != HERO_EPI_DEQUANT) return HERO_ERR_UNSUPPORTED;
         if (res_dt != HERO_F16 && res_dt != HERO_BF16) return HERO_ERR_UNSUPPORTED;
         if (ldr < N) return HERO_ERR_SHAPE;
-        if (ldr % 8 != 0 || !hero_aligned16(residual)) return HERO_ERR_ALIGN;
+        if (ldr % 4 != 0 || !hero_aligned16(residual)) return HERO_ERR_ALIGN;
     }
-    const int64_t c_elem = c_dt == HERO_I32 ? 4 : (c16 ? 2 : 1);
-    if (lda % 16 != 0 || ldb % 16 != 0 || (ldc * c_elem) % 16 != 0) return HERO_ERR_ALIGN;
+    if (lda % 16 != 0 || ldb % 16 != 0 || ldc % 4 != 0) return HERO_ERR_ALIGN;
     if (!hero_aligned16(A) || !hero_aligned16(Bt) || !hero_aligned16(C)) return HERO_ERR_ALIGN;
     if ((M + 127) / 128 > 65535) return HERO_ERR_UNSUPPORTED;
 

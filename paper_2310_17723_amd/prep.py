@@ -1,0 +1,131 @@
+"""Offline preparation of a layer's parameters for libhero (host-side tool, not on the hot
+path): calibrate the static scales with a forward pass of the unquantized layer, fold
+them into the weights, quantize the weights column-wise.
+
+Paper: Sec. 2.1 (column-wise weight quantization W = W_int8 Diag(S_w); FWQ / SQ scales are
+calibrated in a pre-processing phase), Sec. 2.2.2 (W~_q = W_q / S_q, d~ = S_q S_k / sqrt(d),
+W~_o = S_attn W_o / S_o), Sec. 2.2.3 (W~_2 = S_a W_2 / S_x2), Sec. 3 (calibration is a
+forward pass recording min/max, no truncation).
+
+Everything here is plain torch tensor algebra on whatever device the inputs live on; it
+produces the tensors `hero_layer_weights` points to.  The hot path never calls it.
+"""
+from __future__ import annotations
+
+import math
+
+import torch
+
+from . import binding as HB
+
+
+def _ln(x, g, b, eps):
+    return torch.nn.functional.layer_norm(x, (x.shape[-1],), g, b, eps)
+
+
+def _attention(q, k, v, B, S, H, Dh, mask, kv_len):
+    q, k, v = (t.view(B, S, H, Dh).permute(0, 2, 1, 3) for t in (q, k, v))
+    a = (q @ k.transpose(-1, -2)) / math.sqrt(Dh)
+    idx = torch.arange(S, device=q.device)
+    vis = torch.ones((B, 1, S, S), dtype=torch.bool, device=q.device)
+    if kv_len is not None:
+        vis = vis & (idx[None, None, None, :] < kv_len.view(B, 1, 1, 1))
+    if mask == HB.MASK_CAUSAL:
+        L = kv_len.view(B, 1, 1, 1) if kv_len is not None else S
+        vis = vis & (idx[None, None, None, :] <= idx[None, None, :, None] + (L - S))
+    a = a.masked_fill(~vis, float("-inf"))
+    p = torch.softmax(a, dim=-1)
+    p = torch.nan_to_num(p, nan=0.0)                      # rows that see no key
+    return (p @ v).permute(0, 2, 1, 3).reshape(B * S, H * Dh)
+
+
+def reference_layer(p, x, arch, H, Dh, eps, mask, B, S, kv_len=None):
+    """Unquantized layer forward (fp64 on the given device); returns the intermediates
+    whose ranges the static scales are calibrated on, and the layer output."""
+    P = {k: v.double() for k, v in p.items()}
+    x = x.double()
+    d = x.shape[1]
+    xin = _ln(x, P["ln1_g"], P["ln1_b"], eps) if arch == HB.ARCH_PRE_LN else x
+    qkv = xin @ P["w_qkv"] + P["b_qkv"]
+    t = {"q": qkv[:, :d], "k": qkv[:, d:2 * d], "v": qkv[:, 2 * d:]}
+    t["attn"] = _attention(t["q"], t["k"], t["v"], B, S, H, Dh, mask, kv_len)
+    t["o"] = t["attn"] @ P["w_o"] + P["b_o"]
+    if arch == HB.ARCH_POST_LN:
+        mid = _ln(x + t["o"], P["ln1_g"], P["ln1_b"], eps)
+        x1 = mid @ P["w_1"] + P["b_1"]
+    else:
+        mid = x + t["o"]
+        x1 = _ln(mid, P["ln2_g"], P["ln2_b"], eps) @ P["w_1"] + P["b_1"]
+    t["a"] = torch.nn.functional.gelu(x1)
+    t["x2"] = t["a"] @ P["w_2"] + P["b_2"]
+    t["out"] = _ln(mid + t["x2"], P["ln2_g"], P["ln2_b"], eps) if arch == HB.ARCH_POST_LN else mid + t["x2"]
+    return t
+
+
+def _scale(a, dim=None):
+    m = a.abs().amax() if dim is None else a.abs().amax(dim=dim)
+    m = torch.where(m == 0, torch.full_like(m, 127.0), m)
+    return (m / 127.0).float()
+
+
+def calibrate(p, x_calib, arch, H, Dh, eps, mask, B, S, kv_len=None):
+    """Static scales: SQ scalars for X_q, X_k, X_v; FWQ vectors for X_attn, X_o, A, X_2."""
+    t = reference_layer(p, x_calib, arch, H, Dh, eps, mask, B, S, kv_len)
+    sc = {"S_q": _scale(t["q"]), "S_k": _scale(t["k"]), "S_v": _scale(t["v"]),
+          "S_attn": _scale(t["attn"], 0), "S_o": _scale(t["o"], 0), "S_a": _scale(t["a"], 0),
+          "S_x2": _scale(t["x2"], 0), "S_p": torch.tensor(1.0 / 255.0, dtype=torch.float32, device=x_calib.device)}
+    return sc, t["out"]
+
+
+def quantize_columns(W):
+    """Column-wise weight quantization of W [K, N] (fp64/fp32): returns int8 codes stored
+    [N, K] (each output column's K values contiguous) and the fp32 scale per column."""
+    W = W.float()
+    amax = W.abs().amax(dim=0)
+    s = torch.where(amax == 0, torch.ones_like(amax), amax / 127.0)
+    q = torch.clamp(torch.round(W / s[None, :]), -127, 127).to(torch.int8)      # torch.round: half to even
+    return q.t().contiguous(), s.contiguous()
+
+
+def prepare(p, sc, arch, d, Dh, mode=HB.MODE_M3):
+    """Fold the static scales into the weights and quantize.  Returns (tensors, qk_scale,
+    p_scale): `tensors` is keyed by the field names of hero_layer_weights."""
+    P = {k: v.double() for k, v in p.items()}
+    post = arch == HB.ARCH_POST_LN
+    t = {}
+    if mode & HB.M_ATTN:
+        div = torch.cat([sc["S_q"].double().expand(d), sc["S_k"].double().expand(d), sc["S_v"].double().expand(d)])
+        qk_scale = float(sc["S_q"].double() * sc["S_k"].double() / math.sqrt(Dh))
+    else:
+        div = torch.ones(3 * d, dtype=torch.float64, device=P["w_qkv"].device)
+        qk_scale = 1.0 / math.sqrt(Dh)
+    t["w_qkv"], t["w_qkv_s"] = quantize_columns(P["w_qkv"] / div)
+    t["b_qkv"] = (P["b_qkv"] / div).float()
+    pv = sc["S_p"].double() * sc["S_v"].double()
+    if mode & HB.M_ATTN_OUT:
+        t["attn_out_scale"] = (pv / sc["S_attn"].double()).float()
+        wo, bo = sc["S_attn"].double()[:, None] * P["w_o"], P["b_o"]
+        if post:
+            wo, bo = wo / sc["S_o"].double()[None, :], bo / sc["S_o"].double()
+        t["w_o"], t["w_o_s"] = quantize_columns(wo)
+        t["b_o"] = bo.float()
+    else:
+        t["attn_out_scale"] = pv.float().reshape(1)
+        t["w_o_bf16"] = P["w_o"].t().contiguous().to(torch.bfloat16)
+        t["b_o"] = P["b_o"].float()
+    t["w_1"], t["w_1_s"] = quantize_columns(P["w_1"])
+    t["b_1"] = P["b_1"].float()
+    if mode & HB.M_FC2:
+        w2, b2 = sc["S_a"].double()[:, None] * P["w_2"], P["b_2"]
+        if post:
+            w2, b2 = w2 / sc["S_x2"].double()[None, :], b2 / sc["S_x2"].double()
+        t["w_2"], t["w_2_s"] = quantize_columns(w2)
+        t["b_2"] = b2.float()
+    else:
+        t["w_2_bf16"] = P["w_2"].t().contiguous().to(torch.bfloat16)
+        t["b_2"] = P["b_2"].float()
+    for k in ("S_o", "S_x2", "S_a"):
+        t[k] = sc[k].float().contiguous()
+    for k in ("ln1_g", "ln1_b", "ln2_g", "ln2_b"):
+        t[k] = p[k].float().contiguous()
+    return t, qk_scale, float(sc["S_p"])

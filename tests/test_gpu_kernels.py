@@ -110,7 +110,7 @@ def test_gemm_one_hot_probes_operand_layout(hero):
     assert_exact(got, Bt[:, ks].T.astype(np.int32))
     # extreme magnitude: K = 16384 of 127 * -127
     A = np.full((3, 16384), 127, np.int8)
-    Bt = np.full((5, 16384), -127, np.int8)
+    Bt = np.full((8, 16384), -127, np.int8)
     assert (to_np(hero.hero_int8_gemm(dev(A), dev(Bt))) == -127 * 127 * 16384).all()
 
 
