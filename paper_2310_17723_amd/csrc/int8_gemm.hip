@@ -3,22 +3,31 @@
 // behind the accumulators (paper Sec. 2.1 GEMM convention and column-wise weight scales;
 // Sec. 2.2.2 fused dequantization and the bare Round after folding; Sec. 2.2.3 GELU^quant).
 //
-// Both operands are K-contiguous ([M][K] activations, [N][K] weights), so each MFMA
-// operand fragment is one 128-bit LDS read.  The block tile is staged through LDS in
-// BK = 64 byte slabs (row stride padded to 80 bytes: conflict-free for 128-bit reads),
-// double buffered, with the next slab's global loads in flight during the MFMAs.
+// Both operands are K-contiguous ([M][K] activations, [N][K] weights), so every MFMA
+// operand fragment is one 128-bit LDS read.  MFMA: v_mfma_i32_32x32x32_i8 with the WEIGHT
+// fragment as first operand and the activation fragment as second, so the accumulator of
+// lane l holds, for ONE output row m = l % 32, the columns n = 8g + 4(l/32) + t (register
+// 4g + t): the per-row scale is one register and a lane owns 4 consecutive columns.
 //
-// MFMA: v_mfma_i32_32x32x32_i8.  The weight fragment is passed as the first operand and
-// the activation fragment as the second, so the accumulator of lane l holds, for ONE
-// output row m = l % 32, the columns n = 8g + 4(l/32) + t  (register 4g + t): four
-// consecutive columns per register group, which makes the epilogue's stores 4 columns
-// wide and the per-row scale a single register.
+// Two main loops share one epilogue:
+//   * int8_gemm_dma_kernel (large problems): 256x256 block tile, 8 waves of 128x64, slabs
+//     of 64 bytes of K copied global -> LDS directly (global_load_lds_dwordx4) through a
+//     ring of 4 stages; measured on MI355X the L2 -> CU path, not the matrix cores, bounds
+//     smaller tiles (a 128x128 tile needs 64 B/clk/CU at MFMA peak, the path gives 20-35).
+//   * int8_gemm_kernel (small or ragged problems): 128x128 tile staged through registers.
+// The epilogue stages 64-row strips of the output tile in LDS and writes whole row
+// segments (16 bytes per lane, consecutive lanes consecutive addresses).
 #include "hero_common.h"
+#include <cstdlib>
+#include <type_traits>
 
 namespace {
 
+constexpr int KMULT = 64;       // K must be a multiple of this
 constexpr int BK = 64;          // bytes of K per LDS slab
-constexpr int LDS_LD = BK + 16; // padded LDS row stride in bytes
+constexpr int LDS_LD = BK + 16; // padded slab row stride of the register-staged kernel
+constexpr int GROUP_M = 8;      // tile order: 8 row panels x 8 column panels run together on one XCD
+constexpr int NUM_XCD = 8;
 
 struct GemmArgs {
     const int8_t* A; int64_t lda; const float* a_row_scale;
@@ -27,59 +36,225 @@ struct GemmArgs {
     const float* out_col_scale;
     void* C; int64_t ldc;
     int M, N, K;
+    int ntm, ntn, per_xcd;      // tile grid and tiles per XCD
 };
 
-// One output value through the epilogue.  EPI / CDT are compile-time.
-template <int EPI, int CDT>
-__device__ __forceinline__ float epilogue_value(int acc, float rs, bool has_rs, float cs, float bs) {
-    float t = (float)acc;
-    if (has_rs) t = t * rs;
-    float y = fmaf(t, cs, bs);
-    if (EPI == HERO_EPI_DEQUANT_GELU || EPI == HERO_EPI_GELU_REQUANT) y = gelu_erf(y);
-    return y;
+template <int CDT> struct ElemSize { static constexpr int v = CDT == HERO_I32 ? 4 : (CDT == HERO_I8 ? 1 : 2); };
+
+// XCD-aware tile order: workgroups go round-robin to the 8 XCDs, so XCD x takes the
+// contiguous range [x * per_xcd, (x+1) * per_xcd) of a grouped order in which 64
+// consecutive tiles form an 8 x 8 square of panels (operands shared through that XCD's L2).
+template <int BM, int BN>
+__device__ __forceinline__ bool tile_origin(const GemmArgs& g, int& m0, int& n0) {
+    const int seq = (blockIdx.x % NUM_XCD) * g.per_xcd + blockIdx.x / NUM_XCD;
+    if (seq >= g.ntm * g.ntn) return false;
+    const int grp = seq / (GROUP_M * g.ntn), rem = seq % (GROUP_M * g.ntn);
+    const int gsize = min(g.ntm - grp * GROUP_M, GROUP_M);
+    m0 = (grp * GROUP_M + rem % gsize) * BM;
+    n0 = (rem / gsize) * BN;
+    return true;
 }
 
-template <int BM, int BN, int WM, int WN, int EPI, int CDT, int RDT>
-__global__ __launch_bounds__(WM * WN * 64) void int8_gemm_kernel(GemmArgs g) {
+// Per-column epilogue vectors of the tile -> LDS ([3][BN] floats: column scale, bias,
+// output scale), issued before the main loop so their latency hides behind it.
+template <int BN, int NT, int EPI>
+__device__ __forceinline__ void stage_col_vectors(const GemmArgs& g, float* sv, int n0, int tid) {
+    if (EPI == HERO_EPI_RAW_I32) return;
+    for (int c = tid; c < BN; c += NT) {
+        const int n = min(n0 + c, g.N - 1);
+        sv[c] = g.b_col_scale[n];
+        sv[BN + c] = g.bias ? g.bias[n] : 0.0f;
+        if (EPI == HERO_EPI_GELU_REQUANT) sv[2 * BN + c] = g.out_col_scale[n];
+    }
+}
+
+// ---- shared epilogue --------------------------------------------------------------------------
+// TM passes; pass i puts the block's rows {wm*TM*32 + i*32 + 0..31} (for every wm) through the
+// fp32 epilogue, stages them in LDS as a [WM*32][BN] strip and writes whole row segments to HBM.
+// Two strip buffers alternate when they fit, so a pass costs one barrier.
+template <int BM, int BN, int WM, int WN, int EPI, int CDT, int RDT, int STRIP_SPACE>
+__device__ __forceinline__ void epilogue(const GemmArgs& g, v16i (&acc)[BM / WM / 32][BN / WN / 32],
+                                         int8_t* smem, const float* sv, const float (&rsr)[BM / WM / 32],
+                                         int m0, int n0, int tid) {
     constexpr int NT = WM * WN * 64;
+    constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+    constexpr bool FUSE_RES = RDT >= 0;                       // residual added at store time, in fp32
+    constexpr int ES = FUSE_RES ? 4 : ElemSize<CDT>::v;       // bytes one value occupies in the strip
+    constexpr int ROWB = BN * ES, RS = ROWB + 16;             // strip row bytes, padded stride
+    constexpr int STRIP = WM * 32 * RS;
+    constexpr int NBUF = 2 * STRIP <= STRIP_SPACE ? 2 : 1;
+    static_assert(STRIP <= STRIP_SPACE, "strip does not fit the LDS left by the main loop");
+    constexpr int CH = ROWB / 16;                             // 16-byte chunks per strip row
+    const int lane = tid & 63, wave = tid >> 6, wm = wave / WN, wn = wave % WN;
+    const int hh = lane >> 5, ml = lane & 31;
+    const bool has_rs = g.a_row_scale != nullptr;
+    const bool interior = m0 + BM <= g.M && n0 + BN <= g.N && (g.ldc * ElemSize<CDT>::v) % 16 == 0;
+
+    // per-column vectors of this lane's 4-column groups, from LDS into registers once
+    v4f cs[TN * 4], bs[TN * 4], os[TN * 4];
+    if (EPI != HERO_EPI_RAW_I32) {
+#pragma unroll
+        for (int q = 0; q < TN * 4; ++q) {
+            const int nl = wn * TN * 32 + (q >> 2) * 32 + (q & 3) * 8 + hh * 4;
+            cs[q] = *reinterpret_cast<const v4f*>(sv + nl);
+            bs[q] = *reinterpret_cast<const v4f*>(sv + BN + nl);
+            if (EPI == HERO_EPI_GELU_REQUANT) os[q] = *reinterpret_cast<const v4f*>(sv + 2 * BN + nl);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        int8_t* strip = smem + (NBUF == 2 ? (i & 1) * STRIP : 0);
+        int8_t* srow = strip + (wm * 32 + ml) * RS;
+        const float rs = rsr[i];
+#pragma unroll
+        for (int q = 0; q < TN * 4; ++q) {
+            const int j = q >> 2, gq = q & 3;
+            const int nl = wn * TN * 32 + j * 32 + gq * 8 + hh * 4;         // column inside the tile
+            if (EPI == HERO_EPI_RAW_I32) {
+                v4i o = {acc[i][j][4 * gq], acc[i][j][4 * gq + 1], acc[i][j][4 * gq + 2], acc[i][j][4 * gq + 3]};
+                *reinterpret_cast<v4i*>(srow + nl * 4) = o;
+                continue;
+            }
+            float y[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                float v = (float)acc[i][j][4 * gq + t];
+                if (has_rs) v = v * rs;
+                v = fmaf(v, cs[q][t], bs[q][t]);
+                if (EPI == HERO_EPI_DEQUANT_GELU || EPI == HERO_EPI_GELU_REQUANT) v = gelu_erf(v);
+                y[t] = v;
+            }
+            if (EPI == HERO_EPI_REQUANT) {
+                *reinterpret_cast<uint32_t*>(srow + nl) =
+                    pack4_i8(round_sat_i8(y[0]), round_sat_i8(y[1]), round_sat_i8(y[2]), round_sat_i8(y[3]));
+            } else if (EPI == HERO_EPI_GELU_REQUANT) {
+                *reinterpret_cast<uint32_t*>(srow + nl) =
+                    pack4_i8(quant_code_div(y[0], os[q][0]), quant_code_div(y[1], os[q][1]),
+                             quant_code_div(y[2], os[q][2]), quant_code_div(y[3], os[q][3]));
+            } else if (FUSE_RES) {
+                v4f o = {y[0], y[1], y[2], y[3]};
+                *reinterpret_cast<v4f*>(srow + nl * 4) = o;
+            } else {
+                uint32_t h0 = f32_to_hp<CDT>(y[0]), h1 = f32_to_hp<CDT>(y[1]), h2 = f32_to_hp<CDT>(y[2]), h3 = f32_to_hp<CDT>(y[3]);
+                v2i o = {(int)(h0 | (h1 << 16)), (int)(h2 | (h3 << 16))};
+                *reinterpret_cast<v2i*>(srow + nl * 2) = o;
+            }
+        }
+        __syncthreads();
+        // ---- strip -> HBM
+#pragma unroll
+        for (int idx = tid; idx < WM * 32 * CH; idx += NT) {
+            const int row = idx / CH, c = idx % CH;
+            const int mg = m0 + (row >> 5) * TM * 32 + i * 32 + (row & 31);
+            const int8_t* sp = strip + row * RS + c * 16;
+            if constexpr (FUSE_RES) {               // 4 fp32 values + 4 residual values -> 4 x 16-bit
+                const int n = n0 + c * 4;
+                if (!interior && (mg >= g.M || n >= g.N)) continue;
+                v4f y = *reinterpret_cast<const v4f*>(sp);
+                const uint16_t* rp = (const uint16_t*)g.residual + (int64_t)mg * g.ldr + n;
+                uint16_t* cp = (uint16_t*)g.C + (int64_t)mg * g.ldc + n;
+                if (interior || n + 3 < g.N) {
+                    v2i rv = *reinterpret_cast<const v2i*>(rp);
+                    uint32_t h[4];
+#pragma unroll
+                    for (int t = 0; t < 4; ++t)
+                        h[t] = f32_to_hp<CDT>(y[t] + hp_to_f32<RDT>(((uint32_t)rv[t >> 1] >> (16 * (t & 1))) & 0xffffu));
+                    v2i o = {(int)(h[0] | (h[1] << 16)), (int)(h[2] | (h[3] << 16))};
+                    *reinterpret_cast<v2i*>(cp) = o;
+                } else {
+                    for (int t = 0; t < 4; ++t)
+                        if (n + t < g.N) cp[t] = (uint16_t)f32_to_hp<CDT>(y[t] + hp_to_f32<RDT>(rp[t]));
+                }
+            } else {
+                constexpr int EPC = 16 / ES;         // elements per 16-byte chunk
+                const int n = n0 + c * EPC;
+                if (!interior && (mg >= g.M || n >= g.N)) continue;
+                int8_t* cp = (int8_t*)g.C + ((int64_t)mg * g.ldc + n) * ES;
+                v4i w = *reinterpret_cast<const v4i*>(sp);
+                if (interior) {
+                    *reinterpret_cast<v4i*>(cp) = w;
+                } else {                             // ragged edge or a 4-byte-aligned ldc: dword / element stores
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const int nq = n + q * (4 / ES);
+                        if (nq + (4 / ES) <= g.N) *reinterpret_cast<int*>(cp + 4 * q) = w[q];
+                        else if (ES < 4) {
+                            for (int b = 0; b < 4 / ES; ++b)
+                                if (nq + b < g.N) {
+                                    if (ES == 1) cp[4 * q + b] = (int8_t)(w[q] >> (8 * b));
+                                    else *reinterpret_cast<uint16_t*>(cp + 4 * q + 2 * b) = (uint16_t)(w[q] >> (16 * b));
+                                }
+                        }
+                    }
+                }
+            }
+        }
+        if (NBUF == 1 && i + 1 < TM) __syncthreads();
+    }
+}
+
+// =====================================================================================
+// Register-staged main loop (small / ragged problems).  BK-byte slabs, double-buffered in
+// LDS with an 80-byte padded row stride, PD slabs in flight in registers.
+// =====================================================================================
+template <int BM, int BN, int WM, int WN, int PD, int MINW, int EPI, int CDT, int RDT>
+__global__ __launch_bounds__(WM * WN * 64, MINW) void int8_gemm_kernel(GemmArgs g) {
+    constexpr int NT = WM * WN * 64;
+    constexpr int CPR = BK / 16;                              // 16-byte chunks per slab row
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;      // 32x32 MFMA tiles per wave
-    constexpr int A_UNITS = BM * (BK / 16) / NT, B_UNITS = BN * (BK / 16) / NT;
-    static_assert(BM * (BK / 16) % NT == 0 && BN * (BK / 16) % NT == 0, "tile/threads mismatch");
-    __shared__ __attribute__((aligned(16))) int8_t sA[2][BM * LDS_LD];
-    __shared__ __attribute__((aligned(16))) int8_t sB[2][BN * LDS_LD];
+    constexpr int A_UNITS = BM * CPR / NT, B_UNITS = BN * CPR / NT;
+    static_assert(BM * CPR % NT == 0 && BN * CPR % NT == 0, "tile/threads mismatch");
+    static_assert(PD % 2 == 0, "prefetch distance must be even (LDS buffer parity is compile-time)");
+    constexpr int SLAB_BYTES = 2 * (BM + BN) * LDS_LD;
+    constexpr int ES = RDT >= 0 ? 4 : ElemSize<CDT>::v;
+    constexpr int STRIP_BYTES = WM * 32 * (BN * ES + 16);
+    constexpr int POOL = SLAB_BYTES > STRIP_BYTES ? SLAB_BYTES : STRIP_BYTES;
+    __shared__ __attribute__((aligned(16))) int8_t smem[POOL + 3 * BN * 4];
+    int8_t* const sA0 = smem;                                 // [2][BM * LDS_LD]
+    int8_t* const sB0 = smem + 2 * BM * LDS_LD;               // [2][BN * LDS_LD]
+    float* const sv = reinterpret_cast<float*>(smem + POOL);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
-    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+    int m0, n0;
+    if (!tile_origin<BM, BN>(g, m0, n0)) return;
     const int KT = g.K / BK;
 
-    // global -> register staging: unit u of this thread is row (idx/4), 16-byte chunk (idx%4)
-    v4i ra[A_UNITS], rb[B_UNITS];
-    auto load_slab = [&](int kt) {
+    stage_col_vectors<BN, NT, EPI>(g, sv, n0, tid);
+    float rsr[TM];
 #pragma unroll
-        for (int u = 0; u < A_UNITS; ++u) {
-            int idx = tid + u * NT, row = idx >> 2, ch = idx & 3;
-            int m = min(m0 + row, g.M - 1);                                   // clamp: ragged M
-            ra[u] = *reinterpret_cast<const v4i*>(g.A + (int64_t)m * g.lda + (int64_t)kt * BK + ch * 16);
-        }
+    for (int i = 0; i < TM; ++i)
+        rsr[i] = (EPI != HERO_EPI_RAW_I32 && g.a_row_scale) ? g.a_row_scale[min(m0 + wm * TM * 32 + i * 32 + (lane & 31), g.M - 1)] : 1.0f;
+
+    // global -> register -> LDS staging.  Unit u of this thread is slab row idx / CPR,
+    // 16-byte chunk idx % CPR.  PD slabs are in flight in registers ahead of the one in LDS.
+    const int8_t* pa[A_UNITS];
+    const int8_t* pb[B_UNITS];
 #pragma unroll
-        for (int u = 0; u < B_UNITS; ++u) {
-            int idx = tid + u * NT, row = idx >> 2, ch = idx & 3;
-            int n = min(n0 + row, g.N - 1);
-            rb[u] = *reinterpret_cast<const v4i*>(g.Bt + (int64_t)n * g.ldb + (int64_t)kt * BK + ch * 16);
-        }
+    for (int u = 0; u < A_UNITS; ++u) {
+        int idx = tid + u * NT, row = idx / CPR, ch = idx % CPR;
+        pa[u] = g.A + (int64_t)min(m0 + row, g.M - 1) * g.lda + ch * 16;          // clamp: ragged M
+    }
+#pragma unroll
+    for (int u = 0; u < B_UNITS; ++u) {
+        int idx = tid + u * NT, row = idx / CPR, ch = idx % CPR;
+        pb[u] = g.Bt + (int64_t)min(n0 + row, g.N - 1) * g.ldb + ch * 16;
+    }
+    const int lds_unit0 = (tid / CPR) * LDS_LD + (tid % CPR) * 16;                // + u * (NT / CPR) * LDS_LD
+    v4i ra[PD][A_UNITS], rb[PD][B_UNITS];
+    auto load_slab = [&](int kt, int p) {
+#pragma unroll
+        for (int u = 0; u < A_UNITS; ++u) ra[p][u] = *reinterpret_cast<const v4i*>(pa[u] + (int64_t)kt * BK);
+#pragma unroll
+        for (int u = 0; u < B_UNITS; ++u) rb[p][u] = *reinterpret_cast<const v4i*>(pb[u] + (int64_t)kt * BK);
     };
-    auto store_slab = [&](int buf) {
+    auto store_slab = [&](int buf, int p) {
 #pragma unroll
-        for (int u = 0; u < A_UNITS; ++u) {
-            int idx = tid + u * NT, row = idx >> 2, ch = idx & 3;
-            *reinterpret_cast<v4i*>(&sA[buf][row * LDS_LD + ch * 16]) = ra[u];
-        }
+        for (int u = 0; u < A_UNITS; ++u)
+            *reinterpret_cast<v4i*>(sA0 + buf * BM * LDS_LD + lds_unit0 + u * (NT / CPR) * LDS_LD) = ra[p][u];
 #pragma unroll
-        for (int u = 0; u < B_UNITS; ++u) {
-            int idx = tid + u * NT, row = idx >> 2, ch = idx & 3;
-            *reinterpret_cast<v4i*>(&sB[buf][row * LDS_LD + ch * 16]) = rb[u];
-        }
+        for (int u = 0; u < B_UNITS; ++u)
+            *reinterpret_cast<v4i*>(sB0 + buf * BN * LDS_LD + lds_unit0 + u * (NT / CPR) * LDS_LD) = rb[p][u];
     };
 
     v16i acc[TM][TN];
@@ -90,107 +265,238 @@ __global__ __launch_bounds__(WM * WN * 64) void int8_gemm_kernel(GemmArgs g) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
-    load_slab(0);
-    store_slab(0);
+    // Every load is unconditional (slab indices are clamped to the last slab, whose
+    // redundant copies are never read): with no branch between a load and its use the
+    // compiler can wait for exactly the oldest register set and leave the younger ones
+    // in flight.
+    const int last = KT - 1;
+    load_slab(0, 0);
+    store_slab(0, 0);
+#pragma unroll
+    for (int p = 0; p < PD; ++p) load_slab(min(1 + p, last), p);  // slab s waits in register set (s-1) % PD
     __syncthreads();
-    const int frag_off = (lane & 31) * LDS_LD + (lane >> 5) * 16;
-    for (int kt = 0; kt < KT; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < KT) load_slab(kt + 1);
+    const int frag_a = (wm * TM * 32 + (lane & 31)) * LDS_LD + (lane >> 5) * 16;
+    const int frag_b = (wn * TN * 32 + (lane & 31)) * LDS_LD + (lane >> 5) * 16;
+    // One slab.  The body is written in the issue order wanted and pinned with scheduling
+    // barriers: every MFMA is followed by at most one LDS read, one LDS write or one global
+    // load.  A wave issues in order, and a burst of vector-memory instructions stalls it in
+    // front of its next MFMA while the address unit drains; spread out, the memory
+    // instructions issue in the shadow of the 32-cycle MFMAs.
+    constexpr int NM = TM * TN, NFR = TM + TN, NW = A_UNITS + B_UNITS;
+    static_assert(NW <= NM && NFR <= NM, "interleave plan needs one slot per memory instruction");
+    auto iteration = [&](int kt, int buf, auto U) {
+        constexpr int u = decltype(U)::value;
+        const int8_t* sa = sA0 + buf * BM * LDS_LD + frag_a;
+        const int8_t* sb = sB0 + buf * BN * LDS_LD + frag_b;
+        int8_t* wa = sA0 + (buf ^ 1) * BM * LDS_LD + lds_unit0;
+        int8_t* wb = sB0 + (buf ^ 1) * BN * LDS_LD + lds_unit0;
+        const int64_t koff = (int64_t)min(kt + 1 + PD, last) * BK;
+        v4i f0[NFR], f1[NFR];                                     // fragments of k-step 0 / 1: B tiles first, then A tiles
 #pragma unroll
-        for (int ks = 0; ks < BK / 32; ++ks) {
-            v4i fa[TM], fb[TN];
+        for (int t = 0; t < NFR; ++t)
+            f0[t] = *reinterpret_cast<const v4i*>((t < TN ? sb + t * 32 * LDS_LD : sa + (t - TN) * 32 * LDS_LD));
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
-                fa[i] = *reinterpret_cast<const v4i*>(&sA[buf][(wm * TM * 32 + i * 32) * LDS_LD + frag_off + ks * 32]);
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-                fb[j] = *reinterpret_cast<const v4i*>(&sB[buf][(wn * TN * 32 + j * 32) * LDS_LD + frag_off + ks * 32]);
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[j], fa[i], acc[i][j], 0, 0, 0);
-        }
-        if (kt + 1 < KT) store_slab(buf ^ 1);
-        __syncthreads();
-    }
-
-    // ---- epilogue -------------------------------------------------------------------------
-    const bool has_rs = g.a_row_scale != nullptr;
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        const int m = m0 + wm * TM * 32 + i * 32 + (lane & 31);
-        if (m >= g.M) continue;
-        const float rs = (EPI != HERO_EPI_RAW_I32 && has_rs) ? g.a_row_scale[m] : 1.0f;
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-#pragma unroll
-            for (int gq = 0; gq < 4; ++gq) {
-                const int n = n0 + wn * TN * 32 + j * 32 + gq * 8 + (lane >> 5) * 4;
-                if (n >= g.N) continue;
-                const bool full = n + 3 < g.N;
-                const int64_t co = (int64_t)m * g.ldc + n;
-                if (EPI == HERO_EPI_RAW_I32) {
-                    int* cp = (int*)g.C + co;
-                    if (full) {
-                        v4i o = {acc[i][j][4 * gq], acc[i][j][4 * gq + 1], acc[i][j][4 * gq + 2], acc[i][j][4 * gq + 3]};
-                        *reinterpret_cast<v4i*>(cp) = o;
-                    } else {
-                        for (int t = 0; t < 4; ++t) if (n + t < g.N) cp[t] = acc[i][j][4 * gq + t];
-                    }
-                    continue;
-                }
-                float y[4];
-#pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    const int nn = min(n + t, g.N - 1);
-                    const float cs = g.b_col_scale[nn];
-                    const float bs = g.bias ? g.bias[nn] : 0.0f;
-                    y[t] = epilogue_value<EPI, CDT>(acc[i][j][4 * gq + t], rs, has_rs, cs, bs);
-                }
-                if (EPI == HERO_EPI_REQUANT || EPI == HERO_EPI_GELU_REQUANT) {
-                    int q[4];
-#pragma unroll
-                    for (int t = 0; t < 4; ++t) {
-                        if (EPI == HERO_EPI_GELU_REQUANT) q[t] = quant_code_div(y[t], g.out_col_scale[min(n + t, g.N - 1)]);
-                        else q[t] = round_sat_i8(y[t]);
-                    }
-                    int8_t* cp = (int8_t*)g.C + co;
-                    if (full) *reinterpret_cast<uint32_t*>(cp) = pack4_i8(q[0], q[1], q[2], q[3]);
-                    else for (int t = 0; t < 4; ++t) if (n + t < g.N) cp[t] = (int8_t)q[t];
-                } else {    // DEQUANT / DEQUANT_GELU -> 16-bit float
-                    if (RDT >= 0) {
-                        const uint16_t* rp = (const uint16_t*)g.residual + (int64_t)m * g.ldr + n;
-#pragma unroll
-                        for (int t = 0; t < 4; ++t) if (n + t < g.N) y[t] = y[t] + hp_to_f32<RDT>(rp[t]);
-                    }
-                    uint16_t* cp = (uint16_t*)g.C + co;
-                    uint32_t h[4];
-#pragma unroll
-                    for (int t = 0; t < 4; ++t) h[t] = f32_to_hp<CDT>(y[t]);
-                    if (full) {
-                        v2i o = {(int)(h[0] | (h[1] << 16)), (int)(h[2] | (h[3] << 16))};
-                        *reinterpret_cast<v2i*>(cp) = o;
-                    } else {
-                        for (int t = 0; t < 4; ++t) if (n + t < g.N) cp[t] = (uint16_t)h[t];
-                    }
-                }
+        for (int n = 0; n < NM; ++n) {                             // k-step 0
+            const int jj = n / TM, ii = n % TM;
+            acc[ii][jj] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f0[jj], f0[TN + ii], acc[ii][jj], 0, 0, 0);
+            if (n < NFR)
+                f1[n] = *reinterpret_cast<const v4i*>((n < TN ? sb + n * 32 * LDS_LD : sa + (n - TN) * 32 * LDS_LD) + 32);
+            if (n < NW) {                                          // slab kt + 1 from register set u into LDS
+                if (n < A_UNITS) *reinterpret_cast<v4i*>(wa + n * (NT / CPR) * LDS_LD) = ra[u][n];
+                else *reinterpret_cast<v4i*>(wb + (n - A_UNITS) * (NT / CPR) * LDS_LD) = rb[u][n - A_UNITS];
             }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int n = 0; n < NM; ++n) {                             // k-step 1
+            const int jj = n / TM, ii = n % TM;
+            acc[ii][jj] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f1[jj], f1[TN + ii], acc[ii][jj], 0, 0, 0);
+            if (n < NW) {                                          // slab kt + 1 + PD into the freed register set
+                if (n < A_UNITS) ra[u][n] = *reinterpret_cast<const v4i*>(pa[n] + koff);
+                else rb[u][n - A_UNITS] = *reinterpret_cast<const v4i*>(pb[n - A_UNITS] + koff);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        __syncthreads();
+    };
+    int kt = 0;
+    for (; kt + PD <= KT; kt += PD) {
+        iteration(kt, 0, std::integral_constant<int, 0>{});
+        iteration(kt + 1, 1, std::integral_constant<int, 1>{});
+        if constexpr (PD >= 4) {
+            iteration(kt + 2, 0, std::integral_constant<int, 2>{});
+            iteration(kt + 3, 1, std::integral_constant<int, 3>{});
         }
     }
+    if (kt < KT) { iteration(kt, 0, std::integral_constant<int, 0>{}); ++kt; }
+    if constexpr (PD >= 4) {
+        if (kt < KT) { iteration(kt, 1, std::integral_constant<int, 1>{}); ++kt; }
+        if (kt < KT) { iteration(kt, 0, std::integral_constant<int, 2>{}); ++kt; }
+    }
+    // (the loop's closing barrier also guards the reuse of the slab buffers by the epilogue)
+    epilogue<BM, BN, WM, WN, EPI, CDT, RDT, POOL>(g, acc, smem, sv, rsr, m0, n0, tid);
 }
 
-template <int BM, int BN, int WM, int WN, int EPI, int CDT, int RDT>
-hero_status launch_tile(const GemmArgs& g, hipStream_t st) {
-    dim3 grid((g.N + BN - 1) / BN, (g.M + BM - 1) / BM), block(WM * WN * 64);
-    hipLaunchKernelGGL((int8_gemm_kernel<BM, BN, WM, WN, EPI, CDT, RDT>), grid, block, 0, st, g);
+// =====================================================================================
+// Direct-to-LDS main loop (large problems).  A wave-level global_load_lds_dwordx4 writes
+// 1 KB of consecutive LDS, so slab rows are 64 bytes, unpadded, and the four 16-byte chunks
+// of row r are stored at position c ^ ((r >> 2) & 3): the 128-bit fragment reads of 16
+// consecutive rows then fall into 16 different 16-byte bank groups.
+// =====================================================================================
+// s_waitcnt immediate that waits only for vmcnt <= n (gfx9 encoding: vmcnt in bits 3:0 and 15:14,
+// expcnt 6:4 and lgkmcnt 11:8 left at their maxima).
+constexpr int vmcnt_imm(int n) { return 0x0F70 | (n & 15) | ((n >> 4) << 14); }
+
+// One direct global->LDS load: 64 lanes x 16 bytes land at LDS address lds_base + lane * 16
+// (lds_base is wave-uniform and travels in M0).  Written as inline assembly on purpose: the
+// compiler then does not track these loads and does not force vmcnt(0) in front of every LDS
+// read; the kernel waits for exactly the slab it is about to read (vmcnt counts them in order).
+__device__ __forceinline__ void dma16(const int8_t* gp, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :: "v"(gp), "s"(lds_base) : "memory", "m0");
+}
+__device__ __forceinline__ uint32_t lds_offset(const void* p) {
+    return (uint32_t)(uintptr_t)((const __attribute__((address_space(3))) void*)p);
+}
+
+template <int BM, int BN, int WM, int WN, int NS, int MINW, int EPI, int CDT, int RDT>
+__global__ __launch_bounds__(WM * WN * 64, MINW) void int8_gemm_dma_kernel(GemmArgs g) {
+    constexpr int NT = WM * WN * 64, NWAVE = WM * WN;
+    constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+    constexpr int A_BYTES = BM * BK, B_BYTES = BN * BK, STAGE = A_BYTES + B_BYTES;
+    constexpr int A_UNITS = A_BYTES / 16 / NT, B_UNITS = B_BYTES / 16 / NT, NW = A_UNITS + B_UNITS;
+    constexpr int NM = TM * TN, NFR = TM + TN;
+    static_assert(NS >= 3, "ring needs at least three stages");
+    static_assert(NW <= NM && NFR <= NM, "interleave plan needs one slot per memory instruction");
+    constexpr int ES = RDT >= 0 ? 4 : ElemSize<CDT>::v;
+    constexpr int STRIP_BYTES = WM * 32 * (BN * ES + 16);
+    constexpr int POOL = NS * STAGE > STRIP_BYTES ? NS * STAGE : STRIP_BYTES;
+    __shared__ __attribute__((aligned(1024))) int8_t smem[POOL + 3 * BN * 4];
+    float* const sv = reinterpret_cast<float*>(smem + POOL);
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+    int m0, n0;
+    if (!tile_origin<BM, BN>(g, m0, n0)) return;
+    const int KT = g.K / BK, last = KT - 1;
+
+    stage_col_vectors<BN, NT, EPI>(g, sv, n0, tid);
+    float rsr[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+        rsr[i] = (EPI != HERO_EPI_RAW_I32 && g.a_row_scale) ? g.a_row_scale[min(m0 + wm * TM * 32 + i * 32 + (lane & 31), g.M - 1)] : 1.0f;
+
+    // loader: unit u of wave w fills LDS granules [(u * NWAVE + w) * 64, +64) of the A (or B)
+    // part of a stage; lane l owns granule q = that + l  ->  row q / 4, stored chunk q % 4,
+    // which holds global chunk (q % 4) ^ ((row >> 2) & 3).
+    const int8_t* pa[A_UNITS];
+    const int8_t* pb[B_UNITS];
+#pragma unroll
+    for (int u = 0; u < A_UNITS; ++u) {
+        const int q = (u * NWAVE + wave) * 64 + lane, row = q >> 2, c = (q & 3) ^ ((row >> 2) & 3);
+        pa[u] = g.A + (int64_t)min(m0 + row, g.M - 1) * g.lda + c * 16;
+    }
+#pragma unroll
+    for (int u = 0; u < B_UNITS; ++u) {
+        const int q = (u * NWAVE + wave) * 64 + lane, row = q >> 2, c = (q & 3) ^ ((row >> 2) & 3);
+        pb[u] = g.Bt + (int64_t)min(n0 + row, g.N - 1) * g.ldb + c * 16;
+    }
+    const uint32_t wbase = __builtin_amdgcn_readfirstlane(lds_offset(smem) + wave * 1024);   // + stage * STAGE + unit offset
+    auto issue = [&](int n, int kt, int stage) {        // the n-th direct load of slab kt
+        const int64_t koff = (int64_t)min(kt, last) * BK;
+        if (n < A_UNITS) dma16(pa[n] + koff, wbase + stage * STAGE + n * NWAVE * 1024);
+        else dma16(pb[n - A_UNITS] + koff, wbase + stage * STAGE + A_BYTES + (n - A_UNITS) * NWAVE * 1024);
+    };
+    // fragment offsets inside a stage (row rr, k-step ks, half hh): rr*64 + ((2ks+hh) ^ ((rr>>2)&3))*16
+    const int hh = lane >> 5, ml = lane & 31;
+    int fo[2][NFR];
+#pragma unroll
+    for (int t = 0; t < NFR; ++t) {
+        const int rr = (t < TN ? wn * TN * 32 + t * 32 : wm * TM * 32 + (t - TN) * 32) + ml;
+        const int base = (t < TN ? A_BYTES : 0) + rr * 64;
+        fo[0][t] = base + (((0 + hh) ^ ((rr >> 2) & 3)) << 4);
+        fo[1][t] = base + (((2 + hh) ^ ((rr >> 2) & 3)) << 4);
+    }
+
+    v16i acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+
+    // prologue: slabs 0 .. NS-2 in flight, slab 0 landed, its k-step-0 fragments in registers
+#pragma unroll
+    for (int s0 = 0; s0 < NS - 1; ++s0)
+#pragma unroll
+        for (int n = 0; n < NW; ++n) issue(n, s0, s0);
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm((NS - 2) * NW));
+    __syncthreads();
+    v4i f0[NFR], f1[NFR];
+#pragma unroll
+    for (int t = 0; t < NFR; ++t) f0[t] = *reinterpret_cast<const v4i*>(smem + fo[0][t]);
+
+    // One slab per iteration; the barrier sits in the MIDDLE: k-step 0 runs on fragments read
+    // during the previous slab, the barrier then makes slab kt+1 visible, and k-step 1 runs
+    // while the first fragments of slab kt+1 and the direct loads of slab kt+NS-1 are issued,
+    // one memory instruction per MFMA.
+    int stage = 0;
+    for (int kt = 0; kt < KT; ++kt) {
+        const int8_t* st = smem + stage * STAGE;
+        const int nstage = stage + 1 == NS ? 0 : stage + 1;      // slab kt + 1
+        const int pstage = stage == 0 ? NS - 1 : stage - 1;      // slab kt - 1 == slab kt + NS - 1
+        const int8_t* stn = smem + nstage * STAGE;
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int n = 0; n < NM; ++n) {                             // k-step 0
+            const int jj = n / TM, ii = n % TM;
+            acc[ii][jj] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f0[jj], f0[TN + ii], acc[ii][jj], 0, 0, 0);
+            if (n < NFR) f1[n] = *reinterpret_cast<const v4i*>(st + fo[1][n]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm((NS - 3) * NW));     // slab kt + 1 has landed (mine)
+        __syncthreads();                                           // ... and everybody's
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int n = 0; n < NM; ++n) {                             // k-step 1
+            const int jj = n / TM, ii = n % TM;
+            acc[ii][jj] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f1[jj], f1[TN + ii], acc[ii][jj], 0, 0, 0);
+            if (n < NFR) f0[n] = *reinterpret_cast<const v4i*>(stn + fo[0][n]);
+            if (n < NW) issue(n, kt + NS - 1, pstage);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        stage = nstage;
+    }
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));                      // the redundant tail loads
+    __syncthreads();
+    epilogue<BM, BN, WM, WN, EPI, CDT, RDT, POOL>(g, acc, smem, sv, rsr, m0, n0, tid);
+}
+
+template <typename K>
+hero_status launch_grid(GemmArgs g, int BM, int BN, int threads, K kernel, hipStream_t st) {
+    g.ntm = (g.M + BM - 1) / BM;
+    g.ntn = (g.N + BN - 1) / BN;
+    const int64_t tiles = (int64_t)g.ntm * g.ntn;
+    g.per_xcd = (int)((tiles + NUM_XCD - 1) / NUM_XCD);
+    if ((int64_t)g.per_xcd * NUM_XCD > 0x7fffffffLL) return HERO_ERR_SHAPE;
+    hipLaunchKernelGGL(kernel, dim3((unsigned)(g.per_xcd * NUM_XCD)), dim3(threads), 0, st, g);
     return hero_launch_status();
 }
 
 template <int EPI, int CDT, int RDT>
 hero_status launch_epi(const GemmArgs& g, hipStream_t st) {
-    return launch_tile<128, 128, 2, 2, EPI, CDT, RDT>(g, st);
+    const char* e = getenv("HERO_GEMM_TILE");
+    int cfg = e ? atoi(e) : -1;
+    if (cfg < 0) cfg = ((int64_t)g.M * g.N >= (int64_t)256 * 256 * 192) ? 7 : 0;
+    switch (cfg) {
+    case 4: return launch_grid(g, 256, 128, 256, int8_gemm_dma_kernel<256, 128, 2, 2, 3, 2, EPI, CDT, RDT>, st);
+    case 7: return launch_grid(g, 256, 256, 512, int8_gemm_dma_kernel<256, 256, 2, 4, 4, 2, EPI, CDT, RDT>, st);
+    case 8: return launch_grid(g, 256, 256, 512, int8_gemm_dma_kernel<256, 256, 2, 4, 3, 2, EPI, CDT, RDT>, st);
+    case 2: return launch_grid(g, 256, 128, 256, int8_gemm_kernel<256, 128, 2, 2, 2, 2, EPI, CDT, RDT>, st);
+    default: return launch_grid(g, 128, 128, 256, int8_gemm_kernel<128, 128, 2, 2, 2, 2, EPI, CDT, RDT>, st);
+    }
 }
 
 }  // namespace
@@ -203,7 +509,7 @@ extern "C" hero_status hero_int8_gemm(const int8_t* A, int64_t lda, const float*
                                       int64_t M, int64_t N, int64_t K, void* stream) {
     if (M < 0 || N < 0 || K <= 0) return HERO_ERR_SHAPE;
     if (M > 0x7fffffffLL || N > 0x7fffffffLL || K > 0x7fffffffLL) return HERO_ERR_SHAPE;
-    if (K % BK != 0) return HERO_ERR_UNSUPPORTED;
+    if (K % KMULT != 0) return HERO_ERR_UNSUPPORTED;
     if (lda < K || ldb < K || ldc < N) return HERO_ERR_SHAPE;
     if (M == 0 || N == 0) return HERO_OK;
     if (!A || !Bt || !C) return HERO_ERR_NULL;
@@ -224,7 +530,6 @@ extern "C" hero_status hero_int8_gemm(const int8_t* A, int64_t lda, const float*
     }
     if (lda % 16 != 0 || ldb % 16 != 0 || ldc % 4 != 0) return HERO_ERR_ALIGN;
     if (!hero_aligned16(A) || !hero_aligned16(Bt) || !hero_aligned16(C)) return HERO_ERR_ALIGN;
-    if ((M + 127) / 128 > 65535) return HERO_ERR_UNSUPPORTED;
 
     GemmArgs g;
     g.A = A; g.lda = lda; g.a_row_scale = a_row_scale; g.Bt = Bt; g.ldb = ldb; g.b_col_scale = b_col_scale;
