@@ -485,18 +485,16 @@ hero_status launch_grid(GemmArgs g, int BM, int BN, int threads, K kernel, hipSt
     return hero_launch_status();
 }
 
+// Tile choice: the 256x256 direct-to-LDS kernel once the grid has enough tiles to fill about half
+// of the 256 CUs; the 128x128 register-staged kernel otherwise (small, skinny or ragged problems).
+// HERO_GEMM_TILE (0 / 1) overrides the choice for tuning runs.
 template <int EPI, int CDT, int RDT>
 hero_status launch_epi(const GemmArgs& g, hipStream_t st) {
     const char* e = getenv("HERO_GEMM_TILE");
     int cfg = e ? atoi(e) : -1;
-    if (cfg < 0) cfg = ((int64_t)g.M * g.N >= (int64_t)256 * 256 * 192) ? 7 : 0;
-    switch (cfg) {
-    case 4: return launch_grid(g, 256, 128, 256, int8_gemm_dma_kernel<256, 128, 2, 2, 3, 2, EPI, CDT, RDT>, st);
-    case 7: return launch_grid(g, 256, 256, 512, int8_gemm_dma_kernel<256, 256, 2, 4, 4, 2, EPI, CDT, RDT>, st);
-    case 8: return launch_grid(g, 256, 256, 512, int8_gemm_dma_kernel<256, 256, 2, 4, 3, 2, EPI, CDT, RDT>, st);
-    case 2: return launch_grid(g, 256, 128, 256, int8_gemm_kernel<256, 128, 2, 2, 2, 2, EPI, CDT, RDT>, st);
-    default: return launch_grid(g, 128, 128, 256, int8_gemm_kernel<128, 128, 2, 2, 2, 2, EPI, CDT, RDT>, st);
-    }
+    if (cfg < 0) cfg = ((int64_t)((g.M + 255) / 256) * ((g.N + 255) / 256) >= 96) ? 1 : 0;
+    if (cfg == 1) return launch_grid(g, 256, 256, 512, int8_gemm_dma_kernel<256, 256, 2, 4, 4, 2, EPI, CDT, RDT>, st);
+    return launch_grid(g, 128, 128, 256, int8_gemm_kernel<128, 128, 2, 2, 2, 2, EPI, CDT, RDT>, st);
 }
 
 }  // namespace

@@ -249,3 +249,28 @@ def test_int8_attn_strided_views_cache_and_decode(hero):
     z = hero.hero_int8_attn(dev(q1), dk.permute(0, 2, 1, 3)[:, :0], dv.permute(0, 2, 1, 3)[:, :0], qk_scale,
                             float(OL.S_P), dev(cs))
     assert not to_np(z).any()
+
+
+@pytest.mark.parametrize("M,N,K", [(8192, 4096, 1024), (2048 + 77, 3072 + 8, 1024), (8192, 1024, 4096)])
+def test_gemm_full_size_sampled_rows(hero, M, N, K):
+    """The benchmark's launch configuration (256x256 direct-to-LDS kernel, XCD-aware tile
+    order) at the sweep's full sizes: sampled output rows against the oracle, bit-exact, for
+    the raw accumulators, REQUANT and DEQUANT; every tile row-panel and a ragged edge are hit."""
+    c = synth.gemm_case(900 + M, M, K, N, outlier_rows=True)
+    A, Bt, rs, cs, bias = c["A"], c["Bt"], c["a_row_scale"], c["b_col_scale"], c["bias"]
+    g = synth.rng(901)
+    rows = np.unique(np.concatenate([g.integers(0, M, 48), [0, 255, 256, M - 1], np.arange(M // 256) * 256 + 131]))
+    dA, dB = dev(A), dev(Bt)
+    raw = to_np(hero.hero_int8_gemm(dA, dB))
+    assert_exact(raw[rows], O.gemm_i32(A[rows], Bt), "acc rows")
+    cs2 = (cs * np.float32(3000.0 / np.sqrt(K))).astype(np.float32)
+    got = to_np(hero.hero_int8_gemm(dA, dB, dev(rs), dev(cs2), dev(bias), epi=HB.EPI_REQUANT, out_dtype=torch.int8))
+    ref = O.int8_gemm(A[rows], Bt, a_row_scale=rs[rows], b_col_scale=cs2, bias=bias, epi=O.EPI_REQUANT, c_dt=O.I8)
+    assert_exact(got[rows], ref, "requant rows")
+    assert 0 < np.mean(np.abs(ref) == 127) < 0.5
+    got = to_np(hero.hero_int8_gemm(dA, dB, dev(rs), dev(cs), dev(bias), epi=HB.EPI_DEQUANT, out_dtype=torch.float16))
+    ref = O.int8_gemm(A[rows], Bt, a_row_scale=rs[rows], b_col_scale=cs, bias=bias, epi=O.EPI_DEQUANT, c_dt=O.F16)
+    assert_exact(got[rows], ref, "dequant rows")
+    # property that holds at any size: column sums of the raw accumulators
+    colsum = A.astype(np.int64).sum(axis=0) @ Bt.astype(np.int64).T
+    assert np.array_equal(raw.astype(np.int64).sum(axis=0), colsum)
