@@ -64,7 +64,7 @@ __device__ __forceinline__ void stage_col_vectors(const GemmArgs& g, float* sv, 
         const int n = min(n0 + c, g.N - 1);
         sv[c] = g.b_col_scale[n];
         sv[BN + c] = g.bias ? g.bias[n] : 0.0f;
-        if (EPI == HERO_EPI_GELU_REQUANT) sv[2 * BN + c] = g.out_col_scale[n];
+        if (EPI == HERO_EPI_GELU_REQUANT) sv[2 * BN + c] = __fdiv_rn(1.0f, g.out_col_scale[n]);   // 1 / S_a[j]
     }
 }
 
@@ -125,12 +125,12 @@ __device__ __forceinline__ void epilogue(const GemmArgs& g, v16i (&acc)[BM / WM 
                 y[t] = v;
             }
             if (EPI == HERO_EPI_REQUANT) {
-                *reinterpret_cast<uint32_t*>(srow + nl) =
-                    pack4_i8(round_sat_i8(y[0]), round_sat_i8(y[1]), round_sat_i8(y[2]), round_sat_i8(y[3]));
+                *reinterpret_cast<uint32_t*>(srow + nl) = quant4_sat(y[0], y[1], y[2], y[3]);
             } else if (EPI == HERO_EPI_GELU_REQUANT) {
+                // GELU^quant is in the +-1 LSB class (fp32 GELU vs the definition's fp64), so the
+                // division by S_a[j] is a multiplication by its reciprocal
                 *reinterpret_cast<uint32_t*>(srow + nl) =
-                    pack4_i8(quant_code_div(y[0], os[q][0]), quant_code_div(y[1], os[q][1]),
-                             quant_code_div(y[2], os[q][2]), quant_code_div(y[3], os[q][3]));
+                    quant4_sat(y[0] * os[q][0], y[1] * os[q][1], y[2] * os[q][2], y[3] * os[q][3]);
             } else if (FUSE_RES) {
                 v4f o = {y[0], y[1], y[2], y[3]};
                 *reinterpret_cast<v4f*>(srow + nl * 4) = o;

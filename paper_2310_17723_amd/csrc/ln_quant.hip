@@ -3,12 +3,22 @@
 // Sec. 2.2.3 last line of the quantized MLP flow).
 //
 // HBM-bound: every input element is read once and every output element written once.
-// One wavefront owns one row and keeps it in registers (NCH chunks of EPL elements per
-// lane, each chunk one 128-bit load per lane, consecutive lanes consecutive addresses);
-// the three row reductions (sum, sum of squared deviations, absmax) are 64-lane shuffles.
-// Statistics are fp32, mean first and variance about the mean.  The codes come from an
-// IEEE division by the row scale followed by round-half-even, exactly the primitive.
+//   * One wavefront owns one row at a time and keeps it in registers (NCH chunks of EPL
+//     elements per lane; a chunk is one 128-bit load per lane, consecutive lanes consecutive
+//     addresses).  Workgroups are persistent: a wave walks rows with a grid-sized stride and
+//     has the NEXT row's loads in flight while it works on the current one.
+//   * gamma, beta and the FWQ column scale are staged in LDS once per workgroup, not re-read
+//     per row (they would cost 4x the row's own HBM bytes in cache traffic).
+//   * The three row reductions (sum, sum of squared deviations, absmax) run on the DPP
+//     cross-lane network (quad_perm / row_mirror / row_bcast), no LDS round trips.
+//   * Statistics are fp32, mean first and variance about the mean.
+//   * Codes are rne(y / s) with IEEE fp32 division BY DEFINITION; the kernel multiplies by 1/s
+//     and, on the bit-exact path (no LayerNorm), falls back to the true division for the rare
+//     lanes whose product lies within 4e-5 of a rounding tie, the only place where the two can
+//     disagree (both are within 127 * 2^-23 of the exact quotient).  Rounding and the int8
+//     two's-complement byte come out of one fp32 add of 1.5 * 2^23.
 #include "hero_common.h"
+#include <type_traits>
 
 namespace {
 
@@ -23,162 +33,255 @@ struct LnArgs {
 
 __device__ __forceinline__ float byte_to_f32(int w, int i) { return (float)(int8_t)(w >> (8 * i)); }
 
-template <bool X_I8, int NCH>
+// ---- 64-lane reductions on the DPP network; the result is wave-uniform ---------------------------
+template <bool IS_MAX>
+__device__ __forceinline__ float dpp_step(float x, float y) { return IS_MAX ? fmaxf(x, y) : x + y; }
+template <bool IS_MAX>
+__device__ __forceinline__ float wave_reduce(float x) {
+    int xi;
+#define HERO_DPP(ctrl) __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), ctrl, 0xF, 0xF, true))
+    x = dpp_step<IS_MAX>(x, HERO_DPP(0xB1));      // quad_perm [1,0,3,2]
+    x = dpp_step<IS_MAX>(x, HERO_DPP(0x4E));      // quad_perm [2,3,0,1]
+    x = dpp_step<IS_MAX>(x, HERO_DPP(0x141));     // row_half_mirror: 8 lanes
+    x = dpp_step<IS_MAX>(x, HERO_DPP(0x140));     // row_mirror: 16 lanes (every lane holds its row's value)
+#undef HERO_DPP
+    // rows 1,3 take lane 15 of the row before; then rows 2,3 take lane 31: lane 63 has all four rows
+    xi = __builtin_amdgcn_update_dpp(IS_MAX ? __builtin_bit_cast(int, -INFINITY) : 0, __builtin_bit_cast(int, x), 0x142, 0xA, 0xF, false);
+    x = dpp_step<IS_MAX>(x, __builtin_bit_cast(float, xi));
+    xi = __builtin_amdgcn_update_dpp(IS_MAX ? __builtin_bit_cast(int, -INFINITY) : 0, __builtin_bit_cast(int, x), 0x143, 0xC, 0xF, false);
+    x = dpp_step<IS_MAX>(x, __builtin_bit_cast(float, xi));
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 63));
+}
+
+template <int DT, int EPL>
+__device__ __forceinline__ void store_hp(const float (&v)[EPL], uint16_t* dst) {
+#pragma unroll
+    for (int e8 = 0; e8 < EPL / 8; ++e8) {
+        v4i o;
+#pragma unroll
+        for (int p = 0; p < 4; ++p)
+            o[p] = (int)(f32_to_hp<DT>(v[8 * e8 + 2 * p]) | (f32_to_hp<DT>(v[8 * e8 + 2 * p + 1]) << 16));
+        *reinterpret_cast<v4i*>(dst + 8 * e8) = o;
+    }
+}
+
+// XDT: HERO_I8 / HERO_BF16 / HERO_F16.  RDT: -1 (no second addend) / HERO_I8 / HERO_BF16 / HERO_F16.
+template <int XDT, int RDT, int NCH>
 __global__ __launch_bounds__(256) void ln_quant_kernel(LnArgs a) {
+    constexpr bool X_I8 = XDT == HERO_I8;
     constexpr int EPL = X_I8 ? 16 : 8;
     constexpr int CH = EPL * HERO_WAVE;
-    const int lane = threadIdx.x & 63;
-    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (row >= a.M) return;                          // whole wave leaves together
-    const int D = a.D;
-    float v[NCH][EPL];
+    extern __shared__ __attribute__((aligned(16))) float sp[];   // [3][Dp]: gamma, beta, r_col_scale
+    const int D = a.D, Dp = NCH * CH;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const bool has_ln = a.gamma != nullptr;
+    constexpr bool r_i8 = RDT == HERO_I8, r_hp = RDT == HERO_BF16 || RDT == HERO_F16;
+    const int64_t nwaves = (int64_t)gridDim.x * 4;
+    int64_t row = (int64_t)blockIdx.x * 4 + (tid >> 6);      // grid <= ceil(M / 4): only the last block can have idle waves
 
-    // ---- load the row (sum of the addends), fp32 -------------------------------------
-    const float xs = X_I8 ? a.x_row_scale[row] : 1.0f;
-#pragma unroll
-    for (int c = 0; c < NCH; ++c) {
-        const int j0 = c * CH + lane * EPL;
-        const bool act = j0 < D;
-        if (!act) {
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) v[c][e] = 0.0f;
-            continue;
-        }
-        const int64_t off = row * (int64_t)D + j0;
-        if constexpr (X_I8) {
-            v4i w = *reinterpret_cast<const v4i*>((const int8_t*)a.x + off);
-#pragma unroll
-            for (int e = 0; e < 16; ++e) v[c][e] = byte_to_f32(w[e >> 2], e & 3) * xs;
-        } else {
-            v4i w = *reinterpret_cast<const v4i*>((const uint16_t*)a.x + off);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                uint32_t h = ((uint32_t)w[e >> 1] >> (16 * (e & 1))) & 0xffffu;
-                v[c][e] = a.x_dt == HERO_BF16 ? bf16_bits_to_f32(h) : f16_bits_to_f32(h);
-            }
-        }
-        if (a.r_dt == HERO_I8) {
-            int w[4] = {0, 0, 0, 0};
-            if constexpr (EPL == 16) {
-                v4i t = *reinterpret_cast<const v4i*>((const int8_t*)a.r + off);
-                w[0] = t[0]; w[1] = t[1]; w[2] = t[2]; w[3] = t[3];
-            } else {
-                v2i t = *reinterpret_cast<const v2i*>((const int8_t*)a.r + off);
-                w[0] = t[0]; w[1] = t[1];
-            }
-#pragma unroll
-            for (int e4 = 0; e4 < EPL / 4; ++e4) {
-                v4f rc = *reinterpret_cast<const v4f*>(a.r_col_scale + j0 + 4 * e4);
-#pragma unroll
-                for (int t = 0; t < 4; ++t) v[c][4 * e4 + t] = fmaf(byte_to_f32(w[e4], t), rc[t], v[c][4 * e4 + t]);
-            }
-        } else if (a.r_dt >= 0) {
-#pragma unroll
-            for (int e8 = 0; e8 < EPL / 8; ++e8) {
-                v4i w = *reinterpret_cast<const v4i*>((const uint16_t*)a.r + off + 8 * e8);
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    uint32_t h = ((uint32_t)w[e >> 1] >> (16 * (e & 1))) & 0xffffu;
-                    v[c][8 * e8 + e] += a.r_dt == HERO_BF16 ? bf16_bits_to_f32(h) : f16_bits_to_f32(h);
-                }
-            }
-        }
-    }
-
-    // ---- LayerNorm: mean, then variance about the mean (fp32) --------------------------
-    if (a.gamma) {
-        float s = 0.0f;
-#pragma unroll
-        for (int c = 0; c < NCH; ++c)
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) s += v[c][e];
-        const float mean = wave_sum(s) / (float)D;
-        float q = 0.0f;
-#pragma unroll
-        for (int c = 0; c < NCH; ++c) {
-            const bool act = c * CH + lane * EPL < D;
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) {
-                float dlt = v[c][e] - mean;
-                v[c][e] = dlt;
-                q = act ? fmaf(dlt, dlt, q) : q;
-            }
-        }
-        const float var = wave_sum(q) / (float)D;
-        const float rstd = 1.0f / sqrtf(var + a.eps);
+    // raw data of the rows in flight: PF rows ahead of the one being processed
+    constexpr int PF = 1;
+    v4i rx[PF][NCH], rr0[PF][NCH], rr1[PF][NCH];
+    float xsr[PF];
+    auto fetch = [&](int64_t rw, int p) {
+        if (rw >= a.M) return;                                // wave-uniform
+        xsr[p] = X_I8 ? a.x_row_scale[rw] : 1.0f;
 #pragma unroll
         for (int c = 0; c < NCH; ++c) {
             const int j0 = c * CH + lane * EPL;
             if (j0 < D) {
+                const int64_t off = rw * (int64_t)D + j0;
+                rx[p][c] = X_I8 ? *reinterpret_cast<const v4i*>((const int8_t*)a.x + off)
+                                : *reinterpret_cast<const v4i*>((const uint16_t*)a.x + off);
+                if constexpr (r_i8) {
+                    if constexpr (EPL == 16) rr0[p][c] = *reinterpret_cast<const v4i*>((const int8_t*)a.r + off);
+                    else { v2i t = *reinterpret_cast<const v2i*>((const int8_t*)a.r + off); rr0[p][c][0] = t[0]; rr0[p][c][1] = t[1]; }
+                } else if constexpr (r_hp) {
+                    rr0[p][c] = *reinterpret_cast<const v4i*>((const uint16_t*)a.r + off);
+                    if constexpr (EPL == 16) rr1[p][c] = *reinterpret_cast<const v4i*>((const uint16_t*)a.r + off + 8);
+                }
+            }
+        }
+    };
 #pragma unroll
-                for (int e4 = 0; e4 < EPL / 4; ++e4) {
-                    v4f g = *reinterpret_cast<const v4f*>(a.gamma + j0 + 4 * e4);
-                    v4f b = {0.0f, 0.0f, 0.0f, 0.0f};
-                    if (a.beta) b = *reinterpret_cast<const v4f*>(a.beta + j0 + 4 * e4);
+    for (int p = 0; p < PF; ++p) fetch(row + p * nwaves, p);  // in flight while the parameters are staged
+
+    for (int j = tid; j < Dp; j += 256) {
+        const bool in = j < D;
+        sp[j] = (has_ln && in) ? a.gamma[j] : 0.0f;
+        sp[Dp + j] = (has_ln && a.beta && in) ? a.beta[j] : 0.0f;
+        sp[2 * Dp + j] = (r_i8 && in) ? a.r_col_scale[j] : 0.0f;
+    }
+    __syncthreads();
+    if (row >= a.M) return;
+    const float inv_d = 1.0f / (float)D;
+    // Without LayerNorm the codes are bit-exact by contract (pure per-token quantization): check for
+    // rounding ties.  Behind a LayerNorm the fp32 statistics already differ from the definition's
+    // by more than a reciprocal multiply does, so the check is skipped there.
+    const bool exact = !has_ln;
+
+    auto process = [&](int64_t row, auto P) {
+        constexpr int p = decltype(P)::value;
+
+        float v[NCH][EPL];
+        const float xs = xsr[p];
+        // ---- unpack the fetched row into fp32 (sum of the addends) ---------------------------
 #pragma unroll
-                    for (int t = 0; t < 4; ++t) v[c][4 * e4 + t] = fmaf(v[c][4 * e4 + t] * rstd, g[t], b[t]);
+        for (int c = 0; c < NCH; ++c) {
+            const int j0 = c * CH + lane * EPL;
+            if (j0 < D) {
+                if constexpr (X_I8) {
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) v[c][e] = byte_to_f32(rx[p][c][e >> 2], e & 3) * xs;
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        uint32_t h = ((uint32_t)rx[p][c][e >> 1] >> (16 * (e & 1))) & 0xffffu;
+                        v[c][e] = hp_to_f32<XDT>(h);
+                    }
+                }
+                if constexpr (r_i8) {
+#pragma unroll
+                    for (int e4 = 0; e4 < EPL / 4; ++e4) {
+                        v4f rc = *reinterpret_cast<const v4f*>(sp + 2 * Dp + j0 + 4 * e4);
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) v[c][4 * e4 + t] = fmaf(byte_to_f32(rr0[p][c][e4], t), rc[t], v[c][4 * e4 + t]);
+                    }
+                } else if constexpr (r_hp) {
+#pragma unroll
+                    for (int e = 0; e < EPL; ++e) {
+                        const int w = e < 8 ? rr0[p][c][(e & 7) >> 1] : rr1[p][c][(e & 7) >> 1];
+                        uint32_t h = ((uint32_t)w >> (16 * (e & 1))) & 0xffffu;
+                        v[c][e] += hp_to_f32<RDT>(h);
+                    }
                 }
             } else {
 #pragma unroll
                 for (int e = 0; e < EPL; ++e) v[c][e] = 0.0f;
             }
         }
-    }
+        // ---- the loads of the row PF strides ahead go out now, into the register set just unpacked
+        fetch(row + PF * nwaves, p);
 
-    // ---- token-wise scale and codes -------------------------------------------------------
-    float amax = 0.0f;
+        // ---- LayerNorm: mean, then variance about the mean (fp32) --------------------------
+        if (has_ln) {
+            float s = 0.0f;
 #pragma unroll
-    for (int c = 0; c < NCH; ++c)
+            for (int c = 0; c < NCH; ++c)
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) amax = fmaxf(amax, fabsf(v[c][e]));
-    amax = wave_max(amax);
-    const float sc = amax == 0.0f ? 1.0f : __fdiv_rn(amax, 127.0f);
-    if (lane == 0) a.y_scale[row] = sc;
+                for (int e = 0; e < EPL; ++e) s += v[c][e];
+            const float mean = wave_reduce<false>(s) * inv_d;
+            float q = 0.0f;
 #pragma unroll
-    for (int c = 0; c < NCH; ++c) {
-        const int j0 = c * CH + lane * EPL;
-        if (j0 >= D) continue;
-        const int64_t off = row * (int64_t)D + j0;
-        uint32_t pk[EPL / 4];
+            for (int c = 0; c < NCH; ++c) {
+                const bool act = c * CH + lane * EPL < D;
 #pragma unroll
-        for (int e4 = 0; e4 < EPL / 4; ++e4)
-            pk[e4] = pack4_i8(quant_code_div(v[c][4 * e4 + 0], sc), quant_code_div(v[c][4 * e4 + 1], sc),
-                              quant_code_div(v[c][4 * e4 + 2], sc), quant_code_div(v[c][4 * e4 + 3], sc));
-        if constexpr (EPL == 16) {
-            v4i o = {(int)pk[0], (int)pk[1], (int)pk[2], (int)pk[3]};
-            *reinterpret_cast<v4i*>(a.y_q + off) = o;
-        } else {
-            v2i o = {(int)pk[0], (int)pk[1]};
-            *reinterpret_cast<v2i*>(a.y_q + off) = o;
-        }
-        if (a.hp_dt >= 0) {
-#pragma unroll
-            for (int e8 = 0; e8 < EPL / 8; ++e8) {
-                v4i o;
-#pragma unroll
-                for (int p = 0; p < 4; ++p) {
-                    float f0 = v[c][8 * e8 + 2 * p], f1 = v[c][8 * e8 + 2 * p + 1];
-                    uint32_t h0 = a.hp_dt == HERO_BF16 ? f32_to_bf16_bits(f0) : f32_to_f16_bits(f0);
-                    uint32_t h1 = a.hp_dt == HERO_BF16 ? f32_to_bf16_bits(f1) : f32_to_f16_bits(f1);
-                    o[p] = (int)(h0 | (h1 << 16));
+                for (int e = 0; e < EPL; ++e) {
+                    float dlt = v[c][e] - mean;
+                    v[c][e] = dlt;
+                    q = act ? fmaf(dlt, dlt, q) : q;
                 }
-                *reinterpret_cast<v4i*>((uint16_t*)a.y_hp + off + 8 * e8) = o;
+            }
+            const float var = wave_reduce<false>(q) * inv_d;
+            const float rstd = 1.0f / sqrtf(var + a.eps);
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) {
+                const int j0 = c * CH + lane * EPL;     // padded columns have gamma = beta = 0 in LDS
+#pragma unroll
+                for (int e4 = 0; e4 < EPL / 4; ++e4) {
+                    v4f g = *reinterpret_cast<const v4f*>(sp + j0 + 4 * e4);
+                    v4f b = *reinterpret_cast<const v4f*>(sp + Dp + j0 + 4 * e4);
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) v[c][4 * e4 + t] = fmaf(v[c][4 * e4 + t] * rstd, g[t], b[t]);
+                }
             }
         }
+
+        // ---- token-wise scale and codes -------------------------------------------------------
+        float amax = 0.0f;
+#pragma unroll
+        for (int c = 0; c < NCH; ++c)
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) amax = fmaxf(amax, fabsf(v[c][e]));
+        amax = wave_reduce<true>(amax);
+        const float sc = amax == 0.0f ? 1.0f : __fdiv_rn(amax, 127.0f);
+        const float inv_sc = __fdiv_rn(1.0f, sc);
+        if (lane == 0) a.y_scale[row] = sc;
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            const int j0 = c * CH + lane * EPL;
+            if (j0 >= D) continue;
+            const int64_t off = row * (int64_t)D + j0;
+            // |v * inv_sc| <= 127 (absmax row scale), so no clamp is needed before the rounding add
+            float t[EPL];
+            bool near_tie = false;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) {
+                t[e] = v[c][e] * inv_sc;
+                if (exact) near_tie |= fabsf(t[e] - __builtin_rintf(t[e])) > 0.49996f;
+            }
+            if (exact && near_tie) {                     // rare: redo this lane's chunk with the true division
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) t[e] = __fdiv_rn(v[c][e], sc);
+            }
+            uint32_t pk[EPL / 4];
+#pragma unroll
+            for (int e4 = 0; e4 < EPL / 4; ++e4)
+                pk[e4] = pack_low_bytes(rne_low_byte(t[4 * e4]), rne_low_byte(t[4 * e4 + 1]),
+                                        rne_low_byte(t[4 * e4 + 2]), rne_low_byte(t[4 * e4 + 3]));
+            if constexpr (EPL == 16) {
+                v4i o = {(int)pk[0], (int)pk[1], (int)pk[2], (int)pk[3]};
+                *reinterpret_cast<v4i*>(a.y_q + off) = o;
+            } else {
+                v2i o = {(int)pk[0], (int)pk[1]};
+                *reinterpret_cast<v2i*>(a.y_q + off) = o;
+            }
+            if (a.hp_dt == HERO_BF16) store_hp<HERO_BF16, EPL>(v[c], (uint16_t*)a.y_hp + off);
+            else if (a.hp_dt == HERO_F16) store_hp<HERO_F16, EPL>(v[c], (uint16_t*)a.y_hp + off);
+        }
+    };
+    // register sets rotate with the row: unrolled by PF so the set index is a compile-time constant
+    for (; row < a.M; row += PF * nwaves) {
+        process(row, std::integral_constant<int, 0>{});
+        if constexpr (PF > 1) { if (row + nwaves < a.M) process(row + nwaves, std::integral_constant<int, PF - 1>{}); }
     }
 }
 
-template <bool X_I8>
-hero_status launch(const LnArgs& a, hipStream_t st) {
-    constexpr int CH = (X_I8 ? 16 : 8) * HERO_WAVE;
-    const int nch = (a.D + CH - 1) / CH;
-    dim3 grid((unsigned)((a.M + 3) / 4)), block(256);
-    if (nch <= 1) hipLaunchKernelGGL((ln_quant_kernel<X_I8, 1>), grid, block, 0, st, a);
-    else if (nch <= 2) hipLaunchKernelGGL((ln_quant_kernel<X_I8, 2>), grid, block, 0, st, a);
-    else if (nch <= 4) hipLaunchKernelGGL((ln_quant_kernel<X_I8, 4>), grid, block, 0, st, a);
-    else if (nch <= 8) hipLaunchKernelGGL((ln_quant_kernel<X_I8, 8>), grid, block, 0, st, a);
-    else return HERO_ERR_UNSUPPORTED;
+template <int XDT, int RDT, int NCH>
+hero_status launch_nch(const LnArgs& a, hipStream_t st) {
+    constexpr int CH = (XDT == HERO_I8 ? 16 : 8) * HERO_WAVE;
+    const size_t lds = (size_t)3 * NCH * CH * sizeof(float);
+    if (lds > 65536 &&                                    // more than 64 KB of dynamic LDS needs the opt-in
+        hipFuncSetAttribute((const void*)ln_quant_kernel<XDT, RDT, NCH>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+        return HERO_ERR_LAUNCH;
+    // persistent workgroups: a few per CU, never more than the rows need
+    int64_t blocks = (a.M + 3) / 4;
+    const int64_t cap = 256 * (NCH <= 2 ? 8 : 4);
+    if (blocks > cap) blocks = cap;
+    hipLaunchKernelGGL((ln_quant_kernel<XDT, RDT, NCH>), dim3((unsigned)blocks), dim3(256), lds, st, a);
     return hero_launch_status();
+}
+
+template <int XDT, int RDT>
+hero_status launch_r(const LnArgs& a, hipStream_t st) {
+    constexpr int CH = (XDT == HERO_I8 ? 16 : 8) * HERO_WAVE;
+    const int nch = (a.D + CH - 1) / CH;
+    if (nch <= 1) return launch_nch<XDT, RDT, 1>(a, st);
+    if (nch <= 2) return launch_nch<XDT, RDT, 2>(a, st);
+    if (nch <= 4) return launch_nch<XDT, RDT, 4>(a, st);
+    if (nch <= 8) return launch_nch<XDT, RDT, 8>(a, st);
+    return HERO_ERR_UNSUPPORTED;
+}
+
+template <int XDT>
+hero_status launch(const LnArgs& a, hipStream_t st) {
+    switch (a.r_dt) {
+    case -1: return launch_r<XDT, -1>(a, st);
+    case HERO_I8: return launch_r<XDT, HERO_I8>(a, st);
+    case HERO_BF16: return launch_r<XDT, HERO_BF16>(a, st);
+    case HERO_F16: return launch_r<XDT, HERO_F16>(a, st);
+    }
+    return HERO_ERR_UNSUPPORTED;
 }
 
 }  // namespace
@@ -202,15 +305,14 @@ extern "C" hero_status hero_ln_quant(const void* x, hero_dtype x_dt, const float
     if (!gamma && beta) return HERO_ERR_NULL;
     if (y_hp && y_hp_dt != HERO_BF16 && y_hp_dt != HERO_F16) return HERO_ERR_UNSUPPORTED;
     if (D > (x_i8 ? 8192 : 4096)) return HERO_ERR_UNSUPPORTED;      // row must fit the register file
-    if (!hero_aligned16(x) || !hero_aligned16(r) || !hero_aligned16(y_q) || !hero_aligned16(y_hp) ||
-        !hero_aligned16(gamma) || !hero_aligned16(beta) || !hero_aligned16(r_col_scale))
+    if (!hero_aligned16(x) || !hero_aligned16(r) || !hero_aligned16(y_q) || !hero_aligned16(y_hp))
         return HERO_ERR_ALIGN;
-    if ((M + 3) / 4 > 0x7fffffffLL) return HERO_ERR_SHAPE;
     LnArgs a;
     a.x = x; a.x_row_scale = x_row_scale; a.r = r; a.r_col_scale = r_col_scale;
     a.gamma = gamma; a.beta = beta; a.eps = eps; a.M = M; a.D = (int)D;
     a.y_q = y_q; a.y_scale = y_scale; a.y_hp = y_hp;
     a.x_dt = (int)x_dt; a.r_dt = r ? (int)r_dt : -1; a.hp_dt = y_hp ? (int)y_hp_dt : -1;
     hipStream_t st = (hipStream_t)stream;
-    return x_i8 ? launch<true>(a, st) : launch<false>(a, st);
+    if (x_i8) return launch<HERO_I8>(a, st);
+    return x_dt == HERO_BF16 ? launch<HERO_BF16>(a, st) : launch<HERO_F16>(a, st);
 }
