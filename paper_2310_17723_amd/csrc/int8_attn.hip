@@ -16,7 +16,11 @@
 // the same key order, which the V staging does.
 // The matrix cores multiply signed bytes; codes are 0..255, so P-128 is fed and
 // 128 * colsum(V) (one extra MFMA against a vector of ones) is added back, exact in int32.
+// The kernel is bound by the plain-ALU work per score (exp2, conversion, rounding), not by
+// the matrix cores, so both passes are written to spend as few vector instructions per score
+// as possible (see the comment in front of pass 1).
 #include "hero_common.h"
+#include <type_traits>
 
 namespace {
 
@@ -38,8 +42,8 @@ __global__ __launch_bounds__(256) void int8_attn_kernel(AttnArgs a) {
     constexpr int KLD = DH + 16;        // sK row stride (bytes)
     constexpr int VLD = BKV + 16;       // sVt row stride (bytes)
     constexpr int DS = DH / 32;         // 32-wide steps over the head dimension
-    __shared__ __attribute__((aligned(16))) int8_t sK[BKV * KLD];
-    __shared__ __attribute__((aligned(16))) int8_t sVt[DH * VLD];
+    __shared__ __attribute__((aligned(16))) int8_t sK[2][BKV * KLD];
+    __shared__ __attribute__((aligned(16))) int8_t sVt[2][DH * VLD];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int hh = lane >> 5, ql = lane & 31;
@@ -65,76 +69,108 @@ __global__ __launch_bounds__(256) void int8_attn_kernel(AttnArgs a) {
     const int8_t* kbase = a.k + (int64_t)b * a.ks[0] + (int64_t)h * a.ks[2];
     const int8_t* vbase = a.v + (int64_t)b * a.vs[0] + (int64_t)h * a.vs[2];
 
-    auto stage_k = [&](int tile) {
-        constexpr int UNITS = BKV * (DH / 16) / 256;
+    // K / V tiles: global -> registers (next tile, in flight during the current tile's math) -> LDS
+    // (double buffered, one barrier per tile).  V is written transposed, keys permuted so that the
+    // PV operand fragment is one 128-bit read: key row 32kb + 8g + 4h + t -> position 32kb + 16h + 4g + t.
+    constexpr int UNITS = BKV * (DH / 16) / 256;
+    v4i rk[UNITS], rv[UNITS];
+    auto load_k = [&](int tile) {
 #pragma unroll
         for (int u = 0; u < UNITS; ++u) {
             int idx = tid + u * 256, row = idx / (DH / 16), ch = idx % (DH / 16);
             int key = min(tile * BKV + row, a.Skv - 1);
-            v4i w = *reinterpret_cast<const v4i*>(kbase + (int64_t)key * a.ks[1] + ch * 16);
-            *reinterpret_cast<v4i*>(&sK[row * KLD + ch * 16]) = w;
+            rk[u] = *reinterpret_cast<const v4i*>(kbase + (int64_t)key * a.ks[1] + ch * 16);
         }
     };
-    auto stage_v = [&](int tile) {
-        constexpr int UNITS = BKV * (DH / 16) / 256;
+    auto load_v = [&](int tile) {
 #pragma unroll
         for (int u = 0; u < UNITS; ++u) {
             int idx = tid + u * 256, row = idx / (DH / 16), ch = idx % (DH / 16);
             int key = min(tile * BKV + row, a.Skv - 1);
-            v4i w = *reinterpret_cast<const v4i*>(vbase + (int64_t)key * a.vs[1] + ch * 16);
-            // key row = 32*kb + 8g + 4hh' + t  ->  position 32*kb + 16hh' + 4g + t
+            rv[u] = *reinterpret_cast<const v4i*>(vbase + (int64_t)key * a.vs[1] + ch * 16);
+        }
+    };
+    auto store_k = [&](int buf) {
+#pragma unroll
+        for (int u = 0; u < UNITS; ++u) {
+            int idx = tid + u * 256, row = idx / (DH / 16), ch = idx % (DH / 16);
+            *reinterpret_cast<v4i*>(&sK[buf][row * KLD + ch * 16]) = rk[u];
+        }
+    };
+    auto store_v = [&](int buf) {
+#pragma unroll
+        for (int u = 0; u < UNITS; ++u) {
+            int idx = tid + u * 256, row = idx / (DH / 16), ch = idx % (DH / 16);
             int r32 = row & 31;
             int pos = (row & 32) + ((r32 >> 2) & 1) * 16 + (r32 >> 3) * 4 + (r32 & 3);
 #pragma unroll
             for (int e = 0; e < 16; ++e)
-                sVt[(ch * 16 + e) * VLD + pos] = (int8_t)(w[e >> 2] >> (8 * (e & 3)));
+                sVt[buf][(ch * 16 + e) * VLD + pos] = (int8_t)(rv[u][e >> 2] >> (8 * (e & 3)));
         }
     };
     // S^T for the 32-key step s of the staged tile
-    auto scores = [&](int s) {
+    auto scores = [&](int buf, int s) {
         v16i acc;
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[r] = 0;
 #pragma unroll
         for (int d = 0; d < DS; ++d) {
-            v4i kf = *reinterpret_cast<const v4i*>(&sK[(s * 32 + ql) * KLD + d * 32 + hh * 16]);
+            v4i kf = *reinterpret_cast<const v4i*>(&sK[buf][(s * 32 + ql) * KLD + d * 32 + hh * 16]);
             acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(kf, qf[d], acc, 0, 0, 0);
         }
         return acc;
     };
 
+    // Both passes work in the log2 domain on the raw integer scores: p = 2^(acc * c2 - m2) with
+    // c2 = d~ * log2(e).  The row maximum is taken on the integers (the scale is positive), masked
+    // keys are replaced by a very negative integer (only in tiles that contain one), and in pass 2
+    // the normaliser and 1/S_p are folded into the exponent, so a code costs one int->float
+    // conversion, one fma, one exp2 and one saturating round-to-u8.
+    const float c2 = a.qk_scale * 1.44269504088896340736f;
+    constexpr int MASKED = -0x40000000;
+    // first tile in which some key is hidden from some query of this wave (wave-uniform)
+    int nvis_min = nvis;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) nvis_min = min(nvis_min, __shfl_xor(nvis_min, o));
+
     // ---- pass 1: row max and row sum ------------------------------------------------------------
-    float m = -INFINITY, l = 0.0f;
+    float m2 = -INFINITY, l = 0.0f;           // running max (log2 domain) and sum of 2^(a2 - m2), this lane's keys
+    if (ntiles > 0) { load_k(0); store_k(0); }
+    __syncthreads();
     for (int tile = 0; tile < ntiles; ++tile) {
-        __syncthreads();
-        stage_k(tile);
-        __syncthreads();
+        const int buf = tile & 1;
+        if (tile + 1 < ntiles) load_k(tile + 1);
+        const bool edge = (tile + 1) * BKV > nvis_min;
+        auto pass1_tile = [&](auto EDGE) {
 #pragma unroll
-        for (int s = 0; s < BKV / 32; ++s) {
-            v16i acc = scores(s);
-            float av[16];
-            float tmax = -INFINITY;
+            for (int s = 0; s < BKV / 32; ++s) {
+                v16i acc = scores(buf, s);
+                if constexpr (decltype(EDGE)::value) {
+                    const int lim = nvis - (tile * BKV + s * 32 + hh * 4);      // key visible iff 8g + t < lim
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                int key = tile * BKV + s * 32 + (r >> 2) * 8 + hh * 4 + (r & 3);
-                float x = (float)acc[r] * a.qk_scale;
-                av[r] = key < nvis ? x : -INFINITY;
-                tmax = fmaxf(tmax, av[r]);
+                    for (int r = 0; r < 16; ++r) acc[r] = ((r >> 2) * 8 + (r & 3)) < lim ? acc[r] : MASKED;
+                }
+                int imax = acc[0];
+#pragma unroll
+                for (int r = 1; r < 16; ++r) imax = max(imax, acc[r]);
+                imax = max(imax, __shfl_xor(imax, 32));
+                if (imax > MASKED) {                         // same decision in both lanes of a query
+                    const float mn = fmaxf(m2, (float)imax * c2);
+                    float sum = 0.0f;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) sum += __builtin_amdgcn_exp2f(fmaf((float)acc[r], c2, -mn));
+                    l = fmaf(l, __builtin_amdgcn_exp2f(m2 - mn), sum);
+                    m2 = mn;
+                }
             }
-            tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-            if (tmax > -INFINITY) {                      // same decision in both lanes of a query
-                float mn = fmaxf(m, tmax);
-                float sum = 0.0f;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) sum += __expf(av[r] - mn);     // exp(-inf) = 0
-                l = l * __expf(m - mn) + sum;
-                m = mn;
-            }
-        }
+        };
+        if (edge) pass1_tile(std::true_type{}); else pass1_tile(std::false_type{});
+        if (tile + 1 < ntiles) store_k(buf ^ 1);
+        __syncthreads();
     }
     l += __shfl_xor(l, 32);
-    const float inv_l = l > 0.0f ? 1.0f / l : 0.0f;
-    const float inv_ps = 1.0f / a.p_scale;
+    // exponent offset of pass 2: 2^(acc*c2 - m2) / l / S_p = 2^(acc*c2 + off); a row that saw no key gets codes 0
+    const float off = l > 0.0f ? -m2 - __log2f(l * a.p_scale) : -INFINITY;
 
     // ---- pass 2: codes and PV --------------------------------------------------------------------
     v16i o[DS], cs[DS];
@@ -143,37 +179,40 @@ __global__ __launch_bounds__(256) void int8_attn_kernel(AttnArgs a) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) { o[c][r] = 0; cs[c][r] = 0; }
     const v4i ones = {0x01010101, 0x01010101, 0x01010101, 0x01010101};
+    if (ntiles > 0) { load_k(0); load_v(0); store_k(0); store_v(0); }
+    __syncthreads();
     for (int tile = 0; tile < ntiles; ++tile) {
-        __syncthreads();
-        stage_k(tile);
-        stage_v(tile);
-        __syncthreads();
+        const int buf = tile & 1;
+        if (tile + 1 < ntiles) { load_k(tile + 1); load_v(tile + 1); }
+        const bool edge = (tile + 1) * BKV > nvis_min;
+        auto pass2_tile = [&](auto EDGE) {
 #pragma unroll
-        for (int s = 0; s < BKV / 32; ++s) {
-            v16i acc = scores(s);
-            v4i pf;
+            for (int s = 0; s < BKV / 32; ++s) {
+                v16i acc = scores(buf, s);
+                const int lim = nvis - (tile * BKV + s * 32 + hh * 4);          // key visible iff 8g + t < lim
+                v4i pf;
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                int code[4];
+                for (int g = 0; g < 4; ++g) {
+                    uint32_t w = 0;
 #pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    int r = 4 * g + t;
-                    int key = tile * BKV + s * 32 + g * 8 + hh * 4 + t;
-                    float x = (float)acc[r] * a.qk_scale;
-                    float e = key < nvis ? __expf(x - m) : 0.0f;
-                    float c = __builtin_rintf(e * inv_l * inv_ps);
-                    c = fminf(fmaxf(c, 0.0f), 255.0f);
-                    code[t] = (int)c - 128;
+                    for (int t = 0; t < 4; ++t) {
+                        float e = __builtin_amdgcn_exp2f(fmaf((float)acc[4 * g + t], c2, off));
+                        if constexpr (decltype(EDGE)::value) e = (g * 8 + t) < lim ? e : 0.0f;
+                        w = __builtin_amdgcn_cvt_pk_u8_f32(e, t, w);     // sat_[0,255](rne(.)) into byte t
+                    }
+                    pf[g] = (int)(w ^ 0x80808080u);                         // codes - 128 as signed bytes
                 }
-                pf[g] = (int)pack4_i8(code[0], code[1], code[2], code[3]);
-            }
 #pragma unroll
-            for (int c = 0; c < DS; ++c) {
-                v4i vf = *reinterpret_cast<const v4i*>(&sVt[(c * 32 + ql) * VLD + s * 32 + hh * 16]);
-                o[c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(vf, pf, o[c], 0, 0, 0);
-                cs[c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(vf, ones, cs[c], 0, 0, 0);
+                for (int c = 0; c < DS; ++c) {
+                    v4i vf = *reinterpret_cast<const v4i*>(&sVt[buf][(c * 32 + ql) * VLD + s * 32 + hh * 16]);
+                    o[c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(vf, pf, o[c], 0, 0, 0);
+                    cs[c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(vf, ones, cs[c], 0, 0, 0);
+                }
             }
-        }
+        };
+        if (edge) pass2_tile(std::true_type{}); else pass2_tile(std::false_type{});
+        if (tile + 1 < ntiles) { store_k(buf ^ 1); store_v(buf ^ 1); }
+        __syncthreads();
     }
 
     // ---- output: lane holds query ql, channels 32c + 8g + 4hh + t -----------------------------------
@@ -192,8 +231,7 @@ __global__ __launch_bounds__(256) void int8_attn_kernel(AttnArgs a) {
                 y[t] = (float)val * sc;
             }
             if (ODT == HERO_I8) {
-                *reinterpret_cast<uint32_t*>((int8_t*)a.out + orow + e0) =
-                    pack4_i8(round_sat_i8(y[0]), round_sat_i8(y[1]), round_sat_i8(y[2]), round_sat_i8(y[3]));
+                *reinterpret_cast<uint32_t*>((int8_t*)a.out + orow + e0) = quant4_sat(y[0], y[1], y[2], y[3]);
             } else {
                 uint32_t h0 = f32_to_hp<ODT>(y[0]), h1 = f32_to_hp<ODT>(y[1]), h2 = f32_to_hp<ODT>(y[2]), h3 = f32_to_hp<ODT>(y[3]);
                 v2i w = {(int)(h0 | (h1 << 16)), (int)(h2 | (h3 << 16))};
