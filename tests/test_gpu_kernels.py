@@ -274,3 +274,30 @@ def test_gemm_full_size_sampled_rows(hero, M, N, K):
     # property that holds at any size: column sums of the raw accumulators
     colsum = A.astype(np.int64).sum(axis=0) @ Bt.astype(np.int64).T
     assert np.array_equal(raw.astype(np.int64).sum(axis=0), colsum)
+
+
+# ============================================================ BF16 side of a switched module
+@pytest.mark.parametrize("M,N,K", [(200, 136, 256), (130, 512, 1024), (64, 72, 96)])
+def test_bf16_gemm_matches_oracle(hero, M, N, K):
+    g = synth.rng(1000 + M)
+    A = O.f32_to_bf16(g.standard_normal((M, K)).astype(np.float32))
+    Wt = O.f32_to_bf16((g.standard_normal((N, K)) * 0.05).astype(np.float32))
+    bias = (0.1 * g.standard_normal(N)).astype(np.float32)
+    res = O.f32_to_bf16(g.standard_normal((M, N)).astype(np.float32))
+    for gelu, r in ((False, None), (True, None), (False, res), (True, res)):
+        ref = O.bf16_gemm(A, Wt, bias=bias, residual=r, gelu=gelu)
+        got = hero.hero_bf16_gemm(dev(A), dev(Wt), dev(bias), residual=dev(r), gelu=gelu)
+        assert rel_err(O.bf16_to_f32(to_np(got)), O.bf16_to_f32(ref)) <= 2e-2
+
+
+@pytest.mark.parametrize("mask", [O.MASK_NONE, O.MASK_PADDING, O.MASK_CAUSAL])
+@pytest.mark.parametrize("B,S,H,Dh", [(2, 150, 2, 64), (1, 200, 2, 128)])
+def test_bf16_attn_matches_oracle(hero, B, S, H, Dh, mask):
+    g = synth.rng(1100 + S)
+    qkv = O.f32_to_bf16(g.standard_normal((B * S, 3 * H * Dh)).astype(np.float32))
+    qv, kv, vv = (OL._heads(qkv, B, S, H, Dh, i) for i in range(3))
+    kv_len = np.int32([S - 7, 3][:B]) if mask == O.MASK_PADDING else None
+    ref = O.bf16_attn(qv, kv, vv, scale=1.0 / np.sqrt(Dh), mask=mask, kv_len=kv_len)
+    dq = dev(qkv).view(B, S, 3, H, Dh)
+    got = hero.hero_bf16_attn(dq[:, :, 0], dq[:, :, 1], dq[:, :, 2], 1.0 / np.sqrt(Dh), mask=mask, kv_len=dev(kv_len))
+    assert rel_err(O.bf16_to_f32(to_np(got)), O.bf16_to_f32(ref)) <= 2e-2

@@ -96,6 +96,43 @@ def test_pre_ln_layer_prefill_then_decode(hero, Dh, H):
         assert rel_err(O.bf16_to_f32(to_np(h1)), O.bf16_to_f32(ref1)) <= 2e-2
 
 
+@pytest.mark.parametrize("arch", [synth.POST_LN, synth.PRE_LN])
+@pytest.mark.parametrize("mode", ["M1", "M2"])
+def test_mixed_precision_modes(hero, arch, mode):
+    """Table 1: M2 keeps FC2 in BF16; M1 also the attention core and its output linear."""
+    mm = {"M1": OL.MODE_M1, "M2": OL.MODE_M2}[mode]
+    shape = _shape(arch, synth.MASK_CAUSAL if arch == synth.PRE_LN else synth.MASK_PADDING, S=130)
+    B, S, T = shape.B, shape.S, shape.B * shape.S
+    w, emb = _prepare(shape, 51, mm)
+    desc = _desc(hero, shape, mm)
+    W, keep = upload_weights(hero, w)
+    ws = torch.empty(hero.hero_layer_workspace_bytes(desc, B, S), dtype=torch.uint8, device="cuda")
+    h0 = synth.activations(51, shape, T)
+    if arch == synth.POST_LN:
+        kv_len = synth.kv_lengths(51, shape)
+        xq, xs, _ = O.ln_quant(h0, O.F32, None, None, 0, None, emb["g"], emb["b"], shape.eps)
+        oq, os_ = OL.layer_fwd(w, shape, B, S, x_q=xq, x_s=xs, kv_len=kv_len)
+        out_q = torch.empty((T, shape.d), dtype=torch.int8, device="cuda")
+        out_s = torch.empty((T,), dtype=torch.float32, device="cuda")
+        hero.hero_layer_fwd(desc, W, B, S, ws, x_q=dev(xq), x_scale=dev(xs), out_q=out_q, out_scale=out_s, kv_len=dev(kv_len))
+        # TWQ INT8 output: one code step is amax/127 of the row, far more than 2e-2 of a small
+        # value, so the codes themselves are compared (bf16 GEMMs accumulate in another order
+        # than the fp64 oracle, which moves a few values across a rounding boundary)
+        valid = (np.arange(S)[None, :] < kv_len[:, None]).ravel()
+        gq, gs = to_np(out_q)[valid], to_np(out_s)[valid]
+        assert np.allclose(gs, os_[valid], rtol=2e-2)
+        assert np.abs(gq.astype(int) - oq[valid].astype(int)).max() <= 2
+        assert np.mean(gq == oq[valid]) > 0.97
+        return
+    else:
+        hb = O.f32_to_bf16(h0)
+        ref = O.bf16_to_f32(OL.layer_fwd(w, shape, B, S, h=hb))
+        h = dev(hb)
+        hero.hero_layer_fwd(desc, W, B, S, ws, h=h)
+        got = O.bf16_to_f32(to_np(h))
+    assert rel_err(got, ref) <= 2e-2
+
+
 def test_layer_rejects_bad_requests(hero):
     shape = _shape(synth.POST_LN, synth.MASK_NONE)
     desc = _desc(hero, shape, HB.MODE_M3)
