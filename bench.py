@@ -25,6 +25,11 @@ import numpy as np
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
+# HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# (two runs, scaled by the same counters on a plain copy of known size); the summaries are in
+# profiles/.  Keyed by (M, N, K) of the FC1 GeMM^quant; anything else reports null.
+MEASURED_TRAFFIC = {}
+
 PEAK_INT8_TOPS = 5000.0      # MI355X dense INT8 MFMA, TOP/s
 PEAK_HBM_GBS = 8000.0        # MI355X HBM3E, GB/s
 
@@ -154,7 +159,9 @@ def fc1_roofline(hero, shape, seed, iters=20):
     tops = ops / (ms * 1e-3) / 1e12
     return {"bound": "mfma", "kernel": "int8_gemm_kernel<GELU_REQUANT> (FC1)", "shape_mnk": [M, N, K],
             "achieved": round(tops, 2), "peak": PEAK_INT8_TOPS, "unit": "TOP/s", "frac": round(tops / PEAK_INT8_TOPS, 4),
-            "avg_launch_us": round(ms * 1e3, 2), "ops_per_launch": ops, "traffic": None}
+            "avg_launch_us": round(ms * 1e3, 2), "ops_per_launch": ops,
+            "algorithmic_bytes": M * K + N * K + M * N + 4 * (M + 3 * N),
+            "traffic": MEASURED_TRAFFIC.get((M, N, K))}
 
 
 def gemm_sweep(hero, seed, iters=10):
@@ -202,12 +209,13 @@ def ln_bandwidth(hero, T, D, iters=40, nbuf=8):
 
 
 def cpu_baseline(shape, seed, mode_name):
-    """The oracle, as it stands, on a bounded slice: one sequence through one layer."""
+    """The oracle, as it stands, on a bounded slice of the workload (about 10-30 s of CPU work)."""
     import oracle as O
     from oracle import layer as OL
     from paper_2310_17723_amd import synth
     decode = shape.cache_len > 0
-    B, S = (1, min(shape.S, 512)) if not decode else (2, 1)
+    # slice sizes: BERT-large 32 x 512 (the full batch), BERT-base 1 x 128, GPT prefill 1 x 512, decode 2 x 1
+    B, S = ((min(shape.B, 32), min(shape.S, 512)) if shape.d <= 1024 else (1, 512)) if not decode else (2, 1)
     sh = synth.small(shape, B=B, S=S)
     p = synth.layer_params(seed, sh, 0)
     emb = synth.embedding_ln_params(seed, sh)
@@ -224,10 +232,10 @@ def cpu_baseline(shape, seed, mode_name):
         xq, xs, _ = O.ln_quant(h0, O.F32, None, None, 0, None, emb["g"], emb["b"], sh.eps)
         kv = np.full(B, S, np.int32) if sh.mask == synth.MASK_PADDING else None
         OL.layer_fwd(w, sh, B, S, x_q=xq, x_s=xs, kv_len=kv)
-        sample = f"1 sequence x {S} tokens through 1 layer of {shape.name}"
+        sample = f"{B} sequences x {S} tokens through 1 layer of {shape.name}"
     elif not decode:
         OL.layer_fwd(w, sh, B, S, h=O.f32_to_bf16(h0))
-        sample = f"1 sequence x {S} tokens through 1 layer of {shape.name}"
+        sample = f"{B} sequence x {S} tokens through 1 layer of {shape.name}"
     else:
         Smax = shape.cache_len + 1
         cache = {"k": synth.int8_codes(seed, (B, sh.H, Smax, sh.Dh), 0), "v": synth.int8_codes(seed, (B, sh.H, Smax, sh.Dh), 1)}
@@ -304,8 +312,8 @@ def main():
     rec["roofline"] = fc1_roofline(hero, shape, args.seed)
     if not args.no_extras:
         log("[bench] LN^quant bandwidth")
-        Tln = max(st.T, 16384)
-        rec["ln_quant"] = ln_bandwidth(hero, Tln, shape.d)
+        rec["ln_quant"] = ln_bandwidth(hero, max(st.T, 16384), shape.d)
+        rec["ln_quant_large"] = ln_bandwidth(hero, 65536, shape.d, nbuf=4)
         log("[bench] GEMM sweep")
         rec["gemm_sweep"] = gemm_sweep(hero, args.seed)
         del st

@@ -240,6 +240,94 @@ __global__ __launch_bounds__(256) void int8_attn_kernel(AttnArgs a) {
         }
 }
 
+// ------------------------------------------------------------------------------------------
+// Decode (one query per sequence): HBM-bound on the K and V cache, so no matrix cores; K and
+// V are each read exactly once.  One block per (batch, head); 8 lanes share a key (16 bytes of
+// the row each, so a wave-level load covers 8 whole rows = 1 KB of consecutive cache).
+//   phase 1: integer scores q.k (v_dot4) for every key -> LDS
+//   phase 2: row max / sum in the log2 domain (block reduction), codes 0..255 -> LDS
+//   phase 3: acc[e] = sum_k P[k] * v[k][e] in int32, reduced over the key groups through LDS
+// ------------------------------------------------------------------------------------------
+constexpr int DEC_MAX_KEYS = 16384;
+
+template <int DH, int ODT>
+__global__ __launch_bounds__(256) void int8_attn_decode_kernel(AttnArgs a) {
+    constexpr int LPK = DH / 16;                 // lanes per key
+    constexpr int KPI = 256 / LPK;               // keys per block iteration
+    extern __shared__ __attribute__((aligned(16))) int smem_dec[];
+    int* sc = smem_dec;                                            // [len] scores, later codes
+    __shared__ float red[8];
+    __shared__ int racc[KPI][DH + 4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int b = blockIdx.y, h = blockIdx.x;
+    const int len = a.kv_len ? min(max(a.kv_len[b], 0), a.Skv) : a.Skv;     // one query: it sees every valid key
+    const int sub = tid % LPK, kg = tid / LPK;
+    const int8_t* kbase = a.k + (int64_t)b * a.ks[0] + (int64_t)h * a.ks[2] + sub * 16;
+    const int8_t* vbase = a.v + (int64_t)b * a.vs[0] + (int64_t)h * a.vs[2] + sub * 16;
+    const v4i qv = *reinterpret_cast<const v4i*>(a.q + (int64_t)b * a.qs[0] + (int64_t)h * a.qs[2] + sub * 16);
+
+    // ---- phase 1: scores ---------------------------------------------------------------------
+    int lmax = -0x40000000;
+    for (int k0 = 0; k0 < len; k0 += KPI) {
+        const int key = k0 + kg;
+        v4i kv = {0, 0, 0, 0};
+        if (key < len) kv = *reinterpret_cast<const v4i*>(kbase + (int64_t)key * a.ks[1]);
+        int d = 0;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) d = __builtin_amdgcn_sdot4(kv[w], qv[w], d, false);
+#pragma unroll
+        for (int o = 1; o < LPK; o <<= 1) d += __shfl_xor(d, o);
+        if (sub == 0 && key < len) { sc[key] = d; lmax = max(lmax, d); }
+    }
+    // block max
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) lmax = max(lmax, __shfl_xor(lmax, o));
+    if (lane == 0) red[wave] = __int_as_float(lmax);
+    __syncthreads();
+    const int imax = max(max(__float_as_int(red[0]), __float_as_int(red[1])), max(__float_as_int(red[2]), __float_as_int(red[3])));
+    const float c2 = a.qk_scale * 1.44269504088896340736f;
+    const float m2 = (float)imax * c2;
+    // ---- phase 2: sum, then codes --------------------------------------------------------------
+    float lsum = 0.0f;
+    for (int k = tid; k < len; k += 256) lsum += __builtin_amdgcn_exp2f(fmaf((float)sc[k], c2, -m2));
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) lsum += __shfl_xor(lsum, o);
+    if (lane == 0) red[4 + wave] = lsum;
+    __syncthreads();
+    const float l = red[4] + red[5] + red[6] + red[7];
+    const float off = l > 0.0f ? -m2 - __log2f(l * a.p_scale) : -INFINITY;
+    for (int k = tid; k < len; k += 256) {
+        const float e = __builtin_amdgcn_exp2f(fmaf((float)sc[k], c2, off));
+        sc[k] = (int)__builtin_amdgcn_cvt_pk_u8_f32(e, 0, 0u);
+    }
+    __syncthreads();
+    // ---- phase 3: PV ------------------------------------------------------------------------------
+    int acc[16];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[e] = 0;
+    for (int k0 = 0; k0 < len; k0 += KPI) {
+        const int key = k0 + kg;
+        if (key < len) {
+            const v4i vv = *reinterpret_cast<const v4i*>(vbase + (int64_t)key * a.vs[1]);
+            const int p = sc[key];
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[e] += p * (int)(int8_t)(vv[e >> 2] >> (8 * (e & 3)));
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < 16; ++e) racc[kg][sub * 16 + e] = acc[e];
+    __syncthreads();
+    if (tid < DH) {
+        int tot = 0;
+        for (int g = 0; g < KPI; ++g) tot += racc[g][tid];
+        const float scl = a.scale_is_scalar ? a.out_col_scale[0] : a.out_col_scale[h * DH + tid];
+        const float y = (float)tot * scl;
+        const int64_t oidx = (int64_t)b * a.ldo + (int64_t)h * DH + tid;
+        if (ODT == HERO_I8) ((int8_t*)a.out)[oidx] = (int8_t)(rne_low_byte(__builtin_amdgcn_fmed3f(y, -127.0f, 127.0f)) & 0xff);
+        else ((uint16_t*)a.out)[oidx] = (uint16_t)f32_to_hp<ODT>(y);
+    }
+}
+
 __global__ void zero_rows_kernel(int8_t* out, int64_t bytes) {
     int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 16;
     if (i < bytes) *reinterpret_cast<v4i*>(out + i) = v4i{0, 0, 0, 0};
@@ -295,6 +383,18 @@ extern "C" hero_status hero_int8_attn(const int8_t* q, const int64_t q_strides[4
         const int64_t blocks = (bytes / 16 + 255) / 256;
         if (blocks > 0x7fffffffLL) return HERO_ERR_SHAPE;
         hipLaunchKernelGGL(zero_rows_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (int8_t*)out, bytes);
+        return hero_launch_status();
+    }
+    if (Sq == 1 && Skv <= DEC_MAX_KEYS) {          // decode: the cache-streaming kernel
+        dim3 grid((unsigned)H, (unsigned)B), block(256);
+        const size_t lds = (size_t)Skv * sizeof(int);
+#define HERO_DEC(DH_, ODT_) do { \
+            if (lds > 32768 && hipFuncSetAttribute((const void*)int8_attn_decode_kernel<DH_, ODT_>, \
+                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) return HERO_ERR_LAUNCH; \
+            hipLaunchKernelGGL((int8_attn_decode_kernel<DH_, ODT_>), grid, block, lds, st, a); } while (0)
+        if (Dh == 64) { if (out_dt == HERO_I8) HERO_DEC(64, HERO_I8); else if (out_dt == HERO_BF16) HERO_DEC(64, HERO_BF16); else HERO_DEC(64, HERO_F16); }
+        else { if (out_dt == HERO_I8) HERO_DEC(128, HERO_I8); else if (out_dt == HERO_BF16) HERO_DEC(128, HERO_BF16); else HERO_DEC(128, HERO_F16); }
+#undef HERO_DEC
         return hero_launch_status();
     }
     return Dh == 64 ? launch<64>(a, out_dt, st) : launch<128>(a, out_dt, st);

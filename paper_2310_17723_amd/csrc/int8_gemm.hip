@@ -283,7 +283,6 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void int8_gemm_kernel(GemmArgs 
     // front of its next MFMA while the address unit drains; spread out, the memory
     // instructions issue in the shadow of the 32-cycle MFMAs.
     constexpr int NM = TM * TN, NFR = TM + TN, NW = A_UNITS + B_UNITS;
-    static_assert(NW <= NM && NFR <= NM, "interleave plan needs one slot per memory instruction");
     auto iteration = [&](int kt, int buf, auto U) {
         constexpr int u = decltype(U)::value;
         const int8_t* sa = sA0 + buf * BM * LDS_LD + frag_a;
@@ -297,14 +296,16 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void int8_gemm_kernel(GemmArgs 
             f0[t] = *reinterpret_cast<const v4i*>((t < TN ? sb + t * 32 * LDS_LD : sa + (t - TN) * 32 * LDS_LD));
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int n = 0; n < NM; ++n) {                             // k-step 0
+        for (int n = 0; n < NM; ++n) {                             // k-step 0; memory instructions dealt round-robin
             const int jj = n / TM, ii = n % TM;
             acc[ii][jj] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f0[jj], f0[TN + ii], acc[ii][jj], 0, 0, 0);
-            if (n < NFR)
-                f1[n] = *reinterpret_cast<const v4i*>((n < TN ? sb + n * 32 * LDS_LD : sa + (n - TN) * 32 * LDS_LD) + 32);
-            if (n < NW) {                                          // slab kt + 1 from register set u into LDS
-                if (n < A_UNITS) *reinterpret_cast<v4i*>(wa + n * (NT / CPR) * LDS_LD) = ra[u][n];
-                else *reinterpret_cast<v4i*>(wb + (n - A_UNITS) * (NT / CPR) * LDS_LD) = rb[u][n - A_UNITS];
+#pragma unroll
+            for (int t = n; t < NFR; t += NM)
+                f1[t] = *reinterpret_cast<const v4i*>((t < TN ? sb + t * 32 * LDS_LD : sa + (t - TN) * 32 * LDS_LD) + 32);
+#pragma unroll
+            for (int t = n; t < NW; t += NM) {                     // slab kt + 1 from register set u into LDS
+                if (t < A_UNITS) *reinterpret_cast<v4i*>(wa + t * (NT / CPR) * LDS_LD) = ra[u][t];
+                else *reinterpret_cast<v4i*>(wb + (t - A_UNITS) * (NT / CPR) * LDS_LD) = rb[u][t - A_UNITS];
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -312,9 +313,10 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void int8_gemm_kernel(GemmArgs 
         for (int n = 0; n < NM; ++n) {                             // k-step 1
             const int jj = n / TM, ii = n % TM;
             acc[ii][jj] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f1[jj], f1[TN + ii], acc[ii][jj], 0, 0, 0);
-            if (n < NW) {                                          // slab kt + 1 + PD into the freed register set
-                if (n < A_UNITS) ra[u][n] = *reinterpret_cast<const v4i*>(pa[n] + koff);
-                else rb[u][n - A_UNITS] = *reinterpret_cast<const v4i*>(pb[n - A_UNITS] + koff);
+#pragma unroll
+            for (int t = n; t < NW; t += NM) {                     // slab kt + 1 + PD into the freed register set
+                if (t < A_UNITS) ra[u][t] = *reinterpret_cast<const v4i*>(pa[t] + koff);
+                else rb[u][t - A_UNITS] = *reinterpret_cast<const v4i*>(pb[t - A_UNITS] + koff);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -487,13 +489,15 @@ hero_status launch_grid(GemmArgs g, int BM, int BN, int threads, K kernel, hipSt
 
 // Tile choice: the 256x256 direct-to-LDS kernel once the grid has enough tiles to fill about half
 // of the 256 CUs; the 128x128 register-staged kernel otherwise (small, skinny or ragged problems).
-// HERO_GEMM_TILE (0 / 1) overrides the choice for tuning runs.
+// HERO_GEMM_TILE (0 / 1 / 2) overrides the choice for tuning runs.
 template <int EPI, int CDT, int RDT>
 hero_status launch_epi(const GemmArgs& g, hipStream_t st) {
     const char* e = getenv("HERO_GEMM_TILE");
     int cfg = e ? atoi(e) : -1;
     if (cfg < 0) cfg = ((int64_t)((g.M + 255) / 256) * ((g.N + 255) / 256) >= 96) ? 1 : 0;
     if (cfg == 1) return launch_grid(g, 256, 256, 512, int8_gemm_dma_kernel<256, 256, 2, 4, 4, 2, EPI, CDT, RDT>, st);
+    if (cfg == 2 || (cfg < 0 && g.M <= 64))     // skinny M (decode): more, smaller tiles stream the weights from more CUs
+        return launch_grid(g, 64, 64, 256, int8_gemm_kernel<64, 64, 2, 2, 2, 2, EPI, CDT, RDT>, st);
     return launch_grid(g, 128, 128, 256, int8_gemm_kernel<128, 128, 2, 2, 2, 2, EPI, CDT, RDT>, st);
 }
 
