@@ -28,7 +28,10 @@ sys.path.insert(0, ROOT)
 # HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # (two runs, scaled by the same counters on a plain copy of known size); the summaries are in
 # profiles/.  Keyed by (M, N, K) of the FC1 GeMM^quant; anything else reports null.
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {
+    # profiles/bert-large_kernels_hbm_traffic_pmc.txt: fetch 49653.7 KiB x 2.00 (copy calibration), write 65536 KiB x 1.00
+    (16384, 4096, 1024): {"fetch_bytes": 101690778, "write_bytes": 67108864},
+}
 
 PEAK_INT8_TOPS = 5000.0      # MI355X dense INT8 MFMA, TOP/s
 PEAK_HBM_GBS = 8000.0        # MI355X HBM3E, GB/s
@@ -256,6 +259,8 @@ def main():
     ap.add_argument("--layers", type=int, default=None, help="override the stack depth")
     ap.add_argument("--seed", type=int, default=2310)
     ap.add_argument("--no-extras", action="store_true", help="skip the GEMM sweep / LN / CPU legs")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain 256 MiB device copy 5 times (reference for the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the path shards without exchange along tokens; "
@@ -268,6 +273,14 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
+    if args.copy_calibration:
+        src = torch.randint(-127, 128, (256 << 20,), dtype=torch.int8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": 256 << 20, "copy_bytes_written": 256 << 20, "launches": 5}))
+        return
     hero = pkg.load()                     # raises if libhero.so is missing: no fallback
     shape = synth.CONFIGS[WORKLOADS[args.workload]]
     mode = {"M1": HB.MODE_M1, "M2": HB.MODE_M2, "M3": HB.MODE_M3}[args.mode]
