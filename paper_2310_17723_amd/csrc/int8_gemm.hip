@@ -496,6 +496,8 @@ hero_status launch_epi(const GemmArgs& g, hipStream_t st) {
     int cfg = e ? atoi(e) : -1;
     if (cfg < 0) cfg = ((int64_t)((g.M + 255) / 256) * ((g.N + 255) / 256) >= 96) ? 1 : 0;
     if (cfg == 1) return launch_grid(g, 256, 256, 512, int8_gemm_dma_kernel<256, 256, 2, 4, 4, 2, EPI, CDT, RDT>, st);
+    if (cfg == 4) return launch_grid(g, 256, 128, 256, int8_gemm_dma_kernel<256, 128, 2, 2, 3, 2, EPI, CDT, RDT>, st);
+    if (cfg == 5) return launch_grid(g, 128, 256, 256, int8_gemm_dma_kernel<128, 256, 2, 2, 3, 2, EPI, CDT, RDT>, st);
     if (cfg == 2 || (cfg < 0 && g.M <= 64))     // skinny M (decode): more, smaller tiles stream the weights from more CUs
         return launch_grid(g, 64, 64, 256, int8_gemm_kernel<64, 64, 2, 2, 2, 2, EPI, CDT, RDT>, st);
     return launch_grid(g, 128, 128, 256, int8_gemm_kernel<128, 128, 2, 2, 2, 2, EPI, CDT, RDT>, st);
