@@ -45,13 +45,17 @@ template <int CDT> struct ElemSize { static constexpr int v = CDT == HERO_I32 ? 
 // contiguous range [x * per_xcd, (x+1) * per_xcd) of a grouped order in which 64
 // consecutive tiles form an 8 x 8 square of panels (operands shared through that XCD's L2).
 template <int BM, int BN>
-__device__ __forceinline__ bool tile_origin(const GemmArgs& g, int& m0, int& n0) {
-    const int seq = (blockIdx.x % NUM_XCD) * g.per_xcd + blockIdx.x / NUM_XCD;
-    if (seq >= g.ntm * g.ntn) return false;
+__device__ __forceinline__ void tile_from_seq(const GemmArgs& g, int seq, int& m0, int& n0) {
     const int grp = seq / (GROUP_M * g.ntn), rem = seq % (GROUP_M * g.ntn);
     const int gsize = min(g.ntm - grp * GROUP_M, GROUP_M);
     m0 = (grp * GROUP_M + rem % gsize) * BM;
     n0 = (rem / gsize) * BN;
+}
+template <int BM, int BN>
+__device__ __forceinline__ bool tile_origin(const GemmArgs& g, int& m0, int& n0) {
+    const int seq = (blockIdx.x % NUM_XCD) * g.per_xcd + blockIdx.x / NUM_XCD;
+    if (seq >= g.ntm * g.ntn) return false;
+    tile_from_seq<BM, BN>(g, seq, m0, n0);
     return true;
 }
 
@@ -72,7 +76,7 @@ __device__ __forceinline__ void stage_col_vectors(const GemmArgs& g, float* sv, 
 // TM passes; pass i puts the block's rows {wm*TM*32 + i*32 + 0..31} (for every wm) through the
 // fp32 epilogue, stages them in LDS as a [WM*32][BN] strip and writes whole row segments to HBM.
 // Two strip buffers alternate when they fit, so a pass costs one barrier.
-template <int BM, int BN, int WM, int WN, int EPI, int CDT, int RDT, int STRIP_SPACE>
+template <int BM, int BN, int WM, int WN, int EPI, int CDT, int RDT, int STRIP_SPACE, bool OS_RAW = false>
 __device__ __forceinline__ void epilogue(const GemmArgs& g, v16i (&acc)[BM / WM / 32][BN / WN / 32],
                                          int8_t* smem, const float* sv, const float (&rsr)[BM / WM / 32],
                                          int m0, int n0, int tid) {
@@ -98,7 +102,12 @@ __device__ __forceinline__ void epilogue(const GemmArgs& g, v16i (&acc)[BM / WM 
             const int nl = wn * TN * 32 + (q >> 2) * 32 + (q & 3) * 8 + hh * 4;
             cs[q] = *reinterpret_cast<const v4f*>(sv + nl);
             bs[q] = *reinterpret_cast<const v4f*>(sv + BN + nl);
-            if (EPI == HERO_EPI_GELU_REQUANT) os[q] = *reinterpret_cast<const v4f*>(sv + 2 * BN + nl);
+            if (EPI == HERO_EPI_GELU_REQUANT) {
+                os[q] = *reinterpret_cast<const v4f*>(sv + 2 * BN + nl);
+                if (OS_RAW)                                   // the vector holds S_a itself: hardware reciprocal (1 ulp; +-1 LSB class)
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) os[q][t] = __builtin_amdgcn_rcpf(os[q][t]);
+            }
         }
     }
 #pragma unroll
@@ -476,6 +485,180 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void int8_gemm_dma_kernel(GemmA
     epilogue<BM, BN, WM, WN, EPI, CDT, RDT, POOL>(g, acc, smem, sv, rsr, m0, n0, tid);
 }
 
+// =====================================================================================
+// Persistent variant of the direct-to-LDS kernel (large problems, 1-byte outputs): one
+// workgroup per CU walks a strided list of tiles, and the slab ring runs straight through
+// the tile boundaries, so the first slabs of the next tile (and its per-column / per-row
+// epilogue vectors, fetched by the same direct loads into a double-buffered LDS area) are
+// already resident when the epilogue of the current tile ends.  The epilogue strips have
+// LDS of their own behind the ring.  Slab addresses are a wave-uniform tile base in SGPRs
+// plus a per-lane 32-bit offset, so advancing along K is scalar arithmetic.
+// =====================================================================================
+__device__ __forceinline__ void dma16s(uint32_t voff, const int8_t* sbase, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :: "v"(voff), "s"(sbase), "s"(lds_base) : "memory", "m0");
+}
+__device__ __forceinline__ void dma4s(uint32_t voff, const float* sbase, uint32_t lds_base) {   // lane l -> lds_base + 4 l
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
+                 :: "v"(voff), "s"(sbase), "s"(lds_base) : "memory", "m0");
+}
+
+template <int NS, int EPI, int CDT>
+__global__ __launch_bounds__(512, 2) void int8_gemm_persistent_kernel(GemmArgs g) {
+    constexpr int BM = 256, BN = 256, WM = 2, WN = 4;
+    constexpr int NT = WM * WN * 64, NWAVE = WM * WN;
+    constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+    constexpr int A_BYTES = BM * BK, B_BYTES = BN * BK, STAGE = A_BYTES + B_BYTES;
+    constexpr int A_UNITS = A_BYTES / 16 / NT, B_UNITS = B_BYTES / 16 / NT, NW = A_UNITS + B_UNITS;
+    constexpr int NM = TM * TN, NFR = TM + TN;
+    static_assert(NS >= 3 && NW <= NM && NFR <= NM, "ring / interleave plan");
+    static_assert(EPI == HERO_EPI_REQUANT || EPI == HERO_EPI_GELU_REQUANT, "1-byte outputs only");
+    constexpr int RING = NS * STAGE;
+    constexpr int STRIP_BYTES = WM * 32 * (BN * ElemSize<CDT>::v + 16);
+    constexpr int SVF = 4 * BN;                                  // floats per vector set: column scale, bias, S_a, row scale
+    static_assert(BM == BN, "the row-scale vector shares the column vectors' length");
+    static_assert(RING + STRIP_BYTES + 2 * SVF * 4 <= 160 * 1024, "LDS budget");
+    __shared__ __attribute__((aligned(1024))) int8_t smem[RING + STRIP_BYTES + 2 * SVF * 4];
+    int8_t* const strips = smem + RING;
+    float* const sv0 = reinterpret_cast<float*>(smem + RING + STRIP_BYTES);
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+    const int xcd = blockIdx.x % NUM_XCD, slot = blockIdx.x / NUM_XCD, nslot = gridDim.x / NUM_XCD;
+    const int seq_end = min((xcd + 1) * g.per_xcd, g.ntm * g.ntn);
+    int seq = xcd * g.per_xcd + slot;                            // this workgroup's tiles: seq, seq + nslot, ...
+    if (seq >= seq_end) return;
+    const int KT = g.K / BK;
+    const bool has_rs = g.a_row_scale != nullptr, has_bias = g.bias != nullptr;
+    if (!has_bias)                                               // the bias vectors are read by the epilogue either way
+        for (int c = tid; c < 2 * BN; c += NT) sv0[(c / BN) * SVF + BN + c % BN] = 0.0f;
+
+    // loader: unit u of wave w fills LDS granules [(u * NWAVE + w) * 64, +64) of the A (or B) part of
+    // a stage; lane l owns row u * 128 + lrow, stored chunk l % 4 = global chunk (l % 4) ^ ((row >> 2) & 3).
+    const int lrow = wave * 16 + (lane >> 2);
+    const uint32_t lc = (uint32_t)(((lane & 3) ^ ((lrow >> 2) & 3)) * 16);
+    const uint32_t wbase = __builtin_amdgcn_readfirstlane(lds_offset(smem) + wave * 1024);
+    const uint32_t svbase = __builtin_amdgcn_readfirstlane(lds_offset(sv0));
+
+    // ---- issue stream: the tile / slab the next direct loads belong to (runs NS-1 slabs ahead)
+    int iseq = seq, ikt = 0, ipar = 0;
+    const int8_t* ia; const int8_t* ib;                          // wave-uniform: tile base + slab offset
+    uint32_t oa[A_UNITS], ob[B_UNITS];
+    auto set_issue_tile = [&](int s, int par) {
+        int m0i, n0i;
+        tile_from_seq<BM, BN>(g, s, m0i, n0i);
+        ia = g.A + (int64_t)m0i * g.lda;
+        ib = g.Bt + (int64_t)n0i * g.ldb;
+#pragma unroll
+        for (int u = 0; u < A_UNITS; ++u) oa[u] = (uint32_t)min(lrow + u * (NWAVE * 16), g.M - 1 - m0i) * (uint32_t)g.lda + lc;
+#pragma unroll
+        for (int u = 0; u < B_UNITS; ++u) ob[u] = (uint32_t)min(lrow + u * (NWAVE * 16), g.N - 1 - n0i) * (uint32_t)g.ldb + lc;
+        // epilogue vectors of that tile: wave w fetches 64 entries (chunk w % 4) of vectors w / 4 and 2 + w / 4
+        const int wu = __builtin_amdgcn_readfirstlane(wave);
+        const int ch = (wu & 3) * 64, which = wu >> 2;
+        const uint32_t dst = svbase + par * SVF * 4 + ch * 4;
+        const uint32_t cn = (uint32_t)min(ch + lane, g.N - 1 - n0i) * 4u, cm = (uint32_t)min(ch + lane, g.M - 1 - m0i) * 4u;
+        if (which == 0) {
+            dma4s(cn, g.b_col_scale + n0i, dst);
+            if (EPI == HERO_EPI_GELU_REQUANT) dma4s(cn, g.out_col_scale + n0i, dst + 2 * BN * 4);
+        } else {
+            if (has_bias) dma4s(cn, g.bias + n0i, dst + BN * 4);
+            if (has_rs) dma4s(cm, g.a_row_scale + m0i, dst + 3 * BN * 4);
+        }
+    };
+    auto issue = [&](int n, int stage) {                         // the n-th direct load of the issue stream's slab
+        if (n < A_UNITS) dma16s(oa[n], ia, wbase + stage * STAGE + n * NWAVE * 1024);
+        else dma16s(ob[n - A_UNITS], ib, wbase + stage * STAGE + A_BYTES + (n - A_UNITS) * NWAVE * 1024);
+    };
+    auto advance = [&]() {                                       // next slab; past the last tile the last slab repeats (never read)
+        if (++ikt < KT) { ia += BK; ib += BK; return; }
+        if (iseq + nslot < seq_end) {
+            iseq += nslot; ikt = 0; ipar ^= 1;
+            set_issue_tile(iseq, ipar);
+        } else {
+            ikt = KT - 1;
+        }
+    };
+
+    // fragment offsets inside a stage (row rr, k-step ks, half hh): rr*64 + ((2ks+hh) ^ ((rr>>2)&3))*16
+    const int hh = lane >> 5, ml = lane & 31;
+    int fo[2][NFR];
+#pragma unroll
+    for (int t = 0; t < NFR; ++t) {
+        const int rr = (t < TN ? wn * TN * 32 + t * 32 : wm * TM * 32 + (t - TN) * 32) + ml;
+        const int base = (t < TN ? A_BYTES : 0) + rr * 64;
+        fo[0][t] = base + (((0 + hh) ^ ((rr >> 2) & 3)) << 4);
+        fo[1][t] = base + (((2 + hh) ^ ((rr >> 2) & 3)) << 4);
+    }
+
+    // prologue: vectors of the first tile, slabs 0 .. NS-2 in flight, slab 0 landed
+    set_issue_tile(seq, 0);
+#pragma unroll
+    for (int s0 = 0; s0 < NS - 1; ++s0) {
+#pragma unroll
+        for (int n = 0; n < NW; ++n) issue(n, s0);
+        advance();
+    }
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm((NS - 2) * NW));
+    __syncthreads();
+
+    int stage = 0, par = 0;
+    for (;;) {
+        int m0, n0;
+        tile_from_seq<BM, BN>(g, seq, m0, n0);
+        v16i acc[TM][TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+        v4i f0[NFR], f1[NFR];
+#pragma unroll
+        for (int t = 0; t < NFR; ++t) f0[t] = *reinterpret_cast<const v4i*>(smem + stage * STAGE + fo[0][t]);
+
+        // One slab per iteration with the barrier in the middle (see int8_gemm_dma_kernel); the slab issued
+        // in iteration kt is the one NS-1 ahead in the stream, which may already belong to the next tile.
+        for (int kt = 0; kt < KT; ++kt) {
+            const int8_t* st = smem + stage * STAGE;
+            const int nstage = stage + 1 == NS ? 0 : stage + 1;
+            const int pstage = stage == 0 ? NS - 1 : stage - 1;
+            const int8_t* stn = smem + nstage * STAGE;
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int n = 0; n < NM; ++n) {                             // k-step 0
+                const int jj = n / TM, ii = n % TM;
+                acc[ii][jj] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f0[jj], f0[TN + ii], acc[ii][jj], 0, 0, 0);
+                if (n < NFR) f1[n] = *reinterpret_cast<const v4i*>(st + fo[1][n]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm((NS - 3) * NW));     // the next slab has landed (mine)
+            __syncthreads();                                           // ... and everybody's
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int n = 0; n < NM; ++n) {                             // k-step 1
+                const int jj = n / TM, ii = n % TM;
+                acc[ii][jj] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f1[jj], f1[TN + ii], acc[ii][jj], 0, 0, 0);
+                if (n < NFR) f0[n] = *reinterpret_cast<const v4i*>(stn + fo[0][n]);
+                if (n < NW) issue(n, pstage);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            advance();
+            stage = nstage;
+        }
+        // epilogue of this tile; the ring keeps filling with the next tile's slabs meanwhile
+        const float* sv = sv0 + par * SVF;
+        float rsr[TM];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) rsr[i] = has_rs ? sv[3 * BN + wm * TM * 32 + i * 32 + ml] : 1.0f;
+        epilogue<BM, BN, WM, WN, EPI, CDT, -1, STRIP_BYTES, true>(g, acc, strips, sv, rsr, m0, n0, tid);
+        seq += nslot;
+        par ^= 1;
+        if (seq >= seq_end) break;
+    }
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));                      // the redundant tail loads
+}
+
 template <typename K>
 hero_status launch_grid(GemmArgs g, int BM, int BN, int threads, K kernel, hipStream_t st) {
     g.ntm = (g.M + BM - 1) / BM;
@@ -494,10 +677,22 @@ template <int EPI, int CDT, int RDT>
 hero_status launch_epi(const GemmArgs& g, hipStream_t st) {
     const char* e = getenv("HERO_GEMM_TILE");
     int cfg = e ? atoi(e) : -1;
+    GemmArgs g2;
     if (cfg < 0) cfg = ((int64_t)((g.M + 255) / 256) * ((g.N + 255) / 256) >= 96) ? 1 : 0;
+    if constexpr (CDT == HERO_I8) {
+        // persistent form: 1-byte outputs, K long enough that the ring never runs more than one tile ahead,
+        // 32-bit per-lane offsets (256 rows of lda / ldb bytes)
+        if ((cfg == 7 || (cfg == 1 && !e && EPI == HERO_EPI_REQUANT)) && g.K >= 4 * BK && g.lda < (1 << 24) && g.ldb < (1 << 24)) {
+            g2 = g;
+            g2.ntm = (g.M + 255) / 256; g2.ntn = (g.N + 255) / 256;
+            const int64_t tiles = (int64_t)g2.ntm * g2.ntn;
+            g2.per_xcd = (int)((tiles + NUM_XCD - 1) / NUM_XCD);
+            const int nslot = g2.per_xcd < 32 ? g2.per_xcd : 32;      // 32 CUs per XCD, one workgroup each
+            hipLaunchKernelGGL((int8_gemm_persistent_kernel<4, EPI, CDT>), dim3((unsigned)(nslot * NUM_XCD)), dim3(512), 0, st, g2);
+            return hero_launch_status();
+        }
+    }
     if (cfg == 1) return launch_grid(g, 256, 256, 512, int8_gemm_dma_kernel<256, 256, 2, 4, 4, 2, EPI, CDT, RDT>, st);
-    if (cfg == 4) return launch_grid(g, 256, 128, 256, int8_gemm_dma_kernel<256, 128, 2, 2, 3, 2, EPI, CDT, RDT>, st);
-    if (cfg == 5) return launch_grid(g, 128, 256, 256, int8_gemm_dma_kernel<128, 256, 2, 2, 3, 2, EPI, CDT, RDT>, st);
     if (cfg == 2 || (cfg < 0 && g.M <= 64))     // skinny M (decode): more, smaller tiles stream the weights from more CUs
         return launch_grid(g, 64, 64, 256, int8_gemm_kernel<64, 64, 2, 2, 2, 2, EPI, CDT, RDT>, st);
     return launch_grid(g, 128, 128, 256, int8_gemm_kernel<128, 128, 2, 2, 2, 2, EPI, CDT, RDT>, st);

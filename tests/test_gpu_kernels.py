@@ -164,6 +164,40 @@ def test_gemm_gelu_epilogues(hero, M, N, K):
     assert rel_err(O.bf16_to_f32(to_np(gotb)), O.bf16_to_f32(refb)) <= 2e-2
 
 
+@pytest.mark.parametrize("M,N,K", [(2500, 2600, 320), (2560, 2560, 256), (4000, 1700, 704)])
+def test_gemm_many_tiles_requant_ragged_edges(hero, M, N, K, monkeypatch):
+    """Enough 256 x 256 tiles for the large-problem kernels (the persistent one included: several tiles
+    per workgroup, ragged last row and column panels, K of 4 / 5 / 11 slabs), strided operands and output;
+    REQUANT is bit-exact, GELU^quant in the +-1 LSB class, with and without the optional vectors."""
+    c = synth.gemm_case(700 + M, M, K + 64, N)
+    A_full, rs, cs, bias = c["A"], c["a_row_scale"], c["b_col_scale"], c["bias"]
+    A, Bt = A_full[:, :K], c["Bt"][:, :K]
+    dA, dB = dev(A_full)[:, :K], dev(c["Bt"])[:, :K]
+    y = O.int8_gemm(A, Bt, a_row_scale=rs, b_col_scale=cs, bias=bias, epi=O.EPI_DEQUANT, c_dt=O.F32)
+    s_out = np.float32(np.abs(y).max() / 127)
+    cs2, b2 = (cs / s_out).astype(np.float32), (bias / s_out).astype(np.float32)
+    ref = O.int8_gemm(A, Bt, a_row_scale=rs, b_col_scale=cs2, bias=b2, epi=O.EPI_REQUANT, c_dt=O.I8)
+    ref_plain = O.int8_gemm(A, Bt, b_col_scale=cs2 * np.float32(0.01), epi=O.EPI_REQUANT, c_dt=O.I8)
+    csg = (cs * np.float32(30.0 / np.sqrt(K))).astype(np.float32)
+    g = O.int8_gemm(A, Bt, a_row_scale=rs, b_col_scale=csg, bias=bias, epi=O.EPI_DEQUANT_GELU, c_dt=O.F32)
+    s_a = (np.abs(g).max(axis=0) / 127).astype(np.float32)
+    ref_g = O.int8_gemm(A, Bt, a_row_scale=rs, b_col_scale=csg, bias=bias, epi=O.EPI_GELU_REQUANT, out_col_scale=s_a, c_dt=O.I8)
+    for tile in (None, "1", "7"):                  # default choice, one tile per workgroup, persistent
+        if tile is None:
+            monkeypatch.delenv("HERO_GEMM_TILE", raising=False)
+        else:
+            monkeypatch.setenv("HERO_GEMM_TILE", tile)
+        Cbuf = torch.full((M, N + 16), -7, dtype=torch.int8, device="cuda")
+        hero.hero_int8_gemm(dA, dB, dev(rs), dev(cs2), dev(b2), epi=HB.EPI_REQUANT, C_out=Cbuf[:, :N])
+        assert_exact(to_np(Cbuf[:, :N]), ref, f"requant tile={tile}")
+        assert (to_np(Cbuf[:, N:]) == -7).all()
+        got = hero.hero_int8_gemm(dA, dB, None, dev(cs2 * np.float32(0.01)), None, epi=HB.EPI_REQUANT, out_dtype=torch.int8)
+        assert_exact(to_np(got), ref_plain, f"requant, no row scale, no bias, tile={tile}")
+        got = hero.hero_int8_gemm(dA, dB, dev(rs), dev(csg), dev(bias), epi=HB.EPI_GELU_REQUANT,
+                                  out_col_scale=dev(s_a), out_dtype=torch.int8)
+        assert_codes(to_np(got), ref_g, f"gelu requant tile={tile}")
+
+
 def test_gemm_strided_operands_and_errors(hero):
     """Leading dimensions larger than the logical width; invalid combinations are refused."""
     M, N, K = 96, 80, 128
