@@ -5,18 +5,25 @@
 // HBM-bound: every input element is read once and every output element written once.
 //   * One wavefront owns one row at a time and keeps it in registers (NCH chunks of EPL
 //     elements per lane; a chunk is one 128-bit load per lane, consecutive lanes consecutive
-//     addresses).  Workgroups are persistent: a wave walks rows with a grid-sized stride and
-//     has the NEXT row's loads in flight while it works on the current one.
+//     addresses).  Workgroups are persistent and wide (up to 16 waves, one workgroup per CU for
+//     large inputs): a wave walks rows with a grid-sized stride and has the loads of the next
+//     row in flight while it works on the current one.  The fetched registers are passed
+//     through an empty asm statement at the top of each row so that the compiler cannot hoist
+//     their first use (and with it the wait for the loads) up to the point of issue.
 //   * gamma, beta and the FWQ column scale are staged in LDS once per workgroup, not re-read
-//     per row (they would cost 4x the row's own HBM bytes in cache traffic).
+//     from the caches per row.
+//   * INT8 codes are unpacked with one SDWA conversion each (sign-extending byte select).
 //   * The three row reductions (sum, sum of squared deviations, absmax) run on the DPP
 //     cross-lane network (quad_perm / row_mirror / row_bcast), no LDS round trips.
 //   * Statistics are fp32, mean first and variance about the mean.
-//   * Codes are rne(y / s) with IEEE fp32 division BY DEFINITION; the kernel multiplies by 1/s
-//     and, on the bit-exact path (no LayerNorm), falls back to the true division for the rare
-//     lanes whose product lies within 4e-5 of a rounding tie, the only place where the two can
-//     disagree (both are within 127 * 2^-23 of the exact quotient).  Rounding and the int8
-//     two's-complement byte come out of one fp32 add of 1.5 * 2^23.
+//   * Codes are rne(y / s) with IEEE fp32 division BY DEFINITION.  Without LayerNorm (pure
+//     per-token quantization, bit-exact by contract) the kernel multiplies by 1/s and falls back
+//     to the true division for the rare lanes whose product lies within 4e-5 of a rounding tie,
+//     the only place where the two can disagree; rounding and the two's-complement byte come out
+//     of one fp32 add of 1.5 * 2^23.  Behind a LayerNorm the fp32 statistics already differ from
+//     the definition's fp64 ones by more than that, so the +-1 LSB class applies: hardware
+//     reciprocal / reciprocal square root, and v_cvt_pk_u8_f32 of y/s + 128 rounds, saturates
+//     and packs in one instruction (the offset is removed by an XOR of the packed dword).
 #include "hero_common.h"
 #include <type_traits>
 
@@ -31,7 +38,20 @@ struct LnArgs {
     int x_dt, r_dt, hp_dt;       // r_dt / hp_dt = -1 when absent
 };
 
-__device__ __forceinline__ float byte_to_f32(int w, int i) { return (float)(int8_t)(w >> (8 * i)); }
+// sign-extended byte B of w -> fp32 in one instruction
+template <int B>
+__device__ __forceinline__ float sbyte_f32(int w) {
+    float r;
+    if constexpr (B == 0) asm("v_cvt_f32_i32_sdwa %0, sext(%1) dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_0" : "=v"(r) : "v"(w));
+    else if constexpr (B == 1) asm("v_cvt_f32_i32_sdwa %0, sext(%1) dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_1" : "=v"(r) : "v"(w));
+    else if constexpr (B == 2) asm("v_cvt_f32_i32_sdwa %0, sext(%1) dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_2" : "=v"(r) : "v"(w));
+    else asm("v_cvt_f32_i32_sdwa %0, sext(%1) dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_3" : "=v"(r) : "v"(w));
+    return r;
+}
+// the four codes of one dword
+__device__ __forceinline__ void unpack4(int w, float (&o)[4]) {
+    o[0] = sbyte_f32<0>(w); o[1] = sbyte_f32<1>(w); o[2] = sbyte_f32<2>(w); o[3] = sbyte_f32<3>(w);
+}
 
 // ---- 64-lane reductions on the DPP network; the result is wave-uniform ---------------------------
 template <bool IS_MAX>
@@ -65,25 +85,27 @@ __device__ __forceinline__ void store_hp(const float (&v)[EPL], uint16_t* dst) {
     }
 }
 
+constexpr int ln_max_waves(int nch) { return nch <= 2 ? 16 : (nch == 4 ? 8 : 4); }   // per workgroup: the row must fit the registers
+
 // XDT: HERO_I8 / HERO_BF16 / HERO_F16.  RDT: -1 (no second addend) / HERO_I8 / HERO_BF16 / HERO_F16.
-template <int XDT, int RDT, int NCH>
-__global__ __launch_bounds__(256) void ln_quant_kernel(LnArgs a) {
+template <int XDT, int RDT, int NCH, bool HAS_LN>
+__global__ __launch_bounds__(64 * ln_max_waves(NCH)) void ln_quant_kernel(LnArgs a) {
     constexpr bool X_I8 = XDT == HERO_I8;
     constexpr int EPL = X_I8 ? 16 : 8;
     constexpr int CH = EPL * HERO_WAVE;
+    constexpr bool r_i8 = RDT == HERO_I8, r_hp = RDT == HERO_BF16 || RDT == HERO_F16;
+    constexpr int PF = 1;                                     // rows in flight ahead of the current one
     extern __shared__ __attribute__((aligned(16))) float sp[];   // [3][Dp]: gamma, beta, r_col_scale
     const int D = a.D, Dp = NCH * CH;
-    const int tid = threadIdx.x, lane = tid & 63;
-    const bool has_ln = a.gamma != nullptr;
-    constexpr bool r_i8 = RDT == HERO_I8, r_hp = RDT == HERO_BF16 || RDT == HERO_F16;
-    const int64_t nwaves = (int64_t)gridDim.x * 4;
-    int64_t row = (int64_t)blockIdx.x * 4 + (tid >> 6);      // grid <= ceil(M / 4): only the last block can have idle waves
+    const int tid = threadIdx.x, lane = tid & 63, nwb = blockDim.x >> 6;
+    const int64_t tw = (int64_t)gridDim.x * nwb;              // waves in the grid = row stride of a wave
+    int64_t row = (int64_t)blockIdx.x * nwb + (tid >> 6);
 
-    // raw data of the rows in flight: PF rows ahead of the one being processed
-    constexpr int PF = 1;
+    // raw data of the rows in flight
     v4i rx[PF][NCH], rr0[PF][NCH], rr1[PF][NCH];
     float xsr[PF];
-    auto fetch = [&](int64_t rw, int p) {
+    auto fetch = [&](int64_t rw, auto P) {
+        constexpr int p = decltype(P)::value;
         if (rw >= a.M) return;                                // wave-uniform
         xsr[p] = X_I8 ? a.x_row_scale[rw] : 1.0f;
 #pragma unroll
@@ -103,26 +125,30 @@ __global__ __launch_bounds__(256) void ln_quant_kernel(LnArgs a) {
             }
         }
     };
-#pragma unroll
-    for (int p = 0; p < PF; ++p) fetch(row + p * nwaves, p);  // in flight while the parameters are staged
+    fetch(row, std::integral_constant<int, 0>{});             // in flight while the parameters are staged
+    if constexpr (PF > 1) fetch(row + tw, std::integral_constant<int, PF - 1>{});
 
-    for (int j = tid; j < Dp; j += 256) {
+    for (int j = tid; j < Dp; j += blockDim.x) {
         const bool in = j < D;
-        sp[j] = (has_ln && in) ? a.gamma[j] : 0.0f;
-        sp[Dp + j] = (has_ln && a.beta && in) ? a.beta[j] : 0.0f;
+        sp[j] = (HAS_LN && in) ? a.gamma[j] : 0.0f;
+        sp[Dp + j] = (HAS_LN && a.beta && in) ? a.beta[j] : 0.0f;
         sp[2 * Dp + j] = (r_i8 && in) ? a.r_col_scale[j] : 0.0f;
     }
     __syncthreads();
     if (row >= a.M) return;
     const float inv_d = 1.0f / (float)D;
-    // Without LayerNorm the codes are bit-exact by contract (pure per-token quantization): check for
-    // rounding ties.  Behind a LayerNorm the fp32 statistics already differ from the definition's
-    // by more than a reciprocal multiply does, so the check is skipped there.
-    const bool exact = !has_ln;
+    const float npad = (float)(Dp - D);                       // padded columns hold 0 and are corrected for in the variance
 
     auto process = [&](int64_t row, auto P) {
         constexpr int p = decltype(P)::value;
-
+        // first use of the fetched registers: nothing that reads them may move above this point
+        asm volatile("" : "+v"(xsr[p]));
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            asm volatile("" : "+v"(rx[p][c]));
+            if constexpr (r_i8 || r_hp) asm volatile("" : "+v"(rr0[p][c]));
+            if constexpr (r_hp && EPL == 16) asm volatile("" : "+v"(rr1[p][c]));
+        }
         float v[NCH][EPL];
         const float xs = xsr[p];
         // ---- unpack the fetched row into fp32 (sum of the addends) ---------------------------
@@ -132,7 +158,12 @@ __global__ __launch_bounds__(256) void ln_quant_kernel(LnArgs a) {
             if (j0 < D) {
                 if constexpr (X_I8) {
 #pragma unroll
-                    for (int e = 0; e < 16; ++e) v[c][e] = byte_to_f32(rx[p][c][e >> 2], e & 3) * xs;
+                    for (int e4 = 0; e4 < 4; ++e4) {
+                        float f[4];
+                        unpack4(rx[p][c][e4], f);
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) v[c][4 * e4 + t] = f[t] * xs;
+                    }
                 } else {
 #pragma unroll
                     for (int e = 0; e < 8; ++e) {
@@ -143,9 +174,11 @@ __global__ __launch_bounds__(256) void ln_quant_kernel(LnArgs a) {
                 if constexpr (r_i8) {
 #pragma unroll
                     for (int e4 = 0; e4 < EPL / 4; ++e4) {
-                        v4f rc = *reinterpret_cast<const v4f*>(sp + 2 * Dp + j0 + 4 * e4);
+                        float f[4];
+                        unpack4(rr0[p][c][e4], f);
+                        const v4f rc = *reinterpret_cast<const v4f*>(sp + 2 * Dp + j0 + 4 * e4);
 #pragma unroll
-                        for (int t = 0; t < 4; ++t) v[c][4 * e4 + t] = fmaf(byte_to_f32(rr0[p][c][e4], t), rc[t], v[c][4 * e4 + t]);
+                        for (int t = 0; t < 4; ++t) v[c][4 * e4 + t] = fmaf(f[t], rc[t], v[c][4 * e4 + t]);
                     }
                 } else if constexpr (r_hp) {
 #pragma unroll
@@ -161,10 +194,10 @@ __global__ __launch_bounds__(256) void ln_quant_kernel(LnArgs a) {
             }
         }
         // ---- the loads of the row PF strides ahead go out now, into the register set just unpacked
-        fetch(row + PF * nwaves, p);
+        fetch(row + PF * tw, P);
 
         // ---- LayerNorm: mean, then variance about the mean (fp32) --------------------------
-        if (has_ln) {
+        if constexpr (HAS_LN) {
             float s = 0.0f;
 #pragma unroll
             for (int c = 0; c < NCH; ++c)
@@ -173,24 +206,23 @@ __global__ __launch_bounds__(256) void ln_quant_kernel(LnArgs a) {
             const float mean = wave_reduce<false>(s) * inv_d;
             float q = 0.0f;
 #pragma unroll
-            for (int c = 0; c < NCH; ++c) {
-                const bool act = c * CH + lane * EPL < D;
+            for (int c = 0; c < NCH; ++c)
 #pragma unroll
                 for (int e = 0; e < EPL; ++e) {
-                    float dlt = v[c][e] - mean;
+                    const float dlt = v[c][e] - mean;
                     v[c][e] = dlt;
-                    q = act ? fmaf(dlt, dlt, q) : q;
+                    q = fmaf(dlt, dlt, q);
                 }
-            }
-            const float var = wave_reduce<false>(q) * inv_d;
-            const float rstd = 1.0f / sqrtf(var + a.eps);
+            // a padded column contributed (0 - mean)^2
+            const float var = fmaxf(fmaf(-npad * mean, mean, wave_reduce<false>(q)), 0.0f) * inv_d;
+            const float rstd = __builtin_amdgcn_rsqf(var + a.eps);
 #pragma unroll
             for (int c = 0; c < NCH; ++c) {
-                const int j0 = c * CH + lane * EPL;     // padded columns have gamma = beta = 0 in LDS
+                const int j0 = c * CH + lane * EPL;     // padded columns have gamma = beta = 0
 #pragma unroll
                 for (int e4 = 0; e4 < EPL / 4; ++e4) {
-                    v4f g = *reinterpret_cast<const v4f*>(sp + j0 + 4 * e4);
-                    v4f b = *reinterpret_cast<const v4f*>(sp + Dp + j0 + 4 * e4);
+                    const v4f g = *reinterpret_cast<const v4f*>(sp + j0 + 4 * e4);
+                    const v4f b = *reinterpret_cast<const v4f*>(sp + Dp + j0 + 4 * e4);
 #pragma unroll
                     for (int t = 0; t < 4; ++t) v[c][4 * e4 + t] = fmaf(v[c][4 * e4 + t] * rstd, g[t], b[t]);
                 }
@@ -205,30 +237,42 @@ __global__ __launch_bounds__(256) void ln_quant_kernel(LnArgs a) {
             for (int e = 0; e < EPL; ++e) amax = fmaxf(amax, fabsf(v[c][e]));
         amax = wave_reduce<true>(amax);
         const float sc = amax == 0.0f ? 1.0f : __fdiv_rn(amax, 127.0f);
-        const float inv_sc = __fdiv_rn(1.0f, sc);
+        const float inv_sc = HAS_LN ? __builtin_amdgcn_rcpf(sc) : __fdiv_rn(1.0f, sc);
         if (lane == 0) a.y_scale[row] = sc;
 #pragma unroll
         for (int c = 0; c < NCH; ++c) {
             const int j0 = c * CH + lane * EPL;
             if (j0 >= D) continue;
             const int64_t off = row * (int64_t)D + j0;
-            // |v * inv_sc| <= 127 (absmax row scale), so no clamp is needed before the rounding add
-            float t[EPL];
-            bool near_tie = false;
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) {
-                t[e] = v[c][e] * inv_sc;
-                if (exact) near_tie |= fabsf(t[e] - __builtin_rintf(t[e])) > 0.49996f;
-            }
-            if (exact && near_tie) {                     // rare: redo this lane's chunk with the true division
-#pragma unroll
-                for (int e = 0; e < EPL; ++e) t[e] = __fdiv_rn(v[c][e], sc);
-            }
             uint32_t pk[EPL / 4];
+            if constexpr (HAS_LN) {
+                // |v * inv_sc| <= 127 (1 + 2^-22): v * inv_sc + 128 rounds into 1 .. 255
 #pragma unroll
-            for (int e4 = 0; e4 < EPL / 4; ++e4)
-                pk[e4] = pack_low_bytes(rne_low_byte(t[4 * e4]), rne_low_byte(t[4 * e4 + 1]),
-                                        rne_low_byte(t[4 * e4 + 2]), rne_low_byte(t[4 * e4 + 3]));
+                for (int e4 = 0; e4 < EPL / 4; ++e4) {
+                    uint32_t w = 0;
+#pragma unroll
+                    for (int t = 0; t < 4; ++t)
+                        w = __builtin_amdgcn_cvt_pk_u8_f32(fmaf(v[c][4 * e4 + t], inv_sc, 128.0f), t, w);
+                    pk[e4] = w ^ 0x80808080u;
+                }
+            } else {
+                // |v * inv_sc| <= 127 (absmax row scale), so no clamp is needed before the rounding add
+                float t[EPL];
+                bool near_tie = false;
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) {
+                    t[e] = v[c][e] * inv_sc;
+                    near_tie |= fabsf(t[e] - __builtin_rintf(t[e])) > 0.49996f;
+                }
+                if (near_tie) {                              // rare: redo this lane's chunk with the true division
+#pragma unroll
+                    for (int e = 0; e < EPL; ++e) t[e] = __fdiv_rn(v[c][e], sc);
+                }
+#pragma unroll
+                for (int e4 = 0; e4 < EPL / 4; ++e4)
+                    pk[e4] = pack_low_bytes(rne_low_byte(t[4 * e4]), rne_low_byte(t[4 * e4 + 1]),
+                                            rne_low_byte(t[4 * e4 + 2]), rne_low_byte(t[4 * e4 + 3]));
+            }
             if constexpr (EPL == 16) {
                 v4i o = {(int)pk[0], (int)pk[1], (int)pk[2], (int)pk[3]};
                 *reinterpret_cast<v4i*>(a.y_q + off) = o;
@@ -241,9 +285,15 @@ __global__ __launch_bounds__(256) void ln_quant_kernel(LnArgs a) {
         }
     };
     // register sets rotate with the row: unrolled by PF so the set index is a compile-time constant
-    for (; row < a.M; row += PF * nwaves) {
+    for (;;) {
         process(row, std::integral_constant<int, 0>{});
-        if constexpr (PF > 1) { if (row + nwaves < a.M) process(row + nwaves, std::integral_constant<int, PF - 1>{}); }
+        row += tw;
+        if (row >= a.M) break;
+        if constexpr (PF > 1) {
+            process(row, std::integral_constant<int, PF - 1>{});
+            row += tw;
+            if (row >= a.M) break;
+        }
     }
 }
 
@@ -251,14 +301,20 @@ template <int XDT, int RDT, int NCH>
 hero_status launch_nch(const LnArgs& a, hipStream_t st) {
     constexpr int CH = (XDT == HERO_I8 ? 16 : 8) * HERO_WAVE;
     const size_t lds = (size_t)3 * NCH * CH * sizeof(float);
+    const bool has_ln = a.gamma != nullptr;
+    const void* fn = has_ln ? (const void*)ln_quant_kernel<XDT, RDT, NCH, true> : (const void*)ln_quant_kernel<XDT, RDT, NCH, false>;
     if (lds > 65536 &&                                    // more than 64 KB of dynamic LDS needs the opt-in
-        hipFuncSetAttribute((const void*)ln_quant_kernel<XDT, RDT, NCH>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+        hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
         return HERO_ERR_LAUNCH;
-    // persistent workgroups: a few per CU, never more than the rows need
-    int64_t blocks = (a.M + 3) / 4;
-    const int64_t cap = 256 * (NCH <= 2 ? 8 : 4);
+    // persistent workgroups: wide ones (one per CU) once every CU has several rows per wave, else
+    // 4-wave workgroups, never more than the rows need
+    constexpr int MAXW = ln_max_waves(NCH);
+    const int wpb = a.M >= 256 * MAXW ? MAXW : 4;
+    int64_t blocks = (a.M + wpb - 1) / wpb;
+    const int64_t cap = 256 * (MAXW / wpb);
     if (blocks > cap) blocks = cap;
-    hipLaunchKernelGGL((ln_quant_kernel<XDT, RDT, NCH>), dim3((unsigned)blocks), dim3(256), lds, st, a);
+    if (has_ln) hipLaunchKernelGGL((ln_quant_kernel<XDT, RDT, NCH, true>), dim3((unsigned)blocks), dim3(64 * wpb), lds, st, a);
+    else hipLaunchKernelGGL((ln_quant_kernel<XDT, RDT, NCH, false>), dim3((unsigned)blocks), dim3(64 * wpb), lds, st, a);
     return hero_launch_status();
 }
 
