@@ -9,14 +9,16 @@
 // lane l holds, for ONE output row m = l % 32, the columns n = 8g + 4(l/32) + t (register
 // 4g + t): the per-row scale is one register and a lane owns 4 consecutive columns.
 //
-// Two main loops share one epilogue:
-//   * int8_gemm_dma_kernel (large problems): 256x256 block tile, 8 waves of 128x64, slabs
-//     of 64 bytes of K copied global -> LDS directly (global_load_lds_dwordx4) through a
-//     ring of 4 stages; measured on MI355X the L2 -> CU path, not the matrix cores, bounds
+// Three main loops share one epilogue:
+//   * int8_gemm_persistent_kernel (large problems): 256x256 block tile, 8 waves of 128x64,
+//     slabs of 64 bytes of K copied global -> LDS directly (global_load_lds_dwordx4) through
+//     a ring of 4 stages; one workgroup per CU walks its tiles and the ring runs through the
+//     tile boundaries.  Measured on MI355X the L2 -> CU path, not the matrix cores, bounds
 //     smaller tiles (a 128x128 tile needs 64 B/clk/CU at MFMA peak, the path gives 20-35).
-//   * int8_gemm_kernel (small or ragged problems): 128x128 tile staged through registers.
-// The epilogue stages 64-row strips of the output tile in LDS and writes whole row
-// segments (16 bytes per lane, consecutive lanes consecutive addresses).
+//   * int8_gemm_dma_kernel: the same tile, one tile per workgroup (short K, huge strides).
+//   * int8_gemm_kernel (small or skinny problems): 128x128 / 64x64 tile staged through registers.
+// The epilogue works in registers: a lane-half exchange (v_permlane32_swap) gives every lane a
+// contiguous piece of one output row, written with 128-bit stores.
 #include "hero_common.h"
 #include <cstdlib>
 #include <type_traits>
@@ -72,133 +74,170 @@ __device__ __forceinline__ void stage_col_vectors(const GemmArgs& g, float* sv, 
     }
 }
 
-// ---- shared epilogue --------------------------------------------------------------------------
-// TM passes; pass i puts the block's rows {wm*TM*32 + i*32 + 0..31} (for every wm) through the
-// fp32 epilogue, stages them in LDS as a [WM*32][BN] strip and writes whole row segments to HBM.
-// Two strip buffers alternate when they fit, so a pass costs one barrier.
-template <int BM, int BN, int WM, int WN, int EPI, int CDT, int RDT, int STRIP_SPACE, bool OS_RAW = false>
-__device__ __forceinline__ void epilogue(const GemmArgs& g, v16i (&acc)[BM / WM / 32][BN / WN / 32],
-                                         int8_t* smem, const float* sv, const float (&rsr)[BM / WM / 32],
-                                         int m0, int n0, int tid) {
-    constexpr int NT = WM * WN * 64;
-    constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
-    constexpr bool FUSE_RES = RDT >= 0;                       // residual added at store time, in fp32
-    constexpr int ES = FUSE_RES ? 4 : ElemSize<CDT>::v;       // bytes one value occupies in the strip
-    constexpr int ROWB = BN * ES, RS = ROWB + 16;             // strip row bytes, padded stride
-    constexpr int STRIP = WM * 32 * RS;
-    constexpr int NBUF = 2 * STRIP <= STRIP_SPACE ? 2 : 1;
-    static_assert(STRIP <= STRIP_SPACE, "strip does not fit the LDS left by the main loop");
-    constexpr int CH = ROWB / 16;                             // 16-byte chunks per strip row
+// ---- direct epilogue ---------------------------------------------------------------------------
+// No LDS: after the fp32 epilogue a lane holds, for ONE output row, 4-column groups q (columns
+// 8q + 4hh .. + 3 of the wave's 32*TN columns).  v_permlane32_swap exchanges the groups q >= NQ/2
+// of lanes 0..31 with the groups q < NQ/2 of lanes 32..63, after which lane l < 32 owns the
+// row's first 16*TN columns and lane l + 32 the other 16*TN, contiguous in registers: every lane
+// writes one contiguous piece of its row (32 B of INT8 codes, 64 B of 16-bit values for TN = 2)
+// with 128-bit stores, and the residual of the fused add is read in the same layout.
+__device__ __forceinline__ void swap32(uint32_t a, uint32_t b, uint32_t& lo, uint32_t& hi) {
+    auto r = __builtin_amdgcn_permlane32_swap(a, b, false, false);   // r[0] = {a.low, b.low}, r[1] = {a.high, b.high}
+    lo = r[0]; hi = r[1];
+}
+// ND dwords of one row, first column col (ES bytes per element), bounds-checked against N unless `full`
+template <int ES, int ND>
+__device__ __forceinline__ void store_piece(int8_t* cp, const uint32_t (&d)[ND], int col, int N, bool full, bool al16) {
+    constexpr int EPD = 4 / ES;                                     // elements per dword
+    if (full) {
+        if (al16) {
+#pragma unroll
+            for (int k = 0; k < ND / 4; ++k) {
+                v4i o = {(int)d[4 * k], (int)d[4 * k + 1], (int)d[4 * k + 2], (int)d[4 * k + 3]};
+                *reinterpret_cast<v4i*>(cp + 16 * k) = o;
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < ND; ++k) *reinterpret_cast<uint32_t*>(cp + 4 * k) = d[k];
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < ND; ++k) {
+            const int c = col + k * EPD;
+            if (c + EPD <= N) *reinterpret_cast<uint32_t*>(cp + 4 * k) = d[k];
+            else if (ES < 4) {
+#pragma unroll
+                for (int b = 0; b < EPD; ++b)
+                    if (c + b < N) {
+                        if (ES == 1) cp[4 * k + b] = (int8_t)(d[k] >> (8 * b));
+                        else *reinterpret_cast<uint16_t*>(cp + 4 * k + 2 * b) = (uint16_t)(d[k] >> (16 * b));
+                    }
+            }
+        }
+    }
+}
+
+template <int BM, int BN, int WM, int WN, int EPI, int CDT, int RDT, bool OS_RAW = false>
+__device__ __forceinline__ void epilogue_direct(const GemmArgs& g, v16i (&acc)[BM / WM / 32][BN / WN / 32],
+                                                const float* sv, const float (&rsr)[BM / WM / 32],
+                                                int m0, int n0, int tid) {
+    constexpr int TM = BM / WM / 32, TN = BN / WN / 32, NQ = TN * 4, H = NQ / 2;
+    constexpr bool FUSE_RES = RDT >= 0;
+    constexpr int ES = ElemSize<CDT>::v;
     const int lane = tid & 63, wave = tid >> 6, wm = wave / WN, wn = wave % WN;
     const int hh = lane >> 5, ml = lane & 31;
     const bool has_rs = g.a_row_scale != nullptr;
-    const bool interior = m0 + BM <= g.M && n0 + BN <= g.N && (g.ldc * ElemSize<CDT>::v) % 16 == 0;
+    const int colw = n0 + wn * TN * 32;                            // first column of this wave
+    const int col0 = colw + hh * H * 8;                            // first column this lane stores (after the swap)
+    const bool al16 = (g.ldc * ES) % 16 == 0;
+    const bool full = col0 + H * 8 <= g.N;
 
     // per-column vectors of this lane's 4-column groups, from LDS into registers once
-    v4f cs[TN * 4], bs[TN * 4], os[TN * 4];
+    v4f cs[NQ], bs[NQ];
     if (EPI != HERO_EPI_RAW_I32) {
 #pragma unroll
-        for (int q = 0; q < TN * 4; ++q) {
-            const int nl = wn * TN * 32 + (q >> 2) * 32 + (q & 3) * 8 + hh * 4;
+        for (int q = 0; q < NQ; ++q) {
+            const int nl = wn * TN * 32 + q * 8 + hh * 4;
             cs[q] = *reinterpret_cast<const v4f*>(sv + nl);
             bs[q] = *reinterpret_cast<const v4f*>(sv + BN + nl);
-            if (EPI == HERO_EPI_GELU_REQUANT) {
-                os[q] = *reinterpret_cast<const v4f*>(sv + 2 * BN + nl);
-                if (OS_RAW)                                   // the vector holds S_a itself: hardware reciprocal (1 ulp; +-1 LSB class)
-#pragma unroll
-                    for (int t = 0; t < 4; ++t) os[q][t] = __builtin_amdgcn_rcpf(os[q][t]);
-            }
         }
     }
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
-        int8_t* strip = smem + (NBUF == 2 ? (i & 1) * STRIP : 0);
-        int8_t* srow = strip + (wm * 32 + ml) * RS;
+        const int row = m0 + wm * TM * 32 + i * 32 + ml;
+        const bool rowok = row < g.M;
         const float rs = rsr[i];
+        if constexpr (EPI == HERO_EPI_RAW_I32) {                  // 16 bytes per group: stored as they are
+            if (rowok) {
 #pragma unroll
-        for (int q = 0; q < TN * 4; ++q) {
-            const int j = q >> 2, gq = q & 3;
-            const int nl = wn * TN * 32 + j * 32 + gq * 8 + hh * 4;         // column inside the tile
-            if (EPI == HERO_EPI_RAW_I32) {
-                v4i o = {acc[i][j][4 * gq], acc[i][j][4 * gq + 1], acc[i][j][4 * gq + 2], acc[i][j][4 * gq + 3]};
-                *reinterpret_cast<v4i*>(srow + nl * 4) = o;
-                continue;
-            }
-            float y[4];
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                float v = (float)acc[i][j][4 * gq + t];
-                if (has_rs) v = v * rs;
-                v = fmaf(v, cs[q][t], bs[q][t]);
-                if (EPI == HERO_EPI_DEQUANT_GELU || EPI == HERO_EPI_GELU_REQUANT) v = gelu_erf(v);
-                y[t] = v;
-            }
-            if (EPI == HERO_EPI_REQUANT) {
-                *reinterpret_cast<uint32_t*>(srow + nl) = quant4_sat(y[0], y[1], y[2], y[3]);
-            } else if (EPI == HERO_EPI_GELU_REQUANT) {
-                // GELU^quant is in the +-1 LSB class (fp32 GELU vs the definition's fp64), so the
-                // division by S_a[j] is a multiplication by its reciprocal
-                *reinterpret_cast<uint32_t*>(srow + nl) =
-                    quant4_sat(y[0] * os[q][0], y[1] * os[q][1], y[2] * os[q][2], y[3] * os[q][3]);
-            } else if (FUSE_RES) {
-                v4f o = {y[0], y[1], y[2], y[3]};
-                *reinterpret_cast<v4f*>(srow + nl * 4) = o;
-            } else {
-                uint32_t h0 = f32_to_hp<CDT>(y[0]), h1 = f32_to_hp<CDT>(y[1]), h2 = f32_to_hp<CDT>(y[2]), h3 = f32_to_hp<CDT>(y[3]);
-                v2i o = {(int)(h0 | (h1 << 16)), (int)(h2 | (h3 << 16))};
-                *reinterpret_cast<v2i*>(srow + nl * 2) = o;
-            }
-        }
-        __syncthreads();
-        // ---- strip -> HBM
-#pragma unroll
-        for (int idx = tid; idx < WM * 32 * CH; idx += NT) {
-            const int row = idx / CH, c = idx % CH;
-            const int mg = m0 + (row >> 5) * TM * 32 + i * 32 + (row & 31);
-            const int8_t* sp = strip + row * RS + c * 16;
-            if constexpr (FUSE_RES) {               // 4 fp32 values + 4 residual values -> 4 x 16-bit
-                const int n = n0 + c * 4;
-                if (!interior && (mg >= g.M || n >= g.N)) continue;
-                v4f y = *reinterpret_cast<const v4f*>(sp);
-                const uint16_t* rp = (const uint16_t*)g.residual + (int64_t)mg * g.ldr + n;
-                uint16_t* cp = (uint16_t*)g.C + (int64_t)mg * g.ldc + n;
-                if (interior || n + 3 < g.N) {
-                    v2i rv = *reinterpret_cast<const v2i*>(rp);
-                    uint32_t h[4];
-#pragma unroll
-                    for (int t = 0; t < 4; ++t)
-                        h[t] = f32_to_hp<CDT>(y[t] + hp_to_f32<RDT>(((uint32_t)rv[t >> 1] >> (16 * (t & 1))) & 0xffffu));
-                    v2i o = {(int)(h[0] | (h[1] << 16)), (int)(h[2] | (h[3] << 16))};
-                    *reinterpret_cast<v2i*>(cp) = o;
-                } else {
-                    for (int t = 0; t < 4; ++t)
-                        if (n + t < g.N) cp[t] = (uint16_t)f32_to_hp<CDT>(y[t] + hp_to_f32<RDT>(rp[t]));
+                for (int q = 0; q < NQ; ++q) {
+                    const int j = q >> 2, gq = q & 3, col = colw + q * 8 + hh * 4;
+                    const uint32_t d[4] = {(uint32_t)acc[i][j][4 * gq], (uint32_t)acc[i][j][4 * gq + 1],
+                                           (uint32_t)acc[i][j][4 * gq + 2], (uint32_t)acc[i][j][4 * gq + 3]};
+                    if (col < g.N) store_piece<4, 4>((int8_t*)g.C + ((int64_t)row * g.ldc + col) * 4, d, col, g.N, col + 4 <= g.N, al16);
                 }
-            } else {
-                constexpr int EPC = 16 / ES;         // elements per 16-byte chunk
-                const int n = n0 + c * EPC;
-                if (!interior && (mg >= g.M || n >= g.N)) continue;
-                int8_t* cp = (int8_t*)g.C + ((int64_t)mg * g.ldc + n) * ES;
-                v4i w = *reinterpret_cast<const v4i*>(sp);
-                if (interior) {
-                    *reinterpret_cast<v4i*>(cp) = w;
-                } else {                             // ragged edge or a 4-byte-aligned ldc: dword / element stores
+            }
+        } else {
+            float y[NQ][4];
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const int nq = n + q * (4 / ES);
-                        if (nq + (4 / ES) <= g.N) *reinterpret_cast<int*>(cp + 4 * q) = w[q];
-                        else if (ES < 4) {
-                            for (int b = 0; b < 4 / ES; ++b)
-                                if (nq + b < g.N) {
-                                    if (ES == 1) cp[4 * q + b] = (int8_t)(w[q] >> (8 * b));
-                                    else *reinterpret_cast<uint16_t*>(cp + 4 * q + 2 * b) = (uint16_t)(w[q] >> (16 * b));
-                                }
+            for (int q = 0; q < NQ; ++q) {
+                const int j = q >> 2, gq = q & 3;
+                v4f os;                                           // 1 / S_a of the group, re-read per pass (registers)
+                if (EPI == HERO_EPI_GELU_REQUANT) {
+                    int nl = wn * TN * 32 + q * 8 + hh * 4;
+                    asm volatile("" : "+v"(nl));                  // opaque: one load per pass, not one long-lived copy
+                    os = *reinterpret_cast<const v4f*>(sv + 2 * BN + nl);
+                    if (OS_RAW)                                   // the vector holds S_a itself: hardware reciprocal (1 ulp; +-1 LSB class)
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) os[t] = __builtin_amdgcn_rcpf(os[t]);
+                }
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    float v = (float)acc[i][j][4 * gq + t];
+                    if (has_rs) v = v * rs;
+                    v = fmaf(v, cs[q][t], bs[q][t]);
+                    if (EPI == HERO_EPI_DEQUANT_GELU || EPI == HERO_EPI_GELU_REQUANT) v = gelu_erf(v);
+                    // GELU^quant is in the +-1 LSB class (fp32 GELU vs the definition's fp64), so the
+                    // division by S_a[j] is a multiplication by its reciprocal
+                    if (EPI == HERO_EPI_GELU_REQUANT) v = v * os[t];
+                    y[q][t] = v;
+                }
+            }
+            if constexpr (ES == 1) {
+                uint32_t w[NQ], d[NQ];
+#pragma unroll
+                for (int q = 0; q < NQ; ++q) w[q] = quant4_sat(y[q][0], y[q][1], y[q][2], y[q][3]);
+#pragma unroll
+                for (int q = 0; q < H; ++q) swap32(w[q], w[q + H], d[2 * q], d[2 * q + 1]);
+                if (rowok && col0 < g.N) store_piece<1, NQ>((int8_t*)g.C + (int64_t)row * g.ldc + col0, d, col0, g.N, full, al16);
+            } else if constexpr (!FUSE_RES) {
+                uint32_t d[2 * NQ];
+#pragma unroll
+                for (int q = 0; q < H; ++q) {
+                    const uint32_t a0 = f32_to_hp<CDT>(y[q][0]) | (f32_to_hp<CDT>(y[q][1]) << 16);
+                    const uint32_t a1 = f32_to_hp<CDT>(y[q][2]) | (f32_to_hp<CDT>(y[q][3]) << 16);
+                    const uint32_t b0 = f32_to_hp<CDT>(y[q + H][0]) | (f32_to_hp<CDT>(y[q + H][1]) << 16);
+                    const uint32_t b1 = f32_to_hp<CDT>(y[q + H][2]) | (f32_to_hp<CDT>(y[q + H][3]) << 16);
+                    swap32(a0, b0, d[4 * q], d[4 * q + 2]);
+                    swap32(a1, b1, d[4 * q + 1], d[4 * q + 3]);
+                }
+                if (rowok && col0 < g.N) store_piece<2, 2 * NQ>((int8_t*)g.C + ((int64_t)row * g.ldc + col0) * 2, d, col0, g.N, full, al16);
+            } else {
+                // fused residual: the fp32 values change lanes, the residual is read in the stored layout
+                uint32_t z[H][8], d[2 * NQ];
+#pragma unroll
+                for (int q = 0; q < H; ++q)
+#pragma unroll
+                    for (int t = 0; t < 4; ++t)
+                        swap32(__float_as_uint(y[q][t]), __float_as_uint(y[q + H][t]), z[q][t], z[q][4 + t]);
+                if (rowok && col0 < g.N) {
+                    const uint16_t* rp = (const uint16_t*)g.residual + (int64_t)row * g.ldr + col0;
+                    const bool rl16 = (g.ldr * 2) % 16 == 0;
+#pragma unroll
+                    for (int q = 0; q < H; ++q) {
+                        uint32_t r[4];
+                        if (full && rl16) {
+                            v4i rv = *reinterpret_cast<const v4i*>(rp + 8 * q);
+                            r[0] = rv[0]; r[1] = rv[1]; r[2] = rv[2]; r[3] = rv[3];
+                        } else {
+#pragma unroll
+                            for (int k = 0; k < 4; ++k) {
+                                const int c = col0 + 8 * q + 2 * k;
+                                const uint32_t e0 = c < g.N ? rp[8 * q + 2 * k] : 0, e1 = c + 1 < g.N ? rp[8 * q + 2 * k + 1] : 0;
+                                r[k] = e0 | (e1 << 16);
+                            }
+                        }
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) {
+                            const uint32_t h0 = f32_to_hp<CDT>(__uint_as_float(z[q][2 * k]) + hp_to_f32<RDT>(r[k] & 0xffffu));
+                            const uint32_t h1 = f32_to_hp<CDT>(__uint_as_float(z[q][2 * k + 1]) + hp_to_f32<RDT>(r[k] >> 16));
+                            d[4 * q + k] = h0 | (h1 << 16);
                         }
                     }
+                    store_piece<2, 2 * NQ>((int8_t*)g.C + ((int64_t)row * g.ldc + col0) * 2, d, col0, g.N, full, al16);
                 }
             }
         }
-        if (NBUF == 1 && i + 1 < TM) __syncthreads();
     }
 }
 
@@ -214,10 +253,7 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void int8_gemm_kernel(GemmArgs 
     constexpr int A_UNITS = BM * CPR / NT, B_UNITS = BN * CPR / NT;
     static_assert(BM * CPR % NT == 0 && BN * CPR % NT == 0, "tile/threads mismatch");
     static_assert(PD % 2 == 0, "prefetch distance must be even (LDS buffer parity is compile-time)");
-    constexpr int SLAB_BYTES = 2 * (BM + BN) * LDS_LD;
-    constexpr int ES = RDT >= 0 ? 4 : ElemSize<CDT>::v;
-    constexpr int STRIP_BYTES = WM * 32 * (BN * ES + 16);
-    constexpr int POOL = SLAB_BYTES > STRIP_BYTES ? SLAB_BYTES : STRIP_BYTES;
+    constexpr int POOL = 2 * (BM + BN) * LDS_LD;
     __shared__ __attribute__((aligned(16))) int8_t smem[POOL + 3 * BN * 4];
     int8_t* const sA0 = smem;                                 // [2][BM * LDS_LD]
     int8_t* const sB0 = smem + 2 * BM * LDS_LD;               // [2][BN * LDS_LD]
@@ -345,8 +381,7 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void int8_gemm_kernel(GemmArgs 
         if (kt < KT) { iteration(kt, 1, std::integral_constant<int, 1>{}); ++kt; }
         if (kt < KT) { iteration(kt, 0, std::integral_constant<int, 2>{}); ++kt; }
     }
-    // (the loop's closing barrier also guards the reuse of the slab buffers by the epilogue)
-    epilogue<BM, BN, WM, WN, EPI, CDT, RDT, POOL>(g, acc, smem, sv, rsr, m0, n0, tid);
+    epilogue_direct<BM, BN, WM, WN, EPI, CDT, RDT>(g, acc, sv, rsr, m0, n0, tid);
 }
 
 // =====================================================================================
@@ -380,9 +415,7 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void int8_gemm_dma_kernel(GemmA
     constexpr int NM = TM * TN, NFR = TM + TN;
     static_assert(NS >= 3, "ring needs at least three stages");
     static_assert(NW <= NM && NFR <= NM, "interleave plan needs one slot per memory instruction");
-    constexpr int ES = RDT >= 0 ? 4 : ElemSize<CDT>::v;
-    constexpr int STRIP_BYTES = WM * 32 * (BN * ES + 16);
-    constexpr int POOL = NS * STAGE > STRIP_BYTES ? NS * STAGE : STRIP_BYTES;
+    constexpr int POOL = NS * STAGE;
     __shared__ __attribute__((aligned(1024))) int8_t smem[POOL + 3 * BN * 4];
     float* const sv = reinterpret_cast<float*>(smem + POOL);
 
@@ -482,16 +515,15 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void int8_gemm_dma_kernel(GemmA
     }
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));                      // the redundant tail loads
     __syncthreads();
-    epilogue<BM, BN, WM, WN, EPI, CDT, RDT, POOL>(g, acc, smem, sv, rsr, m0, n0, tid);
+    epilogue_direct<BM, BN, WM, WN, EPI, CDT, RDT>(g, acc, sv, rsr, m0, n0, tid);
 }
 
 // =====================================================================================
-// Persistent variant of the direct-to-LDS kernel (large problems, 1-byte outputs): one
+// Persistent variant of the direct-to-LDS kernel (large problems): one
 // workgroup per CU walks a strided list of tiles, and the slab ring runs straight through
 // the tile boundaries, so the first slabs of the next tile (and its per-column / per-row
 // epilogue vectors, fetched by the same direct loads into a double-buffered LDS area) are
-// already resident when the epilogue of the current tile ends.  The epilogue strips have
-// LDS of their own behind the ring.  Slab addresses are a wave-uniform tile base in SGPRs
+// already resident when the epilogue of the current tile ends.  Slab addresses are a wave-uniform tile base in SGPRs
 // plus a per-lane 32-bit offset, so advancing along K is scalar arithmetic.
 // =====================================================================================
 __device__ __forceinline__ void dma16s(uint32_t voff, const int8_t* sbase, uint32_t lds_base) {
@@ -503,7 +535,7 @@ __device__ __forceinline__ void dma4s(uint32_t voff, const float* sbase, uint32_
                  :: "v"(voff), "s"(sbase), "s"(lds_base) : "memory", "m0");
 }
 
-template <int NS, int EPI, int CDT>
+template <int NS, int EPI, int CDT, int RDT>
 __global__ __launch_bounds__(512, 2) void int8_gemm_persistent_kernel(GemmArgs g) {
     constexpr int BM = 256, BN = 256, WM = 2, WN = 4;
     constexpr int NT = WM * WN * 64, NWAVE = WM * WN;
@@ -512,15 +544,12 @@ __global__ __launch_bounds__(512, 2) void int8_gemm_persistent_kernel(GemmArgs g
     constexpr int A_UNITS = A_BYTES / 16 / NT, B_UNITS = B_BYTES / 16 / NT, NW = A_UNITS + B_UNITS;
     constexpr int NM = TM * TN, NFR = TM + TN;
     static_assert(NS >= 3 && NW <= NM && NFR <= NM, "ring / interleave plan");
-    static_assert(EPI == HERO_EPI_REQUANT || EPI == HERO_EPI_GELU_REQUANT, "1-byte outputs only");
     constexpr int RING = NS * STAGE;
-    constexpr int STRIP_BYTES = WM * 32 * (BN * ElemSize<CDT>::v + 16);
     constexpr int SVF = 4 * BN;                                  // floats per vector set: column scale, bias, S_a, row scale
     static_assert(BM == BN, "the row-scale vector shares the column vectors' length");
-    static_assert(RING + STRIP_BYTES + 2 * SVF * 4 <= 160 * 1024, "LDS budget");
-    __shared__ __attribute__((aligned(1024))) int8_t smem[RING + STRIP_BYTES + 2 * SVF * 4];
-    int8_t* const strips = smem + RING;
-    float* const sv0 = reinterpret_cast<float*>(smem + RING + STRIP_BYTES);
+    static_assert(RING + 2 * SVF * 4 <= 160 * 1024, "LDS budget");
+    __shared__ __attribute__((aligned(1024))) int8_t smem[RING + 2 * SVF * 4];
+    float* const sv0 = reinterpret_cast<float*>(smem + RING);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
@@ -558,6 +587,7 @@ __global__ __launch_bounds__(512, 2) void int8_gemm_persistent_kernel(GemmArgs g
         const int ch = (wu & 3) * 64, which = wu >> 2;
         const uint32_t dst = svbase + par * SVF * 4 + ch * 4;
         const uint32_t cn = (uint32_t)min(ch + lane, g.N - 1 - n0i) * 4u, cm = (uint32_t)min(ch + lane, g.M - 1 - m0i) * 4u;
+        if (EPI == HERO_EPI_RAW_I32) return;
         if (which == 0) {
             dma4s(cn, g.b_col_scale + n0i, dst);
             if (EPI == HERO_EPI_GELU_REQUANT) dma4s(cn, g.out_col_scale + n0i, dst + 2 * BN * 4);
@@ -650,8 +680,8 @@ __global__ __launch_bounds__(512, 2) void int8_gemm_persistent_kernel(GemmArgs g
         const float* sv = sv0 + par * SVF;
         float rsr[TM];
 #pragma unroll
-        for (int i = 0; i < TM; ++i) rsr[i] = has_rs ? sv[3 * BN + wm * TM * 32 + i * 32 + ml] : 1.0f;
-        epilogue<BM, BN, WM, WN, EPI, CDT, -1, STRIP_BYTES, true>(g, acc, strips, sv, rsr, m0, n0, tid);
+        for (int i = 0; i < TM; ++i) rsr[i] = (EPI != HERO_EPI_RAW_I32 && has_rs) ? sv[3 * BN + wm * TM * 32 + i * 32 + ml] : 1.0f;
+        epilogue_direct<BM, BN, WM, WN, EPI, CDT, RDT, true>(g, acc, sv, rsr, m0, n0, tid);
         seq += nslot;
         par ^= 1;
         if (seq >= seq_end) break;
@@ -677,20 +707,18 @@ template <int EPI, int CDT, int RDT>
 hero_status launch_epi(const GemmArgs& g, hipStream_t st) {
     const char* e = getenv("HERO_GEMM_TILE");
     int cfg = e ? atoi(e) : -1;
-    GemmArgs g2;
     if (cfg < 0) cfg = ((int64_t)((g.M + 255) / 256) * ((g.N + 255) / 256) >= 96) ? 1 : 0;
-    if constexpr (CDT == HERO_I8) {
-        // persistent form: 1-byte outputs, K long enough that the ring never runs more than one tile ahead,
-        // 32-bit per-lane offsets (256 rows of lda / ldb bytes)
-        if ((cfg == 7 || (cfg == 1 && !e && EPI == HERO_EPI_REQUANT)) && g.K >= 4 * BK && g.lda < (1 << 24) && g.ldb < (1 << 24)) {
-            g2 = g;
-            g2.ntm = (g.M + 255) / 256; g2.ntn = (g.N + 255) / 256;
-            const int64_t tiles = (int64_t)g2.ntm * g2.ntn;
-            g2.per_xcd = (int)((tiles + NUM_XCD - 1) / NUM_XCD);
-            const int nslot = g2.per_xcd < 32 ? g2.per_xcd : 32;      // 32 CUs per XCD, one workgroup each
-            hipLaunchKernelGGL((int8_gemm_persistent_kernel<4, EPI, CDT>), dim3((unsigned)(nslot * NUM_XCD)), dim3(512), 0, st, g2);
-            return hero_launch_status();
-        }
+    // persistent form of the 256x256 kernel: K long enough that the slab ring never runs more than one tile
+    // ahead, 32-bit per-lane offsets (256 rows of lda / ldb bytes)
+    if ((cfg == 7 || (cfg == 1 && !e)) && g.K >= 4 * BK && g.lda < (1 << 24) && g.ldb < (1 << 24)) {
+        GemmArgs gp = g;
+        gp.ntm = (g.M + 255) / 256; gp.ntn = (g.N + 255) / 256;
+        const int64_t tiles = (int64_t)gp.ntm * gp.ntn;
+        if (tiles > 0x7fffff00LL) return HERO_ERR_SHAPE;
+        gp.per_xcd = (int)((tiles + NUM_XCD - 1) / NUM_XCD);
+        const int nslot = gp.per_xcd < 32 ? gp.per_xcd : 32;          // 32 CUs per XCD, one workgroup each
+        hipLaunchKernelGGL((int8_gemm_persistent_kernel<4, EPI, CDT, RDT>), dim3((unsigned)(nslot * NUM_XCD)), dim3(512), 0, st, gp);
+        return hero_launch_status();
     }
     if (cfg == 1) return launch_grid(g, 256, 256, 512, int8_gemm_dma_kernel<256, 256, 2, 4, 4, 2, EPI, CDT, RDT>, st);
     if (cfg == 2 || (cfg < 0 && g.M <= 64))     // skinny M (decode): more, smaller tiles stream the weights from more CUs

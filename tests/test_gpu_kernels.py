@@ -165,10 +165,11 @@ def test_gemm_gelu_epilogues(hero, M, N, K):
 
 
 @pytest.mark.parametrize("M,N,K", [(2500, 2600, 320), (2560, 2560, 256), (4000, 1700, 704)])
-def test_gemm_many_tiles_requant_ragged_edges(hero, M, N, K, monkeypatch):
+def test_gemm_many_tiles_ragged_edges(hero, M, N, K, monkeypatch):
     """Enough 256 x 256 tiles for the large-problem kernels (the persistent one included: several tiles
     per workgroup, ragged last row and column panels, K of 4 / 5 / 11 slabs), strided operands and output;
-    REQUANT is bit-exact, GELU^quant in the +-1 LSB class, with and without the optional vectors."""
+    every epilogue: REQUANT / DEQUANT / residual / raw bit-exact, GELU^quant in the +-1 LSB class, with and
+    without the optional vectors."""
     c = synth.gemm_case(700 + M, M, K + 64, N)
     A_full, rs, cs, bias = c["A"], c["a_row_scale"], c["b_col_scale"], c["bias"]
     A, Bt = A_full[:, :K], c["Bt"][:, :K]
@@ -182,6 +183,11 @@ def test_gemm_many_tiles_requant_ragged_edges(hero, M, N, K, monkeypatch):
     g = O.int8_gemm(A, Bt, a_row_scale=rs, b_col_scale=csg, bias=bias, epi=O.EPI_DEQUANT_GELU, c_dt=O.F32)
     s_a = (np.abs(g).max(axis=0) / 127).astype(np.float32)
     ref_g = O.int8_gemm(A, Bt, a_row_scale=rs, b_col_scale=csg, bias=bias, epi=O.EPI_GELU_REQUANT, out_col_scale=s_a, c_dt=O.I8)
+    ref_raw = O.gemm_i32(A, Bt)
+    ref_f16 = O.int8_gemm(A, Bt, a_row_scale=rs, b_col_scale=cs, bias=bias, epi=O.EPI_DEQUANT, c_dt=O.F16)
+    res = O.f32_to_bf16(synth.rng(11).standard_normal((M, N)).astype(np.float32))
+    ref_res = O.int8_gemm(A, Bt, a_row_scale=rs, b_col_scale=cs, bias=bias, residual=res, res_dt=O.BF16,
+                          epi=O.EPI_DEQUANT, c_dt=O.BF16)
     for tile in (None, "1", "7"):                  # default choice, one tile per workgroup, persistent
         if tile is None:
             monkeypatch.delenv("HERO_GEMM_TILE", raising=False)
@@ -196,6 +202,12 @@ def test_gemm_many_tiles_requant_ragged_edges(hero, M, N, K, monkeypatch):
         got = hero.hero_int8_gemm(dA, dB, dev(rs), dev(csg), dev(bias), epi=HB.EPI_GELU_REQUANT,
                                   out_col_scale=dev(s_a), out_dtype=torch.int8)
         assert_codes(to_np(got), ref_g, f"gelu requant tile={tile}")
+        assert_exact(to_np(hero.hero_int8_gemm(dA, dB)), ref_raw, f"raw tile={tile}")
+        got = hero.hero_int8_gemm(dA, dB, dev(rs), dev(cs), dev(bias), epi=HB.EPI_DEQUANT, out_dtype=torch.float16)
+        assert_exact(to_np(got), ref_f16, f"dequant f16 tile={tile}")
+        dres = dev(res)
+        got = hero.hero_int8_gemm(dA, dB, dev(rs), dev(cs), dev(bias), residual=dres, epi=HB.EPI_DEQUANT, C_out=dres)
+        assert_exact(to_np(got), ref_res, f"dequant + residual in place tile={tile}")
 
 
 def test_gemm_strided_operands_and_errors(hero):
