@@ -702,7 +702,8 @@ hero_status launch_grid(GemmArgs g, int BM, int BN, int threads, K kernel, hipSt
 
 // Tile choice: the 256x256 direct-to-LDS kernel once the grid has enough tiles to fill about half
 // of the 256 CUs; the 128x128 register-staged kernel otherwise (small, skinny or ragged problems).
-// HERO_GEMM_TILE (0 / 1 / 2) overrides the choice for tuning runs.
+// HERO_GEMM_TILE overrides the choice for tuning runs and tests: 0 = 128x128, 1 = 256x256 one tile per
+// workgroup, 2 = 64x64, 7 = 256x256 persistent.
 template <int EPI, int CDT, int RDT>
 hero_status launch_epi(const GemmArgs& g, hipStream_t st) {
     const char* e = getenv("HERO_GEMM_TILE");
