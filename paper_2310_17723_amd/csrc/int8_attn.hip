@@ -48,11 +48,16 @@ __global__ __launch_bounds__(256) void int8_attn_kernel(AttnArgs a) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int hh = lane >> 5, ql = lane & 31;
     // Workgroups go round-robin to the 8 XCDs; all query blocks of one (batch, head) are sent to
-    // the SAME XCD, back to back, so its K / V stream hits that XCD's L2 after the first block.
+    // the SAME XCD, back to back, so its K / V stream hits that XCD's L2 after the first block, and
+    // so are the HG = 128 / DH neighbouring heads whose K / V rows share 128-byte cache lines with it
+    // in the packed [token][head][channel] layout (otherwise each XCD would fetch whole lines to use
+    // a fraction of them).
+    constexpr int HG = DH >= 128 ? 1 : 128 / DH;
     const int nqb = (a.Sq + BQ - 1) / BQ;
-    const int slot = blockIdx.x / 8, bh = (slot / nqb) * 8 + (blockIdx.x % 8);
+    const int slot = blockIdx.x / 8, grp = (slot / (HG * nqb)) * 8 + (blockIdx.x % 8), within = slot % (HG * nqb);
+    const int bh = grp * HG + within / nqb;
     if (bh >= a.B * a.H) return;
-    const int b = bh / a.H, h = bh % a.H, q0 = (slot % nqb) * BQ;
+    const int b = bh / a.H, h = bh % a.H, q0 = (within % nqb) * BQ;
     const int len = a.kv_len ? min(max(a.kv_len[b], 0), a.Skv) : a.Skv;
     const int shift = len - a.Sq;                       // causal: key k visible iff k <= i + shift
     const int qi = q0 + wave * 32 + ql;                 // this lane's query
@@ -340,9 +345,10 @@ __global__ void zero_rows_kernel(int8_t* out, int64_t bytes) {
 
 template <int DH>
 hero_status launch(const AttnArgs& a, hero_dtype out_dt, hipStream_t st) {
-    const int64_t nqb = (a.Sq + BQ - 1) / BQ, groups = ((int64_t)a.B * a.H + 7) / 8;
-    if (groups * 8 * nqb > 0x7fffffffLL) return HERO_ERR_SHAPE;
-    dim3 grid((unsigned)(groups * 8 * nqb)), block(256);
+    constexpr int HG = DH >= 128 ? 1 : 128 / DH;               // heads per workgroup group (see the kernel)
+    const int64_t nqb = (a.Sq + BQ - 1) / BQ, hgroups = ((int64_t)a.B * a.H + HG - 1) / HG, rounds = (hgroups + 7) / 8;
+    if (rounds * 8 * HG * nqb > 0x7fffffffLL) return HERO_ERR_SHAPE;
+    dim3 grid((unsigned)(rounds * 8 * HG * nqb)), block(256);
     if (out_dt == HERO_I8) hipLaunchKernelGGL((int8_attn_kernel<DH, HERO_I8>), grid, block, 0, st, a);
     else if (out_dt == HERO_BF16) hipLaunchKernelGGL((int8_attn_kernel<DH, HERO_BF16>), grid, block, 0, st, a);
     else hipLaunchKernelGGL((int8_attn_kernel<DH, HERO_F16>), grid, block, 0, st, a);
