@@ -29,8 +29,8 @@ sys.path.insert(0, ROOT)
 # (two runs, scaled by the same counters on a plain copy of known size); the summaries are in
 # profiles/.  Keyed by (M, N, K) of the FC1 GeMM^quant; anything else reports null.
 MEASURED_TRAFFIC = {
-    # profiles/bert-large_kernels_hbm_traffic_pmc.txt: fetch 49653.7 KiB x 2.00 (copy calibration), write 65536 KiB x 1.00
-    (16384, 4096, 1024): {"fetch_bytes": 101690778, "write_bytes": 67108864},
+    # profiles/bert-large_kernels_hbm_traffic_pmc.txt: fetch 45550.1 KiB x 2.00 (copy calibration), write 65548.9 KiB x 1.00
+    (16384, 4096, 1024): {"fetch_bytes": 93286605, "write_bytes": 67122074},
 }
 
 PEAK_INT8_TOPS = 5000.0      # MI355X dense INT8 MFMA, TOP/s
@@ -160,7 +160,7 @@ def fc1_roofline(hero, shape, seed, iters=20):
     ms = time_gpu(fn, iters)
     ops = 2.0 * M * N * K
     tops = ops / (ms * 1e-3) / 1e12
-    return {"bound": "mfma", "kernel": "int8_gemm_kernel<GELU_REQUANT> (FC1)", "shape_mnk": [M, N, K],
+    return {"bound": "mfma", "kernel": "int8_gemm_persistent_kernel<GELU_REQUANT> (FC1)", "shape_mnk": [M, N, K],
             "achieved": round(tops, 2), "peak": PEAK_INT8_TOPS, "unit": "TOP/s", "frac": round(tops / PEAK_INT8_TOPS, 4),
             "avg_launch_us": round(ms * 1e3, 2), "ops_per_launch": ops,
             "algorithmic_bytes": M * K + N * K + M * N + 4 * (M + 3 * N),
