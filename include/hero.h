@@ -67,7 +67,8 @@ const char* hero_strerror(hero_status s);
  *            token (then beta must be NULL too).  beta may be NULL (= 0).
  *   y_q [M,D] int8 and y_scale[M] f32 are always written.
  *   y_hp     optional [M,D] copy of y in y_hp_dt (HERO_BF16/HERO_F16) for a BF16 consumer.
- * Constraints: D % 16 == 0, 16 <= D <= 16384.  M == 0 is a no-op.
+ * Constraints: D % 16 == 0, 16 <= D <= 8192 for INT8 x, <= 4096 for 16-bit x (a row lives in one
+ * wavefront's registers; HERO_ERR_UNSUPPORTED beyond).  M == 0 is a no-op.
  * Statistics are fp32 (mean, then variance about the mean) with the row held in registers.
  */
 hero_status hero_ln_quant(const void* x, hero_dtype x_dt, const float* x_row_scale,
