@@ -106,6 +106,27 @@ hero_status hero_int8_gemm(const int8_t* A, int64_t lda, const float* a_row_scal
                            void* C, hero_dtype c_dt, int64_t ldc,
                            int64_t M, int64_t N, int64_t K, void* stream);
 
+/* The same GeMM^quant (Sec. 2.1, 2.2.2, 2.2.3; identical arguments, results and constraints) with a
+ * caller-owned scratch buffer for skinny problems (M <= 128, the decode step): K is split over
+ * several workgroups per output tile so that every CU streams a share of the weights; the exact
+ * int32 partial sums go through the scratch and a second kernel adds them and applies the
+ * epilogue, so the result does not depend on the split.
+ *   hero_int8_gemm_workspace_bytes(M, N, K): bytes of scratch this shape can use (0: it would not
+ *       split; any buffer, or none, is accepted then).
+ *   workspace  device memory, 256-byte aligned (else HERO_ERR_WORKSPACE), at least that many bytes
+ *       (NULL or smaller: the call runs like hero_int8_gemm).  Pure scratch: no initialisation is
+ *       needed and nothing is kept between calls, so consecutive calls ON ONE STREAM can share it;
+ *       calls that may overlap on the GPU (different streams) need buffers of their own.
+ */
+size_t hero_int8_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
+hero_status hero_int8_gemm_ws(const int8_t* A, int64_t lda, const float* a_row_scale,
+                              const int8_t* Bt, int64_t ldb, const float* b_col_scale,
+                              const float* bias, const void* residual, hero_dtype res_dt, int64_t ldr,
+                              hero_epilogue epi, const float* out_col_scale,
+                              void* C, hero_dtype c_dt, int64_t ldc,
+                              int64_t M, int64_t N, int64_t K,
+                              void* workspace, size_t workspace_bytes, void* stream);
+
 /* INT8 attention: QK^T, Softmax^quant, PV.  Paper: Sec. 2.2.2 quantized flow
  *   A = S_q S_k X_q,int8 X_k,int8^T / sqrt(d)   (not quantized; d~ = S_q S_k / sqrt(d))
  *   S_p P_int8 = Softmax^quant(A)               (unsigned codes: softmax has no negatives)

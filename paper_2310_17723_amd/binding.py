@@ -44,6 +44,9 @@ SYMBOLS = {
     "hero_build_arch": (C.c_char_p, []),
     "hero_ln_quant": (i32, [vp, i32, vp, vp, i32, vp, vp, vp, f32, i64, i64, vp, vp, vp, i32, vp]),
     "hero_int8_gemm": (i32, [vp, i64, vp, vp, i64, vp, vp, vp, i32, i64, i32, vp, vp, i32, i64, i64, i64, i64, vp]),
+    "hero_int8_gemm_workspace_bytes": (C.c_size_t, [i64, i64, i64]),
+    "hero_int8_gemm_ws": (i32, [vp, i64, vp, vp, i64, vp, vp, vp, i32, i64, i32, vp, vp, i32, i64, i64, i64, i64,
+                                vp, C.c_size_t, vp]),
     "hero_int8_attn": (i32, [vp, C.POINTER(i64), vp, C.POINTER(i64), vp, C.POINTER(i64), i64, i64, i64, i64, i64,
                              f32, f32, vp, i32, i32, vp, vp, i32, i64, vp]),
     "hero_layer_workspace_bytes": (C.c_size_t, [C.POINTER(LayerDesc), i64, i64]),
@@ -113,22 +116,32 @@ class Hero:
 
     # ------------------------------------------------------------------ GeMM^quant
     def hero_int8_gemm(self, A, Bt, a_row_scale=None, b_col_scale=None, bias=None, residual=None,
-                       epi=EPI_RAW_I32, out_col_scale=None, out_dtype=torch.int32, C_out=None, stream=None):
-        """A [M,K] int8, Bt [N,K] int8 (row strides may exceed K).  Returns C [M,N]."""
+                       epi=EPI_RAW_I32, out_col_scale=None, out_dtype=torch.int32, C_out=None, stream=None,
+                       workspace=None):
+        """A [M,K] int8, Bt [N,K] int8 (row strides may exceed K).  Returns C [M,N].
+        workspace: optional zero-filled uint8 tensor (hero_int8_gemm_workspace_bytes) -> hero_int8_gemm_ws."""
         M, K = A.shape
         N = Bt.shape[0]
         assert Bt.shape[1] == K and A.stride(1) == 1 and Bt.stride(1) == 1
         if C_out is None:
             C_out = torch.empty((M, N), dtype=out_dtype, device=A.device)
         assert C_out.stride(1) == 1
-        st = self.lib.hero_int8_gemm(_ptr(A), A.stride(0) if M > 1 else max(K, A.stride(0)), _ptr(a_row_scale),
-                                     _ptr(Bt), Bt.stride(0) if N > 1 else max(K, Bt.stride(0)), _ptr(b_col_scale),
-                                     _ptr(bias), _ptr(residual),
-                                     _DT[residual.dtype] if residual is not None else 0,
-                                     residual.stride(0) if residual is not None else 0, int(epi), _ptr(out_col_scale),
-                                     _ptr(C_out), _DT[C_out.dtype], C_out.stride(0), M, N, K, _stream(stream))
+        args = (_ptr(A), A.stride(0) if M > 1 else max(K, A.stride(0)), _ptr(a_row_scale),
+                _ptr(Bt), Bt.stride(0) if N > 1 else max(K, Bt.stride(0)), _ptr(b_col_scale),
+                _ptr(bias), _ptr(residual),
+                _DT[residual.dtype] if residual is not None else 0,
+                residual.stride(0) if residual is not None else 0, int(epi), _ptr(out_col_scale),
+                _ptr(C_out), _DT[C_out.dtype], C_out.stride(0), M, N, K)
+        if workspace is None:
+            st = self.lib.hero_int8_gemm(*args, _stream(stream))
+        else:
+            st = self.lib.hero_int8_gemm_ws(*args, _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                            _stream(stream))
         self._check(st)
         return C_out
+
+    def hero_int8_gemm_workspace_bytes(self, M, N, K) -> int:
+        return int(self.lib.hero_int8_gemm_workspace_bytes(M, N, K))
 
     # ------------------------------------------------------------------ INT8 attention
     def hero_int8_attn(self, q, k, v, qk_scale, p_scale, out_col_scale, out_scale_is_scalar=False,

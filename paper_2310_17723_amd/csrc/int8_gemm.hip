@@ -39,6 +39,9 @@ struct GemmArgs {
     void* C; int64_t ldc;
     int M, N, K;
     int ntm, ntn, per_xcd;      // tile grid and tiles per XCD
+    // split-K (skinny M): blockIdx.y picks a range of kslabs slabs and writes raw int32 partial sums
+    // to its own [M][ldc] plane of C (plane stride M * ldc elements); a second kernel adds the planes
+    int ksplit, kslabs;
 };
 
 template <int CDT> struct ElemSize { static constexpr int v = CDT == HERO_I32 ? 4 : (CDT == HERO_I8 ? 1 : 2); };
@@ -245,7 +248,7 @@ __device__ __forceinline__ void epilogue_direct(const GemmArgs& g, v16i (&acc)[B
 // Register-staged main loop (small / ragged problems).  BK-byte slabs, double-buffered in
 // LDS with an 80-byte padded row stride, PD slabs in flight in registers.
 // =====================================================================================
-template <int BM, int BN, int WM, int WN, int PD, int MINW, int EPI, int CDT, int RDT>
+template <int BM, int BN, int WM, int WN, int PD, int MINW, int EPI, int CDT, int RDT, bool SPLITK = false>
 __global__ __launch_bounds__(WM * WN * 64, MINW) void int8_gemm_kernel(GemmArgs g) {
     constexpr int NT = WM * WN * 64;
     constexpr int CPR = BK / 16;                              // 16-byte chunks per slab row
@@ -263,7 +266,9 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void int8_gemm_kernel(GemmArgs 
     const int wm = wave / WN, wn = wave % WN;
     int m0, n0;
     if (!tile_origin<BM, BN>(g, m0, n0)) return;
-    const int KT = g.K / BK;
+    // this workgroup's slabs: all of K, or the blockIdx.y-th range of kslabs slabs (never empty)
+    const int kt0 = SPLITK ? (int)blockIdx.y * g.kslabs : 0;
+    const int KT = SPLITK ? min(g.kslabs, g.K / BK - kt0) : g.K / BK;
 
     stage_col_vectors<BN, NT, EPI>(g, sv, n0, tid);
     float rsr[TM];
@@ -278,12 +283,12 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void int8_gemm_kernel(GemmArgs 
 #pragma unroll
     for (int u = 0; u < A_UNITS; ++u) {
         int idx = tid + u * NT, row = idx / CPR, ch = idx % CPR;
-        pa[u] = g.A + (int64_t)min(m0 + row, g.M - 1) * g.lda + ch * 16;          // clamp: ragged M
+        pa[u] = g.A + (int64_t)min(m0 + row, g.M - 1) * g.lda + ch * 16 + (int64_t)kt0 * BK;   // clamp: ragged M
     }
 #pragma unroll
     for (int u = 0; u < B_UNITS; ++u) {
         int idx = tid + u * NT, row = idx / CPR, ch = idx % CPR;
-        pb[u] = g.Bt + (int64_t)min(n0 + row, g.N - 1) * g.ldb + ch * 16;
+        pb[u] = g.Bt + (int64_t)min(n0 + row, g.N - 1) * g.ldb + ch * 16 + (int64_t)kt0 * BK;
     }
     const int lds_unit0 = (tid / CPR) * LDS_LD + (tid % CPR) * 16;                // + u * (NT / CPR) * LDS_LD
     v4i ra[PD][A_UNITS], rb[PD][B_UNITS];
@@ -380,6 +385,13 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void int8_gemm_kernel(GemmArgs 
     if constexpr (PD >= 4) {
         if (kt < KT) { iteration(kt, 1, std::integral_constant<int, 1>{}); ++kt; }
         if (kt < KT) { iteration(kt, 0, std::integral_constant<int, 2>{}); ++kt; }
+    }
+    if constexpr (SPLITK) {
+        static_assert(EPI == HERO_EPI_RAW_I32, "split-K writes raw partial sums");
+        GemmArgs gp = g;
+        gp.C = (int32_t*)g.C + (int64_t)blockIdx.y * g.M * g.ldc;
+        epilogue_direct<BM, BN, WM, WN, EPI, CDT, RDT>(gp, acc, sv, rsr, m0, n0, tid);
+        return;
     }
     epilogue_direct<BM, BN, WM, WN, EPI, CDT, RDT>(g, acc, sv, rsr, m0, n0, tid);
 }
@@ -689,6 +701,107 @@ __global__ __launch_bounds__(512, 2) void int8_gemm_persistent_kernel(GemmArgs g
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));                      // the redundant tail loads
 }
 
+// Split-K for skinny M (M <= 128: the weights are streamed once and too few tiles exist to do that from
+// every CU).  Pass 1: the register-staged kernel with a second grid dimension over K ranges writes raw int32
+// partial sums, one [M][ldp] plane per range, into the caller's scratch.  Pass 2 (splitk_reduce_kernel) adds
+// the planes and runs the epilogue.  Integer sums commute and the epilogue arithmetic is the same, in the
+// same order, as in the one-pass kernels, so the results are identical; the kernel boundary is the only
+// synchronisation (device-wide fences inside one kernel measured 4x slower than no split at all).
+struct SplitK { int BM, BN, ksplit, kslabs; int64_t ldp; size_t bytes; };
+inline SplitK splitk_plan(int64_t M, int64_t N, int64_t K) {
+    SplitK p = {0, 0, 1, 0, 0, 0};
+    if (M <= 0 || N <= 0 || M > 128 || K % BK != 0) return p;
+    p.BM = p.BN = M <= 64 ? 64 : 128;
+    const int64_t tiles = ((M + p.BM - 1) / p.BM) * ((N + p.BN - 1) / p.BN), kt = K / BK;
+    if (tiles >= 384 || kt < 8) return p;
+    int64_t want = (512 + tiles - 1) / tiles;                         // about two workgroups per CU
+    if (want > 16) want = 16;
+    int64_t kslabs = (kt + want - 1) / want;
+    if (kslabs < 4) kslabs = 4;
+    p.kslabs = (int)kslabs;
+    p.ksplit = (int)((kt + kslabs - 1) / kslabs);                     // every range non-empty
+    if (p.ksplit <= 1) { p.ksplit = 1; return p; }
+    p.ldp = (N + 3) & ~(int64_t)3;
+    p.bytes = (size_t)p.ksplit * M * p.ldp * 4;
+    return p;
+}
+
+// Pass 2 of split-K: one thread per 4 consecutive columns of a row.
+template <int EPI, int CDT, int RDT>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmArgs g, const int32_t* part, int64_t ldp) {
+    constexpr int ES = ElemSize<CDT>::v;
+    const int nq = (g.N + 3) / 4;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (int64_t)g.M * nq) return;
+    const int m = (int)(idx / nq), n = (int)(idx % nq) * 4;
+    v4i a = {0, 0, 0, 0};
+    for (int ks = 0; ks < g.ksplit; ++ks)
+        a += *reinterpret_cast<const v4i*>(part + ((int64_t)ks * g.M + m) * ldp + n);
+    const int nv = min(4, g.N - n);                                    // valid columns
+    uint32_t e[4];                                                     // outputs as element bit patterns
+    if constexpr (EPI == HERO_EPI_RAW_I32) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) e[t] = (uint32_t)a[t];
+    } else {
+        const float rs = g.a_row_scale ? g.a_row_scale[m] : 1.0f;
+        float y[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int nn = min(n + t, g.N - 1);
+            float v = (float)a[t];
+            if (g.a_row_scale) v = v * rs;
+            v = fmaf(v, g.b_col_scale[nn], g.bias ? g.bias[nn] : 0.0f);
+            if (EPI == HERO_EPI_DEQUANT_GELU || EPI == HERO_EPI_GELU_REQUANT) v = gelu_erf(v);
+            if (EPI == HERO_EPI_GELU_REQUANT) v = v * __fdiv_rn(1.0f, g.out_col_scale[nn]);
+            if (RDT >= 0 && t < nv) v += hp_to_f32<RDT>(((const uint16_t*)g.residual)[(int64_t)m * g.ldr + n + t]);
+            y[t] = v;
+        }
+        if constexpr (ES == 1) {
+            const uint32_t w = quant4_sat(y[0], y[1], y[2], y[3]);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) e[t] = (w >> (8 * t)) & 0xffu;
+        } else {
+#pragma unroll
+            for (int t = 0; t < 4; ++t) e[t] = f32_to_hp<CDT>(y[t]);
+        }
+    }
+    int8_t* cp = (int8_t*)g.C + ((int64_t)m * g.ldc + n) * ES;
+    if (nv == 4) {
+        if constexpr (ES == 1) *reinterpret_cast<uint32_t*>(cp) = e[0] | (e[1] << 8) | (e[2] << 16) | (e[3] << 24);
+        else if constexpr (ES == 2) *reinterpret_cast<v2i*>(cp) = v2i{(int)(e[0] | (e[1] << 16)), (int)(e[2] | (e[3] << 16))};
+        else *reinterpret_cast<v4i*>(cp) = v4i{(int)e[0], (int)e[1], (int)e[2], (int)e[3]};
+    } else {
+        for (int t = 0; t < nv; ++t) {
+            if (ES == 1) cp[t] = (int8_t)e[t];
+            else if (ES == 2) reinterpret_cast<uint16_t*>(cp)[t] = (uint16_t)e[t];
+            else reinterpret_cast<uint32_t*>(cp)[t] = e[t];
+        }
+    }
+}
+
+template <int EPI, int CDT, int RDT>
+hero_status launch_splitk(const GemmArgs& g, const SplitK& p, void* ws, hipStream_t st) {
+    GemmArgs g1 = g;                                                   // pass 1: raw partial planes in the scratch
+    g1.a_row_scale = nullptr; g1.b_col_scale = nullptr; g1.bias = nullptr; g1.residual = nullptr; g1.out_col_scale = nullptr;
+    g1.C = ws; g1.ldc = p.ldp;
+    g1.ntm = (g.M + p.BM - 1) / p.BM;
+    g1.ntn = (g.N + p.BN - 1) / p.BN;
+    const int64_t tiles = (int64_t)g1.ntm * g1.ntn;
+    g1.per_xcd = (int)((tiles + NUM_XCD - 1) / NUM_XCD);
+    g1.ksplit = p.ksplit; g1.kslabs = p.kslabs;
+    const dim3 grid((unsigned)(g1.per_xcd * NUM_XCD), (unsigned)p.ksplit);
+    if (p.BM == 64) hipLaunchKernelGGL((int8_gemm_kernel<64, 64, 2, 2, 4, 2, HERO_EPI_RAW_I32, HERO_I32, -1, true>), grid, dim3(256), 0, st, g1);
+    else hipLaunchKernelGGL((int8_gemm_kernel<128, 128, 2, 2, 2, 2, HERO_EPI_RAW_I32, HERO_I32, -1, true>), grid, dim3(256), 0, st, g1);
+    hero_status s1 = hero_launch_status();
+    if (s1 != HERO_OK) return s1;
+    GemmArgs g2 = g;                                                   // pass 2: sum of the planes + epilogue
+    g2.ksplit = p.ksplit; g2.kslabs = p.kslabs;
+    const int64_t threads = (int64_t)g.M * ((g.N + 3) / 4);
+    hipLaunchKernelGGL((splitk_reduce_kernel<EPI, CDT, RDT>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st,
+                       g2, (const int32_t*)ws, p.ldp);
+    return hero_launch_status();
+}
+
 template <typename K>
 hero_status launch_grid(GemmArgs g, int BM, int BN, int threads, K kernel, hipStream_t st) {
     g.ntm = (g.M + BM - 1) / BM;
@@ -705,10 +818,14 @@ hero_status launch_grid(GemmArgs g, int BM, int BN, int threads, K kernel, hipSt
 // HERO_GEMM_TILE overrides the choice for tuning runs and tests: 0 = 128x128, 1 = 256x256 one tile per
 // workgroup, 2 = 64x64, 7 = 256x256 persistent.
 template <int EPI, int CDT, int RDT>
-hero_status launch_epi(const GemmArgs& g, hipStream_t st) {
+hero_status launch_epi(const GemmArgs& g, void* ws, size_t ws_bytes, hipStream_t st) {
     const char* e = getenv("HERO_GEMM_TILE");
     int cfg = e ? atoi(e) : -1;
-    if (cfg < 0) cfg = ((int64_t)((g.M + 255) / 256) * ((g.N + 255) / 256) >= 96) ? 1 : 0;
+    if (cfg < 0 && ws) {                                               // skinny M with a workspace: split K
+        const SplitK p = splitk_plan(g.M, g.N, g.K);
+        if (p.ksplit > 1 && ws_bytes >= p.bytes) return launch_splitk<EPI, CDT, RDT>(g, p, ws, st);
+    }
+    if (cfg < 0) cfg = ((int64_t)((g.M + 255) / 256) * ((g.N + 255) / 256) >= 96) ? 1 : (g.M <= 64 ? 2 : 0);
     // persistent form of the 256x256 kernel: K long enough that the slab ring never runs more than one tile
     // ahead, 32-bit per-lane offsets (256 rows of lda / ldb bytes)
     if ((cfg == 7 || (cfg == 1 && !e)) && g.K >= 4 * BK && g.lda < (1 << 24) && g.ldb < (1 << 24)) {
@@ -722,12 +839,16 @@ hero_status launch_epi(const GemmArgs& g, hipStream_t st) {
         return hero_launch_status();
     }
     if (cfg == 1) return launch_grid(g, 256, 256, 512, int8_gemm_dma_kernel<256, 256, 2, 4, 4, 2, EPI, CDT, RDT>, st);
-    if (cfg == 2 || (cfg < 0 && g.M <= 64))     // skinny M (decode): more, smaller tiles stream the weights from more CUs
+    if (cfg == 2)                               // skinny M (decode): more, smaller tiles stream the weights from more CUs
         return launch_grid(g, 64, 64, 256, int8_gemm_kernel<64, 64, 2, 2, 2, 2, EPI, CDT, RDT>, st);
     return launch_grid(g, 128, 128, 256, int8_gemm_kernel<128, 128, 2, 2, 2, 2, EPI, CDT, RDT>, st);
 }
 
 }  // namespace
+
+extern "C" size_t hero_int8_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K) {
+    return splitk_plan(M, N, K).bytes;
+}
 
 extern "C" hero_status hero_int8_gemm(const int8_t* A, int64_t lda, const float* a_row_scale,
                                       const int8_t* Bt, int64_t ldb, const float* b_col_scale,
@@ -735,6 +856,18 @@ extern "C" hero_status hero_int8_gemm(const int8_t* A, int64_t lda, const float*
                                       hero_epilogue epi, const float* out_col_scale,
                                       void* C, hero_dtype c_dt, int64_t ldc,
                                       int64_t M, int64_t N, int64_t K, void* stream) {
+    return hero_int8_gemm_ws(A, lda, a_row_scale, Bt, ldb, b_col_scale, bias, residual, res_dt, ldr, epi, out_col_scale,
+                             C, c_dt, ldc, M, N, K, nullptr, 0, stream);
+}
+
+extern "C" hero_status hero_int8_gemm_ws(const int8_t* A, int64_t lda, const float* a_row_scale,
+                                         const int8_t* Bt, int64_t ldb, const float* b_col_scale,
+                                         const float* bias, const void* residual, hero_dtype res_dt, int64_t ldr,
+                                         hero_epilogue epi, const float* out_col_scale,
+                                         void* C, hero_dtype c_dt, int64_t ldc,
+                                         int64_t M, int64_t N, int64_t K,
+                                         void* workspace, size_t workspace_bytes, void* stream) {
+    if (workspace && ((uintptr_t)workspace & 255)) return HERO_ERR_WORKSPACE;
     if (M < 0 || N < 0 || K <= 0) return HERO_ERR_SHAPE;
     if (M > 0x7fffffffLL || N > 0x7fffffffLL || K > 0x7fffffffLL) return HERO_ERR_SHAPE;
     if (K % KMULT != 0) return HERO_ERR_UNSUPPORTED;
@@ -763,20 +896,21 @@ extern "C" hero_status hero_int8_gemm(const int8_t* A, int64_t lda, const float*
     g.A = A; g.lda = lda; g.a_row_scale = a_row_scale; g.Bt = Bt; g.ldb = ldb; g.b_col_scale = b_col_scale;
     g.bias = bias; g.residual = residual; g.ldr = ldr; g.out_col_scale = out_col_scale;
     g.C = C; g.ldc = ldc; g.M = (int)M; g.N = (int)N; g.K = (int)K;
+    g.ksplit = 1; g.kslabs = 0;
     hipStream_t st = (hipStream_t)stream;
     switch (epi) {
-    case HERO_EPI_RAW_I32: return launch_epi<HERO_EPI_RAW_I32, HERO_I32, -1>(g, st);
-    case HERO_EPI_REQUANT: return launch_epi<HERO_EPI_REQUANT, HERO_I8, -1>(g, st);
-    case HERO_EPI_GELU_REQUANT: return launch_epi<HERO_EPI_GELU_REQUANT, HERO_I8, -1>(g, st);
+    case HERO_EPI_RAW_I32: return launch_epi<HERO_EPI_RAW_I32, HERO_I32, -1>(g, workspace, workspace_bytes, st);
+    case HERO_EPI_REQUANT: return launch_epi<HERO_EPI_REQUANT, HERO_I8, -1>(g, workspace, workspace_bytes, st);
+    case HERO_EPI_GELU_REQUANT: return launch_epi<HERO_EPI_GELU_REQUANT, HERO_I8, -1>(g, workspace, workspace_bytes, st);
     case HERO_EPI_DEQUANT_GELU:
-        return c_dt == HERO_BF16 ? launch_epi<HERO_EPI_DEQUANT_GELU, HERO_BF16, -1>(g, st)
-                                 : launch_epi<HERO_EPI_DEQUANT_GELU, HERO_F16, -1>(g, st);
+        return c_dt == HERO_BF16 ? launch_epi<HERO_EPI_DEQUANT_GELU, HERO_BF16, -1>(g, workspace, workspace_bytes, st)
+                                 : launch_epi<HERO_EPI_DEQUANT_GELU, HERO_F16, -1>(g, workspace, workspace_bytes, st);
     case HERO_EPI_DEQUANT:
         if (!residual)
-            return c_dt == HERO_BF16 ? launch_epi<HERO_EPI_DEQUANT, HERO_BF16, -1>(g, st)
-                                     : launch_epi<HERO_EPI_DEQUANT, HERO_F16, -1>(g, st);
-        if (c_dt == HERO_BF16 && res_dt == HERO_BF16) return launch_epi<HERO_EPI_DEQUANT, HERO_BF16, HERO_BF16>(g, st);
-        if (c_dt == HERO_F16 && res_dt == HERO_F16) return launch_epi<HERO_EPI_DEQUANT, HERO_F16, HERO_F16>(g, st);
+            return c_dt == HERO_BF16 ? launch_epi<HERO_EPI_DEQUANT, HERO_BF16, -1>(g, workspace, workspace_bytes, st)
+                                     : launch_epi<HERO_EPI_DEQUANT, HERO_F16, -1>(g, workspace, workspace_bytes, st);
+        if (c_dt == HERO_BF16 && res_dt == HERO_BF16) return launch_epi<HERO_EPI_DEQUANT, HERO_BF16, HERO_BF16>(g, workspace, workspace_bytes, st);
+        if (c_dt == HERO_F16 && res_dt == HERO_F16) return launch_epi<HERO_EPI_DEQUANT, HERO_F16, HERO_F16>(g, workspace, workspace_bytes, st);
         return HERO_ERR_UNSUPPORTED;
     default: return HERO_ERR_UNSUPPORTED;
     }

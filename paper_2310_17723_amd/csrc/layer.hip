@@ -8,13 +8,14 @@
 // PRE_LN (GPT):    h (bf16) -> LN^quant -> QKV -> attention -> W_o (+h) -> LN^quant
 //                  -> FC1 + GELU^quant -> FC2 (+h); h is updated in place.
 #include "hero_common.h"
+#include <algorithm>
 
 namespace {
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct Workspace {
-    size_t xin_q, xin_s, qkv, attn, xo, mid_q, mid_s, a, x2, total;
+    size_t xin_q, xin_s, qkv, attn, xo, mid_q, mid_s, a, x2, gemm_ws, gemm_ws_bytes, total;
 };
 
 Workspace plan(const hero_layer_desc* d, int64_t T) {
@@ -34,6 +35,13 @@ Workspace plan(const hero_layer_desc* d, int64_t T) {
     w.mid_s = take((size_t)T * 4);
     w.a = take((size_t)T * d->f * e_a);
     w.x2 = take(pre ? 0 : (size_t)T * d->d * e_a);
+    // split-K scratch of the skinny (decode) GEMMs: the largest of the four shapes, shared (stream order)
+    size_t g = hero_int8_gemm_workspace_bytes(T, 3 * (int64_t)d->d, d->d);
+    g = std::max(g, hero_int8_gemm_workspace_bytes(T, d->d, d->d));
+    g = std::max(g, hero_int8_gemm_workspace_bytes(T, d->f, d->d));
+    g = std::max(g, hero_int8_gemm_workspace_bytes(T, d->d, d->f));
+    w.gemm_ws_bytes = g;
+    w.gemm_ws = take(g);
     w.total = off;
     return w;
 }
@@ -132,15 +140,16 @@ extern "C" hero_status hero_layer_fwd(const hero_layer_desc* desc, const hero_la
     void* act = base + ws.a;
     void* x2 = base + ws.x2;
     hipStream_t st = (hipStream_t)stream;
+    void* gws = ws.gemm_ws_bytes ? (void*)(base + ws.gemm_ws) : nullptr;   // split-K scratch of the skinny GEMMs
 
     // (1) PRE_LN: LN^quant of the residual stream
     if (pre)
         HERO_TRY(hero_ln_quant(io->h, HERO_BF16, nullptr, nullptr, HERO_I8, nullptr, w->ln1_g, w->ln1_b, desc->eps,
                                T, d, xin_q, xin_s, nullptr, HERO_BF16, stream));
     // (2) QKV GeMM^quant: SQ codes for an INT8 attention (bare Round), bf16 values otherwise
-    HERO_TRY(hero_int8_gemm(xin_q, d, xin_s, w->w_qkv, d, w->w_qkv_s, w->b_qkv, nullptr, HERO_BF16, 0,
+    HERO_TRY(hero_int8_gemm_ws(xin_q, d, xin_s, w->w_qkv, d, w->w_qkv_s, w->b_qkv, nullptr, HERO_BF16, 0,
                             attn_i8 ? HERO_EPI_REQUANT : HERO_EPI_DEQUANT, nullptr,
-                            qkv, attn_i8 ? HERO_I8 : HERO_BF16, 3 * d, T, 3 * d, d, stream));
+                            qkv, attn_i8 ? HERO_I8 : HERO_BF16, 3 * d, T, 3 * d, d, gws, ws.gemm_ws_bytes, stream));
     // (3) attention
     const int64_t qs[4] = {S * 3 * d, 3 * d, Dh, 1};
     if (attn_i8) {
@@ -167,8 +176,8 @@ extern "C" hero_status hero_layer_fwd(const hero_layer_desc* desc, const hero_la
     // (4) attention-output linear and the LN^quant that closes the attention module
     if (!pre) {
         if (o_i8) {
-            HERO_TRY(hero_int8_gemm((const int8_t*)attn, d, nullptr, w->w_o, d, w->w_o_s, w->b_o, nullptr, HERO_BF16, 0,
-                                    HERO_EPI_REQUANT, nullptr, xo, HERO_I8, d, T, d, d, stream));
+            HERO_TRY(hero_int8_gemm_ws((const int8_t*)attn, d, nullptr, w->w_o, d, w->w_o_s, w->b_o, nullptr, HERO_BF16, 0,
+                                    HERO_EPI_REQUANT, nullptr, xo, HERO_I8, d, T, d, d, gws, ws.gemm_ws_bytes, stream));
             HERO_TRY(hero_ln_quant(xin_q, HERO_I8, xin_s, xo, HERO_I8, w->S_o, w->ln1_g, w->ln1_b, desc->eps, T, d,
                                    mid_q, mid_s, nullptr, HERO_BF16, stream));
         } else {
@@ -178,22 +187,22 @@ extern "C" hero_status hero_layer_fwd(const hero_layer_desc* desc, const hero_la
         }
     } else {
         if (o_i8)
-            HERO_TRY(hero_int8_gemm((const int8_t*)attn, d, nullptr, w->w_o, d, w->w_o_s, w->b_o, io->h, HERO_BF16, d,
-                                    HERO_EPI_DEQUANT, nullptr, io->h, HERO_BF16, d, T, d, d, stream));
+            HERO_TRY(hero_int8_gemm_ws((const int8_t*)attn, d, nullptr, w->w_o, d, w->w_o_s, w->b_o, io->h, HERO_BF16, d,
+                                    HERO_EPI_DEQUANT, nullptr, io->h, HERO_BF16, d, T, d, d, gws, ws.gemm_ws_bytes, stream));
         else
             HERO_TRY(hero_bf16_gemm(attn, d, w->w_o_bf16, d, w->b_o, io->h, d, 0, io->h, d, T, d, d, stream));
         HERO_TRY(hero_ln_quant(io->h, HERO_BF16, nullptr, nullptr, HERO_I8, nullptr, w->ln2_g, w->ln2_b, desc->eps,
                                T, d, mid_q, mid_s, nullptr, HERO_BF16, stream));
     }
     // (5) FC1 + GELU^quant (X_1 stays in registers)
-    HERO_TRY(hero_int8_gemm(mid_q, d, mid_s, w->w_1, d, w->w_1_s, w->b_1, nullptr, HERO_BF16, 0,
+    HERO_TRY(hero_int8_gemm_ws(mid_q, d, mid_s, w->w_1, d, w->w_1_s, w->b_1, nullptr, HERO_BF16, 0,
                             fc2_i8 ? HERO_EPI_GELU_REQUANT : HERO_EPI_DEQUANT_GELU, w->S_a,
-                            act, fc2_i8 ? HERO_I8 : HERO_BF16, f, T, f, d, stream));
+                            act, fc2_i8 ? HERO_I8 : HERO_BF16, f, T, f, d, gws, ws.gemm_ws_bytes, stream));
     // (6) FC2 and the closing LN^quant (POST_LN) or residual add (PRE_LN)
     if (!pre) {
         if (fc2_i8) {
-            HERO_TRY(hero_int8_gemm((const int8_t*)act, f, nullptr, w->w_2, f, w->w_2_s, w->b_2, nullptr, HERO_BF16, 0,
-                                    HERO_EPI_REQUANT, nullptr, x2, HERO_I8, d, T, d, f, stream));
+            HERO_TRY(hero_int8_gemm_ws((const int8_t*)act, f, nullptr, w->w_2, f, w->w_2_s, w->b_2, nullptr, HERO_BF16, 0,
+                                    HERO_EPI_REQUANT, nullptr, x2, HERO_I8, d, T, d, f, gws, ws.gemm_ws_bytes, stream));
             HERO_TRY(hero_ln_quant(mid_q, HERO_I8, mid_s, x2, HERO_I8, w->S_x2, w->ln2_g, w->ln2_b, desc->eps, T, d,
                                    io->out_q, io->out_scale, nullptr, HERO_BF16, stream));
         } else {
@@ -203,8 +212,8 @@ extern "C" hero_status hero_layer_fwd(const hero_layer_desc* desc, const hero_la
         }
     } else {
         if (fc2_i8)
-            HERO_TRY(hero_int8_gemm((const int8_t*)act, f, nullptr, w->w_2, f, w->w_2_s, w->b_2, io->h, HERO_BF16, d,
-                                    HERO_EPI_DEQUANT, nullptr, io->h, HERO_BF16, d, T, d, f, stream));
+            HERO_TRY(hero_int8_gemm_ws((const int8_t*)act, f, nullptr, w->w_2, f, w->w_2_s, w->b_2, io->h, HERO_BF16, d,
+                                    HERO_EPI_DEQUANT, nullptr, io->h, HERO_BF16, d, T, d, f, gws, ws.gemm_ws_bytes, stream));
         else
             HERO_TRY(hero_bf16_gemm(act, f, w->w_2_bf16, f, w->b_2, io->h, d, 0, io->h, d, T, d, f, stream));
     }

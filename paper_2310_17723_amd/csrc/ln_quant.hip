@@ -128,11 +128,23 @@ __global__ __launch_bounds__(64 * ln_max_waves(NCH)) void ln_quant_kernel(LnArgs
     fetch(row, std::integral_constant<int, 0>{});             // in flight while the parameters are staged
     if constexpr (PF > 1) fetch(row + tw, std::integral_constant<int, PF - 1>{});
 
-    for (int j = tid; j < Dp; j += blockDim.x) {
-        const bool in = j < D;
-        sp[j] = (HAS_LN && in) ? a.gamma[j] : 0.0f;
-        sp[Dp + j] = (HAS_LN && a.beta && in) ? a.beta[j] : 0.0f;
-        sp[2 * Dp + j] = (r_i8 && in) ? a.r_col_scale[j] : 0.0f;
+    // parameters -> LDS, 8 columns per thread and round with all their loads issued before the first LDS
+    // store (one memory latency per round, not one per column: this is the whole cost of a small launch)
+    for (int j0 = tid; j0 < Dp; j0 += 8 * blockDim.x) {
+        float pg[8], pb[8], pr[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int j = j0 + k * blockDim.x;
+            const bool in = j < D;
+            pg[k] = (HAS_LN && in) ? a.gamma[j] : 0.0f;
+            pb[k] = (HAS_LN && a.beta && in) ? a.beta[j] : 0.0f;
+            pr[k] = (r_i8 && in) ? a.r_col_scale[j] : 0.0f;
+        }
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int j = j0 + k * blockDim.x;
+            if (j < Dp) { sp[j] = pg[k]; sp[Dp + j] = pb[k]; sp[2 * Dp + j] = pr[k]; }
+        }
     }
     __syncthreads();
     if (row >= a.M) return;

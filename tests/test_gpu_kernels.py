@@ -210,6 +210,42 @@ def test_gemm_many_tiles_ragged_edges(hero, M, N, K, monkeypatch):
         assert_exact(to_np(got), ref_res, f"dequant + residual in place tile={tile}")
 
 
+@pytest.mark.parametrize("M,N,K", [(64, 4096, 4096), (33, 1000, 2048), (100, 2304, 1024), (1, 512, 16384), (64, 1024, 512)])
+def test_gemm_skinny_split_k_workspace(hero, M, N, K):
+    """hero_int8_gemm_ws: K split over several workgroups per tile with int32 partial sums in a caller-owned
+    scratch.  Integer sums commute, so every epilogue stays in its class (raw / REQUANT / DEQUANT / residual
+    bit-exact); the scratch needs no initialisation (it starts out as garbage here) and serves calls of other shapes."""
+    nbytes = hero.hero_int8_gemm_workspace_bytes(M, N, K)
+    assert nbytes > 0
+    assert hero.hero_int8_gemm_workspace_bytes(4096, N, K) == 0        # not skinny: no split
+    ws = torch.full((max(nbytes, hero.hero_int8_gemm_workspace_bytes(64, 4096, 4096)),), 0xA5, dtype=torch.uint8, device="cuda")
+    c = synth.gemm_case(800 + M, M, K, N)
+    A, Bt, rs, cs, bias = c["A"], c["Bt"], c["a_row_scale"], c["b_col_scale"], c["bias"]
+    dA, dB = dev(A), dev(Bt)
+    assert_exact(to_np(hero.hero_int8_gemm(dA, dB, workspace=ws)), O.gemm_i32(A, Bt), "raw")
+    y = O.int8_gemm(A, Bt, a_row_scale=rs, b_col_scale=cs, bias=bias, epi=O.EPI_DEQUANT, c_dt=O.F32)
+    s_out = np.float32(np.abs(y).max() / 127)
+    cs2, b2 = (cs / s_out).astype(np.float32), (bias / s_out).astype(np.float32)
+    ref = O.int8_gemm(A, Bt, a_row_scale=rs, b_col_scale=cs2, bias=b2, epi=O.EPI_REQUANT, c_dt=O.I8)
+    got = hero.hero_int8_gemm(dA, dB, dev(rs), dev(cs2), dev(b2), epi=HB.EPI_REQUANT, out_dtype=torch.int8, workspace=ws)
+    assert_exact(to_np(got), ref, "requant")
+    res = O.f32_to_bf16(synth.rng(12).standard_normal((M, N)).astype(np.float32))
+    ref = O.int8_gemm(A, Bt, a_row_scale=rs, b_col_scale=cs, bias=bias, residual=res, res_dt=O.BF16,
+                      epi=O.EPI_DEQUANT, c_dt=O.BF16)
+    dres = dev(res)
+    got = hero.hero_int8_gemm(dA, dB, dev(rs), dev(cs), dev(bias), residual=dres, epi=HB.EPI_DEQUANT, C_out=dres, workspace=ws)
+    assert_exact(to_np(got), ref, "dequant + residual in place")
+    csg = (cs * np.float32(30.0 / np.sqrt(K))).astype(np.float32)
+    g = O.int8_gemm(A, Bt, a_row_scale=rs, b_col_scale=csg, bias=bias, epi=O.EPI_DEQUANT_GELU, c_dt=O.F32)
+    s_a = (np.abs(g).max(axis=0) / 127 + 1e-6).astype(np.float32)
+    ref = O.int8_gemm(A, Bt, a_row_scale=rs, b_col_scale=csg, bias=bias, epi=O.EPI_GELU_REQUANT, out_col_scale=s_a, c_dt=O.I8)
+    got = hero.hero_int8_gemm(dA, dB, dev(rs), dev(csg), dev(bias), epi=HB.EPI_GELU_REQUANT, out_col_scale=dev(s_a),
+                              out_dtype=torch.int8, workspace=ws)
+    assert_codes(to_np(got), ref, "gelu requant")
+    with pytest.raises(HB.HeroError):                                   # misaligned scratch
+        hero.hero_int8_gemm(dA, dB, workspace=ws[16:])
+
+
 def test_gemm_strided_operands_and_errors(hero):
     """Leading dimensions larger than the logical width; invalid combinations are refused."""
     M, N, K = 96, 80, 128
