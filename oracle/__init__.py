@@ -213,6 +213,31 @@ def ln_quant(x, x_dt, x_row_scale, r, r_dt, r_col_scale, gamma, beta, eps, y_hp_
     return y_q, y_s, y_hp
 
 
+# ------------------------------------------------------------------ O5b
+def embed_ln_quant(tok_ids, pos_ids, type_ids, tok_table, tok_scale, pos_table, type_table, pt_dt, gamma, beta, eps):
+    """Embedding LN^quant (Sec. 2.2.1): INT8 token table with one TWQ scale per row + position (+ type)
+    rows in pt_dt (BF16 / F16 / F32) -> LayerNorm -> token-wise INT8.  type_table may be None."""
+    i32 = lambda a: None if a is None else np.ascontiguousarray(a, np.int32)
+    f32 = lambda a: None if a is None else np.ascontiguousarray(a, np.float32)
+    tok_ids, pos_ids, type_ids = map(i32, (tok_ids, pos_ids, type_ids))
+    tok_table = np.ascontiguousarray(tok_table, np.int8)
+    V, D = tok_table.shape
+    T = tok_ids.shape[0]
+    pos_table = np.ascontiguousarray(pos_table, _NP_OF[pt_dt])
+    if type_table is not None:
+        type_table = np.ascontiguousarray(type_table, _NP_OF[pt_dt])
+    tok_scale, gamma, beta = map(f32, (tok_scale, gamma, beta))
+    y_q = np.empty((T, D), np.int8)
+    y_s = np.empty((T,), np.float32)
+    rc = lib().orc_embed_ln_quant(_p(tok_ids), _p(pos_ids), _p(type_ids), _p(tok_table), _p(tok_scale), _i64(V),
+                                  _p(pos_table), _i64(pos_table.shape[0]), _p(type_table),
+                                  _i64(0 if type_table is None else type_table.shape[0]), C.c_int(pt_dt),
+                                  _p(gamma), _p(beta), C.c_float(eps), _i64(T), _i64(D), _p(y_q), _p(y_s))
+    if rc != 0:
+        raise ValueError("oracle embed_ln_quant: missing argument" if rc == -1 else "oracle embed_ln_quant: index out of range")
+    return y_q, y_s
+
+
 # ------------------------------------------------------------------ O6
 def _strides(a: np.ndarray):
     """Element strides of a 4-d array as an int64[4] ctypes array."""

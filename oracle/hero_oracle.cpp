@@ -280,6 +280,56 @@ int orc_ln_quant(const void* x, int x_dt, const float* x_row_scale,
 }
 
 // ---------------------------------------------------------------------------------
+// O5b.  Embedding LN^quant (Sec. 2.2.1: S_emb X_emb,int8 = LN^quant(S_xt X_t,int8, X_p, X_s)).
+// Per token i:  h[j] = S_xt[tok_ids[i]] * X_t,int8[tok_ids[i]][j] + X_p[pos_ids[i]][j]
+//                      (+ X_s[type_ids[i]][j] when a type table is given)
+// with the token table in INT8 codes + one TWQ scale per table row and the position / type tables in
+// bf16 / f16 / f32; LayerNorm of h over j and the TWQ quantization exactly as in O5 (sum, mean,
+// biased variance and the normalised value in fp64, one cast to fp32, TWQ primitive in fp32).
+// Returns -2 when an index is out of its table.
+// ---------------------------------------------------------------------------------
+int orc_embed_ln_quant(const int32_t* tok_ids, const int32_t* pos_ids, const int32_t* type_ids,
+                       const int8_t* tok_table, const float* tok_scale, int64_t V,
+                       const void* pos_table, int64_t P, const void* type_table, int64_t NT, int pt_dt,
+                       const float* gamma, const float* beta, float eps,
+                       int64_t T, int64_t D, int8_t* y_q, float* y_scale) {
+    if (!tok_ids || !pos_ids || !tok_table || !tok_scale || !pos_table || !gamma) return -1;
+    if (type_table && !type_ids) return -1;
+    for (int64_t i = 0; i < T; ++i) {
+        if (tok_ids[i] < 0 || tok_ids[i] >= V || pos_ids[i] < 0 || pos_ids[i] >= P) return -2;
+        if (type_table && (type_ids[i] < 0 || type_ids[i] >= NT)) return -2;
+    }
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < T; ++i) {
+        std::vector<double> s(D);
+        const int64_t tk = tok_ids[i], ps = pos_ids[i], ty = type_table ? type_ids[i] : 0;
+        for (int64_t j = 0; j < D; ++j) {
+            double v = (double)tok_scale[tk] * (double)tok_table[tk * D + j];
+            v += (double)load_hp(pos_table, pt_dt, ps * D + j);
+            if (type_table) v += (double)load_hp(type_table, pt_dt, ty * D + j);
+            s[j] = v;
+        }
+        double mu = 0.0;
+        for (int64_t j = 0; j < D; ++j) mu += s[j];
+        mu /= (double)D;
+        double var = 0.0;
+        for (int64_t j = 0; j < D; ++j) var += (s[j] - mu) * (s[j] - mu);
+        var /= (double)D;
+        const double rstd = 1.0 / std::sqrt(var + (double)eps);
+        std::vector<float> y32(D);
+        float amax = 0.0f;
+        for (int64_t j = 0; j < D; ++j) {
+            y32[j] = (float)((s[j] - mu) * rstd * (double)gamma[j] + (beta ? (double)beta[j] : 0.0));
+            amax = std::max(amax, std::fabs(y32[j]));
+        }
+        const float sc = dyn_scale(amax);
+        y_scale[i] = sc;
+        for (int64_t j = 0; j < D; ++j) y_q[i * D + j] = quant_code(y32[j], sc);
+    }
+    return 0;
+}
+
+// ---------------------------------------------------------------------------------
 // O6.  INT8 attention (Sec. 2.2.2, quantized flow, lines A, Softmax^quant, X_attn;
 // and d~ = S_q S_k / sqrt(d)).  Per (batch, head):
 //   acc_qk[i][k] exact;  a = float(acc_qk) * d~  (fp32, A is never quantized);

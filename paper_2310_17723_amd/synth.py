@@ -90,6 +90,28 @@ def embedding_ln_params(seed: int, shape: LayerShape) -> dict:
     return {"g": 1.0 + 0.1 * n(shape.d), "b": 0.02 * n(shape.d)}
 
 
+def embedding_tables(seed: int, d: int, vocab: int = 30522, max_pos: int = 512, n_types: int = 2) -> dict:
+    """fp32 token / position / sentence-type tables: N(0, 0.02^2) rows (the BERT initialiser), the token rows
+    with a log-uniform per-row magnitude spread of 8x, so that per-row scales matter."""
+    g = rng(seed, 910)
+    n = lambda *sh: g.standard_normal(sh, dtype=np.float32)
+    mag = np.exp(g.uniform(np.log(0.5), np.log(4.0), vocab)).astype(np.float32)
+    return {"tok": n(vocab, d) * np.float32(0.02) * mag[:, None], "pos": n(max_pos, d) * np.float32(0.02),
+            "type": n(n_types, d) * np.float32(0.02)}
+
+
+def embedding_ids(seed: int, B: int, S: int, vocab: int = 30522, n_types: int = 2) -> dict:
+    """int32 [B*S] token ids (Zipf-like: rank r drawn with weight 1/(r+10)), position ids t % S and
+    sentence-type ids (0 up to a random split point of each sequence, 1 after it)."""
+    g = rng(seed, 920)
+    w = 1.0 / (np.arange(vocab, dtype=np.float64) + 10.0)
+    tok = g.choice(vocab, size=B * S, p=w / w.sum()).astype(np.int32)
+    pos = np.tile(np.arange(S, dtype=np.int32), B)
+    split = g.integers(S // 4, S, B)
+    typ = (np.arange(S)[None, :] >= split[:, None]).astype(np.int32).reshape(-1) % n_types
+    return {"tok": tok, "pos": pos, "type": typ.astype(np.int32)}
+
+
 def outlier_channels(seed: int, shape: LayerShape) -> np.ndarray:
     g = rng(seed, 800)
     k = int(round(shape.outlier_frac * shape.d))

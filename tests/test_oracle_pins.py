@@ -278,6 +278,53 @@ def test_ln_quant_closed_forms_and_torch():
         np.mean(y5 != ref5.to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)) < 2e-3
 
 
+# ---------------------------------------------------------------- O5b embedding LN^quant
+def test_embed_ln_quant_against_torch_and_invariants():
+    """Sec. 2.2.1.  Pins that do not go through the oracle's own arithmetic: torch's embedding lookups and
+    fp64 layer_norm for the value that is quantized; the half-step property of a round-to-nearest code
+    (|y_q s - y| <= s/2) and s = max|y| / 127 for the quantization; a permutation of the tokens permutes the
+    outputs; dropping any of the three addends changes the result (each term is really there)."""
+    d, V, P, NT, B, S = 96, 500, 40, 2, 3, 40
+    tb = synth.embedding_tables(3, d, V, P, NT)
+    ids = synth.embedding_ids(4, B, S, V, NT)
+    tq, ts = O.quant_twq(tb["tok"])                                   # INT8 token table, one scale per row
+    pos16, typ16 = O.f32_to_bf16(tb["pos"]), O.f32_to_bf16(tb["type"])
+    g = synth.rng(5)
+    gam = (1 + 0.1 * g.standard_normal(d)).astype(np.float32)
+    bet = (0.02 * g.standard_normal(d)).astype(np.float32)
+    eps = 1e-6
+    q, s = O.embed_ln_quant(ids["tok"], ids["pos"], ids["type"], tq, ts, pos16, typ16, O.BF16, gam, bet, eps)
+    F = torch.nn.functional
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a))
+    tok64 = t(ts.astype(np.float64)[:, None] * tq.astype(np.float64))
+    h = F.embedding(t(ids["tok"]).long(), tok64) + F.embedding(t(ids["pos"]).long(), t(O.bf16_to_f32(pos16)).double()) \
+        + F.embedding(t(ids["type"]).long(), t(O.bf16_to_f32(typ16)).double())
+    y = F.layer_norm(h, (d,), t(gam).double(), t(bet).double(), eps).numpy()
+    amax = np.abs(y).max(axis=1)
+    assert np.allclose(s, amax / 127, rtol=3e-7, atol=0)
+    assert (np.abs(q) <= 127).all() and (np.abs(q).max(axis=1) == 127).all()
+    err = np.abs(q.astype(np.float64) * s[:, None].astype(np.float64) - y)
+    assert (err <= 0.5 * s[:, None] * (1 + 1e-5) + 1e-7 * amax[:, None]).all()
+    # f32 tables, no type table
+    q2, s2 = O.embed_ln_quant(ids["tok"], ids["pos"], None, tq, ts, tb["pos"], None, O.F32, gam, None, eps)
+    h2 = F.embedding(t(ids["tok"]).long(), tok64) + F.embedding(t(ids["pos"]).long(), t(tb["pos"]).double())
+    y2 = F.layer_norm(h2, (d,), t(gam).double(), None, eps).numpy()
+    assert np.allclose(s2, np.abs(y2).max(axis=1) / 127, rtol=3e-7, atol=0)
+    assert (np.abs(q2.astype(np.float64) * s2[:, None] - y2) <= 0.5 * s2[:, None] * (1 + 1e-5) + 1e-7).all()
+    assert not np.array_equal(q, q2)                                  # the type rows matter
+    qz, _ = O.embed_ln_quant(ids["tok"], np.zeros_like(ids["pos"]), ids["type"], tq, ts, pos16, typ16, O.BF16, gam, bet, eps)
+    assert not np.array_equal(q, qz)                                  # ... and so do the position rows
+    # permuting the tokens permutes the rows of the output
+    perm = g.permutation(B * S)
+    qp, sp = O.embed_ln_quant(ids["tok"][perm], ids["pos"][perm], ids["type"][perm], tq, ts, pos16, typ16, O.BF16, gam, bet, eps)
+    assert np.array_equal(qp, q[perm]) and np.array_equal(sp, s[perm])
+    bad = ids["tok"].copy(); bad[7] = V
+    with pytest.raises(ValueError):
+        O.embed_ln_quant(bad, ids["pos"], ids["type"], tq, ts, pos16, typ16, O.BF16, gam, bet, eps)
+    with pytest.raises(ValueError):
+        O.embed_ln_quant(ids["tok"], ids["pos"], None, tq, ts, pos16, typ16, O.BF16, gam, bet, eps)
+
+
 # ---------------------------------------------------------------- O6 attention
 def _attn_inputs(seed, B, Sq, Skv, H, Dh):
     g = synth.rng(seed)
