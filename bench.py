@@ -211,6 +211,38 @@ def ln_bandwidth(hero, T, D, iters=40, nbuf=8):
             "gbs": round(gbs, 1), "frac_hbm": round(gbs / PEAK_HBM_GBS, 4), "working_set_mb": nbuf * bytes_ // 2 ** 20}
 
 
+def embed_bandwidth(hero, B, S, D, V=30522, iters=40, nbuf=8):
+    """Embedding LN^quant (Sec. 2.2.1): INT8 token-table gather + bf16 position / type rows -> LN -> TWQ INT8.
+    Algorithmic bytes: one INT8 table row, its scale and three ids read and one INT8 row + scale written per
+    token, the position / type tables once."""
+    import torch
+    from paper_2310_17723_amd import synth
+    T = B * S
+    g = torch.Generator(device="cuda").manual_seed(2)
+    tok = torch.randint(-127, 128, (V, D), dtype=torch.int8, device="cuda", generator=g)
+    ts = torch.rand(V, device="cuda", generator=g) * 1e-3 + 1e-4
+    pos = (torch.randn((S, D), device="cuda", generator=g) * 0.02).to(torch.bfloat16)
+    typ = (torch.randn((2, D), device="cuda", generator=g) * 0.02).to(torch.bfloat16)
+    gam = torch.ones(D, device="cuda")
+    bet = torch.zeros(D, device="cuda")
+    sets = []
+    for k in range(nbuf):
+        ids = synth.embedding_ids(100 + k, B, S, V, 2)
+        sets.append((torch.from_numpy(ids["tok"]).cuda(), torch.from_numpy(ids["pos"]).cuda(), torch.from_numpy(ids["type"]).cuda(),
+                     torch.empty((T, D), dtype=torch.int8, device="cuda"), torch.empty(T, device="cuda")))
+    i = [0]
+
+    def fn():
+        a, b, c, yq, ys = sets[i[0] % nbuf]
+        i[0] += 1
+        hero.hero_embed_ln_quant(a, b, c, tok, ts, pos, typ, gam, bet, 1e-12, y_q=yq, y_scale=ys)
+    ms = time_gpu(fn, iters, warmup=nbuf)
+    bytes_ = T * (2 * D + 20) + (S + 2) * D * 2
+    gbs = bytes_ / (ms * 1e-3) / 1e9
+    return {"T": T, "D": D, "vocab": V, "form": "int8 table + bf16 tables -> int8", "us": round(ms * 1e3, 2),
+            "bytes_per_launch": bytes_, "gbs": round(gbs, 1), "frac_hbm": round(gbs / PEAK_HBM_GBS, 4)}
+
+
 def cpu_baseline(shape, seed, mode_name):
     """The oracle, as it stands, on a bounded slice of the workload (about 10-30 s of CPU work)."""
     import oracle as O
@@ -327,6 +359,7 @@ def main():
         log("[bench] LN^quant bandwidth")
         rec["ln_quant"] = ln_bandwidth(hero, max(st.T, 16384), shape.d)
         rec["ln_quant_large"] = ln_bandwidth(hero, 65536, shape.d, nbuf=4)
+        rec["embed_ln_quant"] = embed_bandwidth(hero, 32, 512, shape.d)
         log("[bench] GEMM sweep")
         rec["gemm_sweep"] = gemm_sweep(hero, args.seed)
         del st

@@ -77,6 +77,28 @@ hero_status hero_ln_quant(const void* x, hero_dtype x_dt, const float* x_row_sca
                           int64_t M, int64_t D,
                           int8_t* y_q, float* y_scale, void* y_hp, hero_dtype y_hp_dt, void* stream);
 
+/* Embedding LN^quant.  Paper: Sec. 2.2.1,
+ *   S_emb X_emb,int8 = LN^quant(S_xt X_t,int8, X_p, X_s)
+ * the token embedding is stored as INT8 codes with one TWQ scale per table row, the (small) position
+ * and sentence-type tables stay in 16-bit floating point; the LayerNorm of their sum is quantized
+ * per token exactly as in hero_ln_quant:
+ *   h[i][j] = tok_scale[t] * tok_table[t][j] + pos_table[p][j] (+ type_table[s][j]),
+ *             t = tok_ids[i], p = pos_ids[i], s = type_ids[i]
+ *   y = LayerNorm_j(h) * gamma + beta ;  y_scale[i] = max_j |y| / 127 ;  y_q = sat(rne(y / y_scale[i]))
+ *   tok_ids, pos_ids, type_ids   int32[T] (device).  An index outside its table cannot be reported
+ *            from an asynchronous call: it is clamped into the table.
+ *   tok_table [V,D] int8, tok_scale [V] f32;  pos_table [P,D], type_table [NT,D] in pt_dt
+ *            (HERO_BF16 / HERO_F16);  type_table == NULL: no third addend (type_ids ignored).
+ *   gamma [D] required, beta [D] or NULL;  y_q [T,D] int8 and y_scale [T] f32 are written.
+ * Constraints: D % 16 == 0, 16 <= D <= 8192; tables and y_q 16-byte aligned.  T == 0 is a no-op.
+ */
+hero_status hero_embed_ln_quant(const int32_t* tok_ids, const int32_t* pos_ids, const int32_t* type_ids,
+                                const int8_t* tok_table, const float* tok_scale, int64_t V,
+                                const void* pos_table, int64_t P,
+                                const void* type_table, int64_t NT, hero_dtype pt_dt,
+                                const float* gamma, const float* beta, float eps,
+                                int64_t T, int64_t D, int8_t* y_q, float* y_scale, void* stream);
+
 /* GeMM^quant: INT8 x INT8 -> INT32 GEMM with the dequantization and the static FWQ/SQ
  * scales fused behind it.  Paper: Sec. 2.1 (Y = XW, column-wise weight scales, weights in
  * column-major format), Sec. 2.2.2 (dequantization and pre-determined scales fused into

@@ -43,6 +43,7 @@ SYMBOLS = {
     "hero_strerror": (C.c_char_p, [i32]),
     "hero_build_arch": (C.c_char_p, []),
     "hero_ln_quant": (i32, [vp, i32, vp, vp, i32, vp, vp, vp, f32, i64, i64, vp, vp, vp, i32, vp]),
+    "hero_embed_ln_quant": (i32, [vp, vp, vp, vp, vp, i64, vp, i64, vp, i64, i32, vp, vp, f32, i64, i64, vp, vp, vp]),
     "hero_int8_gemm": (i32, [vp, i64, vp, vp, i64, vp, vp, vp, i32, i64, i32, vp, vp, i32, i64, i64, i64, i64, vp]),
     "hero_int8_gemm_workspace_bytes": (C.c_size_t, [i64, i64, i64]),
     "hero_int8_gemm_ws": (i32, [vp, i64, vp, vp, i64, vp, vp, vp, i32, i64, i32, vp, vp, i32, i64, i64, i64, i64,
@@ -113,6 +114,22 @@ class Hero:
                                     _DT[y_hp.dtype] if y_hp is not None else 0, _stream(stream))
         self._check(st)
         return y_q, y_scale, y_hp
+
+    def hero_embed_ln_quant(self, tok_ids, pos_ids, type_ids, tok_table, tok_scale, pos_table, type_table,
+                            gamma, beta, eps, y_q=None, y_scale=None, stream=None):
+        """int32 id vectors [T]; tok_table [V,D] int8 + tok_scale [V]; pos/type tables bf16 or f16 (type may be None)."""
+        T = tok_ids.shape[0]
+        V, D = tok_table.shape
+        if y_q is None:
+            y_q = torch.empty((T, D), dtype=torch.int8, device=tok_table.device)
+        if y_scale is None:
+            y_scale = torch.empty((T,), dtype=torch.float32, device=tok_table.device)
+        st = self.lib.hero_embed_ln_quant(_ptr(tok_ids), _ptr(pos_ids), _ptr(type_ids), _ptr(tok_table), _ptr(tok_scale), V,
+                                          _ptr(pos_table), pos_table.shape[0], _ptr(type_table),
+                                          type_table.shape[0] if type_table is not None else 0, _DT[pos_table.dtype],
+                                          _ptr(gamma), _ptr(beta), float(eps), T, D, _ptr(y_q), _ptr(y_scale), _stream(stream))
+        self._check(st)
+        return y_q, y_scale
 
     # ------------------------------------------------------------------ GeMM^quant
     def hero_int8_gemm(self, A, Bt, a_row_scale=None, b_col_scale=None, bias=None, residual=None,

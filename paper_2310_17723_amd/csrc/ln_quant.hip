@@ -36,6 +36,10 @@ struct LnArgs {
     float eps; int64_t M; int D;
     int8_t* y_q; float* y_scale; void* y_hp;
     int x_dt, r_dt, hp_dt;       // r_dt / hp_dt = -1 when absent
+    // gathered form (embedding): row i of x / r / r2 is row x_idx[i] / r_idx[i] / r2_idx[i] of a table
+    // with x_rows / r_rows / r2_rows rows (indices are clamped into the table); r2 is a third addend in r_dt
+    const int32_t* x_idx; const int32_t* r_idx; const void* r2; const int32_t* r2_idx;
+    int x_rows, r_rows, r2_rows;
 };
 
 // sign-extended byte B of w -> fp32 in one instruction
@@ -88,8 +92,9 @@ __device__ __forceinline__ void store_hp(const float (&v)[EPL], uint16_t* dst) {
 constexpr int ln_max_waves(int nch) { return nch <= 2 ? 16 : (nch == 4 ? 8 : 4); }   // per workgroup: the row must fit the registers
 
 // XDT: HERO_I8 / HERO_BF16 / HERO_F16.  RDT: -1 (no second addend) / HERO_I8 / HERO_BF16 / HERO_F16.
-template <int XDT, int RDT, int NCH, bool HAS_LN>
+template <int XDT, int RDT, int NCH, bool HAS_LN, bool GATHER = false>
 __global__ __launch_bounds__(64 * ln_max_waves(NCH)) void ln_quant_kernel(LnArgs a) {
+    static_assert(!GATHER || (XDT == HERO_I8 && (RDT == HERO_BF16 || RDT == HERO_F16) && HAS_LN), "gathered form: INT8 table + 16-bit tables");
     constexpr bool X_I8 = XDT == HERO_I8;
     constexpr int EPL = X_I8 ? 16 : 8;
     constexpr int CH = EPL * HERO_WAVE;
@@ -102,31 +107,50 @@ __global__ __launch_bounds__(64 * ln_max_waves(NCH)) void ln_quant_kernel(LnArgs
     int64_t row = (int64_t)blockIdx.x * nwb + (tid >> 6);
 
     // raw data of the rows in flight
-    v4i rx[PF][NCH], rr0[PF][NCH], rr1[PF][NCH];
+    v4i rx[PF][NCH], rr0[PF][NCH], rr1[PF][NCH], rs0[GATHER ? NCH : 1], rs1[GATHER ? NCH : 1];
     float xsr[PF];
+    // gathered form: the table rows of the NEXT fetch, looked up one row earlier than the data they address
+    int gx = 0, gr = 0, g2 = 0;
+    const bool has_r2 = GATHER && a.r2 != nullptr;
+    auto lookup = [&](int64_t rw) {
+        if (!GATHER || rw >= a.M) return;
+        gx = min(max(a.x_idx[rw], 0), a.x_rows - 1);
+        gr = min(max(a.r_idx[rw], 0), a.r_rows - 1);
+        if (has_r2) g2 = min(max(a.r2_idx[rw], 0), a.r2_rows - 1);
+    };
     auto fetch = [&](int64_t rw, auto P) {
         constexpr int p = decltype(P)::value;
         if (rw >= a.M) return;                                // wave-uniform
-        xsr[p] = X_I8 ? a.x_row_scale[rw] : 1.0f;
+        const int64_t xrow = GATHER ? gx : rw, rrow = GATHER ? gr : rw;
+        xsr[p] = X_I8 ? a.x_row_scale[xrow] : 1.0f;
 #pragma unroll
         for (int c = 0; c < NCH; ++c) {
             const int j0 = c * CH + lane * EPL;
             if (j0 < D) {
-                const int64_t off = rw * (int64_t)D + j0;
+                const int64_t off = xrow * (int64_t)D + j0, roff = rrow * (int64_t)D + j0;
                 rx[p][c] = X_I8 ? *reinterpret_cast<const v4i*>((const int8_t*)a.x + off)
                                 : *reinterpret_cast<const v4i*>((const uint16_t*)a.x + off);
                 if constexpr (r_i8) {
-                    if constexpr (EPL == 16) rr0[p][c] = *reinterpret_cast<const v4i*>((const int8_t*)a.r + off);
-                    else { v2i t = *reinterpret_cast<const v2i*>((const int8_t*)a.r + off); rr0[p][c][0] = t[0]; rr0[p][c][1] = t[1]; }
+                    if constexpr (EPL == 16) rr0[p][c] = *reinterpret_cast<const v4i*>((const int8_t*)a.r + roff);
+                    else { v2i t = *reinterpret_cast<const v2i*>((const int8_t*)a.r + roff); rr0[p][c][0] = t[0]; rr0[p][c][1] = t[1]; }
                 } else if constexpr (r_hp) {
-                    rr0[p][c] = *reinterpret_cast<const v4i*>((const uint16_t*)a.r + off);
-                    if constexpr (EPL == 16) rr1[p][c] = *reinterpret_cast<const v4i*>((const uint16_t*)a.r + off + 8);
+                    rr0[p][c] = *reinterpret_cast<const v4i*>((const uint16_t*)a.r + roff);
+                    if constexpr (EPL == 16) rr1[p][c] = *reinterpret_cast<const v4i*>((const uint16_t*)a.r + roff + 8);
+                }
+                if constexpr (GATHER) {
+                    if (has_r2) {
+                        const int64_t off2 = (int64_t)g2 * D + j0;
+                        rs0[c] = *reinterpret_cast<const v4i*>((const uint16_t*)a.r2 + off2);
+                        rs1[c] = *reinterpret_cast<const v4i*>((const uint16_t*)a.r2 + off2 + 8);
+                    }
                 }
             }
         }
     };
+    lookup(row);
     fetch(row, std::integral_constant<int, 0>{});             // in flight while the parameters are staged
     if constexpr (PF > 1) fetch(row + tw, std::integral_constant<int, PF - 1>{});
+    lookup(row + PF * tw);
 
     // parameters -> LDS, 8 columns per thread and round with all their loads issued before the first LDS
     // store (one memory latency per round, not one per column: this is the whole cost of a small launch)
@@ -160,6 +184,7 @@ __global__ __launch_bounds__(64 * ln_max_waves(NCH)) void ln_quant_kernel(LnArgs
             asm volatile("" : "+v"(rx[p][c]));
             if constexpr (r_i8 || r_hp) asm volatile("" : "+v"(rr0[p][c]));
             if constexpr (r_hp && EPL == 16) asm volatile("" : "+v"(rr1[p][c]));
+            if constexpr (GATHER) { asm volatile("" : "+v"(rs0[c])); asm volatile("" : "+v"(rs1[c])); }
         }
         float v[NCH][EPL];
         const float xs = xsr[p];
@@ -199,6 +224,16 @@ __global__ __launch_bounds__(64 * ln_max_waves(NCH)) void ln_quant_kernel(LnArgs
                         uint32_t h = ((uint32_t)w >> (16 * (e & 1))) & 0xffffu;
                         v[c][e] += hp_to_f32<RDT>(h);
                     }
+                    if constexpr (GATHER) {
+                        if (has_r2) {
+#pragma unroll
+                            for (int e = 0; e < EPL; ++e) {
+                                const int w = e < 8 ? rs0[c][(e & 7) >> 1] : rs1[c][(e & 7) >> 1];
+                                uint32_t h = ((uint32_t)w >> (16 * (e & 1))) & 0xffffu;
+                                v[c][e] += hp_to_f32<RDT>(h);
+                            }
+                        }
+                    }
                 }
             } else {
 #pragma unroll
@@ -207,6 +242,7 @@ __global__ __launch_bounds__(64 * ln_max_waves(NCH)) void ln_quant_kernel(LnArgs
         }
         // ---- the loads of the row PF strides ahead go out now, into the register set just unpacked
         fetch(row + PF * tw, P);
+        lookup(row + 2 * PF * tw);
 
         // ---- LayerNorm: mean, then variance about the mean (fp32) --------------------------
         if constexpr (HAS_LN) {
@@ -309,12 +345,13 @@ __global__ __launch_bounds__(64 * ln_max_waves(NCH)) void ln_quant_kernel(LnArgs
     }
 }
 
-template <int XDT, int RDT, int NCH>
+template <int XDT, int RDT, int NCH, bool GATHER = false>
 hero_status launch_nch(const LnArgs& a, hipStream_t st) {
     constexpr int CH = (XDT == HERO_I8 ? 16 : 8) * HERO_WAVE;
     const size_t lds = (size_t)3 * NCH * CH * sizeof(float);
     const bool has_ln = a.gamma != nullptr;
-    const void* fn = has_ln ? (const void*)ln_quant_kernel<XDT, RDT, NCH, true> : (const void*)ln_quant_kernel<XDT, RDT, NCH, false>;
+    const void* fn = GATHER ? (const void*)ln_quant_kernel<XDT, RDT, NCH, true, GATHER>
+                   : has_ln ? (const void*)ln_quant_kernel<XDT, RDT, NCH, true> : (const void*)ln_quant_kernel<XDT, RDT, NCH, false>;
     if (lds > 65536 &&                                    // more than 64 KB of dynamic LDS needs the opt-in
         hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
         return HERO_ERR_LAUNCH;
@@ -325,7 +362,8 @@ hero_status launch_nch(const LnArgs& a, hipStream_t st) {
     int64_t blocks = (a.M + wpb - 1) / wpb;
     const int64_t cap = 256 * (MAXW / wpb);
     if (blocks > cap) blocks = cap;
-    if (has_ln) hipLaunchKernelGGL((ln_quant_kernel<XDT, RDT, NCH, true>), dim3((unsigned)blocks), dim3(64 * wpb), lds, st, a);
+    if constexpr (GATHER) hipLaunchKernelGGL((ln_quant_kernel<XDT, RDT, NCH, true, true>), dim3((unsigned)blocks), dim3(64 * wpb), lds, st, a);
+    else if (has_ln) hipLaunchKernelGGL((ln_quant_kernel<XDT, RDT, NCH, true>), dim3((unsigned)blocks), dim3(64 * wpb), lds, st, a);
     else hipLaunchKernelGGL((ln_quant_kernel<XDT, RDT, NCH, false>), dim3((unsigned)blocks), dim3(64 * wpb), lds, st, a);
     return hero_launch_status();
 }
@@ -338,6 +376,16 @@ hero_status launch_r(const LnArgs& a, hipStream_t st) {
     if (nch <= 2) return launch_nch<XDT, RDT, 2>(a, st);
     if (nch <= 4) return launch_nch<XDT, RDT, 4>(a, st);
     if (nch <= 8) return launch_nch<XDT, RDT, 8>(a, st);
+    return HERO_ERR_UNSUPPORTED;
+}
+
+template <int RDT>
+hero_status launch_gather(const LnArgs& a, hipStream_t st) {
+    const int nch = (a.D + 16 * HERO_WAVE - 1) / (16 * HERO_WAVE);
+    if (nch <= 1) return launch_nch<HERO_I8, RDT, 1, true>(a, st);
+    if (nch <= 2) return launch_nch<HERO_I8, RDT, 2, true>(a, st);
+    if (nch <= 4) return launch_nch<HERO_I8, RDT, 4, true>(a, st);
+    if (nch <= 8) return launch_nch<HERO_I8, RDT, 8, true>(a, st);
     return HERO_ERR_UNSUPPORTED;
 }
 
@@ -380,7 +428,34 @@ extern "C" hero_status hero_ln_quant(const void* x, hero_dtype x_dt, const float
     a.gamma = gamma; a.beta = beta; a.eps = eps; a.M = M; a.D = (int)D;
     a.y_q = y_q; a.y_scale = y_scale; a.y_hp = y_hp;
     a.x_dt = (int)x_dt; a.r_dt = r ? (int)r_dt : -1; a.hp_dt = y_hp ? (int)y_hp_dt : -1;
+    a.x_idx = a.r_idx = a.r2_idx = nullptr; a.r2 = nullptr; a.x_rows = a.r_rows = a.r2_rows = 0;
     hipStream_t st = (hipStream_t)stream;
     if (x_i8) return launch<HERO_I8>(a, st);
     return x_dt == HERO_BF16 ? launch<HERO_BF16>(a, st) : launch<HERO_F16>(a, st);
+}
+
+extern "C" hero_status hero_embed_ln_quant(const int32_t* tok_ids, const int32_t* pos_ids, const int32_t* type_ids,
+                                           const int8_t* tok_table, const float* tok_scale, int64_t V,
+                                           const void* pos_table, int64_t P,
+                                           const void* type_table, int64_t NT, hero_dtype pt_dt,
+                                           const float* gamma, const float* beta, float eps,
+                                           int64_t T, int64_t D, int8_t* y_q, float* y_scale, void* stream) {
+    if (T < 0 || D <= 0 || V <= 0 || P <= 0 || V > 0x7fffffffLL || P > 0x7fffffffLL) return HERO_ERR_SHAPE;
+    if (type_table && (NT <= 0 || NT > 0x7fffffffLL)) return HERO_ERR_SHAPE;
+    if (D % 16 != 0 || D > 8192) return HERO_ERR_UNSUPPORTED;
+    if (pt_dt != HERO_BF16 && pt_dt != HERO_F16) return HERO_ERR_UNSUPPORTED;
+    if (T == 0) return HERO_OK;
+    if (!tok_ids || !pos_ids || !tok_table || !tok_scale || !pos_table || !gamma || !y_q || !y_scale) return HERO_ERR_NULL;
+    if (type_table && !type_ids) return HERO_ERR_NULL;
+    if (!hero_aligned16(tok_table) || !hero_aligned16(pos_table) || !hero_aligned16(type_table) || !hero_aligned16(y_q))
+        return HERO_ERR_ALIGN;
+    LnArgs a;
+    a.x = tok_table; a.x_row_scale = tok_scale; a.r = pos_table; a.r_col_scale = nullptr;
+    a.gamma = gamma; a.beta = beta; a.eps = eps; a.M = T; a.D = (int)D;
+    a.y_q = y_q; a.y_scale = y_scale; a.y_hp = nullptr;
+    a.x_dt = HERO_I8; a.r_dt = (int)pt_dt; a.hp_dt = -1;
+    a.x_idx = tok_ids; a.r_idx = pos_ids; a.r2 = type_table; a.r2_idx = type_table ? type_ids : nullptr;
+    a.x_rows = (int)V; a.r_rows = (int)P; a.r2_rows = type_table ? (int)NT : 0;
+    hipStream_t st = (hipStream_t)stream;
+    return pt_dt == HERO_BF16 ? launch_gather<HERO_BF16>(a, st) : launch_gather<HERO_F16>(a, st);
 }

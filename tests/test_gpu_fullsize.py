@@ -40,6 +40,32 @@ def test_ln_quant_full_size_sampled_rows(hero, T, D, form):
     assert (qa == 127).all() and (to_np(s) > 0).all()
 
 
+def test_embed_ln_quant_full_size_sampled_rows(hero):
+    """BERT-large embedding at the benchmark's batch (32 x 512 tokens, d = 1024, 30522-row token table)."""
+    B, S, d, V = 32, 512, 1024, 30522
+    T = B * S
+    tb = synth.embedding_tables(2050, d, V, S, 2)
+    ids = synth.embedding_ids(2051, B, S, V, 2)
+    tq, ts = O.quant_twq(tb["tok"])
+    pos16, typ16 = O.f32_to_bf16(tb["pos"]), O.f32_to_bf16(tb["type"])
+    g = synth.rng(2052)
+    gam = (1 + 0.1 * g.standard_normal(d)).astype(np.float32)
+    bet = (0.02 * g.standard_normal(d)).astype(np.float32)
+    q, s = hero.hero_embed_ln_quant(dev(ids["tok"]), dev(ids["pos"]), dev(ids["type"]), dev(tq), dev(ts), dev(pos16),
+                                    dev(typ16), dev(gam), dev(bet), 1e-12)
+    rows = np.unique(np.concatenate([g.integers(0, T, 80), [0, 1, 2, 3, T - 1, T - 2, 4095, 4096, 8191, 8192]]))
+    q_o, s_o = O.embed_ln_quant(ids["tok"][rows], ids["pos"][rows], ids["type"][rows], tq, ts, pos16, typ16, O.BF16,
+                                gam, bet, 1e-12)
+    assert_scales(to_np(s)[rows], s_o)
+    assert_codes(to_np(q)[rows], q_o, "sampled rows")
+    qa = np.abs(to_np(q).astype(np.int16)).max(axis=1)
+    assert (qa == 127).all() and (to_np(s) > 0).all()
+    # equal (token, position, type) triples give equal rows
+    key = ids["tok"].astype(np.int64) * 2048 + ids["pos"] * 2 + ids["type"]
+    _, first, inv = np.unique(key, return_index=True, return_inverse=True)
+    assert np.array_equal(to_np(q), to_np(q)[first][inv])
+
+
 @pytest.mark.parametrize("cfg", [2, 3])
 def test_int8_attn_full_size_sampled_heads(hero, cfg):
     shape = synth.CONFIGS[cfg]

@@ -85,6 +85,38 @@ def test_ln_quant_rejects_bad_arguments(hero):
     assert q.shape == (0, 64)
 
 
+# ============================================================ embedding LN^quant
+@pytest.mark.parametrize("B,S,d,V,typed,dt", [(3, 50, 768, 1000, True, "bf16"), (2, 37, 1024, 333, True, "f16"),
+                                                (5, 16, 48, 64, False, "bf16"), (1, 9, 4096, 100, True, "bf16"),
+                                                (8, 128, 1536, 2000, False, "f16")])
+def test_embed_ln_quant(hero, B, S, d, V, typed, dt):
+    """Sec. 2.2.1: INT8 token table with per-row scales + 16-bit position / type tables -> LN -> TWQ INT8;
+    +-1 LSB class like every LayerNorm-fused path."""
+    tb = synth.embedding_tables(40 + d, d, V, S + 3, 2)
+    ids = synth.embedding_ids(41 + d, B, S, V, 2)
+    tq, ts = O.quant_twq(tb["tok"])
+    odt, tdt = (O.BF16, torch.bfloat16) if dt == "bf16" else (O.F16, torch.float16)
+    cvt = O.f32_to_bf16 if dt == "bf16" else O.f32_to_f16
+    pos16, typ16 = cvt(tb["pos"]), cvt(tb["type"])
+    g = synth.rng(42 + d)
+    gam = (1 + 0.1 * g.standard_normal(d)).astype(np.float32)
+    bet = (0.02 * g.standard_normal(d)).astype(np.float32)
+    q_o, s_o = O.embed_ln_quant(ids["tok"], ids["pos"], ids["type"] if typed else None, tq, ts, pos16,
+                                typ16 if typed else None, odt, gam, bet, 1e-12)
+    q, s = hero.hero_embed_ln_quant(dev(ids["tok"]), dev(ids["pos"]), dev(ids["type"]) if typed else None, dev(tq), dev(ts),
+                                    dev(pos16, tdt), dev(typ16, tdt) if typed else None, dev(gam), dev(bet), 1e-12)
+    assert_scales(to_np(s), s_o, "y_scale")
+    assert_codes(to_np(q), q_o, "y_q")
+    # an index outside its table is clamped (no fault, the other rows unaffected)
+    bad = ids["tok"].copy(); bad[0] = V + 7; bad[1] = -3
+    q2, s2 = hero.hero_embed_ln_quant(dev(bad), dev(ids["pos"]), dev(ids["type"]) if typed else None, dev(tq), dev(ts),
+                                      dev(pos16, tdt), dev(typ16, tdt) if typed else None, dev(gam), dev(bet), 1e-12)
+    assert np.array_equal(to_np(q2)[2:], to_np(q)[2:])
+    with pytest.raises(HB.HeroError):
+        hero.hero_embed_ln_quant(dev(ids["tok"]), dev(ids["pos"]), None, dev(tq), dev(ts), dev(pos16, tdt),
+                                 dev(typ16, tdt), dev(gam), dev(bet), 1e-12)           # type table without type ids
+
+
 # ============================================================ GeMM^quant
 GEMM_SHAPES = [(128, 128, 64), (200, 200, 256), (512, 384, 1024), (77, 1000, 192), (1, 64, 4096), (300, 72, 768)]
 
