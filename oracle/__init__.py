@@ -148,6 +148,26 @@ def weight_quant(W: np.ndarray):
     return Wt, s
 
 
+def weight_fold_quant(W, row_mult=None, col_div=None):
+    """Fold static activation scales into a weight and quantize it column-wise (Sec. 2.2.2: W~_q = W_q / S_q,
+    W~_o = S_attn W_o / S_o; Sec. 2.2.3: W~_2 = S_a W_2 / S_x2; Sec. 2.1 column-wise weight scales):
+    W~[k][n] = row_mult[k] * W[k][n] / col_div[n] in fp64 (multiply, then divide), one cast to fp32, then
+    weight_quant.  W is [K, N]; returns codes [N, K] and scales [N]."""
+    Wd = np.asarray(W, np.float64)
+    if row_mult is not None:
+        Wd = np.asarray(row_mult, np.float64)[:, None] * Wd
+    if col_div is not None:
+        Wd = Wd / np.asarray(col_div, np.float64)[None, :]
+    return weight_quant(Wd.astype(np.float32))
+
+
+def absmax_cols(x, running=None):
+    """Calibration statistic of FWQ / SQ (Sec. 2.1, Sec. 3: the range recorded over calibration data, no
+    truncation): per-column max |x| over the rows, combined with a running maximum.  x fp32 [T, D]."""
+    m = np.abs(np.asarray(x, np.float32)).max(axis=0) if len(x) else np.zeros(np.shape(x)[1], np.float32)
+    return m if running is None else np.maximum(m, np.asarray(running, np.float32))
+
+
 # ------------------------------------------------------------------ O3 / O4
 def gemm_i32(A: np.ndarray, Bt: np.ndarray) -> np.ndarray:
     A = np.ascontiguousarray(A, np.int8)

@@ -131,7 +131,7 @@ def prepare(p, sc, shape, mode=MODE_M3):
         div = np.concatenate([np.full(d, float(sc["S_q"])), np.full(d, float(sc["S_k"])), np.full(d, float(sc["S_v"]))])
     else:
         div = np.ones(3 * d)
-    w["wq_qkv"], w["s_qkv"] = O.weight_quant((P["w_qkv"] / div).astype(np.float32))
+    w["wq_qkv"], w["s_qkv"] = O.weight_fold_quant(P["w_qkv"], None, div)
     w["b_qkv"] = (P["b_qkv"] / div).astype(np.float32)
     w["qk_scale"] = np.float32(float(sc["S_q"]) * float(sc["S_k"]) / math.sqrt(shape.Dh))
     w["bf16_qk_scale"] = np.float32(1.0 / math.sqrt(shape.Dh))
@@ -142,29 +142,25 @@ def prepare(p, sc, shape, mode=MODE_M3):
     # --- attention output linear
     post = shape.arch == POST_LN
     if mode & M_ATTN_OUT:
-        wo = sc["S_attn"].astype(np.float64)[:, None] * P["w_o"]
         bo = P["b_o"]
         if post:
-            wo = wo / sc["S_o"].astype(np.float64)[None, :]
             bo = bo / sc["S_o"].astype(np.float64)
-        w["wq_o"], w["s_o_w"] = O.weight_quant(wo.astype(np.float32))
+        w["wq_o"], w["s_o_w"] = O.weight_fold_quant(P["w_o"], sc["S_attn"], sc["S_o"] if post else None)
         w["b_o"] = bo.astype(np.float32)
     else:
         w["wb_o"] = _bf16(P["w_o"].T.copy())
         w["b_o"] = P["b_o"].astype(np.float32)
     w["S_o"] = sc["S_o"]
     # --- FC1 (always INT8 in Table 1); GELU^quant divides by S_a, nothing to fold
-    w["wq_1"], w["s_1"] = O.weight_quant(P["w_1"].astype(np.float32))
+    w["wq_1"], w["s_1"] = O.weight_fold_quant(P["w_1"])
     w["b_1"] = P["b_1"].astype(np.float32)
     w["S_a"] = sc["S_a"]
     # --- FC2
     if mode & M_FC2:
-        w2 = sc["S_a"].astype(np.float64)[:, None] * P["w_2"]
         b2 = P["b_2"]
         if post:
-            w2 = w2 / sc["S_x2"].astype(np.float64)[None, :]
             b2 = b2 / sc["S_x2"].astype(np.float64)
-        w["wq_2"], w["s_2_w"] = O.weight_quant(w2.astype(np.float32))
+        w["wq_2"], w["s_2_w"] = O.weight_fold_quant(P["w_2"], sc["S_a"], sc["S_x2"] if post else None)
         w["b_2"] = b2.astype(np.float32)
     else:
         w["wb_2"] = _bf16(P["w_2"].T.copy())

@@ -138,6 +138,54 @@ def test_fwq_uses_column_scales_and_weight_quant_layout():
 
 
 # ---------------------------------------------------------------- O3 integer GEMM
+def test_weight_fold_quant_and_absmax_cols():
+    """Fold + column-wise quantization (Sec. 2.2.2 / 2.2.3 folds, Sec. 2.1 column scales) and the calibration
+    statistic.  Pins: power-of-two multipliers fold exactly, so the codes must equal those of the unfolded
+    matrix and the scales shift by the same powers; an exact-rational re-derivation of every code on a small
+    matrix; the half-step property codes * scale ~ folded W; brute-force column maxima."""
+    g = synth.rng(13)
+    K, N = 24, 10
+    W = g.standard_normal((K, N)).astype(np.float32)
+    q0, s0 = O.weight_quant(W)
+    rm = np.float32(2.0) ** g.integers(-3, 4, K)
+    cd = np.float32(2.0) ** g.integers(-3, 4, N)
+    q1, s1 = O.weight_fold_quant(W, None, cd)
+    assert np.array_equal(q1, q0) and np.array_equal(s1, s0 / cd)
+    # general multipliers: exact rationals
+    rm = g.uniform(0.01, 2.0, K).astype(np.float32)
+    cd = g.uniform(0.01, 2.0, N).astype(np.float32)
+    q, s = O.weight_fold_quant(W, rm, cd)
+    assert q.shape == (N, K) and s.shape == (N,)
+    fr = lambda v: Fraction(float(v))
+    for n in range(N):
+        col = []
+        for k in range(K):
+            t = float(np.float64(rm[k]) * np.float64(W[k, n]))             # fp64 product, then fp64 quotient, then fp32
+            col.append(np.float32(np.float64(t) / np.float64(cd[n])))
+        amax = max(abs(float(c)) for c in col)
+        sc = np.float32(np.float32(amax) / np.float32(127))
+        assert s[n] == sc
+        for k in range(K):
+            quo = np.float32(col[k]) / sc                                   # IEEE fp32 quotient
+            exact = fr(quo)
+            lo = math.floor(exact)
+            code = lo if exact - lo < Fraction(1, 2) else lo + 1 if exact - lo > Fraction(1, 2) else lo + (lo % 2)
+            assert q[n, k] == max(-127, min(127, code))
+        exactW = [fr(rm[k]) * fr(W[k, n]) / fr(cd[n]) for k in range(K)]
+        assert all(abs(Fraction(int(q[n, k])) * fr(s[n]) - exactW[k]) <= fr(s[n]) * Fraction(501, 1000) for k in range(K))
+    # only the row multipliers / nothing at all
+    q2, s2 = O.weight_fold_quant(W, rm, None)
+    q3, s3 = O.weight_quant((rm[:, None].astype(np.float64) * W).astype(np.float32))
+    assert np.array_equal(q2, q3) and np.array_equal(s2, s3)
+    assert all(np.array_equal(a, b) for a, b in zip(O.weight_fold_quant(W), (q0, s0)))
+    # calibration statistic: brute force, running maximum, sign-insensitive
+    x = g.standard_normal((17, 6)).astype(np.float32)
+    m = O.absmax_cols(x)
+    assert all(m[j] == max(abs(float(x[i, j])) for i in range(17)) for j in range(6))
+    run = np.float32([0, 10, 0, 0.5, 0, 0])
+    assert np.array_equal(O.absmax_cols(x, run), np.maximum(m, run)) and np.array_equal(O.absmax_cols(-x), m)
+
+
 def test_gemm_int_exact():
     g = synth.rng(6)
     A = g.integers(-127, 128, (37, 200), dtype=np.int8)
