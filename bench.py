@@ -85,8 +85,8 @@ class Stack:
         for l in range(self.layers):
             p = {k: torch.from_numpy(v).to(dev) for k, v in synth.layer_params(seed, shape, l).items()}
             sc, xc = prep.calibrate(p, xc, shape.arch, shape.H, shape.Dh, shape.eps,
-                                    cal_mask if cal_mask != HB.MASK_PADDING else HB.MASK_NONE, Bc, Sc)
-            t, qk, ps = prep.prepare(p, sc, shape.arch, d, shape.Dh, mode)
+                                    cal_mask if cal_mask != HB.MASK_PADDING else HB.MASK_NONE, Bc, Sc, hero=hero)
+            t, qk, ps = prep.prepare(p, sc, shape.arch, d, shape.Dh, mode, hero=hero)
             self.keep.append(t)
             self.weights.append(hero.layer_weights(t, qk, ps))
             del p

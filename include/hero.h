@@ -262,6 +262,29 @@ hero_status hero_bf16_attn(const void* q, const int64_t q_strides[4],
                            int64_t B, int64_t H, int64_t Sq, int64_t Skv, int64_t Dh, float scale,
                            hero_mask mask, const int32_t* kv_len, void* out, int64_t ldo, void* stream);
 
+/* Model-load-time operators (not on the hot path): the pre-processing phase of the method on the GPU.
+ *
+ * hero_absmax_cols -- calibration statistic of the static scales (Sec. 2.1: FWQ / SQ scales are
+ *   calibrated in a pre-processing phase; Sec. 3: ranges recorded over calibration batches):
+ *     col_absmax[j] = max(col_absmax[j], max_i |x[i][j]|)
+ *   x [T,D] HERO_F32 / HERO_BF16 / HERO_F16, leading dimension ldx; col_absmax f32[D] is a RUNNING
+ *   maximum (in/out: zero it before the first batch).  An FWQ scale is col_absmax[j] / 127, an SQ
+ *   scale the maximum over j divided by 127.  Exact (a maximum has no rounding).
+ *
+ * hero_weight_fold_quant -- scale folding (Sec. 2.2.2: W~_q = W_q / S_q, W~_o = S_attn W_o / S_o;
+ *   Sec. 2.2.3: W~_2 = S_a W_2 / S_x2) and column-wise weight quantization (Sec. 2.1):
+ *     W~[k][n] = row_mult[k] * W[k][n] / col_div[n]     fp64: multiply, then divide; one cast to fp32
+ *     col_scale[n] = max_k |W~[k][n]| / 127  (1 for an all-zero column)
+ *     Wt[n][k] = sat(rne(W~[k][n] / col_scale[n]))       IEEE fp32 division
+ *   W [K,N] f32 row-major (the paper's W: input rows, output columns), leading dimension ldw;
+ *   row_mult f32[K] or NULL (= 1), col_div f32[N] or NULL (= 1); Wt [N,K] int8, leading dimension
+ *   ldwt (K contiguous: the operand layout of hero_int8_gemm); col_scale f32[N].
+ * Both return HERO_ERR_SHAPE / HERO_ERR_NULL / HERO_ERR_UNSUPPORTED before any launch. */
+hero_status hero_absmax_cols(const void* x, hero_dtype x_dt, int64_t ldx, int64_t T, int64_t D,
+                             float* col_absmax, void* stream);
+hero_status hero_weight_fold_quant(const float* W, int64_t ldw, const float* row_mult, const float* col_div,
+                                   int64_t K, int64_t N, int8_t* Wt, int64_t ldwt, float* col_scale, void* stream);
+
 /* Library build identification: target architecture string, e.g. "gfx950". */
 const char* hero_build_arch(void);
 

@@ -44,6 +44,8 @@ SYMBOLS = {
     "hero_build_arch": (C.c_char_p, []),
     "hero_ln_quant": (i32, [vp, i32, vp, vp, i32, vp, vp, vp, f32, i64, i64, vp, vp, vp, i32, vp]),
     "hero_embed_ln_quant": (i32, [vp, vp, vp, vp, vp, i64, vp, i64, vp, i64, i32, vp, vp, f32, i64, i64, vp, vp, vp]),
+    "hero_absmax_cols": (i32, [vp, i32, i64, i64, i64, vp, vp]),
+    "hero_weight_fold_quant": (i32, [vp, i64, vp, vp, i64, i64, vp, i64, vp, vp]),
     "hero_int8_gemm": (i32, [vp, i64, vp, vp, i64, vp, vp, vp, i32, i64, i32, vp, vp, i32, i64, i64, i64, i64, vp]),
     "hero_int8_gemm_workspace_bytes": (C.c_size_t, [i64, i64, i64]),
     "hero_int8_gemm_ws": (i32, [vp, i64, vp, vp, i64, vp, vp, vp, i32, i64, i32, vp, vp, i32, i64, i64, i64, i64,
@@ -130,6 +132,27 @@ class Hero:
                                           _ptr(gamma), _ptr(beta), float(eps), T, D, _ptr(y_q), _ptr(y_scale), _stream(stream))
         self._check(st)
         return y_q, y_scale
+
+    # ------------------------------------------------------------------ model-load-time operators
+    def hero_absmax_cols(self, x, col_absmax=None, stream=None):
+        """Running per-column max |x| (x [T,D] f32 / bf16 / f16).  Returns the updated f32[D] tensor."""
+        T, D = x.shape
+        assert x.stride(1) == 1
+        if col_absmax is None:
+            col_absmax = torch.zeros(D, dtype=torch.float32, device=x.device)
+        self._check(self.lib.hero_absmax_cols(_ptr(x), _DT[x.dtype], x.stride(0) if T > 1 else max(D, x.stride(0)), T, D,
+                                              _ptr(col_absmax), _stream(stream)))
+        return col_absmax
+
+    def hero_weight_fold_quant(self, W, row_mult=None, col_div=None, stream=None):
+        """W [K,N] f32 -> (codes [N,K] int8, col_scale [N] f32) of row_mult[:,None] * W / col_div[None,:]."""
+        K, N = W.shape
+        assert W.dtype == torch.float32 and W.stride(1) == 1
+        Wt = torch.empty((N, K), dtype=torch.int8, device=W.device)
+        s = torch.empty(N, dtype=torch.float32, device=W.device)
+        self._check(self.lib.hero_weight_fold_quant(_ptr(W), W.stride(0) if K > 1 else max(N, W.stride(0)), _ptr(row_mult),
+                                                    _ptr(col_div), K, N, _ptr(Wt), K, _ptr(s), _stream(stream)))
+        return Wt, s
 
     # ------------------------------------------------------------------ GeMM^quant
     def hero_int8_gemm(self, A, Bt, a_row_scale=None, b_col_scale=None, bias=None, residual=None,

@@ -68,12 +68,21 @@ def _scale(a, dim=None):
     return (m / 127.0).float()
 
 
-def calibrate(p, x_calib, arch, H, Dh, eps, mask, B, S, kv_len=None):
-    """Static scales: SQ scalars for X_q, X_k, X_v; FWQ vectors for X_attn, X_o, A, X_2."""
+def calibrate(p, x_calib, arch, H, Dh, eps, mask, B, S, kv_len=None, hero=None):
+    """Static scales: SQ scalars for X_q, X_k, X_v; FWQ vectors for X_attn, X_o, A, X_2.  With `hero` (the
+    loaded library) the column maxima come from hero_absmax_cols (a maximum is exact in any precision)."""
     t = reference_layer(p, x_calib, arch, H, Dh, eps, mask, B, S, kv_len)
-    sc = {"S_q": _scale(t["q"]), "S_k": _scale(t["k"]), "S_v": _scale(t["v"]),
-          "S_attn": _scale(t["attn"], 0), "S_o": _scale(t["o"], 0), "S_a": _scale(t["a"], 0),
-          "S_x2": _scale(t["x2"], 0), "S_p": torch.tensor(1.0 / 255.0, dtype=torch.float32, device=x_calib.device)}
+    if hero is not None:
+        def scale(a, dim=None):
+            m = hero.hero_absmax_cols(a.float().contiguous()).double()
+            m = m.amax() if dim is None else m
+            m = torch.where(m == 0, torch.full_like(m, 127.0), m)
+            return (m / 127.0).float()
+    else:
+        scale = _scale
+    sc = {"S_q": scale(t["q"]), "S_k": scale(t["k"]), "S_v": scale(t["v"]),
+          "S_attn": scale(t["attn"], 0), "S_o": scale(t["o"], 0), "S_a": scale(t["a"], 0),
+          "S_x2": scale(t["x2"], 0), "S_p": torch.tensor(1.0 / 255.0, dtype=torch.float32, device=x_calib.device)}
     return sc, t["out"]
 
 
@@ -87,39 +96,49 @@ def quantize_columns(W):
     return q.t().contiguous(), s.contiguous()
 
 
-def prepare(p, sc, arch, d, Dh, mode=HB.MODE_M3):
+def prepare(p, sc, arch, d, Dh, mode=HB.MODE_M3, hero=None):
     """Fold the static scales into the weights and quantize.  Returns (tensors, qk_scale,
-    p_scale): `tensors` is keyed by the field names of hero_layer_weights."""
+    p_scale): `tensors` is keyed by the field names of hero_layer_weights.  With `hero` (the loaded
+    library) the fold + column-wise quantization runs in hero_weight_fold_quant on the weights' device."""
     P = {k: v.double() for k, v in p.items()}
     post = arch == HB.ARCH_POST_LN
     t = {}
+    if hero is not None:
+        f32 = lambda a: None if a is None else a.float().contiguous()
+
+        def quantize_folded(name, rm, cd):
+            return hero.hero_weight_fold_quant(p[name].float().contiguous(), f32(rm), f32(cd))
+    else:
+        def quantize_folded(name, rm, cd):
+            W = P[name]
+            if rm is not None:
+                W = rm.double()[:, None] * W
+            if cd is not None:
+                W = W / cd.double()[None, :]
+            return quantize_columns(W)
     if mode & HB.M_ATTN:
         div = torch.cat([sc["S_q"].double().expand(d), sc["S_k"].double().expand(d), sc["S_v"].double().expand(d)])
         qk_scale = float(sc["S_q"].double() * sc["S_k"].double() / math.sqrt(Dh))
     else:
         div = torch.ones(3 * d, dtype=torch.float64, device=P["w_qkv"].device)
         qk_scale = 1.0 / math.sqrt(Dh)
-    t["w_qkv"], t["w_qkv_s"] = quantize_columns(P["w_qkv"] / div)
+    t["w_qkv"], t["w_qkv_s"] = quantize_folded("w_qkv", None, div if mode & HB.M_ATTN else None)
     t["b_qkv"] = (P["b_qkv"] / div).float()
     pv = sc["S_p"].double() * sc["S_v"].double()
     if mode & HB.M_ATTN_OUT:
         t["attn_out_scale"] = (pv / sc["S_attn"].double()).float()
-        wo, bo = sc["S_attn"].double()[:, None] * P["w_o"], P["b_o"]
-        if post:
-            wo, bo = wo / sc["S_o"].double()[None, :], bo / sc["S_o"].double()
-        t["w_o"], t["w_o_s"] = quantize_columns(wo)
+        bo = P["b_o"] / sc["S_o"].double() if post else P["b_o"]
+        t["w_o"], t["w_o_s"] = quantize_folded("w_o", sc["S_attn"], sc["S_o"] if post else None)
         t["b_o"] = bo.float()
     else:
         t["attn_out_scale"] = pv.float().reshape(1)
         t["w_o_bf16"] = P["w_o"].t().contiguous().to(torch.bfloat16)
         t["b_o"] = P["b_o"].float()
-    t["w_1"], t["w_1_s"] = quantize_columns(P["w_1"])
+    t["w_1"], t["w_1_s"] = quantize_folded("w_1", None, None)
     t["b_1"] = P["b_1"].float()
     if mode & HB.M_FC2:
-        w2, b2 = sc["S_a"].double()[:, None] * P["w_2"], P["b_2"]
-        if post:
-            w2, b2 = w2 / sc["S_x2"].double()[None, :], b2 / sc["S_x2"].double()
-        t["w_2"], t["w_2_s"] = quantize_columns(w2)
+        b2 = P["b_2"] / sc["S_x2"].double() if post else P["b_2"]
+        t["w_2"], t["w_2_s"] = quantize_folded("w_2", sc["S_a"], sc["S_x2"] if post else None)
         t["b_2"] = b2.float()
     else:
         t["w_2_bf16"] = P["w_2"].t().contiguous().to(torch.bfloat16)

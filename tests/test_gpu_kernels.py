@@ -85,6 +85,44 @@ def test_ln_quant_rejects_bad_arguments(hero):
     assert q.shape == (0, 64)
 
 
+# ============================================================ model-load-time operators
+@pytest.mark.parametrize("K,N", [(768, 2304), (100, 37), (1024, 4096), (4096, 1024), (65, 130)])
+def test_weight_fold_quant_bit_exact(hero, K, N):
+    """Fold (fp64, multiply then divide, one cast) + column-wise quantization: codes and scales bit-exact."""
+    g = synth.rng(900 + K)
+    W = (g.standard_normal((K, N)) * 0.02).astype(np.float32)
+    W[:, min(3, N - 1)] = 0                                              # an all-zero column: scale 1, codes 0
+    rm = g.uniform(0.001, 0.05, K).astype(np.float32)
+    cd = g.uniform(0.002, 0.3, N).astype(np.float32)
+    for a, b in ((rm, cd), (None, cd), (rm, None), (None, None)):
+        q_o, s_o = O.weight_fold_quant(W, a, b)
+        q, s = hero.hero_weight_fold_quant(dev(W), dev(a), dev(b))
+        assert_exact(to_np(s), s_o, "column scales")
+        assert_exact(to_np(q), q_o, "codes")
+    # a strided view (leading dimension > N)
+    Wbig = dev(np.concatenate([W, W], axis=1))
+    q, s = hero.hero_weight_fold_quant(Wbig[:, :N], dev(rm), dev(cd))
+    q_o, s_o = O.weight_fold_quant(W, rm, cd)
+    assert_exact(to_np(q), q_o) and assert_exact(to_np(s), s_o)
+
+
+@pytest.mark.parametrize("T,D,dt", [(1000, 768, "f32"), (37, 50, "bf16"), (4096, 1024, "bf16"), (513, 4096, "f16"), (1, 16, "f32")])
+def test_absmax_cols_exact_and_running(hero, T, D, dt):
+    g = synth.rng(950 + D)
+    x = (g.standard_normal((T, D)) * g.uniform(0.1, 30, D)).astype(np.float32)
+    if dt == "f32":
+        xd, xr = dev(x), x
+    elif dt == "bf16":
+        xb = O.f32_to_bf16(x); xd, xr = dev(xb, torch.bfloat16), O.bf16_to_f32(xb)
+    else:
+        xb = O.f32_to_f16(x); xd, xr = dev(xb, torch.float16), O.f16_to_f32(xb)
+    m = hero.hero_absmax_cols(xd)
+    assert_exact(to_np(m), O.absmax_cols(xr), "first batch")
+    x2 = (xr * np.float32(0.5)); x2[T // 2, D // 3] = np.float32(1e4)
+    m2 = hero.hero_absmax_cols(dev(x2), m)                               # running maximum, second batch in f32
+    assert_exact(to_np(m2), O.absmax_cols(x2, O.absmax_cols(xr)), "running maximum")
+
+
 # ============================================================ embedding LN^quant
 @pytest.mark.parametrize("B,S,d,V,typed,dt", [(3, 50, 768, 1000, True, "bf16"), (2, 37, 1024, 333, True, "f16"),
                                                 (5, 16, 48, 64, False, "bf16"), (1, 9, 4096, 100, True, "bf16"),
