@@ -273,6 +273,10 @@ extern "C" hero_status hero_bf16_gemm(const void* A, int64_t lda, const void* Wt
     if (M == 0 || N == 0) return HERO_OK;
     if (!A || !Wt || !C) return HERO_ERR_NULL;
     if (lda % 8 || ldb % 8 || ldc % 4 || !hero_aligned16(A) || !hero_aligned16(Wt) || !hero_aligned16(C)) return HERO_ERR_ALIGN;
+    if (!residual || (ldr % 8 == 0 && hero_aligned16(residual))) {        // large problems: the persistent 256x256 kernel
+        const hero_status big = hero_bf16_gemm_large(A, lda, Wt, ldb, bias, residual, ldr, gelu, C, ldc, M, N, K, (hipStream_t)stream);
+        if (big != HERO_ERR_UNSUPPORTED) return big;
+    }
     if ((M + 127) / 128 > 65535) return HERO_ERR_UNSUPPORTED;
     BGemmArgs g;
     g.A = (const uint16_t*)A; g.lda = lda; g.Wt = (const uint16_t*)Wt; g.ldb = ldb; g.bias = bias;

@@ -120,8 +120,9 @@ __device__ __forceinline__ void store_piece(int8_t* cp, const uint32_t (&d)[ND],
     }
 }
 
-template <int BM, int BN, int WM, int WN, int EPI, int CDT, int RDT, bool OS_RAW = false>
-__device__ __forceinline__ void epilogue_direct(const GemmArgs& g, v16i (&acc)[BM / WM / 32][BN / WN / 32],
+// ACC is v16i (INT8 operands) or v16f (bf16 operands: UNIT, no scales, y = acc + bias).
+template <int BM, int BN, int WM, int WN, int EPI, int CDT, int RDT, bool OS_RAW = false, bool UNIT = false, typename ACC = v16i>
+__device__ __forceinline__ void epilogue_direct(const GemmArgs& g, ACC (&acc)[BM / WM / 32][BN / WN / 32],
                                                 const float* sv, const float (&rsr)[BM / WM / 32],
                                                 int m0, int n0, int tid) {
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32, NQ = TN * 4, H = NQ / 2;
@@ -141,7 +142,7 @@ __device__ __forceinline__ void epilogue_direct(const GemmArgs& g, v16i (&acc)[B
 #pragma unroll
         for (int q = 0; q < NQ; ++q) {
             const int nl = wn * TN * 32 + q * 8 + hh * 4;
-            cs[q] = *reinterpret_cast<const v4f*>(sv + nl);
+            if (!UNIT) cs[q] = *reinterpret_cast<const v4f*>(sv + nl);
             bs[q] = *reinterpret_cast<const v4f*>(sv + BN + nl);
         }
     }
@@ -177,8 +178,11 @@ __device__ __forceinline__ void epilogue_direct(const GemmArgs& g, v16i (&acc)[B
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
                     float v = (float)acc[i][j][4 * gq + t];
-                    if (has_rs) v = v * rs;
-                    v = fmaf(v, cs[q][t], bs[q][t]);
+                    if (UNIT) v = v + bs[q][t];
+                    else {
+                        if (has_rs) v = v * rs;
+                        v = fmaf(v, cs[q][t], bs[q][t]);
+                    }
                     if (EPI == HERO_EPI_DEQUANT_GELU || EPI == HERO_EPI_GELU_REQUANT) v = gelu_erf(v);
                     // GELU^quant is in the +-1 LSB class (fp32 GELU vs the definition's fp64), so the
                     // division by S_a[j] is a multiplication by its reciprocal
@@ -547,8 +551,20 @@ __device__ __forceinline__ void dma4s(uint32_t voff, const float* sbase, uint32_
                  :: "v"(voff), "s"(sbase), "s"(lds_base) : "memory", "m0");
 }
 
-template <int NS, int EPI, int CDT, int RDT>
+// ADT = HERO_I8: INT8 operands, int32 accumulators.  ADT = HERO_BF16: bf16 operands (the BF16 side of a
+// switched module, Sec. 2.3 / Table 1), fp32 accumulators, no scales; K, lda and ldb are then in BYTES,
+// and a 64-byte slab holds two v_mfma_f32_32x32x16_bf16 steps exactly as it holds two INT8 steps.
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+template <int ADT, typename ACC>
+__device__ __forceinline__ ACC mfma_step(v4i a, v4i b, ACC c) {
+    if constexpr (ADT == HERO_I8) return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0);
+    else return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a), __builtin_bit_cast(v8bf, b), c, 0, 0, 0);
+}
+
+template <int NS, int EPI, int CDT, int RDT, int ADT = HERO_I8>
 __global__ __launch_bounds__(512, 2) void int8_gemm_persistent_kernel(GemmArgs g) {
+    using ACC = typename std::conditional<ADT == HERO_I8, v16i, v16f>::type;
+    constexpr bool UNIT = ADT != HERO_I8;
     constexpr int BM = 256, BN = 256, WM = 2, WN = 4;
     constexpr int NT = WM * WN * 64, NWAVE = WM * WN;
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
@@ -601,7 +617,7 @@ __global__ __launch_bounds__(512, 2) void int8_gemm_persistent_kernel(GemmArgs g
         const uint32_t cn = (uint32_t)min(ch + lane, g.N - 1 - n0i) * 4u, cm = (uint32_t)min(ch + lane, g.M - 1 - m0i) * 4u;
         if (EPI == HERO_EPI_RAW_I32) return;
         if (which == 0) {
-            dma4s(cn, g.b_col_scale + n0i, dst);
+            if (!UNIT) dma4s(cn, g.b_col_scale + n0i, dst);
             if (EPI == HERO_EPI_GELU_REQUANT) dma4s(cn, g.out_col_scale + n0i, dst + 2 * BN * 4);
         } else {
             if (has_bias) dma4s(cn, g.bias + n0i, dst + BN * 4);
@@ -648,7 +664,7 @@ __global__ __launch_bounds__(512, 2) void int8_gemm_persistent_kernel(GemmArgs g
     for (;;) {
         int m0, n0;
         tile_from_seq<BM, BN>(g, seq, m0, n0);
-        v16i acc[TM][TN];
+        ACC acc[TM][TN];
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -670,7 +686,7 @@ __global__ __launch_bounds__(512, 2) void int8_gemm_persistent_kernel(GemmArgs g
 #pragma unroll
             for (int n = 0; n < NM; ++n) {                             // k-step 0
                 const int jj = n / TM, ii = n % TM;
-                acc[ii][jj] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f0[jj], f0[TN + ii], acc[ii][jj], 0, 0, 0);
+                acc[ii][jj] = mfma_step<ADT>(f0[jj], f0[TN + ii], acc[ii][jj]);
                 if (n < NFR) f1[n] = *reinterpret_cast<const v4i*>(st + fo[1][n]);
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -680,7 +696,7 @@ __global__ __launch_bounds__(512, 2) void int8_gemm_persistent_kernel(GemmArgs g
 #pragma unroll
             for (int n = 0; n < NM; ++n) {                             // k-step 1
                 const int jj = n / TM, ii = n % TM;
-                acc[ii][jj] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f1[jj], f1[TN + ii], acc[ii][jj], 0, 0, 0);
+                acc[ii][jj] = mfma_step<ADT>(f1[jj], f1[TN + ii], acc[ii][jj]);
                 if (n < NFR) f0[n] = *reinterpret_cast<const v4i*>(stn + fo[0][n]);
                 if (n < NW) issue(n, pstage);
                 __builtin_amdgcn_sched_barrier(0);
@@ -693,7 +709,7 @@ __global__ __launch_bounds__(512, 2) void int8_gemm_persistent_kernel(GemmArgs g
         float rsr[TM];
 #pragma unroll
         for (int i = 0; i < TM; ++i) rsr[i] = (EPI != HERO_EPI_RAW_I32 && has_rs) ? sv[3 * BN + wm * TM * 32 + i * 32 + ml] : 1.0f;
-        epilogue_direct<BM, BN, WM, WN, EPI, CDT, RDT, true>(g, acc, sv, rsr, m0, n0, tid);
+        epilogue_direct<BM, BN, WM, WN, EPI, CDT, RDT, true, UNIT>(g, acc, sv, rsr, m0, n0, tid);
         seq += nslot;
         par ^= 1;
         if (seq >= seq_end) break;
@@ -845,6 +861,33 @@ hero_status launch_epi(const GemmArgs& g, void* ws, size_t ws_bytes, hipStream_t
 }
 
 }  // namespace
+
+// bf16 operands through the persistent 256x256 kernel (called by hero_bf16_gemm for large problems;
+// HERO_ERR_UNSUPPORTED means "not this kernel's case", the caller then uses its own).
+hero_status hero_bf16_gemm_large(const void* A, int64_t lda, const void* Wt, int64_t ldb,
+                                 const float* bias, const void* residual, int64_t ldr, int gelu,
+                                 void* C, int64_t ldc, int64_t M, int64_t N, int64_t K, hipStream_t st) {
+    const int64_t tiles = ((M + 255) / 256) * ((N + 255) / 256);
+    if (tiles < 96 || tiles > 0x7fffff00LL || K % 32 != 0 || K * 2 < 4 * BK || lda * 2 >= (1 << 24) || ldb * 2 >= (1 << 24))
+        return HERO_ERR_UNSUPPORTED;
+    GemmArgs g;
+    g.A = (const int8_t*)A; g.lda = lda * 2; g.a_row_scale = nullptr; g.Bt = (const int8_t*)Wt; g.ldb = ldb * 2;
+    g.b_col_scale = nullptr; g.bias = bias; g.residual = residual; g.ldr = ldr; g.out_col_scale = nullptr;
+    g.C = C; g.ldc = ldc; g.M = (int)M; g.N = (int)N; g.K = (int)(K * 2);
+    g.ksplit = 1; g.kslabs = 0;
+    g.ntm = (int)((M + 255) / 256); g.ntn = (int)((N + 255) / 256);
+    g.per_xcd = (int)((tiles + NUM_XCD - 1) / NUM_XCD);
+    const int nslot = g.per_xcd < 32 ? g.per_xcd : 32;
+    const dim3 grid((unsigned)(nslot * NUM_XCD)), block(512);
+    if (gelu) {
+        if (residual) hipLaunchKernelGGL((int8_gemm_persistent_kernel<4, HERO_EPI_DEQUANT_GELU, HERO_BF16, HERO_BF16, HERO_BF16>), grid, block, 0, st, g);
+        else hipLaunchKernelGGL((int8_gemm_persistent_kernel<4, HERO_EPI_DEQUANT_GELU, HERO_BF16, -1, HERO_BF16>), grid, block, 0, st, g);
+    } else {
+        if (residual) hipLaunchKernelGGL((int8_gemm_persistent_kernel<4, HERO_EPI_DEQUANT, HERO_BF16, HERO_BF16, HERO_BF16>), grid, block, 0, st, g);
+        else hipLaunchKernelGGL((int8_gemm_persistent_kernel<4, HERO_EPI_DEQUANT, HERO_BF16, -1, HERO_BF16>), grid, block, 0, st, g);
+    }
+    return hero_launch_status();
+}
 
 extern "C" size_t hero_int8_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K) {
     return splitk_plan(M, N, K).bytes;

@@ -429,8 +429,9 @@ def test_gemm_full_size_sampled_rows(hero, M, N, K):
 
 
 # ============================================================ BF16 side of a switched module
-@pytest.mark.parametrize("M,N,K", [(200, 136, 256), (130, 512, 1024), (64, 72, 96)])
+@pytest.mark.parametrize("M,N,K", [(200, 136, 256), (130, 512, 1024), (64, 72, 96), (2500, 2600, 160), (2560, 2560, 128)])
 def test_bf16_gemm_matches_oracle(hero, M, N, K):
+    """The last two shapes have enough 256 x 256 tiles for the persistent kernel (ragged edges, 5 / 4 slabs)."""
     g = synth.rng(1000 + M)
     A = O.f32_to_bf16(g.standard_normal((M, K)).astype(np.float32))
     Wt = O.f32_to_bf16((g.standard_normal((N, K)) * 0.05).astype(np.float32))
