@@ -167,7 +167,12 @@ __global__ __launch_bounds__(64 * ln_max_waves(NCH)) void ln_quant_kernel(LnArgs
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
             const int j = j0 + k * blockDim.x;
-            if (j < Dp) { sp[j] = pg[k]; sp[Dp + j] = pb[k]; sp[2 * Dp + j] = pr[k]; }
+            if (j < Dp) {
+                // column j = chunk c, lane l, element 4*e4 + t  ->  [c][e4][l][t]: a wave's 128-bit read of one
+                // (c, e4) then covers 64 consecutive 16-byte slots (no bank conflicts)
+                const int w = j % CH, pos = (((j / CH) * (EPL / 4) + (w % EPL) / 4) * 64 + w / EPL) * 4 + (w % 4);
+                sp[pos] = pg[k]; sp[Dp + pos] = pb[k]; sp[2 * Dp + pos] = pr[k];
+            }
         }
     }
     __syncthreads();
@@ -213,7 +218,7 @@ __global__ __launch_bounds__(64 * ln_max_waves(NCH)) void ln_quant_kernel(LnArgs
                     for (int e4 = 0; e4 < EPL / 4; ++e4) {
                         float f[4];
                         unpack4(rr0[p][c][e4], f);
-                        const v4f rc = *reinterpret_cast<const v4f*>(sp + 2 * Dp + j0 + 4 * e4);
+                        const v4f rc = *reinterpret_cast<const v4f*>(sp + 2 * Dp + ((c * (EPL / 4) + e4) * 64 + lane) * 4);
 #pragma unroll
                         for (int t = 0; t < 4; ++t) v[c][4 * e4 + t] = fmaf(f[t], rc[t], v[c][4 * e4 + t]);
                     }
@@ -266,11 +271,11 @@ __global__ __launch_bounds__(64 * ln_max_waves(NCH)) void ln_quant_kernel(LnArgs
             const float rstd = __builtin_amdgcn_rsqf(var + a.eps);
 #pragma unroll
             for (int c = 0; c < NCH; ++c) {
-                const int j0 = c * CH + lane * EPL;     // padded columns have gamma = beta = 0
+                // (padded columns have gamma = beta = 0)
 #pragma unroll
                 for (int e4 = 0; e4 < EPL / 4; ++e4) {
-                    const v4f g = *reinterpret_cast<const v4f*>(sp + j0 + 4 * e4);
-                    const v4f b = *reinterpret_cast<const v4f*>(sp + Dp + j0 + 4 * e4);
+                    const v4f g = *reinterpret_cast<const v4f*>(sp + ((c * (EPL / 4) + e4) * 64 + lane) * 4);
+                    const v4f b = *reinterpret_cast<const v4f*>(sp + Dp + ((c * (EPL / 4) + e4) * 64 + lane) * 4);
 #pragma unroll
                     for (int t = 0; t < 4; ++t) v[c][4 * e4 + t] = fmaf(v[c][4 * e4 + t] * rstd, g[t], b[t]);
                 }
