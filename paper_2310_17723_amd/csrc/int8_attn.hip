@@ -15,7 +15,10 @@
 // second-operand fragment of the PV MFMA (O^T = V^T P^T) provided V^T is stored in LDS with
 // the same key order, which the V staging does.
 // The matrix cores multiply signed bytes; codes are 0..255, so P-128 is fed and
-// 128 * colsum(V) (one extra MFMA against a vector of ones) is added back, exact in int32.
+// 128 * colsum(V) is added back, exact in int32.  Masked keys carry code 0 (fed as -128), so
+// the column sums run over every staged key and are the same for all queries of the block:
+// the four waves take turns adding them up from the V fragments they already hold (v_dot4
+// against ones) and exchange them through LDS once, at the end.
 // The kernel is bound by the plain-ALU work per score (exp2, conversion, rounding), not by
 // the matrix cores, so both passes are written to spend as few vector instructions per score
 // as possible (see the comment in front of pass 1).
@@ -38,7 +41,7 @@ struct AttnArgs {
 };
 
 template <int DH, int ODT>
-__global__ __launch_bounds__(256) void int8_attn_kernel(AttnArgs a) {
+__global__ __launch_bounds__(256, DH == 64 ? 4 : 3) void int8_attn_kernel(AttnArgs a) {
     constexpr int KLD = DH + 16;        // sK row stride (bytes)
     constexpr int VLD = BKV + 16;       // sVt row stride (bytes)
     constexpr int DS = DH / 32;         // 32-wide steps over the head dimension
@@ -183,12 +186,14 @@ __global__ __launch_bounds__(256) void int8_attn_kernel(AttnArgs a) {
     const float off = l > 0.0f ? -m2 - __log2f(l * a.p_scale) : -INFINITY;
 
     // ---- pass 2: codes and PV --------------------------------------------------------------------
-    v16i o[DS], cs[DS];
+    v16i o[DS];
+    int csum[DS];                                         // this wave's share of colsum(V): channel 32c + ql, keys of half hh
 #pragma unroll
-    for (int c = 0; c < DS; ++c)
+    for (int c = 0; c < DS; ++c) {
+        csum[c] = 0;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) { o[c][r] = 0; cs[c][r] = 0; }
-    const v4i ones = {0x01010101, 0x01010101, 0x01010101, 0x01010101};
+        for (int r = 0; r < 16; ++r) o[c][r] = 0;
+    }
     if (ntiles > 0) { load_k(0); load_v(0); store_k(0); store_v(0); }
     __syncthreads();
     for (int tile = 0; tile < ntiles; ++tile) {
@@ -216,7 +221,10 @@ __global__ __launch_bounds__(256) void int8_attn_kernel(AttnArgs a) {
                 for (int c = 0; c < DS; ++c) {
                     v4i vf = *reinterpret_cast<const v4i*>(&sVt[buf][(c * 32 + ql) * VLD + s * 32 + hh * 16]);
                     o[c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(vf, pf, o[c], 0, 0, 0);
-                    cs[c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(vf, ones, cs[c], 0, 0, 0);
+                    if (((tile * (BKV / 32) + s) & 3) == wave) {         // wave-uniform: one wave per 32-key step
+#pragma unroll
+                        for (int w = 0; w < 4; ++w) csum[c] = __builtin_amdgcn_sdot4(vf[w], 0x01010101, csum[c], false);
+                    }
                 }
             }
         };
@@ -224,6 +232,15 @@ __global__ __launch_bounds__(256) void int8_attn_kernel(AttnArgs a) {
         if (tile + 1 < ntiles) { store_k(buf ^ 1); store_v(buf ^ 1); }
         __syncthreads();
     }
+
+    // ---- colsum(V) of the block: every wave adds its share per channel (the loop's last barrier has
+    // released the K buffers, which now hold the sums)
+    int* const colsum = reinterpret_cast<int*>(&sK[0][0]);
+    for (int c = tid; c < DH; c += 256) colsum[c] = 0;
+    __syncthreads();
+#pragma unroll
+    for (int c = 0; c < DS; ++c) atomicAdd(&colsum[c * 32 + ql], csum[c]);
+    __syncthreads();
 
     // ---- output: lane holds query ql, channels 32c + 8g + 4hh + t -----------------------------------
     if (qi >= a.Sq) return;
@@ -236,7 +253,7 @@ __global__ __launch_bounds__(256) void int8_attn_kernel(AttnArgs a) {
             float y[4];
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
-                int val = o[c][4 * g + t] + 128 * cs[c][4 * g + t];
+                int val = o[c][4 * g + t] + 128 * colsum[e0 + t];
                 float sc = a.scale_is_scalar ? a.out_col_scale[0] : a.out_col_scale[h * DH + e0 + t];
                 y[t] = (float)val * sc;
             }
