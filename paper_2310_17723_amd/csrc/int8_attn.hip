@@ -86,7 +86,9 @@ __global__ __launch_bounds__(256, DH == 64 ? 4 : 3) void int8_attn_kernel(AttnAr
     // (double buffered, one barrier per tile).  V is written transposed, keys permuted so that the
     // PV operand fragment is one 128-bit read: key row 32kb + 8g + 4h + t -> position 32kb + 16h + 4g + t.
     constexpr int UNITS = BKV * (DH / 16) / 256;
-    v4i rk[UNITS], rv[UNITS];
+    constexpr int VUNITS = (BKV / 4) * (DH / 4) / 256;     // V: units of 4 keys x 4 channels (one dword per key)
+    v4i rk[UNITS];
+    int rv[VUNITS][4];
     auto load_k = [&](int tile) {
 #pragma unroll
         for (int u = 0; u < UNITS; ++u) {
@@ -95,12 +97,18 @@ __global__ __launch_bounds__(256, DH == 64 ? 4 : 3) void int8_attn_kernel(AttnAr
             rk[u] = *reinterpret_cast<const v4i*>(kbase + (int64_t)key * a.ks[1] + ch * 16);
         }
     };
+    // V unit: key group kg (4 consecutive keys) x channel group cg (4 channels).  Four consecutive lanes
+    // read 16 contiguous bytes of one key row; the 64 transposed dword stores of a wave (rows 4cg + j,
+    // 16 key-group positions each) fall into 64 different banks.
     auto load_v = [&](int tile) {
 #pragma unroll
-        for (int u = 0; u < UNITS; ++u) {
-            int idx = tid + u * 256, row = idx / (DH / 16), ch = idx % (DH / 16);
-            int key = min(tile * BKV + row, a.Skv - 1);
-            rv[u] = *reinterpret_cast<const v4i*>(vbase + (int64_t)key * a.vs[1] + ch * 16);
+        for (int u = 0; u < VUNITS; ++u) {
+            const int idx = tid + u * 256, kg = (idx >> 2) % (BKV / 4), cg = (idx & 3) + 4 * (idx / BKV);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int key = min(tile * BKV + kg * 4 + i, a.Skv - 1);
+                rv[u][i] = *reinterpret_cast<const int*>(vbase + (int64_t)key * a.vs[1] + cg * 4);
+            }
         }
     };
     auto store_k = [&](int buf) {
@@ -112,13 +120,19 @@ __global__ __launch_bounds__(256, DH == 64 ? 4 : 3) void int8_attn_kernel(AttnAr
     };
     auto store_v = [&](int buf) {
 #pragma unroll
-        for (int u = 0; u < UNITS; ++u) {
-            int idx = tid + u * 256, row = idx / (DH / 16), ch = idx % (DH / 16);
-            int r32 = row & 31;
-            int pos = (row & 32) + ((r32 >> 2) & 1) * 16 + (r32 >> 3) * 4 + (r32 & 3);
+        for (int u = 0; u < VUNITS; ++u) {
+            const int idx = tid + u * 256, kg = (idx >> 2) % (BKV / 4), cg = (idx & 3) + 4 * (idx / BKV);
+            // 4 x 4 byte transpose in registers: dword j of the result = channel 4cg + j of keys 4kg .. 4kg + 3
+            const uint32_t d0 = rv[u][0], d1 = rv[u][1], d2 = rv[u][2], d3 = rv[u][3];
+            const uint32_t lo01 = __builtin_amdgcn_perm(d1, d0, 0x05010400u), hi01 = __builtin_amdgcn_perm(d1, d0, 0x07030602u);
+            const uint32_t lo23 = __builtin_amdgcn_perm(d3, d2, 0x05010400u), hi23 = __builtin_amdgcn_perm(d3, d2, 0x07030602u);
+            const uint32_t t[4] = {__builtin_amdgcn_perm(lo23, lo01, 0x05040100u), __builtin_amdgcn_perm(lo23, lo01, 0x07060302u),
+                                   __builtin_amdgcn_perm(hi23, hi01, 0x05040100u), __builtin_amdgcn_perm(hi23, hi01, 0x07060302u)};
+            // keys 4kg .. 4kg+3 sit at positions pos .. pos+3 of the permuted key order (see above)
+            const int pos = ((kg * 4) & 32) + (kg & 1) * 16 + ((kg & 7) >> 1) * 4;
 #pragma unroll
-            for (int e = 0; e < 16; ++e)
-                sVt[buf][(ch * 16 + e) * VLD + pos] = (int8_t)(rv[u][e >> 2] >> (8 * (e & 3)));
+            for (int j = 0; j < 4; ++j)
+                *reinterpret_cast<uint32_t*>(&sVt[buf][(cg * 4 + j) * VLD + pos]) = t[j];
         }
     };
     // S^T for the 32-key step s of the staged tile
