@@ -291,6 +291,8 @@ def main():
     ap.add_argument("--layers", type=int, default=None, help="override the stack depth")
     ap.add_argument("--seed", type=int, default=2310)
     ap.add_argument("--no-extras", action="store_true", help="skip the GEMM sweep / LN / CPU legs")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one pass of the stack in a HIP graph and time its replays (launch-bound workloads)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 256 MiB device copy 5 times (reference for the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -326,11 +328,21 @@ def main():
     for _ in range(warmup):
         st.step()
     torch.cuda.synchronize()
+    run = st.step
+    if args.graph:
+        # every launch of the stack goes to the current stream and nothing allocates, so the pass can be
+        # captured as it is; the replays then cost one launch
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            st.step()
+        graph.replay()
+        torch.cuda.synchronize()
+        run = graph.replay
     t0 = time.perf_counter()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     for _ in range(steps):
-        st.step()
+        run()
     e1.record()
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
@@ -345,7 +357,7 @@ def main():
         "config": {"workload": shape.name, "arch": "post-LN" if shape.arch == 0 else "pre-LN", "mode": args.mode,
                    "layers": st.layers, "batch": shape.B, "seq_len": shape.S, "hidden": shape.d, "heads": shape.H,
                    "ffn": shape.f, "tokens_per_step": st.T * (shape.steps if decode else 1),
-                   "mask": ["none", "padding", "causal"][shape.mask]},
+                   "mask": ["none", "padding", "causal"][shape.mask], "hip_graph": bool(args.graph)},
         "stack_tokens_per_s": round(value / st.layers, 1),
         "us_per_layer": round(ms_per_step * 1e3 / (st.layers * (shape.steps if decode else 1)), 2),
         "wall_ms_timed_region": round(wall_ms, 2),

@@ -149,3 +149,37 @@ def test_layer_rejects_bad_requests(hero):
     with pytest.raises(HB.HeroError) as e:
         hero.hero_layer_fwd(bad, W, shape.B, shape.S, small_ws, x_q=xq, x_scale=xs, out_q=xq.clone(), out_scale=xs.clone())
     assert e.value.status == 4
+
+
+def test_layer_fwd_in_a_hip_graph_replays_like_eager(hero):
+    """hero_layer_fwd only enqueues kernels (no allocation, no memset, no host synchronisation), so a pass can be
+    captured in a HIP graph.  Every replay is compared with the eager result, with eager work and
+    synchronisations of the program's own between the replays."""
+    shape = _shape(synth.POST_LN, synth.MASK_PADDING)
+    B, S, T = shape.B, shape.S, shape.B * shape.S
+    w, emb = _prepare(shape, 35, OL.MODE_M3)
+    hw, keep = upload_weights(hero, w)
+    desc = _desc(hero, shape, OL.MODE_M3)
+    h0 = synth.activations(36, shape, T)
+    xq, xs, _ = O.ln_quant(h0, O.F32, None, None, 0, None, emb["g"], emb["b"], shape.eps)
+    kv = synth.kv_lengths(36, shape)
+    dxq, dxs, dkv = dev(xq), dev(xs), dev(kv)
+    ws = torch.empty(hero.hero_layer_workspace_bytes(desc, B, S), dtype=torch.uint8, device="cuda")
+    outs = [(torch.empty((T, shape.d), dtype=torch.int8, device="cuda"), torch.empty(T, device="cuda")) for _ in range(2)]
+
+    def run(o):
+        hero.hero_layer_fwd(desc, hw, B, S, ws, x_q=dxq, x_scale=dxs, out_q=o[0], out_scale=o[1], kv_len=dkv)
+    run(outs[0])
+    torch.cuda.synchronize()
+    ref_q, ref_s = outs[0][0].clone(), outs[0][1].clone()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run(outs[1])
+    for rep in range(4):
+        outs[1][0].zero_(); outs[1][1].zero_()
+        run(outs[0])                                            # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(outs[1][0], ref_q) and torch.equal(outs[1][1], ref_s), f"replay {rep}"
+        assert torch.equal(outs[0][0], ref_q)
