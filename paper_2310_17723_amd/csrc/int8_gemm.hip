@@ -729,7 +729,7 @@ inline SplitK splitk_plan(int64_t M, int64_t N, int64_t K) {
     if (M <= 0 || N <= 0 || M > 128 || K % BK != 0) return p;
     p.BM = p.BN = M <= 64 ? 64 : 128;
     const int64_t tiles = ((M + p.BM - 1) / p.BM) * ((N + p.BN - 1) / p.BN), kt = K / BK;
-    if (tiles >= 384 || kt < 8) return p;
+    if (tiles >= 384 || kt < 8 || N * K < (4 << 20)) return p;         // small weights: one pass is launch-bound anyway
     int64_t want = (512 + tiles - 1) / tiles;                         // about two workgroups per CU
     if (want > 16) want = 16;
     int64_t kslabs = (kt + want - 1) / want;
