@@ -830,7 +830,8 @@ hero_status launch_grid(GemmArgs g, int BM, int BN, int threads, K kernel, hipSt
 }
 
 // Tile choice: the 256x256 direct-to-LDS kernel once the grid has enough tiles to fill about half
-// of the 256 CUs; the 128x128 register-staged kernel otherwise (small, skinny or ragged problems).
+// of the 256 CUs; otherwise the register-staged kernel with 128x128 tiles, or 64x64 ones while fewer
+// than 192 tiles of 128x128 exist (small problems are latency-bound: more, shorter workgroups).
 // HERO_GEMM_TILE overrides the choice for tuning runs and tests: 0 = 128x128, 1 = 256x256 one tile per
 // workgroup, 2 = 64x64, 7 = 256x256 persistent.
 template <int EPI, int CDT, int RDT>
@@ -841,7 +842,10 @@ hero_status launch_epi(const GemmArgs& g, void* ws, size_t ws_bytes, hipStream_t
         const SplitK p = splitk_plan(g.M, g.N, g.K);
         if (p.ksplit > 1 && ws_bytes >= p.bytes) return launch_splitk<EPI, CDT, RDT>(g, p, ws, st);
     }
-    if (cfg < 0) cfg = ((int64_t)((g.M + 255) / 256) * ((g.N + 255) / 256) >= 96) ? 1 : (g.M <= 64 ? 2 : 0);
+    if (cfg < 0) {
+        const int64_t t256 = (int64_t)((g.M + 255) / 256) * ((g.N + 255) / 256), t128 = (int64_t)((g.M + 127) / 128) * ((g.N + 127) / 128);
+        cfg = t256 >= 96 ? 1 : ((g.M <= 64 || t128 < 192) ? 2 : 0);      // 64x64 tiles while 128x128 ones would leave CUs idle
+    }
     // persistent form of the 256x256 kernel: K long enough that the slab ring never runs more than one tile
     // ahead, 32-bit per-lane offsets (256 rows of lda / ldb bytes)
     if ((cfg == 7 || (cfg == 1 && !e)) && g.K >= 4 * BK && g.lda < (1 << 24) && g.ldb < (1 << 24)) {
