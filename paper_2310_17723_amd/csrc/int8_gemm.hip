@@ -252,29 +252,36 @@ __device__ __forceinline__ void epilogue_direct(const GemmArgs& g, ACC (&acc)[BM
 // Register-staged main loop (small / ragged problems).  BK-byte slabs, double-buffered in
 // LDS with an 80-byte padded row stride, PD slabs in flight in registers.
 // =====================================================================================
-template <int BM, int BN, int WM, int WN, int PD, int MINW, int EPI, int CDT, int RDT, bool SPLITK = false>
-__global__ __launch_bounds__(WM * WN * 64, MINW) void int8_gemm_kernel(GemmArgs g) {
-    constexpr int NT = WM * WN * 64;
+// KG > 1: KG groups of WM x WN waves share the tile and split K among themselves (every group has its own
+// slab buffers and runs the same number of iterations, so the barriers stay workgroup-wide); the groups'
+// accumulators are added through LDS before the epilogue.  For small problems with a long K: the number of
+// workgroups is fixed by M and N, more waves per workgroup shorten the K loop.
+template <int BM, int BN, int WM, int WN, int PD, int MINW, int EPI, int CDT, int RDT, bool SPLITK = false, int KG = 1>
+__global__ __launch_bounds__(WM * WN * 64 * KG, MINW) void int8_gemm_kernel(GemmArgs g) {
+    constexpr int NT = WM * WN * 64;                          // threads of one K group
     constexpr int CPR = BK / 16;                              // 16-byte chunks per slab row
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;      // 32x32 MFMA tiles per wave
     constexpr int A_UNITS = BM * CPR / NT, B_UNITS = BN * CPR / NT;
     static_assert(BM * CPR % NT == 0 && BN * CPR % NT == 0, "tile/threads mismatch");
     static_assert(PD % 2 == 0, "prefetch distance must be even (LDS buffer parity is compile-time)");
     constexpr int POOL = 2 * (BM + BN) * LDS_LD;
-    __shared__ __attribute__((aligned(16))) int8_t smem[POOL + 3 * BN * 4];
-    int8_t* const sA0 = smem;                                 // [2][BM * LDS_LD]
-    int8_t* const sB0 = smem + 2 * BM * LDS_LD;               // [2][BN * LDS_LD]
-    float* const sv = reinterpret_cast<float*>(smem + POOL);
+    static_assert(KG == 1 || (!SPLITK && BM * BN * 4 <= POOL), "K groups: one tile of accumulators must fit a group's slab buffers");
+    __shared__ __attribute__((aligned(16))) int8_t smem[KG * POOL + 3 * BN * 4];
+    const int kg = KG == 1 ? 0 : (int)threadIdx.x / NT;       // K group of this wave
+    int8_t* const sA0 = smem + kg * POOL;                     // [2][BM * LDS_LD]
+    int8_t* const sB0 = sA0 + 2 * BM * LDS_LD;                // [2][BN * LDS_LD]
+    float* const sv = reinterpret_cast<float*>(smem + KG * POOL);
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = KG == 1 ? (int)threadIdx.x : (int)threadIdx.x % NT, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
     int m0, n0;
     if (!tile_origin<BM, BN>(g, m0, n0)) return;
-    // this workgroup's slabs: all of K, or the blockIdx.y-th range of kslabs slabs (never empty)
-    const int kt0 = SPLITK ? (int)blockIdx.y * g.kslabs : 0;
-    const int KT = SPLITK ? min(g.kslabs, g.K / BK - kt0) : g.K / BK;
+    // this group's slabs: all of K, the blockIdx.y-th range of kslabs slabs (never empty), or the kg-th
+    // of KG equal ranges (the launch requires K / BK to be a multiple of KG)
+    const int kt0 = SPLITK ? (int)blockIdx.y * g.kslabs : kg * (g.K / BK / KG);
+    const int KT = SPLITK ? min(g.kslabs, g.K / BK - kt0) : g.K / BK / KG;
 
-    stage_col_vectors<BN, NT, EPI>(g, sv, n0, tid);
+    stage_col_vectors<BN, NT * KG, EPI>(g, sv, n0, (int)threadIdx.x);
     float rsr[TM];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -389,6 +396,32 @@ __global__ __launch_bounds__(WM * WN * 64, MINW) void int8_gemm_kernel(GemmArgs 
     if constexpr (PD >= 4) {
         if (kt < KT) { iteration(kt, 1, std::integral_constant<int, 1>{}); ++kt; }
         if (kt < KT) { iteration(kt, 0, std::integral_constant<int, 2>{}); ++kt; }
+    }
+    if constexpr (KG > 1) {
+        // groups 1 .. KG-1 hand their accumulators to group 0 (register-major, lane-minor: no bank conflicts);
+        // the loop's last barrier has released every group's slab buffers
+        constexpr int NV = TM * TN * 4;
+        v4i* const mine = reinterpret_cast<v4i*>(smem + kg * POOL) + (wave * NV) * 64 + lane;
+        if (kg > 0) {
+#pragma unroll
+            for (int v = 0; v < NV; ++v) {
+                const int ij = v >> 2, c = (v & 3) * 4;
+                mine[v * 64] = v4i{acc[ij / TN][ij % TN][c], acc[ij / TN][ij % TN][c + 1], acc[ij / TN][ij % TN][c + 2], acc[ij / TN][ij % TN][c + 3]};
+            }
+        }
+        __syncthreads();
+        if (kg > 0) return;
+#pragma unroll
+        for (int k = 1; k < KG; ++k) {
+            const v4i* other = reinterpret_cast<const v4i*>(smem + k * POOL) + (wave * NV) * 64 + lane;
+#pragma unroll
+            for (int v = 0; v < NV; ++v) {
+                const int ij = v >> 2, c = (v & 3) * 4;
+                const v4i o = other[v * 64];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc[ij / TN][ij % TN][c + e] += o[e];
+            }
+        }
     }
     if constexpr (SPLITK) {
         static_assert(EPI == HERO_EPI_RAW_I32, "split-K writes raw partial sums");
@@ -859,8 +892,15 @@ hero_status launch_epi(const GemmArgs& g, void* ws, size_t ws_bytes, hipStream_t
         return hero_launch_status();
     }
     if (cfg == 1) return launch_grid(g, 256, 256, 512, int8_gemm_dma_kernel<256, 256, 2, 4, 4, 2, EPI, CDT, RDT>, st);
-    if (cfg == 2)                               // skinny M (decode): more, smaller tiles stream the weights from more CUs
+    if (cfg == 2) {                             // small or skinny problems: 64x64 tiles
+        // few tiles and a long K: 4 groups of waves per workgroup split K (K / 64 must divide evenly);
+        // measured: 8-10 % at 128 tiles or fewer, a loss with more tiles or with 2 groups
+        const int64_t t64 = (int64_t)((g.M + 63) / 64) * ((g.N + 63) / 64);
+        const int kt = g.K / BK;
+        if (t64 <= 128 && kt >= 32 && kt % 4 == 0)
+            return launch_grid(g, 64, 64, 1024, int8_gemm_kernel<64, 64, 2, 2, 2, 1, EPI, CDT, RDT, false, 4>, st);
         return launch_grid(g, 64, 64, 256, int8_gemm_kernel<64, 64, 2, 2, 2, 2, EPI, CDT, RDT>, st);
+    }
     return launch_grid(g, 128, 128, 256, int8_gemm_kernel<128, 128, 2, 2, 2, 2, EPI, CDT, RDT>, st);
 }
 
