@@ -23,7 +23,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "hero_oracle.cpp")
 _LIB = os.path.join(_HERE, "libhero_oracle.so")
 
-I8, U8, I32, F16, BF16, F32 = range(6)
+I8, U8, I32, F16, BF16, F32, F8 = range(7)
 EPI_RAW_I32, EPI_DEQUANT, EPI_DEQUANT_GELU, EPI_REQUANT, EPI_GELU_REQUANT = range(5)
 MASK_NONE, MASK_PADDING, MASK_CAUSAL = range(3)
 
@@ -110,7 +110,7 @@ def hp_to_f32(h: np.ndarray, dt: int) -> np.ndarray:
     return f16_to_f32(h)
 
 
-_NP_OF = {I8: np.int8, U8: np.uint8, I32: np.int32, F16: np.uint16, BF16: np.uint16, F32: np.float32}
+_NP_OF = {I8: np.int8, U8: np.uint8, I32: np.int32, F16: np.uint16, BF16: np.uint16, F32: np.float32, F8: np.uint8}
 
 
 # ------------------------------------------------------------------ O1 / O2
@@ -209,6 +209,54 @@ def int8_gemm(A, Bt, *, a_row_scale=None, b_col_scale=None, bias=None, residual=
                              _p(Cm), C.c_int(c_dt), _i64(N), _i64(M), _i64(N), _i64(K))
     if rc != 0:
         raise ValueError("oracle int8_gemm: invalid epilogue / dtype combination")
+    return Cm
+
+
+# ------------------------------------------------------------------ O4f: the FP8 (OCP E4M3) variant
+def e4m3_to_f32(c) -> np.ndarray:
+    c = np.ascontiguousarray(c, np.uint8)
+    out = np.empty(c.shape, np.float32)
+    lib().orc_e4m3_to_f32_n(_p(c), _i64(c.size), _p(out))
+    return out
+
+
+def f32_to_e4m3(x) -> np.ndarray:
+    """Round to nearest even, saturate to +-448, NaN -> 0x7F."""
+    x = np.ascontiguousarray(x, np.float32)
+    out = np.empty(x.shape, np.uint8)
+    lib().orc_f32_to_e4m3_n(_p(x), _i64(x.size), _p(out))
+    return out
+
+
+def quant_twq_fp8(x):
+    """Token-wise FP8 quantization: s = max|x| / 448 per row, q = e4m3(x / s)."""
+    x = np.ascontiguousarray(x, np.float32)
+    M, D = x.shape
+    q = np.empty((M, D), np.uint8)
+    s = np.empty((M,), np.float32)
+    lib().orc_quant_twq_fp8(_p(x), _i64(M), _i64(D), _p(q), _p(s))
+    return q, s
+
+
+def fp8_gemm(A, Bt, *, a_row_scale=None, b_col_scale=None, bias=None, residual=None, res_dt=BF16,
+             epi=EPI_DEQUANT, out_col_scale=None, c_dt=F32) -> np.ndarray:
+    """The FP8 GeMM^quant: E4M3 codes in, exact sum (fp64), the INT8 path's fp32 epilogue, E4M3 or 16-bit out."""
+    A = np.ascontiguousarray(A, np.uint8)
+    Bt = np.ascontiguousarray(Bt, np.uint8)
+    M, K = A.shape
+    N, K2 = Bt.shape
+    assert K == K2
+    f32 = lambda a: None if a is None else np.ascontiguousarray(a, np.float32)
+    a_row_scale, b_col_scale, bias, out_col_scale = map(f32, (a_row_scale, b_col_scale, bias, out_col_scale))
+    if residual is not None:
+        residual = np.ascontiguousarray(residual, _NP_OF[res_dt])
+        assert residual.shape == (M, N)
+    Cm = np.empty((M, N), _NP_OF[c_dt])
+    rc = lib().orc_fp8_gemm(_p(A), _i64(K), _p(a_row_scale), _p(Bt), _i64(K), _p(b_col_scale), _p(bias),
+                            _p(residual), C.c_int(res_dt), _i64(N), C.c_int(epi), _p(out_col_scale),
+                            _p(Cm), C.c_int(c_dt), _i64(N), _i64(M), _i64(N), _i64(K))
+    if rc != 0:
+        raise ValueError("oracle fp8_gemm: invalid epilogue / dtype combination")
     return Cm
 
 

@@ -18,6 +18,7 @@
 // numpy/scipy/torch library routines).  No function here is "parity unpinned".
 
 #include <cmath>
+#include <limits>
 #include <cstdint>
 #include <cstring>
 #include <vector>
@@ -219,6 +220,99 @@ int orc_int8_gemm(const int8_t* A, int64_t lda, const float* a_row_scale,
             case ORC_EPI_GELU_REQUANT:
                 ((int8_t*)C)[i * ldc + j] = quant_code((float)orc_gelu((double)y), out_col_scale[j]);
                 break;
+            }
+        }
+    return 0;
+}
+
+// ---------------------------------------------------------------------------------
+// O4f.  The FP8 variant (Sec. 2.1: the method "also works for other 8-bit precision formats, like
+// FP8").  Format: OCP E4M3 (1 sign, 4 exponent bits with bias 7, 3 mantissa bits; subnormals; no
+// infinities; largest finite value 448; the all-ones pattern 0x7F / 0xFF is NaN), the 8-bit float
+// the gfx950 matrix cores multiply.  Conventions mirror the INT8 ones: round to nearest even,
+// SATURATE to +-448, token-wise scale = absmax / 448, static scales folded as before.
+//   orc_e4m3_to_f32 / orc_f32_to_e4m3: the format itself.
+//   orc_quant_twq_fp8: per row  s = max|x| / 448 (1 for a zero row);  q = e4m3(x / s)  (IEEE fp32 quotient).
+//   orc_fp8_gemm: acc = sum_k A[i][k] * Bt[j][k] with every product exact and the sum carried in fp64
+//     (the definition: the exact sum, rounded once); t = float(acc) and then the same fp32 epilogue
+//     as O4, with e4m3(.) in place of sat(rne(.)) for the 8-bit outputs.
+// ---------------------------------------------------------------------------------
+float orc_e4m3_to_f32(uint8_t c) {
+    const int sign = c >> 7, e = (c >> 3) & 15, m = c & 7;
+    float v;
+    if (e == 15 && m == 7) return std::numeric_limits<float>::quiet_NaN();
+    if (e == 0) v = std::ldexp((float)m, -9);                       // subnormal: m/8 * 2^-6
+    else v = std::ldexp(1.0f + (float)m / 8.0f, e - 7);
+    return sign ? -v : v;
+}
+uint8_t orc_f32_to_e4m3(float x) {
+    if (std::isnan(x)) return 0x7F;
+    const uint8_t sign = std::signbit(x) ? 0x80 : 0x00;
+    const double a = std::fabs((double)x);
+    if (a >= 464.0) return sign | 0x7E;                             // beyond the midpoint above 448: saturate
+    if (a < std::ldexp(1.0, -6)) {                                  // subnormal range (may round up to 2^-6 = code 8)
+        const int q = (int)std::nearbyint(a * 512.0);
+        return sign | (uint8_t)q;
+    }
+    int e2;
+    const double fr = std::frexp(a, &e2);                           // a = fr * 2^e2, fr in [0.5, 1)
+    int e = e2 - 1;
+    int q = (int)std::nearbyint((fr * 2.0 - 1.0) * 8.0);            // ties to even in the default rounding mode
+    if (q == 8) { q = 0; ++e; }
+    if (e > 8 || (e == 8 && q > 6)) return sign | 0x7E;
+    return sign | (uint8_t)(((e + 7) << 3) | q);
+}
+void orc_e4m3_to_f32_n(const uint8_t* c, int64_t n, float* out) { for (int64_t i = 0; i < n; ++i) out[i] = orc_e4m3_to_f32(c[i]); }
+void orc_f32_to_e4m3_n(const float* x, int64_t n, uint8_t* out) { for (int64_t i = 0; i < n; ++i) out[i] = orc_f32_to_e4m3(x[i]); }
+
+void orc_quant_twq_fp8(const float* x, int64_t M, int64_t D, uint8_t* q, float* s) {
+    for (int64_t i = 0; i < M; ++i) {
+        float amax = 0.0f;
+        for (int64_t j = 0; j < D; ++j) amax = std::max(amax, std::fabs(x[i * D + j]));
+        volatile float sc = amax == 0.0f ? 1.0f : amax / 448.0f;
+        s[i] = sc;
+        for (int64_t j = 0; j < D; ++j) { volatile float t = x[i * D + j] / sc; q[i * D + j] = orc_f32_to_e4m3(t); }
+    }
+}
+
+int orc_fp8_gemm(const uint8_t* A, int64_t lda, const float* a_row_scale,
+                 const uint8_t* Bt, int64_t ldb, const float* b_col_scale,
+                 const float* bias, const void* residual, int res_dt, int64_t ldr,
+                 int epi, const float* out_col_scale,
+                 void* C, int c_dt, int64_t ldc, int64_t M, int64_t N, int64_t K) {
+    const int ORC_F8 = 6;
+    if (epi == ORC_EPI_RAW_I32) return -1;
+    if ((epi == ORC_EPI_REQUANT || epi == ORC_EPI_GELU_REQUANT) && c_dt != ORC_F8) return -1;
+    if ((epi == ORC_EPI_DEQUANT || epi == ORC_EPI_DEQUANT_GELU) &&
+        !(c_dt == ORC_F16 || c_dt == ORC_BF16 || c_dt == ORC_F32)) return -1;
+    if (epi == ORC_EPI_GELU_REQUANT && !out_col_scale) return -1;
+    if (!b_col_scale) return -1;
+    float lut[256];
+    for (int c = 0; c < 256; ++c) lut[c] = orc_e4m3_to_f32((uint8_t)c);
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < M; ++i)
+        for (int64_t j = 0; j < N; ++j) {
+            double acc = 0.0;
+            for (int64_t k = 0; k < K; ++k) acc += (double)lut[A[i * lda + k]] * (double)lut[Bt[j * ldb + k]];
+            volatile float t = (float)acc;
+            if (a_row_scale) t = t * a_row_scale[i];
+            volatile float y = std::fmaf(t, b_col_scale[j], bias ? bias[j] : 0.0f);
+            switch (epi) {
+            case ORC_EPI_DEQUANT: {
+                float o = y;
+                if (residual) { volatile float r = y + load_hp(residual, res_dt, i * ldr + j); o = r; }
+                store_hp(C, c_dt, i * ldc + j, o);
+                break; }
+            case ORC_EPI_DEQUANT_GELU:
+                store_hp(C, c_dt, i * ldc + j, (float)orc_gelu((double)y));
+                break;
+            case ORC_EPI_REQUANT:
+                ((uint8_t*)C)[i * ldc + j] = orc_f32_to_e4m3(y);
+                break;
+            case ORC_EPI_GELU_REQUANT: {
+                volatile float gq = (float)orc_gelu((double)y) / out_col_scale[j];
+                ((uint8_t*)C)[i * ldc + j] = orc_f32_to_e4m3(gq);
+                break; }
             }
         }
     return 0;

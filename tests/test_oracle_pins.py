@@ -277,6 +277,77 @@ def test_epilogue_general_scales_exact_rational_and_16bit_outputs():
         O.int8_gemm(A, Bt, b_col_scale=cs, epi=O.EPI_REQUANT, c_dt=O.BF16)
 
 
+# ---------------------------------------------------------------- O4f FP8 variant
+def test_fp8_e4m3_format_quantizer_and_gemm():
+    """Pins for the FP8 (OCP E4M3) variant: the format against torch's float8_e4m3fn (all 256 codes decoded, a dense
+    sweep encoded; torch has no saturation, so values beyond 448 are checked against the rule), the token-wise
+    quantizer against its defining properties, the GEMM against a float64 matmul of the decoded operands and an
+    exact-rational epilogue."""
+    codes = np.arange(256, dtype=np.uint8)
+    dec = O.e4m3_to_f32(codes)
+    ref = torch.from_numpy(codes).view(torch.float8_e4m3fn).float().numpy()
+    assert np.array_equal(np.isnan(dec), np.isnan(ref)) and np.array_equal(dec[~np.isnan(dec)], ref[~np.isnan(ref)])
+    assert dec[0x7E] == 448 and dec[0x01] == 2.0 ** -9 and dec[0x08] == 2.0 ** -6 and np.isnan(dec[0x7F])
+    fin = ~np.isnan(dec)
+    assert np.array_equal(O.f32_to_e4m3(dec[fin]) & 0x7F, codes[fin] & 0x7F)          # every finite code round-trips
+    g = synth.rng(14)
+    x = np.concatenate([g.standard_normal(20000) * np.exp(g.uniform(-8, 6, 20000)), dec[fin],
+                        (dec[fin][:-1] + dec[fin][1:]) / 2]).astype(np.float32)        # incl. exact ties
+    x = x[np.abs(x) <= 448]
+    enc = O.f32_to_e4m3(x)
+    tref = torch.from_numpy(x).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    nz = x != 0
+    assert np.array_equal(enc[nz], tref[nz]) and np.array_equal(enc[~nz] & 0x7F, tref[~nz] & 0x7F)
+    big = np.float32([449, 463.9, 464, 1e9, np.inf, -470, -np.inf])
+    assert np.array_equal(O.f32_to_e4m3(big), np.uint8([0x7E, 0x7E, 0x7E, 0x7E, 0x7E, 0xFE, 0xFE]))
+    assert O.f32_to_e4m3(np.float32([np.nan]))[0] & 0x7F == 0x7F
+    # token-wise quantizer: scale = absmax / 448, the absmax element maps to +-448, error within half a step
+    X = (g.standard_normal((9, 64)) * g.uniform(0.1, 30, (9, 1))).astype(np.float32)
+    X[3] = 0
+    q, s = O.quant_twq_fp8(X)
+    amax = np.abs(X).max(axis=1)
+    assert np.array_equal(s, np.where(amax == 0, np.float32(1), amax / np.float32(448)).astype(np.float32))
+    dq = O.e4m3_to_f32(q)
+    assert (np.abs(dq).max(axis=1)[amax > 0] == 448).all() and (dq[3] == 0).all()
+    for i in range(9):
+        for j in range(64):
+            t = np.float32(X[i, j]) / s[i]
+            assert q[i, j] == O.f32_to_e4m3(np.float32([t]))[0]
+            step = max(2.0 ** (math.floor(math.log2(max(abs(float(t)), 2.0 ** -6))) - 3), 2.0 ** -9)
+            assert abs(float(dq[i, j]) - float(t)) <= step / 2 * (1 + 1e-6)
+    # GEMM: float64 matmul of the decoded operands (products of two E4M3 values are exact in fp64, so is their sum here)
+    M, N, K = 5, 7, 256
+    A = O.f32_to_e4m3(g.standard_normal((M, K)).astype(np.float32) * 3)
+    Bt = O.f32_to_e4m3(g.standard_normal((N, K)).astype(np.float32) * 3)
+    acc = O.e4m3_to_f32(A).astype(np.float64) @ O.e4m3_to_f32(Bt).astype(np.float64).T
+    rs = g.uniform(0.01, 0.1, M).astype(np.float32)
+    cs = g.uniform(0.01, 0.1, N).astype(np.float32)
+    bias = g.standard_normal(N).astype(np.float32)
+    y = np.empty((M, N), np.float32)
+    for i in range(M):
+        for j in range(N):
+            t = frac_to_f32(Fraction(float(acc[i, j])))
+            t = frac_to_f32(F(t) * F(rs[i]))
+            y[i, j] = frac_to_f32(F(t) * F(cs[j]) + F(bias[j]))
+    assert np.array_equal(O.fp8_gemm(A, Bt, a_row_scale=rs, b_col_scale=cs, bias=bias, epi=O.EPI_DEQUANT, c_dt=O.F32), y)
+    assert np.array_equal(O.fp8_gemm(A, Bt, a_row_scale=rs, b_col_scale=cs, bias=bias, epi=O.EPI_REQUANT, c_dt=O.F8),
+                          O.f32_to_e4m3(y))
+    bf = O.fp8_gemm(A, Bt, a_row_scale=rs, b_col_scale=cs, bias=bias, epi=O.EPI_DEQUANT, c_dt=O.BF16)
+    assert np.array_equal(bf, torch.from_numpy(y).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16))
+    gl = (0.5 * y.astype(np.float64) * (1 + scipy.special.erf(y.astype(np.float64) / math.sqrt(2)))).astype(np.float32)
+    sa = (np.abs(gl).max(axis=0) / 448 + 1e-6).astype(np.float32)
+    gq = O.fp8_gemm(A, Bt, a_row_scale=rs, b_col_scale=cs, bias=bias, epi=O.EPI_GELU_REQUANT, out_col_scale=sa, c_dt=O.F8)
+    assert np.array_equal(gq, O.f32_to_e4m3((gl / sa[None, :]).astype(np.float32)))
+    # one-hot rows pick single weights: operand layout
+    A1 = np.zeros((3, K), np.uint8); ks = [5, 100, 255]
+    for i, k in enumerate(ks):
+        A1[i, k] = 0x38                                                               # 1.0
+    one = np.ones(N, np.float32)
+    assert np.array_equal(O.fp8_gemm(A1, Bt, b_col_scale=one, epi=O.EPI_DEQUANT, c_dt=O.F32), O.e4m3_to_f32(Bt)[:, ks].T)
+    with pytest.raises(ValueError):
+        O.fp8_gemm(A, Bt, b_col_scale=cs, epi=O.EPI_REQUANT, c_dt=O.BF16)
+
+
 # ---------------------------------------------------------------- O5 LN^quant
 def test_ln_quant_closed_forms_and_torch():
     g = synth.rng(9)
