@@ -36,7 +36,8 @@ typedef enum {
     HERO_ERR_LAUNCH = 6       /* the HIP runtime refused a launch                     */
 } hero_status;
 
-typedef enum { HERO_I8 = 0, HERO_U8 = 1, HERO_I32 = 2, HERO_F16 = 3, HERO_BF16 = 4, HERO_F32 = 5 } hero_dtype;
+typedef enum { HERO_I8 = 0, HERO_U8 = 1, HERO_I32 = 2, HERO_F16 = 3, HERO_BF16 = 4, HERO_F32 = 5,
+               HERO_F8E4M3 = 6 /* OCP E4M3: bias 7, max 448, no infinities */ } hero_dtype;
 
 typedef enum {
     HERO_EPI_RAW_I32 = 0,      /* C = acc                                   (int32)        */
@@ -148,6 +149,23 @@ hero_status hero_int8_gemm_ws(const int8_t* A, int64_t lda, const float* a_row_s
                               void* C, hero_dtype c_dt, int64_t ldc,
                               int64_t M, int64_t N, int64_t K,
                               void* workspace, size_t workspace_bytes, void* stream);
+
+/* The FP8 variant of GeMM^quant (Sec. 2.1: the method "also works for other 8-bit precision formats,
+ * like FP8"): the same operation and epilogue as hero_int8_gemm with OCP E4M3 operands and
+ * fp32 accumulation on the matrix cores.
+ *   acc[i][j] = sum_k A[i][k] * Bt[j][k]     every product exact; the sum in fp32 (hardware order)
+ *   then t = acc * a_row_scale[i] (skipped if NULL); y = fma(t, b_col_scale[j], bias[j]); epilogue:
+ *   DEQUANT / DEQUANT_GELU -> C in HERO_F16 / HERO_BF16 (residual as for hero_int8_gemm);
+ *   REQUANT -> e4m3(y), GELU_REQUANT -> e4m3(GELU(y) / out_col_scale[j]): C in HERO_F8E4M3, round
+ *   to nearest even, saturated to +-448.  HERO_EPI_RAW_I32 does not exist here.
+ *   A [M,K], Bt [N,K] E4M3 bytes, K contiguous.  Constraints as for hero_int8_gemm.
+ * Token-wise FP8 activations use scale = max|x| / 448 per row; static scales fold as for INT8. */
+hero_status hero_fp8_gemm(const void* A, int64_t lda, const float* a_row_scale,
+                          const void* Bt, int64_t ldb, const float* b_col_scale,
+                          const float* bias, const void* residual, hero_dtype res_dt, int64_t ldr,
+                          hero_epilogue epi, const float* out_col_scale,
+                          void* C, hero_dtype c_dt, int64_t ldc,
+                          int64_t M, int64_t N, int64_t K, void* stream);
 
 /* INT8 attention: QK^T, Softmax^quant, PV.  Paper: Sec. 2.2.2 quantized flow
  *   A = S_q S_k X_q,int8 X_k,int8^T / sqrt(d)   (not quantized; d~ = S_q S_k / sqrt(d))

@@ -16,8 +16,9 @@ MODE_M3 = M_QKV | M_ATTN | M_ATTN_OUT | M_FC1 | M_FC2
 MODE_M2 = M_QKV | M_ATTN | M_ATTN_OUT | M_FC1
 MODE_M1 = M_QKV | M_FC1
 
+F8E4M3 = 6
 _DT = {torch.int8: I8, torch.uint8: U8, torch.int32: I32, torch.float16: F16, torch.bfloat16: BF16,
-       torch.float32: F32}
+       torch.float32: F32, torch.float8_e4m3fn: F8E4M3}
 
 vp, i64, f32, i32 = C.c_void_p, C.c_int64, C.c_float, C.c_int
 
@@ -47,6 +48,7 @@ SYMBOLS = {
     "hero_absmax_cols": (i32, [vp, i32, i64, i64, i64, vp, vp]),
     "hero_weight_fold_quant": (i32, [vp, i64, vp, vp, i64, i64, vp, i64, vp, vp]),
     "hero_int8_gemm": (i32, [vp, i64, vp, vp, i64, vp, vp, vp, i32, i64, i32, vp, vp, i32, i64, i64, i64, i64, vp]),
+    "hero_fp8_gemm": (i32, [vp, i64, vp, vp, i64, vp, vp, vp, i32, i64, i32, vp, vp, i32, i64, i64, i64, i64, vp]),
     "hero_int8_gemm_workspace_bytes": (C.c_size_t, [i64, i64, i64]),
     "hero_int8_gemm_ws": (i32, [vp, i64, vp, vp, i64, vp, vp, vp, i32, i64, i32, vp, vp, i32, i64, i64, i64, i64,
                                 vp, C.c_size_t, vp]),
@@ -177,6 +179,23 @@ class Hero:
         else:
             st = self.lib.hero_int8_gemm_ws(*args, _ptr(workspace), workspace.numel() * workspace.element_size(),
                                             _stream(stream))
+        self._check(st)
+        return C_out
+
+    def hero_fp8_gemm(self, A, Bt, a_row_scale, b_col_scale, bias=None, residual=None, epi=EPI_DEQUANT,
+                      out_col_scale=None, out_dtype=torch.bfloat16, C_out=None, stream=None):
+        """The FP8 variant: A [M,K], Bt [N,K] hold E4M3 bytes (torch.float8_e4m3fn or uint8 storage).
+        out_dtype torch.float8_e4m3fn for the REQUANT epilogues, float16 / bfloat16 for DEQUANT."""
+        M, K = A.shape
+        N = Bt.shape[0]
+        assert Bt.shape[1] == K and A.stride(1) == 1 and Bt.stride(1) == 1 and A.element_size() == 1 and Bt.element_size() == 1
+        if C_out is None:
+            C_out = torch.empty((M, N), dtype=out_dtype, device=A.device)
+        st = self.lib.hero_fp8_gemm(_ptr(A), A.stride(0) if M > 1 else max(K, A.stride(0)), _ptr(a_row_scale),
+                                    _ptr(Bt), Bt.stride(0) if N > 1 else max(K, Bt.stride(0)), _ptr(b_col_scale),
+                                    _ptr(bias), _ptr(residual), _DT[residual.dtype] if residual is not None else 0,
+                                    residual.stride(0) if residual is not None else 0, int(epi), _ptr(out_col_scale),
+                                    _ptr(C_out), _DT[C_out.dtype], C_out.stride(0), M, N, K, _stream(stream))
         self._check(st)
         return C_out
 

@@ -81,6 +81,12 @@ __device__ __forceinline__ uint32_t quant4_sat(float y0, float y1, float y2, flo
                           rne_low_byte(__builtin_amdgcn_fmed3f(y2, -127.0f, 127.0f)),
                           rne_low_byte(__builtin_amdgcn_fmed3f(y3, -127.0f, 127.0f)));
 }
+// four fp32 values -> four OCP E4M3 bytes (round to nearest even), saturated to +-448
+__device__ __forceinline__ uint32_t fp8x4_sat(float y0, float y1, float y2, float y3) {
+    int w = __builtin_amdgcn_cvt_pk_fp8_f32(__builtin_amdgcn_fmed3f(y0, -448.0f, 448.0f), __builtin_amdgcn_fmed3f(y1, -448.0f, 448.0f), 0, false);
+    w = __builtin_amdgcn_cvt_pk_fp8_f32(__builtin_amdgcn_fmed3f(y2, -448.0f, 448.0f), __builtin_amdgcn_fmed3f(y3, -448.0f, 448.0f), w, true);
+    return (uint32_t)w;
+}
 // erf-form GELU in fp32:  GELU(x) = x Phi(x) = max(x,0) - |x| Phi(-|x|).
 // Phi(-z) = 2^P(z) with P a degree-6 polynomial: a weighted least-squares fit of log2 Phi(-z) on
 // [0,6] (beyond 6, Phi(-z) < 1e-9 and z is clamped).  Evaluated in fp32 the absolute error of

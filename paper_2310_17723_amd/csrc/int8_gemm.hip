@@ -44,7 +44,28 @@ struct GemmArgs {
     int ksplit, kslabs;
 };
 
-template <int CDT> struct ElemSize { static constexpr int v = CDT == HERO_I32 ? 4 : (CDT == HERO_I8 ? 1 : 2); };
+// Operand types of the main loops.  ADT = HERO_I8: INT8 operands, int32 accumulators.  ADT = HERO_BF16: bf16
+// operands (the BF16 side of a switched module, Sec. 2.3 / Table 1), fp32 accumulators, no scales; K, lda and ldb
+// are then in BYTES, and a 64-byte slab holds two v_mfma_f32_32x32x16_bf16 steps exactly as it holds two INT8
+// steps.  ADT = HERO_F8E4M3: the FP8 variant (Sec. 2.1), fp32 accumulators, the INT8 epilogue; a 16-byte
+// fragment feeds two v_mfma_f32_32x32x16_fp8_fp8 (its low and its high 8 bytes: any grouping of K is a valid
+// contraction as long as both operands use the same one).
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+template <int ADT, typename ACC>
+__device__ __forceinline__ ACC mfma_step(v4i a, v4i b, ACC c) {
+    if constexpr (ADT == HERO_I8) return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0);
+    else if constexpr (ADT == HERO_BF16)
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a), __builtin_bit_cast(v8bf, b), c, 0, 0, 0);
+    else {
+        const long a0 = (long)(((uint64_t)(uint32_t)a[1] << 32) | (uint32_t)a[0]), a1 = (long)(((uint64_t)(uint32_t)a[3] << 32) | (uint32_t)a[2]);
+        const long b0 = (long)(((uint64_t)(uint32_t)b[1] << 32) | (uint32_t)b[0]), b1 = (long)(((uint64_t)(uint32_t)b[3] << 32) | (uint32_t)b[2]);
+        c = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(a0, b0, c, 0, 0, 0);
+        return __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(a1, b1, c, 0, 0, 0);
+    }
+}
+template <int ADT> struct AccOf { using type = typename std::conditional<ADT == HERO_I8, v16i, v16f>::type; };
+
+template <int CDT> struct ElemSize { static constexpr int v = CDT == HERO_I32 ? 4 : ((CDT == HERO_I8 || CDT == HERO_F8E4M3) ? 1 : 2); };
 
 // XCD-aware tile order: workgroups go round-robin to the 8 XCDs, so XCD x takes the
 // contiguous range [x * per_xcd, (x+1) * per_xcd) of a grouped order in which 64
@@ -193,7 +214,8 @@ __device__ __forceinline__ void epilogue_direct(const GemmArgs& g, ACC (&acc)[BM
             if constexpr (ES == 1) {
                 uint32_t w[NQ], d[NQ];
 #pragma unroll
-                for (int q = 0; q < NQ; ++q) w[q] = quant4_sat(y[q][0], y[q][1], y[q][2], y[q][3]);
+                for (int q = 0; q < NQ; ++q)
+                    w[q] = CDT == HERO_F8E4M3 ? fp8x4_sat(y[q][0], y[q][1], y[q][2], y[q][3]) : quant4_sat(y[q][0], y[q][1], y[q][2], y[q][3]);
 #pragma unroll
                 for (int q = 0; q < H; ++q) swap32(w[q], w[q + H], d[2 * q], d[2 * q + 1]);
                 if (rowok && col0 < g.N) store_piece<1, NQ>((int8_t*)g.C + (int64_t)row * g.ldc + col0, d, col0, g.N, full, al16);
@@ -256,8 +278,10 @@ __device__ __forceinline__ void epilogue_direct(const GemmArgs& g, ACC (&acc)[BM
 // slab buffers and runs the same number of iterations, so the barriers stay workgroup-wide); the groups'
 // accumulators are added through LDS before the epilogue.  For small problems with a long K: the number of
 // workgroups is fixed by M and N, more waves per workgroup shorten the K loop.
-template <int BM, int BN, int WM, int WN, int PD, int MINW, int EPI, int CDT, int RDT, bool SPLITK = false, int KG = 1>
+template <int BM, int BN, int WM, int WN, int PD, int MINW, int EPI, int CDT, int RDT, bool SPLITK = false, int KG = 1, int ADT = HERO_I8>
 __global__ __launch_bounds__(WM * WN * 64 * KG, MINW) void int8_gemm_kernel(GemmArgs g) {
+    using ACC = typename AccOf<ADT>::type;
+    static_assert(ADT == HERO_I8 || (!SPLITK && KG == 1), "split K: integer partial sums only");
     constexpr int NT = WM * WN * 64;                          // threads of one K group
     constexpr int CPR = BK / 16;                              // 16-byte chunks per slab row
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;      // 32x32 MFMA tiles per wave
@@ -318,7 +342,7 @@ __global__ __launch_bounds__(WM * WN * 64 * KG, MINW) void int8_gemm_kernel(Gemm
             *reinterpret_cast<v4i*>(sB0 + buf * BN * LDS_LD + lds_unit0 + u * (NT / CPR) * LDS_LD) = rb[p][u];
     };
 
-    v16i acc[TM][TN];
+    ACC acc[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -359,7 +383,7 @@ __global__ __launch_bounds__(WM * WN * 64 * KG, MINW) void int8_gemm_kernel(Gemm
 #pragma unroll
         for (int n = 0; n < NM; ++n) {                             // k-step 0; memory instructions dealt round-robin
             const int jj = n / TM, ii = n % TM;
-            acc[ii][jj] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f0[jj], f0[TN + ii], acc[ii][jj], 0, 0, 0);
+            acc[ii][jj] = mfma_step<ADT>(f0[jj], f0[TN + ii], acc[ii][jj]);
 #pragma unroll
             for (int t = n; t < NFR; t += NM)
                 f1[t] = *reinterpret_cast<const v4i*>((t < TN ? sb + t * 32 * LDS_LD : sa + (t - TN) * 32 * LDS_LD) + 32);
@@ -373,7 +397,7 @@ __global__ __launch_bounds__(WM * WN * 64 * KG, MINW) void int8_gemm_kernel(Gemm
 #pragma unroll
         for (int n = 0; n < NM; ++n) {                             // k-step 1
             const int jj = n / TM, ii = n % TM;
-            acc[ii][jj] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f1[jj], f1[TN + ii], acc[ii][jj], 0, 0, 0);
+            acc[ii][jj] = mfma_step<ADT>(f1[jj], f1[TN + ii], acc[ii][jj]);
 #pragma unroll
             for (int t = n; t < NW; t += NM) {                     // slab kt + 1 + PD into the freed register set
                 if (t < A_UNITS) ra[u][t] = *reinterpret_cast<const v4i*>(pa[t] + koff);
@@ -397,7 +421,7 @@ __global__ __launch_bounds__(WM * WN * 64 * KG, MINW) void int8_gemm_kernel(Gemm
         if (kt < KT) { iteration(kt, 1, std::integral_constant<int, 1>{}); ++kt; }
         if (kt < KT) { iteration(kt, 0, std::integral_constant<int, 2>{}); ++kt; }
     }
-    if constexpr (KG > 1) {
+    if constexpr (KG > 1 && ADT == HERO_I8) {
         // groups 1 .. KG-1 hand their accumulators to group 0 (register-major, lane-minor: no bank conflicts);
         // the loop's last barrier has released every group's slab buffers
         constexpr int NV = TM * TN * 4;
@@ -423,14 +447,14 @@ __global__ __launch_bounds__(WM * WN * 64 * KG, MINW) void int8_gemm_kernel(Gemm
             }
         }
     }
-    if constexpr (SPLITK) {
+    if constexpr (SPLITK && ADT == HERO_I8) {
         static_assert(EPI == HERO_EPI_RAW_I32, "split-K writes raw partial sums");
         GemmArgs gp = g;
         gp.C = (int32_t*)g.C + (int64_t)blockIdx.y * g.M * g.ldc;
         epilogue_direct<BM, BN, WM, WN, EPI, CDT, RDT>(gp, acc, sv, rsr, m0, n0, tid);
         return;
     }
-    epilogue_direct<BM, BN, WM, WN, EPI, CDT, RDT>(g, acc, sv, rsr, m0, n0, tid);
+    epilogue_direct<BM, BN, WM, WN, EPI, CDT, RDT, false, false>(g, acc, sv, rsr, m0, n0, tid);
 }
 
 // =====================================================================================
@@ -584,20 +608,10 @@ __device__ __forceinline__ void dma4s(uint32_t voff, const float* sbase, uint32_
                  :: "v"(voff), "s"(sbase), "s"(lds_base) : "memory", "m0");
 }
 
-// ADT = HERO_I8: INT8 operands, int32 accumulators.  ADT = HERO_BF16: bf16 operands (the BF16 side of a
-// switched module, Sec. 2.3 / Table 1), fp32 accumulators, no scales; K, lda and ldb are then in BYTES,
-// and a 64-byte slab holds two v_mfma_f32_32x32x16_bf16 steps exactly as it holds two INT8 steps.
-typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
-template <int ADT, typename ACC>
-__device__ __forceinline__ ACC mfma_step(v4i a, v4i b, ACC c) {
-    if constexpr (ADT == HERO_I8) return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0);
-    else return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a), __builtin_bit_cast(v8bf, b), c, 0, 0, 0);
-}
-
 template <int NS, int EPI, int CDT, int RDT, int ADT = HERO_I8>
 __global__ __launch_bounds__(512, 2) void int8_gemm_persistent_kernel(GemmArgs g) {
-    using ACC = typename std::conditional<ADT == HERO_I8, v16i, v16f>::type;
-    constexpr bool UNIT = ADT != HERO_I8;
+    using ACC = typename AccOf<ADT>::type;
+    constexpr bool UNIT = ADT == HERO_BF16;
     constexpr int BM = 256, BN = 256, WM = 2, WN = 4;
     constexpr int NT = WM * WN * 64, NWAVE = WM * WN;
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
@@ -931,6 +945,69 @@ hero_status hero_bf16_gemm_large(const void* A, int64_t lda, const void* Wt, int
         else hipLaunchKernelGGL((int8_gemm_persistent_kernel<4, HERO_EPI_DEQUANT, HERO_BF16, -1, HERO_BF16>), grid, block, 0, st, g);
     }
     return hero_launch_status();
+}
+
+// The FP8 variant: the same kernels with E4M3 operands (no split-K: fp32 partial sums would not commute).
+template <int EPI, int CDT, int RDT>
+hero_status launch_epi_fp8(GemmArgs g, hipStream_t st) {
+    const int64_t t256 = (int64_t)((g.M + 255) / 256) * ((g.N + 255) / 256), t128 = (int64_t)((g.M + 127) / 128) * ((g.N + 127) / 128);
+    if (t256 >= 96 && t256 <= 0x7fffff00LL && g.K >= 4 * BK && g.lda < (1 << 24) && g.ldb < (1 << 24)) {
+        g.ntm = (g.M + 255) / 256; g.ntn = (g.N + 255) / 256;
+        g.per_xcd = (int)((t256 + NUM_XCD - 1) / NUM_XCD);
+        const int nslot = g.per_xcd < 32 ? g.per_xcd : 32;
+        hipLaunchKernelGGL((int8_gemm_persistent_kernel<4, EPI, CDT, RDT, HERO_F8E4M3>), dim3((unsigned)(nslot * NUM_XCD)), dim3(512), 0, st, g);
+        return hero_launch_status();
+    }
+    if (g.M <= 64 || t128 < 192)
+        return launch_grid(g, 64, 64, 256, int8_gemm_kernel<64, 64, 2, 2, 2, 2, EPI, CDT, RDT, false, 1, HERO_F8E4M3>, st);
+    return launch_grid(g, 128, 128, 256, int8_gemm_kernel<128, 128, 2, 2, 2, 2, EPI, CDT, RDT, false, 1, HERO_F8E4M3>, st);
+}
+
+extern "C" hero_status hero_fp8_gemm(const void* A, int64_t lda, const float* a_row_scale,
+                                     const void* Bt, int64_t ldb, const float* b_col_scale,
+                                     const float* bias, const void* residual, hero_dtype res_dt, int64_t ldr,
+                                     hero_epilogue epi, const float* out_col_scale,
+                                     void* C, hero_dtype c_dt, int64_t ldc,
+                                     int64_t M, int64_t N, int64_t K, void* stream) {
+    if (M < 0 || N < 0 || K <= 0) return HERO_ERR_SHAPE;
+    if (M > 0x7fffffffLL || N > 0x7fffffffLL || K > 0x7fffffffLL) return HERO_ERR_SHAPE;
+    if (K % KMULT != 0) return HERO_ERR_UNSUPPORTED;
+    if (lda < K || ldb < K || ldc < N) return HERO_ERR_SHAPE;
+    if (M == 0 || N == 0) return HERO_OK;
+    if (!A || !Bt || !C || !b_col_scale) return HERO_ERR_NULL;
+    if (epi == HERO_EPI_GELU_REQUANT && !out_col_scale) return HERO_ERR_NULL;
+    const bool c16 = c_dt == HERO_F16 || c_dt == HERO_BF16;
+    switch (epi) {
+    case HERO_EPI_DEQUANT: case HERO_EPI_DEQUANT_GELU: if (!c16) return HERO_ERR_UNSUPPORTED; break;
+    case HERO_EPI_REQUANT: case HERO_EPI_GELU_REQUANT: if (c_dt != HERO_F8E4M3) return HERO_ERR_UNSUPPORTED; break;
+    default: return HERO_ERR_UNSUPPORTED;
+    }
+    if (residual) {
+        if (epi != HERO_EPI_DEQUANT || res_dt != c_dt) return HERO_ERR_UNSUPPORTED;
+        if (ldr < N) return HERO_ERR_SHAPE;
+        if (ldr % 4 != 0 || !hero_aligned16(residual)) return HERO_ERR_ALIGN;
+    }
+    if (lda % 16 != 0 || ldb % 16 != 0 || ldc % 4 != 0) return HERO_ERR_ALIGN;
+    if (!hero_aligned16(A) || !hero_aligned16(Bt) || !hero_aligned16(C)) return HERO_ERR_ALIGN;
+    GemmArgs g;
+    g.A = (const int8_t*)A; g.lda = lda; g.a_row_scale = a_row_scale; g.Bt = (const int8_t*)Bt; g.ldb = ldb; g.b_col_scale = b_col_scale;
+    g.bias = bias; g.residual = residual; g.ldr = ldr; g.out_col_scale = out_col_scale;
+    g.C = C; g.ldc = ldc; g.M = (int)M; g.N = (int)N; g.K = (int)K;
+    g.ksplit = 1; g.kslabs = 0;
+    hipStream_t st = (hipStream_t)stream;
+    switch (epi) {
+    case HERO_EPI_REQUANT: return launch_epi_fp8<HERO_EPI_REQUANT, HERO_F8E4M3, -1>(g, st);
+    case HERO_EPI_GELU_REQUANT: return launch_epi_fp8<HERO_EPI_GELU_REQUANT, HERO_F8E4M3, -1>(g, st);
+    case HERO_EPI_DEQUANT_GELU:
+        return c_dt == HERO_BF16 ? launch_epi_fp8<HERO_EPI_DEQUANT_GELU, HERO_BF16, -1>(g, st)
+                                 : launch_epi_fp8<HERO_EPI_DEQUANT_GELU, HERO_F16, -1>(g, st);
+    default:
+        if (!residual)
+            return c_dt == HERO_BF16 ? launch_epi_fp8<HERO_EPI_DEQUANT, HERO_BF16, -1>(g, st)
+                                     : launch_epi_fp8<HERO_EPI_DEQUANT, HERO_F16, -1>(g, st);
+        return c_dt == HERO_BF16 ? launch_epi_fp8<HERO_EPI_DEQUANT, HERO_BF16, HERO_BF16>(g, st)
+                                 : launch_epi_fp8<HERO_EPI_DEQUANT, HERO_F16, HERO_F16>(g, st);
+    }
 }
 
 extern "C" size_t hero_int8_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K) {

@@ -10,6 +10,8 @@ def to_np(t):
     t = t.detach().cpu()
     if t.dtype in (torch.bfloat16, torch.float16):
         return t.view(torch.int16).numpy().view(np.uint16)
+    if t.dtype == torch.float8_e4m3fn:
+        return t.view(torch.uint8).numpy()
     return t.numpy()
 
 
@@ -65,3 +67,18 @@ def upload_weights(hero, w):
     t["attn_out_scale"] = dev(w["attn_out_scale"] if mode & HB.M_ATTN_OUT else w["attn_out_scalar"])
     qk = float(w["qk_scale"] if mode & HB.M_ATTN else w["bf16_qk_scale"])
     return hero.layer_weights(t, qk, float(w["S_p"])), t
+
+
+def assert_fp8_codes(got, ref, decode, what="", max_frac=1e-3, acc_rel=0.0):
+    """E4M3 codes: equal on all but max_frac of the elements, and where they differ the decoded values are
+    within one E4M3 step plus acc_rel x rms(ref): the matrix cores' accumulation carries an error that is a
+    fraction of the TYPICAL dot product, not of the individual one, so an output much smaller than typical may
+    move by more than its own (fine) grid step.  The caller derives max_frac and acc_rel."""
+    g, o = decode(got).astype(np.float64), decode(ref).astype(np.float64)
+    step = np.maximum(2.0 ** (np.floor(np.log2(np.maximum(np.abs(o), 2.0 ** -6))) - 3), 2.0 ** -9)
+    slack = acc_rel * np.sqrt(np.mean(o * o))
+    bad = np.abs(g - o) > step * 1.0001 + slack
+    assert not bad.any(), f"{what}: {np.count_nonzero(bad)} codes are further away than one step + {slack:.3g}"
+    frac = np.count_nonzero(got != ref) / got.size
+    assert frac <= max_frac, f"{what}: {frac:.2e} of the codes differ (limit {max_frac:.0e})"
+    return frac
