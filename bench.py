@@ -34,6 +34,7 @@ MEASURED_TRAFFIC = {
 }
 
 PEAK_INT8_TOPS = 5000.0      # MI355X dense INT8 MFMA, TOP/s
+PEAK_FP8_TFLOPS = 5000.0    # MI355X dense FP8 MFMA, TFLOP/s
 PEAK_HBM_GBS = 8000.0        # MI355X HBM3E, GB/s
 
 WORKLOADS = {"bert-base": 0, "bert-large": 2, "gpt-prefill": 3, "gpt-decode": 4}
@@ -182,6 +183,32 @@ def gemm_sweep(hero, seed, iters=10):
                 tops = 2.0 * M * N * K / (ms * 1e-3) / 1e12
                 rows.append({"M": M, "K": K, "N": N, "out": name, "us": round(ms * 1e3, 2), "tops": round(tops, 1),
                              "frac_peak": round(tops / PEAK_INT8_TOPS, 4)})
+    return rows
+
+
+def fp8_gemm_leg(hero, shape, seed, iters=20):
+    """The FP8 variant of the layer's two big GEMMs (Sec. 2.1 names FP8 as the alternative 8-bit format):
+    E4M3 operands from Gaussian data under token-wise / column-wise scales, E4M3 outputs."""
+    import torch
+    from paper_2310_17723_amd import binding as HB
+    g = torch.Generator(device="cuda").manual_seed(seed)
+    M, d, f = shape.B * shape.S, shape.d, shape.f
+    rows = []
+    for name, N, K, epi in (("FC1 GELU^quant", f, d, HB.EPI_GELU_REQUANT), ("FC2 requant", d, f, HB.EPI_REQUANT)):
+        X = torch.randn((M, K), device="cuda", generator=g)
+        W = torch.randn((N, K), device="cuda", generator=g) * 0.03
+        rs = X.abs().amax(dim=1) / 448
+        cs = W.abs().amax(dim=1) / 448
+        A = (X / rs[:, None]).to(torch.float8_e4m3fn)
+        Bt = (W / cs[:, None]).to(torch.float8_e4m3fn)
+        bias = torch.randn(N, device="cuda", generator=g) * 0.02
+        s_out = torch.full((N,), 0.03, dtype=torch.float32, device="cuda")
+        cs2 = cs / 0.05 if epi == HB.EPI_REQUANT else cs
+        out = torch.empty((M, N), dtype=torch.float8_e4m3fn, device="cuda")
+        ms = time_gpu(lambda: hero.hero_fp8_gemm(A, Bt, rs, cs2, bias, epi=epi, out_col_scale=s_out, C_out=out), iters)
+        tf = 2.0 * M * N * K / (ms * 1e-3) / 1e12
+        rows.append({"gemm": name, "shape_mnk": [M, N, K], "us": round(ms * 1e3, 2), "tflops": round(tf, 1),
+                     "peak": PEAK_FP8_TFLOPS, "frac_peak": round(tf / PEAK_FP8_TFLOPS, 4)})
     return rows
 
 
@@ -372,6 +399,8 @@ def main():
         rec["ln_quant"] = ln_bandwidth(hero, max(st.T, 16384), shape.d)
         rec["ln_quant_large"] = ln_bandwidth(hero, 65536, shape.d, nbuf=4)
         rec["embed_ln_quant"] = embed_bandwidth(hero, 32, 512, shape.d)
+        log("[bench] FP8 variant of the FC1 / FC2 GEMMs")
+        rec["fp8_gemm"] = fp8_gemm_leg(hero, shape, args.seed)
         log("[bench] GEMM sweep")
         rec["gemm_sweep"] = gemm_sweep(hero, args.seed)
         del st

@@ -63,6 +63,12 @@ __device__ __forceinline__ ACC mfma_step(v4i a, v4i b, ACC c) {
         return __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(a1, b1, c, 0, 0, 0);
     }
 }
+// FP8 at the full matrix rate: K = 64 per instruction, each lane half carries 32 bytes of its row.
+__device__ __forceinline__ v16f mfma_wide_f8(v4i a_lo, v4i a_hi, v4i b_lo, v4i b_hi, v16f c) {
+    const v8i a = {a_lo[0], a_lo[1], a_lo[2], a_lo[3], a_hi[0], a_hi[1], a_hi[2], a_hi[3]};
+    const v8i b = {b_lo[0], b_lo[1], b_lo[2], b_lo[3], b_hi[0], b_hi[1], b_hi[2], b_hi[3]};
+    return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 0, 0, 0, 0, 0, 0);   // E4M3 x E4M3, unit scales
+}
 template <int ADT> struct AccOf { using type = typename std::conditional<ADT == HERO_I8, v16i, v16f>::type; };
 
 template <int CDT> struct ElemSize { static constexpr int v = CDT == HERO_I32 ? 4 : ((CDT == HERO_I8 || CDT == HERO_F8E4M3) ? 1 : 2); };
@@ -612,13 +618,14 @@ template <int NS, int EPI, int CDT, int RDT, int ADT = HERO_I8>
 __global__ __launch_bounds__(512, 2) void int8_gemm_persistent_kernel(GemmArgs g) {
     using ACC = typename AccOf<ADT>::type;
     constexpr bool UNIT = ADT == HERO_BF16;
+    constexpr bool WIDE = ADT == HERO_F8E4M3;
     constexpr int BM = 256, BN = 256, WM = 2, WN = 4;
     constexpr int NT = WM * WN * 64, NWAVE = WM * WN;
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
     constexpr int A_BYTES = BM * BK, B_BYTES = BN * BK, STAGE = A_BYTES + B_BYTES;
     constexpr int A_UNITS = A_BYTES / 16 / NT, B_UNITS = B_BYTES / 16 / NT, NW = A_UNITS + B_UNITS;
     constexpr int NM = TM * TN, NFR = TM + TN;
-    static_assert(NS >= 3 && NW <= NM && NFR <= NM, "ring / interleave plan");
+    static_assert(NS >= 3 && NW <= NM && NFR <= NM && NW <= NM - (TM - 1), "ring / interleave plan");
     constexpr int RING = NS * STAGE;
     constexpr int SVF = 4 * BN;                                  // floats per vector set: column scale, bias, S_a, row scale
     static_assert(BM == BN, "the row-scale vector shares the column vectors' length");
@@ -721,6 +728,9 @@ __global__ __launch_bounds__(512, 2) void int8_gemm_persistent_kernel(GemmArgs g
         v4i f0[NFR], f1[NFR];
 #pragma unroll
         for (int t = 0; t < NFR; ++t) f0[t] = *reinterpret_cast<const v4i*>(smem + stage * STAGE + fo[0][t]);
+        if (WIDE)
+#pragma unroll
+            for (int t = 0; t < NFR; ++t) f1[t] = *reinterpret_cast<const v4i*>(smem + stage * STAGE + fo[1][t]);
 
         // One slab per iteration with the barrier in the middle (see int8_gemm_dma_kernel); the slab issued
         // in iteration kt is the one NS-1 ahead in the stream, which may already belong to the next tile.
@@ -730,6 +740,36 @@ __global__ __launch_bounds__(512, 2) void int8_gemm_persistent_kernel(GemmArgs g
             const int pstage = stage == 0 ? NS - 1 : stage - 1;
             const int8_t* stn = smem + nstage * STAGE;
             __builtin_amdgcn_sched_barrier(0);
+            if constexpr (WIDE) {
+                // FP8: one 32x32x64 matrix instruction per accumulator and slab (both k halves of a fragment
+                // side by side: any K grouping shared by the two operands is the same contraction).  A
+                // fragment is reloaded from the next slab right after its last use; the barrier that
+                // publishes that slab sits after the first TM instructions.
+#pragma unroll
+                for (int n = 0; n < NM; ++n) {
+                    const int jj = n / TM, ii = n % TM;
+                    acc[ii][jj] = mfma_wide_f8(f0[jj], f1[jj], f0[TN + ii], f1[TN + ii], acc[ii][jj]);
+                    if (n == TM - 1) {
+                        __builtin_amdgcn_s_waitcnt(vmcnt_imm((NS - 3) * NW));
+                        __syncthreads();
+                    }
+                    if (n >= TM - 1) {
+#pragma unroll
+                        for (int t = 0; t < NFR; ++t) {
+                            const int last = t < TN ? t * TM + TM - 1 : (TN - 1) * TM + (t - TN);
+                            if ((last < TM - 1 ? TM - 1 : last) == n) {
+                                f0[t] = *reinterpret_cast<const v4i*>(stn + fo[0][t]);
+                                f1[t] = *reinterpret_cast<const v4i*>(stn + fo[1][t]);
+                            }
+                        }
+                        if (n - (TM - 1) < NW) issue(n - (TM - 1), pstage);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                advance();
+                stage = nstage;
+                continue;
+            }
 #pragma unroll
             for (int n = 0; n < NM; ++n) {                             // k-step 0
                 const int jj = n / TM, ii = n % TM;
