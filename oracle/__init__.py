@@ -334,6 +334,28 @@ def int8_attn(q, k, v, *, qk_scale, p_scale, out_col_scale, out_scale_is_scalar=
     return (out, pd) if dump_p else out
 
 
+def int8_attn_online(q, k, v, *, qk_scale_h, p_scale, out_col_scale, out_scale_is_scalar=False,
+                     mask=MASK_NONE, kv_len=None, out_dt=I8, kv_block=64, dump_c=False):
+    """INT8 attention with the online (quantize-then-normalise) Softmax^quant variant.  qk_scale_h: one d~ per
+    head.  The other arguments as for int8_attn (the same out_col_scale and p_scale)."""
+    B, Sq, H, Dh = q.shape
+    Skv = k.shape[1]
+    ocs = np.ascontiguousarray(out_col_scale, np.float32).reshape(-1)
+    qsh = np.ascontiguousarray(np.broadcast_to(np.asarray(qk_scale_h, np.float32), (H,)))
+    if kv_len is not None:
+        kv_len = np.ascontiguousarray(kv_len, np.int32)
+    out = np.empty((B * Sq, H * Dh), _NP_OF[out_dt])
+    cd = np.zeros((B, H, Sq, Skv), np.uint8) if dump_c else None
+    base = lambda a: C.c_void_p(a.ctypes.data)
+    rc = lib().orc_int8_attn_online(base(q), _strides(q), base(k), _strides(k), base(v), _strides(v),
+                                    _i64(B), _i64(H), _i64(Sq), _i64(Skv), _i64(Dh), _i64(kv_block),
+                                    _p(qsh), C.c_float(p_scale), _p(ocs), C.c_int(int(out_scale_is_scalar)),
+                                    C.c_int(mask), _p(kv_len), _p(out), C.c_int(out_dt), _i64(H * Dh), _p(cd))
+    if rc != 0:
+        raise ValueError("oracle int8_attn_online: invalid arguments")
+    return (out, cd) if dump_c else out
+
+
 # ------------------------------------------------------------------ BF16 side
 def bf16_gemm(A, Wt, bias=None, residual=None, gelu=False) -> np.ndarray:
     A = np.ascontiguousarray(A, np.uint16)

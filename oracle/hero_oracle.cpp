@@ -497,6 +497,91 @@ int orc_int8_attn(const int8_t* q, const int64_t* qs, const int8_t* k, const int
 }
 
 // ---------------------------------------------------------------------------------
+// O6b.  INT8 attention with an ONLINE Softmax^quant -- a variant, not the equation of Sec. 2.2.2:
+// the probabilities are quantized BEFORE they are normalised, block by block, against the running row
+// maximum, so one sweep over the keys suffices and the largest weight of a row always has code 255.
+// The same operands, masks and output scales as orc_int8_attn; qk_scale is per head.
+// Per (batch, head), query i, with the visible keys 0 .. nvis-1 cut into blocks of kv_block keys
+// (block t = keys [t*kv_block, (t+1)*kv_block), aligned to key 0):
+//   a[k]   = float(acc_qk[i][k]) * d~[h]                                  fp32, as in O6
+//   m_t    = max(m_{t-1}, max_{k in t} a[k]),  m_{-1} = -inf              running maximum
+//   c[k]   = sat_[0,255](rne(float(255 exp(a[k] - m_t))))                 unsigned codes, k in block t
+//   O_t[e] = sum_{k in t} c[k] V[k][e],   L_t = sum_{k in t} c[k]          exact integers
+//   O[e]   = sum_t exp(m_t - m_T) O_t[e],  L = sum_t exp(m_t - m_T) L_t    (T = last block; fp64)
+//   X_attn = S_v O / L ;  out = sat(rne(float(O[e] / L * c[j] / S_p)))  with c[j] = S_p S_v / S_attn[j] as in
+//   O6 (the caller passes the same c and S_p as for the two-pass operator: S_p cancels), or float(.) for a
+//   16-bit output with c[0] = S_p S_v.  A query with no visible key outputs 0.
+// c_dump (optional) receives the codes [B,H,Sq,Skv].
+// ---------------------------------------------------------------------------------
+int orc_int8_attn_online(const int8_t* q, const int64_t* qs, const int8_t* k, const int64_t* ks,
+                         const int8_t* v, const int64_t* vs,
+                         int64_t B, int64_t H, int64_t Sq, int64_t Skv, int64_t Dh, int64_t kv_block,
+                         const float* qk_scale_h, float p_scale, const float* out_col_scale, int out_scale_is_scalar,
+                         int mask, const int32_t* kv_len,
+                         void* out, int out_dt, int64_t ldo, uint8_t* c_dump) {
+    if (out_dt == ORC_I8 && out_scale_is_scalar == 0 && !out_col_scale) return -1;
+    if (mask == ORC_MASK_PADDING && !kv_len) return -1;
+    if (kv_block <= 0 || !qk_scale_h) return -1;
+#pragma omp parallel for schedule(dynamic) collapse(2)
+    for (int64_t b = 0; b < B; ++b)
+        for (int64_t h = 0; h < H; ++h) {
+            int64_t len = kv_len ? std::min<int64_t>(kv_len[b], Skv) : Skv;
+            std::vector<float> a(Skv);
+            std::vector<int32_t> codes(Skv);
+            std::vector<double> O(Dh);
+            for (int64_t i = 0; i < Sq; ++i) {
+                int64_t last = len - 1;
+                if (mask == ORC_MASK_CAUSAL) last = std::min<int64_t>(last, i + (len - Sq));
+                const int64_t nvis = last + 1;
+                const int8_t* qi = q + b * qs[0] + i * qs[1] + h * qs[2];
+                for (int64_t kk = 0; kk < nvis; ++kk) {
+                    const int8_t* kr = k + b * ks[0] + kk * ks[1] + h * ks[2];
+                    int32_t acc = 0;
+                    for (int64_t e = 0; e < Dh; ++e) acc += (int32_t)qi[e * qs[3]] * (int32_t)kr[e * ks[3]];
+                    volatile float t = (float)acc * qk_scale_h[h];
+                    a[kk] = t;
+                }
+                for (int64_t kk = 0; kk < Skv; ++kk) codes[kk] = 0;
+                for (int64_t e = 0; e < Dh; ++e) O[e] = 0.0;
+                double L = 0.0, m = -INFINITY;
+                for (int64_t k0 = 0; k0 < nvis; k0 += kv_block) {
+                    const int64_t k1 = std::min(k0 + kv_block, nvis);
+                    double mt = m;
+                    for (int64_t kk = k0; kk < k1; ++kk) mt = std::max(mt, (double)a[kk]);
+                    const double rescale = (m == -INFINITY) ? 0.0 : std::exp(m - mt);   // exp(m_{t-1} - m_t)
+                    int64_t Lt = 0;
+                    for (int64_t kk = k0; kk < k1; ++kk) {
+                        volatile float w = (float)(255.0 * std::exp((double)a[kk] - mt));
+                        float rr = std::nearbyintf(w);
+                        codes[kk] = rr > 255.0f ? 255 : (rr < 0.0f ? 0 : (int32_t)rr);
+                        Lt += codes[kk];
+                    }
+                    L = L * rescale + (double)Lt;
+                    for (int64_t e = 0; e < Dh; ++e) {
+                        int64_t Ot = 0;
+                        for (int64_t kk = k0; kk < k1; ++kk)
+                            Ot += (int64_t)codes[kk] * (int64_t)v[b * vs[0] + kk * vs[1] + h * vs[2] + e * vs[3]];
+                        O[e] = O[e] * rescale + (double)Ot;
+                    }
+                    m = mt;
+                }
+                if (c_dump)
+                    for (int64_t kk = 0; kk < Skv; ++kk)
+                        c_dump[((b * H + h) * Sq + i) * Skv + kk] = (uint8_t)codes[kk];
+                for (int64_t e = 0; e < Dh; ++e) {
+                    const int64_t j = h * Dh + e;
+                    const int64_t o = (b * Sq + i) * ldo + j;
+                    const float c = out_scale_is_scalar ? out_col_scale[0] : out_col_scale[j];
+                    volatile float y = nvis > 0 ? (float)(O[e] / L * (double)c / (double)p_scale) : 0.0f;
+                    if (out_dt == ORC_I8) ((int8_t*)out)[o] = sat_i8(std::nearbyintf(y));
+                    else store_hp(out, out_dt, o, y);
+                }
+            }
+        }
+    return 0;
+}
+
+// ---------------------------------------------------------------------------------
 // BF16 side of a switched module (Sec. 2.3, Table 1: a module marked with a cross runs
 // in FP16/BF16).  Operands are bf16 values; the sums are carried in fp64 and rounded
 // to bf16 once at the end, so this is the value any correct fp32-accumulating kernel

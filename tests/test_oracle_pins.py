@@ -543,6 +543,118 @@ def test_attention_strided_views_and_offset_identity():
     assert np.array_equal(Pi @ V, (Pi - 128) @ V + 128 * V.sum(axis=2, keepdims=True))
 
 
+def test_attention_online_closed_forms():
+    """The online Softmax^quant variant (codes against the running block maximum, normalised at the end):
+    closed forms that a dropped rescale, a wrong exponent sign or a wrong block boundary would break."""
+    B, S, H, Dh = 1, 12, 2, 8
+    q, k, v = _attn_inputs(30, B, S, S, H, Dh)
+    sp = float(OL.S_P)
+    unit = np.full(H * Dh, sp, np.float32)              # c[j] = S_p  ->  the output is O / L itself
+    kw = dict(p_scale=sp, out_col_scale=unit, out_dt=O.F32, out_scale_is_scalar=True)
+    # (1) equal scores, causal: every visible code is 255, the output is the mean of the visible V rows
+    out, Cd = O.int8_attn_online(np.zeros_like(q), k, v, qk_scale_h=[0.01, 0.02], mask=O.MASK_CAUSAL, kv_block=5,
+                                 dump_c=True, **kw)
+    for i in range(S):
+        assert (Cd[0, :, i, :i + 1] == 255).all() and (Cd[0, :, i, i + 1:] == 0).all()
+        for h in range(H):
+            mean = v[0, :i + 1, h, :].astype(np.float64).mean(axis=0)
+            np.testing.assert_allclose(out[i, h * Dh:(h + 1) * Dh], mean, rtol=1e-6, atol=1e-6)
+    # (2) three blocks of 4 keys with one score level each: s0 < s2 < s1.  Blocks 0 and 1 are all 255 (each is
+    # the running maximum when it arrives), block 2 gets c2 = rne(255 exp(s2 - s1)), block 0 is rescaled by
+    # exp(s0 - s1) at the end.
+    qd = np.zeros_like(q)
+    qd[..., 0] = 100
+    kd = np.zeros_like(k)
+    lev = [-30, 50, 20]
+    for t in range(3):
+        kd[0, 4 * t:4 * t + 4, :, 0] = lev[t]
+    dts = np.float32([3e-4, 5e-4])
+    out, Cd = O.int8_attn_online(qd, kd, v, qk_scale_h=dts, kv_block=4, dump_c=True, **kw)
+    for h in range(H):
+        s0, s1, s2 = (float(np.float32(100 * l) * dts[h]) for l in lev)
+        c2 = round(float(np.float32(255.0 * math.exp(s2 - s1))))
+        assert (Cd[0, h, :, :8] == 255).all() and (Cd[0, h, :, 8:] == c2).all() and 0 < c2 < 255
+        V = v[0, :, h, :].astype(np.float64)
+        r0 = math.exp(s0 - s1)
+        num = r0 * 255 * V[0:4].sum(0) + 255 * V[4:8].sum(0) + c2 * V[8:12].sum(0)
+        den = r0 * 255 * 4 + 255 * 4 + c2 * 4
+        for i in range(S):
+            np.testing.assert_allclose(out[i, h * Dh:(h + 1) * Dh], num / den, rtol=1e-6, atol=1e-6)
+    # with the levels in ascending block order the last block is the maximum and c2 never appears
+    # (3) one dominant key -> its V row, whatever block it sits in
+    kd = np.zeros_like(k)
+    kd[0, 9, :, 0] = 127
+    qd[..., 0] = 127
+    out = O.int8_attn_online(qd, kd, v, qk_scale_h=0.01, kv_block=4, **kw)
+    for h in range(H):
+        np.testing.assert_allclose(out[:, h * Dh:(h + 1) * Dh], np.repeat(v[0, 9:10, h, :], S, 0).astype(np.float32), rtol=1e-6)
+    # (4) keys permuted inside their blocks: the same integers, the same output, bit for bit
+    g = synth.rng(31)
+    perm = np.concatenate([4 * t + g.permutation(4) for t in range(3)])
+    cs = g.uniform(2e-5, 6e-5, H * Dh).astype(np.float32)
+    a1 = O.int8_attn_online(q, k, v, qk_scale_h=3e-4, p_scale=sp, out_col_scale=cs, kv_block=4)
+    a2 = O.int8_attn_online(q, k[:, perm], v[:, perm], qk_scale_h=3e-4, p_scale=sp, out_col_scale=cs, kv_block=4)
+    assert np.array_equal(a1, a2)
+
+
+@pytest.mark.parametrize("mask", [O.MASK_NONE, O.MASK_PADDING, O.MASK_CAUSAL])
+def test_attention_online_single_block_against_numpy_and_masks_by_truncation(mask):
+    """One block covering all keys: the codes are rne(255 exp(a - max)) and the output their normalised
+    combination, written out with numpy / scipy; the masks are checked by truncating the inputs instead."""
+    B, Sq, Skv, H, Dh = 3, 9, 9, 2, 16
+    q, k, v = _attn_inputs(32, B, Sq, Skv, H, Dh)
+    kv_len = np.int32([9, 5, 0]) if mask == O.MASK_PADDING else (np.int32([9, 6, 3]) if mask == O.MASK_CAUSAL else None)
+    dts, sp = np.float32([2.5e-4, 4e-4]), float(OL.S_P)
+    cs = synth.rng(33).uniform(0.5, 1.5, H * Dh).astype(np.float32) * np.float32(sp)
+    out, Cd = O.int8_attn_online(q, k, v, qk_scale_h=dts, p_scale=sp, out_col_scale=cs, mask=mask, kv_len=kv_len,
+                                 out_dt=O.I8, kv_block=64, dump_c=True)
+    for b in range(B):
+        L = Skv if kv_len is None else int(kv_len[b])
+        for h in range(H):
+            a = (q[b, :, h].astype(np.int64) @ k[b, :, h].astype(np.int64).T).astype(np.float32) * dts[h]
+            for i in range(Sq):
+                n = max(L if mask != O.MASK_CAUSAL else min(L, i + (L - Sq) + 1), 0)
+                codes = np.zeros(Skv, np.int64)
+                exp = np.zeros(Dh, np.int8)
+                if n > 0:
+                    w = scipy.special.softmax(a[i, :n].astype(np.float64))
+                    codes[:n] = np.rint((255.0 * w / w.max()).astype(np.float32)).astype(np.int64)
+                    y = (codes @ v[b, :, h].astype(np.int64)) / codes.sum() * cs[h * Dh:(h + 1) * Dh].astype(np.float64) / sp
+                    exp = np.clip(np.rint(y.astype(np.float32)), -127, 127).astype(np.int8)
+                assert np.array_equal(Cd[b, h, i], codes.astype(np.uint8))
+                assert np.array_equal(out[b * Sq + i, h * Dh:(h + 1) * Dh], exp)
+                if n > 0 and mask != O.MASK_NONE and i % 4 == 0:    # a masked row = an unmasked call on the visible prefix
+                    sub = O.int8_attn_online(q[b:b + 1, i:i + 1], k[b:b + 1, :n], v[b:b + 1, :n], qk_scale_h=dts, p_scale=sp,
+                                             out_col_scale=cs, out_dt=O.I8, kv_block=4)
+                    ref = O.int8_attn_online(q, k, v, qk_scale_h=dts, p_scale=sp, out_col_scale=cs, mask=mask, kv_len=kv_len,
+                                             out_dt=O.I8, kv_block=4)
+                    assert np.array_equal(sub[0, h * Dh:(h + 1) * Dh], ref[b * Sq + i, h * Dh:(h + 1) * Dh])
+
+
+def test_attention_online_accuracy_against_exact_softmax_and_two_pass():
+    """Accuracy of the variant against the exact (unquantized-P) attention on the same INT8 operands: every
+    weight is off by at most half a code of ITS block's scale, which bounds the output error; and on long,
+    diffuse rows (where the normalised probabilities of the two-pass form use only a few codes) it is the more
+    accurate of the two."""
+    B, Sq, Skv, H, Dh = 1, 16, 256, 2, 16
+    q, k, v = _attn_inputs(34, B, Sq, Skv, H, Dh)
+    sp, dt = float(OL.S_P), np.float32(1.2e-4)
+    unit = np.full(H * Dh, sp, np.float32)
+    on = O.int8_attn_online(q, k, v, qk_scale_h=dt, p_scale=sp, out_col_scale=unit, out_dt=O.F32, out_scale_is_scalar=True, kv_block=64)
+    tp, P = O.int8_attn(q, k, v, qk_scale=float(dt), p_scale=sp, out_col_scale=unit, out_dt=O.F32, out_scale_is_scalar=True, dump_p=True)
+    exact = np.empty_like(on, dtype=np.float64)
+    for h in range(H):
+        a = (q[0, :, h].astype(np.int64) @ k[0, :, h].astype(np.int64).T).astype(np.float32) * dt
+        w = scipy.special.softmax(a.astype(np.float64), axis=1)
+        exact[:, h * Dh:(h + 1) * Dh] = w @ v[0, :, h].astype(np.float64)
+        # hard bound: |w~ - w| <= 0.5/255 per key relative to the row maximum (rescale factors are <= 1)
+        bound = 2 * 127 * Skv * (0.5 / 255) / (w / w.max(axis=1, keepdims=True)).sum(axis=1)
+        assert (np.abs(on[:, h * Dh:(h + 1) * Dh] - exact[:, h * Dh:(h + 1) * Dh]).max(axis=1) <= bound).all()
+    snr = lambda x: 10 * math.log10(float((exact ** 2).sum() / ((x - exact) ** 2).sum()))
+    print("SNR online %.1f dB, two-pass %.1f dB" % (snr(on), snr(tp)))     # O6 with c[0] = S_p returns sum_k P v S_p
+    assert snr(on) > 35 and snr(on) > snr(tp) + 6, (snr(on), snr(tp))
+
+
 # ---------------------------------------------------------------- BF16 side
 def test_bf16_ops_against_torch_fp64():
     g = synth.rng(14)
