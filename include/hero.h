@@ -199,6 +199,30 @@ hero_status hero_int8_attn(const int8_t* q, const int64_t q_strides[4],
                            hero_mask mask, const int32_t* kv_len,
                            void* out, hero_dtype out_dt, int64_t ldo, void* stream);
 
+/* INT8 attention with an ONLINE Softmax^quant: a single-sweep VARIANT of the flow above, not the
+ * equation of Sec. 2.2.2 (which normalises before it quantizes).  The probabilities are quantized
+ * un-normalised, in blocks of 64 keys, against the running row maximum, and normalised once at the
+ * end; the largest weight of a row always has code 255 whatever the sequence length.
+ * Per (b, h), query i, visible keys 0 .. n-1 in blocks t = [64t, 64t + 64) (aligned to key 0):
+ *   a[k]   = float(sum_e q k) * qk_scale_h[h]              one d~ per head (device array f32[H])
+ *   m_t    = max(m_{t-1}, max_{k in t} a[k])               running maximum
+ *   c[k]   = sat_[0,255](rne(255 exp(a[k] - m_t)))         unsigned codes of block t
+ *   O[e]   = sum_t exp(m_t - m_T) sum_{k in t} c[k] v[k][e]   (integer inner sums, exact)
+ *   L      = sum_t exp(m_t - m_T) sum_{k in t} c[k]
+ *   y      = O[e] / L * out_col_scale[j] / p_scale ;  INT8: sat(rne(y)), 16-bit: y with
+ *            out_col_scale[0]
+ * out_col_scale and p_scale mean what they mean for hero_int8_attn (S_p S_v / S_attn[j] and S_p;
+ * S_p cancels), so the two are interchangeable; masks, strides, constraints and errors are the
+ * same, plus HERO_ERR_NULL without qk_scale_h.  Any Sq runs through the same kernel (a one-query
+ * decode call is served but not specialised). */
+hero_status hero_int8_attn_online(const int8_t* q, const int64_t q_strides[4],
+                                  const int8_t* k, const int64_t k_strides[4],
+                                  const int8_t* v, const int64_t v_strides[4],
+                                  int64_t B, int64_t H, int64_t Sq, int64_t Skv, int64_t Dh,
+                                  const float* qk_scale_h, float p_scale, const float* out_col_scale,
+                                  int out_scale_is_scalar, hero_mask mask, const int32_t* kv_len,
+                                  void* out, hero_dtype out_dt, int64_t ldo, void* stream);
+
 /* ---- one transformer layer (Sec. 2.2.2 + 2.2.3 chained, Sec. 2.3 / Table 1 modes) ---- */
 
 typedef enum { HERO_ARCH_POST_LN = 0, HERO_ARCH_PRE_LN = 1 } hero_arch;

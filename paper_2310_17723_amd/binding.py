@@ -54,6 +54,8 @@ SYMBOLS = {
                                 vp, C.c_size_t, vp]),
     "hero_int8_attn": (i32, [vp, C.POINTER(i64), vp, C.POINTER(i64), vp, C.POINTER(i64), i64, i64, i64, i64, i64,
                              f32, f32, vp, i32, i32, vp, vp, i32, i64, vp]),
+    "hero_int8_attn_online": (i32, [vp, C.POINTER(i64), vp, C.POINTER(i64), vp, C.POINTER(i64), i64, i64, i64, i64, i64,
+                                    vp, f32, vp, i32, i32, vp, vp, i32, i64, vp]),
     "hero_layer_workspace_bytes": (C.c_size_t, [C.POINTER(LayerDesc), i64, i64]),
     "hero_layer_fwd": (i32, [C.POINTER(LayerDesc), C.POINTER(LayerWeights), C.POINTER(LayerIO), vp, C.c_size_t, vp]),
     "hero_bf16_gemm": (i32, [vp, i64, vp, i64, vp, vp, i64, i32, vp, i64, i64, i64, i64, vp]),
@@ -214,6 +216,21 @@ class Hero:
                                      B, H, Sq, Skv, Dh, float(qk_scale), float(p_scale), _ptr(out_col_scale),
                                      int(bool(out_scale_is_scalar)), int(mask), _ptr(kv_len), _ptr(out),
                                      _DT[out.dtype], out.stride(0), _stream(stream))
+        self._check(st)
+        return out
+
+    def hero_int8_attn_online(self, q, k, v, qk_scale_h, p_scale, out_col_scale, out_scale_is_scalar=False,
+                              mask=MASK_NONE, kv_len=None, out_dtype=torch.int8, out=None, stream=None):
+        """The single-sweep variant (online Softmax^quant); qk_scale_h: f32[H] device tensor, one d~ per head."""
+        B, Sq, H, Dh = q.shape
+        Skv = k.shape[1]
+        assert qk_scale_h is None or (qk_scale_h.dtype == torch.float32 and qk_scale_h.numel() == H)
+        if out is None:
+            out = torch.empty((B * Sq, H * Dh), dtype=out_dtype, device=q.device)
+        st = self.lib.hero_int8_attn_online(_ptr(q), _strides4(q), _ptr(k), _strides4(k), _ptr(v), _strides4(v),
+                                            B, H, Sq, Skv, Dh, _ptr(qk_scale_h), float(p_scale), _ptr(out_col_scale),
+                                            int(bool(out_scale_is_scalar)), int(mask), _ptr(kv_len), _ptr(out),
+                                            _DT[out.dtype], out.stride(0), _stream(stream))
         self._check(st)
         return out
 

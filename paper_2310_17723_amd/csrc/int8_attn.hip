@@ -35,13 +35,14 @@ struct AttnArgs {
     int64_t qs[4], ks[4], vs[4];
     int B, H, Sq, Skv;
     float qk_scale, p_scale;
+    const float* qk_scale_h;          // per-head d~ (online variant) or NULL
     const float* out_col_scale; int scale_is_scalar;
     int mask; const int32_t* kv_len;
     void* out; int64_t ldo;
 };
 
-template <int DH, int ODT>
-__global__ __launch_bounds__(256, DH == 64 ? 4 : 3) void int8_attn_kernel(AttnArgs a) {
+template <int DH, int ODT, bool ONLINE = false>
+__global__ __launch_bounds__(256, ONLINE ? (DH == 64 ? 3 : 2) : (DH == 64 ? 4 : 3)) void int8_attn_kernel(AttnArgs a) {
     constexpr int KLD = DH + 16;        // sK row stride (bytes)
     constexpr int VLD = BKV + 16;       // sVt row stride (bytes)
     constexpr int DS = DH / 32;         // 32-wide steps over the head dimension
@@ -153,12 +154,127 @@ __global__ __launch_bounds__(256, DH == 64 ? 4 : 3) void int8_attn_kernel(AttnAr
     // keys are replaced by a very negative integer (only in tiles that contain one), and in pass 2
     // the normaliser and 1/S_p are folded into the exponent, so a code costs one int->float
     // conversion, one fma, one exp2 and one saturating round-to-u8.
-    const float c2 = a.qk_scale * 1.44269504088896340736f;
+    const float c2 = (a.qk_scale_h ? a.qk_scale_h[h] : a.qk_scale) * 1.44269504088896340736f;
     constexpr int MASKED = -0x40000000;
     // first tile in which some key is hidden from some query of this wave (wave-uniform)
     int nvis_min = nvis;
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) nvis_min = min(nvis_min, __shfl_xor(nvis_min, o));
+
+    // ---- the online variant: ONE sweep.  The codes of a 64-key tile are taken against the running row
+    // maximum m (so the largest weight seen so far has code 255) and stay un-normalised; the integer sums
+    // of a run of tiles with an unchanged maximum are kept in int32 (oi, li); only when some query of the
+    // wave raises its maximum are they folded into the fp32 accumulators (of, lf) and everything gathered
+    // so far is rescaled by 2^(m_old - m_new); the division by the sum of the weights happens once, at the end.  The matrix cores take
+    // signed bytes: the fragment holds 127 - code (one XOR) and a second MFMA against the constant -127
+    // removes the offset, so oi = -sum_k code_k v_k exactly, with no column sums and no extra vector work.
+    if constexpr (ONLINE) {
+        constexpr float L255 = 7.99435343685885793770f;           // log2(255)
+        v16i oi[DS];
+        v16f of[DS];
+        uint32_t li = 0;
+        float lf = 0.0f, m2 = -INFINITY;
+#pragma unroll
+        for (int c = 0; c < DS; ++c)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) { oi[c][r] = 0; of[c][r] = 0.0f; }
+        const v4i cm127 = {(int)0x81818181u, (int)0x81818181u, (int)0x81818181u, (int)0x81818181u};
+        if (ntiles > 0) { load_k(0); load_v(0); store_k(0); store_v(0); }
+        __syncthreads();
+        for (int tile = 0; tile < ntiles; ++tile) {
+            const int buf = tile & 1;
+            if (tile + 1 < ntiles) { load_k(tile + 1); load_v(tile + 1); }
+            const bool edge = (tile + 1) * BKV > nvis_min;
+            auto online_tile = [&](auto EDGE) {
+                // the tile's maximum first; the scores are computed again for the codes (a second QK^T on
+                // the idle matrix cores costs less than keeping 32 more registers alive)
+                int imax = MASKED;
+                auto tile_scores = [&](int s) {
+                    v16i acc = scores(buf, s);
+                    if constexpr (decltype(EDGE)::value) {
+                        const int lim = nvis - (tile * BKV + s * 32 + hh * 4);  // key visible iff 8g + t < lim
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) acc[r] = ((r >> 2) * 8 + (r & 3)) < lim ? acc[r] : MASKED;
+                    }
+                    return acc;
+                };
+#pragma unroll
+                for (int s = 0; s < BKV / 32; ++s) {
+                    const v16i acc = tile_scores(s);
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) imax = max(imax, acc[r]);
+                }
+                imax = max(imax, __shfl_xor(imax, 32));
+                const float mn = imax > MASKED ? fmaxf(m2, (float)imax * c2) : m2;
+                if (__builtin_amdgcn_ballot_w64(mn != m2) != 0) {                // wave-uniform
+                    const float alpha = mn == m2 ? 1.0f : __builtin_amdgcn_exp2f(m2 - mn);
+#pragma unroll
+                    for (int c = 0; c < DS; ++c)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) { of[c][r] = (of[c][r] + (float)oi[c][r]) * alpha; oi[c][r] = 0; }
+                    lf = (lf + (float)li) * alpha;
+                    li = 0;
+                    m2 = mn;
+                }
+                {
+                    const float off = L255 - m2;
+#pragma unroll
+                    for (int s = 0; s < BKV / 32; ++s) {
+                        const v16i acc = scores(buf, s);
+                        const int lim = nvis - (tile * BKV + s * 32 + hh * 4);
+                        v4i pf;
+#pragma unroll
+                        for (int g = 0; g < 4; ++g) {
+                            uint32_t w = 0;
+#pragma unroll
+                            for (int t = 0; t < 4; ++t) {
+                                float e = __builtin_amdgcn_exp2f(fmaf((float)acc[4 * g + t], c2, off));
+                                if constexpr (decltype(EDGE)::value) e = (g * 8 + t) < lim ? e : 0.0f;
+                                w = __builtin_amdgcn_cvt_pk_u8_f32(e, t, w);
+                            }
+                            li = __builtin_amdgcn_sad_u8(w, 0u, li);             // + the four codes
+                            pf[g] = (int)(w ^ 0x7f7f7f7fu);                      // 127 - code as signed bytes
+                        }
+#pragma unroll
+                        for (int c = 0; c < DS; ++c) {
+                            v4i vf = *reinterpret_cast<const v4i*>(&sVt[buf][(c * 32 + ql) * VLD + s * 32 + hh * 16]);
+                            oi[c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(vf, pf, oi[c], 0, 0, 0);
+                            oi[c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(vf, cm127, oi[c], 0, 0, 0);
+                        }
+                    }
+                }
+            };
+            if (edge) online_tile(std::true_type{}); else online_tile(std::false_type{});
+            if (tile + 1 < ntiles) { store_k(buf ^ 1); store_v(buf ^ 1); }
+            __syncthreads();
+        }
+        if (qi >= a.Sq) return;
+        float l = lf + (float)li;
+        l += __shfl_xor(l, 32);
+        // oi / of hold MINUS the weighted sums; y = O / L * c[j] / S_p
+        const float inv = l > 0.0f ? __fdiv_rn(-1.0f, l * a.p_scale) : 0.0f;
+        const int64_t orow = ((int64_t)b * a.Sq + qi) * a.ldo + (int64_t)h * DH;
+#pragma unroll
+        for (int c = 0; c < DS; ++c)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int e0 = c * 32 + g * 8 + hh * 4;
+                float y[4];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const float sc = a.scale_is_scalar ? a.out_col_scale[0] : a.out_col_scale[h * DH + e0 + t];
+                    y[t] = (of[c][4 * g + t] + (float)oi[c][4 * g + t]) * inv * sc;
+                }
+                if (ODT == HERO_I8) {
+                    *reinterpret_cast<uint32_t*>((int8_t*)a.out + orow + e0) = quant4_sat(y[0], y[1], y[2], y[3]);
+                } else {
+                    uint32_t h0 = f32_to_hp<ODT>(y[0]), h1 = f32_to_hp<ODT>(y[1]), h2 = f32_to_hp<ODT>(y[2]), h3 = f32_to_hp<ODT>(y[3]);
+                    v2i w = {(int)(h0 | (h1 << 16)), (int)(h2 | (h3 << 16))};
+                    *reinterpret_cast<v2i*>((uint16_t*)a.out + orow + e0) = w;
+                }
+            }
+        return;
+    }
 
     // ---- pass 1: row max and row sum ------------------------------------------------------------
     float m2 = -INFINITY, l = 0.0f;           // running max (log2 domain) and sum of 2^(a2 - m2), this lane's keys
@@ -374,27 +490,27 @@ __global__ void zero_rows_kernel(int8_t* out, int64_t bytes) {
     if (i < bytes) *reinterpret_cast<v4i*>(out + i) = v4i{0, 0, 0, 0};
 }
 
-template <int DH>
+template <int DH, bool ONLINE = false>
 hero_status launch(const AttnArgs& a, hero_dtype out_dt, hipStream_t st) {
     constexpr int HG = DH >= 128 ? 1 : 128 / DH;               // heads per workgroup group (see the kernel)
     const int64_t nqb = (a.Sq + BQ - 1) / BQ, hgroups = ((int64_t)a.B * a.H + HG - 1) / HG, rounds = (hgroups + 7) / 8;
     if (rounds * 8 * HG * nqb > 0x7fffffffLL) return HERO_ERR_SHAPE;
     dim3 grid((unsigned)(rounds * 8 * HG * nqb)), block(256);
-    if (out_dt == HERO_I8) hipLaunchKernelGGL((int8_attn_kernel<DH, HERO_I8>), grid, block, 0, st, a);
-    else if (out_dt == HERO_BF16) hipLaunchKernelGGL((int8_attn_kernel<DH, HERO_BF16>), grid, block, 0, st, a);
-    else hipLaunchKernelGGL((int8_attn_kernel<DH, HERO_F16>), grid, block, 0, st, a);
+    if (out_dt == HERO_I8) hipLaunchKernelGGL((int8_attn_kernel<DH, HERO_I8, ONLINE>), grid, block, 0, st, a);
+    else if (out_dt == HERO_BF16) hipLaunchKernelGGL((int8_attn_kernel<DH, HERO_BF16, ONLINE>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((int8_attn_kernel<DH, HERO_F16, ONLINE>), grid, block, 0, st, a);
     return hero_launch_status();
 }
 
-}  // namespace
-
-extern "C" hero_status hero_int8_attn(const int8_t* q, const int64_t q_strides[4],
-                                      const int8_t* k, const int64_t k_strides[4],
-                                      const int8_t* v, const int64_t v_strides[4],
-                                      int64_t B, int64_t H, int64_t Sq, int64_t Skv, int64_t Dh,
-                                      float qk_scale, float p_scale, const float* out_col_scale, int out_scale_is_scalar,
-                                      hero_mask mask, const int32_t* kv_len,
-                                      void* out, hero_dtype out_dt, int64_t ldo, void* stream) {
+// argument checks and dispatch shared by the two entry points (online: the single-sweep variant)
+hero_status attn_entry(const int8_t* q, const int64_t q_strides[4],
+                       const int8_t* k, const int64_t k_strides[4],
+                       const int8_t* v, const int64_t v_strides[4],
+                       int64_t B, int64_t H, int64_t Sq, int64_t Skv, int64_t Dh,
+                       float qk_scale, const float* qk_scale_h, bool online,
+                       float p_scale, const float* out_col_scale, int out_scale_is_scalar,
+                       hero_mask mask, const int32_t* kv_len,
+                       void* out, hero_dtype out_dt, int64_t ldo, void* stream) {
     if (B < 0 || H < 0 || Sq < 0 || Skv < 0) return HERO_ERR_SHAPE;
     if (Dh != 64 && Dh != 128) return HERO_ERR_UNSUPPORTED;
     if (out_dt != HERO_I8 && out_dt != HERO_BF16 && out_dt != HERO_F16) return HERO_ERR_UNSUPPORTED;
@@ -403,6 +519,7 @@ extern "C" hero_status hero_int8_attn(const int8_t* q, const int64_t q_strides[4
     if (!out || !out_col_scale || !q_strides || !k_strides || !v_strides) return HERO_ERR_NULL;
     if (Skv > 0 && (!q || !k || !v)) return HERO_ERR_NULL;
     if (mask == HERO_MASK_PADDING && !kv_len) return HERO_ERR_NULL;
+    if (online && !qk_scale_h) return HERO_ERR_NULL;
     if (out_dt != HERO_I8 && !out_scale_is_scalar) return HERO_ERR_UNSUPPORTED;
     if (!(p_scale > 0.0f)) return HERO_ERR_SHAPE;
     if (ldo < H * Dh) return HERO_ERR_SHAPE;
@@ -419,7 +536,7 @@ extern "C" hero_status hero_int8_attn(const int8_t* q, const int64_t q_strides[4
     a.q = q; a.k = k; a.v = v;
     for (int t = 0; t < 4; ++t) { a.qs[t] = q_strides[t]; a.ks[t] = k_strides[t]; a.vs[t] = v_strides[t]; }
     a.B = (int)B; a.H = (int)H; a.Sq = (int)Sq; a.Skv = (int)Skv;
-    a.qk_scale = qk_scale; a.p_scale = p_scale; a.out_col_scale = out_col_scale; a.scale_is_scalar = out_scale_is_scalar;
+    a.qk_scale = qk_scale; a.qk_scale_h = qk_scale_h; a.p_scale = p_scale; a.out_col_scale = out_col_scale; a.scale_is_scalar = out_scale_is_scalar;
     a.mask = (int)mask; a.kv_len = kv_len; a.out = out; a.ldo = ldo;
     hipStream_t st = (hipStream_t)stream;
     if (Skv == 0) {     // no keys at all: every query outputs 0
@@ -429,6 +546,7 @@ extern "C" hero_status hero_int8_attn(const int8_t* q, const int64_t q_strides[4
         hipLaunchKernelGGL(zero_rows_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (int8_t*)out, bytes);
         return hero_launch_status();
     }
+    if (online) return Dh == 64 ? launch<64, true>(a, out_dt, st) : launch<128, true>(a, out_dt, st);
     if (Sq == 1 && Skv <= DEC_MAX_KEYS) {          // decode: the cache-streaming kernel
         dim3 grid((unsigned)H, (unsigned)B), block(256);
         const size_t lds = (size_t)Skv * sizeof(int);
@@ -442,4 +560,28 @@ extern "C" hero_status hero_int8_attn(const int8_t* q, const int64_t q_strides[4
         return hero_launch_status();
     }
     return Dh == 64 ? launch<64>(a, out_dt, st) : launch<128>(a, out_dt, st);
+}
+
+}  // namespace
+
+extern "C" hero_status hero_int8_attn(const int8_t* q, const int64_t q_strides[4],
+                                      const int8_t* k, const int64_t k_strides[4],
+                                      const int8_t* v, const int64_t v_strides[4],
+                                      int64_t B, int64_t H, int64_t Sq, int64_t Skv, int64_t Dh,
+                                      float qk_scale, float p_scale, const float* out_col_scale, int out_scale_is_scalar,
+                                      hero_mask mask, const int32_t* kv_len,
+                                      void* out, hero_dtype out_dt, int64_t ldo, void* stream) {
+    return attn_entry(q, q_strides, k, k_strides, v, v_strides, B, H, Sq, Skv, Dh, qk_scale, nullptr, false, p_scale,
+                      out_col_scale, out_scale_is_scalar, mask, kv_len, out, out_dt, ldo, stream);
+}
+
+extern "C" hero_status hero_int8_attn_online(const int8_t* q, const int64_t q_strides[4],
+                                             const int8_t* k, const int64_t k_strides[4],
+                                             const int8_t* v, const int64_t v_strides[4],
+                                             int64_t B, int64_t H, int64_t Sq, int64_t Skv, int64_t Dh,
+                                             const float* qk_scale_h, float p_scale, const float* out_col_scale,
+                                             int out_scale_is_scalar, hero_mask mask, const int32_t* kv_len,
+                                             void* out, hero_dtype out_dt, int64_t ldo, void* stream) {
+    return attn_entry(q, q_strides, k, k_strides, v, v_strides, B, H, Sq, Skv, Dh, 0.0f, qk_scale_h, true, p_scale,
+                      out_col_scale, out_scale_is_scalar, mask, kv_len, out, out_dt, ldo, stream);
 }

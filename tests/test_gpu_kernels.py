@@ -374,6 +374,51 @@ def test_int8_attn_matches_oracle(hero, B, Sq, Skv, H, Dh, mask):
     assert rel_err(O.bf16_to_f32(to_np(gotb)), O.bf16_to_f32(refb)) <= 2e-2
 
 
+@pytest.mark.parametrize("mask", [O.MASK_NONE, O.MASK_PADDING, O.MASK_CAUSAL])
+@pytest.mark.parametrize("B,Sq,Skv,H,Dh", ATTN_SHAPES + [(2, 1, 150, 2, 64)])
+def test_int8_attn_online_matches_oracle(hero, B, Sq, Skv, H, Dh, mask):
+    """The single-sweep variant (codes against the running 64-key-block maximum, normalised at the end) against
+    its own oracle; per-head score scales; the output classes of the two-pass operator."""
+    q, k, v, qk_scale, cs = _attn_case(1400 + Sq + Dh, B, Sq, Skv, H, Dh)
+    dts = (np.float32(qk_scale) * np.linspace(0.7, 1.6, H)).astype(np.float32)
+    kv_len = None
+    if mask == O.MASK_PADDING:
+        kv_len = np.int32([Skv - 3, 0][:B]) if B == 2 else np.int32([Skv // 2 + 1])
+    if mask == O.MASK_CAUSAL and Sq != Skv:
+        kv_len = np.int32([Skv, Skv - 50][:B])
+    sp = float(OL.S_P)
+    ref = O.int8_attn_online(q, k, v, qk_scale_h=dts, p_scale=sp, out_col_scale=cs, mask=mask, kv_len=kv_len, kv_block=64)
+    got = hero.hero_int8_attn_online(dev(q), dev(k), dev(v), dev(dts), sp, dev(cs), mask=mask, kv_len=dev(kv_len))
+    assert np.abs(ref).max() > 40
+    assert_codes(to_np(got), ref, "X_attn online", max_frac=3e-3 if ref.size < 2000 else 1e-3)
+    sc = np.float32([cs[0]])
+    refb = O.int8_attn_online(q, k, v, qk_scale_h=dts, p_scale=sp, out_col_scale=sc, out_scale_is_scalar=True,
+                              mask=mask, kv_len=kv_len, out_dt=O.BF16, kv_block=64)
+    gotb = hero.hero_int8_attn_online(dev(q), dev(k), dev(v), dev(dts), sp, dev(sc), out_scale_is_scalar=True,
+                                      mask=mask, kv_len=dev(kv_len), out_dtype=torch.bfloat16)
+    assert rel_err(O.bf16_to_f32(to_np(gotb)), O.bf16_to_f32(refb)) <= 2e-2
+
+
+def test_int8_attn_online_views_errors_and_long_rows(hero):
+    """Fused-buffer views, a long causal row set (many flushes and many tiles without one), no keys, bad arguments."""
+    B, S, H, Dh = 2, 1100, 2, 64
+    d = H * Dh
+    g = synth.rng(1450)
+    qkv = np.clip(np.rint(g.standard_normal((B * S, 3 * d)) * 30), -127, 127).astype(np.int8)
+    _, _, _, qk_scale, cs = _attn_case(1451, 1, 1, 1, H, Dh)
+    dts = np.float32([qk_scale, 2 * qk_scale])
+    qv, kv, vv = (OL._heads(qkv, B, S, H, Dh, i) for i in range(3))
+    sp = float(OL.S_P)
+    ref = O.int8_attn_online(qv, kv, vv, qk_scale_h=dts, p_scale=sp, out_col_scale=cs, mask=O.MASK_CAUSAL)
+    dq = dev(qkv).view(B, S, 3, H, Dh)
+    got = hero.hero_int8_attn_online(dq[:, :, 0], dq[:, :, 1], dq[:, :, 2], dev(dts), sp, dev(cs), mask=HB.MASK_CAUSAL)
+    assert_codes(to_np(got), ref, "online, fused-buffer views, causal 1100")
+    z = hero.hero_int8_attn_online(dq[:, :4, 0], dq[:, :0, 1], dq[:, :0, 2], dev(dts), sp, dev(cs))
+    assert not to_np(z).any()
+    with pytest.raises(HB.HeroError):
+        hero.hero_int8_attn_online(dq[:, :, 0], dq[:, :, 1], dq[:, :, 2], None, sp, dev(cs))
+
+
 def test_int8_attn_strided_views_cache_and_decode(hero):
     """Operands as views into a fused [T,3d] buffer and a [B,H,Smax,Dh] cache; one-query decode."""
     B, S, H, Dh = 3, 70, 2, 64
