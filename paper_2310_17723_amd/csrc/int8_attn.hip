@@ -36,6 +36,7 @@ struct AttnArgs {
     int B, H, Sq, Skv;
     float qk_scale, p_scale;
     const float* qk_scale_h;          // per-head d~ (online variant) or NULL
+    int use_buf;                      // K / V of one (batch, head) span < 2 GB with non-negative strides
     const float* out_col_scale; int scale_is_scalar;
     int mask; const int32_t* kv_len;
     void* out; int64_t ldo;
@@ -61,7 +62,9 @@ __global__ __launch_bounds__(256, ONLINE ? (DH == 64 ? 3 : 2) : (DH == 64 ? 4 : 
     const int slot = blockIdx.x / 8, grp = (slot / (HG * nqb)) * 8 + (blockIdx.x % 8), within = slot % (HG * nqb);
     const int bh = grp * HG + within / nqb;
     if (bh >= a.B * a.H) return;
-    const int b = bh / a.H, h = bh % a.H, q0 = (within % nqb) * BQ;
+    // causal: the last query block sees the most keys, so it is started first (longest job first)
+    const int qb = a.mask == HERO_MASK_CAUSAL ? nqb - 1 - within % nqb : within % nqb;
+    const int b = bh / a.H, h = bh % a.H, q0 = qb * BQ;
     const int len = a.kv_len ? min(max(a.kv_len[b], 0), a.Skv) : a.Skv;
     const int shift = len - a.Sq;                       // causal: key k visible iff k <= i + shift
     const int qi = q0 + wave * 32 + ql;                 // this lane's query
@@ -79,6 +82,11 @@ __global__ __launch_bounds__(256, ONLINE ? (DH == 64 ? 3 : 2) : (DH == 64 ? 4 : 
         const int8_t* qp = a.q + (int64_t)b * a.qs[0] + (int64_t)min(qi, a.Sq - 1) * a.qs[1] + (int64_t)h * a.qs[2];
 #pragma unroll
         for (int d = 0; d < DS; ++d) qf[d] = *reinterpret_cast<const v4i*>(qp + d * 32 + hh * 16);
+        // The fragments pass through an empty asm statement so that they count as arrived from here on:
+        // otherwise the first MFMA of every tile waits for ALL outstanding global loads (vmcnt(0)),
+        // the just-issued prefetch of the next tile included.
+#pragma unroll
+        for (int d = 0; d < DS; ++d) asm volatile("" : "+v"(qf[d]));
     }
     const int8_t* kbase = a.k + (int64_t)b * a.ks[0] + (int64_t)h * a.ks[2];
     const int8_t* vbase = a.v + (int64_t)b * a.vs[0] + (int64_t)h * a.vs[2];
@@ -90,7 +98,34 @@ __global__ __launch_bounds__(256, ONLINE ? (DH == 64 ? 3 : 2) : (DH == 64 ? 4 : 
     constexpr int VUNITS = (BKV / 4) * (DH / 4) / 256;     // V: units of 4 keys x 4 channels (one dword per key)
     v4i rk[UNITS];
     int rv[VUNITS][4];
+    // K / V tiles that lie wholly inside the key range are fetched through buffer descriptors when the
+    // host found that a (batch, head) operand spans less than 2 GB: the address is a wave-uniform base
+    // plus a 32-bit lane offset (one add per load and tile instead of a 64-bit multiply per load).  A
+    // ragged last tile, and operands beyond 2 GB, take clamped 64-bit addresses.
+    __amdgpu_buffer_rsrc_t krs, vrs;
+    uint32_t koff[UNITS], voff[VUNITS];
+    if (a.use_buf) {
+        krs = __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t*>(kbase), 0, (int)((int64_t)(a.Skv - 1) * a.ks[1] + DH), 0x00020000);
+        vrs = __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t*>(vbase), 0, (int)((int64_t)(a.Skv - 1) * a.vs[1] + DH), 0x00020000);
+#pragma unroll
+        for (int u = 0; u < UNITS; ++u) {
+            const int idx = tid + u * 256, row = idx / (DH / 16), ch = idx % (DH / 16);
+            koff[u] = (uint32_t)row * (uint32_t)a.ks[1] + ch * 16;
+        }
+#pragma unroll
+        for (int u = 0; u < VUNITS; ++u) {
+            const int idx = tid + u * 256, kg = (idx >> 2) % (BKV / 4), cg = (idx & 3) + 4 * (idx / BKV);
+            voff[u] = (uint32_t)(kg * 4) * (uint32_t)a.vs[1] + cg * 4;
+        }
+    }
     auto load_k = [&](int tile) {
+        if (a.use_buf && (tile + 1) * BKV <= a.Skv) {
+            const uint32_t tb = (uint32_t)tile * (uint32_t)(BKV * (uint32_t)a.ks[1]);
+#pragma unroll
+            for (int u = 0; u < UNITS; ++u)
+                rk[u] = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(krs, koff[u] + tb, 0, 0));
+            return;
+        }
 #pragma unroll
         for (int u = 0; u < UNITS; ++u) {
             int idx = tid + u * 256, row = idx / (DH / 16), ch = idx % (DH / 16);
@@ -102,6 +137,15 @@ __global__ __launch_bounds__(256, ONLINE ? (DH == 64 ? 3 : 2) : (DH == 64 ? 4 : 
     // read 16 contiguous bytes of one key row; the 64 transposed dword stores of a wave (rows 4cg + j,
     // 16 key-group positions each) fall into 64 different banks.
     auto load_v = [&](int tile) {
+        if (a.use_buf && (tile + 1) * BKV <= a.Skv) {
+            const uint32_t tb = (uint32_t)tile * (uint32_t)(BKV * (uint32_t)a.vs[1]);
+#pragma unroll
+            for (int u = 0; u < VUNITS; ++u)
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    rv[u][i] = (int)__builtin_amdgcn_raw_buffer_load_b32(vrs, voff[u] + tb + (uint32_t)i * (uint32_t)a.vs[1], 0, 0);
+            return;
+        }
 #pragma unroll
         for (int u = 0; u < VUNITS; ++u) {
             const int idx = tid + u * 256, kg = (idx >> 2) % (BKV / 4), cg = (idx & 3) + 4 * (idx / BKV);
@@ -538,6 +582,8 @@ hero_status attn_entry(const int8_t* q, const int64_t q_strides[4],
     a.B = (int)B; a.H = (int)H; a.Sq = (int)Sq; a.Skv = (int)Skv;
     a.qk_scale = qk_scale; a.qk_scale_h = qk_scale_h; a.p_scale = p_scale; a.out_col_scale = out_col_scale; a.scale_is_scalar = out_scale_is_scalar;
     a.mask = (int)mask; a.kv_len = kv_len; a.out = out; a.ldo = ldo;
+    a.use_buf = Skv > 0 && k_strides[1] >= 0 && v_strides[1] >= 0 &&
+                (Skv + BKV) * k_strides[1] + Dh < (1LL << 31) && (Skv + BKV) * v_strides[1] + Dh < (1LL << 31);
     hipStream_t st = (hipStream_t)stream;
     if (Skv == 0) {     // no keys at all: every query outputs 0
         const int64_t bytes = B * Sq * ldo * o_elem;                 // a multiple of 16 (ldo rule)
