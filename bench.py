@@ -212,6 +212,34 @@ def fp8_gemm_leg(hero, shape, seed, iters=20):
     return rows
 
 
+def attn_variants(hero, shape, seed, iters=20):
+    """The attention kernel alone at the workload's shape: the two-pass Softmax^quant of Sec. 2.2.2 (what the
+    layer runs) beside the single-sweep online variant (a different quantization of the probabilities)."""
+    import torch
+    from paper_2310_17723_amd import binding as HB
+    g = torch.Generator(device="cuda").manual_seed(seed)
+    B, S, H, Dh = shape.B, shape.S, shape.H, shape.Dh
+    d = H * Dh
+    qkv = torch.clamp(torch.round(torch.randn((B * S, 3 * d), device="cuda", generator=g) * 30), -127, 127).to(torch.int8)
+    v = qkv.view(B, S, 3, H, Dh)
+    cs = torch.full((d,), 0.005, device="cuda")
+    kvl = None
+    if shape.mask == 1:
+        kvl = torch.randint(shape.kv_lo or S // 2, (shape.kv_hi or S) + 1, (B,), dtype=torch.int32, device="cuda", generator=g)
+    out = torch.empty((B * S, d), dtype=torch.int8, device="cuda")
+    dt = 4.0 / (30 * 30 * Dh)                                   # logits of a few units
+    dth = torch.full((H,), dt, device="cuda")
+    ops = 4.0 * B * H * S * S * Dh * (0.5 if shape.mask == 2 else 1.0)
+    res = {"shape_bshd": [B, S, H, Dh], "mask": ["none", "padding", "causal"][shape.mask], "useful_ops": ops}
+    ms = time_gpu(lambda: hero.hero_int8_attn(v[:, :, 0], v[:, :, 1], v[:, :, 2], dt, 1 / 255, cs, mask=shape.mask,
+                                              kv_len=kvl, out=out), iters)
+    res["two_pass_us"] = round(ms * 1e3, 2)
+    ms = time_gpu(lambda: hero.hero_int8_attn_online(v[:, :, 0], v[:, :, 1], v[:, :, 2], dth, 1 / 255, cs, mask=shape.mask,
+                                                     kv_len=kvl, out=out), iters)
+    res["online_us"] = round(ms * 1e3, 2)
+    return res
+
+
 def ln_bandwidth(hero, T, D, iters=40, nbuf=8):
     """Fused LN + per-token quant on rotating buffers (working set >> the 256 MB cache)."""
     import torch
@@ -399,6 +427,9 @@ def main():
         rec["ln_quant"] = ln_bandwidth(hero, max(st.T, 16384), shape.d)
         rec["ln_quant_large"] = ln_bandwidth(hero, 65536, shape.d, nbuf=4)
         rec["embed_ln_quant"] = embed_bandwidth(hero, 32, 512, shape.d)
+        if shape.S > 1:
+            log("[bench] attention alone: two-pass and online Softmax^quant")
+            rec["attention"] = attn_variants(hero, shape, args.seed)
         log("[bench] FP8 variant of the FC1 / FC2 GEMMs")
         rec["fp8_gemm"] = fp8_gemm_leg(hero, shape, args.seed)
         log("[bench] GEMM sweep")
