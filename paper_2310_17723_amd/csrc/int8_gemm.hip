@@ -625,7 +625,7 @@ __global__ __launch_bounds__(512, 2) void int8_gemm_persistent_kernel(GemmArgs g
     constexpr int A_BYTES = BM * BK, B_BYTES = BN * BK, STAGE = A_BYTES + B_BYTES;
     constexpr int A_UNITS = A_BYTES / 16 / NT, B_UNITS = B_BYTES / 16 / NT, NW = A_UNITS + B_UNITS;
     constexpr int NM = TM * TN, NFR = TM + TN;
-    static_assert(NS >= 3 && NW <= NM && NFR <= NM && NW <= NM - (TM - 1), "ring / interleave plan");
+    static_assert(NS == 4 && 2 * NW <= NM && NFR <= NM && NFR % 2 == 0 && NW <= NM - TM + 1, "ring / interleave plan");
     constexpr int RING = NS * STAGE;
     constexpr int SVF = 4 * BN;                                  // floats per vector set: column scale, bias, S_a, row scale
     static_assert(BM == BN, "the row-scale vector shares the column vectors' length");
@@ -655,8 +655,8 @@ __global__ __launch_bounds__(512, 2) void int8_gemm_persistent_kernel(GemmArgs g
     int iseq = seq, ikt = 0, ipar = 0;
     const int8_t* ia; const int8_t* ib;                          // wave-uniform: tile base + slab offset
     uint32_t oa[A_UNITS], ob[B_UNITS];
-    auto set_issue_tile = [&](int s, int par) {
-        int m0i, n0i;
+    int m0i = 0, n0i = 0;                                        // origin of the issue stream's tile
+    auto set_issue_tile = [&](int s) {
         tile_from_seq<BM, BN>(g, s, m0i, n0i);
         ia = g.A + (int64_t)m0i * g.lda;
         ib = g.Bt + (int64_t)n0i * g.ldb;
@@ -664,7 +664,12 @@ __global__ __launch_bounds__(512, 2) void int8_gemm_persistent_kernel(GemmArgs g
         for (int u = 0; u < A_UNITS; ++u) oa[u] = (uint32_t)min(lrow + u * (NWAVE * 16), g.M - 1 - m0i) * (uint32_t)g.lda + lc;
 #pragma unroll
         for (int u = 0; u < B_UNITS; ++u) ob[u] = (uint32_t)min(lrow + u * (NWAVE * 16), g.N - 1 - n0i) * (uint32_t)g.ldb + lc;
-        // epilogue vectors of that tile: wave w fetches 64 entries (chunk w % 4) of vectors w / 4 and 2 + w / 4
+    };
+    // The epilogue vectors of the issue stream's tile go out together with its FIRST pair, not when the stream
+    // moves on to the tile: their buffer (parity of the tile) is still being read by the epilogue of the tile
+    // two back until every wave has started the tile in between.
+    auto issue_tile_vectors = [&](int par) {
+        // wave w fetches 64 entries (chunk w % 4) of vectors w / 4 and 2 + w / 4
         const int wu = __builtin_amdgcn_readfirstlane(wave);
         const int ch = (wu & 3) * 64, which = wu >> 2;
         const uint32_t dst = svbase + par * SVF * 4 + ch * 4;
@@ -678,17 +683,26 @@ __global__ __launch_bounds__(512, 2) void int8_gemm_persistent_kernel(GemmArgs g
             if (has_rs) dma4s(cm, g.a_row_scale + m0i, dst + 3 * BN * 4);
         }
     };
-    auto issue = [&](int n, int stage) {                         // the n-th direct load of the issue stream's slab
-        if (n < A_UNITS) dma16s(oa[n], ia, wbase + stage * STAGE + n * NWAVE * 1024);
-        else dma16s(ob[n - A_UNITS], ib, wbase + stage * STAGE + A_BYTES + (n - A_UNITS) * NWAVE * 1024);
+    // The issue stream moves in PAIRS of slabs (128 bytes of every row = one cache line): the j-th direct load
+    // of a pair is unit j / 2 of slab j % 2, so the two 64-byte halves of a line are requested back to back and
+    // the second one is served by the line the first one brought in.  A CU pulls 48 B/clk from the L2 that way,
+    // against 30 B/clk when the halves are requested one slab apart (measured; a 256 x 256 tile needs 32).
+    auto issue_pair = [&](int j, int stage0) {                   // stage0: the (even) stage of the pair's first slab
+        if (j == 0 && ikt == 0) issue_tile_vectors(ipar);
+        const int u = j >> 1;
+        const uint32_t lds = wbase + (stage0 + (j & 1)) * STAGE;
+        // (the second slab through its own scalar base: an instruction offset would move the LDS side too)
+        if (u < A_UNITS) dma16s(oa[u], ia + (j & 1) * BK, lds + u * NWAVE * 1024);
+        else dma16s(ob[u - A_UNITS], ib + (j & 1) * BK, lds + A_BYTES + (u - A_UNITS) * NWAVE * 1024);
     };
-    auto advance = [&]() {                                       // next slab; past the last tile the last slab repeats (never read)
-        if (++ikt < KT) { ia += BK; ib += BK; return; }
+    auto advance = [&]() {                                       // next pair; past the last tile the last pair repeats (never read)
+        ikt += 2;
+        if (ikt < KT) { ia += 2 * BK; ib += 2 * BK; return; }
         if (iseq + nslot < seq_end) {
             iseq += nslot; ikt = 0; ipar ^= 1;
-            set_issue_tile(iseq, ipar);
+            set_issue_tile(iseq);
         } else {
-            ikt = KT - 1;
+            ikt = KT - 2;
         }
     };
 
@@ -703,15 +717,15 @@ __global__ __launch_bounds__(512, 2) void int8_gemm_persistent_kernel(GemmArgs g
         fo[1][t] = base + (((2 + hh) ^ ((rr >> 2) & 3)) << 4);
     }
 
-    // prologue: vectors of the first tile, slabs 0 .. NS-2 in flight, slab 0 landed
-    set_issue_tile(seq, 0);
+    // prologue: vectors of the first tile, both pairs of the ring in flight, slab 0 landed
+    set_issue_tile(seq);
 #pragma unroll
-    for (int s0 = 0; s0 < NS - 1; ++s0) {
+    for (int p0 = 0; p0 < 2; ++p0) {
 #pragma unroll
-        for (int n = 0; n < NW; ++n) issue(n, s0);
+        for (int j = 0; j < 2 * NW; ++j) issue_pair(j, 2 * p0);
         advance();
     }
-    __builtin_amdgcn_s_waitcnt(vmcnt_imm((NS - 2) * NW));
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * NW + 1));
     __syncthreads();
 
     int stage = 0, par = 0;
@@ -732,9 +746,14 @@ __global__ __launch_bounds__(512, 2) void int8_gemm_persistent_kernel(GemmArgs g
 #pragma unroll
             for (int t = 0; t < NFR; ++t) f1[t] = *reinterpret_cast<const v4i*>(smem + stage * STAGE + fo[1][t]);
 
-        // One slab per iteration with the barrier in the middle (see int8_gemm_dma_kernel); the slab issued
-        // in iteration kt is the one NS-1 ahead in the stream, which may already belong to the next tile.
-        for (int kt = 0; kt < KT; ++kt) {
+        // One slab per iteration with the barrier in the middle (see int8_gemm_dma_kernel).  KT is even and the
+        // ring holds two pairs: after the barrier of an ODD iteration i every wave has read the last fragment
+        // of the pair (i-1, i), whose two stages then take the pair (i+3, i+4) of the stream, which may
+        // already belong to the next tile.  In program order the loads of a pair alternate between its slabs,
+        // so "slab i+1 has landed" is vmcnt(1) in an odd iteration (only the last load of slab i+2 may be
+        // out) and vmcnt(2 NW) in an even one (the younger pair may be out).
+        auto iteration = [&](auto ODD) {
+            constexpr bool odd = decltype(ODD)::value;
             const int8_t* st = smem + stage * STAGE;
             const int nstage = stage + 1 == NS ? 0 : stage + 1;
             const int pstage = stage == 0 ? NS - 1 : stage - 1;
@@ -750,7 +769,7 @@ __global__ __launch_bounds__(512, 2) void int8_gemm_persistent_kernel(GemmArgs g
                     const int jj = n / TM, ii = n % TM;
                     acc[ii][jj] = mfma_wide_f8(f0[jj], f1[jj], f0[TN + ii], f1[TN + ii], acc[ii][jj]);
                     if (n == TM - 1) {
-                        __builtin_amdgcn_s_waitcnt(vmcnt_imm((NS - 3) * NW));
+                        __builtin_amdgcn_s_waitcnt(vmcnt_imm(odd ? 1 : 2 * NW));
                         __syncthreads();
                     }
                     if (n >= TM - 1) {
@@ -762,34 +781,45 @@ __global__ __launch_bounds__(512, 2) void int8_gemm_persistent_kernel(GemmArgs g
                                 f1[t] = *reinterpret_cast<const v4i*>(stn + fo[1][t]);
                             }
                         }
-                        if (n - (TM - 1) < NW) issue(n - (TM - 1), pstage);
+                        if (odd) {
+                            const int j = 2 * (n - (TM - 1));
+                            if (j < 2 * NW) { issue_pair(j, pstage); issue_pair(j + 1, pstage); }
+                        }
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
-                advance();
-                stage = nstage;
-                continue;
-            }
+            } else {
 #pragma unroll
-            for (int n = 0; n < NM; ++n) {                             // k-step 0
-                const int jj = n / TM, ii = n % TM;
-                acc[ii][jj] = mfma_step<ADT>(f0[jj], f0[TN + ii], acc[ii][jj]);
-                if (n < NFR) f1[n] = *reinterpret_cast<const v4i*>(st + fo[1][n]);
+                for (int n = 0; n < NM; ++n) {                         // k-step 0
+                    const int jj = n / TM, ii = n % TM;
+                    acc[ii][jj] = mfma_step<ADT>(f0[jj], f0[TN + ii], acc[ii][jj]);
+                    if (n < NFR / 2) {                                 // early: the reads must be back before the barrier
+                        f1[2 * n] = *reinterpret_cast<const v4i*>(st + fo[1][2 * n]);
+                        f1[2 * n + 1] = *reinterpret_cast<const v4i*>(st + fo[1][2 * n + 1]);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                __builtin_amdgcn_s_waitcnt(vmcnt_imm(odd ? 1 : 2 * NW));   // the next slab has landed (mine)
+                __syncthreads();                                       // ... and everybody's
                 __builtin_amdgcn_sched_barrier(0);
-            }
-            __builtin_amdgcn_s_waitcnt(vmcnt_imm((NS - 3) * NW));     // the next slab has landed (mine)
-            __syncthreads();                                           // ... and everybody's
-            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int n = 0; n < NM; ++n) {                             // k-step 1
-                const int jj = n / TM, ii = n % TM;
-                acc[ii][jj] = mfma_step<ADT>(f1[jj], f1[TN + ii], acc[ii][jj]);
-                if (n < NFR) f0[n] = *reinterpret_cast<const v4i*>(stn + fo[0][n]);
-                if (n < NW) issue(n, pstage);
-                __builtin_amdgcn_sched_barrier(0);
+                for (int n = 0; n < NM; ++n) {                         // k-step 1
+                    const int jj = n / TM, ii = n % TM;
+                    acc[ii][jj] = mfma_step<ADT>(f1[jj], f1[TN + ii], acc[ii][jj]);
+                    if (n < NFR / 2) {
+                        f0[2 * n] = *reinterpret_cast<const v4i*>(stn + fo[0][2 * n]);
+                        f0[2 * n + 1] = *reinterpret_cast<const v4i*>(stn + fo[0][2 * n + 1]);
+                    }
+                    if (odd && n < NW) { issue_pair(2 * n, pstage); issue_pair(2 * n + 1, pstage); }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
-            advance();
+            if (odd) advance();
             stage = nstage;
+        };
+        for (int kt = 0; kt < KT; kt += 2) {
+            iteration(std::false_type{});
+            iteration(std::true_type{});
         }
         // epilogue of this tile; the ring keeps filling with the next tile's slabs meanwhile
         const float* sv = sv0 + par * SVF;
@@ -935,7 +965,7 @@ hero_status launch_epi(const GemmArgs& g, void* ws, size_t ws_bytes, hipStream_t
     }
     // persistent form of the 256x256 kernel: K long enough that the slab ring never runs more than one tile
     // ahead, 32-bit per-lane offsets (256 rows of lda / ldb bytes)
-    if ((cfg == 7 || (cfg == 1 && !e)) && g.K >= 4 * BK && g.lda < (1 << 24) && g.ldb < (1 << 24)) {
+    if ((cfg == 7 || (cfg == 1 && !e)) && g.K >= 4 * BK && g.K % (2 * BK) == 0 && g.lda < (1 << 24) && g.ldb < (1 << 24)) {
         GemmArgs gp = g;
         gp.ntm = (g.M + 255) / 256; gp.ntn = (g.N + 255) / 256;
         const int64_t tiles = (int64_t)gp.ntm * gp.ntn;
@@ -966,7 +996,7 @@ hero_status hero_bf16_gemm_large(const void* A, int64_t lda, const void* Wt, int
                                  const float* bias, const void* residual, int64_t ldr, int gelu,
                                  void* C, int64_t ldc, int64_t M, int64_t N, int64_t K, hipStream_t st) {
     const int64_t tiles = ((M + 255) / 256) * ((N + 255) / 256);
-    if (tiles < 96 || tiles > 0x7fffff00LL || K % 32 != 0 || K * 2 < 4 * BK || lda * 2 >= (1 << 24) || ldb * 2 >= (1 << 24))
+    if (tiles < 96 || tiles > 0x7fffff00LL || K % 64 != 0 || K * 2 < 4 * BK || lda * 2 >= (1 << 24) || ldb * 2 >= (1 << 24))
         return HERO_ERR_UNSUPPORTED;
     GemmArgs g;
     g.A = (const int8_t*)A; g.lda = lda * 2; g.a_row_scale = nullptr; g.Bt = (const int8_t*)Wt; g.ldb = ldb * 2;
@@ -991,7 +1021,7 @@ hero_status hero_bf16_gemm_large(const void* A, int64_t lda, const void* Wt, int
 template <int EPI, int CDT, int RDT>
 hero_status launch_epi_fp8(GemmArgs g, hipStream_t st) {
     const int64_t t256 = (int64_t)((g.M + 255) / 256) * ((g.N + 255) / 256), t128 = (int64_t)((g.M + 127) / 128) * ((g.N + 127) / 128);
-    if (t256 >= 96 && t256 <= 0x7fffff00LL && g.K >= 4 * BK && g.lda < (1 << 24) && g.ldb < (1 << 24)) {
+    if (t256 >= 96 && t256 <= 0x7fffff00LL && g.K >= 4 * BK && g.K % (2 * BK) == 0 && g.lda < (1 << 24) && g.ldb < (1 << 24)) {
         g.ntm = (g.M + 255) / 256; g.ntn = (g.N + 255) / 256;
         g.per_xcd = (int)((t256 + NUM_XCD - 1) / NUM_XCD);
         const int nslot = g.per_xcd < 32 ? g.per_xcd : 32;
