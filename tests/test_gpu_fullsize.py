@@ -102,6 +102,58 @@ def test_int8_attn_full_size_sampled_heads(hero, cfg):
                 assert d1.max() <= 1 and np.count_nonzero(d1) <= 2, (b, h, i, d1.max(), np.count_nonzero(d1))
 
 
+def test_int8_attn_online_full_size_sampled_heads(hero):
+    """The online Softmax^quant variant at config 2's full size (the launch the bench times): sampled
+    (batch, head) pairs against its oracle, per-head score scales."""
+    shape = synth.CONFIGS[2]
+    B, S, H, Dh, d = shape.B, shape.S, shape.H, shape.Dh, shape.d
+    g = synth.rng(2200)
+    qkv = np.clip(np.rint(g.standard_normal((B * S, 3 * d), dtype=np.float32) * 30), -127, 127).astype(np.int8)
+    kv_len = synth.kv_lengths(2200, shape)
+    dts = (np.float32(6.0 / (900.0 * Dh)) * g.uniform(0.7, 1.5, H)).astype(np.float32)
+    cs = (g.uniform(0.8, 1.2, d) / (255 * 30) * 50).astype(np.float32)
+    dq = dev(qkv).view(B, S, 3, H, Dh)
+    got = to_np(hero.hero_int8_attn_online(dq[:, :, 0], dq[:, :, 1], dq[:, :, 2], dev(dts), float(OL.S_P), dev(cs),
+                                           mask=shape.mask, kv_len=dev(kv_len)))
+    q5 = qkv.reshape(B, S, 3, H, Dh)
+    for (b, h) in [(0, 0), (B - 1, H - 1), (int(g.integers(0, B)), int(g.integers(0, H)))]:
+        qb, kb, vb = (np.ascontiguousarray(q5[b:b + 1, :, i, h:h + 1]) for i in range(3))
+        ref = O.int8_attn_online(qb, kb, vb, qk_scale_h=dts[h:h + 1], p_scale=float(OL.S_P), out_col_scale=cs[h * Dh:(h + 1) * Dh],
+                                 mask=shape.mask, kv_len=kv_len[b:b + 1], kv_block=64)
+        valid = np.arange(S) < kv_len[b]
+        assert_codes(got[b * S:(b + 1) * S, h * Dh:(h + 1) * Dh][valid], ref[valid], f"online (b,h)=({b},{h})")
+
+
+def test_fp8_gemm_full_size_sampled_rows(hero):
+    """The FP8 GEMMs the bench times (FC1 + GELU^quant, FC2 requant at config 2's size): sampled output rows
+    against the oracle's exact-sum definition; the tolerance is the one derived for the FP8 matrix instructions
+    (equal codes on all but 0.5 %, a differing value within one E4M3 step + 1e-3 of the rms)."""
+    from parity import assert_fp8_codes
+    shape = synth.CONFIGS[2]
+    M, d, f = shape.B * shape.S, shape.d, shape.f
+    g = synth.rng(2300)
+    rows = np.unique(np.concatenate([g.integers(0, M, 40), [0, 255, 256, M - 1]]))
+    for (N, K, epi_o, epi_h) in ((f, d, O.EPI_GELU_REQUANT, HB.EPI_GELU_REQUANT), (d, f, O.EPI_REQUANT, HB.EPI_REQUANT)):
+        X = (g.standard_normal((M, K), dtype=np.float32) * g.uniform(0.5, 3, (M, 1)).astype(np.float32))
+        W = g.standard_normal((N, K), dtype=np.float32) * np.float32(0.03)
+        A, rs = O.quant_twq_fp8(X)
+        cs = (np.abs(W).max(axis=1) / 448).astype(np.float32)
+        Bt = O.f32_to_e4m3((W / cs[:, None]).astype(np.float32))
+        bias = (0.05 * g.standard_normal(N)).astype(np.float32)
+        if epi_o == O.EPI_GELU_REQUANT:
+            s_out = np.full(N, 0.02, np.float32)
+            cs_use = cs
+        else:
+            s_out = None
+            cs_use = (cs / np.float32(0.05)).astype(np.float32)
+            bias = (bias / np.float32(0.05)).astype(np.float32)
+        got = to_np(hero.hero_fp8_gemm(dev(A), dev(Bt), dev(rs), dev(cs_use), dev(bias), epi=epi_h, out_col_scale=dev(s_out),
+                                       out_dtype=torch.float8_e4m3fn))
+        ref = O.fp8_gemm(A[rows], Bt, a_row_scale=rs[rows], b_col_scale=cs_use, bias=bias, epi=epi_o, out_col_scale=s_out, c_dt=O.F8)
+        assert_fp8_codes(got[rows], ref, O.e4m3_to_f32, f"fp8 {N}x{K}", max_frac=5e-3, acc_rel=1e-3)
+        assert np.count_nonzero(ref & 0x7F) > ref.size // 2                       # the case is not degenerate
+
+
 def test_bert_large_layer_batch_slice(hero):
     """One layer of the benchmark's stack configuration (d 1024, 16 x 64, f 4096, padding mask),
     4 sequences x 512 tokens: large enough for the 256x256 direct-to-LDS GEMM path."""
