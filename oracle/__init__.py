@@ -261,8 +261,8 @@ def fp8_gemm(A, Bt, *, a_row_scale=None, b_col_scale=None, bias=None, residual=N
 
 
 # ------------------------------------------------------------------ O5
-def ln_quant(x, x_dt, x_row_scale, r, r_dt, r_col_scale, gamma, beta, eps, y_hp_dt=None):
-    """LN^quant: LayerNorm of the sum of the inputs, token-wise quantized output."""
+def ln_quant(x, x_dt, x_row_scale, r, r_dt, r_col_scale, gamma, beta, eps, y_hp_dt=None, fp8=False):
+    """LN^quant: LayerNorm of the sum of the inputs, token-wise quantized output (INT8, or E4M3 with fp8=True)."""
     x = np.ascontiguousarray(x, _NP_OF[x_dt])
     M, D = x.shape
     f32 = lambda a: None if a is None else np.ascontiguousarray(a, np.float32)
@@ -270,10 +270,11 @@ def ln_quant(x, x_dt, x_row_scale, r, r_dt, r_col_scale, gamma, beta, eps, y_hp_
     if r is not None:
         r = np.ascontiguousarray(r, _NP_OF[r_dt])
         assert r.shape == (M, D)
-    y_q = np.empty((M, D), np.int8)
+    y_q = np.empty((M, D), np.uint8 if fp8 else np.int8)
     y_s = np.empty((M,), np.float32)
     y_hp = None if y_hp_dt is None else np.empty((M, D), _NP_OF[y_hp_dt])
-    rc = lib().orc_ln_quant(_p(x), C.c_int(x_dt), _p(x_row_scale), _p(r), C.c_int(r_dt if r is not None else 0),
+    fn = lib().orc_ln_quant_fp8 if fp8 else lib().orc_ln_quant
+    rc = fn(_p(x), C.c_int(x_dt), _p(x_row_scale), _p(r), C.c_int(r_dt if r is not None else 0),
                             _p(r_col_scale), _p(gamma), _p(beta), C.c_float(eps), _i64(M), _i64(D),
                             _p(y_q), _p(y_s), _p(y_hp), C.c_int(y_hp_dt if y_hp_dt is not None else 0))
     if rc != 0:

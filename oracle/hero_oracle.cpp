@@ -29,7 +29,7 @@
 
 extern "C" {
 
-enum { ORC_I8 = 0, ORC_U8 = 1, ORC_I32 = 2, ORC_F16 = 3, ORC_BF16 = 4, ORC_F32 = 5 };
+enum { ORC_I8 = 0, ORC_U8 = 1, ORC_I32 = 2, ORC_F16 = 3, ORC_BF16 = 4, ORC_F32 = 5, ORC_F8 = 6 };
 enum { ORC_EPI_RAW_I32 = 0, ORC_EPI_DEQUANT = 1, ORC_EPI_DEQUANT_GELU = 2,
        ORC_EPI_REQUANT = 3, ORC_EPI_GELU_REQUANT = 4 };
 enum { ORC_MASK_NONE = 0, ORC_MASK_PADDING = 1, ORC_MASK_CAUSAL = 2 };
@@ -280,7 +280,6 @@ int orc_fp8_gemm(const uint8_t* A, int64_t lda, const float* a_row_scale,
                  const float* bias, const void* residual, int res_dt, int64_t ldr,
                  int epi, const float* out_col_scale,
                  void* C, int c_dt, int64_t ldc, int64_t M, int64_t N, int64_t K) {
-    const int ORC_F8 = 6;
     if (epi == ORC_EPI_RAW_I32) return -1;
     if ((epi == ORC_EPI_REQUANT || epi == ORC_EPI_GELU_REQUANT) && c_dt != ORC_F8) return -1;
     if ((epi == ORC_EPI_DEQUANT || epi == ORC_EPI_DEQUANT_GELU) &&
@@ -328,11 +327,14 @@ int orc_fp8_gemm(const uint8_t* A, int64_t lda, const float* a_row_scale,
 // Sum, mean, biased variance and the normalised value in fp64; the result is cast to
 // fp32 once and the TWQ primitive runs in fp32.
 // ---------------------------------------------------------------------------------
-int orc_ln_quant(const void* x, int x_dt, const float* x_row_scale,
-                 const void* r, int r_dt, const float* r_col_scale,
-                 const float* gamma, const float* beta, float eps,
-                 int64_t M, int64_t D,
-                 int8_t* y_q, float* y_scale, void* y_hp, int y_hp_dt) {
+// y_q_dt selects the 8-bit format of the output (Sec. 2.1: INT8 or FP8): ORC_I8 as above, ORC_F8 for
+// token-wise E4M3 codes with scale = max|y| / 448.
+static int ln_quant_impl(const void* x, int x_dt, const float* x_row_scale,
+                         const void* r, int r_dt, const float* r_col_scale,
+                         const float* gamma, const float* beta, float eps,
+                         int64_t M, int64_t D,
+                         void* y_q_, int y_q_dt, float* y_scale, void* y_hp, int y_hp_dt) {
+    int8_t* y_q = (int8_t*)y_q_;
     if (x_dt == ORC_I8 && !x_row_scale) return -1;
     if (r && r_dt == ORC_I8 && !r_col_scale) return -1;
 #pragma omp parallel for schedule(static)
@@ -363,6 +365,16 @@ int orc_ln_quant(const void* x, int x_dt, const float* x_row_scale,
         }
         float amax = 0.0f;
         for (int64_t j = 0; j < D; ++j) amax = std::max(amax, std::fabs(y32[j]));
+        if (y_q_dt == ORC_F8) {
+            volatile float scf = amax == 0.0f ? 1.0f : amax / 448.0f;
+            y_scale[i] = scf;
+            for (int64_t j = 0; j < D; ++j) {
+                volatile float t = y32[j] / scf;
+                ((uint8_t*)y_q_)[i * D + j] = orc_f32_to_e4m3(t);
+                if (y_hp) store_hp(y_hp, y_hp_dt, i * D + j, y32[j]);
+            }
+            continue;
+        }
         float sc = dyn_scale(amax);
         y_scale[i] = sc;
         for (int64_t j = 0; j < D; ++j) {
@@ -371,6 +383,23 @@ int orc_ln_quant(const void* x, int x_dt, const float* x_row_scale,
         }
     }
     return 0;
+}
+
+int orc_ln_quant(const void* x, int x_dt, const float* x_row_scale,
+                 const void* r, int r_dt, const float* r_col_scale,
+                 const float* gamma, const float* beta, float eps,
+                 int64_t M, int64_t D,
+                 int8_t* y_q, float* y_scale, void* y_hp, int y_hp_dt) {
+    return ln_quant_impl(x, x_dt, x_row_scale, r, r_dt, r_col_scale, gamma, beta, eps, M, D, y_q, ORC_I8, y_scale, y_hp, y_hp_dt);
+}
+
+// LN^quant with a token-wise FP8 (E4M3) output: the same y, scale = max|y| / 448, code = e4m3(y / scale).
+int orc_ln_quant_fp8(const void* x, int x_dt, const float* x_row_scale,
+                     const void* r, int r_dt, const float* r_col_scale,
+                     const float* gamma, const float* beta, float eps,
+                     int64_t M, int64_t D,
+                     uint8_t* y_q, float* y_scale, void* y_hp, int y_hp_dt) {
+    return ln_quant_impl(x, x_dt, x_row_scale, r, r_dt, r_col_scale, gamma, beta, eps, M, D, y_q, ORC_F8, y_scale, y_hp, y_hp_dt);
 }
 
 // ---------------------------------------------------------------------------------

@@ -349,6 +349,33 @@ def test_fp8_e4m3_format_quantizer_and_gemm():
 
 
 # ---------------------------------------------------------------- O5 LN^quant
+def test_ln_quant_fp8_output_against_torch_and_the_fp8_quantizer():
+    """LN^quant with a token-wise E4M3 output: without a LayerNorm it is the (pinned) FP8 token-wise quantizer;
+    with one, torch's fp64 layer_norm followed by torch's own float8_e4m3fn rounding of y / (max|y| / 448)."""
+    g = synth.rng(40)
+    M, D = 11, 96
+    X = (g.standard_normal((M, D)) * g.uniform(0.2, 5, (M, 1))).astype(np.float32)
+    q0, s0 = O.quant_twq_fp8(X)
+    q1, s1, _ = O.ln_quant(X, O.F32, None, None, 0, None, None, None, 0.0, fp8=True)
+    assert np.array_equal(q0, q1) and np.array_equal(s0, s1)
+    xq = g.integers(-127, 128, (M, D), dtype=np.int8)
+    rq = g.integers(-127, 128, (M, D), dtype=np.int8)
+    xs = g.uniform(0.005, 0.05, M).astype(np.float32)
+    rc = g.uniform(0.001, 0.02, D).astype(np.float32)
+    gam = (1 + 0.1 * g.standard_normal(D)).astype(np.float32)
+    bet = (0.02 * g.standard_normal(D)).astype(np.float32)
+    q, sc, hp = O.ln_quant(xq, O.I8, xs, rq, O.I8, rc, gam, bet, 1e-5, y_hp_dt=O.BF16, fp8=True)
+    ssum = torch.from_numpy(xq.astype(np.float64) * xs[:, None].astype(np.float64) + rq.astype(np.float64) * rc[None, :].astype(np.float64))
+    y = torch.nn.functional.layer_norm(ssum, (D,), torch.from_numpy(gam).double(), torch.from_numpy(bet).double(), 1e-5).float()
+    s_ref = (y.abs().amax(dim=1) / 448).numpy()
+    np.testing.assert_allclose(sc, s_ref, rtol=2e-7)
+    c_ref = (y / torch.from_numpy(sc)[:, None]).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    assert np.count_nonzero(q != c_ref) <= 2                      # a last-bit difference of y next to a rounding boundary
+    dq = O.e4m3_to_f32(q)
+    assert (np.abs(dq).max(axis=1) == 448).all()
+    assert np.array_equal(hp, torch.from_numpy(O.ln_quant(xq, O.I8, xs, rq, O.I8, rc, gam, bet, 1e-5, y_hp_dt=O.BF16)[2].astype(np.int16)).numpy().view(np.uint16))
+
+
 def test_ln_quant_closed_forms_and_torch():
     g = synth.rng(9)
     M, D = 12, 96
