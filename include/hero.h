@@ -78,6 +78,17 @@ hero_status hero_ln_quant(const void* x, hero_dtype x_dt, const float* x_row_sca
                           int64_t M, int64_t D,
                           int8_t* y_q, float* y_scale, void* y_hp, hero_dtype y_hp_dt, void* stream);
 
+/* LN^quant with a token-wise FP8 output (Sec. 2.1: the 8-bit format may be FP8): everything as for
+ * hero_ln_quant, except
+ *   y_scale[i] = max_j |y[i][j]| / 448 ;  y_q[i][j] = e4m3(y[i][j] / y_scale[i])
+ * (OCP E4M3 bytes, IEEE fp32 division, round to nearest even, saturated to +-448): the A operand and
+ * a_row_scale of hero_fp8_gemm. */
+hero_status hero_ln_quant_fp8(const void* x, hero_dtype x_dt, const float* x_row_scale,
+                              const void* r, hero_dtype r_dt, const float* r_col_scale,
+                              const float* gamma, const float* beta, float eps,
+                              int64_t M, int64_t D,
+                              void* y_q, float* y_scale, void* y_hp, hero_dtype y_hp_dt, void* stream);
+
 /* Embedding LN^quant.  Paper: Sec. 2.2.1,
  *   S_emb X_emb,int8 = LN^quant(S_xt X_t,int8, X_p, X_s)
  * the token embedding is stored as INT8 codes with one TWQ scale per table row, the (small) position

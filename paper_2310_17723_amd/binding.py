@@ -44,6 +44,7 @@ SYMBOLS = {
     "hero_strerror": (C.c_char_p, [i32]),
     "hero_build_arch": (C.c_char_p, []),
     "hero_ln_quant": (i32, [vp, i32, vp, vp, i32, vp, vp, vp, f32, i64, i64, vp, vp, vp, i32, vp]),
+    "hero_ln_quant_fp8": (i32, [vp, i32, vp, vp, i32, vp, vp, vp, f32, i64, i64, vp, vp, vp, i32, vp]),
     "hero_embed_ln_quant": (i32, [vp, vp, vp, vp, vp, i64, vp, i64, vp, i64, i32, vp, vp, f32, i64, i64, vp, vp, vp]),
     "hero_absmax_cols": (i32, [vp, i32, i64, i64, i64, vp, vp]),
     "hero_weight_fold_quant": (i32, [vp, i64, vp, vp, i64, i64, vp, i64, vp, vp]),
@@ -104,17 +105,18 @@ class Hero:
 
     # ------------------------------------------------------------------ LN^quant
     def hero_ln_quant(self, x, x_row_scale=None, r=None, r_col_scale=None, gamma=None, beta=None, eps=1e-5,
-                      y_hp_dtype=None, y_q=None, y_scale=None, y_hp=None, stream=None):
-        """Returns (y_q int8 [M,D], y_scale f32 [M], y_hp or None)."""
+                      y_hp_dtype=None, y_q=None, y_scale=None, y_hp=None, stream=None, fp8=False):
+        """Returns (y_q int8 [M,D] (float8_e4m3fn with fp8=True: hero_ln_quant_fp8), y_scale f32 [M], y_hp or None)."""
         M, D = x.shape
         dev = x.device
-        y_q = torch.empty((M, D), dtype=torch.int8, device=dev) if y_q is None else y_q
+        y_q = torch.empty((M, D), dtype=torch.float8_e4m3fn if fp8 else torch.int8, device=dev) if y_q is None else y_q
         y_scale = torch.empty((M,), dtype=torch.float32, device=dev) if y_scale is None else y_scale
         if y_hp is None and y_hp_dtype is not None:
             y_hp = torch.empty((M, D), dtype=y_hp_dtype, device=dev)
         for t in (x, r):
             assert t is None or t.is_contiguous()
-        st = self.lib.hero_ln_quant(_ptr(x), _DT[x.dtype], _ptr(x_row_scale), _ptr(r),
+        fn = self.lib.hero_ln_quant_fp8 if fp8 else self.lib.hero_ln_quant
+        st = fn(_ptr(x), _DT[x.dtype], _ptr(x_row_scale), _ptr(r),
                                     _DT[r.dtype] if r is not None else 0, _ptr(r_col_scale), _ptr(gamma), _ptr(beta),
                                     float(eps), M, D, _ptr(y_q), _ptr(y_scale), _ptr(y_hp),
                                     _DT[y_hp.dtype] if y_hp is not None else 0, _stream(stream))

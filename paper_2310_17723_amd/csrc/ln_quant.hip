@@ -36,6 +36,7 @@ struct LnArgs {
     float eps; int64_t M; int D;
     int8_t* y_q; float* y_scale; void* y_hp;
     int x_dt, r_dt, hp_dt;       // r_dt / hp_dt = -1 when absent
+    int y_fp8;                   // token-wise E4M3 codes (scale max|y| / 448) instead of INT8 codes
     // gathered form (embedding): row i of x / r / r2 is row x_idx[i] / r_idx[i] / r2_idx[i] of a table
     // with x_rows / r_rows / r2_rows rows (indices are clamped into the table); r2 is a third addend in r_dt
     const int32_t* x_idx; const int32_t* r_idx; const void* r2; const int32_t* r2_idx;
@@ -289,7 +290,7 @@ __global__ __launch_bounds__(64 * ln_max_waves(NCH)) void ln_quant_kernel(LnArgs
 #pragma unroll
             for (int e = 0; e < EPL; ++e) amax = fmaxf(amax, fabsf(v[c][e]));
         amax = wave_reduce<true>(amax);
-        const float sc = amax == 0.0f ? 1.0f : __fdiv_rn(amax, 127.0f);
+        const float sc = amax == 0.0f ? 1.0f : __fdiv_rn(amax, a.y_fp8 ? 448.0f : 127.0f);
         const float inv_sc = HAS_LN ? __builtin_amdgcn_rcpf(sc) : __fdiv_rn(1.0f, sc);
         if (lane == 0) a.y_scale[row] = sc;
 #pragma unroll
@@ -298,7 +299,14 @@ __global__ __launch_bounds__(64 * ln_max_waves(NCH)) void ln_quant_kernel(LnArgs
             if (j0 >= D) continue;
             const int64_t off = row * (int64_t)D + j0;
             uint32_t pk[EPL / 4];
-            if constexpr (HAS_LN) {
+            if (a.y_fp8) {
+                // FP8 output (the variant of Sec. 2.1's 8-bit format): E4M3 of the true quotient, round to
+                // nearest even; |y / s| <= 448 (1 + 2^-23) is clamped to the format's range
+#pragma unroll
+                for (int e4 = 0; e4 < EPL / 4; ++e4)
+                    pk[e4] = fp8x4_sat(__fdiv_rn(v[c][4 * e4], sc), __fdiv_rn(v[c][4 * e4 + 1], sc),
+                                       __fdiv_rn(v[c][4 * e4 + 2], sc), __fdiv_rn(v[c][4 * e4 + 3], sc));
+            } else if constexpr (HAS_LN) {
                 // |v * inv_sc| <= 127 (1 + 2^-22): v * inv_sc + 128 rounds into 1 .. 255
 #pragma unroll
                 for (int e4 = 0; e4 < EPL / 4; ++e4) {
@@ -405,13 +413,11 @@ hero_status launch(const LnArgs& a, hipStream_t st) {
     return HERO_ERR_UNSUPPORTED;
 }
 
-}  // namespace
-
-extern "C" hero_status hero_ln_quant(const void* x, hero_dtype x_dt, const float* x_row_scale,
-                                     const void* r, hero_dtype r_dt, const float* r_col_scale,
-                                     const float* gamma, const float* beta, float eps,
-                                     int64_t M, int64_t D,
-                                     int8_t* y_q, float* y_scale, void* y_hp, hero_dtype y_hp_dt, void* stream) {
+hero_status ln_quant_entry(const void* x, hero_dtype x_dt, const float* x_row_scale,
+                           const void* r, hero_dtype r_dt, const float* r_col_scale,
+                           const float* gamma, const float* beta, float eps,
+                           int64_t M, int64_t D,
+                           void* y_q, int y_fp8, float* y_scale, void* y_hp, hero_dtype y_hp_dt, void* stream) {
     if (M < 0 || D <= 0) return HERO_ERR_SHAPE;
     if (D % 16 != 0) return HERO_ERR_UNSUPPORTED;
     if (M == 0) return HERO_OK;
@@ -431,12 +437,31 @@ extern "C" hero_status hero_ln_quant(const void* x, hero_dtype x_dt, const float
     LnArgs a;
     a.x = x; a.x_row_scale = x_row_scale; a.r = r; a.r_col_scale = r_col_scale;
     a.gamma = gamma; a.beta = beta; a.eps = eps; a.M = M; a.D = (int)D;
-    a.y_q = y_q; a.y_scale = y_scale; a.y_hp = y_hp;
+    a.y_q = (int8_t*)y_q; a.y_scale = y_scale; a.y_hp = y_hp;
     a.x_dt = (int)x_dt; a.r_dt = r ? (int)r_dt : -1; a.hp_dt = y_hp ? (int)y_hp_dt : -1;
+    a.y_fp8 = y_fp8;
     a.x_idx = a.r_idx = a.r2_idx = nullptr; a.r2 = nullptr; a.x_rows = a.r_rows = a.r2_rows = 0;
     hipStream_t st = (hipStream_t)stream;
     if (x_i8) return launch<HERO_I8>(a, st);
     return x_dt == HERO_BF16 ? launch<HERO_BF16>(a, st) : launch<HERO_F16>(a, st);
+}
+
+}  // namespace
+
+extern "C" hero_status hero_ln_quant(const void* x, hero_dtype x_dt, const float* x_row_scale,
+                                     const void* r, hero_dtype r_dt, const float* r_col_scale,
+                                     const float* gamma, const float* beta, float eps,
+                                     int64_t M, int64_t D,
+                                     int8_t* y_q, float* y_scale, void* y_hp, hero_dtype y_hp_dt, void* stream) {
+    return ln_quant_entry(x, x_dt, x_row_scale, r, r_dt, r_col_scale, gamma, beta, eps, M, D, y_q, 0, y_scale, y_hp, y_hp_dt, stream);
+}
+
+extern "C" hero_status hero_ln_quant_fp8(const void* x, hero_dtype x_dt, const float* x_row_scale,
+                                         const void* r, hero_dtype r_dt, const float* r_col_scale,
+                                         const float* gamma, const float* beta, float eps,
+                                         int64_t M, int64_t D,
+                                         void* y_q, float* y_scale, void* y_hp, hero_dtype y_hp_dt, void* stream) {
+    return ln_quant_entry(x, x_dt, x_row_scale, r, r_dt, r_col_scale, gamma, beta, eps, M, D, y_q, 1, y_scale, y_hp, y_hp_dt, stream);
 }
 
 extern "C" hero_status hero_embed_ln_quant(const int32_t* tok_ids, const int32_t* pos_ids, const int32_t* type_ids,
@@ -457,7 +482,7 @@ extern "C" hero_status hero_embed_ln_quant(const int32_t* tok_ids, const int32_t
     LnArgs a;
     a.x = tok_table; a.x_row_scale = tok_scale; a.r = pos_table; a.r_col_scale = nullptr;
     a.gamma = gamma; a.beta = beta; a.eps = eps; a.M = T; a.D = (int)D;
-    a.y_q = y_q; a.y_scale = y_scale; a.y_hp = nullptr;
+    a.y_q = y_q; a.y_scale = y_scale; a.y_hp = nullptr; a.y_fp8 = 0;
     a.x_dt = HERO_I8; a.r_dt = (int)pt_dt; a.hp_dt = -1;
     a.x_idx = tok_ids; a.r_idx = pos_ids; a.r2 = type_table; a.r2_idx = type_table ? type_ids : nullptr;
     a.x_rows = (int)V; a.r_rows = (int)P; a.r2_rows = type_table ? (int)NT : 0;

@@ -72,6 +72,40 @@ def test_ln_quant_pure_per_token_quant_is_bit_exact(hero):
     assert_exact(to_np(q), rq_o)
 
 
+@pytest.mark.parametrize("M,D", [(70, 1024), (33, 4096), (200, 48), (9, 8192)])
+def test_ln_quant_fp8_output(hero, M, D):
+    """hero_ln_quant_fp8: token-wise E4M3 output (scale max|y| / 448).  Behind a LayerNorm the codes are in the
+    tolerance class of the INT8 form (equal on all but 0.1 %, the rest adjacent E4M3 values: y itself differs in
+    its last bits); without one (gamma NULL) the quotient is the IEEE one and the codes are exact.  The result
+    feeds hero_fp8_gemm as A / a_row_scale."""
+    xq, rq, xs, rc, gam, bet, hb = _ln_inputs(1500 + D, M, D)
+    q_o, s_o, _ = O.ln_quant(xq, O.I8, xs, rq, O.I8, rc, gam, bet, 1e-12, fp8=True)
+    q, s, _ = hero.hero_ln_quant(dev(xq), dev(xs), dev(rq), dev(rc), dev(gam), dev(bet), 1e-12, fp8=True)
+    assert_scales(to_np(s), s_o, "y_scale fp8")
+    assert_fp8_codes(to_np(q), q_o, O.e4m3_to_f32, "LN fp8", max_frac=max(1e-3, 2.5 / q_o.size))
+    if D <= 4096:
+        q_o, s_o, hp_o = O.ln_quant(hb, O.BF16, None, None, 0, None, gam, bet, 1e-5, y_hp_dt=O.BF16, fp8=True)
+        q, s, hp = hero.hero_ln_quant(dev(hb), None, None, None, dev(gam), dev(bet), 1e-5, y_hp_dtype=torch.bfloat16, fp8=True)
+        assert_scales(to_np(s), s_o)
+        assert_fp8_codes(to_np(q), q_o, O.e4m3_to_f32, "LN fp8, bf16 input", max_frac=max(1e-3, 2.5 / q_o.size))
+        assert rel_err(O.bf16_to_f32(to_np(hp)), O.bf16_to_f32(hp_o)) <= 2e-2
+        # pure per-token FP8 quantization of a bf16 tensor: exact
+        q_o, s_o, _ = O.ln_quant(hb, O.BF16, None, None, 0, None, None, None, 0.0, fp8=True)
+        q, s, _ = hero.hero_ln_quant(dev(hb), None, None, None, None, None, 0.0, fp8=True)
+        assert_exact(to_np(s), s_o, "fp8 twq scale")
+        assert_exact(to_np(q), q_o, "fp8 twq codes")
+        # ... and the chain LN^quant(FP8) -> FP8 GeMM^quant against the oracle's chain
+        if D == 1024:
+            g = synth.rng(1501)
+            N = 136
+            W = (g.standard_normal((N, D)) * 0.05).astype(np.float32)
+            cs = (np.abs(W).max(axis=1) / 448).astype(np.float32)
+            Bt = O.f32_to_e4m3((W / cs[:, None]).astype(np.float32))
+            ref = O.fp8_gemm(q_o, Bt, a_row_scale=s_o, b_col_scale=cs, epi=O.EPI_DEQUANT, c_dt=O.BF16)
+            got = hero.hero_fp8_gemm(q, dev(Bt), s, dev(cs), epi=HB.EPI_DEQUANT, out_dtype=torch.bfloat16)
+            assert rel_err(O.bf16_to_f32(to_np(got)), O.bf16_to_f32(ref)) <= 2e-2
+
+
 def test_ln_quant_rejects_bad_arguments(hero):
     x = torch.zeros((4, 40), dtype=torch.int8, device="cuda")
     with pytest.raises(HB.HeroError) as e:
