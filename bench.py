@@ -29,8 +29,8 @@ sys.path.insert(0, ROOT)
 # (two runs, scaled by the same counters on a plain copy of known size); the summaries are in
 # profiles/.  Keyed by (M, N, K) of the FC1 GeMM^quant; anything else reports null.
 MEASURED_TRAFFIC = {
-    # profiles/bert-large_kernels_hbm_traffic_pmc.txt: fetch 45550.1 KiB x 2.00 (copy calibration), write 65548.9 KiB x 1.00
-    (16384, 4096, 1024): {"fetch_bytes": 93286605, "write_bytes": 67122074},
+    # profiles/bert-large_kernels_hbm_traffic_pmc.txt: fetch 47583.7 KiB x 2.00 (copy calibration), write 65539.5 KiB x 1.00
+    (16384, 4096, 1024): {"fetch_bytes": 97441604, "write_bytes": 67112448},
 }
 
 PEAK_INT8_TOPS = 5000.0      # MI355X dense INT8 MFMA, TOP/s
