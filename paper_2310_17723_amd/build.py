@@ -20,7 +20,8 @@ LIB = os.path.join(HERE, "libhero.so")
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-Wall", "-Wno-unused-function", "-DHERO_BUILD_ARCH=\"gfx950\""]
+         "-Wall", "-Wno-unused-function", "-Wno-inline-asm",      # (the m0 clobber of the direct-load asm is intended)
+         "-DHERO_BUILD_ARCH=\"gfx950\""]
 
 
 # extra per-file flags
