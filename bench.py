@@ -168,6 +168,27 @@ def fc1_roofline(hero, shape, seed, iters=20):
             "traffic": MEASURED_TRAFFIC.get((M, N, K))}
 
 
+def measured_ceilings(hero):
+    """What this machine sustains, beside the nameplate peaks the fractions are quoted against: a register-only
+    INT8 MFMA loop on near-constant and on random operand bytes (the clock under the matrix cores is power-limited
+    and depends on the data) and a plain 256 MiB device copy."""
+    import torch
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    out = {}
+    for name, rnd in (("mfma_int8_constant_operands_tops", 0), ("mfma_int8_random_operands_tops", 1)):
+        ops = [0.0]
+
+        def fn():
+            ops[0] = hero.hero_probe_mfma_i8(rnd, 2048, sink)
+        ms = time_gpu(fn, 5, warmup=2)
+        out[name] = round(ops[0] / (ms * 1e-3) / 1e12, 1)
+    src = torch.randint(-127, 128, (256 << 20,), dtype=torch.int8, device="cuda")
+    dst = torch.empty_like(src)
+    ms = time_gpu(lambda: hero.hero_probe_copy(src, dst), 5, warmup=2)
+    out["copy_256MiB_gbs"] = round(2.0 * (256 << 20) / (ms * 1e-3) / 1e9, 1)      # read + write
+    return out
+
+
 def gemm_sweep(hero, seed, iters=10):
     import torch
     from paper_2310_17723_amd import binding as HB, synth
@@ -432,6 +453,8 @@ def main():
             rec["attention"] = attn_variants(hero, shape, args.seed)
         log("[bench] FP8 variant of the FC1 / FC2 GEMMs")
         rec["fp8_gemm"] = fp8_gemm_leg(hero, shape, args.seed)
+        log("[bench] measured ceilings (register-only MFMA loop, plain copy)")
+        rec["roofline"]["measured_ceilings"] = measured_ceilings(hero)
         log("[bench] GEMM sweep")
         rec["gemm_sweep"] = gemm_sweep(hero, args.seed)
         del st

@@ -344,6 +344,17 @@ hero_status hero_weight_fold_quant(const float* W, int64_t ldw, const float* row
 /* Library build identification: target architecture string, e.g. "gfx950". */
 const char* hero_build_arch(void);
 
+/* Diagnostics (not on the hot path): the ceilings the kernels are measured against, taken on the
+ * machine at hand.
+ *   hero_probe_mfma_i8  enqueues a register-only loop of v_mfma_i32_32x32x32_i8 (one 512-thread workgroup
+ *     per CU, `iters` x 16 instructions per wave) on near-constant (random_bytes == 0) or random
+ *     (random_bytes != 0) operand bytes: the chip's clock under the matrix cores depends on how many
+ *     operand bits toggle.  *ops (host, may be NULL) receives the integer operations the launch
+ *     performs; sink is one device int32 the kernel may write.
+ *   hero_probe_copy  enqueues a plain device copy of `bytes` (a multiple of 16; 16-byte aligned). */
+hero_status hero_probe_mfma_i8(int random_bytes, int64_t iters, int32_t* sink, double* ops, void* stream);
+hero_status hero_probe_copy(const void* src, void* dst, int64_t bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -57,6 +57,8 @@ SYMBOLS = {
                              f32, f32, vp, i32, i32, vp, vp, i32, i64, vp]),
     "hero_int8_attn_online": (i32, [vp, C.POINTER(i64), vp, C.POINTER(i64), vp, C.POINTER(i64), i64, i64, i64, i64, i64,
                                     vp, f32, vp, i32, i32, vp, vp, i32, i64, vp]),
+    "hero_probe_mfma_i8": (i32, [i32, i64, vp, C.POINTER(C.c_double), vp]),
+    "hero_probe_copy": (i32, [vp, vp, i64, vp]),
     "hero_layer_workspace_bytes": (C.c_size_t, [C.POINTER(LayerDesc), i64, i64]),
     "hero_layer_fwd": (i32, [C.POINTER(LayerDesc), C.POINTER(LayerWeights), C.POINTER(LayerIO), vp, C.c_size_t, vp]),
     "hero_bf16_gemm": (i32, [vp, i64, vp, i64, vp, vp, i64, i32, vp, i64, i64, i64, i64, vp]),
@@ -235,6 +237,17 @@ class Hero:
                                             _DT[out.dtype], out.stride(0), _stream(stream))
         self._check(st)
         return out
+
+    # ------------------------------------------------------------------ diagnostics
+    def hero_probe_mfma_i8(self, random_bytes, iters, sink, stream=None) -> float:
+        """Enqueues the register-only MFMA loop; returns the integer operations of the launch."""
+        ops = C.c_double(0.0)
+        self._check(self.lib.hero_probe_mfma_i8(int(bool(random_bytes)), int(iters), _ptr(sink), C.byref(ops), _stream(stream)))
+        return ops.value
+
+    def hero_probe_copy(self, src, dst, stream=None):
+        assert src.is_contiguous() and dst.is_contiguous() and src.numel() * src.element_size() == dst.numel() * dst.element_size()
+        self._check(self.lib.hero_probe_copy(_ptr(src), _ptr(dst), src.numel() * src.element_size(), _stream(stream)))
 
     # ------------------------------------------------------------------ BF16 side
     def hero_bf16_gemm(self, A, Wt, bias=None, residual=None, gelu=False, C_out=None, stream=None):

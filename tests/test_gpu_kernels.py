@@ -587,3 +587,24 @@ def test_bf16_attn_matches_oracle(hero, B, S, H, Dh, mask):
     dq = dev(qkv).view(B, S, 3, H, Dh)
     got = hero.hero_bf16_attn(dq[:, :, 0], dq[:, :, 1], dq[:, :, 2], 1.0 / np.sqrt(Dh), mask=mask, kv_len=dev(kv_len))
     assert rel_err(O.bf16_to_f32(to_np(got)), O.bf16_to_f32(ref)) <= 2e-2
+
+
+# ============================================================ diagnostics
+def test_probe_entry_points(hero):
+    """The ceiling probes of the bench: the copy copies, the MFMA loop reports its operation count, bad sizes
+    are refused before any launch."""
+    src = torch.randint(-127, 128, (1 << 20,), dtype=torch.int8, device="cuda")
+    dst = torch.zeros_like(src)
+    hero.hero_probe_copy(src, dst)
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst)
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    for rnd in (0, 1):
+        ops = hero.hero_probe_mfma_i8(rnd, 8, sink)
+        torch.cuda.synchronize()
+        cus = torch.cuda.get_device_properties(0).multi_processor_count
+        assert ops == cus * 8 * 8 * 16 * 65536.0 and int(sink.item()) == 0
+    with pytest.raises(HB.HeroError):
+        hero.hero_probe_mfma_i8(0, 0, sink)
+    with pytest.raises(HB.HeroError):
+        hero.hero_probe_copy(src[:24], dst[:24])
