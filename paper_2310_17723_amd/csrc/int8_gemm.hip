@@ -69,6 +69,11 @@ __device__ __forceinline__ v16f mfma_wide_f8(v4i a_lo, v4i a_hi, v4i b_lo, v4i b
     const v8i b = {b_lo[0], b_lo[1], b_lo[2], b_lo[3], b_hi[0], b_hi[1], b_hi[2], b_hi[3]};
     return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 0, 0, 0, 0, 0, 0);   // E4M3 x E4M3, unit scales
 }
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>), in order
+template <int N, int I = 0, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+    if constexpr (I < N) { f(std::integral_constant<int, I>{}); static_for<N, I + 1>(f); }
+}
 template <int ADT> struct AccOf { using type = typename std::conditional<ADT == HERO_I8, v16i, v16f>::type; };
 
 template <int CDT> struct ElemSize { static constexpr int v = CDT == HERO_I32 ? 4 : ((CDT == HERO_I8 || CDT == HERO_F8E4M3) ? 1 : 2); };
@@ -413,20 +418,17 @@ __global__ __launch_bounds__(WM * WN * 64 * KG, MINW) void int8_gemm_kernel(Gemm
         }
         __syncthreads();
     };
+    // PD iterations per trip, one per register set (the set index and the LDS buffer parity are compile-time);
+    // the tail runs the first KT % PD of them
     int kt = 0;
-    for (; kt + PD <= KT; kt += PD) {
-        iteration(kt, 0, std::integral_constant<int, 0>{});
-        iteration(kt + 1, 1, std::integral_constant<int, 1>{});
-        if constexpr (PD >= 4) {
-            iteration(kt + 2, 0, std::integral_constant<int, 2>{});
-            iteration(kt + 3, 1, std::integral_constant<int, 3>{});
-        }
-    }
-    if (kt < KT) { iteration(kt, 0, std::integral_constant<int, 0>{}); ++kt; }
-    if constexpr (PD >= 4) {
-        if (kt < KT) { iteration(kt, 1, std::integral_constant<int, 1>{}); ++kt; }
-        if (kt < KT) { iteration(kt, 0, std::integral_constant<int, 2>{}); ++kt; }
-    }
+    auto trip = [&](auto FULL) {
+        static_for<PD>([&](auto U) {
+            constexpr int u = decltype(U)::value;
+            if (decltype(FULL)::value || kt + u < KT) iteration(kt + u, u & 1, U);
+        });
+    };
+    for (; kt + PD <= KT; kt += PD) trip(std::true_type{});
+    if (kt < KT) trip(std::false_type{});
     if constexpr (KG > 1 && ADT == HERO_I8) {
         // groups 1 .. KG-1 hand their accumulators to group 0 (register-major, lane-minor: no bank conflicts);
         // the loop's last barrier has released every group's slab buffers
@@ -923,6 +925,8 @@ hero_status launch_splitk(const GemmArgs& g, const SplitK& p, void* ws, hipStrea
     g1.per_xcd = (int)((tiles + NUM_XCD - 1) / NUM_XCD);
     g1.ksplit = p.ksplit; g1.kslabs = p.kslabs;
     const dim3 grid((unsigned)(g1.per_xcd * NUM_XCD), (unsigned)p.ksplit);
+    // (measured on 64 x 16384 x 4096: 4, 8 or 16 slabs in flight in registers, and 64 x 128 or 64 x 256 tiles,
+    // stream the weights no faster than this: 2.5-2.6 TB/s)
     if (p.BM == 64) hipLaunchKernelGGL((int8_gemm_kernel<64, 64, 2, 2, 4, 2, HERO_EPI_RAW_I32, HERO_I32, -1, true>), grid, dim3(256), 0, st, g1);
     else hipLaunchKernelGGL((int8_gemm_kernel<128, 128, 2, 2, 2, 2, HERO_EPI_RAW_I32, HERO_I32, -1, true>), grid, dim3(256), 0, st, g1);
     hero_status s1 = hero_launch_status();
