@@ -133,8 +133,8 @@ hero_status hero_embed_ln_quant(const int32_t* tok_ids, const int32_t* pos_ids, 
  * Constraints: K % 64 == 0; lda, ldb multiples of 16; ldc, ldr multiples of 4; base
  * pointers 16-byte aligned; M, N arbitrary (>= 0; zero is a no-op); M < 2^23.
  * The tile shape is chosen from the problem size; the environment variable HERO_GEMM_TILE (0 = 128x128,
- * 1 = 256x256 one tile per workgroup, 2 = 64x64, 7 = 256x256 persistent) overrides it for tuning runs
- * and tests.  Every choice gives the same result.
+ * 1 = 256x256 one tile per workgroup, 2 = 64x64, 7 = 256x256 persistent, 8 = 128x128 persistent) overrides
+ * it for tuning runs and tests.  Every choice gives the same result.
  */
 hero_status hero_int8_gemm(const int8_t* A, int64_t lda, const float* a_row_scale,
                            const int8_t* Bt, int64_t ldb, const float* b_col_scale,

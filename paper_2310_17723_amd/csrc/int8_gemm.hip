@@ -13,8 +13,9 @@
 //   * int8_gemm_persistent_kernel (large problems): 256x256 block tile, 8 waves of 128x64,
 //     slabs of 64 bytes of K copied global -> LDS directly (global_load_lds_dwordx4) through
 //     a ring of 4 stages; one workgroup per CU walks its tiles and the ring runs through the
-//     tile boundaries.  Measured on MI355X the L2 -> CU path, not the matrix cores, bounds
-//     smaller tiles (a 128x128 tile needs 64 B/clk/CU at MFMA peak, the path gives 20-35).
+//     tile boundaries.  A second form, 128x128 with 4 waves of 64x64 and two workgroups per CU,
+//     serves the sizes at which the large tile would leave CUs idle; per tile area it needs
+//     twice the L2 -> LDS traffic and is 10-15 % slower once every CU has work.
 //   * int8_gemm_dma_kernel: the same tile, one tile per workgroup (short K, huge strides).
 //   * int8_gemm_kernel (small or skinny problems): 128x128 / 64x64 tile staged through registers.
 // The epilogue works in registers: a lane-half exchange (v_permlane32_swap) gives every lane a
@@ -616,18 +617,17 @@ __device__ __forceinline__ void dma4s(uint32_t voff, const float* sbase, uint32_
                  :: "v"(voff), "s"(sbase), "s"(lds_base) : "memory", "m0");
 }
 
-template <int NS, int EPI, int CDT, int RDT, int ADT = HERO_I8>
-__global__ __launch_bounds__(512, 2) void int8_gemm_persistent_kernel(GemmArgs g) {
+template <int BM, int BN, int WM, int WN, int NS, int EPI, int CDT, int RDT, int ADT = HERO_I8>
+__global__ __launch_bounds__(WM * WN * 64, 2) void int8_gemm_persistent_kernel(GemmArgs g) {
     using ACC = typename AccOf<ADT>::type;
     constexpr bool UNIT = ADT == HERO_BF16;
     constexpr bool WIDE = ADT == HERO_F8E4M3;
-    constexpr int BM = 256, BN = 256, WM = 2, WN = 4;
     constexpr int NT = WM * WN * 64, NWAVE = WM * WN;
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
     constexpr int A_BYTES = BM * BK, B_BYTES = BN * BK, STAGE = A_BYTES + B_BYTES;
     constexpr int A_UNITS = A_BYTES / 16 / NT, B_UNITS = B_BYTES / 16 / NT, NW = A_UNITS + B_UNITS;
     constexpr int NM = TM * TN, NFR = TM + TN;
-    static_assert(NS == 4 && 2 * NW <= NM && NFR <= NM && NFR % 2 == 0 && NW <= NM - TM + 1, "ring / interleave plan");
+    static_assert(NS == 4 && NW <= NM && NFR <= 2 * NM && NFR % 2 == 0, "ring / interleave plan");
     constexpr int RING = NS * STAGE;
     constexpr int SVF = 4 * BN;                                  // floats per vector set: column scale, bias, S_a, row scale
     static_assert(BM == BN, "the row-scale vector shares the column vectors' length");
@@ -671,9 +671,11 @@ __global__ __launch_bounds__(512, 2) void int8_gemm_persistent_kernel(GemmArgs g
     // moves on to the tile: their buffer (parity of the tile) is still being read by the epilogue of the tile
     // two back until every wave has started the tile in between.
     auto issue_tile_vectors = [&](int par) {
-        // wave w fetches 64 entries (chunk w % 4) of vectors w / 4 and 2 + w / 4
+        // wave w fetches 64 entries (chunk w % CH) of vectors w / CH and 2 + w / CH
+        constexpr int CH = BN / 64;
+        static_assert(NWAVE == 2 * CH, "two vectors per wave");
         const int wu = __builtin_amdgcn_readfirstlane(wave);
-        const int ch = (wu & 3) * 64, which = wu >> 2;
+        const int ch = (wu % CH) * 64, which = wu / CH;
         const uint32_t dst = svbase + par * SVF * 4 + ch * 4;
         const uint32_t cn = (uint32_t)min(ch + lane, g.N - 1 - n0i) * 4u, cm = (uint32_t)min(ch + lane, g.M - 1 - m0i) * 4u;
         if (EPI == HERO_EPI_RAW_I32) return;
@@ -783,9 +785,11 @@ __global__ __launch_bounds__(512, 2) void int8_gemm_persistent_kernel(GemmArgs g
                                 f1[t] = *reinterpret_cast<const v4i*>(stn + fo[1][t]);
                             }
                         }
-                        if (odd) {
-                            const int j = 2 * (n - (TM - 1));
-                            if (j < 2 * NW) { issue_pair(j, pstage); issue_pair(j + 1, pstage); }
+                        if (odd) {                                     // PPS units of the new pair per instruction slot
+                            constexpr int SLOTS = NM - TM + 1, PPS = (NW + SLOTS - 1) / SLOTS;
+#pragma unroll
+                            for (int u = (n - (TM - 1)) * PPS; u < (n - (TM - 1) + 1) * PPS; ++u)
+                                if (u < NW) { issue_pair(2 * u, pstage); issue_pair(2 * u + 1, pstage); }
                         }
                     }
                     __builtin_amdgcn_sched_barrier(0);
@@ -950,11 +954,29 @@ hero_status launch_grid(GemmArgs g, int BM, int BN, int threads, K kernel, hipSt
     return hero_launch_status();
 }
 
-// Tile choice: the 256x256 direct-to-LDS kernel once the grid has enough tiles (160) to keep most
-// of the 256 CUs busy; otherwise the register-staged kernel with 128x128 tiles, or 64x64 ones while fewer
-// than 192 tiles of 128x128 exist (small problems are latency-bound: more, shorter workgroups).
-// HERO_GEMM_TILE overrides the choice for tuning runs and tests: 0 = 128x128, 1 = 256x256 one tile per
-// workgroup, 2 = 64x64, 7 = 256x256 persistent.
+// Tile choice (all measured on MI355X): the persistent 256x256 direct-to-LDS kernel, one workgroup per CU, once
+// the grid has enough tiles (160) to keep most of the 256 CUs busy; the persistent 128x128 form of the same kernel,
+// two workgroups per CU, below that (with 96-128 tiles of 256x256 half of the CUs would idle: 10-30 % faster there)
+// and where the 256x256 tiles would make a second, mostly empty round (257-383 tiles: 15-20 % faster; per full
+// round the small tile is 10-15 % slower, it needs twice the L2 -> LDS traffic); 64x64 register-staged tiles while
+// fewer than 192 tiles of 128x128 exist (small problems are latency-bound: more, shorter workgroups).  The
+// persistent kernels need K >= 256, K % 128 == 0 and 32-bit per-lane offsets; otherwise the one-tile-per-workgroup
+// 256x256 kernel or the register-staged 128x128 one take their place.
+// HERO_GEMM_TILE overrides the choice for tuning runs and tests: 0 = 128x128 register-staged, 1 = 256x256 one tile
+// per workgroup, 2 = 64x64, 7 = 256x256 persistent, 8 = 128x128 persistent.
+template <int BM, int BN, int WM, int WN, int EPI, int CDT, int RDT>
+hero_status launch_persistent(const GemmArgs& g, int wg_per_cu, hipStream_t st) {
+    GemmArgs gp = g;
+    gp.ntm = (g.M + BM - 1) / BM; gp.ntn = (g.N + BN - 1) / BN;
+    const int64_t tiles = (int64_t)gp.ntm * gp.ntn;
+    if (tiles > 0x7fffff00LL) return HERO_ERR_SHAPE;
+    gp.per_xcd = (int)((tiles + NUM_XCD - 1) / NUM_XCD);
+    const int cap = 32 * wg_per_cu;                                   // 32 CUs per XCD
+    const int nslot = gp.per_xcd < cap ? gp.per_xcd : cap;
+    hipLaunchKernelGGL((int8_gemm_persistent_kernel<BM, BN, WM, WN, 4, EPI, CDT, RDT>), dim3((unsigned)(nslot * NUM_XCD)), dim3(WM * WN * 64), 0, st, gp);
+    return hero_launch_status();
+}
+
 template <int EPI, int CDT, int RDT>
 hero_status launch_epi(const GemmArgs& g, void* ws, size_t ws_bytes, hipStream_t st) {
     const char* e = getenv("HERO_GEMM_TILE");
@@ -963,24 +985,19 @@ hero_status launch_epi(const GemmArgs& g, void* ws, size_t ws_bytes, hipStream_t
         const SplitK p = splitk_plan(g.M, g.N, g.K);
         if (p.ksplit > 1 && ws_bytes >= p.bytes) return launch_splitk<EPI, CDT, RDT>(g, p, ws, st);
     }
+    // persistent kernels: K long enough that the slab ring never runs more than one tile ahead, whole pairs of
+    // slabs, 32-bit per-lane offsets (256 rows of lda / ldb bytes)
+    const bool pers_ok = g.K >= 4 * BK && g.K % (2 * BK) == 0 && g.lda < (1 << 24) && g.ldb < (1 << 24);
     if (cfg < 0) {
         const int64_t t256 = (int64_t)((g.M + 255) / 256) * ((g.N + 255) / 256), t128 = (int64_t)((g.M + 127) / 128) * ((g.N + 127) / 128);
-        // measured: with 128 tiles of 256x256 (half of the CUs idle) the 128x128 kernel is 10-15 % faster, with 192
-        // the persistent kernel is 20 % faster
-        cfg = t256 >= 160 ? 1 : ((g.M <= 64 || t128 < 192) ? 2 : 0);     // 64x64 tiles while 128x128 ones would leave CUs idle
+        if (t256 >= 160) cfg = !pers_ok ? 1 : ((t256 > 256 && t256 < 384) ? 8 : 7);
+        else if (g.M <= 64 || t128 < 192) cfg = 2;
+        else cfg = pers_ok ? 8 : 0;
+    } else if ((cfg == 7 || cfg == 8) && !pers_ok) {
+        cfg = cfg == 7 ? 1 : 0;
     }
-    // persistent form of the 256x256 kernel: K long enough that the slab ring never runs more than one tile
-    // ahead, 32-bit per-lane offsets (256 rows of lda / ldb bytes)
-    if ((cfg == 7 || (cfg == 1 && !e)) && g.K >= 4 * BK && g.K % (2 * BK) == 0 && g.lda < (1 << 24) && g.ldb < (1 << 24)) {
-        GemmArgs gp = g;
-        gp.ntm = (g.M + 255) / 256; gp.ntn = (g.N + 255) / 256;
-        const int64_t tiles = (int64_t)gp.ntm * gp.ntn;
-        if (tiles > 0x7fffff00LL) return HERO_ERR_SHAPE;
-        gp.per_xcd = (int)((tiles + NUM_XCD - 1) / NUM_XCD);
-        const int nslot = gp.per_xcd < 32 ? gp.per_xcd : 32;          // 32 CUs per XCD, one workgroup each
-        hipLaunchKernelGGL((int8_gemm_persistent_kernel<4, EPI, CDT, RDT>), dim3((unsigned)(nslot * NUM_XCD)), dim3(512), 0, st, gp);
-        return hero_launch_status();
-    }
+    if (cfg == 7) return launch_persistent<256, 256, 2, 4, EPI, CDT, RDT>(g, 1, st);
+    if (cfg == 8) return launch_persistent<128, 128, 2, 2, EPI, CDT, RDT>(g, 2, st);
     if (cfg == 1) return launch_grid(g, 256, 256, 512, int8_gemm_dma_kernel<256, 256, 2, 4, 4, 2, EPI, CDT, RDT>, st);
     if (cfg == 2) {                             // small or skinny problems: 64x64 tiles
         // few tiles and a long K: 4 groups of waves per workgroup split K (K / 64 must divide evenly);
@@ -996,45 +1013,64 @@ hero_status launch_epi(const GemmArgs& g, void* ws, size_t ws_bytes, hipStream_t
 
 }  // namespace
 
-// bf16 operands through the persistent 256x256 kernel (called by hero_bf16_gemm for large problems;
-// HERO_ERR_UNSUPPORTED means "not this kernel's case", the caller then uses its own).
+// bf16 operands through the persistent kernels (called by hero_bf16_gemm for large problems;
+// HERO_ERR_UNSUPPORTED means "not this kernel's case", the caller then uses its own).  The tile is chosen as for
+// INT8 operands; HERO_BF16_TILE = 7 / 8 / 0 forces the 256x256 / 128x128 form / the caller's kernel for tuning runs and tests.
+namespace {
+template <int BM, int BN, int WM, int WN>
+hero_status launch_bf16_persistent(GemmArgs g, int wg_per_cu, bool gelu, hipStream_t st) {
+    g.ntm = (g.M + BM - 1) / BM; g.ntn = (g.N + BN - 1) / BN;
+    const int64_t tiles = (int64_t)g.ntm * g.ntn;
+    g.per_xcd = (int)((tiles + NUM_XCD - 1) / NUM_XCD);
+    const int cap = 32 * wg_per_cu, nslot = g.per_xcd < cap ? g.per_xcd : cap;
+    const dim3 grid((unsigned)(nslot * NUM_XCD)), block(WM * WN * 64);
+    if (gelu) {
+        if (g.residual) hipLaunchKernelGGL((int8_gemm_persistent_kernel<BM, BN, WM, WN, 4, HERO_EPI_DEQUANT_GELU, HERO_BF16, HERO_BF16, HERO_BF16>), grid, block, 0, st, g);
+        else hipLaunchKernelGGL((int8_gemm_persistent_kernel<BM, BN, WM, WN, 4, HERO_EPI_DEQUANT_GELU, HERO_BF16, -1, HERO_BF16>), grid, block, 0, st, g);
+    } else {
+        if (g.residual) hipLaunchKernelGGL((int8_gemm_persistent_kernel<BM, BN, WM, WN, 4, HERO_EPI_DEQUANT, HERO_BF16, HERO_BF16, HERO_BF16>), grid, block, 0, st, g);
+        else hipLaunchKernelGGL((int8_gemm_persistent_kernel<BM, BN, WM, WN, 4, HERO_EPI_DEQUANT, HERO_BF16, -1, HERO_BF16>), grid, block, 0, st, g);
+    }
+    return hero_launch_status();
+}
+}  // namespace
+
 hero_status hero_bf16_gemm_large(const void* A, int64_t lda, const void* Wt, int64_t ldb,
                                  const float* bias, const void* residual, int64_t ldr, int gelu,
                                  void* C, int64_t ldc, int64_t M, int64_t N, int64_t K, hipStream_t st) {
-    const int64_t tiles = ((M + 255) / 256) * ((N + 255) / 256);
-    if (tiles < 96 || tiles > 0x7fffff00LL || K % 64 != 0 || K * 2 < 4 * BK || lda * 2 >= (1 << 24) || ldb * 2 >= (1 << 24))
+    const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256), t128 = ((M + 127) / 128) * ((N + 127) / 128);
+    if (t128 < 192 || t128 > 0x7fffff00LL || K % 64 != 0 || K * 2 < 4 * BK || lda * 2 >= (1 << 24) || ldb * 2 >= (1 << 24))
         return HERO_ERR_UNSUPPORTED;
     GemmArgs g;
     g.A = (const int8_t*)A; g.lda = lda * 2; g.a_row_scale = nullptr; g.Bt = (const int8_t*)Wt; g.ldb = ldb * 2;
     g.b_col_scale = nullptr; g.bias = bias; g.residual = residual; g.ldr = ldr; g.out_col_scale = nullptr;
     g.C = C; g.ldc = ldc; g.M = (int)M; g.N = (int)N; g.K = (int)(K * 2);
     g.ksplit = 1; g.kslabs = 0;
-    g.ntm = (int)((M + 255) / 256); g.ntn = (int)((N + 255) / 256);
-    g.per_xcd = (int)((tiles + NUM_XCD - 1) / NUM_XCD);
-    const int nslot = g.per_xcd < 32 ? g.per_xcd : 32;
-    const dim3 grid((unsigned)(nslot * NUM_XCD)), block(512);
-    if (gelu) {
-        if (residual) hipLaunchKernelGGL((int8_gemm_persistent_kernel<4, HERO_EPI_DEQUANT_GELU, HERO_BF16, HERO_BF16, HERO_BF16>), grid, block, 0, st, g);
-        else hipLaunchKernelGGL((int8_gemm_persistent_kernel<4, HERO_EPI_DEQUANT_GELU, HERO_BF16, -1, HERO_BF16>), grid, block, 0, st, g);
-    } else {
-        if (residual) hipLaunchKernelGGL((int8_gemm_persistent_kernel<4, HERO_EPI_DEQUANT, HERO_BF16, HERO_BF16, HERO_BF16>), grid, block, 0, st, g);
-        else hipLaunchKernelGGL((int8_gemm_persistent_kernel<4, HERO_EPI_DEQUANT, HERO_BF16, -1, HERO_BF16>), grid, block, 0, st, g);
-    }
-    return hero_launch_status();
+    const char* e = getenv("HERO_BF16_TILE");
+    const int cfg = e ? atoi(e) : ((t256 < 160 || (t256 > 256 && t256 < 384)) ? 8 : 7);
+    if (cfg == 0) return HERO_ERR_UNSUPPORTED;
+    if (cfg == 8) return launch_bf16_persistent<128, 128, 2, 2>(g, 2, gelu != 0, st);
+    return launch_bf16_persistent<256, 256, 2, 4>(g, 1, gelu != 0, st);
 }
 
 // The FP8 variant: the same kernels with E4M3 operands (no split-K: fp32 partial sums would not commute).
 template <int EPI, int CDT, int RDT>
 hero_status launch_epi_fp8(GemmArgs g, hipStream_t st) {
     const int64_t t256 = (int64_t)((g.M + 255) / 256) * ((g.N + 255) / 256), t128 = (int64_t)((g.M + 127) / 128) * ((g.N + 127) / 128);
-    if (t256 >= 160 && t256 <= 0x7fffff00LL && g.K >= 4 * BK && g.K % (2 * BK) == 0 && g.lda < (1 << 24) && g.ldb < (1 << 24)) {
-        g.ntm = (g.M + 255) / 256; g.ntn = (g.N + 255) / 256;
-        g.per_xcd = (int)((t256 + NUM_XCD - 1) / NUM_XCD);
-        const int nslot = g.per_xcd < 32 ? g.per_xcd : 32;
-        hipLaunchKernelGGL((int8_gemm_persistent_kernel<4, EPI, CDT, RDT, HERO_F8E4M3>), dim3((unsigned)(nslot * NUM_XCD)), dim3(512), 0, st, g);
+    const bool pers_ok = t128 <= 0x7fffff00LL && g.K >= 4 * BK && g.K % (2 * BK) == 0 && g.lda < (1 << 24) && g.ldb < (1 << 24);
+    const char* e = getenv("HERO_FP8_TILE");                          // tuning runs and tests: 0 / 7 / 8 as for HERO_GEMM_TILE
+    const int cfg = e ? atoi(e) : -1;
+    const bool small = g.M <= 64 || t128 < 192;
+    if (pers_ok && (cfg == 7 || cfg == 8 || (cfg < 0 && !small))) {
+        const bool tile128 = cfg == 8 || (cfg < 0 && (t256 < 160 || (t256 > 256 && t256 < 384)));
+        g.ntm = tile128 ? (g.M + 127) / 128 : (g.M + 255) / 256; g.ntn = tile128 ? (g.N + 127) / 128 : (g.N + 255) / 256;
+        g.per_xcd = (int)(((tile128 ? t128 : t256) + NUM_XCD - 1) / NUM_XCD);
+        const int cap = tile128 ? 64 : 32, nslot = g.per_xcd < cap ? g.per_xcd : cap;
+        if (tile128) hipLaunchKernelGGL((int8_gemm_persistent_kernel<128, 128, 2, 2, 4, EPI, CDT, RDT, HERO_F8E4M3>), dim3((unsigned)(nslot * NUM_XCD)), dim3(256), 0, st, g);
+        else hipLaunchKernelGGL((int8_gemm_persistent_kernel<256, 256, 2, 4, 4, EPI, CDT, RDT, HERO_F8E4M3>), dim3((unsigned)(nslot * NUM_XCD)), dim3(512), 0, st, g);
         return hero_launch_status();
     }
-    if (g.M <= 64 || t128 < 192)
+    if (small && cfg != 0)
         return launch_grid(g, 64, 64, 256, int8_gemm_kernel<64, 64, 2, 2, 2, 2, EPI, CDT, RDT, false, 1, HERO_F8E4M3>, st);
     return launch_grid(g, 128, 128, 256, int8_gemm_kernel<128, 128, 2, 2, 2, 2, EPI, CDT, RDT, false, 1, HERO_F8E4M3>, st);
 }

@@ -293,7 +293,7 @@ def test_gemm_many_tiles_ragged_edges(hero, M, N, K, monkeypatch):
     res = O.f32_to_bf16(synth.rng(11).standard_normal((M, N)).astype(np.float32))
     ref_res = O.int8_gemm(A, Bt, a_row_scale=rs, b_col_scale=cs, bias=bias, residual=res, res_dt=O.BF16,
                           epi=O.EPI_DEQUANT, c_dt=O.BF16)
-    for tile in (None, "1", "7"):                  # default choice, one tile per workgroup, persistent
+    for tile in (None, "1", "7", "8"):             # default choice, one tile per workgroup, persistent 256 x 256 and 128 x 128
         if tile is None:
             monkeypatch.delenv("HERO_GEMM_TILE", raising=False)
         else:
@@ -510,11 +510,17 @@ def test_gemm_full_size_sampled_rows(hero, M, N, K):
 
 
 # ============================================================ FP8 variant
-@pytest.mark.parametrize("M,N,K", [(200, 136, 256), (64, 72, 192), (300, 520, 1024), (3300, 3400, 384)])
-def test_fp8_gemm_matches_oracle(hero, M, N, K):
+@pytest.mark.parametrize("M,N,K,tile", [(200, 136, 256, None), (64, 72, 192, None), (300, 520, 1024, None), (3300, 3400, 384, None),
+                                         (3300, 3400, 384, "8"), (2500, 2600, 256, None), (2500, 2600, 256, "7")])
+def test_fp8_gemm_matches_oracle(hero, M, N, K, tile, monkeypatch):
     """hero_fp8_gemm (Sec. 2.1: FP8 as the 8-bit format): E4M3 operands, fp32 accumulation on the matrix cores
     (the oracle carries the exact sum), the INT8 path's epilogue.  16-bit outputs within 2e-2, E4M3 outputs equal
-    up to an adjacent code on <= 0.5 %.  The last shape runs the persistent 256 x 256 kernel with ragged edges."""
+    up to an adjacent code on <= 0.5 %.  The large shapes run the persistent kernels with ragged edges: by
+    default the 256 x 256 one (182 tiles) and the 128 x 128 one (110 tiles of 256 x 256), then each the other one."""
+    if tile is None:
+        monkeypatch.delenv("HERO_FP8_TILE", raising=False)
+    else:
+        monkeypatch.setenv("HERO_FP8_TILE", tile)
     g = synth.rng(1300 + M)
     X = (g.standard_normal((M, K)) * g.uniform(0.5, 4, (M, 1))).astype(np.float32)
     W = (g.standard_normal((K, N)) * 0.05).astype(np.float32)
@@ -563,17 +569,24 @@ def test_fp8_gemm_matches_oracle(hero, M, N, K):
 
 # ============================================================ BF16 side of a switched module
 @pytest.mark.parametrize("M,N,K", [(200, 136, 256), (130, 512, 1024), (64, 72, 96), (2500, 2600, 160), (2560, 2560, 128), (2500, 2600, 192)])
-def test_bf16_gemm_matches_oracle(hero, M, N, K):
-    """The last two shapes have enough 256 x 256 tiles for the persistent kernel (ragged edges, 5 / 4 slabs)."""
+def test_bf16_gemm_matches_oracle(hero, M, N, K, monkeypatch):
+    """The last two shapes have enough tiles for the persistent kernels (ragged edges, 5 / 4 slabs, several tiles
+    per workgroup): the default choice, then the 256 x 256 and the 128 x 128 form forced."""
     g = synth.rng(1000 + M)
     A = O.f32_to_bf16(g.standard_normal((M, K)).astype(np.float32))
     Wt = O.f32_to_bf16((g.standard_normal((N, K)) * 0.05).astype(np.float32))
     bias = (0.1 * g.standard_normal(N)).astype(np.float32)
     res = O.f32_to_bf16(g.standard_normal((M, N)).astype(np.float32))
+    big = K % 64 == 0 and -(-M // 128) * -(-N // 128) >= 192
     for gelu, r in ((False, None), (True, None), (False, res), (True, res)):
         ref = O.bf16_gemm(A, Wt, bias=bias, residual=r, gelu=gelu)
-        got = hero.hero_bf16_gemm(dev(A), dev(Wt), dev(bias), residual=dev(r), gelu=gelu)
-        assert rel_err(O.bf16_to_f32(to_np(got)), O.bf16_to_f32(ref)) <= 2e-2
+        for tile in (None, "7", "8") if big else (None,):
+            if tile is None:
+                monkeypatch.delenv("HERO_BF16_TILE", raising=False)
+            else:
+                monkeypatch.setenv("HERO_BF16_TILE", tile)
+            got = hero.hero_bf16_gemm(dev(A), dev(Wt), dev(bias), residual=dev(r), gelu=gelu)
+            assert rel_err(O.bf16_to_f32(to_np(got)), O.bf16_to_f32(ref)) <= 2e-2, (gelu, r is not None, tile)
 
 
 @pytest.mark.parametrize("mask", [O.MASK_NONE, O.MASK_PADDING, O.MASK_CAUSAL])
