@@ -214,9 +214,9 @@ __global__ __launch_bounds__(256) void bf16_attn_kernel(BAttnArgs a) {
 #pragma unroll
                 for (int r = 0; r < 16; r += 2) {
                     const float e0 = __builtin_amdgcn_exp2f(acc[r] - mn), e1 = __builtin_amdgcn_exp2f(acc[r + 1] - mn);
-                    const uint32_t h0 = f32_to_bf16_bits(e0), h1 = f32_to_bf16_bits(e1);
-                    sum += bf16_bits_to_f32(h0) + bf16_bits_to_f32(h1);       // the sum of what PV really multiplies
-                    pb[r >> 1] = h0 | (h1 << 16);
+                    const uint32_t pk = f32x2_to_bf16x2(e0, e1);
+                    sum += __uint_as_float(pk << 16) + __uint_as_float(pk & 0xffff0000u);   // the sum of what PV really multiplies
+                    pb[r >> 1] = pk;
                 }
                 l = fmaf(l, resc, sum);
                 m2 = mn;
@@ -249,10 +249,8 @@ __global__ __launch_bounds__(256) void bf16_attn_kernel(BAttnArgs a) {
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
             const int e0 = c * 32 + g * 8 + hh * 4;
-            uint32_t hb[4];
-#pragma unroll
-            for (int t = 0; t < 4; ++t) hb[t] = f32_to_bf16_bits(o[c][4 * g + t] * inv_l);
-            v2i w = {(int)(hb[0] | (hb[1] << 16)), (int)(hb[2] | (hb[3] << 16))};
+            v2i w = {(int)f32x2_to_bf16x2(o[c][4 * g] * inv_l, o[c][4 * g + 1] * inv_l),
+                     (int)f32x2_to_bf16x2(o[c][4 * g + 2] * inv_l, o[c][4 * g + 3] * inv_l)};
             *reinterpret_cast<v2i*>(a.out + orow + e0) = w;
         }
 }

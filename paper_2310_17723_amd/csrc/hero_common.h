@@ -28,10 +28,15 @@ static inline hero_status hero_launch_status() {
 
 // ---- 16-bit float storage (round to nearest even) -------------------------------------
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
+typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+typedef float v2f __attribute__((ext_vector_type(2)));
+// v_cvt_pk_bf16_f32 (round to nearest even), one instruction for two values
+__device__ __forceinline__ uint32_t f32x2_to_bf16x2(float lo, float hi) {
+    const v2f v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, v2bf));
+}
 __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
-    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+    return (uint32_t)__builtin_bit_cast(unsigned short, (__bf16)f);
 }
 __device__ __forceinline__ float f16_bits_to_f32(uint32_t h) {
     return (float)__builtin_bit_cast(_Float16, (unsigned short)h);
@@ -48,6 +53,11 @@ template <int DT> __device__ __forceinline__ float hp_to_f32(uint32_t h) {
 }
 template <int DT> __device__ __forceinline__ uint32_t f32_to_hp(float f) {
     return DT == HERO_BF16 ? f32_to_bf16_bits(f) : f32_to_f16_bits(f);
+}
+// two values -> one dword of 16-bit floats (lo in bits 0..15)
+template <int DT> __device__ __forceinline__ uint32_t pack2_hp(float lo, float hi) {
+    if constexpr (DT == HERO_BF16) return f32x2_to_bf16x2(lo, hi);
+    else return f32_to_f16_bits(lo) | (f32_to_f16_bits(hi) << 16);
 }
 
 // ---- the quantization primitive ---------------------------------------------------------

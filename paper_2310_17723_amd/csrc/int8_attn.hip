@@ -312,8 +312,7 @@ __global__ __launch_bounds__(256, ONLINE ? (DH == 64 ? 3 : 2) : (DH == 64 ? 4 : 
                 if (ODT == HERO_I8) {
                     *reinterpret_cast<uint32_t*>((int8_t*)a.out + orow + e0) = quant4_sat(y[0], y[1], y[2], y[3]);
                 } else {
-                    uint32_t h0 = f32_to_hp<ODT>(y[0]), h1 = f32_to_hp<ODT>(y[1]), h2 = f32_to_hp<ODT>(y[2]), h3 = f32_to_hp<ODT>(y[3]);
-                    v2i w = {(int)(h0 | (h1 << 16)), (int)(h2 | (h3 << 16))};
+                    v2i w = {(int)pack2_hp<ODT>(y[0], y[1]), (int)pack2_hp<ODT>(y[2], y[3])};
                     *reinterpret_cast<v2i*>((uint16_t*)a.out + orow + e0) = w;
                 }
             }
@@ -434,8 +433,7 @@ __global__ __launch_bounds__(256, ONLINE ? (DH == 64 ? 3 : 2) : (DH == 64 ? 4 : 
             if (ODT == HERO_I8) {
                 *reinterpret_cast<uint32_t*>((int8_t*)a.out + orow + e0) = quant4_sat(y[0], y[1], y[2], y[3]);
             } else {
-                uint32_t h0 = f32_to_hp<ODT>(y[0]), h1 = f32_to_hp<ODT>(y[1]), h2 = f32_to_hp<ODT>(y[2]), h3 = f32_to_hp<ODT>(y[3]);
-                v2i w = {(int)(h0 | (h1 << 16)), (int)(h2 | (h3 << 16))};
+                v2i w = {(int)pack2_hp<ODT>(y[0], y[1]), (int)pack2_hp<ODT>(y[2], y[3])};
                 *reinterpret_cast<v2i*>((uint16_t*)a.out + orow + e0) = w;
             }
         }

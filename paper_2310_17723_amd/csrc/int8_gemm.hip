@@ -235,10 +235,8 @@ __device__ __forceinline__ void epilogue_direct(const GemmArgs& g, ACC (&acc)[BM
                 uint32_t d[2 * NQ];
 #pragma unroll
                 for (int q = 0; q < H; ++q) {
-                    const uint32_t a0 = f32_to_hp<CDT>(y[q][0]) | (f32_to_hp<CDT>(y[q][1]) << 16);
-                    const uint32_t a1 = f32_to_hp<CDT>(y[q][2]) | (f32_to_hp<CDT>(y[q][3]) << 16);
-                    const uint32_t b0 = f32_to_hp<CDT>(y[q + H][0]) | (f32_to_hp<CDT>(y[q + H][1]) << 16);
-                    const uint32_t b1 = f32_to_hp<CDT>(y[q + H][2]) | (f32_to_hp<CDT>(y[q + H][3]) << 16);
+                    const uint32_t a0 = pack2_hp<CDT>(y[q][0], y[q][1]), a1 = pack2_hp<CDT>(y[q][2], y[q][3]);
+                    const uint32_t b0 = pack2_hp<CDT>(y[q + H][0], y[q + H][1]), b1 = pack2_hp<CDT>(y[q + H][2], y[q + H][3]);
                     swap32(a0, b0, d[4 * q], d[4 * q + 2]);
                     swap32(a1, b1, d[4 * q + 1], d[4 * q + 3]);
                 }
@@ -270,9 +268,8 @@ __device__ __forceinline__ void epilogue_direct(const GemmArgs& g, ACC (&acc)[BM
                         }
 #pragma unroll
                         for (int k = 0; k < 4; ++k) {
-                            const uint32_t h0 = f32_to_hp<CDT>(__uint_as_float(z[q][2 * k]) + hp_to_f32<RDT>(r[k] & 0xffffu));
-                            const uint32_t h1 = f32_to_hp<CDT>(__uint_as_float(z[q][2 * k + 1]) + hp_to_f32<RDT>(r[k] >> 16));
-                            d[4 * q + k] = h0 | (h1 << 16);
+                            d[4 * q + k] = pack2_hp<CDT>(__uint_as_float(z[q][2 * k]) + hp_to_f32<RDT>(r[k] & 0xffffu),
+                                                         __uint_as_float(z[q][2 * k + 1]) + hp_to_f32<RDT>(r[k] >> 16));
                         }
                     }
                     store_piece<2, 2 * NQ>((int8_t*)g.C + ((int64_t)row * g.ldc + col0) * 2, d, col0, g.N, full, al16);

@@ -85,7 +85,7 @@ __device__ __forceinline__ void store_hp(const float (&v)[EPL], uint16_t* dst) {
         v4i o;
 #pragma unroll
         for (int p = 0; p < 4; ++p)
-            o[p] = (int)(f32_to_hp<DT>(v[8 * e8 + 2 * p]) | (f32_to_hp<DT>(v[8 * e8 + 2 * p + 1]) << 16));
+            o[p] = (int)pack2_hp<DT>(v[8 * e8 + 2 * p], v[8 * e8 + 2 * p + 1]);
         *reinterpret_cast<v4i*>(dst + 8 * e8) = o;
     }
 }
