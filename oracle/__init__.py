@@ -335,6 +335,28 @@ def int8_attn(q, k, v, *, qk_scale, p_scale, out_col_scale, out_scale_is_scalar=
     return (out, pd) if dump_p else out
 
 
+def fp8_attn(q, k, v, *, qk_scale, p_scale, out_col_scale, out_scale_is_scalar=False,
+             mask=MASK_NONE, kv_len=None, out_dt=F8, dump_p=False):
+    """FP8 attention (the flow of Sec. 2.2.2 with E4M3 codes).  q [B,Sq,H,Dh], k/v [B,Skv,H,Dh] uint8 E4M3 bytes
+    (any strides, unit channel stride); out_dt F8 (per-column scales) or a 16-bit / fp32 type (scalar scale)."""
+    B, Sq, H, Dh = q.shape
+    Skv = k.shape[1]
+    assert q.dtype == np.uint8 and k.dtype == np.uint8 and v.dtype == np.uint8
+    ocs = np.ascontiguousarray(out_col_scale, np.float32).reshape(-1)
+    if kv_len is not None:
+        kv_len = np.ascontiguousarray(kv_len, np.int32)
+    out = np.empty((B * Sq, H * Dh), _NP_OF[out_dt])
+    pd = np.zeros((B, H, Sq, Skv), np.uint8) if dump_p else None
+    base = lambda a: C.c_void_p(a.ctypes.data)
+    rc = lib().orc_fp8_attn(base(q), _strides(q), base(k), _strides(k), base(v), _strides(v),
+                            _i64(B), _i64(H), _i64(Sq), _i64(Skv), _i64(Dh),
+                            C.c_float(qk_scale), C.c_float(p_scale), _p(ocs), C.c_int(int(out_scale_is_scalar)),
+                            C.c_int(mask), _p(kv_len), _p(out), C.c_int(out_dt), _i64(H * Dh), _p(pd))
+    if rc != 0:
+        raise ValueError("oracle fp8_attn: invalid arguments")
+    return (out, pd) if dump_p else out
+
+
 def int8_attn_online(q, k, v, *, qk_scale_h, p_scale, out_col_scale, out_scale_is_scalar=False,
                      mask=MASK_NONE, kv_len=None, out_dt=I8, kv_block=64, dump_c=False):
     """INT8 attention with the online (quantize-then-normalise) Softmax^quant variant.  qk_scale_h: one d~ per

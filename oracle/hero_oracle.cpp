@@ -526,6 +526,79 @@ int orc_int8_attn(const int8_t* q, const int64_t* qs, const int8_t* k, const int
 }
 
 // ---------------------------------------------------------------------------------
+// O6f.  FP8 attention: the quantized attention flow of Sec. 2.2.2 with E4M3 as the 8-bit format
+// (Sec. 2.1).  The same operands, strides, masks and output scales as O6; q, k, v hold E4M3 bytes.
+// Per (batch, head), query i, visible keys k:
+//   a[k]  = float(sum_e q[i][e] k[k][e]) * d~        every product exact, the sum in fp64, rounded once
+//   p     = softmax(a) in fp64
+//   P_f8  = e4m3(float(p) / S_p)                     round to nearest even, saturating at 448; probabilities
+//           are non-negative, so the codes use the positive half of the format and S_p = 1/448 gives p = 1
+//           the largest code
+//   acc[e] = sum_k P_f8[k] v[k][e]                   exact products, fp64 sum, rounded once to fp32
+//   E4M3 out: e4m3(acc[e] * c[j]), c[j] = S_p S_v / S_attn[j];   16-bit / fp32 out: acc[e] * c[0]
+// A query with no visible key outputs 0.  p_dump (optional) receives the codes [B,H,Sq,Skv].
+// ---------------------------------------------------------------------------------
+int orc_fp8_attn(const uint8_t* q, const int64_t* qs, const uint8_t* k, const int64_t* ks,
+                 const uint8_t* v, const int64_t* vs,
+                 int64_t B, int64_t H, int64_t Sq, int64_t Skv, int64_t Dh,
+                 float qk_scale, float p_scale, const float* out_col_scale, int out_scale_is_scalar,
+                 int mask, const int32_t* kv_len,
+                 void* out, int out_dt, int64_t ldo, uint8_t* p_dump) {
+    if (!out_col_scale) return -1;
+    if (mask == ORC_MASK_PADDING && !kv_len) return -1;
+    if (out_dt != ORC_F8 && !out_scale_is_scalar) return -1;
+    float lut[256];
+    for (int c = 0; c < 256; ++c) lut[c] = orc_e4m3_to_f32((uint8_t)c);
+#pragma omp parallel for schedule(dynamic) collapse(2)
+    for (int64_t b = 0; b < B; ++b)
+        for (int64_t h = 0; h < H; ++h) {
+            const int64_t len = kv_len ? std::min<int64_t>(kv_len[b], Skv) : Skv;
+            std::vector<float> a(Skv);
+            std::vector<double> p(Skv);
+            std::vector<uint8_t> codes(Skv);
+            for (int64_t i = 0; i < Sq; ++i) {
+                int64_t last = len - 1;
+                if (mask == ORC_MASK_CAUSAL) last = std::min<int64_t>(last, i + (len - Sq));
+                const int64_t nvis = last + 1;
+                const uint8_t* qi = q + b * qs[0] + i * qs[1] + h * qs[2];
+                for (int64_t kk = 0; kk < nvis; ++kk) {
+                    const uint8_t* kr = k + b * ks[0] + kk * ks[1] + h * ks[2];
+                    double acc = 0.0;
+                    for (int64_t e = 0; e < Dh; ++e) acc += (double)lut[qi[e * qs[3]]] * (double)lut[kr[e * ks[3]]];
+                    volatile float t = (float)acc * qk_scale;
+                    a[kk] = t;
+                }
+                for (int64_t kk = 0; kk < Skv; ++kk) codes[kk] = 0;
+                if (nvis > 0) {
+                    double m = a[0];
+                    for (int64_t kk = 1; kk < nvis; ++kk) m = std::max(m, (double)a[kk]);
+                    double l = 0.0;
+                    for (int64_t kk = 0; kk < nvis; ++kk) { p[kk] = std::exp((double)a[kk] - m); l += p[kk]; }
+                    for (int64_t kk = 0; kk < nvis; ++kk) {
+                        volatile float pf = (float)(p[kk] / l);
+                        volatile float qf = pf / p_scale;
+                        codes[kk] = orc_f32_to_e4m3(qf);
+                    }
+                }
+                if (p_dump)
+                    for (int64_t kk = 0; kk < Skv; ++kk)
+                        p_dump[((b * H + h) * Sq + i) * Skv + kk] = codes[kk];
+                for (int64_t e = 0; e < Dh; ++e) {
+                    double acc = 0.0;
+                    for (int64_t kk = 0; kk < nvis; ++kk)
+                        acc += (double)lut[codes[kk]] * (double)lut[v[b * vs[0] + kk * vs[1] + h * vs[2] + e * vs[3]]];
+                    const int64_t j = h * Dh + e, o = (b * Sq + i) * ldo + j;
+                    const float c = out_scale_is_scalar ? out_col_scale[0] : out_col_scale[j];
+                    volatile float y = (float)acc * c;
+                    if (out_dt == ORC_F8) ((uint8_t*)out)[o] = orc_f32_to_e4m3(y);
+                    else store_hp(out, out_dt, o, y);
+                }
+            }
+        }
+    return 0;
+}
+
+// ---------------------------------------------------------------------------------
 // O6b.  INT8 attention with an ONLINE Softmax^quant -- a variant, not the equation of Sec. 2.2.2:
 // the probabilities are quantized BEFORE they are normalised, block by block, against the running row
 // maximum, so one sweep over the keys suffices and the largest weight of a row always has code 255.

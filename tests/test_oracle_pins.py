@@ -570,6 +570,106 @@ def test_attention_strided_views_and_offset_identity():
     assert np.array_equal(Pi @ V, (Pi - 128) @ V + 128 * V.sum(axis=2, keepdims=True))
 
 
+def _f8(x):
+    """torch's own E4M3 rounding (independent of the oracle's codec), as bytes."""
+    return torch.from_numpy(np.ascontiguousarray(x, np.float32)).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+
+
+def _f8_dec(c):
+    return torch.from_numpy(np.ascontiguousarray(c, np.uint8)).view(torch.float8_e4m3fn).float().numpy()
+
+
+def test_fp8_attention_closed_forms():
+    """Sec. 2.2.2 with E4M3 codes: one visible key -> code 448 -> the V row itself; equal scores over n = 2^j keys
+    -> every code 448 / n exactly -> the mean of the V rows; masks by truncation."""
+    B, S, H, Dh = 1, 8, 2, 16
+    g = synth.rng(70)
+    q = _f8(g.standard_normal((B, S, H, Dh)) * 2)
+    k = _f8(g.standard_normal((B, S, H, Dh)) * 2)
+    v = _f8(g.integers(-8, 9, (B, S, H, Dh)).astype(np.float32))          # small integers: sums are exact
+    sp = np.float32(1.0 / 448.0)
+    vf = _f8_dec(v)
+    # causal, zero queries: query i averages the first i + 1 rows of V; 448 / n is a code for n = 1, 2, 4, 8
+    out, P = O.fp8_attn(np.zeros_like(q), k, v, qk_scale=0.05, p_scale=float(sp), out_col_scale=np.float32([sp]),
+                        out_scale_is_scalar=True, mask=O.MASK_CAUSAL, out_dt=O.F32, dump_p=True)
+    for i in (0, 1, 3, 7):
+        n = i + 1
+        assert (_f8_dec(P[0, :, i, :n]) == 448.0 / n).all() and (P[0, :, i, n:] == 0).all()
+        for h in range(H):
+            acc = (448.0 / n * vf[0, :n, h, :].astype(np.float64).sum(axis=0)).astype(np.float32)     # exact
+            np.testing.assert_array_equal(out[i, h * Dh:(h + 1) * Dh], acc * sp)                       # ~ the mean (S_p is not 2^-j)
+            np.testing.assert_allclose(out[i, h * Dh:(h + 1) * Dh], vf[0, :n, h, :].mean(axis=0), rtol=2e-7, atol=0)
+    # n = 3: 448 / 3 = 149.33 rounds to the code 144 (step 16 between 128 and 256)
+    assert (_f8_dec(P[0, :, 2, :3]) == 144.0).all()
+    # a dominant score: code 448 at the argmax, 0 elsewhere (exp(-huge) / S_p underflows the smallest subnormal 2^-9)
+    qd = np.zeros((B, S, H, Dh), np.float32); kd = np.zeros((B, S, H, Dh), np.float32)
+    qd[..., 0] = 16.0; kd[0, 5, :, 0] = 16.0
+    out, P = O.fp8_attn(_f8(qd), _f8(kd), v, qk_scale=1.0, p_scale=float(sp), out_col_scale=np.float32([sp]),
+                        out_scale_is_scalar=True, out_dt=O.F32, dump_p=True)
+    assert (_f8_dec(P[..., 5]) == 448.0).all() and np.count_nonzero(P) == H * S
+    np.testing.assert_array_equal(out[:, :Dh], np.repeat((448.0 * vf[0, 5:6, 0, :]).astype(np.float32) * sp, S, axis=0))
+    # padding: kv_len = 0 -> zeros; E4M3 output with per-column scales = torch's rounding of acc * c[j]
+    cs = g.uniform(0.5, 2.0, H * Dh).astype(np.float32) * sp
+    o8 = O.fp8_attn(q, k, v, qk_scale=0.05, p_scale=float(sp), out_col_scale=cs, mask=O.MASK_PADDING, kv_len=np.int32([0]))
+    assert not o8.any()
+    o8, P = O.fp8_attn(q, k, v, qk_scale=0.05, p_scale=float(sp), out_col_scale=cs, dump_p=True)
+    acc = np.einsum("bhik,bkhe->bihe", _f8_dec(P).astype(np.float64), vf.astype(np.float64)).reshape(B * S, H * Dh)
+    np.testing.assert_array_equal(o8, _f8(acc.astype(np.float32) * cs[None, :]))
+
+
+@pytest.mark.parametrize("mask", [O.MASK_NONE, O.MASK_PADDING, O.MASK_CAUSAL])
+def test_fp8_attention_against_scipy_softmax_and_torch_rounding(mask):
+    """Every step re-done with numpy / scipy / torch: decoded operands, fp64 scores rounded once, scipy softmax,
+    torch's E4M3 rounding of p / S_p, fp64 PV rounded once, torch's rounding of the scaled output."""
+    B, Sq, Skv, H, Dh = 3, 9, 9, 2, 32
+    g = synth.rng(71)
+    q = _f8(g.standard_normal((B, Sq, H, Dh)) * 3); k = _f8(g.standard_normal((B, Skv, H, Dh)) * 3)
+    v = _f8(g.standard_normal((B, Skv, H, Dh)) * 5)
+    kv_len = np.int32([9, 5, 0]) if mask == O.MASK_PADDING else (np.int32([9, 6, 3]) if mask == O.MASK_CAUSAL else None)
+    d_t, sp = np.float32(0.02), np.float32(1.0 / 448.0)
+    cs = g.uniform(0.5, 2.0, H * Dh).astype(np.float32) * sp * np.float32(20.0)
+    out, P = O.fp8_attn(q, k, v, qk_scale=float(d_t), p_scale=float(sp), out_col_scale=cs, mask=mask, kv_len=kv_len, dump_p=True)
+    qf, kf, vf = (_f8_dec(t).astype(np.float64) for t in (q, k, v))
+    flips = 0
+    for b in range(B):
+        L = Skv if kv_len is None else int(kv_len[b])
+        for h in range(H):
+            a = (qf[b, :, h] @ kf[b, :, h].T).astype(np.float32) * d_t
+            for i in range(Sq):
+                n = max(L if mask != O.MASK_CAUSAL else min(L, i + (L - Sq) + 1), 0)
+                codes = np.zeros(Skv, np.uint8)
+                if n > 0:
+                    p = scipy.special.softmax(a[i, :n].astype(np.float64)).astype(np.float32)
+                    codes[:n] = _f8(p / sp)
+                # scipy's softmax and the oracle's may differ in the last bit of p next to a rounding boundary
+                flips += np.count_nonzero(P[b, h, i] != codes)
+                pv = (_f8_dec(P[b, h, i]).astype(np.float64) @ vf[b, :, h]).astype(np.float32)
+                np.testing.assert_array_equal(out[b * Sq + i, h * Dh:(h + 1) * Dh], _f8(pv * cs[h * Dh:(h + 1) * Dh]))
+    assert flips <= 2
+    if mask == O.MASK_PADDING:
+        assert not out[2 * Sq:].any()
+
+
+def test_fp8_attention_accuracy_and_views():
+    """Dequantized, the FP8 flow follows the exact softmax attention of the decoded operands within the E4M3
+    rounding of P and of the output (3 mantissa bits: relative step 2^-3 .. 2^-4); strided views of a fused QKV
+    buffer give the same bytes as contiguous copies."""
+    B, S, H, Dh = 2, 40, 2, 64
+    g = synth.rng(72)
+    qkv = _f8(g.standard_normal((B * S, 3 * H * Dh)) * 2)
+    qv, kv, vv = (OL._heads(qkv, B, S, H, Dh, i) for i in range(3))
+    sp = np.float32(1.0 / 448.0)
+    kw = dict(qk_scale=0.03, p_scale=float(sp), out_col_scale=np.float32([sp]), out_scale_is_scalar=True, out_dt=O.F32)
+    a = O.fp8_attn(qv, kv, vv, **kw)
+    assert np.array_equal(a, O.fp8_attn(qv.copy(), kv.copy(), vv.copy(), **kw))
+    qf, kf, vf = (_f8_dec(t).astype(np.float64) for t in (qv, kv, vv))
+    ref = OL.fp64_attention(qf.reshape(B * S, -1) * 0.03 * np.sqrt(Dh), kf.reshape(B * S, -1), vf.reshape(B * S, -1),
+                            B, S, S, H, Dh, O.MASK_NONE, None)
+    err = a.astype(np.float64) - ref
+    snr = 10 * np.log10((ref ** 2).sum() / (err ** 2).sum())
+    assert 25.0 < snr < 45.0, snr          # E4M3 rounding of P: relative error <= 2^-4 per term, averaged over the keys
+
+
 def test_attention_online_closed_forms():
     """The online Softmax^quant variant (codes against the running block maximum, normalised at the end):
     closed forms that a dropped rescale, a wrong exponent sign or a wrong block boundary would break."""
