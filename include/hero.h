@@ -237,6 +237,30 @@ hero_status hero_int8_attn_online(const int8_t* q, const int64_t q_strides[4],
                                   int out_scale_is_scalar, hero_mask mask, const int32_t* kv_len,
                                   void* out, hero_dtype out_dt, int64_t ldo, void* stream);
 
+/* FP8 attention: the quantized attention flow of Sec. 2.2.2 with E4M3 as the 8-bit format (Sec. 2.1
+ * allows INT8 or FP8).  q, k, v hold OCP E4M3 bytes (device; the same shapes, element strides and
+ * views as hero_int8_attn).  Per (b, h), query i, visible keys k:
+ *   a[k]  = (sum_e q[i][e] k[k][e]) * qk_scale          fp32 accumulation on the matrix cores
+ *   p     = softmax(a)                                   fp32, normalised BEFORE it is quantized
+ *   P_f8  = e4m3(min(p / p_scale, 448))                  non-negative E4M3 codes; p_scale = 1/448 maps
+ *                                                        p = 1 to the largest code
+ *   acc[e] = sum_k P_f8[k] v[k][e]                       fp32 accumulation on the matrix cores
+ *   out_dt HERO_F8E4M3: e4m3(sat(acc[e] * out_col_scale[h*Dh+e])), out_col_scale = S_p S_v / S_attn[j]
+ *   out_dt HERO_F16 / HERO_BF16: acc[e] * out_col_scale[0]  (out_scale_is_scalar must be 1)
+ * Masks, kv_len, constraints (Dh 64 or 128, strides multiples of 16, 16-byte aligned bases, ldo) and
+ * errors as for hero_int8_attn; the 8-bit output type is HERO_F8E4M3 (HERO_I8 -> HERO_ERR_UNSUPPORTED).
+ * A query with no visible key outputs 0.  Any Sq runs through the same kernel (a one-query decode
+ * call is served but not specialised).  The matrix cores add the 8 products of a lane group with 13
+ * fractional bits below the largest of them, so results agree with an exactly accumulated reference
+ * up to an adjacent E4M3 code on a small fraction of the outputs, not bit for bit. */
+hero_status hero_fp8_attn(const void* q, const int64_t q_strides[4],
+                          const void* k, const int64_t k_strides[4],
+                          const void* v, const int64_t v_strides[4],
+                          int64_t B, int64_t H, int64_t Sq, int64_t Skv, int64_t Dh,
+                          float qk_scale, float p_scale, const float* out_col_scale, int out_scale_is_scalar,
+                          hero_mask mask, const int32_t* kv_len,
+                          void* out, hero_dtype out_dt, int64_t ldo, void* stream);
+
 /* ---- one transformer layer (Sec. 2.2.2 + 2.2.3 chained, Sec. 2.3 / Table 1 modes) ---- */
 
 typedef enum { HERO_ARCH_POST_LN = 0, HERO_ARCH_PRE_LN = 1 } hero_arch;

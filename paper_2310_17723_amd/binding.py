@@ -55,6 +55,8 @@ SYMBOLS = {
                                 vp, C.c_size_t, vp]),
     "hero_int8_attn": (i32, [vp, C.POINTER(i64), vp, C.POINTER(i64), vp, C.POINTER(i64), i64, i64, i64, i64, i64,
                              f32, f32, vp, i32, i32, vp, vp, i32, i64, vp]),
+    "hero_fp8_attn": (i32, [vp, C.POINTER(i64), vp, C.POINTER(i64), vp, C.POINTER(i64), i64, i64, i64, i64, i64,
+                            f32, f32, vp, i32, i32, vp, vp, i32, i64, vp]),
     "hero_int8_attn_online": (i32, [vp, C.POINTER(i64), vp, C.POINTER(i64), vp, C.POINTER(i64), i64, i64, i64, i64, i64,
                                     vp, f32, vp, i32, i32, vp, vp, i32, i64, vp]),
     "hero_probe_mfma_i8": (i32, [i32, i64, vp, C.POINTER(C.c_double), vp]),
@@ -220,6 +222,23 @@ class Hero:
                                      B, H, Sq, Skv, Dh, float(qk_scale), float(p_scale), _ptr(out_col_scale),
                                      int(bool(out_scale_is_scalar)), int(mask), _ptr(kv_len), _ptr(out),
                                      _DT[out.dtype], out.stride(0), _stream(stream))
+        self._check(st)
+        return out
+
+    def hero_fp8_attn(self, q, k, v, qk_scale, p_scale, out_col_scale, out_scale_is_scalar=False,
+                      mask=MASK_NONE, kv_len=None, out_dtype=torch.float8_e4m3fn, out=None, stream=None):
+        """The FP8 variant: q [B,Sq,H,Dh], k/v [B,Skv,H,Dh] hold E4M3 bytes (torch.float8_e4m3fn or uint8 storage).
+        out_dtype torch.float8_e4m3fn (per-column scales) or float16 / bfloat16 (scalar scale)."""
+        B, Sq, H, Dh = q.shape
+        Skv = k.shape[1]
+        assert q.element_size() == 1 and k.element_size() == 1 and v.element_size() == 1
+        if out is None:
+            out = torch.empty((B * Sq, H * Dh), dtype=out_dtype, device=q.device)
+        odt = F8E4M3 if out.element_size() == 1 else _DT[out.dtype]
+        st = self.lib.hero_fp8_attn(_ptr(q), _strides4(q), _ptr(k), _strides4(k), _ptr(v), _strides4(v),
+                                    B, H, Sq, Skv, Dh, float(qk_scale), float(p_scale), _ptr(out_col_scale),
+                                    int(bool(out_scale_is_scalar)), int(mask), _ptr(kv_len), _ptr(out),
+                                    odt, out.stride(0), _stream(stream))
         self._check(st)
         return out
 

@@ -98,6 +98,14 @@ __device__ __forceinline__ uint32_t fp8x4_sat(float y0, float y1, float y2, floa
     w = __builtin_amdgcn_cvt_pk_fp8_f32(__builtin_amdgcn_fmed3f(y2, -448.0f, 448.0f), __builtin_amdgcn_fmed3f(y3, -448.0f, 448.0f), w, true);
     return (uint32_t)w;
 }
+// E4M3 x E4M3 at the full matrix rate: v_mfma_f32_32x32x64_f8f6f4, K = 64 per instruction, each lane half carries
+// 32 bytes of its row (here: two 16-byte fragments side by side; any K grouping shared by both operands is the
+// same contraction).  Unit scales.
+__device__ __forceinline__ v16f mfma_wide_f8(v4i a_lo, v4i a_hi, v4i b_lo, v4i b_hi, v16f c) {
+    const v8i a = {a_lo[0], a_lo[1], a_lo[2], a_lo[3], a_hi[0], a_hi[1], a_hi[2], a_hi[3]};
+    const v8i b = {b_lo[0], b_lo[1], b_lo[2], b_lo[3], b_hi[0], b_hi[1], b_hi[2], b_hi[3]};
+    return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 0, 0, 0, 0, 0, 0);
+}
 // erf-form GELU in fp32:  GELU(x) = x Phi(x) = max(x,0) - |x| Phi(-|x|).
 // Phi(-z) = 2^P(z) with P a degree-6 polynomial: a weighted least-squares fit of log2 Phi(-z) on
 // [0,6] (beyond 6, Phi(-z) < 1e-9 and z is clamped).  Evaluated in fp32 the absolute error of

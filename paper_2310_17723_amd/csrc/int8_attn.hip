@@ -42,8 +42,15 @@ struct AttnArgs {
     void* out; int64_t ldo;
 };
 
-template <int DH, int ODT, bool ONLINE = false>
+// FMT = HERO_F8E4M3: the same flow with E4M3 codes (Sec. 2.1): q, k, v are E4M3 bytes, the scores and the PV sums
+// are fp32 accumulators of v_mfma_f32_32x32x64_f8f6f4, the probabilities are quantized to non-negative E4M3 codes
+// (saturating at 448 = p / S_p for p = 1 with S_p = 1/448), signed operands need no offset and no column sums.
+// Staging, masks, tile order and the two-pass structure are those of the INT8 kernel.
+template <int DH, int ODT, bool ONLINE = false, int FMT = HERO_I8>
 __global__ __launch_bounds__(256, ONLINE ? (DH == 64 ? 3 : 2) : (DH == 64 ? 4 : 3)) void int8_attn_kernel(AttnArgs a) {
+    constexpr bool F8 = FMT == HERO_F8E4M3;
+    static_assert(!(F8 && ONLINE), "the online variant is INT8 only");
+    using SACC = typename std::conditional<F8, v16f, v16i>::type;     // score / output accumulators
     constexpr int KLD = DH + 16;        // sK row stride (bytes)
     constexpr int VLD = BKV + 16;       // sVt row stride (bytes)
     constexpr int DS = DH / 32;         // 32-wide steps over the head dimension
@@ -182,13 +189,22 @@ __global__ __launch_bounds__(256, ONLINE ? (DH == 64 ? 3 : 2) : (DH == 64 ? 4 : 
     };
     // S^T for the 32-key step s of the staged tile
     auto scores = [&](int buf, int s) {
-        v16i acc;
+        SACC acc;
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[r] = 0;
+        if constexpr (F8) {
 #pragma unroll
-        for (int d = 0; d < DS; ++d) {
-            v4i kf = *reinterpret_cast<const v4i*>(&sK[buf][(s * 32 + ql) * KLD + d * 32 + hh * 16]);
-            acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(kf, qf[d], acc, 0, 0, 0);
+            for (int d = 0; d < DS; d += 2) {
+                const v4i k0 = *reinterpret_cast<const v4i*>(&sK[buf][(s * 32 + ql) * KLD + d * 32 + hh * 16]);
+                const v4i k1 = *reinterpret_cast<const v4i*>(&sK[buf][(s * 32 + ql) * KLD + (d + 1) * 32 + hh * 16]);
+                acc = mfma_wide_f8(k0, k1, qf[d], qf[d + 1], acc);
+            }
+        } else {
+#pragma unroll
+            for (int d = 0; d < DS; ++d) {
+                v4i kf = *reinterpret_cast<const v4i*>(&sK[buf][(s * 32 + ql) * KLD + d * 32 + hh * 16]);
+                acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(kf, qf[d], acc, 0, 0, 0);
+            }
         }
         return acc;
     };
@@ -321,6 +337,7 @@ __global__ __launch_bounds__(256, ONLINE ? (DH == 64 ? 3 : 2) : (DH == 64 ? 4 : 
 
     // ---- pass 1: row max and row sum ------------------------------------------------------------
     float m2 = -INFINITY, l = 0.0f;           // running max (log2 domain) and sum of 2^(a2 - m2), this lane's keys
+    constexpr float FMASKED = -3.0e38f;       // E4M3 scores are floats: the mask value of that variant
     if (ntiles > 0) { load_k(0); store_k(0); }
     __syncthreads();
     for (int tile = 0; tile < ntiles; ++tile) {
@@ -330,18 +347,21 @@ __global__ __launch_bounds__(256, ONLINE ? (DH == 64 ? 3 : 2) : (DH == 64 ? 4 : 
         auto pass1_tile = [&](auto EDGE) {
 #pragma unroll
             for (int s = 0; s < BKV / 32; ++s) {
-                v16i acc = scores(buf, s);
+                SACC acc = scores(buf, s);
                 if constexpr (decltype(EDGE)::value) {
                     const int lim = nvis - (tile * BKV + s * 32 + hh * 4);      // key visible iff 8g + t < lim
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) acc[r] = ((r >> 2) * 8 + (r & 3)) < lim ? acc[r] : MASKED;
+                    for (int r = 0; r < 16; ++r) {
+                        if constexpr (F8) acc[r] = ((r >> 2) * 8 + (r & 3)) < lim ? acc[r] : FMASKED;
+                        else acc[r] = ((r >> 2) * 8 + (r & 3)) < lim ? acc[r] : MASKED;
+                    }
                 }
-                int imax = acc[0];
+                auto smax = acc[0];
 #pragma unroll
-                for (int r = 1; r < 16; ++r) imax = max(imax, acc[r]);
-                imax = max(imax, __shfl_xor(imax, 32));
-                if (imax > MASKED) {                         // same decision in both lanes of a query
-                    const float mn = fmaxf(m2, (float)imax * c2);
+                for (int r = 1; r < 16; ++r) smax = max(smax, acc[r]);
+                smax = max(smax, __shfl_xor(smax, 32));
+                if (F8 ? (float)smax > FMASKED : (int)smax > MASKED) {          // same decision in both lanes of a query
+                    const float mn = fmaxf(m2, (float)smax * c2);
                     float sum = 0.0f;
 #pragma unroll
                     for (int r = 0; r < 16; ++r) sum += __builtin_amdgcn_exp2f(fmaf((float)acc[r], c2, -mn));
@@ -359,7 +379,7 @@ __global__ __launch_bounds__(256, ONLINE ? (DH == 64 ? 3 : 2) : (DH == 64 ? 4 : 
     const float off = l > 0.0f ? -m2 - __log2f(l * a.p_scale) : -INFINITY;
 
     // ---- pass 2: codes and PV --------------------------------------------------------------------
-    v16i o[DS];
+    SACC o[DS];
     int csum[DS];                                         // this wave's share of colsum(V): channel 32c + ql, keys of half hh
 #pragma unroll
     for (int c = 0; c < DS; ++c) {
@@ -374,6 +394,33 @@ __global__ __launch_bounds__(256, ONLINE ? (DH == 64 ? 3 : 2) : (DH == 64 ? 4 : 
         if (tile + 1 < ntiles) { load_k(tile + 1); load_v(tile + 1); }
         const bool edge = (tile + 1) * BKV > nvis_min;
         auto pass2_tile = [&](auto EDGE) {
+            if constexpr (F8) {
+                // codes of the whole 64-key tile first (two 32-key steps), then ONE K = 64 matrix instruction per
+                // 32 channels: e4m3(min(2^(acc*c2 + off), 448)), two codes per conversion instruction
+                v4i pf[BKV / 32];
+#pragma unroll
+                for (int s = 0; s < BKV / 32; ++s) {
+                    const v16f acc = scores(buf, s);
+                    const int lim = nvis - (tile * BKV + s * 32 + hh * 4);
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        float e[4];
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) {
+                            e[t] = fminf(__builtin_amdgcn_exp2f(fmaf(acc[4 * g + t], c2, off)), 448.0f);
+                            if constexpr (decltype(EDGE)::value) e[t] = (g * 8 + t) < lim ? e[t] : 0.0f;
+                        }
+                        int w = __builtin_amdgcn_cvt_pk_fp8_f32(e[0], e[1], 0, false);
+                        pf[s][g] = __builtin_amdgcn_cvt_pk_fp8_f32(e[2], e[3], w, true);
+                    }
+                }
+#pragma unroll
+                for (int c = 0; c < DS; ++c) {
+                    const v4i v0 = *reinterpret_cast<const v4i*>(&sVt[buf][(c * 32 + ql) * VLD + hh * 16]);
+                    const v4i v1 = *reinterpret_cast<const v4i*>(&sVt[buf][(c * 32 + ql) * VLD + 32 + hh * 16]);
+                    o[c] = mfma_wide_f8(v0, v1, pf[0], pf[1], o[c]);
+                }
+            } else {
 #pragma unroll
             for (int s = 0; s < BKV / 32; ++s) {
                 v16i acc = scores(buf, s);
@@ -400,6 +447,7 @@ __global__ __launch_bounds__(256, ONLINE ? (DH == 64 ? 3 : 2) : (DH == 64 ? 4 : 
                     }
                 }
             }
+            }
         };
         if (edge) pass2_tile(std::true_type{}); else pass2_tile(std::false_type{});
         if (tile + 1 < ntiles) { store_k(buf ^ 1); store_v(buf ^ 1); }
@@ -409,11 +457,13 @@ __global__ __launch_bounds__(256, ONLINE ? (DH == 64 ? 3 : 2) : (DH == 64 ? 4 : 
     // ---- colsum(V) of the block: every wave adds its share per channel (the loop's last barrier has
     // released the K buffers, which now hold the sums)
     int* const colsum = reinterpret_cast<int*>(&sK[0][0]);
-    for (int c = tid; c < DH; c += 256) colsum[c] = 0;
-    __syncthreads();
+    if constexpr (!F8) {
+        for (int c = tid; c < DH; c += 256) colsum[c] = 0;
+        __syncthreads();
 #pragma unroll
-    for (int c = 0; c < DS; ++c) atomicAdd(&colsum[c * 32 + ql], csum[c]);
-    __syncthreads();
+        for (int c = 0; c < DS; ++c) atomicAdd(&colsum[c * 32 + ql], csum[c]);
+        __syncthreads();
+    }
 
     // ---- output: lane holds query ql, channels 32c + 8g + 4hh + t -----------------------------------
     if (qi >= a.Sq) return;
@@ -426,12 +476,14 @@ __global__ __launch_bounds__(256, ONLINE ? (DH == 64 ? 3 : 2) : (DH == 64 ? 4 : 
             float y[4];
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
-                int val = o[c][4 * g + t] + 128 * colsum[e0 + t];
                 float sc = a.scale_is_scalar ? a.out_col_scale[0] : a.out_col_scale[h * DH + e0 + t];
-                y[t] = (float)val * sc;
+                if constexpr (F8) y[t] = o[c][4 * g + t] * sc;
+                else y[t] = (float)(o[c][4 * g + t] + 128 * colsum[e0 + t]) * sc;
             }
             if (ODT == HERO_I8) {
                 *reinterpret_cast<uint32_t*>((int8_t*)a.out + orow + e0) = quant4_sat(y[0], y[1], y[2], y[3]);
+            } else if (ODT == HERO_F8E4M3) {
+                *reinterpret_cast<uint32_t*>((int8_t*)a.out + orow + e0) = fp8x4_sat(y[0], y[1], y[2], y[3]);
             } else {
                 v2i w = {(int)pack2_hp<ODT>(y[0], y[1]), (int)pack2_hp<ODT>(y[2], y[3])};
                 *reinterpret_cast<v2i*>((uint16_t*)a.out + orow + e0) = w;
@@ -532,15 +584,15 @@ __global__ void zero_rows_kernel(int8_t* out, int64_t bytes) {
     if (i < bytes) *reinterpret_cast<v4i*>(out + i) = v4i{0, 0, 0, 0};
 }
 
-template <int DH, bool ONLINE = false>
+template <int DH, bool ONLINE = false, int FMT = HERO_I8>
 hero_status launch(const AttnArgs& a, hero_dtype out_dt, hipStream_t st) {
     constexpr int HG = DH >= 128 ? 1 : 128 / DH;               // heads per workgroup group (see the kernel)
     const int64_t nqb = (a.Sq + BQ - 1) / BQ, hgroups = ((int64_t)a.B * a.H + HG - 1) / HG, rounds = (hgroups + 7) / 8;
     if (rounds * 8 * HG * nqb > 0x7fffffffLL) return HERO_ERR_SHAPE;
     dim3 grid((unsigned)(rounds * 8 * HG * nqb)), block(256);
-    if (out_dt == HERO_I8) hipLaunchKernelGGL((int8_attn_kernel<DH, HERO_I8, ONLINE>), grid, block, 0, st, a);
-    else if (out_dt == HERO_BF16) hipLaunchKernelGGL((int8_attn_kernel<DH, HERO_BF16, ONLINE>), grid, block, 0, st, a);
-    else hipLaunchKernelGGL((int8_attn_kernel<DH, HERO_F16, ONLINE>), grid, block, 0, st, a);
+    if (out_dt == HERO_BF16) hipLaunchKernelGGL((int8_attn_kernel<DH, HERO_BF16, ONLINE, FMT>), grid, block, 0, st, a);
+    else if (out_dt == HERO_F16) hipLaunchKernelGGL((int8_attn_kernel<DH, HERO_F16, ONLINE, FMT>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((int8_attn_kernel<DH, FMT, ONLINE, FMT>), grid, block, 0, st, a);      // 8-bit output in the operands' format
     return hero_launch_status();
 }
 
@@ -549,20 +601,21 @@ hero_status attn_entry(const int8_t* q, const int64_t q_strides[4],
                        const int8_t* k, const int64_t k_strides[4],
                        const int8_t* v, const int64_t v_strides[4],
                        int64_t B, int64_t H, int64_t Sq, int64_t Skv, int64_t Dh,
-                       float qk_scale, const float* qk_scale_h, bool online,
+                       float qk_scale, const float* qk_scale_h, bool online, bool fp8,
                        float p_scale, const float* out_col_scale, int out_scale_is_scalar,
                        hero_mask mask, const int32_t* kv_len,
                        void* out, hero_dtype out_dt, int64_t ldo, void* stream) {
     if (B < 0 || H < 0 || Sq < 0 || Skv < 0) return HERO_ERR_SHAPE;
     if (Dh != 64 && Dh != 128) return HERO_ERR_UNSUPPORTED;
-    if (out_dt != HERO_I8 && out_dt != HERO_BF16 && out_dt != HERO_F16) return HERO_ERR_UNSUPPORTED;
+    const hero_dtype dt8 = fp8 ? HERO_F8E4M3 : HERO_I8;                  // the 8-bit output format is the operands'
+    if (out_dt != dt8 && out_dt != HERO_BF16 && out_dt != HERO_F16) return HERO_ERR_UNSUPPORTED;
     if (mask != HERO_MASK_NONE && mask != HERO_MASK_PADDING && mask != HERO_MASK_CAUSAL) return HERO_ERR_UNSUPPORTED;
     if (B == 0 || H == 0 || Sq == 0) return HERO_OK;
     if (!out || !out_col_scale || !q_strides || !k_strides || !v_strides) return HERO_ERR_NULL;
     if (Skv > 0 && (!q || !k || !v)) return HERO_ERR_NULL;
     if (mask == HERO_MASK_PADDING && !kv_len) return HERO_ERR_NULL;
     if (online && !qk_scale_h) return HERO_ERR_NULL;
-    if (out_dt != HERO_I8 && !out_scale_is_scalar) return HERO_ERR_UNSUPPORTED;
+    if (out_dt != dt8 && !out_scale_is_scalar) return HERO_ERR_UNSUPPORTED;
     if (!(p_scale > 0.0f)) return HERO_ERR_SHAPE;
     if (ldo < H * Dh) return HERO_ERR_SHAPE;
     if (B > 65535 || H > 65535 || Sq > 0x7fffffffLL || Skv > 0x7fffffffLL) return HERO_ERR_SHAPE;
@@ -571,7 +624,7 @@ hero_status attn_entry(const int8_t* q, const int64_t q_strides[4],
         if (ss[t][3] != 1) return HERO_ERR_UNSUPPORTED;
         if (ss[t][0] % 16 || ss[t][1] % 16 || ss[t][2] % 16) return HERO_ERR_ALIGN;
     }
-    const int64_t o_elem = out_dt == HERO_I8 ? 1 : 2;
+    const int64_t o_elem = out_dt == dt8 ? 1 : 2;
     if ((ldo * o_elem) % 16 != 0 || !hero_aligned16(out) || !hero_aligned16(q) || !hero_aligned16(k) || !hero_aligned16(v))
         return HERO_ERR_ALIGN;
     AttnArgs a;
@@ -590,6 +643,7 @@ hero_status attn_entry(const int8_t* q, const int64_t q_strides[4],
         hipLaunchKernelGGL(zero_rows_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (int8_t*)out, bytes);
         return hero_launch_status();
     }
+    if (fp8) return Dh == 64 ? launch<64, false, HERO_F8E4M3>(a, out_dt, st) : launch<128, false, HERO_F8E4M3>(a, out_dt, st);
     if (online) return Dh == 64 ? launch<64, true>(a, out_dt, st) : launch<128, true>(a, out_dt, st);
     if (Sq == 1 && Skv <= DEC_MAX_KEYS) {          // decode: the cache-streaming kernel
         dim3 grid((unsigned)H, (unsigned)B), block(256);
@@ -615,7 +669,7 @@ extern "C" hero_status hero_int8_attn(const int8_t* q, const int64_t q_strides[4
                                       float qk_scale, float p_scale, const float* out_col_scale, int out_scale_is_scalar,
                                       hero_mask mask, const int32_t* kv_len,
                                       void* out, hero_dtype out_dt, int64_t ldo, void* stream) {
-    return attn_entry(q, q_strides, k, k_strides, v, v_strides, B, H, Sq, Skv, Dh, qk_scale, nullptr, false, p_scale,
+    return attn_entry(q, q_strides, k, k_strides, v, v_strides, B, H, Sq, Skv, Dh, qk_scale, nullptr, false, false, p_scale,
                       out_col_scale, out_scale_is_scalar, mask, kv_len, out, out_dt, ldo, stream);
 }
 
@@ -626,6 +680,17 @@ extern "C" hero_status hero_int8_attn_online(const int8_t* q, const int64_t q_st
                                              const float* qk_scale_h, float p_scale, const float* out_col_scale,
                                              int out_scale_is_scalar, hero_mask mask, const int32_t* kv_len,
                                              void* out, hero_dtype out_dt, int64_t ldo, void* stream) {
-    return attn_entry(q, q_strides, k, k_strides, v, v_strides, B, H, Sq, Skv, Dh, 0.0f, qk_scale_h, true, p_scale,
+    return attn_entry(q, q_strides, k, k_strides, v, v_strides, B, H, Sq, Skv, Dh, 0.0f, qk_scale_h, true, false, p_scale,
                       out_col_scale, out_scale_is_scalar, mask, kv_len, out, out_dt, ldo, stream);
+}
+
+extern "C" hero_status hero_fp8_attn(const void* q, const int64_t q_strides[4],
+                                     const void* k, const int64_t k_strides[4],
+                                     const void* v, const int64_t v_strides[4],
+                                     int64_t B, int64_t H, int64_t Sq, int64_t Skv, int64_t Dh,
+                                     float qk_scale, float p_scale, const float* out_col_scale, int out_scale_is_scalar,
+                                     hero_mask mask, const int32_t* kv_len,
+                                     void* out, hero_dtype out_dt, int64_t ldo, void* stream) {
+    return attn_entry((const int8_t*)q, q_strides, (const int8_t*)k, k_strides, (const int8_t*)v, v_strides, B, H, Sq, Skv, Dh,
+                      qk_scale, nullptr, false, true, p_scale, out_col_scale, out_scale_is_scalar, mask, kv_len, out, out_dt, ldo, stream);
 }

@@ -64,12 +64,6 @@ __device__ __forceinline__ ACC mfma_step(v4i a, v4i b, ACC c) {
         return __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(a1, b1, c, 0, 0, 0);
     }
 }
-// FP8 at the full matrix rate: K = 64 per instruction, each lane half carries 32 bytes of its row.
-__device__ __forceinline__ v16f mfma_wide_f8(v4i a_lo, v4i a_hi, v4i b_lo, v4i b_hi, v16f c) {
-    const v8i a = {a_lo[0], a_lo[1], a_lo[2], a_lo[3], a_hi[0], a_hi[1], a_hi[2], a_hi[3]};
-    const v8i b = {b_lo[0], b_lo[1], b_lo[2], b_lo[3], b_hi[0], b_hi[1], b_hi[2], b_hi[3]};
-    return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 0, 0, 0, 0, 0, 0);   // E4M3 x E4M3, unit scales
-}
 // f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>), in order
 template <int N, int I = 0, typename F>
 __device__ __forceinline__ void static_for(F&& f) {

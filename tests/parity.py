@@ -82,3 +82,35 @@ def assert_fp8_codes(got, ref, decode, what="", max_frac=1e-3, acc_rel=0.0):
     frac = np.count_nonzero(got != ref) / got.size
     assert frac <= max_frac, f"{what}: {frac:.2e} of the codes differ (limit {max_frac:.0e})"
     return frac
+
+
+def assert_fp8_attn_codes(got, ref, decode, what="", max_frac=2e-2, rel_l2=2e-2, flip_rel=0.25):
+    """E4M3 outputs of the FP8 attention.  The probabilities are E4M3 codes themselves (relative step 2^-3 .. 2^-4),
+    and the matrix cores' scores differ from the exactly accumulated ones by ~1e-3 relative, so about one
+    probability in a hundred lands on the neighbouring code; when that happens to a dominant key (p ~ 0.5) the
+    whole output row moves by up to 2^-3 p |v| ~ a quarter of the typical output.  Hence: the decoded outputs
+    agree in relative L2 (the bar of the 16-bit outputs), the codes differ on at most max_frac of the elements,
+    and no element is further away than one output step plus flip_rel x rms(ref)."""
+    g, o = decode(got).astype(np.float64), decode(ref).astype(np.float64)
+    rms = np.sqrt(np.mean(o * o))
+    step = np.maximum(2.0 ** (np.floor(np.log2(np.maximum(np.abs(o), 2.0 ** -6))) - 3), 2.0 ** -9)
+    bad = np.abs(g - o) > step * 1.0001 + flip_rel * rms
+    assert not bad.any(), f"{what}: {np.count_nonzero(bad)} outputs are further away than one step + {flip_rel} rms"
+    l2 = np.sqrt(((g - o) ** 2).sum() / max((o * o).sum(), 1e-30))
+    assert l2 <= rel_l2, f"{what}: relative L2 distance {l2:.2e} (limit {rel_l2:.0e})"
+    frac = np.count_nonzero(got != ref) / got.size
+    assert frac <= max_frac, f"{what}: {frac:.2e} of the codes differ (limit {max_frac:.0e})"
+    return frac
+
+
+def assert_fp8_attn_values(got_f32, ref_f32, what="", rel_l2=2e-2, flip_rel=0.25):
+    """16-bit outputs of the FP8 attention: the same class as assert_fp8_attn_codes without the output grid: relative
+    L2 within rel_l2, every element within flip_rel x rms(ref) (one flipped probability code of a dominant key)
+    plus the 16-bit rounding of its own value."""
+    g, o = got_f32.astype(np.float64), ref_f32.astype(np.float64)
+    rms = np.sqrt(np.mean(o * o))
+    bad = np.abs(g - o) > flip_rel * rms + 2e-2 * np.abs(o)
+    assert not bad.any(), f"{what}: {np.count_nonzero(bad)} outputs are further away than {flip_rel} rms"
+    l2 = np.sqrt(((g - o) ** 2).sum() / max((o * o).sum(), 1e-30))
+    assert l2 <= rel_l2, f"{what}: relative L2 distance {l2:.2e} (limit {rel_l2:.0e})"
+    return l2

@@ -9,7 +9,7 @@ import oracle as O
 from oracle import layer as OL
 from paper_2310_17723_amd import binding as HB
 from paper_2310_17723_amd import synth
-from parity import assert_codes, assert_exact, assert_fp8_codes, assert_scales, dev, rel_err, to_np
+from parity import assert_codes, assert_exact, assert_fp8_attn_codes, assert_fp8_attn_values, assert_fp8_codes, assert_scales, dev, rel_err, to_np
 
 pytestmark = pytest.mark.gpu
 
@@ -565,6 +565,81 @@ def test_fp8_gemm_matches_oracle(hero, M, N, K, tile, monkeypatch):
     assert_fp8_codes(to_np(got), ref, O.e4m3_to_f32, "gelu requant", max_frac=5e-3, acc_rel=1e-3)
     with pytest.raises(HB.HeroError):
         hero.hero_fp8_gemm(dA, dB, dev(rs), dev(cs), epi=HB.EPI_REQUANT, out_dtype=torch.bfloat16)
+
+
+def _fp8_attn_case(seed, B, Sq, Skv, H, Dh):
+    g = synth.rng(seed)
+    mk = lambda s: O.f32_to_e4m3((g.standard_normal(s) * 40).astype(np.float32))     # E4M3 codes of SQ-scaled activations
+    q, k, v = mk((B, Sq, H, Dh)), mk((B, Skv, H, Dh)), mk((B, Skv, H, Dh))
+    qk_scale = float(np.float32(1.5 / (40 * 40 * np.sqrt(Dh))))                       # logits of a few units
+    sp = np.float32(1.0 / 448.0)
+    cs = g.uniform(0.8, 1.2, H * Dh).astype(np.float32) * sp * np.float32(4.0)
+    return q, k, v, qk_scale, float(sp), cs
+
+
+@pytest.mark.parametrize("mask", [O.MASK_NONE, O.MASK_PADDING, O.MASK_CAUSAL])
+@pytest.mark.parametrize("B,Sq,Skv,H,Dh", ATTN_SHAPES)
+def test_fp8_attn_matches_oracle(hero, B, Sq, Skv, H, Dh, mask):
+    """hero_fp8_attn (Sec. 2.2.2 flow with E4M3 codes) against its oracle: E4M3 output with per-column scales in
+    the class derived in parity.assert_fp8_attn_codes, 16-bit outputs in the same class without the output grid."""
+    q, k, v, qk_scale, sp, cs = _fp8_attn_case(2000 + Sq + Dh, B, Sq, Skv, H, Dh)
+    kv_len = None
+    if mask == O.MASK_PADDING:
+        kv_len = np.int32([Skv - 3, 0][:B]) if B == 2 else np.int32([Skv // 2 + 1])
+    if mask == O.MASK_CAUSAL and Sq != Skv:
+        kv_len = np.int32([Skv, Skv - 50][:B])
+    ref = O.fp8_attn(q, k, v, qk_scale=qk_scale, p_scale=sp, out_col_scale=cs, mask=mask, kv_len=kv_len)
+    got = hero.hero_fp8_attn(dev(q), dev(k), dev(v), qk_scale, sp, dev(cs), mask=mask, kv_len=dev(kv_len))
+    assert got.dtype == torch.float8_e4m3fn and np.abs(O.e4m3_to_f32(ref)).max() > 100      # not degenerate
+    assert_fp8_attn_codes(to_np(got.view(torch.uint8)), ref, O.e4m3_to_f32, "X_attn fp8")
+    if mask == O.MASK_PADDING and B == 2:
+        assert not to_np(got.view(torch.uint8))[Sq:].any()               # the batch row without keys
+    sc = np.float32([cs[0]])
+    for odt, tdt, cvt in ((O.BF16, torch.bfloat16, O.bf16_to_f32), (O.F16, torch.float16, O.f16_to_f32)):
+        refb = O.fp8_attn(q, k, v, qk_scale=qk_scale, p_scale=sp, out_col_scale=sc, out_scale_is_scalar=True,
+                          mask=mask, kv_len=kv_len, out_dt=odt)
+        gotb = hero.hero_fp8_attn(dev(q), dev(k), dev(v), qk_scale, sp, dev(sc), out_scale_is_scalar=True,
+                                  mask=mask, kv_len=dev(kv_len), out_dtype=tdt)
+        assert_fp8_attn_values(cvt(to_np(gotb)), cvt(refb), "16-bit output")
+
+
+def test_fp8_attn_views_cache_one_query_and_errors(hero):
+    """Operands as views into a fused [T,3d] buffer and a [B,H,Smax,Dh] cache with one query per sequence; no keys;
+    argument errors (INT8 output type, per-column scales with a 16-bit output, unsupported head size)."""
+    B, S, H, Dh = 3, 70, 2, 64
+    d = H * Dh
+    g = synth.rng(2100)
+    qkv = O.f32_to_e4m3((g.standard_normal((B * S, 3 * d)) * 40).astype(np.float32))
+    _, _, _, qk_scale, sp, cs = _fp8_attn_case(2101, 1, 1, 1, H, Dh)
+    qv, kv, vv = (OL._heads(qkv, B, S, H, Dh, i) for i in range(3))
+    ref = O.fp8_attn(qv, kv, vv, qk_scale=qk_scale, p_scale=sp, out_col_scale=cs, mask=O.MASK_CAUSAL)
+    dq = dev(qkv).view(B, S, 3, H, Dh)
+    got = hero.hero_fp8_attn(dq[:, :, 0], dq[:, :, 1], dq[:, :, 2], qk_scale, sp, dev(cs), mask=HB.MASK_CAUSAL)
+    assert_fp8_attn_codes(to_np(got.view(torch.uint8)), ref, O.e4m3_to_f32, "fused-buffer views")
+    Smax = 96
+    kc = np.zeros((B, H, Smax, Dh), np.uint8)
+    vc = np.zeros((B, H, Smax, Dh), np.uint8)
+    kc[:, :, :S], vc[:, :, :S] = kv.transpose(0, 2, 1, 3), vv.transpose(0, 2, 1, 3)
+    lens = np.int32([S, S - 9, 1])
+    q1 = np.ascontiguousarray(qv[:, -1:, :, :])
+    ref = O.fp8_attn(q1, kc.transpose(0, 2, 1, 3), vc.transpose(0, 2, 1, 3), qk_scale=qk_scale, p_scale=sp,
+                     out_col_scale=cs, mask=O.MASK_PADDING, kv_len=lens)
+    dk, dv = dev(kc), dev(vc)
+    got = hero.hero_fp8_attn(dev(q1), dk.permute(0, 2, 1, 3), dv.permute(0, 2, 1, 3), qk_scale, sp, dev(cs),
+                             mask=HB.MASK_PADDING, kv_len=dev(lens))
+    assert_fp8_attn_codes(to_np(got.view(torch.uint8)), ref, O.e4m3_to_f32, "one query against the cache", max_frac=3e-2)
+    z = hero.hero_fp8_attn(dev(q1), dk.permute(0, 2, 1, 3)[:, :0], dv.permute(0, 2, 1, 3)[:, :0], qk_scale, sp, dev(cs))
+    assert not to_np(z.view(torch.uint8)).any()
+    with pytest.raises(HB.HeroError):
+        hero.hero_fp8_attn(dq[:, :, 0], dq[:, :, 1], dq[:, :, 2], qk_scale, sp, dev(cs), out_dtype=torch.bfloat16)   # needs a scalar scale
+    with pytest.raises(HB.HeroError):
+        st = hero.lib.hero_fp8_attn(dq.data_ptr(), HB._strides4(dq[:, :, 0]), dq.data_ptr(), HB._strides4(dq[:, :, 1]),
+                                    dq.data_ptr(), HB._strides4(dq[:, :, 2]), B, H, S, S, Dh, qk_scale, sp,
+                                    dev(cs).data_ptr(), 0, 0, None, got.data_ptr(), HB.I8, d, None)
+        hero._check(st)                                                   # INT8 is not an output type of the FP8 flow
+    with pytest.raises(HB.HeroError):
+        bad = dev(qkv[:, :3 * 2 * 32]).view(B, S, 3, 2, 32)
+        hero.hero_fp8_attn(bad[:, :, 0], bad[:, :, 1], bad[:, :, 2], qk_scale, sp, dev(cs[:64]))
 
 
 # ============================================================ BF16 side of a switched module
