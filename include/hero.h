@@ -68,6 +68,8 @@ const char* hero_strerror(hero_status s);
  *            token (then beta must be NULL too).  beta may be NULL (= 0).
  *   y_q [M,D] int8 and y_scale[M] f32 are always written.
  *   y_hp     optional [M,D] copy of y in y_hp_dt (HERO_BF16/HERO_F16) for a BF16 consumer.
+ *   The 8-bit inputs may hold OCP E4M3 codes instead (x_dt / r_dt = HERO_F8E4M3, the same scales; the
+ *   FP8 variant of Sec. 2.1); two 8-bit addends must be of one format (else HERO_ERR_UNSUPPORTED).
  * Constraints: D % 16 == 0, 16 <= D <= 8192 for INT8 x, <= 4096 for 16-bit x (a row lives in one
  * wavefront's registers; HERO_ERR_UNSUPPORTED beyond).  M == 0 is a no-op.
  * Statistics are fp32 (mean, then variance about the mean) with the row held in registers.

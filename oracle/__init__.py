@@ -161,6 +161,18 @@ def weight_fold_quant(W, row_mult=None, col_div=None):
     return weight_quant(Wd.astype(np.float32))
 
 
+def weight_fold_quant_fp8(W, row_mult=None, col_div=None):
+    """The FP8 variant (Sec. 2.1) of weight_fold_quant: the same folds in fp64 and one cast to fp32, then column-wise
+    E4M3 codes with scale max|column| / 448 (the token-wise FP8 quantizer applied to the transposed weight).
+    W is [K, N]; returns codes uint8 [N, K] and scales [N]."""
+    Wd = np.asarray(W, np.float64)
+    if row_mult is not None:
+        Wd = np.asarray(row_mult, np.float64)[:, None] * Wd
+    if col_div is not None:
+        Wd = Wd / np.asarray(col_div, np.float64)[None, :]
+    return quant_twq_fp8(np.ascontiguousarray(Wd.astype(np.float32).T))
+
+
 def absmax_cols(x, running=None):
     """Calibration statistic of FWQ / SQ (Sec. 2.1, Sec. 3: the range recorded over calibration data, no
     truncation): per-column max |x| over the rows, combined with a running maximum.  x fp32 [T, D]."""

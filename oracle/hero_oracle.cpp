@@ -335,19 +335,20 @@ static int ln_quant_impl(const void* x, int x_dt, const float* x_row_scale,
                          int64_t M, int64_t D,
                          void* y_q_, int y_q_dt, float* y_scale, void* y_hp, int y_hp_dt) {
     int8_t* y_q = (int8_t*)y_q_;
-    if (x_dt == ORC_I8 && !x_row_scale) return -1;
-    if (r && r_dt == ORC_I8 && !r_col_scale) return -1;
+    // 8-bit addends: INT8 codes or E4M3 codes (ORC_F8), each times its scale
+    const bool x8 = x_dt == ORC_I8 || x_dt == ORC_F8, r8 = r && (r_dt == ORC_I8 || r_dt == ORC_F8);
+    if (x8 && !x_row_scale) return -1;
+    if (r8 && !r_col_scale) return -1;
+    auto code = [](const void* p, int dt, int64_t idx) -> double {
+        return dt == ORC_I8 ? (double)((const int8_t*)p)[idx] : (double)orc_e4m3_to_f32(((const uint8_t*)p)[idx]);
+    };
 #pragma omp parallel for schedule(static)
     for (int64_t i = 0; i < M; ++i) {
         std::vector<double> s(D);
         std::vector<float> y32(D);
         for (int64_t j = 0; j < D; ++j) {
-            double v = (x_dt == ORC_I8)
-                ? (double)x_row_scale[i] * (double)((const int8_t*)x)[i * D + j]
-                : (double)load_hp(x, x_dt, i * D + j);
-            if (r) v += (r_dt == ORC_I8)
-                ? (double)r_col_scale[j] * (double)((const int8_t*)r)[i * D + j]
-                : (double)load_hp(r, r_dt, i * D + j);
+            double v = x8 ? (double)x_row_scale[i] * code(x, x_dt, i * D + j) : (double)load_hp(x, x_dt, i * D + j);
+            if (r) v += r8 ? (double)r_col_scale[j] * code(r, r_dt, i * D + j) : (double)load_hp(r, r_dt, i * D + j);
             s[j] = v;
         }
         if (gamma) {

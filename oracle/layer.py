@@ -29,6 +29,7 @@ MODE_M3 = M_QKV | M_ATTN | M_ATTN_OUT | M_FC1 | M_FC2
 MODE_M2 = M_QKV | M_ATTN | M_ATTN_OUT | M_FC1
 MODE_M1 = M_QKV | M_FC1
 S_P = np.float32(1.0 / 255.0)
+S_P_FP8 = np.float32(1.0 / 448.0)     # the FP8 variant: p = 1 is the largest E4M3 code
 
 
 # ------------------------------------------------------------------ unquantized model (fp64)
@@ -95,21 +96,23 @@ def fp64_layer(p, x, shape, B, S, kv_len=None):
 
 
 # ------------------------------------------------------------------ calibration + preparation
-def _absmax_scale(a, axis=None):
-    """Static scale = absmax / 127 over the calibration tokens (no truncation, Sec. 3
-    discussion); a zero range gets scale 1."""
+def _absmax_scale(a, axis=None, qmax=127.0):
+    """Static scale = absmax / qmax over the calibration tokens (no truncation, Sec. 3
+    discussion); qmax = 127 for INT8 codes, 448 for E4M3; a zero range gets scale 1."""
     m = np.abs(a).max(axis=axis)
-    s = np.where(m == 0.0, 127.0, m) / 127.0
+    s = np.where(m == 0.0, qmax, m) / qmax
     return np.float32(s) if axis is None else s.astype(np.float32)
 
 
-def calibrate(p, x_calib, shape, B, S, kv_len=None):
+def calibrate(p, x_calib, shape, B, S, kv_len=None, fp8=False):
     """Static scales from a forward pass of the unquantized layer on calibration tokens:
-    SQ scalars for X_q, X_k, X_v; FWQ vectors for X_attn, X_o, A, X_2; S_p = 1/255."""
+    SQ scalars for X_q, X_k, X_v; FWQ vectors for X_attn, X_o, A, X_2; S_p = 1/255 (fp8: every range is
+    mapped to the largest E4M3 value 448 instead of 127, and S_p = 1/448)."""
     t = fp64_layer(p, np.asarray(x_calib, np.float64), shape, B, S, kv_len)
-    sc = {"S_q": _absmax_scale(t["q"]), "S_k": _absmax_scale(t["k"]), "S_v": _absmax_scale(t["v"]),
-          "S_attn": _absmax_scale(t["attn"], 0), "S_o": _absmax_scale(t["o"], 0),
-          "S_a": _absmax_scale(t["a"], 0), "S_x2": _absmax_scale(t["x2"], 0), "S_p": S_P}
+    qm = 448.0 if fp8 else 127.0
+    sc = {"S_q": _absmax_scale(t["q"], None, qm), "S_k": _absmax_scale(t["k"], None, qm), "S_v": _absmax_scale(t["v"], None, qm),
+          "S_attn": _absmax_scale(t["attn"], 0, qm), "S_o": _absmax_scale(t["o"], 0, qm),
+          "S_a": _absmax_scale(t["a"], 0, qm), "S_x2": _absmax_scale(t["x2"], 0, qm), "S_p": S_P_FP8 if fp8 else S_P}
     return sc, t["out"]
 
 
@@ -117,21 +120,26 @@ def _bf16(a):
     return O.f32_to_bf16(np.asarray(a, np.float32))
 
 
-def prepare(p, sc, shape, mode=MODE_M3):
+def prepare(p, sc, shape, mode=MODE_M3, fp8=False):
     """Fold the static scales into the weights, then quantize column-wise (Sec. 2.2.2:
     W~_q = W_q / S_q and W~_o = S_attn W_o / S_o;  Sec. 2.2.3: W~_2 = S_a W_2 / S_x2).
     Biases fold with the output scale.  Folding is done in fp64, cast to fp32 once, then
-    quantized.  BF16 modules keep the unfolded weights cast to bf16, stored [N][K]."""
+    quantized.  BF16 modules keep the unfolded weights cast to bf16, stored [N][K].
+    fp8: the FP8 variant of Sec. 2.1 (every module 8-bit): the same folds, E4M3 weight codes with column scale
+    max / 448; the scales in ``sc`` must come from calibrate(..., fp8=True)."""
     d = shape.d
     P = {k_: np.asarray(v_, np.float64) for k_, v_ in p.items()}
-    w = {"mode": mode, "S_p": sc["S_p"]}
+    w = {"mode": mode, "S_p": sc["S_p"], "fp8": bool(fp8)}
+    if fp8 and mode != MODE_M3:
+        raise ValueError("the FP8 variant runs every module in 8 bits")
+    fold_quant = O.weight_fold_quant_fp8 if fp8 else O.weight_fold_quant
     # --- QKV (always INT8 in Table 1).  INT8 attention consumes SQ codes, so S_{q,k,v}
     # are folded; a BF16 attention consumes dequantized values, so nothing is folded.
     if mode & M_ATTN:
         div = np.concatenate([np.full(d, float(sc["S_q"])), np.full(d, float(sc["S_k"])), np.full(d, float(sc["S_v"]))])
     else:
         div = np.ones(3 * d)
-    w["wq_qkv"], w["s_qkv"] = O.weight_fold_quant(P["w_qkv"], None, div)
+    w["wq_qkv"], w["s_qkv"] = fold_quant(P["w_qkv"], None, div)
     w["b_qkv"] = (P["b_qkv"] / div).astype(np.float32)
     w["qk_scale"] = np.float32(float(sc["S_q"]) * float(sc["S_k"]) / math.sqrt(shape.Dh))
     w["bf16_qk_scale"] = np.float32(1.0 / math.sqrt(shape.Dh))
@@ -145,14 +153,14 @@ def prepare(p, sc, shape, mode=MODE_M3):
         bo = P["b_o"]
         if post:
             bo = bo / sc["S_o"].astype(np.float64)
-        w["wq_o"], w["s_o_w"] = O.weight_fold_quant(P["w_o"], sc["S_attn"], sc["S_o"] if post else None)
+        w["wq_o"], w["s_o_w"] = fold_quant(P["w_o"], sc["S_attn"], sc["S_o"] if post else None)
         w["b_o"] = bo.astype(np.float32)
     else:
         w["wb_o"] = _bf16(P["w_o"].T.copy())
         w["b_o"] = P["b_o"].astype(np.float32)
     w["S_o"] = sc["S_o"]
     # --- FC1 (always INT8 in Table 1); GELU^quant divides by S_a, nothing to fold
-    w["wq_1"], w["s_1"] = O.weight_fold_quant(P["w_1"])
+    w["wq_1"], w["s_1"] = fold_quant(P["w_1"])
     w["b_1"] = P["b_1"].astype(np.float32)
     w["S_a"] = sc["S_a"]
     # --- FC2
@@ -160,7 +168,7 @@ def prepare(p, sc, shape, mode=MODE_M3):
         b2 = P["b_2"]
         if post:
             b2 = b2 / sc["S_x2"].astype(np.float64)
-        w["wq_2"], w["s_2_w"] = O.weight_fold_quant(P["w_2"], sc["S_a"], sc["S_x2"] if post else None)
+        w["wq_2"], w["s_2_w"] = fold_quant(P["w_2"], sc["S_a"], sc["S_x2"] if post else None)
         w["b_2"] = b2.astype(np.float32)
     else:
         w["wb_2"] = _bf16(P["w_2"].T.copy())
@@ -183,6 +191,8 @@ def layer_fwd(w, shape, B, S, *, x_q=None, x_s=None, h=None, kv_len=None, cache=
     {k, v: int8 [B,H,Smax,Dh]}; the S new key/value rows are written at positions
     kv_len[b]-S .. kv_len[b]-1 and attention runs over the cache.  ``trace`` (a dict)
     receives every intermediate."""
+    if w.get("fp8"):
+        return layer_fwd_fp8(w, shape, B, S, x_q=x_q, x_s=x_s, h=h, kv_len=kv_len, cache=cache, trace=trace)
     d, H, Dh, mode = shape.d, shape.H, shape.Dh, w["mode"]
     T = B * S
     tr = trace if trace is not None else {}
@@ -268,5 +278,60 @@ def layer_fwd(w, shape, B, S, *, x_q=None, x_s=None, h=None, kv_len=None, cache=
                          epi=O.EPI_DEQUANT, c_dt=O.BF16)
     else:
         h2 = O.bf16_gemm(a, w["wb_2"], bias=w["b_2"], residual=h1)
+    tr["h2"] = h2
+    return h2
+
+
+def layer_fwd_fp8(w, shape, B, S, *, x_q=None, x_s=None, h=None, kv_len=None, cache=None, trace=None):
+    """The same layer with E4M3 as the 8-bit format of every module (Sec. 2.1: the method works for FP8 as for
+    INT8): the dataflow, scale granularities (TWQ / FWQ / SQ) and folds of layer_fwd, with the FP8 operators.
+    POST_LN: (x_q uint8 E4M3 [T,d], x_s f32 [T]) -> (out_q, out_s); PRE_LN: h (bf16 bit patterns) -> new h.
+    ``cache`` holds E4M3 bytes [B,H,Smax,Dh]."""
+    d, H, Dh = shape.d, shape.H, shape.Dh
+    tr = trace if trace is not None else {}
+    post = shape.arch == POST_LN
+    sp = float(w["S_p"])
+    if post:
+        xin_q, xin_s = x_q, x_s
+    else:
+        xin_q, xin_s, _ = O.ln_quant(h, O.BF16, None, None, 0, None, w["ln1_g"], w["ln1_b"], shape.eps, fp8=True)
+    tr["xin_q"], tr["xin_s"] = xin_q, xin_s
+    qkv = O.fp8_gemm(xin_q, w["wq_qkv"], a_row_scale=xin_s, b_col_scale=w["s_qkv"], bias=w["b_qkv"],
+                     epi=O.EPI_REQUANT, c_dt=O.F8)
+    tr["qkv"] = qkv
+    qv = _heads(qkv, B, S, H, Dh, 0)
+    if cache is not None:
+        kn, vn = _heads(qkv, B, S, H, Dh, 1), _heads(qkv, B, S, H, Dh, 2)
+        for b in range(B):
+            p0 = int(kv_len[b]) - S
+            cache["k"][b, :, p0:p0 + S, :] = kn[b].transpose(1, 0, 2)
+            cache["v"][b, :, p0:p0 + S, :] = vn[b].transpose(1, 0, 2)
+        kv, vv = cache["k"].transpose(0, 2, 1, 3), cache["v"].transpose(0, 2, 1, 3)
+    else:
+        kv, vv = _heads(qkv, B, S, H, Dh, 1), _heads(qkv, B, S, H, Dh, 2)
+    attn = O.fp8_attn(qv, kv, vv, qk_scale=float(w["qk_scale"]), p_scale=sp, out_col_scale=w["attn_out_scale"],
+                      mask=shape.mask, kv_len=kv_len, out_dt=O.F8)
+    tr["attn"] = attn
+    if post:
+        xo = O.fp8_gemm(attn, w["wq_o"], b_col_scale=w["s_o_w"], bias=w["b_o"], epi=O.EPI_REQUANT, c_dt=O.F8)
+        tr["xo"] = xo
+        mid_q, mid_s, _ = O.ln_quant(xin_q, O.F8, xin_s, xo, O.F8, w["S_o"], w["ln1_g"], w["ln1_b"], shape.eps, fp8=True)
+    else:
+        h1 = O.fp8_gemm(attn, w["wq_o"], b_col_scale=w["s_o_w"], bias=w["b_o"], residual=h, res_dt=O.BF16,
+                        epi=O.EPI_DEQUANT, c_dt=O.BF16)
+        tr["h1"] = h1
+        mid_q, mid_s, _ = O.ln_quant(h1, O.BF16, None, None, 0, None, w["ln2_g"], w["ln2_b"], shape.eps, fp8=True)
+    tr["mid_q"], tr["mid_s"] = mid_q, mid_s
+    a = O.fp8_gemm(mid_q, w["wq_1"], a_row_scale=mid_s, b_col_scale=w["s_1"], bias=w["b_1"],
+                   epi=O.EPI_GELU_REQUANT, out_col_scale=w["S_a"], c_dt=O.F8)
+    tr["a"] = a
+    if post:
+        x2 = O.fp8_gemm(a, w["wq_2"], b_col_scale=w["s_2_w"], bias=w["b_2"], epi=O.EPI_REQUANT, c_dt=O.F8)
+        tr["x2"] = x2
+        out_q, out_s, _ = O.ln_quant(mid_q, O.F8, mid_s, x2, O.F8, w["S_x2"], w["ln2_g"], w["ln2_b"], shape.eps, fp8=True)
+        tr["out_q"], tr["out_s"] = out_q, out_s
+        return out_q, out_s
+    h2 = O.fp8_gemm(a, w["wq_2"], b_col_scale=w["s_2_w"], bias=w["b_2"], residual=h1, res_dt=O.BF16,
+                    epi=O.EPI_DEQUANT, c_dt=O.BF16)
     tr["h2"] = h2
     return h2

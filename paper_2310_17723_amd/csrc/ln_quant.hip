@@ -37,6 +37,7 @@ struct LnArgs {
     int8_t* y_q; float* y_scale; void* y_hp;
     int x_dt, r_dt, hp_dt;       // r_dt / hp_dt = -1 when absent
     int y_fp8;                   // token-wise E4M3 codes (scale max|y| / 448) instead of INT8 codes
+    int in_fp8;                  // the 8-bit inputs (x and / or r with x_dt / r_dt = HERO_I8 here) hold E4M3 codes
     // gathered form (embedding): row i of x / r / r2 is row x_idx[i] / r_idx[i] / r2_idx[i] of a table
     // with x_rows / r_rows / r2_rows rows (indices are clamped into the table); r2 is a third addend in r_dt
     const int32_t* x_idx; const int32_t* r_idx; const void* r2; const int32_t* r2_idx;
@@ -53,9 +54,14 @@ __device__ __forceinline__ float sbyte_f32(int w) {
     else asm("v_cvt_f32_i32_sdwa %0, sext(%1) dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_3" : "=v"(r) : "v"(w));
     return r;
 }
-// the four codes of one dword
-__device__ __forceinline__ void unpack4(int w, float (&o)[4]) {
-    o[0] = sbyte_f32<0>(w); o[1] = sbyte_f32<1>(w); o[2] = sbyte_f32<2>(w); o[3] = sbyte_f32<3>(w);
+// the four codes of one dword: INT8, or E4M3 (v_cvt_f32_fp8 with a byte select) when f8 (wave-uniform)
+__device__ __forceinline__ void unpack4(int w, float (&o)[4], bool f8 = false) {
+    if (f8) {
+        o[0] = __builtin_amdgcn_cvt_f32_fp8(w, 0); o[1] = __builtin_amdgcn_cvt_f32_fp8(w, 1);
+        o[2] = __builtin_amdgcn_cvt_f32_fp8(w, 2); o[3] = __builtin_amdgcn_cvt_f32_fp8(w, 3);
+    } else {
+        o[0] = sbyte_f32<0>(w); o[1] = sbyte_f32<1>(w); o[2] = sbyte_f32<2>(w); o[3] = sbyte_f32<3>(w);
+    }
 }
 
 // ---- 64-lane reductions on the DPP network; the result is wave-uniform ---------------------------
@@ -178,6 +184,7 @@ __global__ __launch_bounds__(64 * ln_max_waves(NCH)) void ln_quant_kernel(LnArgs
     }
     __syncthreads();
     if (row >= a.M) return;
+    const bool in_f8 = !GATHER && a.in_fp8 != 0;
     const float inv_d = 1.0f / (float)D;
     const float npad = (float)(Dp - D);                       // padded columns hold 0 and are corrected for in the variance
 
@@ -203,7 +210,7 @@ __global__ __launch_bounds__(64 * ln_max_waves(NCH)) void ln_quant_kernel(LnArgs
 #pragma unroll
                     for (int e4 = 0; e4 < 4; ++e4) {
                         float f[4];
-                        unpack4(rx[p][c][e4], f);
+                        unpack4(rx[p][c][e4], f, in_f8);
 #pragma unroll
                         for (int t = 0; t < 4; ++t) v[c][4 * e4 + t] = f[t] * xs;
                     }
@@ -218,7 +225,7 @@ __global__ __launch_bounds__(64 * ln_max_waves(NCH)) void ln_quant_kernel(LnArgs
 #pragma unroll
                     for (int e4 = 0; e4 < EPL / 4; ++e4) {
                         float f[4];
-                        unpack4(rr0[p][c][e4], f);
+                        unpack4(rr0[p][c][e4], f, in_f8);
                         const v4f rc = *reinterpret_cast<const v4f*>(sp + 2 * Dp + ((c * (EPL / 4) + e4) * 64 + lane) * 4);
 #pragma unroll
                         for (int t = 0; t < 4; ++t) v[c][4 * e4 + t] = fmaf(f[t], rc[t], v[c][4 * e4 + t]);
@@ -422,12 +429,17 @@ hero_status ln_quant_entry(const void* x, hero_dtype x_dt, const float* x_row_sc
     if (D % 16 != 0) return HERO_ERR_UNSUPPORTED;
     if (M == 0) return HERO_OK;
     if (!x || !y_q || !y_scale) return HERO_ERR_NULL;
-    const bool x_i8 = x_dt == HERO_I8;
+    // 8-bit inputs: INT8 codes or E4M3 codes (one format per call: the kernels unpack both addends the same way)
+    const bool x_i8 = x_dt == HERO_I8 || x_dt == HERO_F8E4M3;
     if (!x_i8 && x_dt != HERO_BF16 && x_dt != HERO_F16) return HERO_ERR_UNSUPPORTED;
     if (x_i8 && !x_row_scale) return HERO_ERR_NULL;
+    int in_fp8 = x_dt == HERO_F8E4M3;
     if (r) {
-        if (r_dt != HERO_I8 && r_dt != HERO_BF16 && r_dt != HERO_F16) return HERO_ERR_UNSUPPORTED;
-        if (r_dt == HERO_I8 && !r_col_scale) return HERO_ERR_NULL;
+        const bool r_8 = r_dt == HERO_I8 || r_dt == HERO_F8E4M3;
+        if (!r_8 && r_dt != HERO_BF16 && r_dt != HERO_F16) return HERO_ERR_UNSUPPORTED;
+        if (r_8 && !r_col_scale) return HERO_ERR_NULL;
+        if (r_8 && x_i8 && r_dt != x_dt) return HERO_ERR_UNSUPPORTED;
+        if (r_dt == HERO_F8E4M3) { in_fp8 = 1; r_dt = HERO_I8; }
     }
     if (!gamma && beta) return HERO_ERR_NULL;
     if (y_hp && y_hp_dt != HERO_BF16 && y_hp_dt != HERO_F16) return HERO_ERR_UNSUPPORTED;
@@ -438,8 +450,8 @@ hero_status ln_quant_entry(const void* x, hero_dtype x_dt, const float* x_row_sc
     a.x = x; a.x_row_scale = x_row_scale; a.r = r; a.r_col_scale = r_col_scale;
     a.gamma = gamma; a.beta = beta; a.eps = eps; a.M = M; a.D = (int)D;
     a.y_q = (int8_t*)y_q; a.y_scale = y_scale; a.y_hp = y_hp;
-    a.x_dt = (int)x_dt; a.r_dt = r ? (int)r_dt : -1; a.hp_dt = y_hp ? (int)y_hp_dt : -1;
-    a.y_fp8 = y_fp8;
+    a.x_dt = x_i8 ? (int)HERO_I8 : (int)x_dt; a.r_dt = r ? (int)r_dt : -1; a.hp_dt = y_hp ? (int)y_hp_dt : -1;
+    a.y_fp8 = y_fp8; a.in_fp8 = in_fp8;
     a.x_idx = a.r_idx = a.r2_idx = nullptr; a.r2 = nullptr; a.x_rows = a.r_rows = a.r2_rows = 0;
     hipStream_t st = (hipStream_t)stream;
     if (x_i8) return launch<HERO_I8>(a, st);
@@ -482,7 +494,7 @@ extern "C" hero_status hero_embed_ln_quant(const int32_t* tok_ids, const int32_t
     LnArgs a;
     a.x = tok_table; a.x_row_scale = tok_scale; a.r = pos_table; a.r_col_scale = nullptr;
     a.gamma = gamma; a.beta = beta; a.eps = eps; a.M = T; a.D = (int)D;
-    a.y_q = y_q; a.y_scale = y_scale; a.y_hp = nullptr; a.y_fp8 = 0;
+    a.y_q = y_q; a.y_scale = y_scale; a.y_hp = nullptr; a.y_fp8 = 0; a.in_fp8 = 0;
     a.x_dt = HERO_I8; a.r_dt = (int)pt_dt; a.hp_dt = -1;
     a.x_idx = tok_ids; a.r_idx = pos_ids; a.r2 = type_table; a.r2_idx = type_table ? type_ids : nullptr;
     a.x_rows = (int)V; a.r_rows = (int)P; a.r2_rows = type_table ? (int)NT : 0;
