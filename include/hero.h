@@ -267,8 +267,12 @@ hero_status hero_fp8_attn(const void* q, const int64_t q_strides[4],
 
 typedef enum { HERO_ARCH_POST_LN = 0, HERO_ARCH_PRE_LN = 1 } hero_arch;
 
-/* mode_mask: one bit per switchable module of Table 1; set = INT8, clear = BF16. */
-enum { HERO_M_QKV = 1, HERO_M_ATTN = 2, HERO_M_ATTN_OUT = 4, HERO_M_FC1 = 8, HERO_M_FC2 = 16 };
+/* mode_mask: one bit per switchable module of Table 1; set = INT8, clear = BF16.
+ * HERO_M_FP8 (only together with all five module bits): the 8-bit format of the whole layer is OCP E4M3
+ * instead of INT8 (Sec. 2.1).  Every int8_t* of hero_layer_weights / hero_layer_io then holds E4M3 bytes
+ * (weights quantized column-wise to max|column| / 448, static scales calibrated to 448, p_scale = 1/448),
+ * and the layer runs hero_ln_quant_fp8 / hero_fp8_gemm / hero_fp8_attn in place of the INT8 entry points. */
+enum { HERO_M_QKV = 1, HERO_M_ATTN = 2, HERO_M_ATTN_OUT = 4, HERO_M_FC1 = 8, HERO_M_FC2 = 16, HERO_M_FP8 = 32 };
 #define HERO_MODE_M3 (HERO_M_QKV | HERO_M_ATTN | HERO_M_ATTN_OUT | HERO_M_FC1 | HERO_M_FC2)
 #define HERO_MODE_M2 (HERO_M_QKV | HERO_M_ATTN | HERO_M_ATTN_OUT | HERO_M_FC1)
 #define HERO_MODE_M1 (HERO_M_QKV | HERO_M_FC1)

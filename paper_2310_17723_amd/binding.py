@@ -11,7 +11,7 @@ I8, U8, I32, F16, BF16, F32 = range(6)
 EPI_RAW_I32, EPI_DEQUANT, EPI_DEQUANT_GELU, EPI_REQUANT, EPI_GELU_REQUANT = range(5)
 MASK_NONE, MASK_PADDING, MASK_CAUSAL = range(3)
 ARCH_POST_LN, ARCH_PRE_LN = 0, 1
-M_QKV, M_ATTN, M_ATTN_OUT, M_FC1, M_FC2 = 1, 2, 4, 8, 16
+M_QKV, M_ATTN, M_ATTN_OUT, M_FC1, M_FC2, M_FP8 = 1, 2, 4, 8, 16, 32
 MODE_M3 = M_QKV | M_ATTN | M_ATTN_OUT | M_FC1 | M_FC2
 MODE_M2 = M_QKV | M_ATTN | M_ATTN_OUT | M_FC1
 MODE_M1 = M_QKV | M_FC1

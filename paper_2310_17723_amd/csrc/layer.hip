@@ -35,11 +35,15 @@ Workspace plan(const hero_layer_desc* d, int64_t T) {
     w.mid_s = take((size_t)T * 4);
     w.a = take((size_t)T * d->f * e_a);
     w.x2 = take(pre ? 0 : (size_t)T * d->d * e_a);
-    // split-K scratch of the skinny (decode) GEMMs: the largest of the four shapes, shared (stream order)
-    size_t g = hero_int8_gemm_workspace_bytes(T, 3 * (int64_t)d->d, d->d);
-    g = std::max(g, hero_int8_gemm_workspace_bytes(T, d->d, d->d));
-    g = std::max(g, hero_int8_gemm_workspace_bytes(T, d->f, d->d));
-    g = std::max(g, hero_int8_gemm_workspace_bytes(T, d->d, d->f));
+    // split-K scratch of the skinny (decode) GEMMs: the largest of the four shapes, shared (stream order);
+    // none in the FP8 variant (fp32 partial sums would not commute)
+    size_t g = 0;
+    if (!(d->mode_mask & HERO_M_FP8)) {
+        g = hero_int8_gemm_workspace_bytes(T, 3 * (int64_t)d->d, d->d);
+        g = std::max(g, hero_int8_gemm_workspace_bytes(T, d->d, d->d));
+        g = std::max(g, hero_int8_gemm_workspace_bytes(T, d->f, d->d));
+        g = std::max(g, hero_int8_gemm_workspace_bytes(T, d->d, d->f));
+    }
     w.gemm_ws_bytes = g;
     w.gemm_ws = take(g);
     w.total = off;
@@ -71,7 +75,8 @@ hero_status check(const hero_layer_desc* d) {
     const uint32_t m = d->mode_mask;
     if (!(m & HERO_M_QKV) || !(m & HERO_M_FC1)) return HERO_ERR_UNSUPPORTED;
     if ((m & HERO_M_ATTN_OUT) && !(m & HERO_M_ATTN)) return HERO_ERR_UNSUPPORTED;
-    if (m & ~(uint32_t)HERO_MODE_M3) return HERO_ERR_UNSUPPORTED;
+    if (m & ~(uint32_t)(HERO_MODE_M3 | HERO_M_FP8)) return HERO_ERR_UNSUPPORTED;
+    if ((m & HERO_M_FP8) && (m & HERO_MODE_M3) != HERO_MODE_M3) return HERO_ERR_UNSUPPORTED;   // FP8: every module 8-bit
     return HERO_OK;
 }
 
@@ -141,6 +146,54 @@ extern "C" hero_status hero_layer_fwd(const hero_layer_desc* desc, const hero_la
     void* x2 = base + ws.x2;
     hipStream_t st = (hipStream_t)stream;
     void* gws = ws.gemm_ws_bytes ? (void*)(base + ws.gemm_ws) : nullptr;   // split-K scratch of the skinny GEMMs
+
+    // ---- the FP8 variant (Sec. 2.1): the same chain with E4M3 codes in every 8-bit buffer
+    if (mode & HERO_M_FP8) {
+        const hero_dtype F8 = HERO_F8E4M3;
+        if (pre)
+            HERO_TRY(hero_ln_quant_fp8(io->h, HERO_BF16, nullptr, nullptr, F8, nullptr, w->ln1_g, w->ln1_b, desc->eps,
+                                       T, d, xin_q, xin_s, nullptr, HERO_BF16, stream));
+        HERO_TRY(hero_fp8_gemm(xin_q, d, xin_s, w->w_qkv, d, w->w_qkv_s, w->b_qkv, nullptr, HERO_BF16, 0,
+                               HERO_EPI_REQUANT, nullptr, qkv, F8, 3 * d, T, 3 * d, d, stream));
+        const int64_t qs[4] = {S * 3 * d, 3 * d, Dh, 1};
+        const int8_t* qp = (const int8_t*)qkv;
+        const int8_t *kp = qp + d, *vp = qp + 2 * d;
+        int64_t ks[4] = {qs[0], qs[1], qs[2], qs[3]};
+        int64_t Skv = S;
+        if (cache) {                                              // the cache holds E4M3 (SQ) codes: a byte copy
+            const int64_t n = T * (d / 16);
+            hipLaunchKernelGGL(kv_append_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
+                               qp, io->k_cache, io->v_cache, io->kv_len, (int)B, (int)S, (int)H, (int)Dh, io->Smax);
+            HERO_TRY(hero_launch_status());
+            kp = io->k_cache; vp = io->v_cache; Skv = io->Smax;
+            ks[0] = H * io->Smax * Dh; ks[1] = Dh; ks[2] = io->Smax * Dh; ks[3] = 1;
+        }
+        HERO_TRY(hero_fp8_attn(qp, qs, kp, ks, vp, ks, B, H, S, Skv, Dh, w->qk_scale, w->p_scale,
+                               w->attn_out_scale, 0, (hero_mask)desc->mask, io->kv_len, attn, F8, d, stream));
+        if (!pre) {
+            HERO_TRY(hero_fp8_gemm(attn, d, nullptr, w->w_o, d, w->w_o_s, w->b_o, nullptr, HERO_BF16, 0,
+                                   HERO_EPI_REQUANT, nullptr, xo, F8, d, T, d, d, stream));
+            HERO_TRY(hero_ln_quant_fp8(xin_q, F8, xin_s, xo, F8, w->S_o, w->ln1_g, w->ln1_b, desc->eps, T, d,
+                                       mid_q, mid_s, nullptr, HERO_BF16, stream));
+        } else {
+            HERO_TRY(hero_fp8_gemm(attn, d, nullptr, w->w_o, d, w->w_o_s, w->b_o, io->h, HERO_BF16, d,
+                                   HERO_EPI_DEQUANT, nullptr, io->h, HERO_BF16, d, T, d, d, stream));
+            HERO_TRY(hero_ln_quant_fp8(io->h, HERO_BF16, nullptr, nullptr, F8, nullptr, w->ln2_g, w->ln2_b, desc->eps,
+                                       T, d, mid_q, mid_s, nullptr, HERO_BF16, stream));
+        }
+        HERO_TRY(hero_fp8_gemm(mid_q, d, mid_s, w->w_1, d, w->w_1_s, w->b_1, nullptr, HERO_BF16, 0,
+                               HERO_EPI_GELU_REQUANT, w->S_a, act, F8, f, T, f, d, stream));
+        if (!pre) {
+            HERO_TRY(hero_fp8_gemm(act, f, nullptr, w->w_2, f, w->w_2_s, w->b_2, nullptr, HERO_BF16, 0,
+                                   HERO_EPI_REQUANT, nullptr, x2, F8, d, T, d, f, stream));
+            HERO_TRY(hero_ln_quant_fp8(mid_q, F8, mid_s, x2, F8, w->S_x2, w->ln2_g, w->ln2_b, desc->eps, T, d,
+                                       io->out_q, io->out_scale, nullptr, HERO_BF16, stream));
+        } else {
+            HERO_TRY(hero_fp8_gemm(act, f, nullptr, w->w_2, f, w->w_2_s, w->b_2, io->h, HERO_BF16, d,
+                                   HERO_EPI_DEQUANT, nullptr, io->h, HERO_BF16, d, T, d, f, stream));
+        }
+        return HERO_OK;
+    }
 
     // (1) PRE_LN: LN^quant of the residual stream
     if (pre)

@@ -106,6 +106,32 @@ def test_ln_quant_fp8_output(hero, M, D):
             assert rel_err(O.bf16_to_f32(to_np(got)), O.bf16_to_f32(ref)) <= 2e-2
 
 
+@pytest.mark.parametrize("M,D", [(70, 1024), (9, 8192), (200, 48)])
+def test_ln_quant_e4m3_addends(hero, M, D):
+    """The 8-bit addends as E4M3 codes (the FP8 layer's LN^quant(S_in X_in, X_o S_o)): same scales, same classes;
+    an INT8 output from E4M3 addends is served too; INT8 and E4M3 addends in one call are refused."""
+    g = synth.rng(1600 + D)
+    x8 = O.f32_to_e4m3((g.standard_normal((M, D)) * 60).astype(np.float32))
+    r8 = O.f32_to_e4m3((g.standard_normal((M, D)) * 60).astype(np.float32))
+    _, _, xs, rc, gam, bet, _ = _ln_inputs(1601 + D, M, D)
+    f8 = lambda a: dev(a).view(torch.float8_e4m3fn)
+    q_o, s_o, _ = O.ln_quant(x8, O.F8, xs, r8, O.F8, rc, gam, bet, 1e-5, fp8=True)
+    q, s, _ = hero.hero_ln_quant(f8(x8), dev(xs), f8(r8), dev(rc), dev(gam), dev(bet), 1e-5, fp8=True)
+    assert_scales(to_np(s), s_o, "y_scale")
+    assert_fp8_codes(to_np(q), q_o, O.e4m3_to_f32, "LN fp8 <- fp8", max_frac=max(1e-3, 2.5 / q_o.size))
+    q_o, s_o, _ = O.ln_quant(x8, O.F8, xs, r8, O.F8, rc, gam, bet, 1e-5)
+    q, s, _ = hero.hero_ln_quant(f8(x8), dev(xs), f8(r8), dev(rc), dev(gam), dev(bet), 1e-5)
+    assert_scales(to_np(s), s_o, "y_scale")
+    assert_codes(to_np(q), q_o, "LN int8 <- fp8", max_frac=max(1e-3, 2.5 / q_o.size))
+    # no LayerNorm: the decoded, scaled codes quantized per token, exact
+    q_o, s_o, _ = O.ln_quant(x8, O.F8, xs, None, 0, None, None, None, 0.0, fp8=True)
+    q, s, _ = hero.hero_ln_quant(f8(x8), dev(xs), None, None, None, None, 0.0, fp8=True)
+    assert_exact(to_np(s), s_o, "twq scale")
+    assert_exact(to_np(q), q_o, "twq codes")
+    with pytest.raises(HB.HeroError):
+        hero.hero_ln_quant(f8(x8), dev(xs), dev(r8.view(np.int8)), dev(rc), dev(gam), dev(bet), 1e-5, fp8=True)
+
+
 def test_ln_quant_rejects_bad_arguments(hero):
     x = torch.zeros((4, 40), dtype=torch.int8, device="cuda")
     with pytest.raises(HB.HeroError) as e:

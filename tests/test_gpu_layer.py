@@ -11,7 +11,7 @@ import oracle as O
 from oracle import layer as OL
 from paper_2310_17723_amd import binding as HB
 from paper_2310_17723_amd import synth
-from parity import dev, rel_err, to_np, upload_weights
+from parity import assert_fp8_attn_values, dev, rel_err, to_np, upload_weights
 
 pytestmark = pytest.mark.gpu
 
@@ -23,15 +23,15 @@ def _shape(arch, mask, **kw):
     return synth.small(synth.CONFIGS[0], **base)
 
 
-def _prepare(shape, seed, mode):
+def _prepare(shape, seed, mode, fp8=False):
     p = synth.layer_params(seed, shape)
     emb = synth.embedding_ln_params(seed, shape)
     Tc = 2 * shape.B * shape.S
     hc = synth.activations(seed, shape, Tc, stream=1).astype(np.float64)
     if shape.arch == synth.POST_LN:
         hc = OL._ln64(hc, emb["g"].astype(np.float64), emb["b"].astype(np.float64), shape.eps)
-    sc, _ = OL.calibrate(p, hc, shape, 2 * shape.B, shape.S)
-    return OL.prepare(p, sc, shape, mode), emb
+    sc, _ = OL.calibrate(p, hc, shape, 2 * shape.B, shape.S, fp8=fp8)
+    return OL.prepare(p, sc, shape, mode, fp8=fp8), emb
 
 
 def _desc(hero, shape, mode):
@@ -131,6 +131,74 @@ def test_mixed_precision_modes(hero, arch, mode):
         hero.hero_layer_fwd(desc, W, B, S, ws, h=h)
         got = O.bf16_to_f32(to_np(h))
     assert rel_err(got, ref) <= 2e-2
+
+
+# ---- the FP8 variant of the layer (HERO_M_FP8): E4M3 codes in every 8-bit buffer.  The end-to-end class: a flipped
+# probability code of a dominant key moves a whole attention row by up to a quarter of the typical output (see
+# parity.assert_fp8_attn_codes) and every later E4M3 rounding (relative step 2^-3 .. 2^-4) may then land on the
+# neighbouring code, so the reconstructed outputs are compared in relative L2 (2e-2, the layer bar of the INT8
+# path) with every element within one E4M3 step of its own value plus a quarter of the rms.
+@pytest.mark.parametrize("mask", [synth.MASK_NONE, synth.MASK_PADDING])
+def test_post_ln_layer_fp8(hero, mask):
+    shape = _shape(synth.POST_LN, mask)
+    B, S, T = shape.B, shape.S, shape.B * shape.S
+    w, emb = _prepare(shape, 31, OL.MODE_M3, fp8=True)
+    h0 = synth.activations(31, shape, T)
+    xq, xs, _ = O.ln_quant(h0, O.F32, None, None, 0, None, emb["g"], emb["b"], shape.eps, fp8=True)
+    kv_len = synth.kv_lengths(31, shape) if mask == synth.MASK_PADDING else None
+    oq, os_ = OL.layer_fwd(w, shape, B, S, x_q=xq, x_s=xs, kv_len=kv_len)
+    desc = _desc(hero, shape, HB.MODE_M3 | HB.M_FP8)
+    W, keep = upload_weights(hero, w)
+    ws = torch.empty(hero.hero_layer_workspace_bytes(desc, B, S), dtype=torch.uint8, device="cuda")
+    out_q = torch.empty((T, shape.d), dtype=torch.uint8, device="cuda")
+    out_s = torch.empty((T,), dtype=torch.float32, device="cuda")
+    hero.hero_layer_fwd(desc, W, B, S, ws, x_q=dev(xq), x_scale=dev(xs), out_q=out_q, out_scale=out_s, kv_len=dev(kv_len))
+    gq, gs = to_np(out_q), to_np(out_s)
+    valid = np.ones(T, bool)
+    if kv_len is not None:
+        valid = (np.arange(S)[None, :] < kv_len[:, None]).ravel()
+    ref = (O.e4m3_to_f32(oq).astype(np.float64) * os_[:, None])[valid]
+    got = (O.e4m3_to_f32(gq).astype(np.float64) * gs[:, None])[valid]
+    rms = np.sqrt(np.mean(ref * ref))
+    assert np.sqrt(((got - ref) ** 2).sum() / (ref ** 2).sum()) <= 2e-2
+    assert (np.abs(got - ref) <= 0.125 * np.abs(ref) + 0.25 * rms).all()
+    assert np.allclose(gs[valid], os_[valid], rtol=3e-2)
+    assert np.mean(gq[valid] == oq[valid]) > 0.8                   # measured 0.88-0.89
+
+
+@pytest.mark.parametrize("Dh,H", [(64, 4), (128, 2)])
+def test_pre_ln_layer_fp8_prefill_then_decode(hero, Dh, H):
+    """Causal prefill that fills the E4M3 KV cache, then three one-token steps (served by the general kernel)."""
+    shape = _shape(synth.PRE_LN, synth.MASK_CAUSAL, Dh=Dh, H=H, S=100)
+    B, S, T, d = shape.B, shape.S, shape.B * shape.S, shape.d
+    w, _ = _prepare(shape, 41, OL.MODE_M3, fp8=True)
+    hb = O.f32_to_bf16(synth.activations(41, shape, T))
+    Smax = S + 8
+    cache = {"k": np.zeros((B, H, Smax, Dh), np.uint8), "v": np.zeros((B, H, Smax, Dh), np.uint8)}
+    kv = np.full(B, S, np.int32)
+    ref = OL.layer_fwd(w, shape, B, S, h=hb, kv_len=kv, cache=cache)
+    desc = _desc(hero, shape, HB.MODE_M3 | HB.M_FP8)
+    W, keep = upload_weights(hero, w)
+    ws = torch.empty(hero.hero_layer_workspace_bytes(desc, B, S), dtype=torch.uint8, device="cuda")
+    kc = torch.zeros((B, H, Smax, Dh), dtype=torch.uint8, device="cuda")
+    vc = torch.zeros_like(kc)
+    h = dev(hb)
+    hero.hero_layer_fwd(desc, W, B, S, ws, h=h, kv_len=dev(kv), k_cache=kc, v_cache=vc)
+    assert_fp8_attn_values(O.bf16_to_f32(to_np(h)), O.bf16_to_f32(ref), "prefill h")
+    assert np.mean(to_np(kc) == cache["k"]) > 0.99 and np.mean(to_np(vc) == cache["v"]) > 0.99
+    for step in range(3):
+        hb1 = O.f32_to_bf16(synth.activations(41, shape, B, stream=10 + step))
+        kv = kv + 1
+        ref1 = OL.layer_fwd(w, shape, B, 1, h=hb1, kv_len=kv, cache=cache)
+        h1 = dev(hb1)
+        hero.hero_layer_fwd(desc, W, B, 1, ws, h=h1, kv_len=dev(kv), k_cache=kc, v_cache=vc)
+        assert_fp8_attn_values(O.bf16_to_f32(to_np(h1)), O.bf16_to_f32(ref1), f"decode step {step}")
+
+
+def test_layer_fp8_needs_every_module_8bit(hero):
+    shape = _shape(synth.POST_LN, synth.MASK_NONE)
+    assert hero.hero_layer_workspace_bytes(_desc(hero, shape, HB.MODE_M2 | HB.M_FP8), 2, 8) == 0
+    assert hero.hero_layer_workspace_bytes(_desc(hero, shape, HB.MODE_M3 | HB.M_FP8), 2, 8) > 0
 
 
 def test_layer_rejects_bad_requests(hero):
