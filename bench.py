@@ -233,9 +233,60 @@ def fp8_gemm_leg(hero, shape, seed, iters=20):
     return rows
 
 
+def fp8_layer_leg(hero, shape, seed, iters=10):
+    """One layer of the workload in the FP8 variant (mode bit M_FP8: E4M3 codes in every 8-bit buffer).  Timing
+    only: Gaussian weights quantized column-wise to E4M3 here with torch, static scales set to the ranges such a
+    layer has (its parity against the oracle's FP8 layer is in the tests); prefill workloads only."""
+    import torch
+    from paper_2310_17723_amd import binding as HB
+    g = torch.Generator(device="cuda").manual_seed(seed + 7)
+    B, S, d, f, H, Dh = shape.B, shape.S, shape.d, shape.f, shape.H, shape.Dh
+    T = B * S
+
+    def wq(N, K, std):
+        W = torch.randn((N, K), device="cuda", generator=g) * std
+        cs = W.abs().amax(dim=1) / 448
+        return (W / cs[:, None]).to(torch.float8_e4m3fn), cs
+
+    t = {}
+    t["w_qkv"], t["w_qkv_s"] = wq(3 * d, d, 0.02)
+    t["w_o"], t["w_o_s"] = wq(d, d, 0.02)
+    t["w_1"], t["w_1_s"] = wq(f, d, 0.02)
+    t["w_2"], t["w_2_s"] = wq(d, f, 0.02)
+    t["w_qkv_s"] = t["w_qkv_s"] * 4.0                    # folded 1 / S_{q,k,v}: codes spread over the E4M3 range
+    for n, k in (("b_qkv", 3 * d), ("b_o", d), ("b_1", f), ("b_2", d)):
+        t[n] = torch.randn(k, device="cuda", generator=g) * 0.02
+    for n in ("ln1_g", "ln2_g"):
+        t[n] = torch.ones(d, device="cuda")
+    for n in ("ln1_b", "ln2_b"):
+        t[n] = torch.zeros(d, device="cuda")
+    t["S_o"] = torch.full((d,), 2.0 / 448, device="cuda")
+    t["S_x2"] = torch.full((d,), 2.0 / 448, device="cuda")
+    t["S_a"] = torch.full((f,), 4.0 / 448, device="cuda")
+    t["attn_out_scale"] = torch.full((d,), 1.0 / 448 * 4.0, device="cuda")
+    W = hero.layer_weights(t, 1.5 / (100 * 100 * Dh ** 0.5), 1.0 / 448)
+    desc = hero.layer_desc(shape.arch, d, H, Dh, f, shape.eps, shape.mask, HB.MODE_M3 | HB.M_FP8)
+    ws = torch.empty(hero.hero_layer_workspace_bytes(desc, B, S), dtype=torch.uint8, device="cuda")
+    kvl = None
+    if shape.mask == 1:
+        kvl = torch.randint(shape.kv_lo or S // 2, (shape.kv_hi or S) + 1, (B,), dtype=torch.int32, device="cuda", generator=g)
+    h0 = torch.randn((T, d), device="cuda", generator=g).to(torch.bfloat16)
+    if shape.arch == 0:
+        xq, xs, _ = hero.hero_ln_quant(h0, None, None, None, t["ln1_g"], t["ln1_b"], shape.eps, fp8=True)
+        oq, os_ = torch.empty_like(xq), torch.empty_like(xs)
+        fn = lambda: hero.hero_layer_fwd(desc, W, B, S, ws, x_q=xq, x_scale=xs, out_q=oq, out_scale=os_, kv_len=kvl)
+    else:
+        h = h0.clone()
+        fn = lambda: hero.hero_layer_fwd(desc, W, B, S, ws, h=h)
+    ms = time_gpu(fn, iters)
+    return {"workload": shape.name, "mode": "M3 + FP8 (E4M3)", "us_per_layer": round(ms * 1e3, 2),
+            "layer_tokens_per_s": round(T / (ms * 1e-3), 1)}
+
+
 def attn_variants(hero, shape, seed, iters=20):
     """The attention kernel alone at the workload's shape: the two-pass Softmax^quant of Sec. 2.2.2 (what the
-    layer runs) beside the single-sweep online variant (a different quantization of the probabilities)."""
+    layer runs) beside the single-sweep online variant (a different quantization of the probabilities) and the
+    FP8 variant of the two-pass flow."""
     import torch
     from paper_2310_17723_amd import binding as HB
     g = torch.Generator(device="cuda").manual_seed(seed)
@@ -258,6 +309,12 @@ def attn_variants(hero, shape, seed, iters=20):
     ms = time_gpu(lambda: hero.hero_int8_attn_online(v[:, :, 0], v[:, :, 1], v[:, :, 2], dth, 1 / 255, cs, mask=shape.mask,
                                                      kv_len=kvl, out=out), iters)
     res["online_us"] = round(ms * 1e3, 2)
+    q8 = (torch.randn((B * S, 3 * d), device="cuda", generator=g) * 40).to(torch.float8_e4m3fn)
+    v8 = q8.view(B, S, 3, H, Dh)
+    out8 = torch.empty((B * S, d), dtype=torch.float8_e4m3fn, device="cuda")
+    ms = time_gpu(lambda: hero.hero_fp8_attn(v8[:, :, 0], v8[:, :, 1], v8[:, :, 2], 1.5 / (40 * 40 * Dh ** 0.5), 1 / 448, cs,
+                                             mask=shape.mask, kv_len=kvl, out=out8), iters)
+    res["fp8_two_pass_us"] = round(ms * 1e3, 2)
     return res
 
 
@@ -453,6 +510,9 @@ def main():
             rec["attention"] = attn_variants(hero, shape, args.seed)
         log("[bench] FP8 variant of the FC1 / FC2 GEMMs")
         rec["fp8_gemm"] = fp8_gemm_leg(hero, shape, args.seed)
+        if not decode:
+            log("[bench] FP8 variant of the whole layer")
+            rec["fp8_layer"] = fp8_layer_leg(hero, shape, args.seed)
         log("[bench] measured ceilings (register-only MFMA loop, plain copy)")
         rec["roofline"]["measured_ceilings"] = measured_ceilings(hero)
         log("[bench] GEMM sweep")
