@@ -124,6 +124,28 @@ def test_int8_attn_online_full_size_sampled_heads(hero):
         assert_codes(got[b * S:(b + 1) * S, h * Dh:(h + 1) * Dh][valid], ref[valid], f"online (b,h)=({b},{h})")
 
 
+def test_fp8_attn_full_size_sampled_heads(hero):
+    """hero_fp8_attn at config 2's full size (the launch the bench times): sampled (batch, head) pairs against its
+    oracle in the class derived in parity.assert_fp8_attn_codes."""
+    from parity import assert_fp8_attn_codes
+    shape = synth.CONFIGS[2]
+    B, S, H, Dh, d = shape.B, shape.S, shape.H, shape.Dh, shape.d
+    g = synth.rng(2400)
+    qkv = O.f32_to_e4m3(g.standard_normal((B * S, 3 * d), dtype=np.float32) * np.float32(40))
+    kv_len = synth.kv_lengths(2400, shape)
+    qk_scale, sp = float(np.float32(1.5 / (40 * 40 * np.sqrt(Dh)))), float(OL.S_P_FP8)
+    cs = (g.uniform(0.8, 1.2, d) * sp * 4.0).astype(np.float32)
+    dq = dev(qkv).view(B, S, 3, H, Dh)
+    got = to_np(hero.hero_fp8_attn(dq[:, :, 0], dq[:, :, 1], dq[:, :, 2], qk_scale, sp, dev(cs), mask=shape.mask, kv_len=dev(kv_len)))
+    q5 = qkv.reshape(B, S, 3, H, Dh)
+    for (b, h) in [(0, 0), (B - 1, H - 1), (int(g.integers(0, B)), int(g.integers(0, H)))]:
+        qb, kb, vb = (np.ascontiguousarray(q5[b:b + 1, :, i, h:h + 1]) for i in range(3))
+        ref = O.fp8_attn(qb, kb, vb, qk_scale=qk_scale, p_scale=sp, out_col_scale=cs[h * Dh:(h + 1) * Dh],
+                         mask=shape.mask, kv_len=kv_len[b:b + 1])
+        valid = np.arange(S) < kv_len[b]
+        assert_fp8_attn_codes(got[b * S:(b + 1) * S, h * Dh:(h + 1) * Dh][valid], ref[valid], O.e4m3_to_f32, f"fp8 (b,h)=({b},{h})")
+
+
 def test_fp8_gemm_full_size_sampled_rows(hero):
     """The FP8 GEMMs the bench times (FC1 + GELU^quant, FC2 requant at config 2's size): sampled output rows
     against the oracle's exact-sum definition; the tolerance is the one derived for the FP8 matrix instructions
