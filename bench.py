@@ -61,7 +61,7 @@ def time_gpu(fn, iters, warmup=3):
 class Stack:
     """Device-resident prepared weights + activations of one workload."""
 
-    def __init__(self, hero, shape, seed, mode, layers=None):
+    def __init__(self, hero, shape, seed, mode, layers=None, fp8=False):
         import torch
         from paper_2310_17723_amd import binding as HB, prep, synth
         self.hero, self.shape, self.mode = hero, shape, mode
@@ -81,13 +81,15 @@ class Stack:
         if post:
             xc = torch.nn.functional.layer_norm(xc, (d,), self.emb["g"].double(), self.emb["b"].double(), shape.eps)
         cal_mask = shape.mask if not decode else HB.MASK_CAUSAL
-        self.desc = hero.layer_desc(shape.arch, d, shape.H, shape.Dh, shape.f, shape.eps, shape.mask, mode)
+        self.fp8 = fp8
+        self.desc = hero.layer_desc(shape.arch, d, shape.H, shape.Dh, shape.f, shape.eps, shape.mask,
+                                    mode | (HB.M_FP8 if fp8 else 0))
         self.weights, self.keep = [], []
         for l in range(self.layers):
             p = {k: torch.from_numpy(v).to(dev) for k, v in synth.layer_params(seed, shape, l).items()}
             sc, xc = prep.calibrate(p, xc, shape.arch, shape.H, shape.Dh, shape.eps,
-                                    cal_mask if cal_mask != HB.MASK_PADDING else HB.MASK_NONE, Bc, Sc, hero=hero)
-            t, qk, ps = prep.prepare(p, sc, shape.arch, d, shape.Dh, mode, hero=hero)
+                                    cal_mask if cal_mask != HB.MASK_PADDING else HB.MASK_NONE, Bc, Sc, hero=hero, fp8=fp8)
+            t, qk, ps = prep.prepare(p, sc, shape.arch, d, shape.Dh, mode, hero=hero, fp8=fp8)
             self.keep.append(t)
             self.weights.append(hero.layer_weights(t, qk, ps))
             del p
@@ -99,7 +101,7 @@ class Stack:
         self.ws = torch.empty(hero.hero_layer_workspace_bytes(self.desc, B, S), dtype=torch.uint8, device=dev)
         if post:
             self.x0_q, self.x0_s, _ = hero.hero_ln_quant(h0.to(torch.bfloat16), None, None, None, self.emb["g"],
-                                                         self.emb["b"], shape.eps)
+                                                         self.emb["b"], shape.eps, fp8=fp8)
             self.buf = [(torch.empty_like(self.x0_q), torch.empty_like(self.x0_s)) for _ in range(2)]
         else:
             self.h0 = h0.to(torch.bfloat16)
@@ -112,6 +114,9 @@ class Stack:
             for l in range(self.layers):
                 kc = torch.from_numpy(synth.int8_codes(seed, (B, shape.H, Smax, shape.Dh), stream=2 * l)).to(dev)
                 vc = torch.from_numpy(synth.int8_codes(seed, (B, shape.H, Smax, shape.Dh), stream=2 * l + 1)).to(dev)
+                if fp8:                                   # the bytes are E4M3 codes here: no NaN patterns (0x7F / 0xFF)
+                    for c in (kc, vc):
+                        c[(c & 0x7F) == 0x7F] -= 1
                 self.caches.append((kc, vc))
             # kv_len for every decode step, precomputed: the caller owns the counter
             self.kv_steps = torch.stack([torch.full((B,), shape.cache_len + t + 1, dtype=torch.int32)
@@ -424,6 +429,8 @@ def main():
     ap.add_argument("--layers", type=int, default=None, help="override the stack depth")
     ap.add_argument("--seed", type=int, default=2310)
     ap.add_argument("--no-extras", action="store_true", help="skip the GEMM sweep / LN / CPU legs")
+    ap.add_argument("--fp8", action="store_true",
+                    help="run the stack in the FP8 variant (E4M3 codes in every 8-bit buffer; mode M3 only)")
     ap.add_argument("--graph", action="store_true",
                     help="capture one pass of the stack in a HIP graph and time its replays (launch-bound workloads)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -456,7 +463,10 @@ def main():
     warmup = args.warmup if args.warmup is not None else (1 if decode else 3)
 
     log(f"[bench] preparing {shape.name} ({args.mode}) ...")
-    st = Stack(hero, shape, args.seed, mode, args.layers)
+    if args.fp8 and args.mode != "M3":
+        print("bench.py: --fp8 runs every module in 8 bits (mode M3)", file=sys.stderr)
+        sys.exit(2)
+    st = Stack(hero, shape, args.seed, mode, args.layers, fp8=args.fp8)
     log("[bench] warm-up")
     for _ in range(warmup):
         st.step()
@@ -486,8 +496,8 @@ def main():
     rec = {
         "metric": "W8A8 layer tokens/s", "value": round(value, 1), "unit": "layer-tokens/s",
         "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(ms_per_step, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
-        "config": {"workload": shape.name, "arch": "post-LN" if shape.arch == 0 else "pre-LN", "mode": args.mode,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f8e4m3" if args.fp8 else "int8", "data": "synthetic",
+        "config": {"workload": shape.name, "arch": "post-LN" if shape.arch == 0 else "pre-LN", "mode": args.mode + ("+FP8" if args.fp8 else ""),
                    "layers": st.layers, "batch": shape.B, "seq_len": shape.S, "hidden": shape.d, "heads": shape.H,
                    "ffn": shape.f, "tokens_per_step": st.T * (shape.steps if decode else 1),
                    "mask": ["none", "padding", "causal"][shape.mask], "hip_graph": bool(args.graph)},

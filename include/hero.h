@@ -365,11 +365,15 @@ hero_status hero_bf16_attn(const void* q, const int64_t q_strides[4],
  *   W [K,N] f32 row-major (the paper's W: input rows, output columns), leading dimension ldw;
  *   row_mult f32[K] or NULL (= 1), col_div f32[N] or NULL (= 1); Wt [N,K] int8, leading dimension
  *   ldwt (K contiguous: the operand layout of hero_int8_gemm); col_scale f32[N].
- * Both return HERO_ERR_SHAPE / HERO_ERR_NULL / HERO_ERR_UNSUPPORTED before any launch. */
+ *   hero_weight_fold_quant_fp8: the FP8 variant (Sec. 2.1): the same fold, col_scale[n] = max / 448 and
+ *   Wt[n][k] = e4m3(W~[k][n] / col_scale[n]) (OCP E4M3 bytes: the operand of hero_fp8_gemm).
+ * All return HERO_ERR_SHAPE / HERO_ERR_NULL / HERO_ERR_UNSUPPORTED before any launch. */
 hero_status hero_absmax_cols(const void* x, hero_dtype x_dt, int64_t ldx, int64_t T, int64_t D,
                              float* col_absmax, void* stream);
 hero_status hero_weight_fold_quant(const float* W, int64_t ldw, const float* row_mult, const float* col_div,
                                    int64_t K, int64_t N, int8_t* Wt, int64_t ldwt, float* col_scale, void* stream);
+hero_status hero_weight_fold_quant_fp8(const float* W, int64_t ldw, const float* row_mult, const float* col_div,
+                                       int64_t K, int64_t N, void* Wt, int64_t ldwt, float* col_scale, void* stream);
 
 /* Library build identification: target architecture string, e.g. "gfx950". */
 const char* hero_build_arch(void);

@@ -48,6 +48,7 @@ SYMBOLS = {
     "hero_embed_ln_quant": (i32, [vp, vp, vp, vp, vp, i64, vp, i64, vp, i64, i32, vp, vp, f32, i64, i64, vp, vp, vp]),
     "hero_absmax_cols": (i32, [vp, i32, i64, i64, i64, vp, vp]),
     "hero_weight_fold_quant": (i32, [vp, i64, vp, vp, i64, i64, vp, i64, vp, vp]),
+    "hero_weight_fold_quant_fp8": (i32, [vp, i64, vp, vp, i64, i64, vp, i64, vp, vp]),
     "hero_int8_gemm": (i32, [vp, i64, vp, vp, i64, vp, vp, vp, i32, i64, i32, vp, vp, i32, i64, i64, i64, i64, vp]),
     "hero_fp8_gemm": (i32, [vp, i64, vp, vp, i64, vp, vp, vp, i32, i64, i32, vp, vp, i32, i64, i64, i64, i64, vp]),
     "hero_int8_gemm_workspace_bytes": (C.c_size_t, [i64, i64, i64]),
@@ -154,14 +155,16 @@ class Hero:
                                               _ptr(col_absmax), _stream(stream)))
         return col_absmax
 
-    def hero_weight_fold_quant(self, W, row_mult=None, col_div=None, stream=None):
-        """W [K,N] f32 -> (codes [N,K] int8, col_scale [N] f32) of row_mult[:,None] * W / col_div[None,:]."""
+    def hero_weight_fold_quant(self, W, row_mult=None, col_div=None, stream=None, fp8=False):
+        """W [K,N] f32 -> (codes [N,K] int8, col_scale [N] f32) of row_mult[:,None] * W / col_div[None,:];
+        fp8=True: E4M3 codes (torch.float8_e4m3fn) with scale max / 448 (hero_weight_fold_quant_fp8)."""
         K, N = W.shape
         assert W.dtype == torch.float32 and W.stride(1) == 1
-        Wt = torch.empty((N, K), dtype=torch.int8, device=W.device)
+        Wt = torch.empty((N, K), dtype=torch.float8_e4m3fn if fp8 else torch.int8, device=W.device)
         s = torch.empty(N, dtype=torch.float32, device=W.device)
-        self._check(self.lib.hero_weight_fold_quant(_ptr(W), W.stride(0) if K > 1 else max(N, W.stride(0)), _ptr(row_mult),
-                                                    _ptr(col_div), K, N, _ptr(Wt), K, _ptr(s), _stream(stream)))
+        fn = self.lib.hero_weight_fold_quant_fp8 if fp8 else self.lib.hero_weight_fold_quant
+        self._check(fn(_ptr(W), W.stride(0) if K > 1 else max(N, W.stride(0)), _ptr(row_mult),
+                       _ptr(col_div), K, N, _ptr(Wt), K, _ptr(s), _stream(stream)))
         return Wt, s
 
     # ------------------------------------------------------------------ GeMM^quant

@@ -5,7 +5,8 @@
 //   hero_weight_fold_quant scale folding (Sec. 2.2.2: W~_q = W_q / S_q, W~_o = S_attn W_o / S_o;
 //                          Sec. 2.2.3: W~_2 = S_a W_2 / S_x2) followed by the column-wise weight
 //                          quantization W = W_int8 Diag(S_w) of Sec. 2.1, codes stored [N][K]
-//                          (each output column's K values contiguous: the GEMM's operand layout).
+//                          (each output column's K values contiguous: the GEMM's operand layout);
+//                          hero_weight_fold_quant_fp8: the same with E4M3 codes and scale max / 448.
 // Both are bandwidth-trivial one-off passes; they are written for exactness (the fold runs in fp64,
 // multiply then divide, one cast to fp32, IEEE division by the scale, round half to even) so that the
 // codes are bit-identical to the definition's.
@@ -51,6 +52,8 @@ __global__ __launch_bounds__(256) void fold_absmax_kernel(const float* W, int64_
 }
 
 // pass 2: codes, transposed through LDS: a 64 x 64 tile is read along n (coalesced), written along k
+// F8: E4M3 codes with scale max / 448 (the FP8 variant of Sec. 2.1) instead of INT8 codes with scale max / 127
+template <bool F8>
 __global__ __launch_bounds__(256) void fold_quant_kernel(const float* W, int64_t ldw, const float* row_mult, const float* col_div,
                                                          int K, int N, const float* amax, int8_t* Wt, int64_t ldwt) {
     __shared__ int8_t tile[64][64 + 4];                           // [n][k]
@@ -58,11 +61,15 @@ __global__ __launch_bounds__(256) void fold_quant_kernel(const float* W, int64_t
     const int tn = threadIdx.x & 63, tk = threadIdx.x >> 6;       // 4 k-rows per sweep
     const int n = n0 + tn;
     float sc = 1.0f;
-    if (n < N) { const float a = amax[n]; sc = a == 0.0f ? 1.0f : __fdiv_rn(a, 127.0f); }
+    if (n < N) { const float a = amax[n]; sc = a == 0.0f ? 1.0f : __fdiv_rn(a, F8 ? 448.0f : 127.0f); }
     for (int kk = tk; kk < 64; kk += 4) {
         const int k = k0 + kk;
         int code = 0;
-        if (n < N && k < K) code = quant_code_div(folded(W, ldw, row_mult, col_div, k, n), sc);
+        if (n < N && k < K) {
+            const float w = folded(W, ldw, row_mult, col_div, k, n);
+            if (F8) code = (int)(fp8x4_sat(__fdiv_rn(w, sc), 0.0f, 0.0f, 0.0f) & 0xffu);
+            else code = quant_code_div(w, sc);
+        }
         tile[tn][kk] = (int8_t)code;
     }
     __syncthreads();
@@ -72,9 +79,9 @@ __global__ __launch_bounds__(256) void fold_quant_kernel(const float* W, int64_t
 }
 
 // pass 3: amax -> scale, in place
-__global__ void amax_to_scale_kernel(float* s, int N) {
+__global__ void amax_to_scale_kernel(float* s, int N, float qmax) {
     const int n = blockIdx.x * blockDim.x + threadIdx.x;
-    if (n < N) { const float a = s[n]; s[n] = a == 0.0f ? 1.0f : __fdiv_rn(a, 127.0f); }
+    if (n < N) { const float a = s[n]; s[n] = a == 0.0f ? 1.0f : __fdiv_rn(a, qmax); }
 }
 
 __global__ void fill_f32_kernel(float* p, int n, float v) {
@@ -104,8 +111,9 @@ extern "C" hero_status hero_absmax_cols(const void* x, hero_dtype x_dt, int64_t 
     return hero_launch_status();
 }
 
-extern "C" hero_status hero_weight_fold_quant(const float* W, int64_t ldw, const float* row_mult, const float* col_div,
-                                              int64_t K, int64_t N, int8_t* Wt, int64_t ldwt, float* col_scale, void* stream) {
+namespace {
+hero_status weight_fold_quant_entry(const float* W, int64_t ldw, const float* row_mult, const float* col_div,
+                                    int64_t K, int64_t N, int8_t* Wt, int64_t ldwt, float* col_scale, bool fp8, void* stream) {
     if (K <= 0 || N <= 0 || K > 0x7fffffffLL || N > 0x7fffffffLL || ldw < N || ldwt < K) return HERO_ERR_SHAPE;
     if ((N + 63) / 64 > 0x7fffffffLL || (K + 63) / 64 > 65535) return HERO_ERR_SHAPE;
     if (!W || !Wt || !col_scale) return HERO_ERR_NULL;
@@ -118,8 +126,20 @@ extern "C" hero_status hero_weight_fold_quant(const float* W, int64_t ldw, const
     if (ranges > 65535) { ranges = 65535; rpb = (K + ranges - 1) / ranges; }
     hipLaunchKernelGGL(fold_absmax_kernel, dim3((unsigned)((N + 255) / 256), (unsigned)ranges), dim3(256), 0, st,
                        W, ldw, row_mult, col_div, (int)K, (int)N, col_scale, (int)rpb);
-    hipLaunchKernelGGL(fold_quant_kernel, dim3((unsigned)((N + 63) / 64), (unsigned)((K + 63) / 64)), dim3(256), 0, st,
-                       W, ldw, row_mult, col_div, (int)K, (int)N, col_scale, Wt, ldwt);
-    hipLaunchKernelGGL(amax_to_scale_kernel, dim3((unsigned)((N + 255) / 256)), dim3(256), 0, st, col_scale, (int)N);
+    const dim3 qgrid((unsigned)((N + 63) / 64), (unsigned)((K + 63) / 64));
+    if (fp8) hipLaunchKernelGGL(fold_quant_kernel<true>, qgrid, dim3(256), 0, st, W, ldw, row_mult, col_div, (int)K, (int)N, col_scale, Wt, ldwt);
+    else hipLaunchKernelGGL(fold_quant_kernel<false>, qgrid, dim3(256), 0, st, W, ldw, row_mult, col_div, (int)K, (int)N, col_scale, Wt, ldwt);
+    hipLaunchKernelGGL(amax_to_scale_kernel, dim3((unsigned)((N + 255) / 256)), dim3(256), 0, st, col_scale, (int)N, fp8 ? 448.0f : 127.0f);
     return hero_launch_status();
+}
+}  // namespace
+
+extern "C" hero_status hero_weight_fold_quant(const float* W, int64_t ldw, const float* row_mult, const float* col_div,
+                                              int64_t K, int64_t N, int8_t* Wt, int64_t ldwt, float* col_scale, void* stream) {
+    return weight_fold_quant_entry(W, ldw, row_mult, col_div, K, N, Wt, ldwt, col_scale, false, stream);
+}
+
+extern "C" hero_status hero_weight_fold_quant_fp8(const float* W, int64_t ldw, const float* row_mult, const float* col_div,
+                                                  int64_t K, int64_t N, void* Wt, int64_t ldwt, float* col_scale, void* stream) {
+    return weight_fold_quant_entry(W, ldw, row_mult, col_div, K, N, (int8_t*)Wt, ldwt, col_scale, true, stream);
 }

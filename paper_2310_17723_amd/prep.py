@@ -62,27 +62,30 @@ def reference_layer(p, x, arch, H, Dh, eps, mask, B, S, kv_len=None):
     return t
 
 
-def _scale(a, dim=None):
+def _scale(a, dim=None, qmax=127.0):
     m = a.abs().amax() if dim is None else a.abs().amax(dim=dim)
-    m = torch.where(m == 0, torch.full_like(m, 127.0), m)
-    return (m / 127.0).float()
+    m = torch.where(m == 0, torch.full_like(m, qmax), m)
+    return (m / qmax).float()
 
 
-def calibrate(p, x_calib, arch, H, Dh, eps, mask, B, S, kv_len=None, hero=None):
+def calibrate(p, x_calib, arch, H, Dh, eps, mask, B, S, kv_len=None, hero=None, fp8=False):
     """Static scales: SQ scalars for X_q, X_k, X_v; FWQ vectors for X_attn, X_o, A, X_2.  With `hero` (the
-    loaded library) the column maxima come from hero_absmax_cols (a maximum is exact in any precision)."""
+    loaded library) the column maxima come from hero_absmax_cols (a maximum is exact in any precision).
+    fp8: the FP8 variant (Sec. 2.1): ranges are mapped to the largest E4M3 value 448, S_p = 1/448."""
     t = reference_layer(p, x_calib, arch, H, Dh, eps, mask, B, S, kv_len)
+    qmax = 448.0 if fp8 else 127.0
     if hero is not None:
         def scale(a, dim=None):
             m = hero.hero_absmax_cols(a.float().contiguous()).double()
             m = m.amax() if dim is None else m
-            m = torch.where(m == 0, torch.full_like(m, 127.0), m)
-            return (m / 127.0).float()
+            m = torch.where(m == 0, torch.full_like(m, qmax), m)
+            return (m / qmax).float()
     else:
-        scale = _scale
+        scale = lambda a, dim=None: _scale(a, dim, qmax)
     sc = {"S_q": scale(t["q"]), "S_k": scale(t["k"]), "S_v": scale(t["v"]),
           "S_attn": scale(t["attn"], 0), "S_o": scale(t["o"], 0), "S_a": scale(t["a"], 0),
-          "S_x2": scale(t["x2"], 0), "S_p": torch.tensor(1.0 / 255.0, dtype=torch.float32, device=x_calib.device)}
+          "S_x2": scale(t["x2"], 0),
+          "S_p": torch.tensor(1.0 / 448.0 if fp8 else 1.0 / 255.0, dtype=torch.float32, device=x_calib.device)}
     return sc, t["out"]
 
 
@@ -96,18 +99,21 @@ def quantize_columns(W):
     return q.t().contiguous(), s.contiguous()
 
 
-def prepare(p, sc, arch, d, Dh, mode=HB.MODE_M3, hero=None):
+def prepare(p, sc, arch, d, Dh, mode=HB.MODE_M3, hero=None, fp8=False):
     """Fold the static scales into the weights and quantize.  Returns (tensors, qk_scale,
     p_scale): `tensors` is keyed by the field names of hero_layer_weights.  With `hero` (the loaded
-    library) the fold + column-wise quantization runs in hero_weight_fold_quant on the weights' device."""
+    library) the fold + column-wise quantization runs in hero_weight_fold_quant on the weights' device.
+    fp8 (needs `hero`, mode M3, scales from calibrate(fp8=True)): E4M3 weights for a layer run with M_FP8."""
     P = {k: v.double() for k, v in p.items()}
     post = arch == HB.ARCH_POST_LN
     t = {}
+    if fp8 and (hero is None or mode != HB.MODE_M3):
+        raise ValueError("the FP8 variant is prepared on the GPU and runs every module in 8 bits")
     if hero is not None:
         f32 = lambda a: None if a is None else a.float().contiguous()
 
         def quantize_folded(name, rm, cd):
-            return hero.hero_weight_fold_quant(p[name].float().contiguous(), f32(rm), f32(cd))
+            return hero.hero_weight_fold_quant(p[name].float().contiguous(), f32(rm), f32(cd), fp8=fp8)
     else:
         def quantize_folded(name, rm, cd):
             W = P[name]

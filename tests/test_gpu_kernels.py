@@ -159,6 +159,11 @@ def test_weight_fold_quant_bit_exact(hero, K, N):
         q, s = hero.hero_weight_fold_quant(dev(W), dev(a), dev(b))
         assert_exact(to_np(s), s_o, "column scales")
         assert_exact(to_np(q), q_o, "codes")
+        # the FP8 variant: E4M3 codes, scale max / 448, the same fold: bit-exact as well
+        q_o, s_o = O.weight_fold_quant_fp8(W, a, b)
+        q, s = hero.hero_weight_fold_quant(dev(W), dev(a), dev(b), fp8=True)
+        assert_exact(to_np(s), s_o, "fp8 column scales")
+        assert_exact(to_np(q), q_o, "fp8 codes")
     # a strided view (leading dimension > N)
     Wbig = dev(np.concatenate([W, W], axis=1))
     q, s = hero.hero_weight_fold_quant(Wbig[:, :N], dev(rm), dev(cd))
