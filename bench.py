@@ -30,7 +30,7 @@ sys.path.insert(0, ROOT)
 # profiles/.  Keyed by (M, N, K) of the FC1 GeMM^quant; anything else reports null.
 MEASURED_TRAFFIC = {
     # profiles/bert-large_kernels_hbm_traffic_pmc.txt: fetch 47583.7 KiB x 2.00 (copy calibration), write 65539.5 KiB x 1.00
-    (16384, 4096, 1024): {"fetch_bytes": 97441604, "write_bytes": 67112448},
+    (16384, 4096, 1024): {"fetch_bytes": 97467201, "write_bytes": 67112038},
 }
 
 PEAK_INT8_TOPS = 5000.0      # MI355X dense INT8 MFMA, TOP/s
