@@ -146,8 +146,9 @@ hero_status hero_int8_gemm(const int8_t* A, int64_t lda, const float* a_row_scal
                            int64_t M, int64_t N, int64_t K, void* stream);
 
 /* The same GeMM^quant (Sec. 2.1, 2.2.2, 2.2.3; identical arguments, results and constraints) with a
- * caller-owned scratch buffer for skinny problems (M <= 128, the decode step): K is split over
- * several workgroups per output tile so that every CU streams a share of the weights; the exact
+ * caller-owned scratch buffer for skinny problems with a long K (M <= 128, K >= 8192, few output tiles:
+ * the widest linear of a decode step): K is split over several workgroups per output tile so that
+ * every CU streams a share of the weights; the exact
  * int32 partial sums go through the scratch and a second kernel adds them and applies the
  * epilogue, so the result does not depend on the split.
  *   hero_int8_gemm_workspace_bytes(M, N, K): bytes of scratch this shape can use (0: it would not

@@ -831,8 +831,8 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void int8_gemm_persistent_kernel(G
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));                      // the redundant tail loads
 }
 
-// Split-K for skinny M (M <= 128: the weights are streamed once and too few tiles exist to do that from
-// every CU).  Pass 1: the register-staged kernel with a second grid dimension over K ranges writes raw int32
+// Split-K for skinny M with a long K (M <= 128, K >= 8192, at most 128 tiles: the weights are streamed once and
+// too few tiles exist to do that from every CU).  Pass 1: the register-staged kernel with a second grid dimension over K ranges writes raw int32
 // partial sums, one [M][ldp] plane per range, into the caller's scratch.  Pass 2 (splitk_reduce_kernel) adds
 // the planes and runs the epilogue.  Integer sums commute and the epilogue arithmetic is the same, in the
 // same order, as in the one-pass kernels, so the results are identical; the kernel boundary is the only
@@ -843,7 +843,11 @@ inline SplitK splitk_plan(int64_t M, int64_t N, int64_t K) {
     if (M <= 0 || N <= 0 || M > 128 || K % BK != 0) return p;
     p.BM = p.BN = M <= 64 ? 64 : 128;
     const int64_t tiles = ((M + p.BM - 1) / p.BM) * ((N + p.BN - 1) / p.BN), kt = K / BK;
-    if (tiles >= 384 || kt < 8 || N * K < (4 << 20)) return p;         // small weights: one pass is launch-bound anyway
+    // Measured: two launches pay only for a long K over few tiles (64 x 4096 x 16384: 20 us against 31 in one pass);
+    // with K = 4096 the one-pass kernels (four K groups per workgroup up to 128 tiles, plain 64 x 64 tiles beyond)
+    // are 20-35 % faster than the split (64 x 12288 x 4096: 15.4 against 20.1 us), and small weights are
+    // launch-bound anyway.
+    if (tiles > 128 || kt < 128 || N * K < (4 << 20)) return p;
     int64_t want = (512 + tiles - 1) / tiles;                         // about two workgroups per CU
     if (want > 16) want = 16;
     int64_t kslabs = (kt + want - 1) / want;
