@@ -252,8 +252,8 @@ hero_status hero_int8_attn_online(const int8_t* q, const int64_t q_strides[4],
  *   out_dt HERO_F16 / HERO_BF16: acc[e] * out_col_scale[0]  (out_scale_is_scalar must be 1)
  * Masks, kv_len, constraints (Dh 64 or 128, strides multiples of 16, 16-byte aligned bases, ldo) and
  * errors as for hero_int8_attn; the 8-bit output type is HERO_F8E4M3 (HERO_I8 -> HERO_ERR_UNSUPPORTED).
- * A query with no visible key outputs 0.  Any Sq runs through the same kernel (a one-query decode
- * call is served but not specialised).  The matrix cores add the 8 products of a lane group with 13
+ * A query with no visible key outputs 0.  A one-query call (Sq == 1, Skv <= 16384) takes the
+ * cache-streaming kernel, as for INT8 (fp32 sums on the vector ALU there).  The matrix cores add the 8 products of a lane group with 13
  * fractional bits below the largest of them, so results agree with an exactly accumulated reference
  * up to an adjacent E4M3 code on a small fraction of the outputs, not bit for bit. */
 hero_status hero_fp8_attn(const void* q, const int64_t q_strides[4],

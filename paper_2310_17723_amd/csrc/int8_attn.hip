@@ -501,14 +501,18 @@ __global__ __launch_bounds__(256, ONLINE ? (DH == 64 ? 3 : 2) : (DH == 64 ? 4 : 
 // ------------------------------------------------------------------------------------------
 constexpr int DEC_MAX_KEYS = 16384;
 
-template <int DH, int ODT>
+// FMT = HERO_F8E4M3: E4M3 operands: the bytes are decoded two at a time (v_cvt_pk_f32_fp8), scores and PV sums are
+// fp32, the probability code is e4m3(min(p / S_p, 448)) and its decoded value is what PV multiplies.
+template <int DH, int ODT, int FMT = HERO_I8>
 __global__ __launch_bounds__(256) void int8_attn_decode_kernel(AttnArgs a) {
+    constexpr bool F8 = FMT == HERO_F8E4M3;
+    using ST = typename std::conditional<F8, float, int>::type;      // score / accumulator element
     constexpr int LPK = DH / 16;                 // lanes per key
     constexpr int KPI = 256 / LPK;               // keys per block iteration
     extern __shared__ __attribute__((aligned(16))) int smem_dec[];
-    int* sc = smem_dec;                                            // [len] scores, later codes
+    ST* sc = reinterpret_cast<ST*>(smem_dec);                      // [len] scores, later codes (F8: their decoded values)
     __shared__ float red[8];
-    __shared__ int racc[KPI][DH + 4];
+    __shared__ ST racc[KPI][DH + 4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int b = blockIdx.y, h = blockIdx.x;
     const int len = a.kv_len ? min(max(a.kv_len[b], 0), a.Skv) : a.Skv;     // one query: it sees every valid key
@@ -516,16 +520,34 @@ __global__ __launch_bounds__(256) void int8_attn_decode_kernel(AttnArgs a) {
     const int8_t* kbase = a.k + (int64_t)b * a.ks[0] + (int64_t)h * a.ks[2] + sub * 16;
     const int8_t* vbase = a.v + (int64_t)b * a.vs[0] + (int64_t)h * a.vs[2] + sub * 16;
     const v4i qv = *reinterpret_cast<const v4i*>(a.q + (int64_t)b * a.qs[0] + (int64_t)h * a.qs[2] + sub * 16);
+    // 16 E4M3 bytes -> 16 floats
+    auto decode16 = [](const v4i& w, float (&f)[16]) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const auto lo = __builtin_amdgcn_cvt_pk_f32_fp8(w[i], false), hi = __builtin_amdgcn_cvt_pk_f32_fp8(w[i], true);
+            f[4 * i] = lo[0]; f[4 * i + 1] = lo[1]; f[4 * i + 2] = hi[0]; f[4 * i + 3] = hi[1];
+        }
+    };
+    float qf[16];
+    if constexpr (F8) decode16(qv, qf);
 
     // ---- phase 1: scores ---------------------------------------------------------------------
-    int lmax = -0x40000000;
+    constexpr float FMASKED = -3.0e38f;
+    ST lmax = F8 ? (ST)FMASKED : (ST)-0x40000000;
     for (int k0 = 0; k0 < len; k0 += KPI) {
         const int key = k0 + kg;
         v4i kv = {0, 0, 0, 0};
         if (key < len) kv = *reinterpret_cast<const v4i*>(kbase + (int64_t)key * a.ks[1]);
-        int d = 0;
+        ST d = 0;
+        if constexpr (F8) {
+            float kf[16];
+            decode16(kv, kf);
 #pragma unroll
-        for (int w = 0; w < 4; ++w) d = __builtin_amdgcn_sdot4(kv[w], qv[w], d, false);
+            for (int e = 0; e < 16; ++e) d = fmaf(kf[e], qf[e], d);
+        } else {
+#pragma unroll
+            for (int w = 0; w < 4; ++w) d = __builtin_amdgcn_sdot4(kv[w], qv[w], d, false);
+        }
 #pragma unroll
         for (int o = 1; o < LPK; o <<= 1) d += __shfl_xor(d, o);
         if (sub == 0 && key < len) { sc[key] = d; lmax = max(lmax, d); }
@@ -533,11 +555,12 @@ __global__ __launch_bounds__(256) void int8_attn_decode_kernel(AttnArgs a) {
     // block max
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) lmax = max(lmax, __shfl_xor(lmax, o));
-    if (lane == 0) red[wave] = __int_as_float(lmax);
+    if (lane == 0) red[wave] = F8 ? (float)lmax : __int_as_float((int)lmax);
     __syncthreads();
-    const int imax = max(max(__float_as_int(red[0]), __float_as_int(red[1])), max(__float_as_int(red[2]), __float_as_int(red[3])));
     const float c2 = a.qk_scale * 1.44269504088896340736f;
-    const float m2 = (float)imax * c2;
+    float m2;
+    if constexpr (F8) m2 = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3])) * c2;
+    else m2 = (float)max(max(__float_as_int(red[0]), __float_as_int(red[1])), max(__float_as_int(red[2]), __float_as_int(red[3]))) * c2;
     // ---- phase 2: sum, then codes --------------------------------------------------------------
     float lsum = 0.0f;
     for (int k = tid; k < len; k += 256) lsum += __builtin_amdgcn_exp2f(fmaf((float)sc[k], c2, -m2));
@@ -549,32 +572,41 @@ __global__ __launch_bounds__(256) void int8_attn_decode_kernel(AttnArgs a) {
     const float off = l > 0.0f ? -m2 - __log2f(l * a.p_scale) : -INFINITY;
     for (int k = tid; k < len; k += 256) {
         const float e = __builtin_amdgcn_exp2f(fmaf((float)sc[k], c2, off));
-        sc[k] = (int)__builtin_amdgcn_cvt_pk_u8_f32(e, 0, 0u);
+        if constexpr (F8) sc[k] = __builtin_amdgcn_cvt_f32_fp8(__builtin_amdgcn_cvt_pk_fp8_f32(fminf(e, 448.0f), 0.0f, 0, false), 0);
+        else sc[k] = (int)__builtin_amdgcn_cvt_pk_u8_f32(e, 0, 0u);
     }
     __syncthreads();
     // ---- phase 3: PV ------------------------------------------------------------------------------
-    int acc[16];
+    ST acc[16];
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc[e] = 0;
     for (int k0 = 0; k0 < len; k0 += KPI) {
         const int key = k0 + kg;
         if (key < len) {
             const v4i vv = *reinterpret_cast<const v4i*>(vbase + (int64_t)key * a.vs[1]);
-            const int p = sc[key];
+            const ST p = sc[key];
+            if constexpr (F8) {
+                float vf[16];
+                decode16(vv, vf);
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[e] += p * (int)(int8_t)(vv[e >> 2] >> (8 * (e & 3)));
+                for (int e = 0; e < 16; ++e) acc[e] = fmaf(p, vf[e], acc[e]);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[e] += p * (int)(int8_t)(vv[e >> 2] >> (8 * (e & 3)));
+            }
         }
     }
 #pragma unroll
     for (int e = 0; e < 16; ++e) racc[kg][sub * 16 + e] = acc[e];
     __syncthreads();
     if (tid < DH) {
-        int tot = 0;
+        ST tot = 0;
         for (int g = 0; g < KPI; ++g) tot += racc[g][tid];
         const float scl = a.scale_is_scalar ? a.out_col_scale[0] : a.out_col_scale[h * DH + tid];
         const float y = (float)tot * scl;
         const int64_t oidx = (int64_t)b * a.ldo + (int64_t)h * DH + tid;
         if (ODT == HERO_I8) ((int8_t*)a.out)[oidx] = (int8_t)(rne_low_byte(__builtin_amdgcn_fmed3f(y, -127.0f, 127.0f)) & 0xff);
+        else if (ODT == HERO_F8E4M3) ((uint8_t*)a.out)[oidx] = (uint8_t)(fp8x4_sat(y, 0.0f, 0.0f, 0.0f) & 0xffu);
         else ((uint16_t*)a.out)[oidx] = (uint16_t)f32_to_hp<ODT>(y);
     }
 }
@@ -643,20 +675,24 @@ hero_status attn_entry(const int8_t* q, const int64_t q_strides[4],
         hipLaunchKernelGGL(zero_rows_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (int8_t*)out, bytes);
         return hero_launch_status();
     }
-    if (fp8) return Dh == 64 ? launch<64, false, HERO_F8E4M3>(a, out_dt, st) : launch<128, false, HERO_F8E4M3>(a, out_dt, st);
     if (online) return Dh == 64 ? launch<64, true>(a, out_dt, st) : launch<128, true>(a, out_dt, st);
     if (Sq == 1 && Skv <= DEC_MAX_KEYS) {          // decode: the cache-streaming kernel
         dim3 grid((unsigned)H, (unsigned)B), block(256);
         const size_t lds = (size_t)Skv * sizeof(int);
-#define HERO_DEC(DH_, ODT_) do { \
-            if (lds > 32768 && hipFuncSetAttribute((const void*)int8_attn_decode_kernel<DH_, ODT_>, \
+#define HERO_DEC(DH_, ODT_, FMT_) do { \
+            if (lds > 32768 && hipFuncSetAttribute((const void*)int8_attn_decode_kernel<DH_, ODT_, FMT_>, \
                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) return HERO_ERR_LAUNCH; \
-            hipLaunchKernelGGL((int8_attn_decode_kernel<DH_, ODT_>), grid, block, lds, st, a); } while (0)
-        if (Dh == 64) { if (out_dt == HERO_I8) HERO_DEC(64, HERO_I8); else if (out_dt == HERO_BF16) HERO_DEC(64, HERO_BF16); else HERO_DEC(64, HERO_F16); }
-        else { if (out_dt == HERO_I8) HERO_DEC(128, HERO_I8); else if (out_dt == HERO_BF16) HERO_DEC(128, HERO_BF16); else HERO_DEC(128, HERO_F16); }
+            hipLaunchKernelGGL((int8_attn_decode_kernel<DH_, ODT_, FMT_>), grid, block, lds, st, a); } while (0)
+#define HERO_DEC_DT(DH_, FMT_) do { \
+            if (out_dt == HERO_BF16) HERO_DEC(DH_, HERO_BF16, FMT_); else if (out_dt == HERO_F16) HERO_DEC(DH_, HERO_F16, FMT_); \
+            else HERO_DEC(DH_, FMT_, FMT_); } while (0)
+        if (fp8) { if (Dh == 64) HERO_DEC_DT(64, HERO_F8E4M3); else HERO_DEC_DT(128, HERO_F8E4M3); }
+        else { if (Dh == 64) HERO_DEC_DT(64, HERO_I8); else HERO_DEC_DT(128, HERO_I8); }
+#undef HERO_DEC_DT
 #undef HERO_DEC
         return hero_launch_status();
     }
+    if (fp8) return Dh == 64 ? launch<64, false, HERO_F8E4M3>(a, out_dt, st) : launch<128, false, HERO_F8E4M3>(a, out_dt, st);
     return Dh == 64 ? launch<64>(a, out_dt, st) : launch<128>(a, out_dt, st);
 }
 

@@ -284,7 +284,7 @@ __device__ __forceinline__ void epilogue_direct(const GemmArgs& g, ACC (&acc)[BM
 template <int BM, int BN, int WM, int WN, int PD, int MINW, int EPI, int CDT, int RDT, bool SPLITK = false, int KG = 1, int ADT = HERO_I8>
 __global__ __launch_bounds__(WM * WN * 64 * KG, MINW) void int8_gemm_kernel(GemmArgs g) {
     using ACC = typename AccOf<ADT>::type;
-    static_assert(ADT == HERO_I8 || (!SPLITK && KG == 1), "split K: integer partial sums only");
+    static_assert(ADT == HERO_I8 || !SPLITK, "split K over workgroups: integer partial sums only");
     constexpr int NT = WM * WN * 64;                          // threads of one K group
     constexpr int CPR = BK / 16;                              // 16-byte chunks per slab row
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;      // 32x32 MFMA tiles per wave
@@ -421,27 +421,29 @@ __global__ __launch_bounds__(WM * WN * 64 * KG, MINW) void int8_gemm_kernel(Gemm
     };
     for (; kt + PD <= KT; kt += PD) trip(std::true_type{});
     if (kt < KT) trip(std::false_type{});
-    if constexpr (KG > 1 && ADT == HERO_I8) {
+    if constexpr (KG > 1) {
         // groups 1 .. KG-1 hand their accumulators to group 0 (register-major, lane-minor: no bank conflicts);
-        // the loop's last barrier has released every group's slab buffers
+        // the loop's last barrier has released every group's slab buffers.  Integer sums are exact in any order;
+        // the fp32 sums of the FP8 variant are added in the fixed order group 0, 1, .., KG-1.
+        using V4 = typename std::conditional<ADT == HERO_I8, v4i, v4f>::type;
         constexpr int NV = TM * TN * 4;
-        v4i* const mine = reinterpret_cast<v4i*>(smem + kg * POOL) + (wave * NV) * 64 + lane;
+        V4* const mine = reinterpret_cast<V4*>(smem + kg * POOL) + (wave * NV) * 64 + lane;
         if (kg > 0) {
 #pragma unroll
             for (int v = 0; v < NV; ++v) {
                 const int ij = v >> 2, c = (v & 3) * 4;
-                mine[v * 64] = v4i{acc[ij / TN][ij % TN][c], acc[ij / TN][ij % TN][c + 1], acc[ij / TN][ij % TN][c + 2], acc[ij / TN][ij % TN][c + 3]};
+                mine[v * 64] = V4{acc[ij / TN][ij % TN][c], acc[ij / TN][ij % TN][c + 1], acc[ij / TN][ij % TN][c + 2], acc[ij / TN][ij % TN][c + 3]};
             }
         }
         __syncthreads();
         if (kg > 0) return;
 #pragma unroll
         for (int k = 1; k < KG; ++k) {
-            const v4i* other = reinterpret_cast<const v4i*>(smem + k * POOL) + (wave * NV) * 64 + lane;
+            const V4* other = reinterpret_cast<const V4*>(smem + k * POOL) + (wave * NV) * 64 + lane;
 #pragma unroll
             for (int v = 0; v < NV; ++v) {
                 const int ij = v >> 2, c = (v & 3) * 4;
-                const v4i o = other[v * 64];
+                const V4 o = other[v * 64];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) acc[ij / TN][ij % TN][c + e] += o[e];
             }
@@ -1065,8 +1067,14 @@ hero_status launch_epi_fp8(GemmArgs g, hipStream_t st) {
         else hipLaunchKernelGGL((int8_gemm_persistent_kernel<256, 256, 2, 4, 4, EPI, CDT, RDT, HERO_F8E4M3>), dim3((unsigned)(nslot * NUM_XCD)), dim3(512), 0, st, g);
         return hero_launch_status();
     }
-    if (small && cfg != 0)
+    if (small && cfg != 0) {
+        // few tiles and a long K: four groups of waves per workgroup split K, as for INT8 operands
+        const int64_t t64 = (int64_t)((g.M + 63) / 64) * ((g.N + 63) / 64);
+        const int kt = g.K / BK;
+        if (t64 <= 128 && kt >= 32 && kt % 4 == 0)
+            return launch_grid(g, 64, 64, 1024, int8_gemm_kernel<64, 64, 2, 2, 2, 1, EPI, CDT, RDT, false, 4, HERO_F8E4M3>, st);
         return launch_grid(g, 64, 64, 256, int8_gemm_kernel<64, 64, 2, 2, 2, 2, EPI, CDT, RDT, false, 1, HERO_F8E4M3>, st);
+    }
     return launch_grid(g, 128, 128, 256, int8_gemm_kernel<128, 128, 2, 2, 2, 2, EPI, CDT, RDT, false, 1, HERO_F8E4M3>, st);
 }
 

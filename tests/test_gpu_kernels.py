@@ -543,12 +543,14 @@ def test_gemm_full_size_sampled_rows(hero, M, N, K):
 
 # ============================================================ FP8 variant
 @pytest.mark.parametrize("M,N,K,tile", [(200, 136, 256, None), (64, 72, 192, None), (300, 520, 1024, None), (3300, 3400, 384, None),
-                                         (3300, 3400, 384, "8"), (2500, 2600, 256, None), (2500, 2600, 256, "7")])
+                                         (3300, 3400, 384, "8"), (2500, 2600, 256, None), (2500, 2600, 256, "7"),
+                                         (100, 264, 2304, None)])
 def test_fp8_gemm_matches_oracle(hero, M, N, K, tile, monkeypatch):
     """hero_fp8_gemm (Sec. 2.1: FP8 as the 8-bit format): E4M3 operands, fp32 accumulation on the matrix cores
     (the oracle carries the exact sum), the INT8 path's epilogue.  16-bit outputs within 2e-2, E4M3 outputs equal
     up to an adjacent code on <= 0.5 %.  The large shapes run the persistent kernels with ragged edges: by
-    default the 256 x 256 one (182 tiles) and the 128 x 128 one (110 tiles of 256 x 256), then each the other one."""
+    default the 256 x 256 one (182 tiles) and the 128 x 128 one (110 tiles of 256 x 256), then each the other one.
+    The last shape (few tiles, K = 2304) runs the workgroup with four K groups: fp32 partial sums added through LDS."""
     if tile is None:
         monkeypatch.delenv("HERO_FP8_TILE", raising=False)
     else:
