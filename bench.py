@@ -44,18 +44,30 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def time_gpu(fn, iters, warmup=3):
+def time_gpu(fn, iters, warmup=3, graph=False):
+    """ms per call of fn, HIP events around `iters` back-to-back calls.  graph=True: the calls are captured into a
+    HIP graph once and the replay is timed, so a short kernel is not hidden behind the ~10 us one call costs on the
+    host (Python -> ctypes -> launch); nothing in the library allocates or clears memory, so its calls capture as
+    they are."""
     import torch
     for _ in range(warmup):
         fn()
     torch.cuda.synchronize()
+    run, per = (lambda: [fn() for _ in range(iters)]), iters
+    if graph:
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for _ in range(iters):
+                fn()
+        g.replay()
+        torch.cuda.synchronize()
+        run = g.replay
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
-    for _ in range(iters):
-        fn()
+    run()
     e1.record()
     torch.cuda.synchronize()
-    return e0.elapsed_time(e1) / iters      # ms per call
+    return e0.elapsed_time(e1) / per      # ms per call
 
 
 class Stack:
@@ -205,7 +217,7 @@ def gemm_sweep(hero, seed, iters=10):
             rs, cs, bias = (torch.from_numpy(c[k]).cuda() for k in ("a_row_scale", "b_col_scale", "bias"))
             for name, epi, dt in (("fp16", HB.EPI_DEQUANT, torch.float16), ("int8", HB.EPI_REQUANT, torch.int8)):
                 out = torch.empty((M, N), dtype=dt, device="cuda")
-                ms = time_gpu(lambda: hero.hero_int8_gemm(A, Bt, rs, cs, bias, epi=epi, C_out=out), iters)
+                ms = time_gpu(lambda: hero.hero_int8_gemm(A, Bt, rs, cs, bias, epi=epi, C_out=out), iters, graph=True)
                 tops = 2.0 * M * N * K / (ms * 1e-3) / 1e12
                 rows.append({"M": M, "K": K, "N": N, "out": name, "us": round(ms * 1e3, 2), "tops": round(tops, 1),
                              "frac_peak": round(tops / PEAK_INT8_TOPS, 4)})
