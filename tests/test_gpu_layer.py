@@ -201,6 +201,40 @@ def test_layer_fp8_needs_every_module_8bit(hero):
     assert hero.hero_layer_workspace_bytes(_desc(hero, shape, HB.MODE_M3 | HB.M_FP8), 2, 8) > 0
 
 
+@pytest.mark.parametrize("arch", [synth.POST_LN, synth.PRE_LN])
+@pytest.mark.parametrize("fp8", [False, True])
+def test_gpu_preparation_matches_the_oracles(hero, arch, fp8):
+    """paper_2310_17723_amd.prep (what bench.py prepares its stacks with: the unquantized layer in torch fp64 on the
+    GPU, hero_absmax_cols, hero_weight_fold_quant[_fp8]) against the oracle's calibrate / prepare on the same
+    parameters and calibration tokens: the static scales agree to fp32 rounding, the folded weight codes are the same
+    (a scale that differs in its last bit may move a code at a rounding boundary), biases and attention scalars
+    agree to fp32 rounding."""
+    from paper_2310_17723_amd import prep
+    shape = _shape(arch, synth.MASK_CAUSAL if arch == synth.PRE_LN else synth.MASK_NONE, S=64)
+    B, S, d = 2 * shape.B, shape.S, shape.d
+    p = synth.layer_params(61, shape)
+    emb = synth.embedding_ln_params(61, shape)
+    hc = synth.activations(61, shape, B * S, stream=1).astype(np.float64)
+    if arch == synth.POST_LN:
+        hc = OL._ln64(hc, emb["g"].astype(np.float64), emb["b"].astype(np.float64), shape.eps)
+    sc_o, _ = OL.calibrate(p, hc, shape, B, S, fp8=fp8)
+    w_o = OL.prepare(p, sc_o, shape, OL.MODE_M3, fp8=fp8)
+    pt = {k: torch.from_numpy(v).cuda() for k, v in p.items()}
+    sc_g, _ = prep.calibrate(pt, torch.from_numpy(hc).cuda(), shape.arch, shape.H, shape.Dh, shape.eps, shape.mask, B, S,
+                             hero=hero, fp8=fp8)
+    for k in ("S_q", "S_k", "S_v", "S_attn", "S_o", "S_a", "S_x2", "S_p"):
+        np.testing.assert_allclose(sc_g[k].cpu().numpy(), np.asarray(sc_o[k]), rtol=3e-7, err_msg=k)
+    t, qk, ps = prep.prepare(pt, sc_g, shape.arch, d, shape.Dh, HB.MODE_M3, hero=hero, fp8=fp8)
+    assert abs(qk / float(w_o["qk_scale"]) - 1) < 1e-6 and ps == float(w_o["S_p"])
+    names = {"w_qkv": "wq_qkv", "w_o": "wq_o", "w_1": "wq_1", "w_2": "wq_2"}
+    for g_, o_ in names.items():
+        cg, co = to_np(t[g_].view(torch.uint8)), np.asarray(w_o[o_]).view(np.uint8)
+        assert np.mean(cg != co) <= 1e-3, (g_, np.mean(cg != co))
+    for g_, o_ in (("w_qkv_s", "s_qkv"), ("w_o_s", "s_o_w"), ("w_1_s", "s_1"), ("w_2_s", "s_2_w"), ("b_qkv", "b_qkv"), ("b_o", "b_o"),
+                   ("b_1", "b_1"), ("b_2", "b_2"), ("attn_out_scale", "attn_out_scale")):
+        np.testing.assert_allclose(t[g_].cpu().numpy(), np.asarray(w_o[o_]), rtol=1e-6, atol=1e-9, err_msg=g_)
+
+
 def test_layer_rejects_bad_requests(hero):
     shape = _shape(synth.POST_LN, synth.MASK_NONE)
     desc = _desc(hero, shape, HB.MODE_M3)
