@@ -201,3 +201,32 @@ def test_bert_large_layer_batch_slice(hero):
     assert np.allclose(gs, os_[valid], rtol=1e-3)
     assert np.abs(gq.astype(int) - oq[valid].astype(int)).max() <= 2
     assert np.mean(gq == oq[valid]) > 0.99
+
+
+def test_bert_large_layer_batch_slice_fp8(hero):
+    """The same slice through the FP8 variant of the layer (HERO_M_FP8): reconstructed outputs in relative L2, every
+    element within one E4M3 step of its own value plus a quarter of the rms (the class of tests/test_gpu_layer.py)."""
+    shape = synth.small(synth.CONFIGS[2], B=4)
+    B, S, T = shape.B, shape.S, shape.B * shape.S
+    p = synth.layer_params(62, shape)
+    emb = synth.embedding_ln_params(62, shape)
+    hc = OL._ln64(synth.activations(62, shape, 512, stream=1).astype(np.float64), emb["g"].astype(np.float64),
+                  emb["b"].astype(np.float64), shape.eps)
+    sc, _ = OL.calibrate(p, hc, synth.small(shape, mask=synth.MASK_NONE), 2, 256, fp8=True)
+    w = OL.prepare(p, sc, shape, OL.MODE_M3, fp8=True)
+    xq, xs, _ = O.ln_quant(synth.activations(62, shape, T), O.F32, None, None, 0, None, emb["g"], emb["b"], shape.eps, fp8=True)
+    kv_len = synth.kv_lengths(62, shape)
+    oq, os_ = OL.layer_fwd(w, shape, B, S, x_q=xq, x_s=xs, kv_len=kv_len)
+    desc = hero.layer_desc(shape.arch, shape.d, shape.H, shape.Dh, shape.f, shape.eps, shape.mask, HB.MODE_M3 | HB.M_FP8)
+    W, keep = upload_weights(hero, w)
+    ws = torch.empty(hero.hero_layer_workspace_bytes(desc, B, S), dtype=torch.uint8, device="cuda")
+    out_q = torch.empty((T, shape.d), dtype=torch.uint8, device="cuda")
+    out_s = torch.empty((T,), dtype=torch.float32, device="cuda")
+    hero.hero_layer_fwd(desc, W, B, S, ws, x_q=dev(xq), x_scale=dev(xs), out_q=out_q, out_scale=out_s, kv_len=dev(kv_len))
+    valid = (np.arange(S)[None, :] < kv_len[:, None]).ravel()
+    ref = (O.e4m3_to_f32(oq).astype(np.float64) * os_[:, None])[valid]
+    got = (O.e4m3_to_f32(to_np(out_q)).astype(np.float64) * to_np(out_s)[:, None])[valid]
+    rms = np.sqrt(np.mean(ref * ref))
+    assert np.sqrt(((got - ref) ** 2).sum() / (ref ** 2).sum()) <= 2e-2
+    assert (np.abs(got - ref) <= 0.125 * np.abs(ref) + 0.25 * rms).all()
+    assert np.allclose(to_np(out_s)[valid], os_[valid], rtol=3e-2)
