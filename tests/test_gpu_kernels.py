@@ -516,6 +516,35 @@ def test_int8_attn_strided_views_cache_and_decode(hero):
     assert not to_np(z).any()
 
 
+@pytest.mark.parametrize("Dh", [64, 128])
+@pytest.mark.parametrize("Skv", [16384, 16400])
+def test_one_query_attention_at_the_longest_cache(hero, Dh, Skv):
+    """One query against 16384 keys (the longest cache the cache-streaming kernel takes: 64 KB of scores in LDS on
+    top of its static buffers) and against 16400 (served by the general kernel), INT8 and E4M3 codes."""
+    B, H = 2, 2
+    g = synth.rng(3000 + Dh + Skv)
+    mk = lambda s: np.clip(np.rint(g.standard_normal(s) * 30), -127, 127).astype(np.int8)
+    q, kc, vc = mk((B, 1, H, Dh)), mk((B, H, Skv, Dh)), mk((B, H, Skv, Dh))
+    lens = np.int32([Skv, Skv - 777])
+    qk_scale = float(np.float32(4.5 / (900.0 * np.sqrt(Dh))))       # peaked rows: over 16384 keys a diffuse row has only zero codes
+    cs = (g.uniform(0.8, 1.2, H * Dh) / (255 * 30) * 400).astype(np.float32)
+    ref = O.int8_attn(q, kc.transpose(0, 2, 1, 3), vc.transpose(0, 2, 1, 3), qk_scale=qk_scale, p_scale=float(OL.S_P),
+                      out_col_scale=cs, mask=O.MASK_PADDING, kv_len=lens)
+    dk, dv = dev(kc), dev(vc)
+    got = hero.hero_int8_attn(dev(q), dk.permute(0, 2, 1, 3), dv.permute(0, 2, 1, 3), qk_scale, float(OL.S_P), dev(cs),
+                              mask=HB.MASK_PADDING, kv_len=dev(lens))
+    assert np.abs(ref).max() > 20
+    assert_codes(to_np(got), ref, "one query, longest cache", max_frac=2.5 / ref.size)
+    q8, k8, v8 = (O.f32_to_e4m3(t.astype(np.float32)) for t in (q, kc, vc))            # the same values as E4M3 codes
+    sp = float(OL.S_P_FP8)
+    cs8 = (cs * np.float32(255.0 / 448.0)).astype(np.float32)
+    ref8 = O.fp8_attn(q8, k8.transpose(0, 2, 1, 3), v8.transpose(0, 2, 1, 3), qk_scale=qk_scale, p_scale=sp, out_col_scale=cs8,
+                      mask=O.MASK_PADDING, kv_len=lens)
+    got8 = hero.hero_fp8_attn(dev(q8), dev(k8).permute(0, 2, 1, 3), dev(v8).permute(0, 2, 1, 3), qk_scale, sp, dev(cs8),
+                              mask=HB.MASK_PADDING, kv_len=dev(lens))
+    assert_fp8_attn_codes(to_np(got8.view(torch.uint8)), ref8, O.e4m3_to_f32, "one query, longest cache, fp8", max_frac=4e-2)
+
+
 @pytest.mark.parametrize("M,N,K", [(8192, 4096, 1024), (2048 + 77, 3072 + 8, 1024), (8192, 1024, 4096)])
 def test_gemm_full_size_sampled_rows(hero, M, N, K):
     """The benchmark's launch configuration (256x256 direct-to-LDS kernel, XCD-aware tile
