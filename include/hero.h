@@ -176,7 +176,10 @@ hero_status hero_int8_gemm_ws(const int8_t* A, int64_t lda, const float* a_row_s
  *   REQUANT -> e4m3(y), GELU_REQUANT -> e4m3(GELU(y) / out_col_scale[j]): C in HERO_F8E4M3, round
  *   to nearest even, saturated to +-448.  HERO_EPI_RAW_I32 does not exist here.
  *   A [M,K], Bt [N,K] E4M3 bytes, K contiguous.  Constraints as for hero_int8_gemm.
- * Token-wise FP8 activations use scale = max|x| / 448 per row; static scales fold as for INT8. */
+ * Token-wise FP8 activations use scale = max|x| / 448 per row; static scales fold as for INT8.
+ * The order of the fp32 accumulation depends on the tile the library picks for a shape (fixed for a
+ * given shape and build), so results are reproducible but not bit-identical across tile choices;
+ * the environment variable HERO_FP8_TILE (0 / 7 / 8, as HERO_GEMM_TILE) forces one for tests. */
 hero_status hero_fp8_gemm(const void* A, int64_t lda, const float* a_row_scale,
                           const void* Bt, int64_t ldb, const float* b_col_scale,
                           const float* bias, const void* residual, hero_dtype res_dt, int64_t ldr,
