@@ -203,6 +203,19 @@ def measured_ceilings(hero):
     dst = torch.empty_like(src)
     ms = time_gpu(lambda: hero.hero_probe_copy(src, dst), 5, warmup=2)
     out["copy_256MiB_gbs"] = round(2.0 * (256 << 20) / (ms * 1e-3) / 1e9, 1)      # read + write
+    del src, dst
+    # a copy that moves what one LN^quant call of the bench moves (48 MiB), on rotating buffers like that leg
+    n, nbuf = 24 << 20, 8
+    bufs = [(torch.randint(-127, 128, (n,), dtype=torch.int8, device="cuda"), torch.empty(n, dtype=torch.int8, device="cuda"))
+            for _ in range(nbuf)]
+    i = [0]
+
+    def cp():
+        a, b = bufs[i[0] % nbuf]
+        i[0] += 1
+        hero.hero_probe_copy(a, b)
+    ms = time_gpu(cp, 40, warmup=nbuf)
+    out["copy_24MiB_rotating_gbs"] = round(2.0 * n / (ms * 1e-3) / 1e9, 1)
     return out
 
 
@@ -537,6 +550,8 @@ def main():
             rec["fp8_layer"] = fp8_layer_leg(hero, shape, args.seed)
         log("[bench] measured ceilings (register-only MFMA loop, plain copy)")
         rec["roofline"]["measured_ceilings"] = measured_ceilings(hero)
+        rec["ln_quant"]["frac_of_same_size_copy"] = round(rec["ln_quant"]["gbs"] / rec["roofline"]["measured_ceilings"]["copy_24MiB_rotating_gbs"], 4)
+        rec["ln_quant_large"]["frac_of_large_copy"] = round(rec["ln_quant_large"]["gbs"] / rec["roofline"]["measured_ceilings"]["copy_256MiB_gbs"], 4)
         log("[bench] GEMM sweep")
         rec["gemm_sweep"] = gemm_sweep(hero, args.seed)
         del st
