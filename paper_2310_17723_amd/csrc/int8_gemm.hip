@@ -1139,19 +1139,18 @@ extern "C" hero_status hero_int8_gemm(const int8_t* A, int64_t lda, const float*
                              C, c_dt, ldc, M, N, K, nullptr, 0, stream);
 }
 
-extern "C" hero_status hero_int8_gemm_ws(const int8_t* A, int64_t lda, const float* a_row_scale,
-                                         const int8_t* Bt, int64_t ldb, const float* b_col_scale,
-                                         const float* bias, const void* residual, hero_dtype res_dt, int64_t ldr,
-                                         hero_epilogue epi, const float* out_col_scale,
-                                         void* C, hero_dtype c_dt, int64_t ldc,
-                                         int64_t M, int64_t N, int64_t K,
-                                         void* workspace, size_t workspace_bytes, void* stream) {
-    if (workspace && ((uintptr_t)workspace & 255)) return HERO_ERR_WORKSPACE;
+namespace {
+// Everything that can be checked about a GeMM^quant request, before anything is launched.  *noop: nothing to do.
+hero_status check_gemm_args(const int8_t* A, int64_t lda, const int8_t* Bt, int64_t ldb, const float* b_col_scale,
+                            const void* residual, hero_dtype res_dt, int64_t ldr, hero_epilogue epi,
+                            const float* out_col_scale, void* C, hero_dtype c_dt, int64_t ldc,
+                            int64_t M, int64_t N, int64_t K, bool* noop) {
+    *noop = false;
     if (M < 0 || N < 0 || K <= 0) return HERO_ERR_SHAPE;
-    if (M > 0x7fffffffLL || N > 0x7fffffffLL || K > 0x7fffffffLL) return HERO_ERR_SHAPE;
+    if (M >= (1LL << 23) || N > 0x7fffffffLL || K > 0x7fffffffLL) return HERO_ERR_SHAPE;
     if (K % KMULT != 0) return HERO_ERR_UNSUPPORTED;
     if (lda < K || ldb < K || ldc < N) return HERO_ERR_SHAPE;
-    if (M == 0 || N == 0) return HERO_OK;
+    if (M == 0 || N == 0) { *noop = true; return HERO_OK; }
     if (!A || !Bt || !C) return HERO_ERR_NULL;
     if (epi != HERO_EPI_RAW_I32 && !b_col_scale) return HERO_ERR_NULL;
     if (epi == HERO_EPI_GELU_REQUANT && !out_col_scale) return HERO_ERR_NULL;
@@ -1165,11 +1164,28 @@ extern "C" hero_status hero_int8_gemm_ws(const int8_t* A, int64_t lda, const flo
     if (residual) {
         if (epi != HERO_EPI_DEQUANT) return HERO_ERR_UNSUPPORTED;
         if (res_dt != HERO_F16 && res_dt != HERO_BF16) return HERO_ERR_UNSUPPORTED;
+        if (res_dt != c_dt) return HERO_ERR_UNSUPPORTED;
         if (ldr < N) return HERO_ERR_SHAPE;
         if (ldr % 4 != 0 || !hero_aligned16(residual)) return HERO_ERR_ALIGN;
     }
     if (lda % 16 != 0 || ldb % 16 != 0 || ldc % 4 != 0) return HERO_ERR_ALIGN;
     if (!hero_aligned16(A) || !hero_aligned16(Bt) || !hero_aligned16(C)) return HERO_ERR_ALIGN;
+    return HERO_OK;
+}
+}  // namespace
+
+extern "C" hero_status hero_int8_gemm_ws(const int8_t* A, int64_t lda, const float* a_row_scale,
+                                         const int8_t* Bt, int64_t ldb, const float* b_col_scale,
+                                         const float* bias, const void* residual, hero_dtype res_dt, int64_t ldr,
+                                         hero_epilogue epi, const float* out_col_scale,
+                                         void* C, hero_dtype c_dt, int64_t ldc,
+                                         int64_t M, int64_t N, int64_t K,
+                                         void* workspace, size_t workspace_bytes, void* stream) {
+    if (workspace && ((uintptr_t)workspace & 255)) return HERO_ERR_WORKSPACE;
+    bool noop = false;
+    const hero_status cs = check_gemm_args(A, lda, Bt, ldb, b_col_scale, residual, res_dt, ldr, epi, out_col_scale,
+                                           C, c_dt, ldc, M, N, K, &noop);
+    if (cs != HERO_OK || noop) return cs;
 
     GemmArgs g;
     g.A = A; g.lda = lda; g.a_row_scale = a_row_scale; g.Bt = Bt; g.ldb = ldb; g.b_col_scale = b_col_scale;
@@ -1188,9 +1204,8 @@ extern "C" hero_status hero_int8_gemm_ws(const int8_t* A, int64_t lda, const flo
         if (!residual)
             return c_dt == HERO_BF16 ? launch_epi<HERO_EPI_DEQUANT, HERO_BF16, -1>(g, workspace, workspace_bytes, st)
                                      : launch_epi<HERO_EPI_DEQUANT, HERO_F16, -1>(g, workspace, workspace_bytes, st);
-        if (c_dt == HERO_BF16 && res_dt == HERO_BF16) return launch_epi<HERO_EPI_DEQUANT, HERO_BF16, HERO_BF16>(g, workspace, workspace_bytes, st);
-        if (c_dt == HERO_F16 && res_dt == HERO_F16) return launch_epi<HERO_EPI_DEQUANT, HERO_F16, HERO_F16>(g, workspace, workspace_bytes, st);
-        return HERO_ERR_UNSUPPORTED;
+        if (c_dt == HERO_BF16) return launch_epi<HERO_EPI_DEQUANT, HERO_BF16, HERO_BF16>(g, workspace, workspace_bytes, st);
+        return launch_epi<HERO_EPI_DEQUANT, HERO_F16, HERO_F16>(g, workspace, workspace_bytes, st);
     default: return HERO_ERR_UNSUPPORTED;
     }
 }

@@ -198,9 +198,13 @@ def test_bert_large_layer_batch_slice(hero):
     hero.hero_layer_fwd(desc, W, B, S, ws, x_q=dev(xq), x_scale=dev(xs), out_q=out_q, out_scale=out_s, kv_len=dev(kv_len))
     valid = (np.arange(S)[None, :] < kv_len[:, None]).ravel()
     gq, gs = to_np(out_q)[valid], to_np(out_s)[valid]
-    assert np.allclose(gs, os_[valid], rtol=1e-3)
-    assert np.abs(gq.astype(int) - oq[valid].astype(int)).max() <= 2
-    assert np.mean(gq == oq[valid]) > 0.99
+    print(f"[parity] bert_large_slice: identical {np.mean(gq == oq[valid]):.5f} max diff "
+          f"{np.abs(gq.astype(int) - oq[valid].astype(int)).max()} scale rel {np.max(np.abs(gs - os_[valid]) / os_[valid]):.2e}")
+    # measured: identical 0.99972, max difference 2, scales 8.3e-4 (a flipped X_mid code of a row moves its FC1 /
+    # FC2 outputs and with them the row's absmax)
+    assert np.allclose(gs, os_[valid], rtol=4e-3)
+    assert np.abs(gq.astype(int) - oq[valid].astype(int)).max() <= 3
+    assert np.mean(gq == oq[valid]) >= 0.999
 
 
 def test_bert_large_layer_batch_slice_fp8(hero):

@@ -60,9 +60,14 @@ def test_post_ln_layer_m3(hero, mask):
         valid = (np.arange(S)[None, :] < kv_len[:, None]).ravel()
     ref = oq.astype(np.float32) * os_[:, None]
     got = gq.astype(np.float32) * gs[:, None]
+    print(f"[parity] post_ln_m3 mask={mask}: identical {np.mean(gq[valid] == oq[valid]):.5f} max diff "
+          f"{np.abs(gq[valid].astype(int) - oq[valid].astype(int)).max()} scale rel {np.max(np.abs(gs[valid] - os_[valid]) / os_[valid]):.2e}")
+    # measured on MI355X: every code identical, scales equal to 2e-7; the margin allows a handful of +-1 LSB flips
+    # of the LayerNorm / softmax / GELU stages and what they do downstream (see tests/test_gpu_configs.py)
     assert rel_err(got[valid], ref[valid]) <= 2e-2
-    assert np.mean(gq[valid] == oq[valid]) > 0.99
-    assert np.abs(gq[valid].astype(int) - oq[valid].astype(int)).max() <= 2
+    assert np.mean(gq[valid] == oq[valid]) >= 0.999
+    assert np.abs(gq[valid].astype(int) - oq[valid].astype(int)).max() <= 1
+    assert np.allclose(gs[valid], os_[valid], rtol=1e-3)
 
 
 @pytest.mark.parametrize("Dh,H", [(64, 4), (128, 2)])
@@ -120,9 +125,14 @@ def test_mixed_precision_modes(hero, arch, mode):
         # than the fp64 oracle, which moves a few values across a rounding boundary)
         valid = (np.arange(S)[None, :] < kv_len[:, None]).ravel()
         gq, gs = to_np(out_q)[valid], to_np(out_s)[valid]
-        assert np.allclose(gs, os_[valid], rtol=2e-2)
-        assert np.abs(gq.astype(int) - oq[valid].astype(int)).max() <= 2
-        assert np.mean(gq == oq[valid]) > 0.97
+        print(f"[parity] mixed {mode}: identical {np.mean(gq == oq[valid]):.5f} max diff "
+              f"{np.abs(gq.astype(int) - oq[valid].astype(int)).max()} scale rel {np.max(np.abs(gs - os_[valid]) / os_[valid]):.2e}")
+        # measured: M1 identical 0.9910, max difference 2, scales 8.7e-4; M2 identical 0.99997, max difference 1,
+        # scales 3e-6 (M2 has one bf16 GEMM, M1 three plus the bf16 attention core)
+        floor, dmax, srel = {"M1": (0.98, 3, 5e-3), "M2": (0.999, 2, 1e-3)}[mode]
+        assert np.allclose(gs, os_[valid], rtol=srel)
+        assert np.abs(gq.astype(int) - oq[valid].astype(int)).max() <= dmax
+        assert np.mean(gq == oq[valid]) >= floor
         return
     else:
         hb = O.f32_to_bf16(h0)
@@ -130,7 +140,8 @@ def test_mixed_precision_modes(hero, arch, mode):
         h = dev(hb)
         hero.hero_layer_fwd(desc, W, B, S, ws, h=h)
         got = O.bf16_to_f32(to_np(h))
-    assert rel_err(got, ref) <= 2e-2
+    print(f"[parity] mixed {mode} pre-LN: rel_err {rel_err(got, ref):.2e}")
+    assert rel_err(got, ref) <= 2e-2                          # the 16-bit output bar; measured 7.1e-3 (M1), 6.6e-3 (M2)
 
 
 # ---- the FP8 variant of the layer (HERO_M_FP8): E4M3 codes in every 8-bit buffer.  The end-to-end class: a flipped
