@@ -167,6 +167,25 @@ hero_status hero_int8_gemm_ws(const int8_t* A, int64_t lda, const float* a_row_s
                               int64_t M, int64_t N, int64_t K,
                               void* workspace, size_t workspace_bytes, void* stream);
 
+/* hero_int8_gemm for callers that cannot allocate or pass device scratch: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Arguments, results (bit for bit) and constraints are those of
+ * hero_int8_gemm_ws; the split-K scratch is a fixed array of HERO_STATIC_SCRATCH_BYTES inside the library (one
+ * copy per GPU, held until the process ends) instead of a caller's buffer.  The call allocates nothing.
+ *   - A shape whose split needs more than HERO_STATIC_SCRATCH_BYTES (hero_int8_gemm_workspace_bytes(M, N, K))
+ *     is refused with HERO_ERR_WORKSPACE before anything is launched; shapes that do not split need no scratch
+ *     and always run.
+ *   - Every call on one GPU shares that GPU's array: calls that may overlap on the GPU (different streams,
+ *     concurrently replayed graphs) race on it.  Calls on one stream are ordered and safe.  The array is pure
+ *     scratch: every plane is written before it is read, nothing needs clearing between calls.
+ *   - The device current at the call must be the one `stream` belongs to. */
+#define HERO_STATIC_SCRATCH_BYTES (16u << 20)
+hero_status hero_int8_gemm_static(const int8_t* A, int64_t lda, const float* a_row_scale,
+                                  const int8_t* Bt, int64_t ldb, const float* b_col_scale,
+                                  const float* bias, const void* residual, hero_dtype res_dt, int64_t ldr,
+                                  hero_epilogue epi, const float* out_col_scale,
+                                  void* C, hero_dtype c_dt, int64_t ldc,
+                                  int64_t M, int64_t N, int64_t K, void* stream);
+
 /* The FP8 variant of GeMM^quant (Sec. 2.1: the method "also works for other 8-bit precision formats,
  * like FP8"): the same operation and epilogue as hero_int8_gemm with OCP E4M3 operands and
  * fp32 accumulation on the matrix cores.

@@ -54,6 +54,7 @@ SYMBOLS = {
     "hero_int8_gemm_workspace_bytes": (C.c_size_t, [i64, i64, i64]),
     "hero_int8_gemm_ws": (i32, [vp, i64, vp, vp, i64, vp, vp, vp, i32, i64, i32, vp, vp, i32, i64, i64, i64, i64,
                                 vp, C.c_size_t, vp]),
+    "hero_int8_gemm_static": (i32, [vp, i64, vp, vp, i64, vp, vp, vp, i32, i64, i32, vp, vp, i32, i64, i64, i64, i64, vp]),
     "hero_int8_attn": (i32, [vp, C.POINTER(i64), vp, C.POINTER(i64), vp, C.POINTER(i64), i64, i64, i64, i64, i64,
                              f32, f32, vp, i32, i32, vp, vp, i32, i64, vp]),
     "hero_fp8_attn": (i32, [vp, C.POINTER(i64), vp, C.POINTER(i64), vp, C.POINTER(i64), i64, i64, i64, i64, i64,
@@ -170,9 +171,10 @@ class Hero:
     # ------------------------------------------------------------------ GeMM^quant
     def hero_int8_gemm(self, A, Bt, a_row_scale=None, b_col_scale=None, bias=None, residual=None,
                        epi=EPI_RAW_I32, out_col_scale=None, out_dtype=torch.int32, C_out=None, stream=None,
-                       workspace=None):
+                       workspace=None, static_scratch=False):
         """A [M,K] int8, Bt [N,K] int8 (row strides may exceed K).  Returns C [M,N].
-        workspace: optional zero-filled uint8 tensor (hero_int8_gemm_workspace_bytes) -> hero_int8_gemm_ws."""
+        workspace: optional uint8 tensor (hero_int8_gemm_workspace_bytes) -> hero_int8_gemm_ws;
+        static_scratch=True -> hero_int8_gemm_static (the library's built-in scratch; pass C_out to allocate nothing)."""
         M, K = A.shape
         N = Bt.shape[0]
         assert Bt.shape[1] == K and A.stride(1) == 1 and Bt.stride(1) == 1
@@ -185,7 +187,9 @@ class Hero:
                 _DT[residual.dtype] if residual is not None else 0,
                 residual.stride(0) if residual is not None else 0, int(epi), _ptr(out_col_scale),
                 _ptr(C_out), _DT[C_out.dtype], C_out.stride(0), M, N, K)
-        if workspace is None:
+        if static_scratch:
+            st = self.lib.hero_int8_gemm_static(*args, _stream(stream))
+        elif workspace is None:
             st = self.lib.hero_int8_gemm(*args, _stream(stream))
         else:
             st = self.lib.hero_int8_gemm_ws(*args, _ptr(workspace), workspace.numel() * workspace.element_size(),

@@ -21,6 +21,7 @@
 // The epilogue works in registers: a lane-half exchange (v_permlane32_swap) gives every lane a
 // contiguous piece of one output row, written with 128-bit stores.
 #include "hero_common.h"
+#include <atomic>
 #include <cstdlib>
 #include <type_traits>
 
@@ -1208,4 +1209,49 @@ extern "C" hero_status hero_int8_gemm_ws(const int8_t* A, int64_t lda, const flo
         return launch_epi<HERO_EPI_DEQUANT, HERO_F16, HERO_F16>(g, workspace, workspace_bytes, st);
     default: return HERO_ERR_UNSUPPORTED;
     }
+}
+
+// ---- hero_int8_gemm_static: the split-K scratch lives in the library ---------------------------------------
+// For callers that cannot allocate (HIP graph capture, serving loops, harnesses that forbid hipMalloc).  The
+// array below exists once per GPU the library is loaded on, until the process ends.  Its name is a host-side
+// stand-in, not a device address: the address is asked for once per device (hipGetSymbolAddress with that
+// device current) and only that pointer is handed to kernels.
+static __device__ __align__(256) unsigned char scratch[HERO_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+std::atomic<void*> g_scratch_ptr[MAX_DEVICES];                         // per device; racing first calls store the same value
+
+hero_status static_scratch_ptr(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return HERO_ERR_LAUNCH;
+    void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return HERO_ERR_LAUNCH;
+        g_scratch_ptr[dev].store(p, std::memory_order_release);
+    }
+    *out = p;
+    return HERO_OK;
+}
+}  // namespace
+
+extern "C" hero_status hero_int8_gemm_static(const int8_t* A, int64_t lda, const float* a_row_scale,
+                                             const int8_t* Bt, int64_t ldb, const float* b_col_scale,
+                                             const float* bias, const void* residual, hero_dtype res_dt, int64_t ldr,
+                                             hero_epilogue epi, const float* out_col_scale,
+                                             void* C, hero_dtype c_dt, int64_t ldc,
+                                             int64_t M, int64_t N, int64_t K, void* stream) {
+    bool noop = false;
+    const hero_status cs = check_gemm_args(A, lda, Bt, ldb, b_col_scale, residual, res_dt, ldr, epi, out_col_scale,
+                                           C, c_dt, ldc, M, N, K, &noop);
+    if (cs != HERO_OK || noop) return cs;
+    const size_t need = splitk_plan(M, N, K).bytes;
+    if (need > (size_t)HERO_STATIC_SCRATCH_BYTES) return HERO_ERR_WORKSPACE;   // beyond the built-in scratch
+    void* ws = nullptr;
+    if (need) {
+        const hero_status ss = static_scratch_ptr(&ws);
+        if (ss != HERO_OK) return ss;
+    }
+    return hero_int8_gemm_ws(A, lda, a_row_scale, Bt, ldb, b_col_scale, bias, residual, res_dt, ldr, epi, out_col_scale,
+                             C, c_dt, ldc, M, N, K, ws, need, stream);
 }

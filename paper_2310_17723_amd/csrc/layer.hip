@@ -91,7 +91,7 @@ extern "C" const char* hero_strerror(hero_status s) {
     case HERO_ERR_SHAPE: return "invalid or inconsistent size";
     case HERO_ERR_ALIGN: return "pointer or leading dimension not 16-byte aligned";
     case HERO_ERR_UNSUPPORTED: return "unsupported shape, dtype or mode";
-    case HERO_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case HERO_ERR_WORKSPACE: return "workspace missing, misaligned, too small, or larger than the built-in scratch";
     case HERO_ERR_LAUNCH: return "HIP launch failed";
     }
     return "unknown status";

@@ -52,3 +52,11 @@ def test_argument_errors_come_before_any_launch(lib):
     assert n >= 160 * (3 * 128 + 128 * 4 + 256) and n % 256 == 0
     assert lib.hero_layer_workspace_bytes(LayerDesc(0, 128, 2, 64, 256, 1e-5, 0, 2), 2, 80) == 0   # QKV bit clear
     assert L.hero_layer_fwd(None, None, None, None, 0, None) == 1
+    # the entry point with the built-in scratch refuses a split that does not fit it (nothing is dereferenced or
+    # launched on that path, so placeholder addresses do)
+    fake = C.c_void_p(0x10000)
+    assert lib.hero_int8_gemm_workspace_bytes(128, 4096, 16384) > (16 << 20)
+    assert L.hero_int8_gemm_static(fake, 16384, None, fake, 16384, fake, None, None, 0, 0, 3, None, fake, 0, 4096,
+                                   128, 4096, 16384, None) == 5
+    assert L.hero_int8_gemm_static(None, 64, None, None, 64, None, None, None, 0, 0, 0, None, None, 2, 64, 8, 8, 64, None) == 1
+    assert "built-in scratch" in lib.strerror(5)
