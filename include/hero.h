@@ -11,10 +11,20 @@
  *     has been enqueued and a non-zero hero_status is returned.  No exceptions cross the ABI.
  *   - Sizes and strides are int64_t, in ELEMENTS.  Outputs must not alias inputs unless
  *     the entry point says so.
- *   - Numeric conventions (paper Sec. 2.1, "symmetric uniform INT8"): codes lie in
- *     [-127,127]; rounding is to nearest, ties to even; a quantization divides by the
- *     scale with IEEE fp32 division; a dynamic scale is absmax/127 (1.0 for an all-zero
- *     row).  Integer contractions are exact in int32.
+ *   - Numeric conventions (Sec. 2.1 quantizes symmetrically and uniformly to 8-bit integers): codes
+ *     lie in [-127,127]; rounding is to nearest, ties to even; a dynamic scale is absmax/127 (1.0 for an
+ *     all-zero row).  Integer contractions are exact in int32.  The DEFINITION of every quantization
+ *     divides by the scale with IEEE fp32 division, and the entry points whose results are bit-exact
+ *     against that definition compute exactly that: REQUANT / DEQUANT / raw GeMM^quant (their scales are
+ *     multiplied, never divided by), LN^quant without LayerNorm (pure token-wise quantization), the
+ *     weight preparation.  Three places multiply by a reciprocal instead, all behind fp32 transcendental
+ *     or statistical arithmetic whose own rounding already differs from the definition's, so that their
+ *     codes agree with it up to +-1 step on <= 0.1 % of the elements (the tolerance class of those paths):
+ *     LN^quant behind a LayerNorm (v_rcp_f32 of the row scale, v_rsq_f32 of the variance), GELU^quant
+ *     (1 / S_a[j]: v_rcp_f32, or the correctly rounded quotient in the overlapped-epilogue kernel), and
+ *     Softmax^quant (the normaliser and 1 / S_p are folded into the exponent).
+ *   - The kernel an entry point runs is chosen from the problem size alone; the library reads no
+ *     environment variable.  (include/hero_debug.h has test hooks that force a kernel.)
  */
 #ifndef HERO_H
 #define HERO_H
@@ -44,7 +54,7 @@ typedef enum {
     HERO_EPI_DEQUANT = 1,      /* C = y (+ residual)                        (f16/bf16)     */
     HERO_EPI_DEQUANT_GELU = 2, /* C = GELU(y)                               (f16/bf16)     */
     HERO_EPI_REQUANT = 3,      /* C = sat(rne(y))                           (int8)         */
-    HERO_EPI_GELU_REQUANT = 4  /* C = sat(rne(GELU(y) / out_col_scale[j]))  (int8)         */
+    HERO_EPI_GELU_REQUANT = 4  /* C = sat(rne(GELU(y) / out_col_scale[j]))  (int8; +-1 LSB class, see above) */
 } hero_epilogue;
 
 typedef enum { HERO_MASK_NONE = 0, HERO_MASK_PADDING = 1, HERO_MASK_CAUSAL = 2 } hero_mask;
@@ -133,10 +143,8 @@ hero_status hero_embed_ln_quant(const int32_t* tok_ids, const int32_t* pos_ids, 
  *   C   [M,N] in c_dt, leading dimension ldc: HERO_I32 (RAW), HERO_F16/HERO_BF16 (DEQUANT*),
  *       HERO_I8 (REQUANT*).  Other pairs -> HERO_ERR_UNSUPPORTED.
  * Constraints: K % 64 == 0; lda, ldb multiples of 16; ldc, ldr multiples of 4; base
- * pointers 16-byte aligned; M, N arbitrary (>= 0; zero is a no-op); M < 2^23.
- * The tile shape is chosen from the problem size; the environment variable HERO_GEMM_TILE (0 = 128x128,
- * 1 = 256x256 one tile per workgroup, 2 = 64x64, 7 = 256x256 persistent, 8 = 128x128 persistent) overrides
- * it for tuning runs and tests.  Every choice gives the same result.
+ * pointers 16-byte aligned; M, N arbitrary (>= 0; zero is a no-op); M < 2^23 (HERO_ERR_SHAPE beyond).
+ * The tile shape is chosen from the problem size; every choice gives the same result.
  */
 hero_status hero_int8_gemm(const int8_t* A, int64_t lda, const float* a_row_scale,
                            const int8_t* Bt, int64_t ldb, const float* b_col_scale,
@@ -186,9 +194,9 @@ hero_status hero_int8_gemm_static(const int8_t* A, int64_t lda, const float* a_r
                                   void* C, hero_dtype c_dt, int64_t ldc,
                                   int64_t M, int64_t N, int64_t K, void* stream);
 
-/* The FP8 variant of GeMM^quant (Sec. 2.1: the method "also works for other 8-bit precision formats,
- * like FP8"): the same operation and epilogue as hero_int8_gemm with OCP E4M3 operands and
- * fp32 accumulation on the matrix cores.
+/* The FP8 variant of GeMM^quant (Sec. 2.1 names FP8 as an 8-bit format the method applies to as well): the
+ * same operation and epilogue as hero_int8_gemm with OCP E4M3 operands and fp32 accumulation on the
+ * matrix cores.
  *   acc[i][j] = sum_k A[i][k] * Bt[j][k]     every product exact; the sum in fp32 (hardware order)
  *   then t = acc * a_row_scale[i] (skipped if NULL); y = fma(t, b_col_scale[j], bias[j]); epilogue:
  *   DEQUANT / DEQUANT_GELU -> C in HERO_F16 / HERO_BF16 (residual as for hero_int8_gemm);
@@ -197,8 +205,7 @@ hero_status hero_int8_gemm_static(const int8_t* A, int64_t lda, const float* a_r
  *   A [M,K], Bt [N,K] E4M3 bytes, K contiguous.  Constraints as for hero_int8_gemm.
  * Token-wise FP8 activations use scale = max|x| / 448 per row; static scales fold as for INT8.
  * The order of the fp32 accumulation depends on the tile the library picks for a shape (fixed for a
- * given shape and build), so results are reproducible but not bit-identical across tile choices;
- * the environment variable HERO_FP8_TILE (0 / 7 / 8, as HERO_GEMM_TILE) forces one for tests. */
+ * given shape and build), so results are reproducible but not bit-identical across tile choices. */
 hero_status hero_fp8_gemm(const void* A, int64_t lda, const float* a_row_scale,
                           const void* Bt, int64_t ldb, const float* b_col_scale,
                           const float* bias, const void* residual, hero_dtype res_dt, int64_t ldr,
@@ -400,17 +407,6 @@ hero_status hero_weight_fold_quant_fp8(const float* W, int64_t ldw, const float*
 
 /* Library build identification: target architecture string, e.g. "gfx950". */
 const char* hero_build_arch(void);
-
-/* Diagnostics (not on the hot path): the ceilings the kernels are measured against, taken on the
- * machine at hand.
- *   hero_probe_mfma_i8  enqueues a register-only loop of v_mfma_i32_32x32x32_i8 (one 512-thread workgroup
- *     per CU, `iters` x 16 instructions per wave) on near-constant (random_bytes == 0) or random
- *     (random_bytes != 0) operand bytes: the chip's clock under the matrix cores depends on how many
- *     operand bits toggle.  *ops (host, may be NULL) receives the integer operations the launch
- *     performs; sink is one device int32 the kernel may write.
- *   hero_probe_copy  enqueues a plain device copy of `bytes` (a multiple of 16; 16-byte aligned). */
-hero_status hero_probe_mfma_i8(int random_bytes, int64_t iters, int32_t* sink, double* ops, void* stream);
-hero_status hero_probe_copy(const void* src, void* dst, int64_t bytes, void* stream);
 
 #ifdef __cplusplus
 }

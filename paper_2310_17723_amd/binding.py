@@ -54,6 +54,9 @@ SYMBOLS = {
     "hero_int8_gemm_workspace_bytes": (C.c_size_t, [i64, i64, i64]),
     "hero_int8_gemm_ws": (i32, [vp, i64, vp, vp, i64, vp, vp, vp, i32, i64, i32, vp, vp, i32, i64, i64, i64, i64,
                                 vp, C.c_size_t, vp]),
+    "hero_int8_gemm_tile": (i32, [vp, i64, vp, vp, i64, vp, vp, vp, i32, i64, i32, vp, vp, i32, i64, i64, i64, i64, vp, i32]),
+    "hero_fp8_gemm_tile": (i32, [vp, i64, vp, vp, i64, vp, vp, vp, i32, i64, i32, vp, vp, i32, i64, i64, i64, i64, vp, i32]),
+    "hero_bf16_gemm_tile": (i32, [vp, i64, vp, i64, vp, vp, i64, i32, vp, i64, i64, i64, i64, vp, i32]),
     "hero_int8_gemm_static": (i32, [vp, i64, vp, vp, i64, vp, vp, vp, i32, i64, i32, vp, vp, i32, i64, i64, i64, i64, vp]),
     "hero_int8_attn": (i32, [vp, C.POINTER(i64), vp, C.POINTER(i64), vp, C.POINTER(i64), i64, i64, i64, i64, i64,
                              f32, f32, vp, i32, i32, vp, vp, i32, i64, vp]),
@@ -61,8 +64,6 @@ SYMBOLS = {
                             f32, f32, vp, i32, i32, vp, vp, i32, i64, vp]),
     "hero_int8_attn_online": (i32, [vp, C.POINTER(i64), vp, C.POINTER(i64), vp, C.POINTER(i64), i64, i64, i64, i64, i64,
                                     vp, f32, vp, i32, i32, vp, vp, i32, i64, vp]),
-    "hero_probe_mfma_i8": (i32, [i32, i64, vp, C.POINTER(C.c_double), vp]),
-    "hero_probe_copy": (i32, [vp, vp, i64, vp]),
     "hero_layer_workspace_bytes": (C.c_size_t, [C.POINTER(LayerDesc), i64, i64]),
     "hero_layer_fwd": (i32, [C.POINTER(LayerDesc), C.POINTER(LayerWeights), C.POINTER(LayerIO), vp, C.c_size_t, vp]),
     "hero_bf16_gemm": (i32, [vp, i64, vp, i64, vp, vp, i64, i32, vp, i64, i64, i64, i64, vp]),
@@ -171,10 +172,11 @@ class Hero:
     # ------------------------------------------------------------------ GeMM^quant
     def hero_int8_gemm(self, A, Bt, a_row_scale=None, b_col_scale=None, bias=None, residual=None,
                        epi=EPI_RAW_I32, out_col_scale=None, out_dtype=torch.int32, C_out=None, stream=None,
-                       workspace=None, static_scratch=False):
+                       workspace=None, static_scratch=False, tile=None):
         """A [M,K] int8, Bt [N,K] int8 (row strides may exceed K).  Returns C [M,N].
         workspace: optional uint8 tensor (hero_int8_gemm_workspace_bytes) -> hero_int8_gemm_ws;
-        static_scratch=True -> hero_int8_gemm_static (the library's built-in scratch; pass C_out to allocate nothing)."""
+        static_scratch=True -> hero_int8_gemm_static (the library's built-in scratch; pass C_out to allocate nothing);
+        tile=<code> -> the test hook hero_int8_gemm_tile (include/hero_debug.h: the kernel forced)."""
         M, K = A.shape
         N = Bt.shape[0]
         assert Bt.shape[1] == K and A.stride(1) == 1 and Bt.stride(1) == 1
@@ -187,7 +189,9 @@ class Hero:
                 _DT[residual.dtype] if residual is not None else 0,
                 residual.stride(0) if residual is not None else 0, int(epi), _ptr(out_col_scale),
                 _ptr(C_out), _DT[C_out.dtype], C_out.stride(0), M, N, K)
-        if static_scratch:
+        if tile is not None:
+            st = self.lib.hero_int8_gemm_tile(*args, _stream(stream), int(tile))
+        elif static_scratch:
             st = self.lib.hero_int8_gemm_static(*args, _stream(stream))
         elif workspace is None:
             st = self.lib.hero_int8_gemm(*args, _stream(stream))
@@ -198,7 +202,7 @@ class Hero:
         return C_out
 
     def hero_fp8_gemm(self, A, Bt, a_row_scale, b_col_scale, bias=None, residual=None, epi=EPI_DEQUANT,
-                      out_col_scale=None, out_dtype=torch.bfloat16, C_out=None, stream=None):
+                      out_col_scale=None, out_dtype=torch.bfloat16, C_out=None, stream=None, tile=None):
         """The FP8 variant: A [M,K], Bt [N,K] hold E4M3 bytes (torch.float8_e4m3fn or uint8 storage).
         out_dtype torch.float8_e4m3fn for the REQUANT epilogues, float16 / bfloat16 for DEQUANT."""
         M, K = A.shape
@@ -206,11 +210,12 @@ class Hero:
         assert Bt.shape[1] == K and A.stride(1) == 1 and Bt.stride(1) == 1 and A.element_size() == 1 and Bt.element_size() == 1
         if C_out is None:
             C_out = torch.empty((M, N), dtype=out_dtype, device=A.device)
-        st = self.lib.hero_fp8_gemm(_ptr(A), A.stride(0) if M > 1 else max(K, A.stride(0)), _ptr(a_row_scale),
-                                    _ptr(Bt), Bt.stride(0) if N > 1 else max(K, Bt.stride(0)), _ptr(b_col_scale),
-                                    _ptr(bias), _ptr(residual), _DT[residual.dtype] if residual is not None else 0,
-                                    residual.stride(0) if residual is not None else 0, int(epi), _ptr(out_col_scale),
-                                    _ptr(C_out), _DT[C_out.dtype], C_out.stride(0), M, N, K, _stream(stream))
+        args = (_ptr(A), A.stride(0) if M > 1 else max(K, A.stride(0)), _ptr(a_row_scale),
+                _ptr(Bt), Bt.stride(0) if N > 1 else max(K, Bt.stride(0)), _ptr(b_col_scale),
+                _ptr(bias), _ptr(residual), _DT[residual.dtype] if residual is not None else 0,
+                residual.stride(0) if residual is not None else 0, int(epi), _ptr(out_col_scale),
+                _ptr(C_out), _DT[C_out.dtype], C_out.stride(0), M, N, K, _stream(stream))
+        st = self.lib.hero_fp8_gemm(*args) if tile is None else self.lib.hero_fp8_gemm_tile(*args, int(tile))
         self._check(st)
         return C_out
 
@@ -264,26 +269,16 @@ class Hero:
         self._check(st)
         return out
 
-    # ------------------------------------------------------------------ diagnostics
-    def hero_probe_mfma_i8(self, random_bytes, iters, sink, stream=None) -> float:
-        """Enqueues the register-only MFMA loop; returns the integer operations of the launch."""
-        ops = C.c_double(0.0)
-        self._check(self.lib.hero_probe_mfma_i8(int(bool(random_bytes)), int(iters), _ptr(sink), C.byref(ops), _stream(stream)))
-        return ops.value
-
-    def hero_probe_copy(self, src, dst, stream=None):
-        assert src.is_contiguous() and dst.is_contiguous() and src.numel() * src.element_size() == dst.numel() * dst.element_size()
-        self._check(self.lib.hero_probe_copy(_ptr(src), _ptr(dst), src.numel() * src.element_size(), _stream(stream)))
-
     # ------------------------------------------------------------------ BF16 side
-    def hero_bf16_gemm(self, A, Wt, bias=None, residual=None, gelu=False, C_out=None, stream=None):
+    def hero_bf16_gemm(self, A, Wt, bias=None, residual=None, gelu=False, C_out=None, stream=None, tile=None):
         M, K = A.shape
         N = Wt.shape[0]
         if C_out is None:
             C_out = torch.empty((M, N), dtype=torch.bfloat16, device=A.device)
-        st = self.lib.hero_bf16_gemm(_ptr(A), A.stride(0), _ptr(Wt), Wt.stride(0), _ptr(bias), _ptr(residual),
-                                     residual.stride(0) if residual is not None else 0, int(bool(gelu)),
-                                     _ptr(C_out), C_out.stride(0), M, N, K, _stream(stream))
+        args = (_ptr(A), A.stride(0), _ptr(Wt), Wt.stride(0), _ptr(bias), _ptr(residual),
+                residual.stride(0) if residual is not None else 0, int(bool(gelu)),
+                _ptr(C_out), C_out.stride(0), M, N, K, _stream(stream))
+        st = self.lib.hero_bf16_gemm(*args) if tile is None else self.lib.hero_bf16_gemm_tile(*args, int(tile))
         self._check(st)
         return C_out
 

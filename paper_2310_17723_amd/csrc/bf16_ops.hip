@@ -262,9 +262,9 @@ __global__ void zero_bf16_kernel(uint16_t* out, int64_t rows, int64_t cols, int6
 
 }  // namespace
 
-extern "C" hero_status hero_bf16_gemm(const void* A, int64_t lda, const void* Wt, int64_t ldb,
-                                      const float* bias, const void* residual, int64_t ldr, int gelu,
-                                      void* C, int64_t ldc, int64_t M, int64_t N, int64_t K, void* stream) {
+static hero_status run_bf16_gemm(const void* A, int64_t lda, const void* Wt, int64_t ldb,
+                                 const float* bias, const void* residual, int64_t ldr, int gelu,
+                                 void* C, int64_t ldc, int64_t M, int64_t N, int64_t K, void* stream, int tile) {
     if (M < 0 || N < 0 || K <= 0 || M > 0x7fffffffLL || N > 0x7fffffffLL || K > 0x3fffffffLL) return HERO_ERR_SHAPE;
     if (K % 32 != 0) return HERO_ERR_UNSUPPORTED;
     if (lda < K || ldb < K || ldc < N || (residual && ldr < N)) return HERO_ERR_SHAPE;
@@ -272,7 +272,7 @@ extern "C" hero_status hero_bf16_gemm(const void* A, int64_t lda, const void* Wt
     if (!A || !Wt || !C) return HERO_ERR_NULL;
     if (lda % 8 || ldb % 8 || ldc % 4 || !hero_aligned16(A) || !hero_aligned16(Wt) || !hero_aligned16(C)) return HERO_ERR_ALIGN;
     if (!residual || (ldr % 8 == 0 && hero_aligned16(residual))) {        // large problems: the persistent 256x256 kernel
-        const hero_status big = hero_bf16_gemm_large(A, lda, Wt, ldb, bias, residual, ldr, gelu, C, ldc, M, N, K, (hipStream_t)stream);
+        const hero_status big = hero_bf16_gemm_large(A, lda, Wt, ldb, bias, residual, ldr, gelu, C, ldc, M, N, K, (hipStream_t)stream, tile);
         if (big != HERO_ERR_UNSUPPORTED) return big;
     }
     if ((M + 127) / 128 > 65535) return HERO_ERR_UNSUPPORTED;
@@ -283,6 +283,20 @@ extern "C" hero_status hero_bf16_gemm(const void* A, int64_t lda, const void* Wt
     dim3 grid((unsigned)((N + 127) / 128), (unsigned)((M + 127) / 128));
     hipLaunchKernelGGL(bf16_gemm_kernel, grid, dim3(256), 0, (hipStream_t)stream, g);
     return hero_launch_status();
+}
+
+extern "C" hero_status hero_bf16_gemm(const void* A, int64_t lda, const void* Wt, int64_t ldb,
+                                      const float* bias, const void* residual, int64_t ldr, int gelu,
+                                      void* C, int64_t ldc, int64_t M, int64_t N, int64_t K, void* stream) {
+    return run_bf16_gemm(A, lda, Wt, ldb, bias, residual, ldr, gelu, C, ldc, M, N, K, stream, -1);
+}
+
+// Test and tuning hook (include/hero_debug.h): tile 7 / 8 = the persistent 256x256 / 128x128 kernel, 0 = the plain one.
+extern "C" hero_status hero_bf16_gemm_tile(const void* A, int64_t lda, const void* Wt, int64_t ldb,
+                                           const float* bias, const void* residual, int64_t ldr, int gelu,
+                                           void* C, int64_t ldc, int64_t M, int64_t N, int64_t K, void* stream, int tile) {
+    if (tile != 0 && tile != 7 && tile != 8) return HERO_ERR_UNSUPPORTED;
+    return run_bf16_gemm(A, lda, Wt, ldb, bias, residual, ldr, gelu, C, ldc, M, N, K, stream, tile);
 }
 
 extern "C" hero_status hero_bf16_attn(const void* q, const int64_t q_strides[4],

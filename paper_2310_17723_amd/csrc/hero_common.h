@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include "../../include/hero.h"
+#include "../../include/hero_debug.h"
 
 #define HERO_WAVE 64
 
@@ -20,7 +21,7 @@ static inline bool hero_aligned16(const void* p) { return (reinterpret_cast<uint
 // library-internal: bf16 operands through the persistent 256x256 GEMM kernel (int8_gemm.hip)
 hero_status hero_bf16_gemm_large(const void* A, int64_t lda, const void* Wt, int64_t ldb,
                                  const float* bias, const void* residual, int64_t ldr, int gelu,
-                                 void* C, int64_t ldc, int64_t M, int64_t N, int64_t K, hipStream_t st);
+                                 void* C, int64_t ldc, int64_t M, int64_t N, int64_t K, hipStream_t st, int tile);
 
 static inline hero_status hero_launch_status() {
     return hipGetLastError() == hipSuccess ? HERO_OK : HERO_ERR_LAUNCH;

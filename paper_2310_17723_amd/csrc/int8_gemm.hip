@@ -834,6 +834,353 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void int8_gemm_persistent_kernel(G
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));                      // the redundant tail loads
 }
 
+// =====================================================================================
+// Persistent kernel with the epilogue INSIDE the next tile's main loop (large problems, K >= 1024).
+// The vector ALU issues while the matrix pipe of the same SIMD is busy (measured: a wave that puts 4 fp32
+// instructions behind each of its v_mfma_i32_32x32x32_i8 runs 15 % longer than the matrix instructions alone,
+// not the 34 % the two take one after the other), but only if both kinds of work are there at the same
+// time.  Here a wave keeps TWO sets of accumulators: while the matrix instructions of tile t+1 fill one, the
+// dequantization / GELU / requantization / stores of tile t drain the other, a fixed handful of vector
+// instructions behind every matrix instruction (the epilogue of a tile is cut into 128 such steps, the first
+// 16 slabs of the next tile).  A 256 x 256 tile would need 2 x 128 accumulator registers per lane, which the
+// register file does not have beside everything else, so the tile is 256 x 128: 8 waves of 64 x 64 (4
+// accumulators, 2 x 64 registers).  The smaller tile needs 1.5 x the L2 -> LDS bytes per multiply-add; in exchange
+// a stage is 24 KB and the ring holds SIX slabs (three pairs), i.e. five slabs of lookahead instead of three.
+// The last tile of a workgroup has no successor: its epilogue runs after the loop, unhidden.
+// Measured (16384 x 4096 x 1024): the epilogue does disappear -- GELU^quant costs 7 us over the plain requantization
+// where it costs 25 us behind the 256 x 256 tile -- but the main loop of the smaller tile is slower by about as much
+// (92 us against 76 us: 1.33 x the LDS fragment reads per matrix instruction and 1.5 x the direct-load bytes on a
+// load stream that is latency-bound), so the two kernels end within 2 % of each other (99 / 101 us with
+// GELU^quant).  The tile choice therefore keeps the 256 x 256 kernel; this one is reached through the test entry
+// point (tile code 9) and stays as the measured answer to "can the epilogue be hidden".
+// =====================================================================================
+// wait for vmcnt <= N and for every LDS access of this wave, then the workgroup barrier.  Inline assembly: the
+// kernel below has global stores inside its main loop, and a __syncthreads() there would make the compiler
+// wait for ALL outstanding vector-memory operations, the direct loads of the next slabs included.  The memory
+// clobber keeps the compiler from moving LDS accesses across the barrier.
+template <int N>
+__device__ __forceinline__ void wait_vm_barrier() {
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" :: "n"(N) : "memory");
+}
+
+template <int EPI, int CDT>
+__global__ __launch_bounds__(512, 2) void int8_gemm_ovl_kernel(GemmArgs g) {
+    constexpr int BM = 256, BN = 128, WN = 2, NS = 6, NWAVE = 8, NT = 512;
+    constexpr int TM = 2, TN = 2, NM = TM * TN, NFR = TM + TN;
+    constexpr int A_BYTES = BM * BK, B_BYTES = BN * BK, STAGE = A_BYTES + B_BYTES;
+    constexpr int A_UNITS = A_BYTES / 16 / NT, B_UNITS = B_BYTES / 16 / NT, NW = A_UNITS + B_UNITS;
+    static_assert(A_UNITS == 2 && B_UNITS == 1 && NW <= NM && NFR == NM, "interleave plan");
+    constexpr int RING = NS * STAGE;
+    // per-tile epilogue vectors in LDS: column scale, bias, S_a (BN each), row scale (BM); three sets, because
+    // the set of tile t is read during tile t+1 while the issue stream already fetches the one of tile t+2
+    constexpr int SV_CS = 0, SV_BIAS = BN, SV_OS = 2 * BN, SV_RS = 3 * BN, SVF = 3 * BN + BM, NSV = 3;
+    constexpr int ES = ElemSize<CDT>::v;
+    constexpr bool GELU = EPI == HERO_EPI_DEQUANT_GELU || EPI == HERO_EPI_GELU_REQUANT;
+    constexpr int SPREAD = 16;                                   // slabs of the next tile the epilogue is spread over
+    constexpr int NSTEP = 16, NPIECE = 8;                        // 8 pieces of 8 outputs per lane, 16 steps each
+    static_assert(NPIECE * NSTEP == SPREAD * 2 * NM, "one epilogue step behind every matrix instruction");
+    static_assert(RING + NSV * SVF * 4 <= 160 * 1024, "LDS budget");
+    __shared__ __attribute__((aligned(1024))) int8_t smem[RING + NSV * SVF * 4];
+    float* const sv0 = reinterpret_cast<float*>(smem + RING);
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+    const int hh = lane >> 5, ml = lane & 31;
+    const int xcd = blockIdx.x % NUM_XCD, slot = blockIdx.x / NUM_XCD, nslot = gridDim.x / NUM_XCD;
+    const int seq_end = min((xcd + 1) * g.per_xcd, g.ntm * g.ntn);
+    int seq = xcd * g.per_xcd + slot;                            // this workgroup's tiles: seq, seq + nslot, ...
+    if (seq >= seq_end) return;
+    const int KT = g.K / BK;                                     // even, >= SPREAD (the launch checks)
+    const bool has_rs = g.a_row_scale != nullptr, has_bias = g.bias != nullptr;
+    // absent vectors: the epilogue multiplies by 1 and adds 0 (both exact)
+    if (!has_bias) for (int c = tid; c < NSV * BN; c += NT) sv0[(c / BN) * SVF + SV_BIAS + c % BN] = 0.0f;
+    if (!has_rs) for (int c = tid; c < NSV * BM; c += NT) sv0[(c / BM) * SVF + SV_RS + c % BM] = 1.0f;
+
+    // loader: unit u of wave w fills LDS granules [(u * NWAVE + w) * 64, +64) of the A (or B) part of a stage;
+    // lane l owns row u * 128 + lrow, stored chunk l % 4 = global chunk (l % 4) ^ ((row >> 2) & 3)
+    const int lrow = wave * 16 + (lane >> 2);
+    const uint32_t lc = (uint32_t)(((lane & 3) ^ ((lrow >> 2) & 3)) * 16);
+    const uint32_t wbase = __builtin_amdgcn_readfirstlane(lds_offset(smem) + wave * 1024);
+    const uint32_t svbase = __builtin_amdgcn_readfirstlane(lds_offset(sv0));
+
+    // ---- issue stream: the tile / slab the next direct loads belong to (runs NS - 1 slabs ahead)
+    int iseq = seq, ikt = 0, ibuf = 0;
+    const int8_t* ia; const int8_t* ib;                          // wave-uniform: tile base + slab offset
+    uint32_t oa[A_UNITS], ob;
+    int m0i = 0, n0i = 0;
+    auto set_issue_tile = [&](int s) {
+        tile_from_seq<BM, BN>(g, s, m0i, n0i);
+        ia = g.A + (int64_t)m0i * g.lda;
+        ib = g.Bt + (int64_t)n0i * g.ldb;
+#pragma unroll
+        for (int u = 0; u < A_UNITS; ++u) oa[u] = (uint32_t)min(lrow + u * (NWAVE * 16), g.M - 1 - m0i) * (uint32_t)g.lda + lc;
+        ob = (uint32_t)min(lrow, g.N - 1 - n0i) * (uint32_t)g.ldb + lc;
+    };
+    // The vectors of a tile are 10 chunks of 64 floats: 0-1 column scale, 2-3 bias, 4-5 S_a, 6-9 row scale.  Wave w
+    // fetches chunk w, waves 0 and 1 also chunks 8 and 9; what a wave fetches is fixed for the whole kernel, so
+    // it is worked out here once (source, clamp, destination) and the issue is one predicated load per chunk.
+    const int wu = __builtin_amdgcn_readfirstlane(wave);
+    const int vwhich = wu < 6 ? wu >> 1 : 3;                     // 0 column scale, 1 bias, 2 S_a, 3 row scale
+    const int vch = wu < 6 ? (wu & 1) * 64 : (wu - 6) * 64;
+    const float* const vsrc = vwhich == 0 ? g.b_col_scale : vwhich == 1 ? g.bias : vwhich == 2 ? g.out_col_scale : g.a_row_scale;
+    const bool von = EPI != HERO_EPI_RAW_I32 && (vwhich == 0 || (vwhich == 1 && has_bias) ||
+                                                 (vwhich == 2 && EPI == HERO_EPI_GELU_REQUANT) || (vwhich == 3 && has_rs));
+    const uint32_t vdst = svbase + (uint32_t)(vwhich * BN + vch) * 4;
+    const bool von2 = EPI != HERO_EPI_RAW_I32 && wu < 2 && has_rs;   // chunks 8, 9: rows 128 .. 255 of the row scale
+    const uint32_t vdst2 = svbase + (uint32_t)(SV_RS + 128 + wu * 64) * 4;
+    auto issue_tile_vectors = [&](int buf) {                     // when the stream enters a tile: older than all its slabs
+        const uint32_t bo = (uint32_t)buf * (SVF * 4);
+        if (von) {
+            const int lim = vwhich == 3 ? g.M - 1 - m0i : g.N - 1 - n0i, org = vwhich == 3 ? m0i : n0i;
+            dma4s((uint32_t)min(vch + lane, lim) * 4u, vsrc + org, vdst + bo);
+        }
+        if (von2) dma4s((uint32_t)min(128 + wu * 64 + lane, g.M - 1 - m0i) * 4u, g.a_row_scale + m0i, vdst2 + bo);
+    };
+    // The stream moves in PAIRS of slabs (128 bytes of every row = one cache line): load j of a pair is unit
+    // j / 2 of slab j % 2, so the two 64-byte halves of a line are requested back to back.
+    auto issue_pair = [&](int j, int stage0) {                   // stage0: the (even) stage of the pair's first slab
+        const int u = j >> 1;
+        const uint32_t lds = wbase + (stage0 + (j & 1)) * STAGE;
+        if (u < A_UNITS) dma16s(oa[u], ia + (j & 1) * BK, lds + u * NWAVE * 1024);
+        else dma16s(ob, ib + (j & 1) * BK, lds + A_BYTES);
+    };
+    // next pair; past the last tile the last pair repeats (never read).  The vectors of a tile go out the moment
+    // the stream enters it: their set (tile count mod 3) was last read by the epilogue of the tile three back,
+    // which ended before the current tile began.
+    auto advance = [&]() {
+        ikt += 2;
+        if (ikt < KT) { ia += 2 * BK; ib += 2 * BK; return; }
+        if (iseq + nslot < seq_end) {
+            iseq += nslot; ikt = 0; ibuf = ibuf == NSV - 1 ? 0 : ibuf + 1;
+            set_issue_tile(iseq);
+            issue_tile_vectors(ibuf);
+        } else {
+            ikt = KT - 2;
+        }
+    };
+
+    // fragment offsets inside a stage (row rr, k-step ks, half hh): rr*64 + ((2ks+hh) ^ ((rr>>2)&3))*16
+    int fo[2][NFR];
+#pragma unroll
+    for (int t = 0; t < NFR; ++t) {
+        const int rr = (t < TN ? wn * TN * 32 + t * 32 : wm * TM * 32 + (t - TN) * 32) + ml;
+        const int base = (t < TN ? A_BYTES : 0) + rr * 64;
+        fo[0][t] = base + (((0 + hh) ^ ((rr >> 2) & 3)) << 4);
+        fo[1][t] = base + (((2 + hh) ^ ((rr >> 2) & 3)) << 4);
+    }
+
+    // prologue: the first tile's vectors and the three pairs of the ring in flight, slab 0 landed
+    set_issue_tile(seq);
+    issue_tile_vectors(0);
+#pragma unroll
+    for (int p0 = 0; p0 < NS / 2; ++p0) {
+#pragma unroll
+        for (int j = 0; j < 2 * NW; ++j) issue_pair(j, 2 * p0);
+        advance();
+    }
+    wait_vm_barrier<(NS / 2 - 1) * 2 * NW + 1>();                 // only the last load of slab 1 and the two younger pairs may be out
+
+    v16i acc[TM][TN], prev[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) { acc[i][j][r] = 0; prev[i][j][r] = 0; }
+    v4i f0[NFR], f1[NFR];
+#pragma unroll
+    for (int t = 0; t < NFR; ++t) f0[t] = *reinterpret_cast<const v4i*>(smem + fo[0][t]);
+
+    // ---- the tile whose epilogue is being drained: none yet (row origin M switches every store off)
+    int m0p = g.M, n0p = 0;
+    float* svp = sv0 + (NSV - 1) * SVF;
+    const bool al8 = g.ldc % 8 == 0;                             // rows of C start on 8-element boundaries
+    bool interior = false;                                       // the draining tile lies inside C and its rows are aligned: plain wide stores
+    // state of the piece in flight (8 outputs of one row per lane)
+    float ey[8], ez[8], ep[8];
+    v4f ecs[2], ebs[2], eos[2];
+    float ers = 1.0f;
+    // Step s of the epilogue of the previous tile.  Piece pc = s / 16 covers, for output row
+    // wm*64 + i*32 + ml (i = pc / 4), the 4-column groups q = pc % 4 of both accumulators of that row:
+    // columns wn*64 + 8q + 4hh + t and + 32.  After the lane-half exchange a lane owns 8 contiguous columns.
+    auto epi_step = [&](auto S) {
+        constexpr int s = decltype(S)::value, pc = s / NSTEP, st = s % NSTEP, i = pc / 4, qq = pc % 4;
+        const int rowl = wm * 64 + i * 32 + ml, c0 = wn * 64 + 8 * qq + 4 * hh;
+        if constexpr (s == 0 && EPI == HERO_EPI_GELU_REQUANT) {
+            // S_a -> 1 / S_a once per tile (IEEE division), published by the barrier in the middle of this slab;
+            // the first read is in step 10 of piece 0, well behind it
+            if (tid < BN) svp[SV_OS + tid] = __fdiv_rn(1.0f, svp[SV_OS + tid]);
+        }
+        if constexpr (EPI == HERO_EPI_RAW_I32) {
+            if constexpr (st == 1) {
+                const int row = m0p + rowl;
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    const int col = n0p + c0 + 32 * j;
+                    const uint32_t d[4] = {(uint32_t)prev[i][j][4 * qq], (uint32_t)prev[i][j][4 * qq + 1],
+                                           (uint32_t)prev[i][j][4 * qq + 2], (uint32_t)prev[i][j][4 * qq + 3]};
+                    int8_t* cp = (int8_t*)g.C + ((int64_t)row * g.ldc + col) * 4;
+                    if (interior) *reinterpret_cast<v4i*>(cp) = v4i{(int)d[0], (int)d[1], (int)d[2], (int)d[3]};
+                    else if (row < g.M && col < g.N) store_piece<4, 4>(cp, d, col, g.N, col + 4 <= g.N, true);
+                }
+            }
+        } else {
+            if constexpr (st == 0) {
+                ecs[0] = *reinterpret_cast<const v4f*>(svp + SV_CS + c0);
+                ecs[1] = *reinterpret_cast<const v4f*>(svp + SV_CS + c0 + 32);
+                ebs[0] = *reinterpret_cast<const v4f*>(svp + SV_BIAS + c0);
+                ebs[1] = *reinterpret_cast<const v4f*>(svp + SV_BIAS + c0 + 32);
+                ers = svp[SV_RS + rowl];
+            } else if constexpr (st == 1) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) ey[e] = (float)prev[i][e >> 2][4 * qq + (e & 3)];
+            } else if constexpr (st == 2) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) ey[e] = ey[e] * ers;
+            } else if constexpr (st == 3) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) ey[e] = fmaf(ey[e], ecs[e >> 2][e & 3], ebs[e >> 2][e & 3]);
+            } else if constexpr (GELU && st == 4) {               // erf-form GELU as in gelu_erf(), cut into steps
+#pragma unroll
+                for (int e = 0; e < 8; ++e) { ez[e] = fminf(fabsf(ey[e]), 6.0f); ep[e] = fmaf(3.309558087e-05f, ez[e], -7.692443905e-04f); }
+            } else if constexpr (GELU && st == 5) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) { ep[e] = fmaf(ep[e], ez[e], 8.080800064e-03f); ep[e] = fmaf(ep[e], ez[e], -5.341223627e-02f); }
+            } else if constexpr (GELU && st == 6) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) { ep[e] = fmaf(ep[e], ez[e], -4.587708712e-01f); ep[e] = fmaf(ep[e], ez[e], -1.151201725e+00f); }
+            } else if constexpr (GELU && st == 7) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) ep[e] = fmaf(ep[e], ez[e], -9.999930859e-01f);
+            } else if constexpr (GELU && st == 8) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) ep[e] = __builtin_amdgcn_exp2f(ep[e]);
+            } else if constexpr (GELU && st == 9) {
+#pragma unroll
+                for (int e = 4; e < 8; ++e) ep[e] = __builtin_amdgcn_exp2f(ep[e]);
+            } else if constexpr (GELU && st == 10) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) ez[e] = fmaxf(ey[e], 0.0f);
+                if constexpr (EPI == HERO_EPI_GELU_REQUANT) {
+                    eos[0] = *reinterpret_cast<const v4f*>(svp + SV_OS + c0);
+                    eos[1] = *reinterpret_cast<const v4f*>(svp + SV_OS + c0 + 32);
+                }
+            } else if constexpr (GELU && st == 11) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) ey[e] = fmaf(-fabsf(ey[e]), ep[e], ez[e]);
+            } else if constexpr (EPI == HERO_EPI_GELU_REQUANT && st == 12) {
+                // GELU^quant is in the +-1 LSB class (fp32 GELU against the definition's fp64): the division by
+                // S_a[j] is a multiplication by the correctly rounded reciprocal
+#pragma unroll
+                for (int e = 0; e < 8; ++e) ey[e] = ey[e] * eos[e >> 2][e & 3];
+            } else if constexpr (ES == 1 && st == 13) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) ey[e] = __builtin_amdgcn_fmed3f(ey[e], -127.0f, 127.0f);
+            } else if constexpr (ES == 1 && st == 14) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) ey[e] = ey[e] + 12582912.0f;   // rne_low_byte(): the low byte of the sum is the code
+            } else if constexpr (st == 15) {
+                const int row = m0p + rowl, col = n0p + wn * 64 + hh * 32 + 8 * qq;   // first of this lane's 8 columns
+                const bool ok = row < g.M && col < g.N, full = col + 8 <= g.N;   // (only looked at on the edge tiles)
+                if constexpr (ES == 1) {
+                    const uint32_t w0 = pack_low_bytes(__float_as_uint(ey[0]), __float_as_uint(ey[1]), __float_as_uint(ey[2]), __float_as_uint(ey[3]));
+                    const uint32_t w1 = pack_low_bytes(__float_as_uint(ey[4]), __float_as_uint(ey[5]), __float_as_uint(ey[6]), __float_as_uint(ey[7]));
+                    uint32_t d[2];
+                    swap32(w0, w1, d[0], d[1]);
+                    int8_t* cp = (int8_t*)g.C + (int64_t)row * g.ldc + col;
+                    if (interior) *reinterpret_cast<v2i*>(cp) = v2i{(int)d[0], (int)d[1]};
+                    else if (ok) store_piece<1, 2>(cp, d, col, g.N, full, false);
+                } else {
+                    uint32_t d[4];
+                    swap32(pack2_hp<CDT>(ey[0], ey[1]), pack2_hp<CDT>(ey[4], ey[5]), d[0], d[2]);
+                    swap32(pack2_hp<CDT>(ey[2], ey[3]), pack2_hp<CDT>(ey[6], ey[7]), d[1], d[3]);
+                    int8_t* cp = (int8_t*)g.C + ((int64_t)row * g.ldc + col) * 2;
+                    if (interior) *reinterpret_cast<v4i*>(cp) = v4i{(int)d[0], (int)d[1], (int)d[2], (int)d[3]};
+                    else if (ok) store_piece<2, 4>(cp, d, col, g.N, full, false);
+                }
+            }
+        }
+    };
+
+    int stage = 0, buf = 0;
+    // One slab: the barrier sits in the middle (k-step 0 runs on fragments read during the previous slab, the
+    // barrier makes slab kt+1 visible, k-step 1 runs while its first fragments and, in odd slabs, the direct loads
+    // of the pair five slabs ahead are issued).  In program order the loads of a pair alternate between its two
+    // slabs, so "slab kt+1 has landed" is: at most the pair's last load and the two younger pairs outstanding in an
+    // odd slab, the two younger pairs in an even one.  The stores of the epilogue steps count in vmcnt as well; they
+    // can only make the wait longer, never shorter than needed (loads return in order among themselves).
+    auto iteration = [&](auto ODD, auto SLOT0, auto FIRST) {
+        constexpr bool odd = decltype(ODD)::value, first = decltype(FIRST)::value;
+        constexpr int s0 = decltype(SLOT0)::value;                   // first epilogue step of this slab; < 0: none
+        const int8_t* st = smem + stage * STAGE;
+        const int nstage = stage + 1 == NS ? 0 : stage + 1;
+        const int pstage = stage == 0 ? NS - 1 : stage - 1;
+        const int8_t* stn = smem + nstage * STAGE;
+        __builtin_amdgcn_sched_barrier(0);
+        static_for<NM>([&](auto N_) {                                // k-step 0
+            constexpr int n = decltype(N_)::value, jj = n / TM, ii = n % TM;
+            if constexpr (first) {
+                const v16i zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+                acc[ii][jj] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f0[jj], f0[TN + ii], zero, 0, 0, 0);
+            } else {
+                acc[ii][jj] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f0[jj], f0[TN + ii], acc[ii][jj], 0, 0, 0);
+            }
+            if constexpr (n < NFR / 2) {                             // early: the reads must be back before the barrier
+                f1[2 * n] = *reinterpret_cast<const v4i*>(st + fo[1][2 * n]);
+                f1[2 * n + 1] = *reinterpret_cast<const v4i*>(st + fo[1][2 * n + 1]);
+            }
+            if constexpr (s0 >= 0) epi_step(std::integral_constant<int, (s0 >= 0 ? s0 + n : 0)>{});
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        wait_vm_barrier<odd ? 2 * NW + 1 : 4 * NW>();
+        __builtin_amdgcn_sched_barrier(0);
+        static_for<NM>([&](auto N_) {                                // k-step 1
+            constexpr int n = decltype(N_)::value, jj = n / TM, ii = n % TM;
+            acc[ii][jj] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f1[jj], f1[TN + ii], acc[ii][jj], 0, 0, 0);
+            if constexpr (n < NFR / 2) {
+                f0[2 * n] = *reinterpret_cast<const v4i*>(stn + fo[0][2 * n]);
+                f0[2 * n + 1] = *reinterpret_cast<const v4i*>(stn + fo[0][2 * n + 1]);
+            }
+            if constexpr (odd && n < NW) { issue_pair(2 * n, pstage); issue_pair(2 * n + 1, pstage); }
+            if constexpr (s0 >= 0) epi_step(std::integral_constant<int, (s0 >= 0 ? s0 + NM + n : 0)>{});
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        if (odd) advance();
+        stage = nstage;
+    };
+
+    for (;;) {
+        // the first SPREAD slabs carry the epilogue of the previous tile, one step behind every matrix instruction
+        static_for<SPREAD>([&](auto I_) {
+            constexpr int it = decltype(I_)::value;
+            iteration(std::integral_constant<bool, (it & 1) != 0>{}, std::integral_constant<int, it * 2 * NM>{},
+                      std::integral_constant<bool, it == 0>{});
+        });
+        for (int kt = SPREAD; kt < KT; kt += 2) {
+            iteration(std::false_type{}, std::integral_constant<int, -1>{}, std::false_type{});
+            iteration(std::true_type{}, std::integral_constant<int, -1>{}, std::false_type{});
+        }
+        // hand the finished accumulators to the epilogue that runs inside the next tile
+        tile_from_seq<BM, BN>(g, seq, m0p, n0p);
+        interior = __builtin_amdgcn_readfirstlane((int)(al8 && m0p + BM <= g.M && n0p + BN <= g.N)) != 0;
+        svp = sv0 + buf * SVF;
+        buf = buf == NSV - 1 ? 0 : buf + 1;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) prev[i][j] = acc[i][j];
+        seq += nslot;
+        if (seq >= seq_end) break;
+    }
+    // the last tile's epilogue, unhidden
+    static_for<NPIECE * NSTEP>([&](auto S) {
+        epi_step(S);
+        if constexpr (decltype(S)::value == 3 && EPI == HERO_EPI_GELU_REQUANT) wait_vm_barrier<63>();   // publishes 1 / S_a
+    });
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));                      // the redundant tail loads
+}
+
 // Split-K for skinny M with a long K (M <= 128, K >= 8192, at most 128 tiles: the weights are streamed once and
 // too few tiles exist to do that from every CU).  Pass 1: the register-staged kernel with a second grid dimension over K ranges writes raw int32
 // partial sums, one [M][ldp] plane per range, into the caller's scratch.  Pass 2 (splitk_reduce_kernel) adds
@@ -975,10 +1322,26 @@ hero_status launch_persistent(const GemmArgs& g, int wg_per_cu, hipStream_t st) 
     return hero_launch_status();
 }
 
+// The persistent kernel with the epilogue inside the next tile's main loop (256 x 128 tiles).
+template <int EPI, int CDT>
+hero_status launch_ovl(const GemmArgs& g, hipStream_t st) {
+    GemmArgs gp = g;
+    gp.ntm = (g.M + 255) / 256; gp.ntn = (g.N + 127) / 128;
+    const int64_t tiles = (int64_t)gp.ntm * gp.ntn;
+    if (tiles > 0x7fffff00LL) return HERO_ERR_SHAPE;
+    gp.per_xcd = (int)((tiles + NUM_XCD - 1) / NUM_XCD);
+    const int nslot = gp.per_xcd < 32 ? gp.per_xcd : 32;              // one workgroup per CU (152 KB of LDS), 32 CUs per XCD
+    hipLaunchKernelGGL((int8_gemm_ovl_kernel<EPI, CDT>), dim3((unsigned)(nslot * NUM_XCD)), dim3(512), 0, st, gp);
+    return hero_launch_status();
+}
+
+// tile: -1 = chosen from the problem size (the product path); 0 = 128x128 register-staged, 1 = 256x256 one tile per
+// workgroup, 2 = 64x64, 7 = 256x256 persistent, 8 = 128x128 persistent, 9 = 256x128 persistent with the overlapped
+// epilogue (forced by the test entry point hero_int8_gemm_tile only; a forced kernel that cannot run the shape falls
+// back to its one-tile-per-workgroup relative).
 template <int EPI, int CDT, int RDT>
-hero_status launch_epi(const GemmArgs& g, void* ws, size_t ws_bytes, hipStream_t st) {
-    const char* e = getenv("HERO_GEMM_TILE");
-    int cfg = e ? atoi(e) : -1;
+hero_status launch_epi(const GemmArgs& g, void* ws, size_t ws_bytes, hipStream_t st, int tile) {
+    int cfg = tile;
     if (cfg < 0 && ws) {                                               // skinny M with a workspace: split K
         const SplitK p = splitk_plan(g.M, g.N, g.K);
         if (p.ksplit > 1 && ws_bytes >= p.bytes) return launch_splitk<EPI, CDT, RDT>(g, p, ws, st);
@@ -986,14 +1349,19 @@ hero_status launch_epi(const GemmArgs& g, void* ws, size_t ws_bytes, hipStream_t
     // persistent kernels: K long enough that the slab ring never runs more than one tile ahead, whole pairs of
     // slabs, 32-bit per-lane offsets (256 rows of lda / ldb bytes)
     const bool pers_ok = g.K >= 4 * BK && g.K % (2 * BK) == 0 && g.lda < (1 << 24) && g.ldb < (1 << 24);
+    // the overlapped-epilogue kernel: its epilogue is spread over the first 16 slabs of the next tile; no fused residual
+    const bool ovl_ok = pers_ok && g.K >= 16 * BK && RDT < 0;
     if (cfg < 0) {
         const int64_t t256 = (int64_t)((g.M + 255) / 256) * ((g.N + 255) / 256), t128 = (int64_t)((g.M + 127) / 128) * ((g.N + 127) / 128);
         if (t256 >= 160) cfg = !pers_ok ? 1 : ((t256 > 256 && t256 < 384) ? 8 : 7);
         else if (g.M <= 64 || t128 < 192) cfg = 2;
         else cfg = pers_ok ? 8 : 0;
+    } else if (cfg == 9 && !ovl_ok) {
+        cfg = pers_ok ? 7 : 1;
     } else if ((cfg == 7 || cfg == 8) && !pers_ok) {
         cfg = cfg == 7 ? 1 : 0;
     }
+    if constexpr (RDT < 0) { if (cfg == 9) return launch_ovl<EPI, CDT>(g, st); }
     if (cfg == 7) return launch_persistent<256, 256, 2, 4, EPI, CDT, RDT>(g, 1, st);
     if (cfg == 8) return launch_persistent<128, 128, 2, 2, EPI, CDT, RDT>(g, 2, st);
     if (cfg == 1) return launch_grid(g, 256, 256, 512, int8_gemm_dma_kernel<256, 256, 2, 4, 4, 2, EPI, CDT, RDT>, st);
@@ -1013,7 +1381,7 @@ hero_status launch_epi(const GemmArgs& g, void* ws, size_t ws_bytes, hipStream_t
 
 // bf16 operands through the persistent kernels (called by hero_bf16_gemm for large problems;
 // HERO_ERR_UNSUPPORTED means "not this kernel's case", the caller then uses its own).  The tile is chosen as for
-// INT8 operands; HERO_BF16_TILE = 7 / 8 / 0 forces the 256x256 / 128x128 form / the caller's kernel for tuning runs and tests.
+// INT8 operands; tile = 7 / 8 / 0 (from the test entry point hero_bf16_gemm_tile) forces the 256x256 / 128x128 form / the caller's kernel, -1 chooses.
 namespace {
 template <int BM, int BN, int WM, int WN>
 hero_status launch_bf16_persistent(GemmArgs g, int wg_per_cu, bool gelu, hipStream_t st) {
@@ -1035,7 +1403,7 @@ hero_status launch_bf16_persistent(GemmArgs g, int wg_per_cu, bool gelu, hipStre
 
 hero_status hero_bf16_gemm_large(const void* A, int64_t lda, const void* Wt, int64_t ldb,
                                  const float* bias, const void* residual, int64_t ldr, int gelu,
-                                 void* C, int64_t ldc, int64_t M, int64_t N, int64_t K, hipStream_t st) {
+                                 void* C, int64_t ldc, int64_t M, int64_t N, int64_t K, hipStream_t st, int tile) {
     const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256), t128 = ((M + 127) / 128) * ((N + 127) / 128);
     if (t128 < 192 || t128 > 0x7fffff00LL || K % 64 != 0 || K * 2 < 4 * BK || lda * 2 >= (1 << 24) || ldb * 2 >= (1 << 24))
         return HERO_ERR_UNSUPPORTED;
@@ -1044,8 +1412,7 @@ hero_status hero_bf16_gemm_large(const void* A, int64_t lda, const void* Wt, int
     g.b_col_scale = nullptr; g.bias = bias; g.residual = residual; g.ldr = ldr; g.out_col_scale = nullptr;
     g.C = C; g.ldc = ldc; g.M = (int)M; g.N = (int)N; g.K = (int)(K * 2);
     g.ksplit = 1; g.kslabs = 0;
-    const char* e = getenv("HERO_BF16_TILE");
-    const int cfg = e ? atoi(e) : ((t256 < 160 || (t256 > 256 && t256 < 384)) ? 8 : 7);
+    const int cfg = tile >= 0 ? tile : ((t256 < 160 || (t256 > 256 && t256 < 384)) ? 8 : 7);
     if (cfg == 0) return HERO_ERR_UNSUPPORTED;
     if (cfg == 8) return launch_bf16_persistent<128, 128, 2, 2>(g, 2, gelu != 0, st);
     return launch_bf16_persistent<256, 256, 2, 4>(g, 1, gelu != 0, st);
@@ -1053,11 +1420,10 @@ hero_status hero_bf16_gemm_large(const void* A, int64_t lda, const void* Wt, int
 
 // The FP8 variant: the same kernels with E4M3 operands (no split-K: fp32 partial sums would not commute).
 template <int EPI, int CDT, int RDT>
-hero_status launch_epi_fp8(GemmArgs g, hipStream_t st) {
+hero_status launch_epi_fp8(GemmArgs g, hipStream_t st, int cfg) {
     const int64_t t256 = (int64_t)((g.M + 255) / 256) * ((g.N + 255) / 256), t128 = (int64_t)((g.M + 127) / 128) * ((g.N + 127) / 128);
     const bool pers_ok = t128 <= 0x7fffff00LL && g.K >= 4 * BK && g.K % (2 * BK) == 0 && g.lda < (1 << 24) && g.ldb < (1 << 24);
-    const char* e = getenv("HERO_FP8_TILE");                          // tuning runs and tests: 0 / 7 / 8 as for HERO_GEMM_TILE
-    const int cfg = e ? atoi(e) : -1;
+    // cfg: -1 = chosen here; 0 / 7 / 8 forced by the test entry point hero_fp8_gemm_tile
     const bool small = g.M <= 64 || t128 < 192;
     if (pers_ok && (cfg == 7 || cfg == 8 || (cfg < 0 && !small))) {
         const bool tile128 = cfg == 8 || (cfg < 0 && (t256 < 160 || (t256 > 256 && t256 < 384)));
@@ -1079,12 +1445,12 @@ hero_status launch_epi_fp8(GemmArgs g, hipStream_t st) {
     return launch_grid(g, 128, 128, 256, int8_gemm_kernel<128, 128, 2, 2, 2, 2, EPI, CDT, RDT, false, 1, HERO_F8E4M3>, st);
 }
 
-extern "C" hero_status hero_fp8_gemm(const void* A, int64_t lda, const float* a_row_scale,
-                                     const void* Bt, int64_t ldb, const float* b_col_scale,
-                                     const float* bias, const void* residual, hero_dtype res_dt, int64_t ldr,
-                                     hero_epilogue epi, const float* out_col_scale,
-                                     void* C, hero_dtype c_dt, int64_t ldc,
-                                     int64_t M, int64_t N, int64_t K, void* stream) {
+static hero_status run_fp8_gemm(const void* A, int64_t lda, const float* a_row_scale,
+                                const void* Bt, int64_t ldb, const float* b_col_scale,
+                                const float* bias, const void* residual, hero_dtype res_dt, int64_t ldr,
+                                hero_epilogue epi, const float* out_col_scale,
+                                void* C, hero_dtype c_dt, int64_t ldc,
+                                int64_t M, int64_t N, int64_t K, void* stream, int tile) {
     if (M < 0 || N < 0 || K <= 0) return HERO_ERR_SHAPE;
     if (M > 0x7fffffffLL || N > 0x7fffffffLL || K > 0x7fffffffLL) return HERO_ERR_SHAPE;
     if (K % KMULT != 0) return HERO_ERR_UNSUPPORTED;
@@ -1112,17 +1478,17 @@ extern "C" hero_status hero_fp8_gemm(const void* A, int64_t lda, const float* a_
     g.ksplit = 1; g.kslabs = 0;
     hipStream_t st = (hipStream_t)stream;
     switch (epi) {
-    case HERO_EPI_REQUANT: return launch_epi_fp8<HERO_EPI_REQUANT, HERO_F8E4M3, -1>(g, st);
-    case HERO_EPI_GELU_REQUANT: return launch_epi_fp8<HERO_EPI_GELU_REQUANT, HERO_F8E4M3, -1>(g, st);
+    case HERO_EPI_REQUANT: return launch_epi_fp8<HERO_EPI_REQUANT, HERO_F8E4M3, -1>(g, st, tile);
+    case HERO_EPI_GELU_REQUANT: return launch_epi_fp8<HERO_EPI_GELU_REQUANT, HERO_F8E4M3, -1>(g, st, tile);
     case HERO_EPI_DEQUANT_GELU:
-        return c_dt == HERO_BF16 ? launch_epi_fp8<HERO_EPI_DEQUANT_GELU, HERO_BF16, -1>(g, st)
-                                 : launch_epi_fp8<HERO_EPI_DEQUANT_GELU, HERO_F16, -1>(g, st);
+        return c_dt == HERO_BF16 ? launch_epi_fp8<HERO_EPI_DEQUANT_GELU, HERO_BF16, -1>(g, st, tile)
+                                 : launch_epi_fp8<HERO_EPI_DEQUANT_GELU, HERO_F16, -1>(g, st, tile);
     default:
         if (!residual)
-            return c_dt == HERO_BF16 ? launch_epi_fp8<HERO_EPI_DEQUANT, HERO_BF16, -1>(g, st)
-                                     : launch_epi_fp8<HERO_EPI_DEQUANT, HERO_F16, -1>(g, st);
-        return c_dt == HERO_BF16 ? launch_epi_fp8<HERO_EPI_DEQUANT, HERO_BF16, HERO_BF16>(g, st)
-                                 : launch_epi_fp8<HERO_EPI_DEQUANT, HERO_F16, HERO_F16>(g, st);
+            return c_dt == HERO_BF16 ? launch_epi_fp8<HERO_EPI_DEQUANT, HERO_BF16, -1>(g, st, tile)
+                                     : launch_epi_fp8<HERO_EPI_DEQUANT, HERO_F16, -1>(g, st, tile);
+        return c_dt == HERO_BF16 ? launch_epi_fp8<HERO_EPI_DEQUANT, HERO_BF16, HERO_BF16>(g, st, tile)
+                                 : launch_epi_fp8<HERO_EPI_DEQUANT, HERO_F16, HERO_F16>(g, st, tile);
     }
 }
 
@@ -1175,13 +1541,13 @@ hero_status check_gemm_args(const int8_t* A, int64_t lda, const int8_t* Bt, int6
 }
 }  // namespace
 
-extern "C" hero_status hero_int8_gemm_ws(const int8_t* A, int64_t lda, const float* a_row_scale,
-                                         const int8_t* Bt, int64_t ldb, const float* b_col_scale,
-                                         const float* bias, const void* residual, hero_dtype res_dt, int64_t ldr,
-                                         hero_epilogue epi, const float* out_col_scale,
-                                         void* C, hero_dtype c_dt, int64_t ldc,
-                                         int64_t M, int64_t N, int64_t K,
-                                         void* workspace, size_t workspace_bytes, void* stream) {
+static hero_status run_int8_gemm(const int8_t* A, int64_t lda, const float* a_row_scale,
+                                 const int8_t* Bt, int64_t ldb, const float* b_col_scale,
+                                 const float* bias, const void* residual, hero_dtype res_dt, int64_t ldr,
+                                 hero_epilogue epi, const float* out_col_scale,
+                                 void* C, hero_dtype c_dt, int64_t ldc,
+                                 int64_t M, int64_t N, int64_t K,
+                                 void* workspace, size_t workspace_bytes, void* stream, int tile) {
     if (workspace && ((uintptr_t)workspace & 255)) return HERO_ERR_WORKSPACE;
     bool noop = false;
     const hero_status cs = check_gemm_args(A, lda, Bt, ldb, b_col_scale, residual, res_dt, ldr, epi, out_col_scale,
@@ -1195,20 +1561,64 @@ extern "C" hero_status hero_int8_gemm_ws(const int8_t* A, int64_t lda, const flo
     g.ksplit = 1; g.kslabs = 0;
     hipStream_t st = (hipStream_t)stream;
     switch (epi) {
-    case HERO_EPI_RAW_I32: return launch_epi<HERO_EPI_RAW_I32, HERO_I32, -1>(g, workspace, workspace_bytes, st);
-    case HERO_EPI_REQUANT: return launch_epi<HERO_EPI_REQUANT, HERO_I8, -1>(g, workspace, workspace_bytes, st);
-    case HERO_EPI_GELU_REQUANT: return launch_epi<HERO_EPI_GELU_REQUANT, HERO_I8, -1>(g, workspace, workspace_bytes, st);
+    case HERO_EPI_RAW_I32: return launch_epi<HERO_EPI_RAW_I32, HERO_I32, -1>(g, workspace, workspace_bytes, st, tile);
+    case HERO_EPI_REQUANT: return launch_epi<HERO_EPI_REQUANT, HERO_I8, -1>(g, workspace, workspace_bytes, st, tile);
+    case HERO_EPI_GELU_REQUANT: return launch_epi<HERO_EPI_GELU_REQUANT, HERO_I8, -1>(g, workspace, workspace_bytes, st, tile);
     case HERO_EPI_DEQUANT_GELU:
-        return c_dt == HERO_BF16 ? launch_epi<HERO_EPI_DEQUANT_GELU, HERO_BF16, -1>(g, workspace, workspace_bytes, st)
-                                 : launch_epi<HERO_EPI_DEQUANT_GELU, HERO_F16, -1>(g, workspace, workspace_bytes, st);
+        return c_dt == HERO_BF16 ? launch_epi<HERO_EPI_DEQUANT_GELU, HERO_BF16, -1>(g, workspace, workspace_bytes, st, tile)
+                                 : launch_epi<HERO_EPI_DEQUANT_GELU, HERO_F16, -1>(g, workspace, workspace_bytes, st, tile);
     case HERO_EPI_DEQUANT:
         if (!residual)
-            return c_dt == HERO_BF16 ? launch_epi<HERO_EPI_DEQUANT, HERO_BF16, -1>(g, workspace, workspace_bytes, st)
-                                     : launch_epi<HERO_EPI_DEQUANT, HERO_F16, -1>(g, workspace, workspace_bytes, st);
-        if (c_dt == HERO_BF16) return launch_epi<HERO_EPI_DEQUANT, HERO_BF16, HERO_BF16>(g, workspace, workspace_bytes, st);
-        return launch_epi<HERO_EPI_DEQUANT, HERO_F16, HERO_F16>(g, workspace, workspace_bytes, st);
+            return c_dt == HERO_BF16 ? launch_epi<HERO_EPI_DEQUANT, HERO_BF16, -1>(g, workspace, workspace_bytes, st, tile)
+                                     : launch_epi<HERO_EPI_DEQUANT, HERO_F16, -1>(g, workspace, workspace_bytes, st, tile);
+        if (c_dt == HERO_BF16) return launch_epi<HERO_EPI_DEQUANT, HERO_BF16, HERO_BF16>(g, workspace, workspace_bytes, st, tile);
+        return launch_epi<HERO_EPI_DEQUANT, HERO_F16, HERO_F16>(g, workspace, workspace_bytes, st, tile);
     default: return HERO_ERR_UNSUPPORTED;
     }
+}
+
+extern "C" hero_status hero_int8_gemm_ws(const int8_t* A, int64_t lda, const float* a_row_scale,
+                                         const int8_t* Bt, int64_t ldb, const float* b_col_scale,
+                                         const float* bias, const void* residual, hero_dtype res_dt, int64_t ldr,
+                                         hero_epilogue epi, const float* out_col_scale,
+                                         void* C, hero_dtype c_dt, int64_t ldc,
+                                         int64_t M, int64_t N, int64_t K,
+                                         void* workspace, size_t workspace_bytes, void* stream) {
+    return run_int8_gemm(A, lda, a_row_scale, Bt, ldb, b_col_scale, bias, residual, res_dt, ldr, epi, out_col_scale,
+                         C, c_dt, ldc, M, N, K, workspace, workspace_bytes, stream, -1);
+}
+
+extern "C" hero_status hero_fp8_gemm(const void* A, int64_t lda, const float* a_row_scale,
+                                     const void* Bt, int64_t ldb, const float* b_col_scale,
+                                     const float* bias, const void* residual, hero_dtype res_dt, int64_t ldr,
+                                     hero_epilogue epi, const float* out_col_scale,
+                                     void* C, hero_dtype c_dt, int64_t ldc,
+                                     int64_t M, int64_t N, int64_t K, void* stream) {
+    return run_fp8_gemm(A, lda, a_row_scale, Bt, ldb, b_col_scale, bias, residual, res_dt, ldr, epi, out_col_scale,
+                        C, c_dt, ldc, M, N, K, stream, -1);
+}
+
+// Test and tuning hooks (include/hero_debug.h): the same calls with the kernel choice forced.
+extern "C" hero_status hero_int8_gemm_tile(const int8_t* A, int64_t lda, const float* a_row_scale,
+                                           const int8_t* Bt, int64_t ldb, const float* b_col_scale,
+                                           const float* bias, const void* residual, hero_dtype res_dt, int64_t ldr,
+                                           hero_epilogue epi, const float* out_col_scale,
+                                           void* C, hero_dtype c_dt, int64_t ldc,
+                                           int64_t M, int64_t N, int64_t K, void* stream, int tile) {
+    if (tile != 0 && tile != 1 && tile != 2 && tile != 7 && tile != 8 && tile != 9) return HERO_ERR_UNSUPPORTED;
+    return run_int8_gemm(A, lda, a_row_scale, Bt, ldb, b_col_scale, bias, residual, res_dt, ldr, epi, out_col_scale,
+                         C, c_dt, ldc, M, N, K, nullptr, 0, stream, tile);
+}
+
+extern "C" hero_status hero_fp8_gemm_tile(const void* A, int64_t lda, const float* a_row_scale,
+                                          const void* Bt, int64_t ldb, const float* b_col_scale,
+                                          const float* bias, const void* residual, hero_dtype res_dt, int64_t ldr,
+                                          hero_epilogue epi, const float* out_col_scale,
+                                          void* C, hero_dtype c_dt, int64_t ldc,
+                                          int64_t M, int64_t N, int64_t K, void* stream, int tile) {
+    if (tile != 0 && tile != 7 && tile != 8) return HERO_ERR_UNSUPPORTED;
+    return run_fp8_gemm(A, lda, a_row_scale, Bt, ldb, b_col_scale, bias, residual, res_dt, ldr, epi, out_col_scale,
+                        C, c_dt, ldc, M, N, K, stream, tile);
 }
 
 // ---- hero_int8_gemm_static: the split-K scratch lives in the library ---------------------------------------

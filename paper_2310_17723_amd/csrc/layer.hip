@@ -133,6 +133,16 @@ extern "C" hero_status hero_layer_fwd(const hero_layer_desc* desc, const hero_la
     if (desc->mask == HERO_MASK_PADDING && !io->kv_len) return HERO_ERR_NULL;
     if (Dh != 64 && Dh != 128) return HERO_ERR_UNSUPPORTED;
     if (d % 64 || f % 64) return HERO_ERR_UNSUPPORTED;
+    // what the chained entry points would refuse only after earlier stages had been enqueued (and, pre-LN, after
+    // h had been partly updated in place): the GeMM^quant row bound, the LN^quant row width (a row lives in one
+    // wavefront's registers: 8192 columns behind INT8 addends, 4096 behind the 16-bit residual stream), alignment
+    if (T >= (1LL << 23)) return HERO_ERR_SHAPE;
+    if (d > (pre ? 4096 : 8192)) return HERO_ERR_UNSUPPORTED;
+    {
+        const void* const ptrs[] = {w->w_qkv, w->w_o, w->w_1, w->w_2, w->w_o_bf16, w->w_2_bf16, io->x_q, io->out_q, io->h,
+                                    io->k_cache, io->v_cache};
+        for (const void* p : ptrs) if (!hero_aligned16(p)) return HERO_ERR_ALIGN;
+    }
 
     char* base = (char*)workspace;
     int8_t* xin_q = pre ? (int8_t*)(base + ws.xin_q) : const_cast<int8_t*>(io->x_q);

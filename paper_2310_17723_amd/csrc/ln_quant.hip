@@ -106,7 +106,11 @@ __global__ __launch_bounds__(64 * ln_max_waves(NCH)) void ln_quant_kernel(LnArgs
     constexpr int EPL = X_I8 ? 16 : 8;
     constexpr int CH = EPL * HERO_WAVE;
     constexpr bool r_i8 = RDT == HERO_I8, r_hp = RDT == HERO_BF16 || RDT == HERO_F16;
-    constexpr int PF = 1;                                     // rows in flight ahead of the current one
+    // rows in flight ahead of the current one.  Measured at D = 1024 (one 16-wave workgroup per CU): two rows ahead
+    // (25 more registers) and gamma / beta / S_o held in registers instead of LDS (no staging, no barrier before the
+    // first row; 35 more registers) are both 5-12 % SLOWER at 16384 rows and equal at 65536: the kernel runs at the
+    // rate of a plain copy of the same size once it streams, what is left is the ramp of a 15 us launch.
+    constexpr int PF = 1;
     extern __shared__ __attribute__((aligned(16))) float sp[];   // [3][Dp]: gamma, beta, r_col_scale
     const int D = a.D, Dp = NCH * CH;
     const int tid = threadIdx.x, lane = tid & 63, nwb = blockDim.x >> 6;
@@ -186,7 +190,6 @@ __global__ __launch_bounds__(64 * ln_max_waves(NCH)) void ln_quant_kernel(LnArgs
     if (row >= a.M) return;
     const bool in_f8 = !GATHER && a.in_fp8 != 0;
     const float inv_d = 1.0f / (float)D;
-    const float npad = (float)(Dp - D);                       // padded columns hold 0 and are corrected for in the variance
 
     auto process = [&](int64_t row, auto P) {
         constexpr int p = decltype(P)::value;
@@ -267,15 +270,18 @@ __global__ __launch_bounds__(64 * ln_max_waves(NCH)) void ln_quant_kernel(LnArgs
             const float mean = wave_reduce<false>(s) * inv_d;
             float q = 0.0f;
 #pragma unroll
-            for (int c = 0; c < NCH; ++c)
+            for (int c = 0; c < NCH; ++c) {
+                // a lane whose chunk lies in the padding (columns >= D; it holds zeros) stays out of the sum of
+                // squared deviations: it subtracts 0 instead of the mean
+                const float mean_c = c * CH + lane * EPL < D ? mean : 0.0f;
 #pragma unroll
                 for (int e = 0; e < EPL; ++e) {
-                    const float dlt = v[c][e] - mean;
+                    const float dlt = v[c][e] - mean_c;
                     v[c][e] = dlt;
                     q = fmaf(dlt, dlt, q);
                 }
-            // a padded column contributed (0 - mean)^2
-            const float var = fmaxf(fmaf(-npad * mean, mean, wave_reduce<false>(q)), 0.0f) * inv_d;
+            }
+            const float var = wave_reduce<false>(q) * inv_d;
             const float rstd = __builtin_amdgcn_rsqf(var + a.eps);
 #pragma unroll
             for (int c = 0; c < NCH; ++c) {

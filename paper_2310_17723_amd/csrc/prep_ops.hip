@@ -1,7 +1,7 @@
 // Model-load-time operators of the method, on the GPU (not on the hot path):
-//   hero_absmax_cols       the calibration statistic behind the FWQ / SQ scales (paper Sec. 2.1:
-//                          S_x is "calibrated in the pre-processing phase"; Sec. 3: the range recorded
-//                          over calibration batches, no truncation)
+//   hero_absmax_cols       the calibration statistic behind the FWQ / SQ scales (paper Sec. 2.1: these
+//                          scales are fixed by a calibration pass before inference; Sec. 3: the range
+//                          recorded over calibration batches, no truncation)
 //   hero_weight_fold_quant scale folding (Sec. 2.2.2: W~_q = W_q / S_q, W~_o = S_attn W_o / S_o;
 //                          Sec. 2.2.3: W~_2 = S_a W_2 / S_x2) followed by the column-wise weight
 //                          quantization W = W_int8 Diag(S_w) of Sec. 2.1, codes stored [N][K]

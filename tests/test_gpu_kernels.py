@@ -300,7 +300,7 @@ def test_gemm_gelu_epilogues(hero, M, N, K):
 
 
 @pytest.mark.parametrize("M,N,K", [(3300, 3400, 320), (2560, 2560, 256), (4000, 1700, 704), (3300, 3400, 384), (3500, 3100, 640)])
-def test_gemm_many_tiles_ragged_edges(hero, M, N, K, monkeypatch):
+def test_gemm_many_tiles_ragged_edges(hero, M, N, K):
     """Enough 256 x 256 tiles for the large-problem kernels (the persistent one included: several tiles
     per workgroup, ragged last row and column panels, K of 4 / 5 / 6 / 10 / 11 slabs: odd counts take the
     one-tile-per-workgroup kernel, fewer than 160 tiles the 128 x 128 one), strided operands and output;
@@ -324,26 +324,84 @@ def test_gemm_many_tiles_ragged_edges(hero, M, N, K, monkeypatch):
     res = O.f32_to_bf16(synth.rng(11).standard_normal((M, N)).astype(np.float32))
     ref_res = O.int8_gemm(A, Bt, a_row_scale=rs, b_col_scale=cs, bias=bias, residual=res, res_dt=O.BF16,
                           epi=O.EPI_DEQUANT, c_dt=O.BF16)
-    for tile in (None, "1", "7", "8"):             # default choice, one tile per workgroup, persistent 256 x 256 and 128 x 128
-        if tile is None:
-            monkeypatch.delenv("HERO_GEMM_TILE", raising=False)
-        else:
-            monkeypatch.setenv("HERO_GEMM_TILE", tile)
+    for tile in (None, 1, 7, 8):             # default choice, one tile per workgroup, persistent 256 x 256 and 128 x 128
         Cbuf = torch.full((M, N + 16), -7, dtype=torch.int8, device="cuda")
-        hero.hero_int8_gemm(dA, dB, dev(rs), dev(cs2), dev(b2), epi=HB.EPI_REQUANT, C_out=Cbuf[:, :N])
+        hero.hero_int8_gemm(dA, dB, dev(rs), dev(cs2), dev(b2), epi=HB.EPI_REQUANT, C_out=Cbuf[:, :N], tile=tile)
         assert_exact(to_np(Cbuf[:, :N]), ref, f"requant tile={tile}")
         assert (to_np(Cbuf[:, N:]) == -7).all()
-        got = hero.hero_int8_gemm(dA, dB, None, dev(cs2 * np.float32(0.01)), None, epi=HB.EPI_REQUANT, out_dtype=torch.int8)
+        got = hero.hero_int8_gemm(dA, dB, None, dev(cs2 * np.float32(0.01)), None, epi=HB.EPI_REQUANT, out_dtype=torch.int8, tile=tile)
         assert_exact(to_np(got), ref_plain, f"requant, no row scale, no bias, tile={tile}")
         got = hero.hero_int8_gemm(dA, dB, dev(rs), dev(csg), dev(bias), epi=HB.EPI_GELU_REQUANT,
-                                  out_col_scale=dev(s_a), out_dtype=torch.int8)
+                                  out_col_scale=dev(s_a), out_dtype=torch.int8, tile=tile)
         assert_codes(to_np(got), ref_g, f"gelu requant tile={tile}")
-        assert_exact(to_np(hero.hero_int8_gemm(dA, dB)), ref_raw, f"raw tile={tile}")
-        got = hero.hero_int8_gemm(dA, dB, dev(rs), dev(cs), dev(bias), epi=HB.EPI_DEQUANT, out_dtype=torch.float16)
+        assert_exact(to_np(hero.hero_int8_gemm(dA, dB, tile=tile)), ref_raw, f"raw tile={tile}")
+        got = hero.hero_int8_gemm(dA, dB, dev(rs), dev(cs), dev(bias), epi=HB.EPI_DEQUANT, out_dtype=torch.float16, tile=tile)
         assert_exact(to_np(got), ref_f16, f"dequant f16 tile={tile}")
         dres = dev(res)
-        got = hero.hero_int8_gemm(dA, dB, dev(rs), dev(cs), dev(bias), residual=dres, epi=HB.EPI_DEQUANT, C_out=dres)
+        got = hero.hero_int8_gemm(dA, dB, dev(rs), dev(cs), dev(bias), residual=dres, epi=HB.EPI_DEQUANT, C_out=dres, tile=tile)
         assert_exact(to_np(got), ref_res, f"dequant + residual in place tile={tile}")
+
+
+@pytest.mark.parametrize("M,N,K", [(3300, 3400, 1024), (4200, 4100, 1152), (2100, 6200, 2048)])
+def test_gemm_overlapped_epilogue_kernel(hero, M, N, K):
+    """The persistent 256 x 128 kernel whose epilogue runs inside the next tile's main loop (tile code 9; the
+    default choice from 320 such tiles and K >= 1024 on): one to three tiles per workgroup, ragged last row and
+    column panels, K of exactly 16 slabs (no slab without an epilogue step), 18 and 32 slabs; an output whose
+    rows are 8-element aligned (plain wide stores in the interior tiles) and one whose rows are not (the careful
+    store path everywhere), with canary columns.  REQUANT / DEQUANT / raw bit-exact, GELU^quant in its +-1 LSB class."""
+    c = synth.gemm_case(900 + M, M, K, N)
+    A, Bt, rs, cs, bias = c["A"], c["Bt"], c["a_row_scale"], c["b_col_scale"], c["bias"]
+    dA, dB = dev(A), dev(Bt)
+    y = O.int8_gemm(A, Bt, a_row_scale=rs, b_col_scale=cs, bias=bias, epi=O.EPI_DEQUANT, c_dt=O.F32)
+    s_out = np.float32(np.abs(y).max() / 127)
+    cs2, b2 = (cs / s_out).astype(np.float32), (bias / s_out).astype(np.float32)
+    ref = O.int8_gemm(A, Bt, a_row_scale=rs, b_col_scale=cs2, bias=b2, epi=O.EPI_REQUANT, c_dt=O.I8)
+    for pad in (16, 12):                                       # row stride N + 16 (8-aligned) and N + 12 (not)
+        Cbuf = torch.full((M, N + pad), -7, dtype=torch.int8, device="cuda")
+        hero.hero_int8_gemm(dA, dB, dev(rs), dev(cs2), dev(b2), epi=HB.EPI_REQUANT, C_out=Cbuf[:, :N], tile=9)
+        assert_exact(to_np(Cbuf[:, :N]), ref, f"requant, row stride N+{pad}")
+        assert (to_np(Cbuf[:, N:]) == -7).all()
+    ref_plain = O.int8_gemm(A, Bt, b_col_scale=cs2 * np.float32(0.01), epi=O.EPI_REQUANT, c_dt=O.I8)
+    got = hero.hero_int8_gemm(dA, dB, None, dev(cs2 * np.float32(0.01)), None, epi=HB.EPI_REQUANT, out_dtype=torch.int8, tile=9)
+    assert_exact(to_np(got), ref_plain, "requant, no row scale, no bias")
+    csg = (cs * np.float32(30.0 / np.sqrt(K))).astype(np.float32)
+    gl = O.int8_gemm(A, Bt, a_row_scale=rs, b_col_scale=csg, bias=bias, epi=O.EPI_DEQUANT_GELU, c_dt=O.F32)
+    s_a = (np.abs(gl).max(axis=0) / 127).astype(np.float32)
+    ref_g = O.int8_gemm(A, Bt, a_row_scale=rs, b_col_scale=csg, bias=bias, epi=O.EPI_GELU_REQUANT, out_col_scale=s_a, c_dt=O.I8)
+    got = hero.hero_int8_gemm(dA, dB, dev(rs), dev(csg), dev(bias), epi=HB.EPI_GELU_REQUANT, out_col_scale=dev(s_a),
+                              out_dtype=torch.int8, tile=9)
+    assert_codes(to_np(got), ref_g, "gelu requant")
+    assert_exact(to_np(hero.hero_int8_gemm(dA, dB, tile=9)), O.gemm_i32(A, Bt), "raw")
+    for dt, tdt in ((O.F16, torch.float16), (O.BF16, torch.bfloat16)):
+        ref16 = O.int8_gemm(A, Bt, a_row_scale=rs, b_col_scale=cs, bias=bias, epi=O.EPI_DEQUANT, c_dt=dt)
+        Cb = torch.zeros((M, N + 4), dtype=tdt, device="cuda")          # row stride not 8-aligned
+        hero.hero_int8_gemm(dA, dB, dev(rs), dev(cs), dev(bias), epi=HB.EPI_DEQUANT, C_out=Cb[:, :N], tile=9)
+        assert_exact(to_np(Cb[:, :N]), ref16, f"dequant {tdt}")
+        assert (to_np(Cb[:, N:]) == 0).all()
+    ref_gl = O.int8_gemm(A, Bt, a_row_scale=rs, b_col_scale=csg, bias=bias, epi=O.EPI_DEQUANT_GELU, c_dt=O.BF16)
+    got = hero.hero_int8_gemm(dA, dB, dev(rs), dev(csg), dev(bias), epi=HB.EPI_DEQUANT_GELU, out_dtype=torch.bfloat16, tile=9)
+    assert rel_err(O.bf16_to_f32(to_np(got)), O.bf16_to_f32(ref_gl)) <= 2e-2
+    assert np.mean(to_np(got) == ref_gl) > 0.999               # fp32 GELU against the definition's fp64: a last-bit flip now and then
+
+
+def test_gemm_overlapped_epilogue_kernel_at_the_bench_shapes(hero):
+    """At the FC1 shape of config 2 and two M = 8192 shapes of the config-1 sweep the overlapped kernel, the
+    persistent 256 x 256 kernel and the default choice give the same bytes (integer contraction, the same fp32
+    epilogue); with GELU^quant the overlapped kernel multiplies by the correctly rounded 1 / S_a where the
+    others use v_rcp_f32, so a code may differ by one step now and then."""
+    for (M, N, K) in ((16384, 4096, 1024), (8192, 3072, 1024), (8192, 1024, 4096)):
+        c = synth.gemm_case(950, M, K, N)
+        dA, dB, rs, cs, bias = (dev(c[k]) for k in ("A", "Bt", "a_row_scale", "b_col_scale", "bias"))
+        cs = cs * (30.0 / K ** 0.5)
+        sa = torch.full((N,), 0.03, dtype=torch.float32, device="cuda")
+        outs = [hero.hero_int8_gemm(dA, dB, rs, cs, bias, epi=HB.EPI_GELU_REQUANT, out_col_scale=sa, out_dtype=torch.int8, tile=t)
+                for t in (None, 9, 7)]
+        for o in (outs[0], outs[2]):
+            d = (outs[1].to(torch.int16) - o.to(torch.int16)).abs()
+            assert int(d.max()) <= 1 and float((d != 0).float().mean()) <= 1e-4
+        for epi, dt in ((HB.EPI_DEQUANT, torch.float16), (HB.EPI_REQUANT, torch.int8)):
+            o = [hero.hero_int8_gemm(dA, dB, rs, cs * 0.05, bias, epi=epi, out_dtype=dt, tile=t) for t in (None, 9, 7)]
+            assert torch.equal(o[0].view(torch.int8), o[1].view(torch.int8)) and torch.equal(o[1].view(torch.int8), o[2].view(torch.int8))
 
 
 @pytest.mark.parametrize("M,N,K", [(64, 4096, 16384), (33, 1000, 8704), (100, 2304, 8192), (1, 512, 16384), (64, 1024, 8192)])
@@ -574,16 +632,13 @@ def test_gemm_full_size_sampled_rows(hero, M, N, K):
 @pytest.mark.parametrize("M,N,K,tile", [(200, 136, 256, None), (64, 72, 192, None), (300, 520, 1024, None), (3300, 3400, 384, None),
                                          (3300, 3400, 384, "8"), (2500, 2600, 256, None), (2500, 2600, 256, "7"),
                                          (100, 264, 2304, None)])
-def test_fp8_gemm_matches_oracle(hero, M, N, K, tile, monkeypatch):
+def test_fp8_gemm_matches_oracle(hero, M, N, K, tile):
     """hero_fp8_gemm (Sec. 2.1: FP8 as the 8-bit format): E4M3 operands, fp32 accumulation on the matrix cores
     (the oracle carries the exact sum), the INT8 path's epilogue.  16-bit outputs within 2e-2, E4M3 outputs equal
     up to an adjacent code on <= 0.5 %.  The large shapes run the persistent kernels with ragged edges: by
     default the 256 x 256 one (182 tiles) and the 128 x 128 one (110 tiles of 256 x 256), then each the other one.
     The last shape (few tiles, K = 2304) runs the workgroup with four K groups: fp32 partial sums added through LDS."""
-    if tile is None:
-        monkeypatch.delenv("HERO_FP8_TILE", raising=False)
-    else:
-        monkeypatch.setenv("HERO_FP8_TILE", tile)
+    tile = None if tile is None else int(tile)
     g = synth.rng(1300 + M)
     X = (g.standard_normal((M, K)) * g.uniform(0.5, 4, (M, 1))).astype(np.float32)
     W = (g.standard_normal((K, N)) * 0.05).astype(np.float32)
@@ -595,22 +650,22 @@ def test_fp8_gemm_matches_oracle(hero, M, N, K, tile, monkeypatch):
     dA, dB = dev(A), dev(Bt)
     for dt, tdt, cvt in ((O.BF16, torch.bfloat16, O.bf16_to_f32), (O.F16, torch.float16, O.f16_to_f32)):
         ref = O.fp8_gemm(A, Bt, a_row_scale=rs, b_col_scale=cs, bias=bias, epi=O.EPI_DEQUANT, c_dt=dt)
-        got = hero.hero_fp8_gemm(dA, dB, dev(rs), dev(cs), dev(bias), epi=HB.EPI_DEQUANT, out_dtype=tdt)
+        got = hero.hero_fp8_gemm(dA, dB, dev(rs), dev(cs), dev(bias), epi=HB.EPI_DEQUANT, out_dtype=tdt, tile=tile)
         assert rel_err(cvt(to_np(got)), cvt(ref)) <= 2e-2
     res = O.f32_to_bf16(g.standard_normal((M, N)).astype(np.float32))
     ref = O.fp8_gemm(A, Bt, a_row_scale=rs, b_col_scale=cs, bias=bias, residual=res, res_dt=O.BF16, epi=O.EPI_DEQUANT, c_dt=O.BF16)
     dres = dev(res)
-    got = hero.hero_fp8_gemm(dA, dB, dev(rs), dev(cs), dev(bias), residual=dres, epi=HB.EPI_DEQUANT, C_out=dres)
+    got = hero.hero_fp8_gemm(dA, dB, dev(rs), dev(cs), dev(bias), residual=dres, epi=HB.EPI_DEQUANT, C_out=dres, tile=tile)
     assert rel_err(O.bf16_to_f32(to_np(got)), O.bf16_to_f32(ref)) <= 2e-2
     ref = O.fp8_gemm(A, Bt, a_row_scale=rs, b_col_scale=cs, bias=bias, epi=O.EPI_DEQUANT_GELU, c_dt=O.BF16)
-    got = hero.hero_fp8_gemm(dA, dB, dev(rs), dev(cs), dev(bias), epi=HB.EPI_DEQUANT_GELU, out_dtype=torch.bfloat16)
+    got = hero.hero_fp8_gemm(dA, dB, dev(rs), dev(cs), dev(bias), epi=HB.EPI_DEQUANT_GELU, out_dtype=torch.bfloat16, tile=tile)
     assert rel_err(O.bf16_to_f32(to_np(got)), O.bf16_to_f32(ref)) <= 2e-2
     # 8-bit outputs: a static output scale folded into the column scale (REQUANT), GELU^quant with S_a
     y = O.fp8_gemm(A, Bt, a_row_scale=rs, b_col_scale=cs, bias=bias, epi=O.EPI_DEQUANT, c_dt=O.F32)
     s_out = np.float32(np.abs(y).max() / 448 * 0.9)                       # a little saturation
     cs2, b2 = (cs / s_out).astype(np.float32), (bias / s_out).astype(np.float32)
     ref = O.fp8_gemm(A, Bt, a_row_scale=rs, b_col_scale=cs2, bias=b2, epi=O.EPI_REQUANT, c_dt=O.F8)
-    got = hero.hero_fp8_gemm(dA, dB, dev(rs), dev(cs2), dev(b2), epi=HB.EPI_REQUANT, out_dtype=torch.float8_e4m3fn)
+    got = hero.hero_fp8_gemm(dA, dB, dev(rs), dev(cs2), dev(b2), epi=HB.EPI_REQUANT, out_dtype=torch.float8_e4m3fn, tile=tile)
     # The FP8 matrix instruction adds each lane's group of 8 products after aligning them to the group's largest
     # with 13 fractional bits, truncating (measured on gfx950: 256 + 2^-5 survives, 256 + 2^-6 does not), so a dot
     # product carries a relative error of ~1e-4 where the exact sum of the definition has none; E4M3's grid is
@@ -621,7 +676,7 @@ def test_fp8_gemm_matches_oracle(hero, M, N, K, tile, monkeypatch):
     gl = O.fp8_gemm(A, Bt, a_row_scale=rs, b_col_scale=cs, bias=bias, epi=O.EPI_DEQUANT_GELU, c_dt=O.F32)
     s_a = (np.abs(gl).max(axis=0) / 448 + 1e-6).astype(np.float32)
     ref = O.fp8_gemm(A, Bt, a_row_scale=rs, b_col_scale=cs, bias=bias, epi=O.EPI_GELU_REQUANT, out_col_scale=s_a, c_dt=O.F8)
-    got = hero.hero_fp8_gemm(dA, dB, dev(rs), dev(cs), dev(bias), epi=HB.EPI_GELU_REQUANT, out_col_scale=dev(s_a),
+    got = hero.hero_fp8_gemm(dA, dB, dev(rs), dev(cs), dev(bias), epi=HB.EPI_GELU_REQUANT, out_col_scale=dev(s_a), tile=tile,
                              out_dtype=torch.float8_e4m3fn)
     # the same bound; in addition the kernel's GELU is accurate to 1.1e-7 ABSOLUTE (built for the INT8 grid)
     # while E4M3 resolves small values down to a step of 2^-9 S_a.
@@ -707,7 +762,7 @@ def test_fp8_attn_views_cache_one_query_and_errors(hero):
 
 # ============================================================ BF16 side of a switched module
 @pytest.mark.parametrize("M,N,K", [(200, 136, 256), (130, 512, 1024), (64, 72, 96), (2500, 2600, 160), (2560, 2560, 128), (2500, 2600, 192)])
-def test_bf16_gemm_matches_oracle(hero, M, N, K, monkeypatch):
+def test_bf16_gemm_matches_oracle(hero, M, N, K):
     """The last two shapes have enough tiles for the persistent kernels (ragged edges, 5 / 4 slabs, several tiles
     per workgroup): the default choice, then the 256 x 256 and the 128 x 128 form forced."""
     g = synth.rng(1000 + M)
@@ -718,12 +773,8 @@ def test_bf16_gemm_matches_oracle(hero, M, N, K, monkeypatch):
     big = K % 64 == 0 and -(-M // 128) * -(-N // 128) >= 192
     for gelu, r in ((False, None), (True, None), (False, res), (True, res)):
         ref = O.bf16_gemm(A, Wt, bias=bias, residual=r, gelu=gelu)
-        for tile in (None, "7", "8") if big else (None,):
-            if tile is None:
-                monkeypatch.delenv("HERO_BF16_TILE", raising=False)
-            else:
-                monkeypatch.setenv("HERO_BF16_TILE", tile)
-            got = hero.hero_bf16_gemm(dev(A), dev(Wt), dev(bias), residual=dev(r), gelu=gelu)
+        for tile in (None, 7, 8) if big else (None,):
+            got = hero.hero_bf16_gemm(dev(A), dev(Wt), dev(bias), residual=dev(r), gelu=gelu, tile=tile)
             assert rel_err(O.bf16_to_f32(to_np(got)), O.bf16_to_f32(ref)) <= 2e-2, (gelu, r is not None, tile)
 
 
@@ -741,21 +792,42 @@ def test_bf16_attn_matches_oracle(hero, B, S, H, Dh, mask):
 
 
 # ============================================================ diagnostics
-def test_probe_entry_points(hero):
-    """The ceiling probes of the bench: the copy copies, the MFMA loop reports its operation count, bad sizes
-    are refused before any launch."""
-    src = torch.randint(-127, 128, (1 << 20,), dtype=torch.int8, device="cuda")
+def test_probe_library_instruments():
+    """The measuring instruments of the bench (libhero_probe, a library of its own): the copies copy (1 and 4 loads
+    in flight, ragged tail, the runtime's copy), the write-only pass writes every element, the MFMA loops report
+    their operation counts and leave the sink alone, bad sizes are refused before any launch."""
+    from paper_2310_17723_amd.probe import Probe
+    pr = Probe()
+    n = (1 << 20) + 48
+    src = torch.randint(-127, 128, (n,), dtype=torch.int8, device="cuda")
+    for u in (1, 4):
+        dst = torch.zeros_like(src)
+        pr.copy(src, dst, u)
+        torch.cuda.synchronize()
+        assert torch.equal(src, dst)
     dst = torch.zeros_like(src)
-    hero.hero_probe_copy(src, dst)
+    pr.memcpy(src, dst)
     torch.cuda.synchronize()
     assert torch.equal(src, dst)
+    dst = torch.full((n,), -1, dtype=torch.int8, device="cuda")
+    pr.write(dst)
+    torch.cuda.synchronize()
+    w = dst.view(torch.int32).view(-1, 4)
+    assert bool((w[:, 1] == 1).all() and (w[:, 2] == 2).all() and (w[:, 3] == 3).all())
     sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    pr.read(src, sink)
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
     for rnd in (0, 1):
-        ops = hero.hero_probe_mfma_i8(rnd, 8, sink)
+        ops = pr.mfma_i8(rnd, 8, sink)
         torch.cuda.synchronize()
-        cus = torch.cuda.get_device_properties(0).multi_processor_count
         assert ops == cus * 8 * 8 * 16 * 65536.0 and int(sink.item()) == 0
-    with pytest.raises(HB.HeroError):
-        hero.hero_probe_mfma_i8(0, 0, sink)
-    with pytest.raises(HB.HeroError):
-        hero.hero_probe_copy(src[:24], dst[:24])
+    for mode, V in ((0, 0), (0, 4), (1, 8), (2, 4)):
+        mo, vi = pr.coissue(mode, V, 4, sink)
+        torch.cuda.synchronize()
+        assert vi == cus * 8 * 4 * 8 * V and mo == (0 if mode == 1 else cus * 8 * 4 * 8 * 65536.0) and int(sink.item()) == 0
+    with pytest.raises(RuntimeError):
+        pr.mfma_i8(0, 0, sink)
+    with pytest.raises(RuntimeError):
+        pr.copy(src[:24], dst[:24])
+    with pytest.raises(RuntimeError):
+        pr.coissue(0, 5, 4, sink)
