@@ -25,13 +25,14 @@ import numpy as np
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-# HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# (two runs, scaled by the same counters on a plain copy of known size); the summaries are in
-# profiles/.  Keyed by (M, N, K) of the FC1 GeMM^quant; anything else reports null.
-MEASURED_TRAFFIC = {
-    # profiles/bert-large_kernels_hbm_traffic_pmc.txt: fetch 47583.7 KiB x 2.00 (copy calibration), write 65539.5 KiB x 1.00
-    (16384, 4096, 1024): {"fetch_bytes": 97467201, "write_bytes": 67112038},
-}
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs, scaled by the same
+# counters on a plain copy of known size) are NOT typed in here: they are read from profiles/measured_traffic.json,
+# which names the commit and the commands they were taken with (written from the rocprofv3 summaries beside it).
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "measured_traffic.json")
+
+# what SURVEY's roofline gives per workload, in layer-tokens/s (INT8 MFMA peak for the prefill stacks, 8 TB/s
+# for the decode step); bert-base is latency-bound and has none
+LAYER_BOUND = {"bert-large-32x512": 185e6, "gpt-prefill-8x2048": 12e6, "gpt-decode-64x1": 0.39e6}
 
 PEAK_INT8_TOPS = 5000.0      # MI355X dense INT8 MFMA, TOP/s
 PEAK_FP8_TFLOPS = 5000.0    # MI355X dense FP8 MFMA, TFLOP/s
@@ -44,9 +45,21 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def time_gpu(fn, iters, warmup=3, graph=False):
-    """ms per call of fn, HIP events around `iters` back-to-back calls.  graph=True: the calls are captured into a
-    HIP graph once and the replay is timed, so a short kernel is not hidden behind the ~10 us one call costs on the
+def measured_traffic(key):
+    try:
+        with open(TRAFFIC_FILE) as f:
+            t = json.load(f)
+        e = dict(t["kernels"][key])
+        e["measured_at_commit"] = t.get("commit")
+        return e
+    except (OSError, KeyError, ValueError):
+        return None
+
+
+def time_gpu(fn, iters, warmup=3, graph=False, repeats=5):
+    """ms per call of fn: HIP events (on the current stream, the one the library launches on) around `iters`
+    back-to-back calls, the MEDIAN of `repeats` such measurements.  graph=True: the calls are captured into a HIP
+    graph once and the replays are timed, so a short kernel is not hidden behind the ~10 us one call costs on the
     host (Python -> ctypes -> launch); nothing in the library allocates or clears memory, so its calls capture as
     they are."""
     import torch
@@ -62,18 +75,23 @@ def time_gpu(fn, iters, warmup=3, graph=False):
         g.replay()
         torch.cuda.synchronize()
         run = g.replay
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    run()
-    e1.record()
-    torch.cuda.synchronize()
-    return e0.elapsed_time(e1) / per      # ms per call
+    ts = []
+    for _ in range(repeats):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        run()
+        e1.record()
+        torch.cuda.synchronize()
+        ts.append(e0.elapsed_time(e1) / per)
+    return float(np.median(ts))      # ms per call
 
 
 class Stack:
     """Device-resident prepared weights + activations of one workload."""
 
-    def __init__(self, hero, shape, seed, mode, layers=None, fp8=False):
+    def __init__(self, hero, shape, seed, mode, layers=None, fp8=False, share=None):
+        """share: another Stack of the same model (config 4 decodes with config 3's layers): its prepared
+        weights are reused instead of being calibrated and quantized again."""
         import torch
         from paper_2310_17723_amd import binding as HB, prep, synth
         self.hero, self.shape, self.mode = hero, shape, mode
@@ -97,7 +115,10 @@ class Stack:
         self.desc = hero.layer_desc(shape.arch, d, shape.H, shape.Dh, shape.f, shape.eps, shape.mask,
                                     mode | (HB.M_FP8 if fp8 else 0))
         self.weights, self.keep = [], []
-        for l in range(self.layers):
+        if share is not None:
+            assert (share.shape.d, share.shape.f, share.shape.H, share.mode, share.fp8) == (d, shape.f, shape.H, mode, fp8)
+            self.weights, self.keep = share.weights[:self.layers], share.keep[:self.layers]
+        for l in range(self.layers if share is None else 0):
             p = {k: torch.from_numpy(v).to(dev) for k, v in synth.layer_params(seed, shape, l).items()}
             sc, xc = prep.calibrate(p, xc, shape.arch, shape.H, shape.Dh, shape.eps,
                                     cal_mask if cal_mask != HB.MASK_PADDING else HB.MASK_NONE, Bc, Sc, hero=hero, fp8=fp8)
@@ -123,9 +144,10 @@ class Stack:
             Smax = shape.cache_len + shape.steps
             self.Smax = Smax
             self.caches = []
+            gen = torch.Generator(device="cuda").manual_seed(seed)      # uniform INT8 codes, drawn on the GPU (4.6 GB)
             for l in range(self.layers):
-                kc = torch.from_numpy(synth.int8_codes(seed, (B, shape.H, Smax, shape.Dh), stream=2 * l)).to(dev)
-                vc = torch.from_numpy(synth.int8_codes(seed, (B, shape.H, Smax, shape.Dh), stream=2 * l + 1)).to(dev)
+                kc = torch.randint(-127, 128, (B, shape.H, Smax, shape.Dh), dtype=torch.int8, device=dev, generator=gen)
+                vc = torch.randint(-127, 128, (B, shape.H, Smax, shape.Dh), dtype=torch.int8, device=dev, generator=gen)
                 if fp8:                                   # the bytes are E4M3 codes here: no NaN patterns (0x7F / 0xFF)
                     for c in (kc, vc):
                         c[(c & 0x7F) == 0x7F] -= 1
@@ -158,12 +180,38 @@ class Stack:
                     hero.hero_layer_fwd(self.desc, self.weights[l], B, 1, self.ws, h=self.h, kv_len=self.kv_steps[t],
                                         k_cache=kc, v_cache=vc)
 
+    def sanity(self):
+        """Cheap check of what the LAST pass left behind, so that a stack that produced garbage cannot post a
+        number: finite values in a plausible range, TWQ rows that reach the code +-127, codes not all saturated."""
+        import torch
+        sh = self.shape
+        if sh.arch == 0:
+            oq, os_ = self.buf[(self.layers - 1) & 1]
+            rows = torch.ones(self.T, dtype=torch.bool, device=oq.device)
+            if self.kv_len is not None:
+                rows = (torch.arange(sh.S, device=oq.device)[None, :] < self.kv_len[:, None]).reshape(-1)
+            sc = os_[rows]
+            ok_scale = bool(torch.isfinite(sc).all() and (sc > 1e-6).all() and (sc < 1e3).all())
+            if self.fp8:
+                v = oq.view(torch.uint8)[rows]
+                sat = float(((v & 0x7F) >= 0x7E).float().mean())
+                return {"ok": ok_scale and sat < 0.2, "scales_finite_in_range": ok_scale, "saturated_code_fraction": round(sat, 5)}
+            q = oq[rows].to(torch.int16).abs()
+            reach = bool((q.amax(dim=1) == 127).all())
+            sat = float((q == 127).float().mean())
+            return {"ok": ok_scale and reach and sat < 0.2, "scales_finite_in_range": ok_scale,
+                    "every_row_reaches_127": reach, "saturated_code_fraction": round(sat, 5)}
+        h = self.h.float()
+        fin = bool(torch.isfinite(h).all())
+        rms = float(h.pow(2).mean().sqrt()) if fin else float("nan")
+        return {"ok": fin and 0.1 < rms < 100.0, "finite": fin, "rms": round(rms, 3)}
+
     def tokens_layers_per_step(self):
         sh = self.shape
         return self.T * self.layers * (sh.steps if self.caches is not None else 1)
 
 
-def fc1_roofline(hero, shape, seed, iters=20):
+def fc1_roofline(hero, shape, seed, iters=20, tile=None):
     """The dominant kernel alone: FC1 GeMM^quant + GELU^quant at the workload's shape."""
     import torch
     from paper_2310_17723_amd import binding as HB, synth
@@ -174,35 +222,55 @@ def fc1_roofline(hero, shape, seed, iters=20):
     cs = cs * (30.0 / K ** 0.5)
     sa = torch.full((N,), 0.03, dtype=torch.float32, device="cuda")
     out = torch.empty((M, N), dtype=torch.int8, device="cuda")
-    fn = lambda: hero.hero_int8_gemm(A, Bt, rs, cs, bias, epi=HB.EPI_GELU_REQUANT, out_col_scale=sa, C_out=out)
+    fn = lambda: hero.hero_int8_gemm(A, Bt, rs, cs, bias, epi=HB.EPI_GELU_REQUANT, out_col_scale=sa, C_out=out, tile=tile)
     ms = time_gpu(fn, iters)
     ops = 2.0 * M * N * K
     tops = ops / (ms * 1e-3) / 1e12
     return {"bound": "mfma", "kernel": "int8_gemm_persistent_kernel<GELU_REQUANT> (FC1)", "shape_mnk": [M, N, K],
             "achieved": round(tops, 2), "peak": PEAK_INT8_TOPS, "unit": "TOP/s", "frac": round(tops / PEAK_INT8_TOPS, 4),
-            "avg_launch_us": round(ms * 1e3, 2), "ops_per_launch": ops,
+            "avg_launch_us": round(ms * 1e3, 2), "ops_per_launch": ops, "timing": "median of 5 x 20 launches, HIP events",
             "algorithmic_bytes": M * K + N * K + M * N + 4 * (M + 3 * N),
-            "traffic": MEASURED_TRAFFIC.get((M, N, K))}
+            "traffic": measured_traffic(f"fc1_gelu_requant_{M}x{N}x{K}")}
 
 
-def measured_ceilings(hero):
-    """What this machine sustains, beside the nameplate peaks the fractions are quoted against: a register-only
-    INT8 MFMA loop on near-constant and on random operand bytes (the clock under the matrix cores is power-limited
-    and depends on the data) and a plain 256 MiB device copy."""
+def measured_ceilings():
+    """What this machine sustains, beside the nameplate peaks the fractions are quoted against, from the
+    instruments of libhero_probe (a library of its own, loaded only here).  Matrix cores: a register-only INT8
+    MFMA loop on near-constant and on random operand bytes (the clock under the matrix cores is power-limited and
+    depends on the data), and the same loop with 4 / 8 fp32 vector instructions behind every matrix instruction of
+    a wave, or in the other wave of the SIMD (does the vector ALU issue while the matrix pipe is busy?).  HBM: five
+    instruments on 256 MiB buffers (read only, write only, copy with 1 and with 4 independent 16-byte loads in
+    flight per lane, the runtime's device-to-device copy) and a copy of one LN^quant call's volume on rotating buffers."""
     import torch
+    from paper_2310_17723_amd.probe import Probe
+    pr = Probe()
     sink = torch.zeros(1, dtype=torch.int32, device="cuda")
     out = {}
     for name, rnd in (("mfma_int8_constant_operands_tops", 0), ("mfma_int8_random_operands_tops", 1)):
         ops = [0.0]
 
         def fn():
-            ops[0] = hero.hero_probe_mfma_i8(rnd, 2048, sink)
-        ms = time_gpu(fn, 5, warmup=2)
+            ops[0] = pr.mfma_i8(rnd, 2048, sink)
+        ms = time_gpu(fn, 5, warmup=2, repeats=3)
         out[name] = round(ops[0] / (ms * 1e-3) / 1e12, 1)
-    src = torch.randint(-127, 128, (256 << 20,), dtype=torch.int8, device="cuda")
+    co = {}
+    for name, mode, V in (("mfma_only", 0, 0), ("valu4_only", 1, 4), ("valu8_only", 1, 8), ("in_wave_mfma_valu4", 0, 4),
+                          ("in_wave_mfma_valu8", 0, 8), ("cross_wave_mfma_valu4", 2, 4), ("cross_wave_mfma_valu8", 2, 8)):
+        ms = time_gpu(lambda: pr.coissue(mode, V, 1000, sink), 3, warmup=1, repeats=3)
+        co[name + "_us"] = round(ms * 1e3, 1)
+    co["hidden_fraction_in_wave_valu4"] = round(1.0 - (co["in_wave_mfma_valu4_us"] - co["mfma_only_us"]) / co["valu4_only_us"], 3)
+    co["hidden_fraction_in_wave_valu8"] = round(1.0 - (co["in_wave_mfma_valu8_us"] - co["mfma_only_us"]) / co["valu8_only_us"], 3)
+    co["hidden_fraction_cross_wave_valu4"] = round(1.0 - (co["cross_wave_mfma_valu4_us"] - co["mfma_only_us"]) / co["valu4_only_us"], 3)
+    out["mfma_valu_coissue"] = co
+    n = 256 << 20
+    src = torch.randint(-127, 128, (n,), dtype=torch.int8, device="cuda")
     dst = torch.empty_like(src)
-    ms = time_gpu(lambda: hero.hero_probe_copy(src, dst), 5, warmup=2)
-    out["copy_256MiB_gbs"] = round(2.0 * (256 << 20) / (ms * 1e-3) / 1e9, 1)      # read + write
+    gbs = lambda moved, ms: round(moved / (ms * 1e-3) / 1e9, 1)
+    out["hbm_read_only_256MiB_gbs"] = gbs(n, time_gpu(lambda: pr.read(src, sink), 5, warmup=2, repeats=3))
+    out["hbm_write_only_256MiB_gbs"] = gbs(n, time_gpu(lambda: pr.write(dst), 5, warmup=2, repeats=3))
+    out["copy_256MiB_gbs"] = gbs(2 * n, time_gpu(lambda: pr.copy(src, dst, 1), 5, warmup=2, repeats=3))      # read + write
+    out["copy_256MiB_4_loads_in_flight_gbs"] = gbs(2 * n, time_gpu(lambda: pr.copy(src, dst, 4), 5, warmup=2, repeats=3))
+    out["hip_memcpy_dtod_256MiB_gbs"] = gbs(2 * n, time_gpu(lambda: pr.memcpy(src, dst), 5, warmup=2, repeats=3))
     del src, dst
     # a copy that moves what one LN^quant call of the bench moves (48 MiB), on rotating buffers like that leg
     n, nbuf = 24 << 20, 8
@@ -213,9 +281,10 @@ def measured_ceilings(hero):
     def cp():
         a, b = bufs[i[0] % nbuf]
         i[0] += 1
-        hero.hero_probe_copy(a, b)
-    ms = time_gpu(cp, 40, warmup=nbuf)
+        pr.copy(a, b, 4)
+    ms = time_gpu(cp, 40, warmup=nbuf, graph=True, repeats=5)
     out["copy_24MiB_rotating_gbs"] = round(2.0 * n / (ms * 1e-3) / 1e9, 1)
+    out["hbm_best_copy_gbs"] = max(out["copy_256MiB_gbs"], out["copy_256MiB_4_loads_in_flight_gbs"], out["hip_memcpy_dtod_256MiB_gbs"])
     return out
 
 
@@ -367,11 +436,13 @@ def ln_bandwidth(hero, T, D, iters=40, nbuf=8):
         x, r, xs, yq, ys = sets[i[0] % nbuf]
         i[0] += 1
         hero.hero_ln_quant(x, xs, r, rc, gam, bet, 1e-12, y_q=yq, y_scale=ys)
-    ms = time_gpu(fn, iters, warmup=nbuf)
+    ms = time_gpu(fn, iters, warmup=nbuf, graph=True)            # replays of a HIP graph: no host time in the figure
     bytes_ = T * (3 * D + 8)
     gbs = bytes_ / (ms * 1e-3) / 1e9
     return {"T": T, "D": D, "form": "int8+int8->int8", "us": round(ms * 1e3, 2), "bytes_per_launch": bytes_,
-            "gbs": round(gbs, 1), "frac_hbm": round(gbs / PEAK_HBM_GBS, 4), "working_set_mb": nbuf * bytes_ // 2 ** 20}
+            "gbs": round(gbs, 1), "frac_hbm": round(gbs / PEAK_HBM_GBS, 4), "working_set_mb": nbuf * bytes_ // 2 ** 20,
+            "timing": f"median of 5 replays of a HIP graph of {iters} launches on {nbuf} rotating buffer sets",
+            "counters": measured_traffic(f"ln_quant_{T}x{D}")}
 
 
 def embed_bandwidth(hero, B, S, D, V=30522, iters=40, nbuf=8):
@@ -399,49 +470,163 @@ def embed_bandwidth(hero, B, S, D, V=30522, iters=40, nbuf=8):
         a, b, c, yq, ys = sets[i[0] % nbuf]
         i[0] += 1
         hero.hero_embed_ln_quant(a, b, c, tok, ts, pos, typ, gam, bet, 1e-12, y_q=yq, y_scale=ys)
-    ms = time_gpu(fn, iters, warmup=nbuf)
+    ms = time_gpu(fn, iters, warmup=nbuf, graph=True)
     bytes_ = T * (2 * D + 20) + (S + 2) * D * 2
     gbs = bytes_ / (ms * 1e-3) / 1e9
     return {"T": T, "D": D, "vocab": V, "form": "int8 table + bf16 tables -> int8", "us": round(ms * 1e3, 2),
-            "bytes_per_launch": bytes_, "gbs": round(gbs, 1), "frac_hbm": round(gbs / PEAK_HBM_GBS, 4)}
+            "bytes_per_launch": bytes_, "gbs": round(gbs, 1), "frac_hbm": round(gbs / PEAK_HBM_GBS, 4),
+            "timing": f"median of 5 replays of a HIP graph of {iters} launches on {nbuf} rotating id / output sets"}
 
 
-def cpu_baseline(shape, seed, mode_name):
-    """The oracle, as it stands, on a bounded slice of the workload (about 10-30 s of CPU work)."""
+def cpu_baseline(shape, seed, mode_name="M3", prepared=None):
+    """The oracle, as it stands, timed on a bounded slice of the workload (the forward passes only; calibration
+    and weight preparation are outside the clock).  Slices: BERT-base in full; BERT-large one sequence x 512
+    tokens through all 24 layers (M3) or one layer (M1); GPT prefill one sequence x 2048 tokens through one layer;
+    GPT decode two batch rows x 4 steps against a 2048-key cache through one layer.  `prepared`: oracle weights
+    of the same model to reuse (the decode slice takes the prefill slice's).  Returns (record, prepared)."""
     import oracle as O
     from oracle import layer as OL
     from paper_2310_17723_amd import synth
     decode = shape.cache_len > 0
-    # slice sizes: BERT-large 32 x 512 (the full batch), BERT-base 1 x 128, GPT prefill 1 x 512, decode 2 x 1
-    B, S = ((min(shape.B, 32), min(shape.S, 512)) if shape.d <= 1024 else (1, 512)) if not decode else (2, 1)
+    mode = {"M1": OL.MODE_M1, "M2": OL.MODE_M2, "M3": OL.MODE_M3}[mode_name]
+    if decode:
+        B, S, L = 2, 1, 1
+    elif shape.d > 1024:
+        B, S, L = 1, shape.S, 1
+    elif shape.layers > 1:
+        B, S, L = 1, shape.S, (shape.layers if mode_name == "M3" else 1)
+    else:
+        B, S, L = shape.B, shape.S, 1
     sh = synth.small(shape, B=B, S=S)
-    p = synth.layer_params(seed, sh, 0)
     emb = synth.embedding_ln_params(seed, sh)
-    Sc = 64
-    xc = synth.activations(seed, sh, 2 * Sc, stream=1).astype(np.float64)
-    if sh.arch == synth.POST_LN:
-        xc = OL._ln64(xc, emb["g"].astype(np.float64), emb["b"].astype(np.float64), sh.eps)
-    cal = synth.small(sh, mask=synth.MASK_NONE if sh.mask == synth.MASK_PADDING else sh.mask)
-    sc, _ = OL.calibrate(p, xc, cal, 2, Sc)
-    w = OL.prepare(p, sc, sh, OL.MODE_M3)
+    if prepared is None:
+        Sc = 128
+        xc = synth.activations(seed, sh, Sc, stream=1).astype(np.float64)
+        if sh.arch == synth.POST_LN:
+            xc = OL._ln64(xc, emb["g"].astype(np.float64), emb["b"].astype(np.float64), sh.eps)
+        cal = synth.small(sh, mask=synth.MASK_NONE if sh.mask == synth.MASK_PADDING else sh.mask)
+        if decode:
+            cal = synth.small(cal, mask=synth.MASK_CAUSAL)
+        prepared = []
+        for l in range(L):
+            p = synth.layer_params(seed, sh, l)
+            sc, xc = OL.calibrate(p, xc, cal, 1, Sc)
+            prepared.append(OL.prepare(p, sc, sh, mode))
+            del p
     h0 = synth.activations(seed, sh, B * S)
+    steps = 1
     t0 = time.perf_counter()
     if sh.arch == synth.POST_LN:
         xq, xs, _ = O.ln_quant(h0, O.F32, None, None, 0, None, emb["g"], emb["b"], sh.eps)
         kv = np.full(B, S, np.int32) if sh.mask == synth.MASK_PADDING else None
-        OL.layer_fwd(w, sh, B, S, x_q=xq, x_s=xs, kv_len=kv)
-        sample = f"{B} sequences x {S} tokens through 1 layer of {shape.name}"
+        for l in range(L):
+            xq, xs = OL.layer_fwd(prepared[l], sh, B, S, x_q=xq, x_s=xs, kv_len=kv)
+        sample = f"{B} sequence(s) x {S} tokens through {L} layer(s) of {shape.name} ({mode_name})"
     elif not decode:
-        OL.layer_fwd(w, sh, B, S, h=O.f32_to_bf16(h0))
+        OL.layer_fwd(prepared[0], sh, B, S, h=O.f32_to_bf16(h0))
         sample = f"{B} sequence x {S} tokens through 1 layer of {shape.name}"
     else:
-        Smax = shape.cache_len + 1
+        steps = 4
+        Smax = shape.cache_len + steps
         cache = {"k": synth.int8_codes(seed, (B, sh.H, Smax, sh.Dh), 0), "v": synth.int8_codes(seed, (B, sh.H, Smax, sh.Dh), 1)}
-        OL.layer_fwd(w, sh, B, 1, h=O.f32_to_bf16(h0), kv_len=np.full(B, Smax, np.int32), cache=cache)
-        sample = f"{B} sequences x 1 decode token (cache {shape.cache_len}) through 1 layer of {shape.name}"
+        t0 = time.perf_counter()
+        for t in range(steps):
+            OL.layer_fwd(prepared[0], sh, B, 1, h=O.f32_to_bf16(h0), kv_len=np.full(B, shape.cache_len + t + 1, np.int32), cache=cache)
+        sample = f"{B} sequences x {steps} decode steps (cache {shape.cache_len}) through 1 layer of {shape.name}"
     dt = time.perf_counter() - t0
-    return {"value": round(B * S / dt, 2), "unit": "layer-tokens/s", "cores": O.num_threads(), "kind": "oracle",
-            "sample": sample, "seconds": round(dt, 2)}
+    return ({"value": round(B * S * L * steps / dt, 2), "unit": "layer-tokens/s", "cores": O.num_threads(), "kind": "oracle",
+             "sample": sample, "seconds": round(dt, 2)}, prepared)
+
+
+def time_stack(st, steps, repeats=5, graph=False):
+    """ms per pass of the stack: HIP events around `steps` passes, median of `repeats`."""
+    import torch
+    st.step()
+    torch.cuda.synchronize()
+    run = st.step
+    if graph:
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            st.step()
+        g.replay()
+        torch.cuda.synchronize()
+        run = g.replay
+    ts = []
+    for _ in range(repeats):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            run()
+        e1.record()
+        torch.cuda.synchronize()
+        ts.append(e0.elapsed_time(e1) / steps)
+    return float(np.median(ts)), [round(t, 4) for t in ts]
+
+
+def workload_record(st, ms_per_step, mode_name, graph, launches=None):
+    sh = st.shape
+    decode = st.caches is not None
+    per_layer_us = ms_per_step * 1e3 / (st.layers * (sh.steps if decode else 1))
+    tps = st.tokens_layers_per_step() / (ms_per_step * 1e-3)
+    rec = {"workload": sh.name, "mode": mode_name, "layers": st.layers, "tokens_per_step": st.T * (sh.steps if decode else 1),
+           "hip_graph": bool(graph), "ms_per_step": round(ms_per_step, 4), "us_per_layer": round(per_layer_us, 2),
+           "layer_tokens_per_s": round(tps, 1), "timing": "median of 5 repeats, HIP events around whole passes"}
+    bound = LAYER_BOUND.get(sh.name)
+    if bound:
+        rec["roofline_bound_layer_tokens_per_s"] = bound
+        rec["frac_of_bound"] = round(tps / bound, 4)
+    if launches:
+        rec["launches_per_layer"] = launches
+    rec["sanity"] = st.sanity()
+    return rec
+
+
+def other_workloads(hero, seed):
+    """Configs 0, 3, 4 and config 2 in the mixed mode M1 (attention core, attention-output linear and FC2 in BF16):
+    each timed like the headline stack, each with the oracle beside it on its own slice."""
+    import torch
+    from paper_2310_17723_amd import binding as HB, synth
+    out = {}
+    # ---- config 2, M1
+    log("[bench] config 2 in M1 (BF16 attention / attention-output / FC2)")
+    sh = synth.CONFIGS[2]
+    st = Stack(hero, sh, seed, HB.MODE_M1)
+    ms, _ = time_stack(st, 3)
+    out["bert-large-32x512_M1"] = workload_record(st, ms, "M1", False)
+    del st
+    torch.cuda.empty_cache()
+    out["bert-large-32x512_M1"]["cpu_baseline"], _ = cpu_baseline(sh, seed, "M1")
+    # ---- config 0: eager and as a HIP graph (9 launches of a few microseconds each)
+    log("[bench] config 0 (BERT-base 1 x 128): eager and HIP graph")
+    sh = synth.CONFIGS[0]
+    st = Stack(hero, sh, seed, HB.MODE_M3)
+    ms, _ = time_stack(st, 50)
+    out["bert-base-1x128_eager"] = workload_record(st, ms, "M3", False, launches=9)
+    ms, _ = time_stack(st, 50, graph=True)
+    out["bert-base-1x128_graph"] = workload_record(st, ms, "M3", True, launches=9)
+    del st
+    cb, _ = cpu_baseline(sh, seed, "M3")
+    out["bert-base-1x128_eager"]["cpu_baseline"] = cb
+    out["bert-base-1x128_graph"]["cpu_baseline"] = cb
+    # ---- config 3, then config 4 on the same prepared layers
+    log("[bench] config 3 (GPT prefill 8 x 2048, d 4096, 4 layers)")
+    sh3, sh4 = synth.CONFIGS[3], synth.CONFIGS[4]
+    st3 = Stack(hero, sh3, seed, HB.MODE_M3)
+    ms, _ = time_stack(st3, 2)
+    out["gpt-prefill-8x2048"] = workload_record(st3, ms, "M3", False)
+    log("[bench] config 4 (GPT decode 64 x 1 against a 2048-token INT8 cache, 128 steps, 4 layers)")
+    st4 = Stack(hero, sh4, seed, HB.MODE_M3, share=st3)
+    st3.ws = st3.h = st3.h0 = None
+    torch.cuda.empty_cache()
+    ms, _ = time_stack(st4, 1, repeats=3)
+    out["gpt-decode-64x1"] = workload_record(st4, ms, "M3", False)
+    out["gpt-decode-64x1"]["timing"] = "median of 3 repeats of the 128-step pass"
+    del st3, st4
+    torch.cuda.empty_cache()
+    log("[bench] CPU oracle on the config 3 / 4 slices")
+    out["gpt-prefill-8x2048"]["cpu_baseline"], prepared = cpu_baseline(sh3, seed, "M3")
+    out["gpt-decode-64x1"]["cpu_baseline"], _ = cpu_baseline(sh4, seed, "M3", prepared=prepared)
+    return out
 
 
 def main():
@@ -453,11 +638,16 @@ def main():
     ap.add_argument("--mode", default="M3", choices=["M1", "M2", "M3"])
     ap.add_argument("--layers", type=int, default=None, help="override the stack depth")
     ap.add_argument("--seed", type=int, default=2310)
-    ap.add_argument("--no-extras", action="store_true", help="skip the GEMM sweep / LN / CPU legs")
+    ap.add_argument("--no-extras", action="store_true", help="skip the GEMM sweep / LN / other-workload / CPU legs")
+    ap.add_argument("--no-workloads", action="store_true", help="skip the legs of the other configs (0, 3, 4, config 2 in M1)")
     ap.add_argument("--fp8", action="store_true",
                     help="run the stack in the FP8 variant (E4M3 codes in every 8-bit buffer; mode M3 only)")
     ap.add_argument("--graph", action="store_true",
                     help="capture one pass of the stack in a HIP graph and time its replays (launch-bound workloads)")
+    ap.add_argument("--only", default=None, choices=["ln", "coissue", "fc1", "attention"],
+                    help="run one leg alone and print its record (for rocprofv3 counter runs): the LN^quant bandwidth legs, "
+                         "the MFMA + VALU co-issue probe, the FC1 GeMM^quant (with --tile), the attention kernels")
+    ap.add_argument("--tile", type=int, default=None, help="with --only fc1: force a GEMM kernel through the test hook (7, 8, 9)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 256 MiB device copy 5 times (reference for the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -482,6 +672,25 @@ def main():
         return
     hero = pkg.load()                     # raises if libhero.so is missing: no fallback
     shape = synth.CONFIGS[WORKLOADS[args.workload]]
+    if args.only == "ln":
+        print(json.dumps({"ln_quant": ln_bandwidth(hero, 16384, shape.d), "ln_quant_large": ln_bandwidth(hero, 65536, shape.d, nbuf=4),
+                          "embed_ln_quant": embed_bandwidth(hero, 32, 512, shape.d)}))
+        return
+    if args.only == "coissue":
+        from paper_2310_17723_amd.probe import Probe
+        pr, sink = Probe(), torch.zeros(1, dtype=torch.int32, device="cuda")
+        for mode, V in ((0, 0), (1, 4), (1, 8), (0, 4), (0, 8), (2, 4), (2, 8)):
+            pr.coissue(mode, V, 1000, sink)
+            pr.coissue(mode, V, 1000, sink)
+        torch.cuda.synchronize()
+        print(json.dumps({"launched": "probe_coissue_kernel<mode, V> twice each: (0,0) (1,4) (1,8) (0,4) (0,8) (2,4) (2,8), 1000 iterations"}))
+        return
+    if args.only == "fc1":
+        print(json.dumps(fc1_roofline(hero, shape, args.seed, tile=args.tile)))
+        return
+    if args.only == "attention":
+        print(json.dumps(attn_variants(hero, shape, args.seed)))
+        return
     mode = {"M1": HB.MODE_M1, "M2": HB.MODE_M2, "M3": HB.MODE_M3}[args.mode]
     decode = shape.cache_len > 0
     steps = args.steps if args.steps is not None else (1 if decode else 10)
@@ -517,6 +726,19 @@ def main():
     ms_per_step = e0.elapsed_time(e1) / steps
     tl = st.tokens_layers_per_step()
     value = tl / (ms_per_step * 1e-3)
+    sanity = st.sanity()
+    if not sanity["ok"]:
+        print(f"bench.py: the timed stack left implausible outputs behind: {sanity}", file=sys.stderr)
+        sys.exit(4)
+    # four more timings of the same K steps: `value` is the first one (the contract's K steps), the spread is reported
+    reps = [round(ms_per_step, 4)]
+    for _ in range(4 if not decode else 0):
+        e0.record()
+        for _ in range(steps):
+            run()
+        e1.record()
+        torch.cuda.synchronize()
+        reps.append(round(e0.elapsed_time(e1) / steps, 4))
 
     rec = {
         "metric": "W8A8 layer tokens/s", "value": round(value, 1), "unit": "layer-tokens/s",
@@ -529,6 +751,8 @@ def main():
         "stack_tokens_per_s": round(value / st.layers, 1),
         "us_per_layer": round(ms_per_step * 1e3 / (st.layers * (shape.steps if decode else 1)), 2),
         "wall_ms_timed_region": round(wall_ms, 2),
+        "ms_per_step_repeats": reps, "ms_per_step_median": round(float(np.median(reps)), 4),
+        "sanity": sanity,
     }
     if st.kv_len is not None:
         real = int(st.kv_len.sum().item())
@@ -548,16 +772,19 @@ def main():
         if not decode:
             log("[bench] FP8 variant of the whole layer")
             rec["fp8_layer"] = fp8_layer_leg(hero, shape, args.seed)
-        log("[bench] measured ceilings (register-only MFMA loop, plain copy)")
-        rec["roofline"]["measured_ceilings"] = measured_ceilings(hero)
-        rec["ln_quant"]["frac_of_same_size_copy"] = round(rec["ln_quant"]["gbs"] / rec["roofline"]["measured_ceilings"]["copy_24MiB_rotating_gbs"], 4)
-        rec["ln_quant_large"]["frac_of_large_copy"] = round(rec["ln_quant_large"]["gbs"] / rec["roofline"]["measured_ceilings"]["copy_256MiB_gbs"], 4)
+        log("[bench] measured ceilings (MFMA loops, MFMA + VALU co-issue, HBM streams)")
+        rec["roofline"]["measured_ceilings"] = measured_ceilings()
+        mc = rec["roofline"]["measured_ceilings"]
+        rec["ln_quant"]["frac_of_same_size_copy"] = round(rec["ln_quant"]["gbs"] / mc["copy_24MiB_rotating_gbs"], 4)
+        rec["ln_quant_large"]["frac_of_best_large_copy"] = round(rec["ln_quant_large"]["gbs"] / mc["hbm_best_copy_gbs"], 4)
         log("[bench] GEMM sweep")
         rec["gemm_sweep"] = gemm_sweep(hero, args.seed)
         del st
         torch.cuda.empty_cache()
         log("[bench] CPU oracle baseline")
-        rec["cpu_baseline"] = cpu_baseline(shape, args.seed, args.mode)
+        rec["cpu_baseline"], _ = cpu_baseline(shape, args.seed, args.mode)
+        if not args.no_workloads and args.workload == "bert-large" and args.mode == "M3" and not args.fp8:
+            rec["workloads"] = other_workloads(hero, args.seed)
     print(json.dumps(rec), flush=True)
 
 

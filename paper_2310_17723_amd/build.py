@@ -17,6 +17,8 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhero.so")
+PROBE_SRC = os.path.join(HERE, "probe", "probe_ops.hip")      # bench-side measuring instruments: a library of their own
+PROBE_LIB = os.path.join(HERE, "libhero_probe.so")
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -53,6 +55,13 @@ def build_lib(verbose: bool = True, jobs: int = 8) -> str:
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
+    cmd = [hipcc, *FLAGS, "-shared", "-o", PROBE_LIB, PROBE_SRC]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if r.returncode != 0:
+        sys.stderr.write(r.stdout + "\n")
+        raise RuntimeError("hipcc failed on the probe library")
     return LIB
 
 

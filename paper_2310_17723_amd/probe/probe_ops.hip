@@ -1,16 +1,26 @@
-// Diagnostics, not on the hot path: the ceilings the kernels are measured against, taken on the machine at
-// hand.  hero_probe_mfma_i8 runs a register-only loop of v_mfma_i32_32x32x32_i8 (one 512-thread workgroup per CU,
-// two waves per SIMD, eight independent accumulators per wave, nothing else in the loop), whose rate is the
-// matrix cores' rate at the clock the chip sustains under that load.  The clock depends on how many operand bits
-// toggle, so the operands are either near-constant or random bytes.  hero_probe_copy is a plain device copy.
-#include "hero_common.h"
+// libhero_probe: measuring instruments of bench.py, NOT part of the product library.  They establish, on the
+// machine at hand, the ceilings the kernels of libhero are compared with:
+//   * a register-only loop of v_mfma_i32_32x32x32_i8 (the matrix cores' rate at the clock the chip sustains under
+//     that load; the clock depends on how many operand bits toggle, so the operands are near-constant or random);
+//   * the same loop with fp32 vector instructions between the matrix instructions of a wave, or in the other wave
+//     of the SIMD (does the vector ALU issue while the matrix pipe is busy?);
+//   * HBM streams: read-only, write-only, copy with 1 or 4 independent 16-byte loads in flight per lane, and the
+//     runtime's own device-to-device copy.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "../../include/hero_probe.h"
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
 
 namespace {
+
+inline int launch_status() { return hipGetLastError() == hipSuccess ? 0 : 6; }
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 __device__ __forceinline__ unsigned lcg(unsigned& s) { s = s * 1664525u + 1013904223u; return s ^ (s >> 13) ^ (s << 7); }
 
 __global__ __launch_bounds__(512) void probe_mfma_i8_kernel(int random_bytes, int iters, int* sink) {
-    typedef int v16i_t __attribute__((ext_vector_type(16)));
     unsigned seed = threadIdx.x * 7919u + blockIdx.x * 104729u + 1u;
     v4i fa[4], fb[2];
 #pragma unroll
@@ -21,7 +31,7 @@ __global__ __launch_bounds__(512) void probe_mfma_i8_kernel(int random_bytes, in
     for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j) fb[i][j] = random_bytes ? (int)lcg(seed) : 0x01010101;
-    v16i_t acc[8];
+    v16i acc[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i)
 #pragma unroll
@@ -41,28 +51,167 @@ __global__ __launch_bounds__(512) void probe_mfma_i8_kernel(int random_bytes, in
     if (s == 0x7fffffff) sink[0] = s;                     // keeps the loop alive; never true for these operands' sums
 }
 
+// ---- matrix and vector instructions together.  Inline assembly pins the order: per iteration 8 matrix
+// instructions on 8 independent accumulators, V fp32 fma behind each (16 independent chains).
+__device__ __forceinline__ void asm_mfma(v16i& c, v4i a, v4i b) {
+    asm volatile("v_mfma_i32_32x32x32_i8 %0, %1, %2, %0" : "+v"(c) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ void asm_fma(float& x, float a, float b) {
+    asm volatile("v_fma_f32 %0, %1, %2, %0" : "+v"(x) : "v"(a), "v"(b));
+}
+// MODE 0: every wave: 8 x (matrix instruction, V fma).  MODE 1: every wave: the fma only.
+// MODE 2: waves 0-3 (one per SIMD) twice the matrix instructions, waves 4-7 twice the fma: the same work, split by wave.
+template <int MODE, int V>
+__global__ __launch_bounds__(512) void probe_coissue_kernel(int iters, int* sink) {
+    extern __shared__ int lds[];                                   // sized to keep one workgroup per CU
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    unsigned seed = threadIdx.x * 7919u + blockIdx.x * 104729u + 1u;
+    v4i a, b;
+    for (int i = 0; i < 4; ++i) { a[i] = (int)lcg(seed); b[i] = (int)lcg(seed); }
+    v16i acc[8];
+    for (int j = 0; j < 8; ++j) for (int r = 0; r < 16; ++r) acc[j][r] = 0;
+    float x[16];
+    for (int i = 0; i < 16; ++i) x[i] = 0.001f * (lane + i);
+    const float fa = 0.999f, fb = 1e-4f;
+    if (MODE == 2 && wave < 4) {
+        for (int it = 0; it < 2 * iters; ++it) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) asm_mfma(acc[j], a, b);
+        }
+    } else if (MODE == 2 || MODE == 1) {
+        for (int it = 0; it < (MODE == 2 ? 2 * iters : iters); ++it) {
+#pragma unroll
+            for (int j = 0; j < 8 * V; ++j) asm_fma(x[j & 15], fa, fb);
+        }
+    } else {
+        for (int it = 0; it < iters; ++it) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                asm_mfma(acc[j], a, b);
+#pragma unroll
+                for (int v = 0; v < V; ++v) asm_fma(x[(j * V + v) & 15], fa, fb);
+            }
+        }
+    }
+    asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");   // the last matrix results are read below
+    int s = 0;
+    for (int j = 0; j < 8; ++j) for (int r = 0; r < 16; ++r) s ^= acc[j][r];
+    float fs = 0;
+    for (int i = 0; i < 16; ++i) fs += x[i];
+    if (s == 0x7fffffff && fs == 123.0f) sink[0] = s + lds[lane];
+}
+
+template <int MODE, int V>
+int launch_coissue(int cus, int iters, int* sink, hipStream_t st) {
+    const size_t lds = 100 * 1024;
+    static bool once = false;
+    if (!once) {
+        if (hipFuncSetAttribute((const void*)probe_coissue_kernel<MODE, V>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) return 6;
+        once = true;
+    }
+    hipLaunchKernelGGL((probe_coissue_kernel<MODE, V>), dim3((unsigned)cus), dim3(512), lds, st, iters, sink);
+    return launch_status();
+}
+
+// ---- HBM streams.  Grid-stride over 16-byte elements, U independent loads in flight per lane and trip.
+template <int U>
 __global__ __launch_bounds__(256) void probe_copy_kernel(const v4i* __restrict__ src, v4i* __restrict__ dst, int64_t n16) {
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (int64_t)gridDim.x * 256) dst[i] = src[i];
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    for (; i + (U - 1) * stride < n16; i += U * stride) {
+        v4i r[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) r[u] = src[i + u * stride];
+#pragma unroll
+        for (int u = 0; u < U; ++u) dst[i + u * stride] = r[u];
+    }
+    for (; i < n16; i += stride) dst[i] = src[i];
+}
+__global__ __launch_bounds__(256) void probe_read_kernel(const v4i* __restrict__ src, int64_t n16, int* sink) {
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    v4i s = {0, 0, 0, 0};
+    for (; i + 3 * stride < n16; i += 4 * stride) {
+        const v4i r0 = src[i], r1 = src[i + stride], r2 = src[i + 2 * stride], r3 = src[i + 3 * stride];
+        s ^= r0 ^ r1 ^ r2 ^ r3;
+    }
+    for (; i < n16; i += stride) s ^= src[i];
+    if ((s[0] ^ s[1] ^ s[2] ^ s[3]) == 0x5a5a5a5b) sink[0] = 1;     // keeps the loads alive
+}
+__global__ __launch_bounds__(256) void probe_write_kernel(v4i* __restrict__ dst, int64_t n16) {
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    const v4i v = {(int)threadIdx.x, 1, 2, 3};
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) dst[i] = v;
 }
 
 }  // namespace
 
-extern "C" hero_status hero_probe_mfma_i8(int random_bytes, int64_t iters, int32_t* sink, double* ops, void* stream) {
-    if (iters <= 0 || iters > 0x7fffffffLL) return HERO_ERR_SHAPE;
-    if (!sink) return HERO_ERR_NULL;
+extern "C" int hero_probe_mfma_i8(int random_bytes, int64_t iters, int32_t* sink, double* ops, void* stream) {
+    if (iters <= 0 || iters > 0x7fffffffLL) return 2;
+    if (!sink) return 1;
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
-        return HERO_ERR_LAUNCH;
+        return 6;
     hipLaunchKernelGGL(probe_mfma_i8_kernel, dim3((unsigned)cus), dim3(512), 0, (hipStream_t)stream, random_bytes, (int)iters, sink);
     if (ops) *ops = (double)cus * 8.0 * (double)iters * 16.0 * 65536.0;      // 8 waves x 16 instructions x 2*32*32*32 per iteration
-    return hero_launch_status();
+    return launch_status();
 }
 
-extern "C" hero_status hero_probe_copy(const void* src, void* dst, int64_t bytes, void* stream) {
-    if (bytes < 0 || bytes % 16 != 0) return HERO_ERR_SHAPE;
-    if (bytes == 0) return HERO_OK;
-    if (!src || !dst) return HERO_ERR_NULL;
-    if (!hero_aligned16(src) || !hero_aligned16(dst)) return HERO_ERR_ALIGN;
-    hipLaunchKernelGGL(probe_copy_kernel, dim3(256 * 16), dim3(256), 0, (hipStream_t)stream, (const v4i*)src, (v4i*)dst, bytes / 16);
-    return hero_launch_status();
+extern "C" int hero_probe_coissue(int mode, int valu_per_mfma, int64_t iters, int32_t* sink, double* mfma_ops,
+                                  double* valu_wave_instr, void* stream) {
+    if (iters <= 0 || iters > 0x3fffffffLL) return 2;
+    if (!sink) return 1;
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+        return 6;
+    hipStream_t st = (hipStream_t)stream;
+    const int it = (int)iters, V = valu_per_mfma;
+    int rc = 4;
+    if (mode == 0 && V == 0) rc = launch_coissue<0, 0>(cus, it, sink, st);
+    else if (mode == 0 && V == 4) rc = launch_coissue<0, 4>(cus, it, sink, st);
+    else if (mode == 0 && V == 8) rc = launch_coissue<0, 8>(cus, it, sink, st);
+    else if (mode == 1 && V == 4) rc = launch_coissue<1, 4>(cus, it, sink, st);
+    else if (mode == 1 && V == 8) rc = launch_coissue<1, 8>(cus, it, sink, st);
+    else if (mode == 2 && V == 4) rc = launch_coissue<2, 4>(cus, it, sink, st);
+    else if (mode == 2 && V == 8) rc = launch_coissue<2, 8>(cus, it, sink, st);
+    if (mfma_ops) *mfma_ops = mode == 1 ? 0.0 : (double)cus * 8.0 * (double)iters * 8.0 * 65536.0;
+    if (valu_wave_instr) *valu_wave_instr = (double)cus * 8.0 * (double)iters * 8.0 * V;
+    return rc;
+}
+
+extern "C" int hero_probe_copy(const void* src, void* dst, int64_t bytes, int loads_in_flight, void* stream) {
+    if (bytes < 0 || bytes % 16 != 0 || (loads_in_flight != 1 && loads_in_flight != 4)) return 2;
+    if (bytes == 0) return 0;
+    if (!src || !dst) return 1;
+    if (!aligned16(src) || !aligned16(dst)) return 3;
+    if (loads_in_flight == 1)
+        hipLaunchKernelGGL(probe_copy_kernel<1>, dim3(256 * 16), dim3(256), 0, (hipStream_t)stream, (const v4i*)src, (v4i*)dst, bytes / 16);
+    else
+        hipLaunchKernelGGL(probe_copy_kernel<4>, dim3(256 * 8), dim3(256), 0, (hipStream_t)stream, (const v4i*)src, (v4i*)dst, bytes / 16);
+    return launch_status();
+}
+
+extern "C" int hero_probe_read(const void* src, int64_t bytes, int32_t* sink, void* stream) {
+    if (bytes < 0 || bytes % 16 != 0) return 2;
+    if (bytes == 0) return 0;
+    if (!src || !sink) return 1;
+    if (!aligned16(src)) return 3;
+    hipLaunchKernelGGL(probe_read_kernel, dim3(256 * 8), dim3(256), 0, (hipStream_t)stream, (const v4i*)src, bytes / 16, sink);
+    return launch_status();
+}
+
+extern "C" int hero_probe_write(void* dst, int64_t bytes, void* stream) {
+    if (bytes < 0 || bytes % 16 != 0) return 2;
+    if (bytes == 0) return 0;
+    if (!dst) return 1;
+    if (!aligned16(dst)) return 3;
+    hipLaunchKernelGGL(probe_write_kernel, dim3(256 * 16), dim3(256), 0, (hipStream_t)stream, (v4i*)dst, bytes / 16);
+    return launch_status();
+}
+
+extern "C" int hero_probe_memcpy(const void* src, void* dst, int64_t bytes, void* stream) {
+    if (bytes < 0) return 2;
+    if (bytes == 0) return 0;
+    if (!src || !dst) return 1;
+    return hipMemcpyDtoDAsync((hipDeviceptr_t)dst, (hipDeviceptr_t)src, (size_t)bytes, (hipStream_t)stream) == hipSuccess ? 0 : 6;
 }

@@ -9,10 +9,13 @@ import pytest
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "hero.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(hero_[a-z0-9_]+)\s*\(", text)))
+def declared_symbols(headers=("hero.h", "hero_debug.h")):
+    names = set()
+    for h in headers:
+        text = open(os.path.join(ROOT, "include", h)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(hero_[a-z0-9_]+)\s*\(", text))
+    return sorted(names)
 
 
 @pytest.fixture(scope="module")
@@ -29,6 +32,19 @@ def test_every_declared_symbol_is_exported_and_bound(lib):
         assert hasattr(lib.lib, n), f"libhero.so does not export {n}"
         assert n in binding.SYMBOLS, f"binding does not declare {n}"
     assert lib.build_arch() == "gfx950"
+
+
+def test_probe_library_exports_what_its_header_declares():
+    """The bench-side instruments (include/hero_probe.h) live in a library of their own; libhero does not carry them."""
+    import ctypes
+    from paper_2310_17723_amd import probe
+    names = declared_symbols(("hero_probe.h",))
+    assert set(names) == set(probe.SYMBOLS)
+    plib = ctypes.CDLL(probe.LIB_PATH)
+    import paper_2310_17723_amd as pkg
+    for n in names:
+        assert hasattr(plib, n), f"libhero_probe.so does not export {n}"
+        assert not hasattr(pkg.load().lib, n), f"libhero.so still exports the bench instrument {n}"
 
 
 def test_argument_errors_come_before_any_launch(lib):
