@@ -28,6 +28,9 @@ EPI_RAW_I32, EPI_DEQUANT, EPI_DEQUANT_GELU, EPI_REQUANT, EPI_GELU_REQUANT = rang
 MASK_NONE, MASK_PADDING, MASK_CAUSAL = range(3)
 
 
+_SAN_LIB = os.path.join(_HERE, "libhero_oracle_san.so")
+
+
 def build(force: bool = False) -> str:
     """Compile the C++ oracle with g++ (no intrinsics, no fast-math, no contraction)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
@@ -37,13 +40,25 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
+def build_sanitized() -> str:
+    """The same source with AddressSanitizer + UndefinedBehaviorSanitizer (a checker of the checker: the pins
+    are re-run against this build by tests/test_oracle_sanitized.py).  Selected with HERO_ORACLE_SANITIZED=1 in a
+    process that has the sanitizer runtime preloaded."""
+    if not os.path.exists(_SAN_LIB) or os.path.getmtime(_SAN_LIB) < os.path.getmtime(_SRC):
+        cmd = ["g++", "-O1", "-g", "-std=c++17", "-fopenmp", "-ffp-contract=off", "-fPIC", "-shared",
+               "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined", "-fno-omit-frame-pointer",
+               "-Wall", "-o", _SAN_LIB, _SRC]
+        subprocess.run(cmd, check=True)
+    return _SAN_LIB
+
+
 _lib = None
 
 
 def lib():
     global _lib
     if _lib is None:
-        _lib = C.CDLL(build())
+        _lib = C.CDLL(build_sanitized() if os.environ.get("HERO_ORACLE_SANITIZED") == "1" else build())
         _lib.orc_f32_to_bf16.restype = C.c_uint16
         _lib.orc_f32_to_bf16.argtypes = [C.c_float]
         _lib.orc_bf16_to_f32.restype = C.c_float

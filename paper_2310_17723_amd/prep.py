@@ -7,8 +7,10 @@ calibrated in a pre-processing phase), Sec. 2.2.2 (W~_q = W_q / S_q, d~ = S_q S_
 W~_o = S_attn W_o / S_o), Sec. 2.2.3 (W~_2 = S_a W_2 / S_x2), Sec. 3 (calibration is a
 forward pass recording min/max, no truncation).
 
-Everything here is plain torch tensor algebra on whatever device the inputs live on; it
-produces the tensors `hero_layer_weights` points to.  The hot path never calls it.
+The unquantized reference forward is plain torch fp64 on the GPU; the calibration statistic
+(column maxima) and the fold + column-wise weight quantization run in the library's own load-time
+operators (hero_absmax_cols, hero_weight_fold_quant[_fp8]) -- there is one route, and it needs the
+loaded library.  Produces the tensors `hero_layer_weights` points to.  The hot path never calls it.
 """
 from __future__ import annotations
 
@@ -62,26 +64,18 @@ def reference_layer(p, x, arch, H, Dh, eps, mask, B, S, kv_len=None):
     return t
 
 
-def _scale(a, dim=None, qmax=127.0):
-    m = a.abs().amax() if dim is None else a.abs().amax(dim=dim)
-    m = torch.where(m == 0, torch.full_like(m, qmax), m)
-    return (m / qmax).float()
-
-
-def calibrate(p, x_calib, arch, H, Dh, eps, mask, B, S, kv_len=None, hero=None, fp8=False):
-    """Static scales: SQ scalars for X_q, X_k, X_v; FWQ vectors for X_attn, X_o, A, X_2.  With `hero` (the
-    loaded library) the column maxima come from hero_absmax_cols (a maximum is exact in any precision).
+def calibrate(p, x_calib, arch, H, Dh, eps, mask, B, S, kv_len=None, *, hero, fp8=False):
+    """Static scales: SQ scalars for X_q, X_k, X_v; FWQ vectors for X_attn, X_o, A, X_2.  The column maxima
+    come from hero_absmax_cols of the loaded library `hero` (a maximum is exact in any precision).
     fp8: the FP8 variant (Sec. 2.1): ranges are mapped to the largest E4M3 value 448, S_p = 1/448."""
     t = reference_layer(p, x_calib, arch, H, Dh, eps, mask, B, S, kv_len)
     qmax = 448.0 if fp8 else 127.0
-    if hero is not None:
-        def scale(a, dim=None):
-            m = hero.hero_absmax_cols(a.float().contiguous()).double()
-            m = m.amax() if dim is None else m
-            m = torch.where(m == 0, torch.full_like(m, qmax), m)
-            return (m / qmax).float()
-    else:
-        scale = lambda a, dim=None: _scale(a, dim, qmax)
+
+    def scale(a, dim=None):
+        m = hero.hero_absmax_cols(a.float().contiguous()).double()
+        m = m.amax() if dim is None else m
+        m = torch.where(m == 0, torch.full_like(m, qmax), m)
+        return (m / qmax).float()
     sc = {"S_q": scale(t["q"]), "S_k": scale(t["k"]), "S_v": scale(t["v"]),
           "S_attn": scale(t["attn"], 0), "S_o": scale(t["o"], 0), "S_a": scale(t["a"], 0),
           "S_x2": scale(t["x2"], 0),
@@ -89,39 +83,20 @@ def calibrate(p, x_calib, arch, H, Dh, eps, mask, B, S, kv_len=None, hero=None, 
     return sc, t["out"]
 
 
-def quantize_columns(W):
-    """Column-wise weight quantization of W [K, N] (fp64/fp32): returns int8 codes stored
-    [N, K] (each output column's K values contiguous) and the fp32 scale per column."""
-    W = W.float()
-    amax = W.abs().amax(dim=0)
-    s = torch.where(amax == 0, torch.ones_like(amax), amax / 127.0)
-    q = torch.clamp(torch.round(W / s[None, :]), -127, 127).to(torch.int8)      # torch.round: half to even
-    return q.t().contiguous(), s.contiguous()
-
-
-def prepare(p, sc, arch, d, Dh, mode=HB.MODE_M3, hero=None, fp8=False):
+def prepare(p, sc, arch, d, Dh, mode=HB.MODE_M3, *, hero, fp8=False):
     """Fold the static scales into the weights and quantize.  Returns (tensors, qk_scale,
-    p_scale): `tensors` is keyed by the field names of hero_layer_weights.  With `hero` (the loaded
-    library) the fold + column-wise quantization runs in hero_weight_fold_quant on the weights' device.
-    fp8 (needs `hero`, mode M3, scales from calibrate(fp8=True)): E4M3 weights for a layer run with M_FP8."""
+    p_scale): `tensors` is keyed by the field names of hero_layer_weights.  The fold + column-wise
+    quantization runs in hero_weight_fold_quant of the loaded library `hero`, on the weights' device.
+    fp8 (mode M3, scales from calibrate(fp8=True)): E4M3 weights for a layer run with M_FP8."""
     P = {k: v.double() for k, v in p.items()}
     post = arch == HB.ARCH_POST_LN
     t = {}
-    if fp8 and (hero is None or mode != HB.MODE_M3):
-        raise ValueError("the FP8 variant is prepared on the GPU and runs every module in 8 bits")
-    if hero is not None:
-        f32 = lambda a: None if a is None else a.float().contiguous()
+    if fp8 and mode != HB.MODE_M3:
+        raise ValueError("the FP8 variant runs every module in 8 bits")
+    f32 = lambda a: None if a is None else a.float().contiguous()
 
-        def quantize_folded(name, rm, cd):
-            return hero.hero_weight_fold_quant(p[name].float().contiguous(), f32(rm), f32(cd), fp8=fp8)
-    else:
-        def quantize_folded(name, rm, cd):
-            W = P[name]
-            if rm is not None:
-                W = rm.double()[:, None] * W
-            if cd is not None:
-                W = W / cd.double()[None, :]
-            return quantize_columns(W)
+    def quantize_folded(name, rm, cd):
+        return hero.hero_weight_fold_quant(p[name].float().contiguous(), f32(rm), f32(cd), fp8=fp8)
     if mode & HB.M_ATTN:
         div = torch.cat([sc["S_q"].double().expand(d), sc["S_k"].double().expand(d), sc["S_v"].double().expand(d)])
         qk_scale = float(sc["S_q"].double() * sc["S_k"].double() / math.sqrt(Dh))
