@@ -407,7 +407,9 @@ def int8_attn_online(q, k, v, *, qk_scale_h, p_scale, out_col_scale, out_scale_i
 
 
 # ------------------------------------------------------------------ BF16 side
-def bf16_gemm(A, Wt, bias=None, residual=None, gelu=False) -> np.ndarray:
+def hp_gemm(A, Wt, bias=None, residual=None, gelu=False, dt=BF16) -> np.ndarray:
+    """The 16-bit side of a switched module (Sec. 2.3): C = act(A W + bias) (+ residual), operands, residual and
+    result in `dt` (BF16 or F16 bit patterns), fp64 sums rounded once."""
     A = np.ascontiguousarray(A, np.uint16)
     Wt = np.ascontiguousarray(Wt, np.uint16)
     M, K = A.shape
@@ -417,22 +419,38 @@ def bf16_gemm(A, Wt, bias=None, residual=None, gelu=False) -> np.ndarray:
     if residual is not None:
         residual = np.ascontiguousarray(residual, np.uint16)
     Cm = np.empty((M, N), np.uint16)
-    lib().orc_bf16_gemm(_p(A), _i64(K), _p(Wt), _i64(K), _p(bias), _p(residual), _i64(N), C.c_int(int(gelu)),
-                        _p(Cm), _i64(N), _i64(M), _i64(N), _i64(K))
+    rc = lib().orc_hp_gemm(_p(A), _i64(K), _p(Wt), _i64(K), _p(bias), _p(residual), _i64(N), C.c_int(int(gelu)),
+                           _p(Cm), _i64(N), _i64(M), _i64(N), _i64(K), C.c_int(dt))
+    if rc != 0:
+        raise ValueError("oracle hp_gemm: dt must be BF16 or F16")
     return Cm
 
 
-def bf16_attn(q, k, v, *, scale, mask=MASK_NONE, kv_len=None) -> np.ndarray:
+def bf16_gemm(A, Wt, bias=None, residual=None, gelu=False) -> np.ndarray:
+    return hp_gemm(A, Wt, bias, residual, gelu, BF16)
+
+
+def hp_attn(q, k, v, *, scale, mask=MASK_NONE, kv_len=None, dt=BF16) -> np.ndarray:
     B, Sq, H, Dh = q.shape
     Skv = k.shape[1]
     if kv_len is not None:
         kv_len = np.ascontiguousarray(kv_len, np.int32)
     out = np.empty((B * Sq, H * Dh), np.uint16)
     base = lambda a: C.c_void_p(a.ctypes.data)
-    lib().orc_bf16_attn(base(q), _strides(q), base(k), _strides(k), base(v), _strides(v),
-                        _i64(B), _i64(H), _i64(Sq), _i64(Skv), _i64(Dh), C.c_float(scale),
-                        C.c_int(mask), _p(kv_len), _p(out), _i64(H * Dh))
+    rc = lib().orc_hp_attn(base(q), _strides(q), base(k), _strides(k), base(v), _strides(v),
+                           _i64(B), _i64(H), _i64(Sq), _i64(Skv), _i64(Dh), C.c_float(scale),
+                           C.c_int(mask), _p(kv_len), _p(out), _i64(H * Dh), C.c_int(dt))
+    if rc != 0:
+        raise ValueError("oracle hp_attn: dt must be BF16 or F16")
     return out
+
+
+def bf16_attn(q, k, v, *, scale, mask=MASK_NONE, kv_len=None) -> np.ndarray:
+    return hp_attn(q, k, v, scale=scale, mask=mask, kv_len=kv_len, dt=BF16)
+
+
+def f32_to_hp(x, dt):
+    return f32_to_bf16(x) if dt == BF16 else f32_to_f16(x)
 
 
 def gelu(x: float) -> float:

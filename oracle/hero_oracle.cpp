@@ -691,29 +691,38 @@ int orc_int8_attn_online(const int8_t* q, const int64_t* qs, const int8_t* k, co
 // must approach.
 //   C = act(A W + bias) (+ residual),  A [M,K] bf16, Wt [N][K] bf16, C bf16.
 // ---------------------------------------------------------------------------------
-int orc_bf16_gemm(const uint16_t* A, int64_t lda, const uint16_t* Wt, int64_t ldb,
-                  const float* bias, const uint16_t* residual, int64_t ldr, int gelu,
-                  uint16_t* C, int64_t ldc, int64_t M, int64_t N, int64_t K) {
+// dt = ORC_BF16 or ORC_F16: the 16-bit type of operands, residual and result (Sec. 2.3: a switched module runs in
+// FP16 / BF16).
+int orc_hp_gemm(const uint16_t* A, int64_t lda, const uint16_t* Wt, int64_t ldb,
+                const float* bias, const uint16_t* residual, int64_t ldr, int gelu,
+                uint16_t* C, int64_t ldc, int64_t M, int64_t N, int64_t K, int dt) {
+    if (dt != ORC_BF16 && dt != ORC_F16) return -1;
 #pragma omp parallel for schedule(static)
     for (int64_t i = 0; i < M; ++i)
         for (int64_t j = 0; j < N; ++j) {
             double acc = 0.0;
             for (int64_t kk = 0; kk < K; ++kk)
-                acc += (double)orc_bf16_to_f32(A[i * lda + kk]) * (double)orc_bf16_to_f32(Wt[j * ldb + kk]);
+                acc += (double)load_hp(A, dt, i * lda + kk) * (double)load_hp(Wt, dt, j * ldb + kk);
             if (bias) acc += (double)bias[j];
             if (gelu) acc = orc_gelu(acc);
-            if (residual) acc += (double)orc_bf16_to_f32(residual[i * ldr + j]);
-            C[i * ldc + j] = orc_f32_to_bf16((float)acc);
+            if (residual) acc += (double)load_hp(residual, dt, i * ldr + j);
+            store_hp(C, dt, i * ldc + j, (float)acc);
         }
     return 0;
 }
+int orc_bf16_gemm(const uint16_t* A, int64_t lda, const uint16_t* Wt, int64_t ldb,
+                  const float* bias, const uint16_t* residual, int64_t ldr, int gelu,
+                  uint16_t* C, int64_t ldc, int64_t M, int64_t N, int64_t K) {
+    return orc_hp_gemm(A, lda, Wt, ldb, bias, residual, ldr, gelu, C, ldc, M, N, K, ORC_BF16);
+}
 
-// BF16 attention core: softmax(Q K^T * scale) V in fp64 on bf16 inputs, bf16 out.
+// 16-bit attention core: softmax(Q K^T * scale) V in fp64 on bf16 / f16 inputs, output in the same type.
 // Same strides and mask rules as orc_int8_attn.
-int orc_bf16_attn(const uint16_t* q, const int64_t* qs, const uint16_t* k, const int64_t* ks,
-                  const uint16_t* v, const int64_t* vs,
-                  int64_t B, int64_t H, int64_t Sq, int64_t Skv, int64_t Dh, float scale,
-                  int mask, const int32_t* kv_len, uint16_t* out, int64_t ldo) {
+int orc_hp_attn(const uint16_t* q, const int64_t* qs, const uint16_t* k, const int64_t* ks,
+                const uint16_t* v, const int64_t* vs,
+                int64_t B, int64_t H, int64_t Sq, int64_t Skv, int64_t Dh, float scale,
+                int mask, const int32_t* kv_len, uint16_t* out, int64_t ldo, int dt) {
+    if (dt != ORC_BF16 && dt != ORC_F16) return -1;
 #pragma omp parallel for schedule(dynamic) collapse(2)
     for (int64_t b = 0; b < B; ++b)
         for (int64_t h = 0; h < H; ++h) {
@@ -727,8 +736,8 @@ int orc_bf16_attn(const uint16_t* q, const int64_t* qs, const uint16_t* k, const
                 for (int64_t kk = 0; kk < nvis; ++kk) {
                     double acc = 0.0;
                     for (int64_t e = 0; e < Dh; ++e)
-                        acc += (double)orc_bf16_to_f32(q[b * qs[0] + i * qs[1] + h * qs[2] + e * qs[3]]) *
-                               (double)orc_bf16_to_f32(k[b * ks[0] + kk * ks[1] + h * ks[2] + e * ks[3]]);
+                        acc += (double)load_hp(q, dt, b * qs[0] + i * qs[1] + h * qs[2] + e * qs[3]) *
+                               (double)load_hp(k, dt, b * ks[0] + kk * ks[1] + h * ks[2] + e * ks[3]);
                     p[kk] = acc * (double)scale;
                     m = std::max(m, p[kk]);
                 }
@@ -737,12 +746,18 @@ int orc_bf16_attn(const uint16_t* q, const int64_t* qs, const uint16_t* k, const
                 for (int64_t e = 0; e < Dh; ++e) {
                     double acc = 0.0;
                     for (int64_t kk = 0; kk < nvis; ++kk)
-                        acc += p[kk] * (double)orc_bf16_to_f32(v[b * vs[0] + kk * vs[1] + h * vs[2] + e * vs[3]]);
-                    out[(b * Sq + i) * ldo + h * Dh + e] = orc_f32_to_bf16(nvis > 0 ? (float)(acc / l) : 0.0f);
+                        acc += p[kk] * (double)load_hp(v, dt, b * vs[0] + kk * vs[1] + h * vs[2] + e * vs[3]);
+                    store_hp(out, dt, (b * Sq + i) * ldo + h * Dh + e, nvis > 0 ? (float)(acc / l) : 0.0f);
                 }
             }
         }
     return 0;
+}
+int orc_bf16_attn(const uint16_t* q, const int64_t* qs, const uint16_t* k, const int64_t* ks,
+                  const uint16_t* v, const int64_t* vs,
+                  int64_t B, int64_t H, int64_t Sq, int64_t Skv, int64_t Dh, float scale,
+                  int mask, const int32_t* kv_len, uint16_t* out, int64_t ldo) {
+    return orc_hp_attn(q, qs, k, ks, v, vs, B, H, Sq, Skv, Dh, scale, mask, kv_len, out, ldo, ORC_BF16);
 }
 
 int orc_num_threads(void) {

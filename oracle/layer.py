@@ -28,6 +28,7 @@ M_QKV, M_ATTN, M_ATTN_OUT, M_FC1, M_FC2 = 1, 2, 4, 8, 16
 MODE_M3 = M_QKV | M_ATTN | M_ATTN_OUT | M_FC1 | M_FC2
 MODE_M2 = M_QKV | M_ATTN | M_ATTN_OUT | M_FC1
 MODE_M1 = M_QKV | M_FC1
+MODE_M0 = 0          # every module 16-bit: the layer of Table 2's FP16 row
 S_P = np.float32(1.0 / 255.0)
 S_P_FP8 = np.float32(1.0 / 448.0)     # the FP8 variant: p = 1 is the largest E4M3 code
 
@@ -116,11 +117,24 @@ def calibrate(p, x_calib, shape, B, S, kv_len=None, fp8=False):
     return sc, t["out"]
 
 
-def _bf16(a):
-    return O.f32_to_bf16(np.asarray(a, np.float32))
+def _hp(a, dt):
+    return O.f32_to_hp(np.asarray(a, np.float32), dt)
 
 
-def prepare(p, sc, shape, mode=MODE_M3, fp8=False):
+def check_mode(mode):
+    """Which module subsets are a layer (Sec. 2.3: every module has an INT8 / 16-bit switch).  A 16-bit module
+    hands 16-bit values on, and the method has no stand-alone quantization kernel, so an INT8 attention needs an
+    INT8 QKV in front of it (SQ codes), an INT8 attention-output linear an INT8 attention (FWQ codes), an INT8 FC2
+    an INT8 FC1 (GELU^quant codes).  Table 1's M1 / M2 / M3 and the all-16-bit layer satisfy this."""
+    if (mode & M_ATTN) and not (mode & M_QKV):
+        raise ValueError("an INT8 attention needs an INT8 QKV GeMM in front of it")
+    if (mode & M_ATTN_OUT) and not (mode & M_ATTN):
+        raise ValueError("an INT8 attention-output linear needs INT8 attention in front of it")
+    if (mode & M_FC2) and not (mode & M_FC1):
+        raise ValueError("an INT8 FC2 needs an INT8 FC1 (GELU^quant) in front of it")
+
+
+def prepare(p, sc, shape, mode=MODE_M3, fp8=False, hp_dt=O.BF16):
     """Fold the static scales into the weights, then quantize column-wise (Sec. 2.2.2:
     W~_q = W_q / S_q and W~_o = S_attn W_o / S_o;  Sec. 2.2.3: W~_2 = S_a W_2 / S_x2).
     Biases fold with the output scale.  Folding is done in fp64, cast to fp32 once, then
@@ -129,17 +143,23 @@ def prepare(p, sc, shape, mode=MODE_M3, fp8=False):
     max / 448; the scales in ``sc`` must come from calibrate(..., fp8=True)."""
     d = shape.d
     P = {k_: np.asarray(v_, np.float64) for k_, v_ in p.items()}
-    w = {"mode": mode, "S_p": sc["S_p"], "fp8": bool(fp8)}
+    w = {"mode": mode, "S_p": sc["S_p"], "fp8": bool(fp8), "hp_dt": hp_dt}
     if fp8 and mode != MODE_M3:
         raise ValueError("the FP8 variant runs every module in 8 bits")
+    if hp_dt not in (O.BF16, O.F16):
+        raise ValueError("the 16-bit side is BF16 or FP16")
+    check_mode(mode)
     fold_quant = O.weight_fold_quant_fp8 if fp8 else O.weight_fold_quant
-    # --- QKV (always INT8 in Table 1).  INT8 attention consumes SQ codes, so S_{q,k,v}
-    # are folded; a BF16 attention consumes dequantized values, so nothing is folded.
+    # --- QKV (INT8 in every mode of Table 1; 16-bit in the all-16-bit layer).  INT8 attention consumes SQ
+    # codes, so S_{q,k,v} are folded; a 16-bit attention consumes dequantized values, so nothing is folded.
     if mode & M_ATTN:
         div = np.concatenate([np.full(d, float(sc["S_q"])), np.full(d, float(sc["S_k"])), np.full(d, float(sc["S_v"]))])
     else:
         div = np.ones(3 * d)
-    w["wq_qkv"], w["s_qkv"] = fold_quant(P["w_qkv"], None, div)
+    if mode & M_QKV:
+        w["wq_qkv"], w["s_qkv"] = fold_quant(P["w_qkv"], None, div)
+    else:
+        w["wb_qkv"] = _hp(P["w_qkv"].T.copy(), hp_dt)
     w["b_qkv"] = (P["b_qkv"] / div).astype(np.float32)
     w["qk_scale"] = np.float32(float(sc["S_q"]) * float(sc["S_k"]) / math.sqrt(shape.Dh))
     w["bf16_qk_scale"] = np.float32(1.0 / math.sqrt(shape.Dh))
@@ -156,11 +176,14 @@ def prepare(p, sc, shape, mode=MODE_M3, fp8=False):
         w["wq_o"], w["s_o_w"] = fold_quant(P["w_o"], sc["S_attn"], sc["S_o"] if post else None)
         w["b_o"] = bo.astype(np.float32)
     else:
-        w["wb_o"] = _bf16(P["w_o"].T.copy())
+        w["wb_o"] = _hp(P["w_o"].T.copy(), hp_dt)
         w["b_o"] = P["b_o"].astype(np.float32)
     w["S_o"] = sc["S_o"]
-    # --- FC1 (always INT8 in Table 1); GELU^quant divides by S_a, nothing to fold
-    w["wq_1"], w["s_1"] = fold_quant(P["w_1"])
+    # --- FC1 (INT8 in every mode of Table 1); GELU^quant divides by S_a, nothing to fold
+    if mode & M_FC1:
+        w["wq_1"], w["s_1"] = fold_quant(P["w_1"])
+    else:
+        w["wb_1"] = _hp(P["w_1"].T.copy(), hp_dt)
     w["b_1"] = P["b_1"].astype(np.float32)
     w["S_a"] = sc["S_a"]
     # --- FC2
@@ -171,7 +194,7 @@ def prepare(p, sc, shape, mode=MODE_M3, fp8=False):
         w["wq_2"], w["s_2_w"] = fold_quant(P["w_2"], sc["S_a"], sc["S_x2"] if post else None)
         w["b_2"] = b2.astype(np.float32)
     else:
-        w["wb_2"] = _bf16(P["w_2"].T.copy())
+        w["wb_2"] = _hp(P["w_2"].T.copy(), hp_dt)
         w["b_2"] = P["b_2"].astype(np.float32)
     w["S_x2"] = sc["S_x2"]
     for k_ in ("ln1_g", "ln1_b", "ln2_g", "ln2_b"):
@@ -185,34 +208,38 @@ def _heads(a2d, B, S, H, Dh, part, parts=3):
     return a2d.reshape(B, S, parts, H, Dh)[:, :, part]
 
 
-def layer_fwd(w, shape, B, S, *, x_q=None, x_s=None, h=None, kv_len=None, cache=None, trace=None):
-    """One W8A8 layer.  POST_LN: input (x_q int8 [T,d], x_s f32 [T]) -> (out_q, out_s).
-    PRE_LN: input h (bf16 bit patterns [T,d]) -> new h.  ``cache`` (PRE_LN only) is a dict
-    {k, v: int8 [B,H,Smax,Dh]}; the S new key/value rows are written at positions
-    kv_len[b]-S .. kv_len[b]-1 and attention runs over the cache.  ``trace`` (a dict)
-    receives every intermediate."""
+def layer_fwd(w, shape, B, S, *, x_q=None, x_s=None, x_hp=None, h=None, kv_len=None, cache=None, trace=None):
+    """One layer, every module INT8 or 16-bit as the mode mask says (Sec. 2.3).
+    POST_LN: input (x_q int8 [T,d], x_s f32 [T]) when the QKV GeMM is INT8, else x_hp (16-bit bit patterns [T,d]);
+    returns (out_q, out_s); the 16-bit copy of the output a 16-bit successor would read is trace["out_hp"].
+    PRE_LN: input h (16-bit bit patterns [T,d]) -> new h.  ``cache`` (INT8 attention only) is a dict
+    {k, v: int8 [B,H,Smax,Dh]}; the S new key/value rows are written at positions kv_len[b]-S .. kv_len[b]-1 and
+    attention runs over the cache.  ``trace`` (a dict) receives every intermediate.  The 16-bit type is
+    w["hp_dt"] (BF16 or F16)."""
     if w.get("fp8"):
         return layer_fwd_fp8(w, shape, B, S, x_q=x_q, x_s=x_s, h=h, kv_len=kv_len, cache=cache, trace=trace)
     d, H, Dh, mode = shape.d, shape.H, shape.Dh, w["mode"]
-    T = B * S
+    hp = w.get("hp_dt", O.BF16)
     tr = trace if trace is not None else {}
     post = shape.arch == POST_LN
-    if not (mode & M_QKV and mode & M_FC1):
-        raise ValueError("QKV and FC1 are INT8 in every mode of Table 1")
-    if (mode & M_ATTN_OUT) and not (mode & M_ATTN):
-        raise ValueError("an INT8 attention-output linear needs INT8 attention in front of it")
+    check_mode(mode)
+    q_i8, attn_i8, o_i8 = bool(mode & M_QKV), bool(mode & M_ATTN), bool(mode & M_ATTN_OUT)
+    f1_i8, f2_i8 = bool(mode & M_FC1), bool(mode & M_FC2)
+    if cache is not None and not attn_i8:
+        raise ValueError("the KV cache holds INT8 (SQ) codes: it needs the INT8 attention")
+    # ---- the layer input as the QKV GeMM reads it
     if post:
-        xin_q, xin_s = x_q, x_s
+        xin_q, xin_s, xin_hp = (x_q, x_s, None) if q_i8 else (None, None, x_hp)
     else:
-        xin_q, xin_s, _ = O.ln_quant(h, O.BF16, None, None, 0, None, w["ln1_g"], w["ln1_b"], shape.eps)
-    tr["xin_q"], tr["xin_s"] = xin_q, xin_s
-    # ---- QKV GeMM^quant; the bare Round of the folded weights when attention is INT8
-    if mode & M_ATTN:
+        xin_q, xin_s, xin_hp = O.ln_quant(h, hp, None, None, 0, None, w["ln1_g"], w["ln1_b"], shape.eps,
+                                          y_hp_dt=None if q_i8 else hp)
+    tr["xin_q"], tr["xin_s"], tr["xin_hp"] = xin_q, xin_s, xin_hp
+    # ---- QKV: SQ codes (the bare Round of the folded weights) for an INT8 attention, 16-bit values otherwise
+    if q_i8:
         qkv = O.int8_gemm(xin_q, w["wq_qkv"], a_row_scale=xin_s, b_col_scale=w["s_qkv"], bias=w["b_qkv"],
-                          epi=O.EPI_REQUANT, c_dt=O.I8)
+                          epi=O.EPI_REQUANT if attn_i8 else O.EPI_DEQUANT, c_dt=O.I8 if attn_i8 else hp)
     else:
-        qkv = O.int8_gemm(xin_q, w["wq_qkv"], a_row_scale=xin_s, b_col_scale=w["s_qkv"], bias=w["b_qkv"],
-                          epi=O.EPI_DEQUANT, c_dt=O.BF16)
+        qkv = O.hp_gemm(xin_hp, w["wb_qkv"], bias=w["b_qkv"], dt=hp)
     tr["qkv"] = qkv
     qv = _heads(qkv, B, S, H, Dh, 0)
     if cache is not None:
@@ -222,62 +249,67 @@ def layer_fwd(w, shape, B, S, *, x_q=None, x_s=None, h=None, kv_len=None, cache=
             cache["k"][b, :, p0:p0 + S, :] = kn[b].transpose(1, 0, 2)
             cache["v"][b, :, p0:p0 + S, :] = vn[b].transpose(1, 0, 2)
         kv, vv = cache["k"].transpose(0, 2, 1, 3), cache["v"].transpose(0, 2, 1, 3)   # [B,Smax,H,Dh] views
-        mask = shape.mask
     else:
         kv, vv = _heads(qkv, B, S, H, Dh, 1), _heads(qkv, B, S, H, Dh, 2)
-        mask = shape.mask
+    mask = shape.mask
     # ---- attention
-    if mode & M_ATTN:
-        to_i8 = bool(mode & M_ATTN_OUT)
+    if attn_i8:
         attn = O.int8_attn(qv, kv, vv, qk_scale=float(w["qk_scale"]), p_scale=float(w["S_p"]),
-                           out_col_scale=w["attn_out_scale"] if to_i8 else w["attn_out_scalar"],
-                           out_scale_is_scalar=not to_i8, mask=mask, kv_len=kv_len,
-                           out_dt=O.I8 if to_i8 else O.BF16)
+                           out_col_scale=w["attn_out_scale"] if o_i8 else w["attn_out_scalar"],
+                           out_scale_is_scalar=not o_i8, mask=mask, kv_len=kv_len,
+                           out_dt=O.I8 if o_i8 else hp)
     else:
-        attn = O.bf16_attn(qv, kv, vv, scale=float(w["bf16_qk_scale"]), mask=mask, kv_len=kv_len)
+        attn = O.hp_attn(qv, kv, vv, scale=float(w["bf16_qk_scale"]), mask=mask, kv_len=kv_len, dt=hp)
     tr["attn"] = attn
     # ---- attention output linear, then (post-LN) LN^quant of the two addends
+    x_in = (xin_q, O.I8, xin_s) if q_i8 else (xin_hp, hp, None)
     if post:
-        if mode & M_ATTN_OUT:
+        if o_i8:
             xo = O.int8_gemm(attn, w["wq_o"], b_col_scale=w["s_o_w"], bias=w["b_o"], epi=O.EPI_REQUANT, c_dt=O.I8)
-            mid_q, mid_s, mid_hp = O.ln_quant(xin_q, O.I8, xin_s, xo, O.I8, w["S_o"], w["ln1_g"], w["ln1_b"], shape.eps)
+            r_in = (xo, O.I8, w["S_o"])
         else:
-            xo = O.bf16_gemm(attn, w["wb_o"], bias=w["b_o"])
-            mid_q, mid_s, mid_hp = O.ln_quant(xin_q, O.I8, xin_s, xo, O.BF16, None, w["ln1_g"], w["ln1_b"], shape.eps)
+            xo = O.hp_gemm(attn, w["wb_o"], bias=w["b_o"], dt=hp)
+            r_in = (xo, hp, None)
         tr["xo"] = xo
+        mid_q, mid_s, mid_hp = O.ln_quant(x_in[0], x_in[1], x_in[2], r_in[0], r_in[1], r_in[2], w["ln1_g"], w["ln1_b"],
+                                          shape.eps, y_hp_dt=None if f1_i8 else hp)
     else:
-        if mode & M_ATTN_OUT:
-            h1 = O.int8_gemm(attn, w["wq_o"], b_col_scale=w["s_o_w"], bias=w["b_o"], residual=h, res_dt=O.BF16,
-                             epi=O.EPI_DEQUANT, c_dt=O.BF16)
+        if o_i8:
+            h1 = O.int8_gemm(attn, w["wq_o"], b_col_scale=w["s_o_w"], bias=w["b_o"], residual=h, res_dt=hp,
+                             epi=O.EPI_DEQUANT, c_dt=hp)
         else:
-            h1 = O.bf16_gemm(attn, w["wb_o"], bias=w["b_o"], residual=h)
+            h1 = O.hp_gemm(attn, w["wb_o"], bias=w["b_o"], residual=h, dt=hp)
         tr["h1"] = h1
-        mid_q, mid_s, _ = O.ln_quant(h1, O.BF16, None, None, 0, None, w["ln2_g"], w["ln2_b"], shape.eps)
-    tr["mid_q"], tr["mid_s"] = mid_q, mid_s
-    # ---- FC1 + GELU^quant
-    if mode & M_FC2:
+        mid_q, mid_s, mid_hp = O.ln_quant(h1, hp, None, None, 0, None, w["ln2_g"], w["ln2_b"], shape.eps,
+                                          y_hp_dt=None if f1_i8 else hp)
+    tr["mid_q"], tr["mid_s"], tr["mid_hp"] = mid_q, mid_s, mid_hp
+    # ---- FC1 + GELU (GELU^quant when FC2 is INT8)
+    if f1_i8:
         a = O.int8_gemm(mid_q, w["wq_1"], a_row_scale=mid_s, b_col_scale=w["s_1"], bias=w["b_1"],
-                        epi=O.EPI_GELU_REQUANT, out_col_scale=w["S_a"], c_dt=O.I8)
+                        epi=O.EPI_GELU_REQUANT if f2_i8 else O.EPI_DEQUANT_GELU,
+                        out_col_scale=w["S_a"] if f2_i8 else None, c_dt=O.I8 if f2_i8 else hp)
     else:
-        a = O.int8_gemm(mid_q, w["wq_1"], a_row_scale=mid_s, b_col_scale=w["s_1"], bias=w["b_1"],
-                        epi=O.EPI_DEQUANT_GELU, c_dt=O.BF16)
+        a = O.hp_gemm(mid_hp, w["wb_1"], bias=w["b_1"], gelu=True, dt=hp)
     tr["a"] = a
     # ---- FC2 and the closing LN^quant (post-LN) or residual add (pre-LN)
     if post:
-        if mode & M_FC2:
+        if f2_i8:
             x2 = O.int8_gemm(a, w["wq_2"], b_col_scale=w["s_2_w"], bias=w["b_2"], epi=O.EPI_REQUANT, c_dt=O.I8)
-            out_q, out_s, _ = O.ln_quant(mid_q, O.I8, mid_s, x2, O.I8, w["S_x2"], w["ln2_g"], w["ln2_b"], shape.eps)
+            r2 = (x2, O.I8, w["S_x2"])
         else:
-            x2 = O.bf16_gemm(a, w["wb_2"], bias=w["b_2"])
-            out_q, out_s, _ = O.ln_quant(mid_q, O.I8, mid_s, x2, O.BF16, None, w["ln2_g"], w["ln2_b"], shape.eps)
+            x2 = O.hp_gemm(a, w["wb_2"], bias=w["b_2"], dt=hp)
+            r2 = (x2, hp, None)
+        m_in = (mid_q, O.I8, mid_s) if f1_i8 else (mid_hp, hp, None)
+        out_q, out_s, out_hp = O.ln_quant(m_in[0], m_in[1], m_in[2], r2[0], r2[1], r2[2], w["ln2_g"], w["ln2_b"],
+                                          shape.eps, y_hp_dt=hp)
         tr["x2"] = x2
-        tr["out_q"], tr["out_s"] = out_q, out_s
+        tr["out_q"], tr["out_s"], tr["out_hp"] = out_q, out_s, out_hp
         return out_q, out_s
-    if mode & M_FC2:
-        h2 = O.int8_gemm(a, w["wq_2"], b_col_scale=w["s_2_w"], bias=w["b_2"], residual=h1, res_dt=O.BF16,
-                         epi=O.EPI_DEQUANT, c_dt=O.BF16)
+    if f2_i8:
+        h2 = O.int8_gemm(a, w["wq_2"], b_col_scale=w["s_2_w"], bias=w["b_2"], residual=h1, res_dt=hp,
+                         epi=O.EPI_DEQUANT, c_dt=hp)
     else:
-        h2 = O.bf16_gemm(a, w["wb_2"], bias=w["b_2"], residual=h1)
+        h2 = O.hp_gemm(a, w["wb_2"], bias=w["b_2"], residual=h1, dt=hp)
     tr["h2"] = h2
     return h2
 

@@ -782,25 +782,31 @@ def test_attention_online_accuracy_against_exact_softmax_and_two_pass():
     assert snr(on) > 35 and snr(on) > snr(tp) + 6, (snr(on), snr(tp))
 
 
-# ---------------------------------------------------------------- BF16 side
-def test_bf16_ops_against_torch_fp64():
+# ---------------------------------------------------------------- 16-bit side (BF16 / FP16)
+@pytest.mark.parametrize("dt", [O.BF16, O.F16])
+def test_16bit_ops_against_torch_fp64(dt):
     g = synth.rng(14)
+    tdt = torch.bfloat16 if dt == O.BF16 else torch.float16
+    enc = lambda a: O.f32_to_hp(a.astype(np.float32), dt)
+    tb = lambda u: torch.from_numpy(O.hp_to_f32(u, dt)).double()
+    bits = lambda t: t.float().to(tdt).view(torch.int16).numpy().view(np.uint16)
     M, K, N = 5, 48, 7
-    A = O.f32_to_bf16(g.standard_normal((M, K)).astype(np.float32))
-    Wt = O.f32_to_bf16(g.standard_normal((N, K)).astype(np.float32))
+    A, Wt, res = enc(g.standard_normal((M, K))), enc(g.standard_normal((N, K))), enc(g.standard_normal((M, N)))
     bias = g.standard_normal(N).astype(np.float32)
-    res = O.f32_to_bf16(g.standard_normal((M, N)).astype(np.float32))
-    tb = lambda u: torch.from_numpy(O.bf16_to_f32(u)).double()
     ref = torch.nn.functional.gelu(tb(A) @ tb(Wt).T + torch.from_numpy(bias).double()) + tb(res)
-    got = O.bf16_gemm(A, Wt, bias=bias, residual=res, gelu=True)
-    assert np.array_equal(got, ref.float().to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16))
+    got = O.hp_gemm(A, Wt, bias=bias, residual=res, gelu=True, dt=dt)
+    assert np.array_equal(got, bits(ref))
+    if dt == O.BF16:
+        assert np.array_equal(got, O.bf16_gemm(A, Wt, bias=bias, residual=res, gelu=True))
     B, S, H, Dh = 2, 5, 2, 8
-    q, k, v = (O.f32_to_bf16(g.standard_normal((B, S, H, Dh)).astype(np.float32)) for _ in range(3))
-    out = O.bf16_attn(q, k, v, scale=0.35, mask=O.MASK_CAUSAL)
+    q, k, v = (enc(g.standard_normal((B, S, H, Dh))) for _ in range(3))
+    out = O.hp_attn(q, k, v, scale=0.35, mask=O.MASK_CAUSAL, dt=dt)
     tq, tk, tv = (tb(u).permute(0, 2, 1, 3) for u in (q, k, v))
     ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, is_causal=True, scale=0.35)
     ref = ref.permute(0, 2, 1, 3).reshape(B * S, H * Dh)
-    assert np.array_equal(out, ref.float().to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16))
+    assert np.array_equal(out, bits(ref))
+    with pytest.raises(ValueError):
+        O.hp_gemm(A, Wt, dt=O.F32)
 
 
 # ---------------------------------------------------------------- layer: folds, modes, sanity
@@ -896,6 +902,58 @@ def test_layer_modes_track_fp64_model(arch):
             got = O.bf16_to_f32(OL.layer_fwd(w, shape, B, S, h=hb)).astype(np.float64)
         snr[name] = 10 * math.log10((ref ** 2).sum() / ((ref - got) ** 2).sum())
     assert all(v > 15.0 for v in snr.values()), snr
+
+
+@pytest.mark.parametrize("hp", [O.BF16, O.F16])
+@pytest.mark.parametrize("arch", [synth.POST_LN, synth.PRE_LN])
+def test_module_switch_all_subsets_ordered_against_fp64_model(arch, hp):
+    """Sec. 2.3: every module has an INT8 / 16-bit switch.  The all-16-bit layer (Table 2's FP16 row; mode 0) is
+    the unquantized layer up to 16-bit rounding; switching modules to INT8 one group at a time (M1, M2, M3 of
+    Table 1, and the two subsets in between that keep a whole sub-block 16-bit) can only add quantization
+    noise.  Pinned against the fp64 layer: SNR(M0) is at the level of the 16-bit format (bf16: 8 bits of
+    significand, fp16: 11), and SNR(M0) >= SNR(M1) >= SNR(M2) >= SNR(M3) up to half a dB of luck.  A mis-wired
+    16-bit module (wrong weight, missing bias or residual, GELU left out) drops its mode to ~0-10 dB and breaks
+    the order.  Subsets that would need a stand-alone quantization kernel are refused."""
+    mask = synth.MASK_NONE if arch == synth.POST_LN else synth.MASK_CAUSAL
+    shape = _tiny_shape(arch, mask)
+    B, S = shape.B, shape.S
+    p, sc, _, h0, emb = _setup(shape)
+    enc = lambda a: O.f32_to_hp(np.asarray(a, np.float32), hp)
+    dec = lambda u: O.hp_to_f32(u, hp).astype(np.float64)
+    if arch == synth.POST_LN:
+        xq, xs, xf = O.ln_quant(h0, O.F32, None, None, 0, None, emb["g"], emb["b"], shape.eps, y_hp_dt=O.F32)
+        ref = OL.fp64_layer(p, xf.astype(np.float64), shape, B, S)["out"]
+    else:
+        hb = enc(h0)
+        ref = OL.fp64_layer(p, dec(hb), shape, B, S)["out"]
+    A_ONLY = OL.M_QKV | OL.M_ATTN | OL.M_ATTN_OUT                      # attention block INT8, MLP block 16-bit
+    F_ONLY = OL.M_FC1 | OL.M_FC2                                        # the other way round
+    snr = {}
+    for name, mode in (("M0", OL.MODE_M0), ("M1", OL.MODE_M1), ("M2", OL.MODE_M2), ("M3", OL.MODE_M3),
+                       ("attn-block", A_ONLY), ("mlp-block", F_ONLY), ("qkv", OL.M_QKV), ("fc1", OL.M_FC1)):
+        w = OL.prepare(p, sc, shape, mode, hp_dt=hp)
+        tr = {}
+        if arch == synth.POST_LN:
+            kw = dict(x_q=xq, x_s=xs) if mode & OL.M_QKV else dict(x_hp=enc(xf))
+            OL.layer_fwd(w, shape, B, S, trace=tr, **kw)
+            got = dec(tr["out_hp"])
+        else:
+            got = dec(OL.layer_fwd(w, shape, B, S, h=hb, trace=tr))
+        snr[name] = 10 * math.log10((ref ** 2).sum() / ((ref - got) ** 2).sum())
+        # a 16-bit module reads and writes 16-bit tensors, an INT8 module INT8 ones
+        assert (tr["qkv"].dtype == np.int8) == bool(mode & OL.M_ATTN)
+        assert (tr["a"].dtype == np.int8) == bool(mode & OL.M_FC2)
+    print({k: round(v, 1) for k, v in snr.items()})
+    assert snr["M0"] > (38.0 if hp == O.BF16 else 55.0), snr
+    assert snr["M0"] + 0.5 >= snr["M1"] and snr["M1"] + 0.5 >= snr["M2"] and snr["M2"] + 0.5 >= snr["M3"], snr
+    for k in ("attn-block", "mlp-block", "qkv", "fc1"):
+        assert snr["M0"] + 0.5 >= snr[k] >= snr["M3"] - 0.5, (k, snr)
+    assert snr["M3"] > 15.0
+    for bad in (OL.M_ATTN, OL.M_QKV | OL.M_ATTN_OUT, OL.M_FC2, OL.M_QKV | OL.M_FC2):
+        with pytest.raises(ValueError):
+            OL.prepare(p, sc, shape, bad, hp_dt=hp)
+    with pytest.raises(ValueError):
+        OL.prepare(p, sc, shape, OL.MODE_M1, hp_dt=O.F32)
 
 
 @pytest.mark.parametrize("arch", [synth.POST_LN, synth.PRE_LN])
