@@ -297,56 +297,70 @@ hero_status hero_fp8_attn(const void* q, const int64_t q_strides[4],
 
 typedef enum { HERO_ARCH_POST_LN = 0, HERO_ARCH_PRE_LN = 1 } hero_arch;
 
-/* mode_mask: one bit per switchable module of Table 1; set = INT8, clear = BF16.
+/* mode_mask: one bit per switchable module (Sec. 2.3; the columns of Table 1 after "Embedding"); set = INT8,
+ * clear = 16-bit.  Table 1's modes are HERO_MODE_M1 / M2 / M3; HERO_MODE_M0 (no module bit) is the all-16-bit
+ * layer, the FP16 row of Table 2.  A 16-bit module hands 16-bit values on and the method has no stand-alone
+ * quantization kernel, so: ATTN set needs QKV set (the INT8 attention reads SQ codes), ATTN_OUT set needs ATTN
+ * set, FC2 set needs FC1 set (GELU^quant codes); any other subset is HERO_ERR_UNSUPPORTED.
+ * HERO_M_F16: the 16-bit type of the layer -- switched modules, the 16-bit copies between them, the PRE_LN
+ * residual stream h -- is FP16 instead of BF16.
  * HERO_M_FP8 (only together with all five module bits): the 8-bit format of the whole layer is OCP E4M3
  * instead of INT8 (Sec. 2.1).  Every int8_t* of hero_layer_weights / hero_layer_io then holds E4M3 bytes
  * (weights quantized column-wise to max|column| / 448, static scales calibrated to 448, p_scale = 1/448),
  * and the layer runs hero_ln_quant_fp8 / hero_fp8_gemm / hero_fp8_attn in place of the INT8 entry points. */
-enum { HERO_M_QKV = 1, HERO_M_ATTN = 2, HERO_M_ATTN_OUT = 4, HERO_M_FC1 = 8, HERO_M_FC2 = 16, HERO_M_FP8 = 32 };
+enum { HERO_M_QKV = 1, HERO_M_ATTN = 2, HERO_M_ATTN_OUT = 4, HERO_M_FC1 = 8, HERO_M_FC2 = 16, HERO_M_FP8 = 32,
+       HERO_M_F16 = 64 };
 #define HERO_MODE_M3 (HERO_M_QKV | HERO_M_ATTN | HERO_M_ATTN_OUT | HERO_M_FC1 | HERO_M_FC2)
 #define HERO_MODE_M2 (HERO_M_QKV | HERO_M_ATTN | HERO_M_ATTN_OUT | HERO_M_FC1)
 #define HERO_MODE_M1 (HERO_M_QKV | HERO_M_FC1)
+#define HERO_MODE_M0 0
 
 typedef struct {
     int32_t arch;       /* hero_arch                                          */
     int32_t d, H, Dh, f; /* hidden width, heads, head width (H*Dh == d), FFN width */
     float eps;          /* LayerNorm epsilon                                  */
     int32_t mask;       /* hero_mask                                          */
-    uint32_t mode_mask; /* HERO_M_* bits; QKV and FC1 must be set (Table 1)   */
+    uint32_t mode_mask; /* HERO_M_* bits                                      */
 } hero_layer_desc;
 
 /* Prepared (folded, column-quantized) parameters, all device pointers.  INT8 weights are
  * [N][K] (K contiguous); *_s are their f32 column scales; biases are f32 and already
- * folded with the output scale where the output is requantized.  A BF16 module takes its
- * weight in *_bf16 ([N][K] bf16, unfolded) and ignores the INT8 fields. */
+ * folded with the output scale where the output is requantized.  A 16-bit module takes its
+ * weight in *_bf16 / *_hp ([N][K] in the layer's 16-bit type -- bf16, or fp16 with HERO_M_F16 --,
+ * unfolded) and ignores the INT8 fields. */
 typedef struct {
     const int8_t* w_qkv; const float* w_qkv_s; const float* b_qkv;          /* [3d][d] */
     const int8_t* w_o;   const float* w_o_s;   const float* b_o;            /* [d][d]  */
     const int8_t* w_1;   const float* w_1_s;   const float* b_1;            /* [f][d]  */
     const int8_t* w_2;   const float* w_2_s;   const float* b_2;            /* [d][f]  */
-    const void* w_o_bf16; const void* w_2_bf16;                             /* BF16 modules */
+    const void* w_o_bf16; const void* w_2_bf16;                             /* 16-bit attention-output / FC2 */
     const float* ln1_g; const float* ln1_b; const float* ln2_g; const float* ln2_b;
     const float* S_o;   /* [d] FWQ scale of X_o  (POST_LN, INT8 attention-output)      */
     const float* S_x2;  /* [d] FWQ scale of X_2  (POST_LN, INT8 FC2)                   */
     const float* S_a;   /* [f] FWQ scale of A = GELU(X_1) (INT8 FC2)                   */
     const float* attn_out_scale; /* [d] S_p S_v / S_attn[j] (INT8 attention-output) or
-                                    1 float S_p S_v (BF16 attention-output)            */
-    float qk_scale;     /* d~ = S_q S_k / sqrt(Dh)  (INT8 attention) or 1/sqrt(Dh) (BF16) */
+                                    1 float S_p S_v (16-bit attention-output)          */
+    float qk_scale;     /* d~ = S_q S_k / sqrt(Dh)  (INT8 attention) or 1/sqrt(Dh) (16-bit) */
     float p_scale;      /* S_p                                                         */
+    const void* w_qkv_hp; const void* w_1_hp;                               /* 16-bit QKV / FC1 */
 } hero_layer_weights;
 
 typedef struct {
     int64_t B, S;            /* sequences and new tokens per sequence; T = B*S rows    */
-    /* POST_LN: TWQ input and output */
+    /* POST_LN: TWQ input (read when the QKV module is INT8) and output (always written) */
     const int8_t* x_q; const float* x_scale;     /* [T,d] int8, [T] f32               */
     int8_t* out_q;     float* out_scale;         /* [T,d] int8, [T] f32               */
-    /* PRE_LN: BF16 residual stream, updated IN PLACE */
-    void* h;                                     /* [T,d] bf16                        */
+    /* PRE_LN: 16-bit residual stream, updated IN PLACE */
+    void* h;                                     /* [T,d] bf16 (fp16 with HERO_M_F16)  */
     const int32_t* kv_len;   /* [B] visible keys per sequence INCLUDING this call's S tokens;
                                 NULL = S for every sequence (no cache, no padding)     */
-    /* optional INT8 KV cache [B,H,Smax,Dh] (PRE_LN or POST_LN): this call's K/V codes are
-       written at positions kv_len[b]-S .. kv_len[b]-1 and attention reads the cache.   */
+    /* optional INT8 KV cache [B,H,Smax,Dh] (PRE_LN or POST_LN; INT8 attention only): this call's K/V codes
+       are written at positions kv_len[b]-S .. kv_len[b]-1 and attention reads the cache.   */
     int8_t* k_cache; int8_t* v_cache; int64_t Smax;
+    /* POST_LN with a 16-bit QKV module: the layer input [T,d] in the layer's 16-bit type (x_q / x_scale are then
+       not read).  out_hp (optional, any mode): the 16-bit copy of the layer output, i.e. the x_hp of a successor
+       whose QKV module is 16-bit. */
+    const void* x_hp; void* out_hp;
 } hero_layer_io;
 
 /* Bytes of scratch hero_layer_fwd needs for T = B*S rows of this layer. */
@@ -356,22 +370,30 @@ size_t hero_layer_workspace_bytes(const hero_layer_desc* desc, int64_t B, int64_
  * closing LN^quant on `stream`, with no host synchronisation.  Paper: Sec. 2.2.2, 2.2.3,
  * Sec. 2.3 Table 1.  `workspace` is device scratch of at least
  * hero_layer_workspace_bytes() bytes, 256-byte aligned, owned by the caller; its contents
- * are undefined afterwards.  Supported mode masks: QKV and FC1 set; ATTN_OUT set only if
- * ATTN is set (an INT8 output linear behind a BF16 attention would need the stand-alone
- * quantization kernel the method removes). */
+ * are undefined afterwards.  Supported mode masks: see mode_mask above. */
 hero_status hero_layer_fwd(const hero_layer_desc* desc, const hero_layer_weights* w, const hero_layer_io* io,
                            void* workspace, size_t workspace_bytes, void* stream);
 
-/* BF16 side of a switched module (Sec. 2.3, Table 1): C = act(A Wt^T + bias) (+ residual).
- * A [M,K] bf16 (lda), Wt [N][K] bf16 (ldb), bias f32[N] or NULL, residual [M,N] bf16 or
- * NULL (ldr; C may alias it), gelu != 0 applies erf-GELU before the residual, C [M,N] bf16
- * (ldc).  fp32 accumulation.  Constraints: K % 32 == 0; lda, ldb, ldc, ldr multiples of 8. */
+/* 16-bit side of a switched module (Sec. 2.3, Table 1: a module that is not INT8 runs in FP16 / BF16):
+ * C = act(A Wt^T + bias) (+ residual).  dt = HERO_BF16 or HERO_F16 is the type of A [M,K] (lda), Wt [N][K] (ldb),
+ * residual [M,N] or NULL (ldr; C may alias it) and C [M,N] (ldc); bias f32[N] or NULL; gelu != 0 applies erf-GELU
+ * before the residual.  fp32 accumulation on the matrix cores.  Constraints: K % 32 == 0; lda, ldb multiples of 8,
+ * ldc, ldr of 4; base pointers 16-byte aligned.  hero_bf16_gemm is hero_hp_gemm with dt = HERO_BF16. */
+hero_status hero_hp_gemm(const void* A, int64_t lda, const void* Wt, int64_t ldb,
+                         const float* bias, const void* residual, int64_t ldr, int gelu,
+                         void* C, int64_t ldc, int64_t M, int64_t N, int64_t K, hero_dtype dt, void* stream);
 hero_status hero_bf16_gemm(const void* A, int64_t lda, const void* Wt, int64_t ldb,
                            const float* bias, const void* residual, int64_t ldr, int gelu,
                            void* C, int64_t ldc, int64_t M, int64_t N, int64_t K, void* stream);
 
-/* BF16 attention core softmax(q k^T * scale) v with the same operand description and mask
- * rules as hero_int8_attn (strides multiples of 8 elements); out [B*Sq, H*Dh] bf16. */
+/* 16-bit attention core softmax(q k^T * scale) v with the same operand description and mask rules as
+ * hero_int8_attn (strides multiples of 8 elements); q, k, v and out [B*Sq, H*Dh] in dt (HERO_BF16 / HERO_F16).
+ * hero_bf16_attn is hero_hp_attn with dt = HERO_BF16. */
+hero_status hero_hp_attn(const void* q, const int64_t q_strides[4],
+                         const void* k, const int64_t k_strides[4],
+                         const void* v, const int64_t v_strides[4],
+                         int64_t B, int64_t H, int64_t Sq, int64_t Skv, int64_t Dh, float scale,
+                         hero_mask mask, const int32_t* kv_len, void* out, int64_t ldo, hero_dtype dt, void* stream);
 hero_status hero_bf16_attn(const void* q, const int64_t q_strides[4],
                            const void* k, const int64_t k_strides[4],
                            const void* v, const int64_t v_strides[4],

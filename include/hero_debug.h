@@ -33,11 +33,11 @@ hero_status hero_fp8_gemm_tile(const void* A, int64_t lda, const float* a_row_sc
                                void* C, hero_dtype c_dt, int64_t ldc,
                                int64_t M, int64_t N, int64_t K, void* stream, int tile);
 
-/* The BF16 side of a switched module (Sec. 2.3, Table 1).  tile: 0 = the plain 128x128 kernel, 7 / 8 = the
- * persistent 256x256 / 128x128 kernel. */
-hero_status hero_bf16_gemm_tile(const void* A, int64_t lda, const void* Wt, int64_t ldb,
-                                const float* bias, const void* residual, int64_t ldr, int gelu,
-                                void* C, int64_t ldc, int64_t M, int64_t N, int64_t K, void* stream, int tile);
+/* The 16-bit side of a switched module (Sec. 2.3, Table 1; hero_hp_gemm).  tile: 0 = the plain 128x128 kernel,
+ * 7 / 8 = the persistent 256x256 / 128x128 kernel. */
+hero_status hero_hp_gemm_tile(const void* A, int64_t lda, const void* Wt, int64_t ldb,
+                              const float* bias, const void* residual, int64_t ldr, int gelu,
+                              void* C, int64_t ldc, int64_t M, int64_t N, int64_t K, hero_dtype dt, void* stream, int tile);
 
 #ifdef __cplusplus
 }

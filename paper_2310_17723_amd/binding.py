@@ -11,10 +11,11 @@ I8, U8, I32, F16, BF16, F32 = range(6)
 EPI_RAW_I32, EPI_DEQUANT, EPI_DEQUANT_GELU, EPI_REQUANT, EPI_GELU_REQUANT = range(5)
 MASK_NONE, MASK_PADDING, MASK_CAUSAL = range(3)
 ARCH_POST_LN, ARCH_PRE_LN = 0, 1
-M_QKV, M_ATTN, M_ATTN_OUT, M_FC1, M_FC2, M_FP8 = 1, 2, 4, 8, 16, 32
+M_QKV, M_ATTN, M_ATTN_OUT, M_FC1, M_FC2, M_FP8, M_F16 = 1, 2, 4, 8, 16, 32, 64
 MODE_M3 = M_QKV | M_ATTN | M_ATTN_OUT | M_FC1 | M_FC2
 MODE_M2 = M_QKV | M_ATTN | M_ATTN_OUT | M_FC1
 MODE_M1 = M_QKV | M_FC1
+MODE_M0 = 0
 
 F8E4M3 = 6
 _DT = {torch.int8: I8, torch.uint8: U8, torch.int32: I32, torch.float16: F16, torch.bfloat16: BF16,
@@ -32,12 +33,12 @@ class LayerWeights(C.Structure):
     _fields_ = [(n, vp) for n in (
         "w_qkv", "w_qkv_s", "b_qkv", "w_o", "w_o_s", "b_o", "w_1", "w_1_s", "b_1", "w_2", "w_2_s", "b_2",
         "w_o_bf16", "w_2_bf16", "ln1_g", "ln1_b", "ln2_g", "ln2_b", "S_o", "S_x2", "S_a", "attn_out_scale")] + \
-        [("qk_scale", C.c_float), ("p_scale", C.c_float)]
+        [("qk_scale", C.c_float), ("p_scale", C.c_float), ("w_qkv_hp", vp), ("w_1_hp", vp)]
 
 
 class LayerIO(C.Structure):
     _fields_ = [("B", i64), ("S", i64), ("x_q", vp), ("x_scale", vp), ("out_q", vp), ("out_scale", vp),
-                ("h", vp), ("kv_len", vp), ("k_cache", vp), ("v_cache", vp), ("Smax", i64)]
+                ("h", vp), ("kv_len", vp), ("k_cache", vp), ("v_cache", vp), ("Smax", i64), ("x_hp", vp), ("out_hp", vp)]
 
 
 SYMBOLS = {
@@ -56,7 +57,10 @@ SYMBOLS = {
                                 vp, C.c_size_t, vp]),
     "hero_int8_gemm_tile": (i32, [vp, i64, vp, vp, i64, vp, vp, vp, i32, i64, i32, vp, vp, i32, i64, i64, i64, i64, vp, i32]),
     "hero_fp8_gemm_tile": (i32, [vp, i64, vp, vp, i64, vp, vp, vp, i32, i64, i32, vp, vp, i32, i64, i64, i64, i64, vp, i32]),
-    "hero_bf16_gemm_tile": (i32, [vp, i64, vp, i64, vp, vp, i64, i32, vp, i64, i64, i64, i64, vp, i32]),
+    "hero_hp_gemm_tile": (i32, [vp, i64, vp, i64, vp, vp, i64, i32, vp, i64, i64, i64, i64, i32, vp, i32]),
+    "hero_hp_gemm": (i32, [vp, i64, vp, i64, vp, vp, i64, i32, vp, i64, i64, i64, i64, i32, vp]),
+    "hero_hp_attn": (i32, [vp, C.POINTER(i64), vp, C.POINTER(i64), vp, C.POINTER(i64), i64, i64, i64, i64, i64,
+                           f32, i32, vp, vp, i64, i32, vp]),
     "hero_int8_gemm_static": (i32, [vp, i64, vp, vp, i64, vp, vp, vp, i32, i64, i32, vp, vp, i32, i64, i64, i64, i64, vp]),
     "hero_int8_attn": (i32, [vp, C.POINTER(i64), vp, C.POINTER(i64), vp, C.POINTER(i64), i64, i64, i64, i64, i64,
                              f32, f32, vp, i32, i32, vp, vp, i32, i64, vp]),
@@ -270,17 +274,45 @@ class Hero:
         return out
 
     # ------------------------------------------------------------------ BF16 side
+    def hero_hp_gemm(self, A, Wt, bias=None, residual=None, gelu=False, C_out=None, stream=None, tile=None):
+        """The 16-bit side of a switched module: A, Wt (and residual) bf16 or fp16 tensors of ONE type, which is
+        also the result's."""
+        M, K = A.shape
+        N = Wt.shape[0]
+        assert A.dtype == Wt.dtype and A.dtype in (torch.bfloat16, torch.float16)
+        if C_out is None:
+            C_out = torch.empty((M, N), dtype=A.dtype, device=A.device)
+        args = (_ptr(A), A.stride(0), _ptr(Wt), Wt.stride(0), _ptr(bias), _ptr(residual),
+                residual.stride(0) if residual is not None else 0, int(bool(gelu)),
+                _ptr(C_out), C_out.stride(0), M, N, K, _DT[A.dtype], _stream(stream))
+        st = self.lib.hero_hp_gemm(*args) if tile is None else self.lib.hero_hp_gemm_tile(*args, int(tile))
+        self._check(st)
+        return C_out
+
     def hero_bf16_gemm(self, A, Wt, bias=None, residual=None, gelu=False, C_out=None, stream=None, tile=None):
+        if tile is not None:
+            return self.hero_hp_gemm(A, Wt, bias, residual, gelu, C_out, stream, tile)
         M, K = A.shape
         N = Wt.shape[0]
         if C_out is None:
             C_out = torch.empty((M, N), dtype=torch.bfloat16, device=A.device)
-        args = (_ptr(A), A.stride(0), _ptr(Wt), Wt.stride(0), _ptr(bias), _ptr(residual),
-                residual.stride(0) if residual is not None else 0, int(bool(gelu)),
-                _ptr(C_out), C_out.stride(0), M, N, K, _stream(stream))
-        st = self.lib.hero_bf16_gemm(*args) if tile is None else self.lib.hero_bf16_gemm_tile(*args, int(tile))
+        st = self.lib.hero_bf16_gemm(_ptr(A), A.stride(0), _ptr(Wt), Wt.stride(0), _ptr(bias), _ptr(residual),
+                                     residual.stride(0) if residual is not None else 0, int(bool(gelu)),
+                                     _ptr(C_out), C_out.stride(0), M, N, K, _stream(stream))
         self._check(st)
         return C_out
+
+    def hero_hp_attn(self, q, k, v, scale, mask=MASK_NONE, kv_len=None, out=None, stream=None):
+        B, Sq, H, Dh = q.shape
+        Skv = k.shape[1]
+        assert q.dtype in (torch.bfloat16, torch.float16) and k.dtype == q.dtype and v.dtype == q.dtype
+        if out is None:
+            out = torch.empty((B * Sq, H * Dh), dtype=q.dtype, device=q.device)
+        st = self.lib.hero_hp_attn(_ptr(q), _strides4(q), _ptr(k), _strides4(k), _ptr(v), _strides4(v),
+                                   B, H, Sq, Skv, Dh, float(scale), int(mask), _ptr(kv_len), _ptr(out),
+                                   out.stride(0), _DT[q.dtype], _stream(stream))
+        self._check(st)
+        return out
 
     def hero_bf16_attn(self, q, k, v, scale, mask=MASK_NONE, kv_len=None, out=None, stream=None):
         B, Sq, H, Dh = q.shape
@@ -313,10 +345,10 @@ class Hero:
         return int(self.lib.hero_layer_workspace_bytes(C.byref(desc), B, S))
 
     def hero_layer_fwd(self, desc, weights, B, S, workspace, *, x_q=None, x_scale=None, out_q=None, out_scale=None,
-                       h=None, kv_len=None, k_cache=None, v_cache=None, stream=None):
-        io = LayerIO(B, S, *(None if t is None else t.data_ptr() for t in (x_q, x_scale, out_q, out_scale, h, kv_len,
-                                                                            k_cache, v_cache)),
-                     k_cache.shape[2] if k_cache is not None else 0)
+                       h=None, kv_len=None, k_cache=None, v_cache=None, x_hp=None, out_hp=None, stream=None):
+        ptr = lambda t: None if t is None else t.data_ptr()
+        io = LayerIO(B, S, *(ptr(t) for t in (x_q, x_scale, out_q, out_scale, h, kv_len, k_cache, v_cache)),
+                     k_cache.shape[2] if k_cache is not None else 0, ptr(x_hp), ptr(out_hp))
         st = self.lib.hero_layer_fwd(C.byref(desc), C.byref(weights), C.byref(io), _ptr(workspace),
                                      workspace.numel() * workspace.element_size(), _stream(stream))
         self._check(st)

@@ -1,15 +1,22 @@
-// BF16 side of a switched module (paper Sec. 2.3, Table 1: a module marked with a cross runs
-// in FP16/BF16): hero_bf16_gemm and hero_bf16_attn.  bf16 operands, fp32 accumulation on the
-// matrix cores (v_mfma_f32_32x32x16_bf16), bf16 results.  These kernels make the mixed modes
-// M1 / M2 functional; they follow the same operand layouts as the INT8 kernels (both operands
-// K-contiguous, weight fragment first so a lane owns one output row) but are not tuned further.
+// 16-bit side of a switched module (paper Sec. 2.3, Table 1: a module marked with a cross runs
+// in FP16 / BF16): hero_hp_gemm and hero_hp_attn (and their BF16-only names hero_bf16_gemm / hero_bf16_attn).
+// bf16 or fp16 operands, fp32 accumulation on the matrix cores (v_mfma_f32_32x32x16_bf16 / _f16), results in
+// the operands' type.  These kernels make the mixed modes functional; they follow the same operand layouts as
+// the INT8 kernels (both operands K-contiguous, weight fragment first so a lane owns one output row); large
+// GEMMs go to the persistent kernels of int8_gemm.hip.
 #include "hero_common.h"
 
 namespace {
 
 typedef __bf16 v8b __attribute__((ext_vector_type(8)));
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 
-__device__ __forceinline__ v8b as_bf16x8(v4i w) { return __builtin_bit_cast(v8b, w); }
+// one 32x32x16 matrix instruction on 8 + 8 16-bit values per lane; DT = HERO_BF16 or HERO_F16
+template <int DT>
+__device__ __forceinline__ v16f mfma_hp(v4i a, v4i b, v16f c) {
+    if constexpr (DT == HERO_BF16) return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8b, a), __builtin_bit_cast(v8b, b), c, 0, 0, 0);
+    else return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, a), __builtin_bit_cast(v8h, b), c, 0, 0, 0);
+}
 
 // ------------------------------------------------------------------------------------------
 // GEMM: C = act(A Wt^T + bias) (+ residual).  128x128 tile, 4 waves of 64x64, slabs of 32
@@ -24,6 +31,7 @@ struct BGemmArgs {
     uint16_t* C; int64_t ldc; int M, N, K;
 };
 
+template <int DT>
 __global__ __launch_bounds__(256) void bf16_gemm_kernel(BGemmArgs g) {
     constexpr int BM = 128, BN = 128, TM = 2, TN = 2, NT = 256, CPR = GBK / 16;
     constexpr int UNITS = BM * CPR / NT;
@@ -82,7 +90,7 @@ __global__ __launch_bounds__(256) void bf16_gemm_kernel(BGemmArgs g) {
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(fb[j]), as_bf16x8(fa[i]), acc[i][j], 0, 0, 0);
+                    acc[i][j] = mfma_hp<DT>(fb[j], fa[i], acc[i][j]);
         }
         store(buf ^ 1);                       // slab kt + 1 (a redundant copy of the last slab at the end)
         load(min(kt + 2, last));
@@ -105,8 +113,8 @@ __global__ __launch_bounds__(256) void bf16_gemm_kernel(BGemmArgs g) {
                     const int nn = min(n + t, g.N - 1);
                     float y = acc[i][j][4 * gq + t] + (g.bias ? g.bias[nn] : 0.0f);
                     if (g.gelu) y = gelu_erf(y);
-                    if (g.residual && n + t < g.N) y += bf16_bits_to_f32(g.residual[(int64_t)m * g.ldr + n + t]);
-                    h[t] = f32_to_bf16_bits(y);
+                    if (g.residual && n + t < g.N) y += hp_to_f32<DT>(g.residual[(int64_t)m * g.ldr + n + t]);
+                    h[t] = f32_to_hp<DT>(y);
                 }
                 uint16_t* cp = g.C + (int64_t)m * g.ldc + n;
                 if (n + 3 < g.N) {
@@ -134,7 +142,7 @@ struct BAttnArgs {
     uint16_t* out; int64_t ldo;
 };
 
-template <int DH>
+template <int DH, int DT>
 __global__ __launch_bounds__(256) void bf16_attn_kernel(BAttnArgs a) {
     constexpr int KLD = DH * 2 + 16;       // sK row stride, bytes
     constexpr int VLD = ABKV * 2 + 16;     // sVt row stride, bytes (64 keys of bf16)
@@ -196,7 +204,7 @@ __global__ __launch_bounds__(256) void bf16_attn_kernel(BAttnArgs a) {
 #pragma unroll
             for (int d = 0; d < DS; ++d) {
                 v4i kf = *reinterpret_cast<const v4i*>(&sK[(s * 32 + ql) * KLD + d * 32 + hh * 16]);
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kf), as_bf16x8(qf[d]), acc, 0, 0, 0);
+                acc = mfma_hp<DT>(kf, qf[d], acc);
             }
             float tmax = -INFINITY;
 #pragma unroll
@@ -214,8 +222,8 @@ __global__ __launch_bounds__(256) void bf16_attn_kernel(BAttnArgs a) {
 #pragma unroll
                 for (int r = 0; r < 16; r += 2) {
                     const float e0 = __builtin_amdgcn_exp2f(acc[r] - mn), e1 = __builtin_amdgcn_exp2f(acc[r + 1] - mn);
-                    const uint32_t pk = f32x2_to_bf16x2(e0, e1);
-                    sum += __uint_as_float(pk << 16) + __uint_as_float(pk & 0xffff0000u);   // the sum of what PV really multiplies
+                    const uint32_t pk = pack2_hp<DT>(e0, e1);
+                    sum += hp_to_f32<DT>(pk & 0xffffu) + hp_to_f32<DT>(pk >> 16);           // the sum of what PV really multiplies
                     pb[r >> 1] = pk;
                 }
                 l = fmaf(l, resc, sum);
@@ -235,7 +243,7 @@ __global__ __launch_bounds__(256) void bf16_attn_kernel(BAttnArgs a) {
 #pragma unroll
                 for (int c = 0; c < CT; ++c) {
                     v4i vf = *reinterpret_cast<const v4i*>(&sVt[(c * 32 + ql) * VLD + (s * 32 + st * 16 + hh * 8) * 2]);
-                    o[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(vf), as_bf16x8(pf), o[c], 0, 0, 0);
+                    o[c] = mfma_hp<DT>(vf, pf, o[c]);
                 }
             }
         }
@@ -249,8 +257,8 @@ __global__ __launch_bounds__(256) void bf16_attn_kernel(BAttnArgs a) {
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
             const int e0 = c * 32 + g * 8 + hh * 4;
-            v2i w = {(int)f32x2_to_bf16x2(o[c][4 * g] * inv_l, o[c][4 * g + 1] * inv_l),
-                     (int)f32x2_to_bf16x2(o[c][4 * g + 2] * inv_l, o[c][4 * g + 3] * inv_l)};
+            v2i w = {(int)pack2_hp<DT>(o[c][4 * g] * inv_l, o[c][4 * g + 1] * inv_l),
+                     (int)pack2_hp<DT>(o[c][4 * g + 2] * inv_l, o[c][4 * g + 3] * inv_l)};
             *reinterpret_cast<v2i*>(a.out + orow + e0) = w;
         }
 }
@@ -262,17 +270,18 @@ __global__ void zero_bf16_kernel(uint16_t* out, int64_t rows, int64_t cols, int6
 
 }  // namespace
 
-static hero_status run_bf16_gemm(const void* A, int64_t lda, const void* Wt, int64_t ldb,
-                                 const float* bias, const void* residual, int64_t ldr, int gelu,
-                                 void* C, int64_t ldc, int64_t M, int64_t N, int64_t K, void* stream, int tile) {
+static hero_status run_hp_gemm(const void* A, int64_t lda, const void* Wt, int64_t ldb,
+                               const float* bias, const void* residual, int64_t ldr, int gelu,
+                               void* C, int64_t ldc, int64_t M, int64_t N, int64_t K, hero_dtype dt, void* stream, int tile) {
+    if (dt != HERO_BF16 && dt != HERO_F16) return HERO_ERR_UNSUPPORTED;
     if (M < 0 || N < 0 || K <= 0 || M > 0x7fffffffLL || N > 0x7fffffffLL || K > 0x3fffffffLL) return HERO_ERR_SHAPE;
     if (K % 32 != 0) return HERO_ERR_UNSUPPORTED;
     if (lda < K || ldb < K || ldc < N || (residual && ldr < N)) return HERO_ERR_SHAPE;
     if (M == 0 || N == 0) return HERO_OK;
     if (!A || !Wt || !C) return HERO_ERR_NULL;
     if (lda % 8 || ldb % 8 || ldc % 4 || !hero_aligned16(A) || !hero_aligned16(Wt) || !hero_aligned16(C)) return HERO_ERR_ALIGN;
-    if (!residual || (ldr % 8 == 0 && hero_aligned16(residual))) {        // large problems: the persistent 256x256 kernel
-        const hero_status big = hero_bf16_gemm_large(A, lda, Wt, ldb, bias, residual, ldr, gelu, C, ldc, M, N, K, (hipStream_t)stream, tile);
+    if (!residual || (ldr % 8 == 0 && hero_aligned16(residual))) {        // large problems: the persistent kernels
+        const hero_status big = hero_hp_gemm_large(A, lda, Wt, ldb, bias, residual, ldr, gelu, C, ldc, M, N, K, dt, (hipStream_t)stream, tile);
         if (big != HERO_ERR_UNSUPPORTED) return big;
     }
     if ((M + 127) / 128 > 65535) return HERO_ERR_UNSUPPORTED;
@@ -281,22 +290,29 @@ static hero_status run_bf16_gemm(const void* A, int64_t lda, const void* Wt, int
     g.residual = (const uint16_t*)residual; g.ldr = ldr; g.gelu = gelu; g.C = (uint16_t*)C; g.ldc = ldc;
     g.M = (int)M; g.N = (int)N; g.K = (int)K;
     dim3 grid((unsigned)((N + 127) / 128), (unsigned)((M + 127) / 128));
-    hipLaunchKernelGGL(bf16_gemm_kernel, grid, dim3(256), 0, (hipStream_t)stream, g);
+    if (dt == HERO_BF16) hipLaunchKernelGGL(bf16_gemm_kernel<HERO_BF16>, grid, dim3(256), 0, (hipStream_t)stream, g);
+    else hipLaunchKernelGGL(bf16_gemm_kernel<HERO_F16>, grid, dim3(256), 0, (hipStream_t)stream, g);
     return hero_launch_status();
+}
+
+extern "C" hero_status hero_hp_gemm(const void* A, int64_t lda, const void* Wt, int64_t ldb,
+                                    const float* bias, const void* residual, int64_t ldr, int gelu,
+                                    void* C, int64_t ldc, int64_t M, int64_t N, int64_t K, hero_dtype dt, void* stream) {
+    return run_hp_gemm(A, lda, Wt, ldb, bias, residual, ldr, gelu, C, ldc, M, N, K, dt, stream, -1);
 }
 
 extern "C" hero_status hero_bf16_gemm(const void* A, int64_t lda, const void* Wt, int64_t ldb,
                                       const float* bias, const void* residual, int64_t ldr, int gelu,
                                       void* C, int64_t ldc, int64_t M, int64_t N, int64_t K, void* stream) {
-    return run_bf16_gemm(A, lda, Wt, ldb, bias, residual, ldr, gelu, C, ldc, M, N, K, stream, -1);
+    return run_hp_gemm(A, lda, Wt, ldb, bias, residual, ldr, gelu, C, ldc, M, N, K, HERO_BF16, stream, -1);
 }
 
 // Test and tuning hook (include/hero_debug.h): tile 7 / 8 = the persistent 256x256 / 128x128 kernel, 0 = the plain one.
-extern "C" hero_status hero_bf16_gemm_tile(const void* A, int64_t lda, const void* Wt, int64_t ldb,
-                                           const float* bias, const void* residual, int64_t ldr, int gelu,
-                                           void* C, int64_t ldc, int64_t M, int64_t N, int64_t K, void* stream, int tile) {
+extern "C" hero_status hero_hp_gemm_tile(const void* A, int64_t lda, const void* Wt, int64_t ldb,
+                                         const float* bias, const void* residual, int64_t ldr, int gelu,
+                                         void* C, int64_t ldc, int64_t M, int64_t N, int64_t K, hero_dtype dt, void* stream, int tile) {
     if (tile != 0 && tile != 7 && tile != 8) return HERO_ERR_UNSUPPORTED;
-    return run_bf16_gemm(A, lda, Wt, ldb, bias, residual, ldr, gelu, C, ldc, M, N, K, stream, tile);
+    return run_hp_gemm(A, lda, Wt, ldb, bias, residual, ldr, gelu, C, ldc, M, N, K, dt, stream, tile);
 }
 
 extern "C" hero_status hero_bf16_attn(const void* q, const int64_t q_strides[4],
@@ -304,6 +320,15 @@ extern "C" hero_status hero_bf16_attn(const void* q, const int64_t q_strides[4],
                                       const void* v, const int64_t v_strides[4],
                                       int64_t B, int64_t H, int64_t Sq, int64_t Skv, int64_t Dh, float scale,
                                       hero_mask mask, const int32_t* kv_len, void* out, int64_t ldo, void* stream) {
+    return hero_hp_attn(q, q_strides, k, k_strides, v, v_strides, B, H, Sq, Skv, Dh, scale, mask, kv_len, out, ldo, HERO_BF16, stream);
+}
+
+extern "C" hero_status hero_hp_attn(const void* q, const int64_t q_strides[4],
+                                    const void* k, const int64_t k_strides[4],
+                                    const void* v, const int64_t v_strides[4],
+                                    int64_t B, int64_t H, int64_t Sq, int64_t Skv, int64_t Dh, float scale,
+                                    hero_mask mask, const int32_t* kv_len, void* out, int64_t ldo, hero_dtype dt, void* stream) {
+    if (dt != HERO_BF16 && dt != HERO_F16) return HERO_ERR_UNSUPPORTED;
     if (B < 0 || H < 0 || Sq < 0 || Skv < 0) return HERO_ERR_SHAPE;
     if (Dh != 64 && Dh != 128) return HERO_ERR_UNSUPPORTED;
     if (mask != HERO_MASK_NONE && mask != HERO_MASK_PADDING && mask != HERO_MASK_CAUSAL) return HERO_ERR_UNSUPPORTED;
@@ -331,7 +356,12 @@ extern "C" hero_status hero_bf16_attn(const void* q, const int64_t q_strides[4],
     a.B = (int)B; a.H = (int)H; a.Sq = (int)Sq; a.Skv = (int)Skv; a.scale = scale; a.mask = (int)mask; a.kv_len = kv_len;
     a.out = (uint16_t*)out; a.ldo = ldo;
     dim3 grid((unsigned)((Sq + ABQ - 1) / ABQ), (unsigned)H, (unsigned)B);
-    if (Dh == 64) hipLaunchKernelGGL(bf16_attn_kernel<64>, grid, dim3(256), 0, st, a);
-    else hipLaunchKernelGGL(bf16_attn_kernel<128>, grid, dim3(256), 0, st, a);
+    if (dt == HERO_BF16) {
+        if (Dh == 64) hipLaunchKernelGGL((bf16_attn_kernel<64, HERO_BF16>), grid, dim3(256), 0, st, a);
+        else hipLaunchKernelGGL((bf16_attn_kernel<128, HERO_BF16>), grid, dim3(256), 0, st, a);
+    } else {
+        if (Dh == 64) hipLaunchKernelGGL((bf16_attn_kernel<64, HERO_F16>), grid, dim3(256), 0, st, a);
+        else hipLaunchKernelGGL((bf16_attn_kernel<128, HERO_F16>), grid, dim3(256), 0, st, a);
+    }
     return hero_launch_status();
 }

@@ -18,10 +18,10 @@ typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 
 static inline bool hero_aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-// library-internal: bf16 operands through the persistent 256x256 GEMM kernel (int8_gemm.hip)
-hero_status hero_bf16_gemm_large(const void* A, int64_t lda, const void* Wt, int64_t ldb,
-                                 const float* bias, const void* residual, int64_t ldr, int gelu,
-                                 void* C, int64_t ldc, int64_t M, int64_t N, int64_t K, hipStream_t st, int tile);
+// library-internal: 16-bit operands (dt = HERO_BF16 / HERO_F16) through the persistent GEMM kernels (int8_gemm.hip)
+hero_status hero_hp_gemm_large(const void* A, int64_t lda, const void* Wt, int64_t ldb,
+                               const float* bias, const void* residual, int64_t ldr, int gelu,
+                               void* C, int64_t ldc, int64_t M, int64_t N, int64_t K, hero_dtype dt, hipStream_t st, int tile);
 
 static inline hero_status hero_launch_status() {
     return hipGetLastError() == hipSuccess ? HERO_OK : HERO_ERR_LAUNCH;

@@ -53,11 +53,14 @@ struct GemmArgs {
 // fragment feeds two v_mfma_f32_32x32x16_fp8_fp8 (its low and its high 8 bytes: any grouping of K is a valid
 // contraction as long as both operands use the same one).
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+typedef _Float16 v8hf __attribute__((ext_vector_type(8)));
 template <int ADT, typename ACC>
 __device__ __forceinline__ ACC mfma_step(v4i a, v4i b, ACC c) {
     if constexpr (ADT == HERO_I8) return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0);
     else if constexpr (ADT == HERO_BF16)
         return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a), __builtin_bit_cast(v8bf, b), c, 0, 0, 0);
+    else if constexpr (ADT == HERO_F16)
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8hf, a), __builtin_bit_cast(v8hf, b), c, 0, 0, 0);
     else {
         const long a0 = (long)(((uint64_t)(uint32_t)a[1] << 32) | (uint32_t)a[0]), a1 = (long)(((uint64_t)(uint32_t)a[3] << 32) | (uint32_t)a[2]);
         const long b0 = (long)(((uint64_t)(uint32_t)b[1] << 32) | (uint32_t)b[0]), b1 = (long)(((uint64_t)(uint32_t)b[3] << 32) | (uint32_t)b[2]);
@@ -614,7 +617,7 @@ __device__ __forceinline__ void dma4s(uint32_t voff, const float* sbase, uint32_
 template <int BM, int BN, int WM, int WN, int NS, int EPI, int CDT, int RDT, int ADT = HERO_I8>
 __global__ __launch_bounds__(WM * WN * 64, 2) void int8_gemm_persistent_kernel(GemmArgs g) {
     using ACC = typename AccOf<ADT>::type;
-    constexpr bool UNIT = ADT == HERO_BF16;
+    constexpr bool UNIT = ADT == HERO_BF16 || ADT == HERO_F16;      // 16-bit operands: no scales, y = acc + bias
     constexpr bool WIDE = ADT == HERO_F8E4M3;
     constexpr int NT = WM * WN * 64, NWAVE = WM * WN;
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
@@ -1379,31 +1382,32 @@ hero_status launch_epi(const GemmArgs& g, void* ws, size_t ws_bytes, hipStream_t
 
 }  // namespace
 
-// bf16 operands through the persistent kernels (called by hero_bf16_gemm for large problems;
-// HERO_ERR_UNSUPPORTED means "not this kernel's case", the caller then uses its own).  The tile is chosen as for
-// INT8 operands; tile = 7 / 8 / 0 (from the test entry point hero_bf16_gemm_tile) forces the 256x256 / 128x128 form / the caller's kernel, -1 chooses.
+// 16-bit operands (bf16 or fp16: the 16-bit side of a switched module) through the persistent kernels (called by
+// hero_hp_gemm for large problems; HERO_ERR_UNSUPPORTED means "not this kernel's case", the caller then uses its
+// own).  The tile is chosen as for INT8 operands; tile = 7 / 8 / 0 (from the test entry point hero_hp_gemm_tile)
+// forces the 256x256 / 128x128 form / the caller's kernel, -1 chooses.
 namespace {
-template <int BM, int BN, int WM, int WN>
-hero_status launch_bf16_persistent(GemmArgs g, int wg_per_cu, bool gelu, hipStream_t st) {
+template <int BM, int BN, int WM, int WN, int DT>
+hero_status launch_hp_persistent(GemmArgs g, int wg_per_cu, bool gelu, hipStream_t st) {
     g.ntm = (g.M + BM - 1) / BM; g.ntn = (g.N + BN - 1) / BN;
     const int64_t tiles = (int64_t)g.ntm * g.ntn;
     g.per_xcd = (int)((tiles + NUM_XCD - 1) / NUM_XCD);
     const int cap = 32 * wg_per_cu, nslot = g.per_xcd < cap ? g.per_xcd : cap;
     const dim3 grid((unsigned)(nslot * NUM_XCD)), block(WM * WN * 64);
     if (gelu) {
-        if (g.residual) hipLaunchKernelGGL((int8_gemm_persistent_kernel<BM, BN, WM, WN, 4, HERO_EPI_DEQUANT_GELU, HERO_BF16, HERO_BF16, HERO_BF16>), grid, block, 0, st, g);
-        else hipLaunchKernelGGL((int8_gemm_persistent_kernel<BM, BN, WM, WN, 4, HERO_EPI_DEQUANT_GELU, HERO_BF16, -1, HERO_BF16>), grid, block, 0, st, g);
+        if (g.residual) hipLaunchKernelGGL((int8_gemm_persistent_kernel<BM, BN, WM, WN, 4, HERO_EPI_DEQUANT_GELU, DT, DT, DT>), grid, block, 0, st, g);
+        else hipLaunchKernelGGL((int8_gemm_persistent_kernel<BM, BN, WM, WN, 4, HERO_EPI_DEQUANT_GELU, DT, -1, DT>), grid, block, 0, st, g);
     } else {
-        if (g.residual) hipLaunchKernelGGL((int8_gemm_persistent_kernel<BM, BN, WM, WN, 4, HERO_EPI_DEQUANT, HERO_BF16, HERO_BF16, HERO_BF16>), grid, block, 0, st, g);
-        else hipLaunchKernelGGL((int8_gemm_persistent_kernel<BM, BN, WM, WN, 4, HERO_EPI_DEQUANT, HERO_BF16, -1, HERO_BF16>), grid, block, 0, st, g);
+        if (g.residual) hipLaunchKernelGGL((int8_gemm_persistent_kernel<BM, BN, WM, WN, 4, HERO_EPI_DEQUANT, DT, DT, DT>), grid, block, 0, st, g);
+        else hipLaunchKernelGGL((int8_gemm_persistent_kernel<BM, BN, WM, WN, 4, HERO_EPI_DEQUANT, DT, -1, DT>), grid, block, 0, st, g);
     }
     return hero_launch_status();
 }
 }  // namespace
 
-hero_status hero_bf16_gemm_large(const void* A, int64_t lda, const void* Wt, int64_t ldb,
-                                 const float* bias, const void* residual, int64_t ldr, int gelu,
-                                 void* C, int64_t ldc, int64_t M, int64_t N, int64_t K, hipStream_t st, int tile) {
+hero_status hero_hp_gemm_large(const void* A, int64_t lda, const void* Wt, int64_t ldb,
+                               const float* bias, const void* residual, int64_t ldr, int gelu,
+                               void* C, int64_t ldc, int64_t M, int64_t N, int64_t K, hero_dtype dt, hipStream_t st, int tile) {
     const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256), t128 = ((M + 127) / 128) * ((N + 127) / 128);
     if (t128 < 192 || t128 > 0x7fffff00LL || K % 64 != 0 || K * 2 < 4 * BK || lda * 2 >= (1 << 24) || ldb * 2 >= (1 << 24))
         return HERO_ERR_UNSUPPORTED;
@@ -1414,8 +1418,12 @@ hero_status hero_bf16_gemm_large(const void* A, int64_t lda, const void* Wt, int
     g.ksplit = 1; g.kslabs = 0;
     const int cfg = tile >= 0 ? tile : ((t256 < 160 || (t256 > 256 && t256 < 384)) ? 8 : 7);
     if (cfg == 0) return HERO_ERR_UNSUPPORTED;
-    if (cfg == 8) return launch_bf16_persistent<128, 128, 2, 2>(g, 2, gelu != 0, st);
-    return launch_bf16_persistent<256, 256, 2, 4>(g, 1, gelu != 0, st);
+    if (dt == HERO_BF16) {
+        if (cfg == 8) return launch_hp_persistent<128, 128, 2, 2, HERO_BF16>(g, 2, gelu != 0, st);
+        return launch_hp_persistent<256, 256, 2, 4, HERO_BF16>(g, 1, gelu != 0, st);
+    }
+    if (cfg == 8) return launch_hp_persistent<128, 128, 2, 2, HERO_F16>(g, 2, gelu != 0, st);
+    return launch_hp_persistent<256, 256, 2, 4, HERO_F16>(g, 1, gelu != 0, st);
 }
 
 // The FP8 variant: the same kernels with E4M3 operands (no split-K: fp32 partial sums would not commute).

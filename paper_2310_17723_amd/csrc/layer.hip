@@ -5,8 +5,11 @@
 //
 // POST_LN (BERT):  X_in,int8 S_in -> QKV -> attention -> W_o -> LN^quant(X_in, X_o)
 //                  -> FC1 + GELU^quant -> FC2 -> LN^quant(X_mid, X_2) -> X_out,int8 S_out
-// PRE_LN (GPT):    h (bf16) -> LN^quant -> QKV -> attention -> W_o (+h) -> LN^quant
+// PRE_LN (GPT):    h (16-bit) -> LN^quant -> QKV -> attention -> W_o (+h) -> LN^quant
 //                  -> FC1 + GELU^quant -> FC2 (+h); h is updated in place.
+// Every module is INT8 or 16-bit (bf16, or fp16 with HERO_M_F16) as its mode bit says; a tensor between two
+// modules is INT8 codes when its consumer is INT8 and 16-bit values otherwise (LN^quant writes its 16-bit copy
+// beside the codes when the next linear is 16-bit).
 #include "hero_common.h"
 #include <algorithm>
 
@@ -15,7 +18,7 @@ namespace {
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct Workspace {
-    size_t xin_q, xin_s, qkv, attn, xo, mid_q, mid_s, a, x2, gemm_ws, gemm_ws_bytes, total;
+    size_t xin_q, xin_s, xin_hp, qkv, attn, xo, mid_q, mid_s, mid_hp, a, x2, gemm_ws, gemm_ws_bytes, total;
 };
 
 Workspace plan(const hero_layer_desc* d, int64_t T) {
@@ -28,11 +31,13 @@ Workspace plan(const hero_layer_desc* d, int64_t T) {
     auto take = [&](size_t bytes) { size_t o = off; off += align256(bytes); return o; };
     w.xin_q = take(pre ? (size_t)T * d->d : 0);
     w.xin_s = take(pre ? (size_t)T * 4 : 0);
+    w.xin_hp = take(pre && !(d->mode_mask & HERO_M_QKV) ? (size_t)T * d->d * 2 : 0);   // 16-bit LN output for a 16-bit QKV
     w.qkv = take((size_t)T * 3 * d->d * e_qkv);
     w.attn = take((size_t)T * d->d * e_attn);
     w.xo = take(pre ? 0 : (size_t)T * d->d * e_attn);
     w.mid_q = take((size_t)T * d->d);
     w.mid_s = take((size_t)T * 4);
+    w.mid_hp = take(!(d->mode_mask & HERO_M_FC1) ? (size_t)T * d->d * 2 : 0);          // 16-bit X_mid for a 16-bit FC1
     w.a = take((size_t)T * d->f * e_a);
     w.x2 = take(pre ? 0 : (size_t)T * d->d * e_a);
     // split-K scratch of the skinny (decode) GEMMs: the largest of the four shapes, shared (stream order);
@@ -73,10 +78,13 @@ hero_status check(const hero_layer_desc* d) {
     if (d->arch != HERO_ARCH_POST_LN && d->arch != HERO_ARCH_PRE_LN) return HERO_ERR_UNSUPPORTED;
     if (d->d <= 0 || d->H <= 0 || d->Dh <= 0 || d->f <= 0 || (int64_t)d->H * d->Dh != d->d) return HERO_ERR_SHAPE;
     const uint32_t m = d->mode_mask;
-    if (!(m & HERO_M_QKV) || !(m & HERO_M_FC1)) return HERO_ERR_UNSUPPORTED;
+    // a 16-bit module hands 16-bit values on, and there is no stand-alone quantization kernel (the method removes
+    // it): INT8 attention needs an INT8 QKV, an INT8 output linear an INT8 attention, an INT8 FC2 an INT8 FC1
+    if ((m & HERO_M_ATTN) && !(m & HERO_M_QKV)) return HERO_ERR_UNSUPPORTED;
     if ((m & HERO_M_ATTN_OUT) && !(m & HERO_M_ATTN)) return HERO_ERR_UNSUPPORTED;
-    if (m & ~(uint32_t)(HERO_MODE_M3 | HERO_M_FP8)) return HERO_ERR_UNSUPPORTED;
-    if ((m & HERO_M_FP8) && (m & HERO_MODE_M3) != HERO_MODE_M3) return HERO_ERR_UNSUPPORTED;   // FP8: every module 8-bit
+    if ((m & HERO_M_FC2) && !(m & HERO_M_FC1)) return HERO_ERR_UNSUPPORTED;
+    if (m & ~(uint32_t)(HERO_MODE_M3 | HERO_M_FP8 | HERO_M_F16)) return HERO_ERR_UNSUPPORTED;
+    if ((m & HERO_M_FP8) && (m & (HERO_MODE_M3 | HERO_M_F16)) != HERO_MODE_M3) return HERO_ERR_UNSUPPORTED;   // FP8: every module 8-bit
     return HERO_OK;
 }
 
@@ -115,13 +123,17 @@ extern "C" hero_status hero_layer_fwd(const hero_layer_desc* desc, const hero_la
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < ws.total) return HERO_ERR_WORKSPACE;
     const bool pre = desc->arch == HERO_ARCH_PRE_LN;
     const uint32_t mode = desc->mode_mask;
-    const bool attn_i8 = mode & HERO_M_ATTN, o_i8 = mode & HERO_M_ATTN_OUT, fc2_i8 = mode & HERO_M_FC2;
+    const bool q_i8 = mode & HERO_M_QKV, attn_i8 = mode & HERO_M_ATTN, o_i8 = mode & HERO_M_ATTN_OUT;
+    const bool fc1_i8 = mode & HERO_M_FC1, fc2_i8 = mode & HERO_M_FC2;
+    const hero_dtype HP = (mode & HERO_M_F16) ? HERO_F16 : HERO_BF16;     // the layer's 16-bit type
     const int64_t d = desc->d, f = desc->f, H = desc->H, Dh = desc->Dh;
     const bool cache = io->k_cache || io->v_cache;
     // ---- everything that can be checked is checked before the first launch
-    if (pre ? !io->h : (!io->x_q || !io->x_scale || !io->out_q || !io->out_scale)) return HERO_ERR_NULL;
-    if (!w->w_qkv || !w->w_qkv_s || !w->w_1 || !w->w_1_s || !w->ln1_g || !w->ln2_g || !w->attn_out_scale)
-        return HERO_ERR_NULL;
+    if (pre ? !io->h : (!io->out_q || !io->out_scale || (q_i8 ? (!io->x_q || !io->x_scale) : !io->x_hp))) return HERO_ERR_NULL;
+    if (!w->ln1_g || !w->ln2_g) return HERO_ERR_NULL;
+    if (q_i8 ? (!w->w_qkv || !w->w_qkv_s) : !w->w_qkv_hp) return HERO_ERR_NULL;
+    if (fc1_i8 ? (!w->w_1 || !w->w_1_s) : !w->w_1_hp) return HERO_ERR_NULL;
+    if (attn_i8 && !w->attn_out_scale) return HERO_ERR_NULL;
     if (o_i8 ? (!w->w_o || !w->w_o_s) : !w->w_o_bf16) return HERO_ERR_NULL;
     if (fc2_i8 ? (!w->w_2 || !w->w_2_s || !w->S_a) : !w->w_2_bf16) return HERO_ERR_NULL;
     if (!pre && ((o_i8 && !w->S_o) || (fc2_i8 && !w->S_x2))) return HERO_ERR_NULL;
@@ -137,16 +149,18 @@ extern "C" hero_status hero_layer_fwd(const hero_layer_desc* desc, const hero_la
     // h had been partly updated in place): the GeMM^quant row bound, the LN^quant row width (a row lives in one
     // wavefront's registers: 8192 columns behind INT8 addends, 4096 behind the 16-bit residual stream), alignment
     if (T >= (1LL << 23)) return HERO_ERR_SHAPE;
-    if (d > (pre ? 4096 : 8192)) return HERO_ERR_UNSUPPORTED;
+    if (d > ((pre || !q_i8 || !fc1_i8) ? 4096 : 8192)) return HERO_ERR_UNSUPPORTED;
     {
-        const void* const ptrs[] = {w->w_qkv, w->w_o, w->w_1, w->w_2, w->w_o_bf16, w->w_2_bf16, io->x_q, io->out_q, io->h,
-                                    io->k_cache, io->v_cache};
+        const void* const ptrs[] = {w->w_qkv, w->w_o, w->w_1, w->w_2, w->w_o_bf16, w->w_2_bf16, w->w_qkv_hp, w->w_1_hp,
+                                    io->x_q, io->out_q, io->h, io->k_cache, io->v_cache, io->x_hp, io->out_hp};
         for (const void* p : ptrs) if (!hero_aligned16(p)) return HERO_ERR_ALIGN;
     }
 
     char* base = (char*)workspace;
     int8_t* xin_q = pre ? (int8_t*)(base + ws.xin_q) : const_cast<int8_t*>(io->x_q);
     float* xin_s = pre ? (float*)(base + ws.xin_s) : const_cast<float*>(io->x_scale);
+    void* xin_hp = pre ? (void*)(base + ws.xin_hp) : const_cast<void*>(io->x_hp);    // read only when QKV is 16-bit
+    void* mid_hp = base + ws.mid_hp;
     void* qkv = base + ws.qkv;
     void* attn = base + ws.attn;
     void* xo = base + ws.xo;
@@ -205,14 +219,17 @@ extern "C" hero_status hero_layer_fwd(const hero_layer_desc* desc, const hero_la
         return HERO_OK;
     }
 
-    // (1) PRE_LN: LN^quant of the residual stream
+    // (1) PRE_LN: LN^quant of the residual stream (with its 16-bit copy when the QKV module is 16-bit)
     if (pre)
-        HERO_TRY(hero_ln_quant(io->h, HERO_BF16, nullptr, nullptr, HERO_I8, nullptr, w->ln1_g, w->ln1_b, desc->eps,
-                               T, d, xin_q, xin_s, nullptr, HERO_BF16, stream));
-    // (2) QKV GeMM^quant: SQ codes for an INT8 attention (bare Round), bf16 values otherwise
-    HERO_TRY(hero_int8_gemm_ws(xin_q, d, xin_s, w->w_qkv, d, w->w_qkv_s, w->b_qkv, nullptr, HERO_BF16, 0,
-                            attn_i8 ? HERO_EPI_REQUANT : HERO_EPI_DEQUANT, nullptr,
-                            qkv, attn_i8 ? HERO_I8 : HERO_BF16, 3 * d, T, 3 * d, d, gws, ws.gemm_ws_bytes, stream));
+        HERO_TRY(hero_ln_quant(io->h, HP, nullptr, nullptr, HERO_I8, nullptr, w->ln1_g, w->ln1_b, desc->eps,
+                               T, d, xin_q, xin_s, q_i8 ? nullptr : xin_hp, HP, stream));
+    // (2) QKV: SQ codes for an INT8 attention (bare Round), 16-bit values otherwise
+    if (q_i8)
+        HERO_TRY(hero_int8_gemm_ws(xin_q, d, xin_s, w->w_qkv, d, w->w_qkv_s, w->b_qkv, nullptr, HP, 0,
+                                attn_i8 ? HERO_EPI_REQUANT : HERO_EPI_DEQUANT, nullptr,
+                                qkv, attn_i8 ? HERO_I8 : HP, 3 * d, T, 3 * d, d, gws, ws.gemm_ws_bytes, stream));
+    else
+        HERO_TRY(hero_hp_gemm(xin_hp, d, w->w_qkv_hp, d, w->b_qkv, nullptr, 0, 0, qkv, 3 * d, T, 3 * d, d, HP, stream));
     // (3) attention
     const int64_t qs[4] = {S * 3 * d, 3 * d, Dh, 1};
     if (attn_i8) {
@@ -230,55 +247,56 @@ extern "C" hero_status hero_layer_fwd(const hero_layer_desc* desc, const hero_la
         }
         HERO_TRY(hero_int8_attn(qp, qs, kp, ks, vp, ks, B, H, S, Skv, Dh, w->qk_scale, w->p_scale,
                                 w->attn_out_scale, o_i8 ? 0 : 1, (hero_mask)desc->mask, io->kv_len,
-                                attn, o_i8 ? HERO_I8 : HERO_BF16, d, stream));
+                                attn, o_i8 ? HERO_I8 : HP, d, stream));
     } else {
         const uint16_t* qp = (const uint16_t*)qkv;
-        HERO_TRY(hero_bf16_attn(qp, qs, qp + d, qs, qp + 2 * d, qs, B, H, S, S, Dh, w->qk_scale,
-                                (hero_mask)desc->mask, io->kv_len, attn, d, stream));
+        HERO_TRY(hero_hp_attn(qp, qs, qp + d, qs, qp + 2 * d, qs, B, H, S, S, Dh, w->qk_scale,
+                              (hero_mask)desc->mask, io->kv_len, attn, d, HP, stream));
     }
-    // (4) attention-output linear and the LN^quant that closes the attention module
+    // (4) attention-output linear and the LN^quant that closes the attention module; X_mid also as 16-bit values
+    // when FC1 is 16-bit
+    const void* x1 = q_i8 ? (const void*)xin_q : (const void*)xin_hp;      // the layer input as LN^quant's first addend
+    const hero_dtype x1_dt = q_i8 ? HERO_I8 : HP;
     if (!pre) {
-        if (o_i8) {
-            HERO_TRY(hero_int8_gemm_ws((const int8_t*)attn, d, nullptr, w->w_o, d, w->w_o_s, w->b_o, nullptr, HERO_BF16, 0,
+        if (o_i8)
+            HERO_TRY(hero_int8_gemm_ws((const int8_t*)attn, d, nullptr, w->w_o, d, w->w_o_s, w->b_o, nullptr, HP, 0,
                                     HERO_EPI_REQUANT, nullptr, xo, HERO_I8, d, T, d, d, gws, ws.gemm_ws_bytes, stream));
-            HERO_TRY(hero_ln_quant(xin_q, HERO_I8, xin_s, xo, HERO_I8, w->S_o, w->ln1_g, w->ln1_b, desc->eps, T, d,
-                                   mid_q, mid_s, nullptr, HERO_BF16, stream));
-        } else {
-            HERO_TRY(hero_bf16_gemm(attn, d, w->w_o_bf16, d, w->b_o, nullptr, 0, 0, xo, d, T, d, d, stream));
-            HERO_TRY(hero_ln_quant(xin_q, HERO_I8, xin_s, xo, HERO_BF16, nullptr, w->ln1_g, w->ln1_b, desc->eps, T, d,
-                                   mid_q, mid_s, nullptr, HERO_BF16, stream));
-        }
+        else
+            HERO_TRY(hero_hp_gemm(attn, d, w->w_o_bf16, d, w->b_o, nullptr, 0, 0, xo, d, T, d, d, HP, stream));
+        HERO_TRY(hero_ln_quant(x1, x1_dt, q_i8 ? xin_s : nullptr, xo, o_i8 ? HERO_I8 : HP, o_i8 ? w->S_o : nullptr,
+                               w->ln1_g, w->ln1_b, desc->eps, T, d, mid_q, mid_s, fc1_i8 ? nullptr : mid_hp, HP, stream));
     } else {
         if (o_i8)
-            HERO_TRY(hero_int8_gemm_ws((const int8_t*)attn, d, nullptr, w->w_o, d, w->w_o_s, w->b_o, io->h, HERO_BF16, d,
-                                    HERO_EPI_DEQUANT, nullptr, io->h, HERO_BF16, d, T, d, d, gws, ws.gemm_ws_bytes, stream));
+            HERO_TRY(hero_int8_gemm_ws((const int8_t*)attn, d, nullptr, w->w_o, d, w->w_o_s, w->b_o, io->h, HP, d,
+                                    HERO_EPI_DEQUANT, nullptr, io->h, HP, d, T, d, d, gws, ws.gemm_ws_bytes, stream));
         else
-            HERO_TRY(hero_bf16_gemm(attn, d, w->w_o_bf16, d, w->b_o, io->h, d, 0, io->h, d, T, d, d, stream));
-        HERO_TRY(hero_ln_quant(io->h, HERO_BF16, nullptr, nullptr, HERO_I8, nullptr, w->ln2_g, w->ln2_b, desc->eps,
-                               T, d, mid_q, mid_s, nullptr, HERO_BF16, stream));
+            HERO_TRY(hero_hp_gemm(attn, d, w->w_o_bf16, d, w->b_o, io->h, d, 0, io->h, d, T, d, d, HP, stream));
+        HERO_TRY(hero_ln_quant(io->h, HP, nullptr, nullptr, HERO_I8, nullptr, w->ln2_g, w->ln2_b, desc->eps,
+                               T, d, mid_q, mid_s, fc1_i8 ? nullptr : mid_hp, HP, stream));
     }
-    // (5) FC1 + GELU^quant (X_1 stays in registers)
-    HERO_TRY(hero_int8_gemm_ws(mid_q, d, mid_s, w->w_1, d, w->w_1_s, w->b_1, nullptr, HERO_BF16, 0,
-                            fc2_i8 ? HERO_EPI_GELU_REQUANT : HERO_EPI_DEQUANT_GELU, w->S_a,
-                            act, fc2_i8 ? HERO_I8 : HERO_BF16, f, T, f, d, gws, ws.gemm_ws_bytes, stream));
+    // (5) FC1 + GELU: GELU^quant codes for an INT8 FC2 (X_1 stays in registers), 16-bit values otherwise
+    if (fc1_i8)
+        HERO_TRY(hero_int8_gemm_ws(mid_q, d, mid_s, w->w_1, d, w->w_1_s, w->b_1, nullptr, HP, 0,
+                                fc2_i8 ? HERO_EPI_GELU_REQUANT : HERO_EPI_DEQUANT_GELU, w->S_a,
+                                act, fc2_i8 ? HERO_I8 : HP, f, T, f, d, gws, ws.gemm_ws_bytes, stream));
+    else
+        HERO_TRY(hero_hp_gemm(mid_hp, d, w->w_1_hp, d, w->b_1, nullptr, 0, 1, act, f, T, f, d, HP, stream));
     // (6) FC2 and the closing LN^quant (POST_LN) or residual add (PRE_LN)
     if (!pre) {
-        if (fc2_i8) {
-            HERO_TRY(hero_int8_gemm_ws((const int8_t*)act, f, nullptr, w->w_2, f, w->w_2_s, w->b_2, nullptr, HERO_BF16, 0,
+        if (fc2_i8)
+            HERO_TRY(hero_int8_gemm_ws((const int8_t*)act, f, nullptr, w->w_2, f, w->w_2_s, w->b_2, nullptr, HP, 0,
                                     HERO_EPI_REQUANT, nullptr, x2, HERO_I8, d, T, d, f, gws, ws.gemm_ws_bytes, stream));
-            HERO_TRY(hero_ln_quant(mid_q, HERO_I8, mid_s, x2, HERO_I8, w->S_x2, w->ln2_g, w->ln2_b, desc->eps, T, d,
-                                   io->out_q, io->out_scale, nullptr, HERO_BF16, stream));
-        } else {
-            HERO_TRY(hero_bf16_gemm(act, f, w->w_2_bf16, f, w->b_2, nullptr, 0, 0, x2, d, T, d, f, stream));
-            HERO_TRY(hero_ln_quant(mid_q, HERO_I8, mid_s, x2, HERO_BF16, nullptr, w->ln2_g, w->ln2_b, desc->eps, T, d,
-                                   io->out_q, io->out_scale, nullptr, HERO_BF16, stream));
-        }
+        else
+            HERO_TRY(hero_hp_gemm(act, f, w->w_2_bf16, f, w->b_2, nullptr, 0, 0, x2, d, T, d, f, HP, stream));
+        HERO_TRY(hero_ln_quant(fc1_i8 ? (const void*)mid_q : (const void*)mid_hp, fc1_i8 ? HERO_I8 : HP, fc1_i8 ? mid_s : nullptr,
+                               x2, fc2_i8 ? HERO_I8 : HP, fc2_i8 ? w->S_x2 : nullptr, w->ln2_g, w->ln2_b, desc->eps, T, d,
+                               io->out_q, io->out_scale, io->out_hp, HP, stream));
     } else {
         if (fc2_i8)
-            HERO_TRY(hero_int8_gemm_ws((const int8_t*)act, f, nullptr, w->w_2, f, w->w_2_s, w->b_2, io->h, HERO_BF16, d,
-                                    HERO_EPI_DEQUANT, nullptr, io->h, HERO_BF16, d, T, d, f, gws, ws.gemm_ws_bytes, stream));
+            HERO_TRY(hero_int8_gemm_ws((const int8_t*)act, f, nullptr, w->w_2, f, w->w_2_s, w->b_2, io->h, HP, d,
+                                    HERO_EPI_DEQUANT, nullptr, io->h, HP, d, T, d, f, gws, ws.gemm_ws_bytes, stream));
         else
-            HERO_TRY(hero_bf16_gemm(act, f, w->w_2_bf16, f, w->b_2, io->h, d, 0, io->h, d, T, d, f, stream));
+            HERO_TRY(hero_hp_gemm(act, f, w->w_2_bf16, f, w->b_2, io->h, d, 0, io->h, d, T, d, f, HP, stream));
     }
     return HERO_OK;
 }

@@ -61,7 +61,7 @@ def upload_weights(hero, w):
     mode = w["mode"]
     names = {"w_qkv": "wq_qkv", "w_qkv_s": "s_qkv", "b_qkv": "b_qkv", "w_o": "wq_o", "w_o_s": "s_o_w", "b_o": "b_o",
              "w_1": "wq_1", "w_1_s": "s_1", "b_1": "b_1", "w_2": "wq_2", "w_2_s": "s_2_w", "b_2": "b_2",
-             "w_o_bf16": "wb_o", "w_2_bf16": "wb_2", "ln1_g": "ln1_g", "ln1_b": "ln1_b", "ln2_g": "ln2_g",
+             "w_o_bf16": "wb_o", "w_2_bf16": "wb_2", "w_qkv_hp": "wb_qkv", "w_1_hp": "wb_1", "ln1_g": "ln1_g", "ln1_b": "ln1_b", "ln2_g": "ln2_g",
              "ln2_b": "ln2_b", "S_o": "S_o", "S_x2": "S_x2", "S_a": "S_a"}
     t = {k: dev(w[v]) for k, v in names.items() if v in w}
     t["attn_out_scale"] = dev(w["attn_out_scale"] if mode & HB.M_ATTN_OUT else w["attn_out_scalar"])

@@ -760,38 +760,51 @@ def test_fp8_attn_views_cache_one_query_and_errors(hero):
         hero.hero_fp8_attn(bad[:, :, 0], bad[:, :, 1], bad[:, :, 2], qk_scale, sp, dev(cs[:64]))
 
 
-# ============================================================ BF16 side of a switched module
+# ============================================================ 16-bit side of a switched module (BF16 / FP16)
+@pytest.mark.parametrize("dt", ["bf16", "f16"])
 @pytest.mark.parametrize("M,N,K", [(200, 136, 256), (130, 512, 1024), (64, 72, 96), (2500, 2600, 160), (2560, 2560, 128), (2500, 2600, 192)])
-def test_bf16_gemm_matches_oracle(hero, M, N, K):
-    """The last two shapes have enough tiles for the persistent kernels (ragged edges, 5 / 4 slabs, several tiles
-    per workgroup): the default choice, then the 256 x 256 and the 128 x 128 form forced."""
+def test_hp_gemm_matches_oracle(hero, M, N, K, dt):
+    """hero_hp_gemm (Sec. 2.3: a switched module runs in FP16 / BF16) in both 16-bit types.  The last three shapes
+    have enough tiles for the persistent kernels (ragged edges, 5 / 4 / 6 slabs, several tiles per workgroup): the
+    default choice, then the 256 x 256 and the 128 x 128 form forced."""
+    odt, tdt = (O.BF16, torch.bfloat16) if dt == "bf16" else (O.F16, torch.float16)
+    enc = lambda a: O.f32_to_hp(a.astype(np.float32), odt)
+    dec = lambda u: O.hp_to_f32(u, odt)
     g = synth.rng(1000 + M)
-    A = O.f32_to_bf16(g.standard_normal((M, K)).astype(np.float32))
-    Wt = O.f32_to_bf16((g.standard_normal((N, K)) * 0.05).astype(np.float32))
+    A, Wt = enc(g.standard_normal((M, K))), enc(g.standard_normal((N, K)) * 0.05)
     bias = (0.1 * g.standard_normal(N)).astype(np.float32)
-    res = O.f32_to_bf16(g.standard_normal((M, N)).astype(np.float32))
+    res = enc(g.standard_normal((M, N)))
     big = K % 64 == 0 and -(-M // 128) * -(-N // 128) >= 192
     for gelu, r in ((False, None), (True, None), (False, res), (True, res)):
-        ref = O.bf16_gemm(A, Wt, bias=bias, residual=r, gelu=gelu)
+        ref = O.hp_gemm(A, Wt, bias=bias, residual=r, gelu=gelu, dt=odt)
         for tile in (None, 7, 8) if big else (None,):
-            got = hero.hero_bf16_gemm(dev(A), dev(Wt), dev(bias), residual=dev(r), gelu=gelu, tile=tile)
-            assert rel_err(O.bf16_to_f32(to_np(got)), O.bf16_to_f32(ref)) <= 2e-2, (gelu, r is not None, tile)
+            got = hero.hero_hp_gemm(dev(A, tdt), dev(Wt, tdt), dev(bias), residual=dev(r, tdt), gelu=gelu, tile=tile)
+            assert got.dtype == tdt
+            assert rel_err(dec(to_np(got)), dec(ref)) <= 2e-2, (gelu, r is not None, tile)
+    if dt == "bf16":                                           # the BF16-only name is the same call
+        a = hero.hero_bf16_gemm(dev(A), dev(Wt), dev(bias), residual=dev(res), gelu=True)
+        b = hero.hero_hp_gemm(dev(A), dev(Wt), dev(bias), residual=dev(res), gelu=True)
+        assert torch.equal(a.view(torch.int16), b.view(torch.int16))
 
 
+@pytest.mark.parametrize("dt", ["bf16", "f16"])
 @pytest.mark.parametrize("mask", [O.MASK_NONE, O.MASK_PADDING, O.MASK_CAUSAL])
 @pytest.mark.parametrize("B,S,H,Dh", [(2, 150, 2, 64), (1, 200, 2, 128)])
-def test_bf16_attn_matches_oracle(hero, B, S, H, Dh, mask):
+def test_hp_attn_matches_oracle(hero, B, S, H, Dh, mask, dt):
+    odt, tdt = (O.BF16, torch.bfloat16) if dt == "bf16" else (O.F16, torch.float16)
     g = synth.rng(1100 + S)
-    qkv = O.f32_to_bf16(g.standard_normal((B * S, 3 * H * Dh)).astype(np.float32))
+    qkv = O.f32_to_hp(g.standard_normal((B * S, 3 * H * Dh)).astype(np.float32), odt)
     qv, kv, vv = (OL._heads(qkv, B, S, H, Dh, i) for i in range(3))
     kv_len = np.int32([S - 7, 3][:B]) if mask == O.MASK_PADDING else None
-    ref = O.bf16_attn(qv, kv, vv, scale=1.0 / np.sqrt(Dh), mask=mask, kv_len=kv_len)
-    dq = dev(qkv).view(B, S, 3, H, Dh)
-    got = hero.hero_bf16_attn(dq[:, :, 0], dq[:, :, 1], dq[:, :, 2], 1.0 / np.sqrt(Dh), mask=mask, kv_len=dev(kv_len))
-    assert rel_err(O.bf16_to_f32(to_np(got)), O.bf16_to_f32(ref)) <= 2e-2
+    ref = O.hp_attn(qv, kv, vv, scale=1.0 / np.sqrt(Dh), mask=mask, kv_len=kv_len, dt=odt)
+    dq = dev(qkv, tdt).view(B, S, 3, H, Dh)
+    got = hero.hero_hp_attn(dq[:, :, 0], dq[:, :, 1], dq[:, :, 2], 1.0 / np.sqrt(Dh), mask=mask, kv_len=dev(kv_len))
+    assert rel_err(O.hp_to_f32(to_np(got), odt), O.hp_to_f32(ref, odt)) <= 2e-2
+    if dt == "bf16":
+        b = hero.hero_bf16_attn(dq[:, :, 0], dq[:, :, 1], dq[:, :, 2], 1.0 / np.sqrt(Dh), mask=mask, kv_len=dev(kv_len))
+        assert torch.equal(got.view(torch.int16), b.view(torch.int16))
 
 
-# ============================================================ diagnostics
 def test_probe_library_instruments():
     """The measuring instruments of the bench (libhero_probe, a library of its own): the copies copy (1 and 4 loads
     in flight, ragged tail, the runtime's copy), the write-only pass writes every element, the MFMA loops report
