@@ -402,6 +402,9 @@ def attn_variants(hero, shape, seed, iters=20):
     dth = torch.full((H,), dt, device="cuda")
     ops = 4.0 * B * H * S * S * Dh * (0.5 if shape.mask == 2 else 1.0)
     res = {"shape_bshd": [B, S, H, Dh], "mask": ["none", "padding", "causal"][shape.mask], "useful_ops": ops}
+    if kvl is not None:
+        # padded positions neither ask nor are asked: the fraction of the S x S (query, key) pairs that are computed
+        res["real_pair_fraction"] = round(float((kvl.double() ** 2).mean().item()) / (S * S), 4)
     ms = time_gpu(lambda: hero.hero_int8_attn(v[:, :, 0], v[:, :, 1], v[:, :, 2], dt, 1 / 255, cs, mask=shape.mask,
                                               kv_len=kvl, out=out), iters)
     res["two_pass_us"] = round(ms * 1e3, 2)

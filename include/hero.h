@@ -230,8 +230,10 @@ hero_status hero_fp8_gemm(const void* A, int64_t lda, const float* a_row_scale,
  *   or a [B,H,Smax,Dh] KV cache.
  *   mask: key k is visible to query i iff k < kv_len[b] (when kv_len != NULL; required for
  *   HERO_MASK_PADDING) and, for HERO_MASK_CAUSAL, k <= i + (len_b - Sq) with len_b =
- *   min(kv_len[b], Skv) (or Skv): the last query sees the last valid key.  A query that
- *   sees no key outputs 0.
+ *   min(kv_len[b], Skv) (or Skv): the last query sees the last valid key.  With
+ *   HERO_MASK_PADDING and Sq == Skv (self-attention over a padded batch) the positions
+ *   i >= kv_len[b] are padding as queries too and see no key.  A query that sees no key
+ *   outputs 0.  The same rules hold for every attention entry point of this header.
  *   out [B*Sq, H*Dh] row-major with leading dimension ldo.
  * Constraints: Dh in {64, 128}; B, H, Sq, Skv >= 0 (zero is a no-op).
  * The softmax is normalised BEFORE it is quantized, as the equation says, so the kernel

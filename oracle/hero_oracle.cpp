@@ -464,8 +464,9 @@ int orc_embed_ln_quant(const int32_t* tok_ids, const int32_t* pos_ids, const int
 // Strides are in elements, ordered (batch, position, head, channel).
 // Mask: key k is visible to query i iff  k < kv_len[b] (when kv_len != NULL) and, for
 // CAUSAL, k <= i + (kvlen_b - Sq), i.e. the last query sees the last valid key.
-// A query with no visible key outputs 0.  p_dump (optional) receives the codes
-// [B,H,Sq,Skv].
+// With the PADDING mask in self-attention (Sq == Skv) the positions i >= kv_len[b] are padding as
+// queries too: they see no key.  A query with no visible key outputs 0.  p_dump (optional)
+// receives the codes [B,H,Sq,Skv].
 // ---------------------------------------------------------------------------------
 int orc_int8_attn(const int8_t* q, const int64_t* qs, const int8_t* k, const int64_t* ks,
                   const int8_t* v, const int64_t* vs,
@@ -485,6 +486,7 @@ int orc_int8_attn(const int8_t* q, const int64_t* qs, const int8_t* k, const int
             for (int64_t i = 0; i < Sq; ++i) {
                 int64_t last = len - 1;                              // last visible key
                 if (mask == ORC_MASK_CAUSAL) last = std::min<int64_t>(last, i + (len - Sq));
+                if (mask == ORC_MASK_PADDING && Sq == Skv && i >= len) last = -1;   // a padded position asks nothing
                 int64_t nvis = last + 1;
                 const int8_t* qi = q + b * qs[0] + i * qs[1] + h * qs[2];
                 for (int64_t kk = 0; kk < nvis; ++kk) {
@@ -560,6 +562,7 @@ int orc_fp8_attn(const uint8_t* q, const int64_t* qs, const uint8_t* k, const in
             for (int64_t i = 0; i < Sq; ++i) {
                 int64_t last = len - 1;
                 if (mask == ORC_MASK_CAUSAL) last = std::min<int64_t>(last, i + (len - Sq));
+                if (mask == ORC_MASK_PADDING && Sq == Skv && i >= len) last = -1;   // a padded position asks nothing
                 const int64_t nvis = last + 1;
                 const uint8_t* qi = q + b * qs[0] + i * qs[1] + h * qs[2];
                 for (int64_t kk = 0; kk < nvis; ++kk) {
@@ -635,6 +638,7 @@ int orc_int8_attn_online(const int8_t* q, const int64_t* qs, const int8_t* k, co
             for (int64_t i = 0; i < Sq; ++i) {
                 int64_t last = len - 1;
                 if (mask == ORC_MASK_CAUSAL) last = std::min<int64_t>(last, i + (len - Sq));
+                if (mask == ORC_MASK_PADDING && Sq == Skv && i >= len) last = -1;   // a padded position asks nothing
                 const int64_t nvis = last + 1;
                 const int8_t* qi = q + b * qs[0] + i * qs[1] + h * qs[2];
                 for (int64_t kk = 0; kk < nvis; ++kk) {
@@ -731,6 +735,7 @@ int orc_hp_attn(const uint16_t* q, const int64_t* qs, const uint16_t* k, const i
             for (int64_t i = 0; i < Sq; ++i) {
                 int64_t last = len - 1;
                 if (mask == ORC_MASK_CAUSAL) last = std::min<int64_t>(last, i + (len - Sq));
+                if (mask == ORC_MASK_PADDING && Sq == Skv && i >= len) last = -1;   // a padded position asks nothing
                 int64_t nvis = last + 1;
                 double m = -INFINITY;
                 for (int64_t kk = 0; kk < nvis; ++kk) {

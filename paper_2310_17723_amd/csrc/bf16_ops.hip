@@ -160,6 +160,11 @@ __global__ __launch_bounds__(256) void bf16_attn_kernel(BAttnArgs a) {
     nvis = max(nvis, 0);
     int kmax = len;
     if (a.mask == HERO_MASK_CAUSAL) kmax = min(len, min(q0 + ABQ, a.Sq) + shift);
+    // PADDING mask in self-attention: the positions >= len are padding as queries too; they see no key (output 0)
+    if (a.mask == HERO_MASK_PADDING && a.Sq == a.Skv) {
+        if (qi >= len) nvis = 0;
+        if (q0 >= len) kmax = 0;
+    }
     const int ntiles = (max(kmax, 0) + ABKV - 1) / ABKV;
 
     v4i qf[DS];

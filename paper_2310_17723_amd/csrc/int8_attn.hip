@@ -7,7 +7,7 @@
 // (pass 1: QK^T, row max / row sum; pass 2: QK^T again, codes, PV).  A and P never leave
 // the chip.
 //
-// Layout.  A block owns 128 queries of one (batch, head); each of its 4 waves owns 32.
+// Layout.  A block owns 128 queries of one (batch, head); each of its 4 waves owns 32 of them.
 // Scores are computed TRANSPOSED, S^T = K Q^T (v_mfma_i32_32x32x32_i8 with the key
 // fragment as first operand), so lane l holds query l % 32 and the keys 8g + 4(l/32) + t
 // of a 32-key step in accumulator register 4g + t: a query's row statistics need one
@@ -69,12 +69,20 @@ __global__ __launch_bounds__(256, ONLINE ? (DH == 64 ? 3 : 2) : (DH == 64 ? 4 : 
     const int slot = blockIdx.x / 8, grp = (slot / (HG * nqb)) * 8 + (blockIdx.x % 8), within = slot % (HG * nqb);
     const int bh = grp * HG + within / nqb;
     if (bh >= a.B * a.H) return;
-    // causal: the last query block sees the most keys, so it is started first (longest job first)
-    const int qb = a.mask == HERO_MASK_CAUSAL ? nqb - 1 - within % nqb : within % nqb;
+    // The query blocks of a (batch, head) differ in length (causal: block j sees j + 1 blocks of keys; padding: the
+    // blocks past the sequence's end leave at once), and the hardware places workgroups on the compute units in
+    // launch order, round and round: with the same order inside every group a compute unit is handed the same kind
+    // of block every time, the long ones always go to the same few, and the launch waits for those.  The order
+    // inside a group therefore rotates with a hash of the group's number.
+    const uint32_t rot = ((uint32_t)(slot / (HG * nqb)) * 2654435761u) >> 20;
+    const int qb = (int)((within % nqb + rot) % (uint32_t)nqb);
     const int b = bh / a.H, h = bh % a.H, q0 = qb * BQ;
     const int len = a.kv_len ? min(max(a.kv_len[b], 0), a.Skv) : a.Skv;
     const int shift = len - a.Sq;                       // causal: key k visible iff k <= i + shift
-    const int qi = q0 + wave * 32 + ql;                 // this lane's query
+    // Which 32 queries of the block a wave owns rotates with the block: with the padding mask the last sub-blocks
+    // of a sequence's last block are idle, and the busy waves of co-resident blocks should not share a SIMD.
+    const int wq = (wave + slot) & 3;
+    const int qi = q0 + wq * 32 + ql;                   // this lane's query
     int nvis = len;
     if (a.mask == HERO_MASK_CAUSAL) nvis = min(len, qi + shift + 1);
     nvis = max(nvis, 0);
@@ -82,6 +90,21 @@ __global__ __launch_bounds__(256, ONLINE ? (DH == 64 ? 3 : 2) : (DH == 64 ? 4 : 
     int kmax = len;
     if (a.mask == HERO_MASK_CAUSAL) kmax = min(len, min(q0 + BQ, a.Sq) + shift);
     const int ntiles = (max(kmax, 0) + BKV - 1) / BKV;
+    // PADDING mask in self-attention: the positions >= len are padding as queries too and their output rows are
+    // zeros.  A block with no real query writes them and leaves; a wave with no real query keeps staging K / V
+    // and meeting the barriers (and adds its share of the column sums) but computes no score.
+    const int qlim = (a.mask == HERO_MASK_PADDING && a.Sq == a.Skv) ? len : a.Sq;
+    if (q0 >= qlim) {
+        constexpr int U = DH / 4;                              // stores of 4 elements, as the output stage below
+        const int rows = min(BQ, a.Sq - q0);
+        for (int idx = tid; idx < rows * U; idx += 256) {
+            const int64_t e = ((int64_t)b * a.Sq + q0 + idx / U) * a.ldo + (int64_t)h * DH + (idx % U) * 4;
+            if (ODT == HERO_I8 || ODT == HERO_F8E4M3) *reinterpret_cast<uint32_t*>((int8_t*)a.out + e) = 0u;
+            else { v2i z = {0, 0}; *reinterpret_cast<v2i*>((uint16_t*)a.out + e) = z; }
+        }
+        return;
+    }
+    const bool wact = __builtin_amdgcn_readfirstlane(q0 + wq * 32) < qlim;     // wave-uniform
 
     // ---- Q fragments (second MFMA operand), kept in registers -----------------------------
     v4i qf[DS];
@@ -304,7 +327,7 @@ __global__ __launch_bounds__(256, ONLINE ? (DH == 64 ? 3 : 2) : (DH == 64 ? 4 : 
                     }
                 }
             };
-            if (edge) online_tile(std::true_type{}); else online_tile(std::false_type{});
+            if (!wact) {} else if (edge) online_tile(std::true_type{}); else online_tile(std::false_type{});
             if (tile + 1 < ntiles) { store_k(buf ^ 1); store_v(buf ^ 1); }
             __syncthreads();
         }
@@ -324,6 +347,7 @@ __global__ __launch_bounds__(256, ONLINE ? (DH == 64 ? 3 : 2) : (DH == 64 ? 4 : 
                 for (int t = 0; t < 4; ++t) {
                     const float sc = a.scale_is_scalar ? a.out_col_scale[0] : a.out_col_scale[h * DH + e0 + t];
                     y[t] = (of[c][4 * g + t] + (float)oi[c][4 * g + t]) * inv * sc;
+                    if (qi >= qlim) y[t] = 0.0f;              // padded query: zeros
                 }
                 if (ODT == HERO_I8) {
                     *reinterpret_cast<uint32_t*>((int8_t*)a.out + orow + e0) = quant4_sat(y[0], y[1], y[2], y[3]);
@@ -370,7 +394,7 @@ __global__ __launch_bounds__(256, ONLINE ? (DH == 64 ? 3 : 2) : (DH == 64 ? 4 : 
                 }
             }
         };
-        if (edge) pass1_tile(std::true_type{}); else pass1_tile(std::false_type{});
+        if (!wact) {} else if (edge) pass1_tile(std::true_type{}); else pass1_tile(std::false_type{});
         if (tile + 1 < ntiles) store_k(buf ^ 1);
         __syncthreads();
     }
@@ -449,7 +473,20 @@ __global__ __launch_bounds__(256, ONLINE ? (DH == 64 ? 3 : 2) : (DH == 64 ? 4 : 
             }
             }
         };
-        if (edge) pass2_tile(std::true_type{}); else pass2_tile(std::false_type{});
+        if (!wact) {
+            if constexpr (!F8) {                              // only the wave's share of the column sums
+#pragma unroll
+                for (int s = 0; s < BKV / 32; ++s)
+                    if (((tile * (BKV / 32) + s) & 3) == wave) {
+#pragma unroll
+                        for (int c = 0; c < DS; ++c) {
+                            const v4i vf = *reinterpret_cast<const v4i*>(&sVt[buf][(c * 32 + ql) * VLD + s * 32 + hh * 16]);
+#pragma unroll
+                            for (int w = 0; w < 4; ++w) csum[c] = __builtin_amdgcn_sdot4(vf[w], 0x01010101, csum[c], false);
+                        }
+                    }
+            }
+        } else if (edge) pass2_tile(std::true_type{}); else pass2_tile(std::false_type{});
         if (tile + 1 < ntiles) { store_k(buf ^ 1); store_v(buf ^ 1); }
         __syncthreads();
     }
@@ -479,6 +516,7 @@ __global__ __launch_bounds__(256, ONLINE ? (DH == 64 ? 3 : 2) : (DH == 64 ? 4 : 
                 float sc = a.scale_is_scalar ? a.out_col_scale[0] : a.out_col_scale[h * DH + e0 + t];
                 if constexpr (F8) y[t] = o[c][4 * g + t] * sc;
                 else y[t] = (float)(o[c][4 * g + t] + 128 * colsum[e0 + t]) * sc;
+                if (qi >= qlim) y[t] = 0.0f;                  // padded query: zeros
             }
             if (ODT == HERO_I8) {
                 *reinterpret_cast<uint32_t*>((int8_t*)a.out + orow + e0) = quant4_sat(y[0], y[1], y[2], y[3]);

@@ -805,6 +805,63 @@ def test_hp_attn_matches_oracle(hero, B, S, H, Dh, mask, dt):
         assert torch.equal(got.view(torch.int16), b.view(torch.int16))
 
 
+@pytest.mark.parametrize("Dh", [64, 128])
+def test_attention_padded_positions_ask_nothing(hero, Dh):
+    """Padding mask in self-attention: the positions i >= kv_len[b] are padding as queries too and their output rows
+    are zeros (all bits), in every attention entry point; lengths on and next to the 32-query and 128-query
+    boundaries of the kernels' work split, a full row and an empty one; the real rows in their usual classes; the
+    outputs are pre-filled so that rows nobody writes would show.  With Sq != Skv the queries are not the padded
+    positions and every one of them is answered."""
+    B, S, H = 8, 384, 2
+    kv_len = np.int32([384, 300, 129, 128, 97, 33, 1, 0])
+    pad = (np.arange(S)[None, :] >= kv_len[:, None]).reshape(-1)              # [B*S] rows that are padding
+    q, k, v, qk_scale, cs = _attn_case(4100 + Dh, B, S, S, H, Dh)
+    sp, sc = float(OL.S_P), np.float32([cs[0]])
+    kw = dict(mask=O.MASK_PADDING, kv_len=kv_len)
+    dkw = dict(mask=O.MASK_PADDING, kv_len=dev(kv_len))
+    fill8 = lambda: torch.full((B * S, H * Dh), 77, dtype=torch.int8, device="cuda")
+    fill16 = lambda: torch.full((B * S, H * Dh), 3.0, dtype=torch.bfloat16, device="cuda")
+    # two-pass INT8
+    ref = O.int8_attn(q, k, v, qk_scale=qk_scale, p_scale=sp, out_col_scale=cs, **kw)
+    got = to_np(hero.hero_int8_attn(dev(q), dev(k), dev(v), qk_scale, sp, dev(cs), out=fill8(), **dkw))
+    assert not ref[pad].any() and not got[pad].any() and np.abs(got[~pad]).max() > 40
+    assert_codes(got, ref, "X_attn")
+    refb = O.int8_attn(q, k, v, qk_scale=qk_scale, p_scale=sp, out_col_scale=sc, out_scale_is_scalar=True, out_dt=O.BF16, **kw)
+    gotb = to_np(hero.hero_int8_attn(dev(q), dev(k), dev(v), qk_scale, sp, dev(sc), out_scale_is_scalar=True,
+                                     out_dtype=torch.bfloat16, out=fill16(), **dkw))
+    assert not refb[pad].any() and not gotb[pad].any()
+    assert rel_err(O.bf16_to_f32(gotb), O.bf16_to_f32(refb)) <= 2e-2
+    # online variant
+    dts = (np.float32(qk_scale) * np.linspace(0.8, 1.3, H)).astype(np.float32)
+    ref = O.int8_attn_online(q, k, v, qk_scale_h=dts, p_scale=sp, out_col_scale=cs, kv_block=64, **kw)
+    got = to_np(hero.hero_int8_attn_online(dev(q), dev(k), dev(v), dev(dts), sp, dev(cs), out=fill8(), **dkw))
+    assert not ref[pad].any() and not got[pad].any()
+    assert_codes(got, ref, "X_attn online")
+    # FP8
+    q8, k8, v8, qs8, sp8, cs8 = _fp8_attn_case(4200 + Dh, B, S, S, H, Dh)
+    ref = O.fp8_attn(q8, k8, v8, qk_scale=qs8, p_scale=sp8, out_col_scale=cs8, **kw)
+    got = to_np(hero.hero_fp8_attn(dev(q8), dev(k8), dev(v8), qs8, sp8, dev(cs8),
+                                   out=fill8().view(torch.float8_e4m3fn), **dkw).view(torch.uint8))
+    assert not ref[pad].any() and not got[pad].any() and got[~pad].any()
+    assert_fp8_attn_codes(got, ref, O.e4m3_to_f32, "X_attn fp8")
+    # 16-bit attention
+    g = synth.rng(4300 + Dh)
+    for odt, tdt in ((O.BF16, torch.bfloat16), (O.F16, torch.float16)):
+        qkv = O.f32_to_hp(g.standard_normal((B * S, 3 * H * Dh)).astype(np.float32), odt)
+        qv, kv_, vv = (OL._heads(qkv, B, S, H, Dh, i) for i in range(3))
+        ref = O.hp_attn(qv, kv_, vv, scale=1.0 / np.sqrt(Dh), dt=odt, **kw)
+        dq = dev(qkv, tdt).view(B, S, 3, H, Dh)
+        got = to_np(hero.hero_hp_attn(dq[:, :, 0], dq[:, :, 1], dq[:, :, 2], 1.0 / np.sqrt(Dh), **dkw))
+        assert not ref[pad].any() and not got[pad].any()
+        assert rel_err(O.hp_to_f32(got, odt), O.hp_to_f32(ref, odt)) <= 2e-2
+    # the queries of a cross-attention (Sq != Skv) are all real
+    Sq = 200
+    ref = O.int8_attn(q[:, :Sq], k, v, qk_scale=qk_scale, p_scale=sp, out_col_scale=cs, **kw)
+    got = to_np(hero.hero_int8_attn(dev(q[:, :Sq].copy()), dev(k), dev(v), qk_scale, sp, dev(cs), **dkw))
+    assert_codes(got, ref, "X_attn cross")
+    assert all(got[b * Sq + 150:(b + 1) * Sq].any() for b in range(B - 1)) and not got[(B - 1) * Sq:].any()
+
+
 def test_probe_library_instruments():
     """The measuring instruments of the bench (libhero_probe, a library of its own): the copies copy (1 and 4 loads
     in flight, ragged tail, the runtime's copy), the write-only pass writes every element, the MFMA loops report

@@ -56,7 +56,7 @@ def test_post_ln_layer_m3(hero, mask):
     hero.hero_layer_fwd(desc, W, B, S, ws, x_q=dev(xq), x_scale=dev(xs), out_q=out_q, out_scale=out_s, kv_len=dev(kv_len))
     gq, gs = to_np(out_q), to_np(out_s)
     valid = np.ones(T, bool)
-    if kv_len is not None:       # padded query rows are computed but carry no meaning
+    if kv_len is not None:       # padded positions ask nothing in the attention and carry no meaning after it
         valid = (np.arange(S)[None, :] < kv_len[:, None]).ravel()
     ref = oq.astype(np.float32) * os_[:, None]
     got = gq.astype(np.float32) * gs[:, None]

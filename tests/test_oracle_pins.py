@@ -516,9 +516,12 @@ def test_attention_closed_forms():
                 assert int(out[i, h * Dh + e]) == max(-127, min(127, rne_int(F(y))))
 
 
-@pytest.mark.parametrize("mask", [O.MASK_NONE, O.MASK_PADDING, O.MASK_CAUSAL])
-def test_attention_against_scipy_softmax(mask):
-    B, Sq, Skv, H, Dh = 3, 9, 9, 2, 16
+@pytest.mark.parametrize("mask,Sq", [(O.MASK_NONE, 9), (O.MASK_PADDING, 9), (O.MASK_PADDING, 7), (O.MASK_CAUSAL, 9)])
+def test_attention_against_scipy_softmax(mask, Sq):
+    """The mask rules written out independently: key k < kv_len[b]; causal k <= i + (len - Sq); with the padding
+    mask in self-attention (Sq == Skv) a position i >= kv_len[b] is padding as a query too and sees no key, while
+    with Sq != Skv (the queries are not the padded positions) every query sees the valid keys."""
+    B, Skv, H, Dh = 3, 9, 2, 16
     q, k, v = _attn_inputs(11, B, Sq, Skv, H, Dh)
     kv_len = np.int32([9, 5, 0]) if mask == O.MASK_PADDING else (np.int32([9, 6, 3]) if mask == O.MASK_CAUSAL else None)
     d_t, sp = np.float32(2.5e-4), OL.S_P
@@ -533,6 +536,8 @@ def test_attention_against_scipy_softmax(mask):
             for i in range(Sq):
                 n = L if mask != O.MASK_CAUSAL else min(L, i + (L - Sq) + 1)
                 n = max(n, 0)
+                if mask == O.MASK_PADDING and Sq == Skv and i >= L:
+                    n = 0
                 codes = np.zeros(Skv, np.int64)
                 if n > 0:
                     p = scipy.special.softmax(a[i, :n].astype(np.float64)).astype(np.float32)
@@ -544,6 +549,8 @@ def test_attention_against_scipy_softmax(mask):
                 assert np.array_equal(out[b * Sq + i, h * Dh:(h + 1) * Dh], exp)
     if mask == O.MASK_PADDING:
         assert not out[2 * Sq:].any()            # a batch row with no visible key outputs 0
+        assert out[Sq:Sq + 5].any()
+        assert out[Sq + 5:2 * Sq].any() == (Sq != Skv)     # positions 5.. of the length-5 row: padding only in self-attention
 
 
 def test_attention_strided_views_and_offset_identity():
@@ -637,6 +644,8 @@ def test_fp8_attention_against_scipy_softmax_and_torch_rounding(mask):
             a = (qf[b, :, h] @ kf[b, :, h].T).astype(np.float32) * d_t
             for i in range(Sq):
                 n = max(L if mask != O.MASK_CAUSAL else min(L, i + (L - Sq) + 1), 0)
+                if mask == O.MASK_PADDING and Sq == Skv and i >= L:
+                    n = 0                            # self-attention: a padded position asks nothing
                 codes = np.zeros(Skv, np.uint8)
                 if n > 0:
                     p = scipy.special.softmax(a[i, :n].astype(np.float64)).astype(np.float32)
@@ -741,6 +750,8 @@ def test_attention_online_single_block_against_numpy_and_masks_by_truncation(mas
             a = (q[b, :, h].astype(np.int64) @ k[b, :, h].astype(np.int64).T).astype(np.float32) * dts[h]
             for i in range(Sq):
                 n = max(L if mask != O.MASK_CAUSAL else min(L, i + (L - Sq) + 1), 0)
+                if mask == O.MASK_PADDING and Sq == Skv and i >= L:
+                    n = 0                            # self-attention: a padded position asks nothing
                 codes = np.zeros(Skv, np.int64)
                 exp = np.zeros(Dh, np.int8)
                 if n > 0:
