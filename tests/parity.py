@@ -84,31 +84,84 @@ def assert_fp8_codes(got, ref, decode, what="", max_frac=1e-3, acc_rel=0.0):
     return frac
 
 
-def assert_fp8_attn_codes(got, ref, decode, what="", max_frac=2e-2, rel_l2=2e-2, flip_rel=0.25):
-    """E4M3 outputs of the FP8 attention.  The probabilities are E4M3 codes themselves (relative step 2^-3 .. 2^-4),
-    and the matrix cores' scores differ from the exactly accumulated ones by ~1e-3 relative, so about one
-    probability in a hundred lands on the neighbouring code; when that happens to a dominant key (p ~ 0.5) the
-    whole output row moves by up to 2^-3 p |v| ~ a quarter of the typical output.  Hence: the decoded outputs
-    agree in relative L2 (the bar of the 16-bit outputs), the codes differ on at most max_frac of the elements,
-    and no element is further away than one output step plus flip_rel x rms(ref)."""
+def fp8_attn_flip_bound(q8, k8, v8, qk_scale, p_scale, out_col_scale, mask=0, kv_len=None, tau=5e-4):
+    """Where, and by how much, the FP8 attention's output MAY differ from the oracle's because a probability code
+    landed on the neighbouring E4M3 value.  The codes are e4m3(p / S_p); the kernel's p differs from the oracle's by
+    a small relative error (the matrix cores' accumulation of the E4M3 products, exp2 / log2 approximations), so a
+    code can differ only where p / S_p lies within a relative distance tau of a rounding boundary of the E4M3 grid,
+    and then by one grid step.  tau is measured: on the four shapes of the kernel tests every deviation of more than
+    one output step is explained from tau = 2e-4 on (one is not at 1e-4); the default leaves a factor 2.5.  From the oracle's side of the computation alone (decoded operands, fp64 softmax) this
+    returns D[row, column] = sum over the keys flagged that way of step_k |v_k[column]| c[column]: the largest
+    output deviation those flips can cause.  D is 0 wherever no key of the row is near a boundary.
+    q8 [B,Sq,H,Dh], k8 / v8 [B,Skv,H,Dh] E4M3 codes (any strides); returns float64 [B*Sq, H*Dh]."""
+    import oracle as O
+    qf, kf, vf = (O.e4m3_to_f32(np.ascontiguousarray(t)).astype(np.float64) for t in (q8, k8, v8))
+    B, Sq, H, Dh = qf.shape
+    Skv = kf.shape[1]
+    cs = np.broadcast_to(np.asarray(out_col_scale, np.float64).ravel(), (H * Dh,)) if np.size(out_col_scale) > 1 \
+        else np.full(H * Dh, float(np.asarray(out_col_scale).ravel()[0]))
+    D = np.zeros((B * Sq, H * Dh))
+    ki, qi = np.arange(Skv)[None, :], np.arange(Sq)[:, None]
+    for b in range(B):
+        L = Skv if kv_len is None else int(min(max(kv_len[b], 0), Skv))
+        vis = np.broadcast_to(ki < L, (Sq, Skv)).copy()
+        if mask == 2:
+            vis &= ki <= qi + (L - Sq)
+        if mask == 1 and Sq == Skv:
+            vis &= qi < L
+        for h in range(H):
+            a = (qf[b, :, h] @ kf[b, :, h].T).astype(np.float32).astype(np.float64) * np.float64(np.float32(qk_scale))
+            a = np.where(vis, a, -np.inf)
+            m = np.max(a, axis=1, keepdims=True)
+            m = np.where(np.isfinite(m), m, 0.0)
+            e = np.exp(a - m)
+            x = e / np.maximum(e.sum(axis=1, keepdims=True), 1e-300) / p_scale
+            step = 2.0 ** (np.floor(np.log2(np.maximum(x, 2.0 ** -6))) - 3)          # grid step at x (2^-9 below 2^-6)
+            u = x / step
+            near = vis & (np.abs(u - np.floor(u) - 0.5) * step <= tau * x)
+            D[b * Sq:(b + 1) * Sq, h * Dh:(h + 1) * Dh] = ((near * step) @ np.abs(vf[b, :, h])) * cs[h * Dh:(h + 1) * Dh]
+    return D
+
+
+def assert_fp8_attn_codes(got, ref, decode, what="", flip_bound=None, clean_frac=5e-3):
+    """E4M3 outputs of the FP8 attention against the oracle's, with the tolerance the oracle's own probabilities
+    justify (fp8_attn_flip_bound): every decoded output is within flip_bound (the flips that are possible in its row)
+    plus one step of the output grid (the final rounding of nearly equal fp32 values); and where no flip is possible
+    (flip_bound == 0) the codes are the oracle's on all but clean_frac of the elements.  clean_frac is the class of
+    the FP8 GEMMs (assert_fp8_codes): the matrix cores' PV sums are off by ~1e-4 of a typical sum, which moves an
+    output across a boundary of its 2^-3 .. 2^-4 relative grid on ~1e-3 of the elements (measured 0.7e-3 .. 1.6e-3,
+    independent of tau, i.e. not caused by probability flips)."""
     g, o = decode(got).astype(np.float64), decode(ref).astype(np.float64)
+    D = np.zeros_like(o) if flip_bound is None else flip_bound
+    assert D.shape == o.shape, (what, D.shape, o.shape)
     rms = np.sqrt(np.mean(o * o))
     step = np.maximum(2.0 ** (np.floor(np.log2(np.maximum(np.abs(o), 2.0 ** -6))) - 3), 2.0 ** -9)
-    bad = np.abs(g - o) > step * 1.0001 + flip_rel * rms
-    assert not bad.any(), f"{what}: {np.count_nonzero(bad)} outputs are further away than one step + {flip_rel} rms"
-    l2 = np.sqrt(((g - o) ** 2).sum() / max((o * o).sum(), 1e-30))
-    assert l2 <= rel_l2, f"{what}: relative L2 distance {l2:.2e} (limit {rel_l2:.0e})"
-    frac = np.count_nonzero(got != ref) / got.size
-    assert frac <= max_frac, f"{what}: {frac:.2e} of the codes differ (limit {max_frac:.0e})"
-    return frac
+    # 1e-3 rms: the accumulation error of the matrix cores is a fraction of the TYPICAL sum (acc_rel of the FP8 GEMM
+    # class); an output near zero, whose own grid step is far finer than that, may move by several of its steps
+    bad = np.abs(g - o) > D * 1.0001 + step * 1.0001 + 1e-3 * rms
+    assert not bad.any(), f"{what}: {np.count_nonzero(bad)} outputs are further away than the possible flips + one output step, " \
+                          f"worst excess {np.max(np.abs(g - o) - D - step):.3g} (rms {rms:.3g})"
+    clean = D == 0
+    ndiff = np.count_nonzero((got != ref) & clean)
+    assert ndiff <= max(clean_frac * max(np.count_nonzero(clean), 1), 2.5), \
+        f"{what}: {ndiff} of {np.count_nonzero(clean)} codes differ where no probability is near a rounding boundary"
+    return float(np.mean(clean)), float(np.mean(got != ref))
 
 
-def assert_fp8_attn_values(got_f32, ref_f32, what="", rel_l2=2e-2, flip_rel=0.25):
-    """16-bit outputs of the FP8 attention: the same class as assert_fp8_attn_codes without the output grid: relative
-    L2 within rel_l2, every element within flip_rel x rms(ref) (one flipped probability code of a dominant key)
-    plus the 16-bit rounding of its own value."""
+def assert_fp8_attn_values(got_f32, ref_f32, what="", rel_l2=2e-2, flip_rel=0.25, flip_bound=None):
+    """16-bit outputs of the FP8 attention.  With flip_bound (fp8_attn_flip_bound, kernel-level tests): every element
+    within the possible flips of its row plus the 16-bit rounding of its own value plus the accumulation error of the
+    matrix cores.  Without it (whole-layer tests,
+    where a flipped code has passed through later operators): relative L2 within rel_l2 and every element within
+    flip_rel x rms(ref) plus the 16-bit rounding of its own value."""
     g, o = got_f32.astype(np.float64), ref_f32.astype(np.float64)
     rms = np.sqrt(np.mean(o * o))
+    if flip_bound is not None:
+        # 1e-3 rms: the matrix cores' PV sums carry an error that is a fraction of the TYPICAL sum (the acc_rel of the
+        # FP8 GEMM class), which an output much smaller than typical shows in full
+        bad = np.abs(g - o) > flip_bound * 1.0001 + 2.0 ** -7 * np.abs(o) + 1e-3 * rms
+        assert not bad.any(), f"{what}: {np.count_nonzero(bad)} outputs are further away than the possible flips + the 16-bit rounding"
+        return 0.0
     bad = np.abs(g - o) > flip_rel * rms + 2e-2 * np.abs(o)
     assert not bad.any(), f"{what}: {np.count_nonzero(bad)} outputs are further away than {flip_rel} rms"
     l2 = np.sqrt(((g - o) ** 2).sum() / max((o * o).sum(), 1e-30))
