@@ -1277,8 +1277,8 @@ hero_status launch_splitk(const GemmArgs& g, const SplitK& p, void* ws, hipStrea
     g1.per_xcd = (int)((tiles + NUM_XCD - 1) / NUM_XCD);
     g1.ksplit = p.ksplit; g1.kslabs = p.kslabs;
     const dim3 grid((unsigned)(g1.per_xcd * NUM_XCD), (unsigned)p.ksplit);
-    // (measured on 64 x 16384 x 4096: 4, 8 or 16 slabs in flight in registers, and 64 x 128 or 64 x 256 tiles,
-    // stream the weights no faster than this: 2.5-2.6 TB/s)
+    // (measured on 64 x 4096 x 16384 with cold weights: 8 slabs in flight are 3 % slower than 4; 26 us with the
+    // reduction pass, 2.6 TB/s)
     if (p.BM == 64) hipLaunchKernelGGL((int8_gemm_kernel<64, 64, 2, 2, 4, 2, HERO_EPI_RAW_I32, HERO_I32, -1, true>), grid, dim3(256), 0, st, g1);
     else hipLaunchKernelGGL((int8_gemm_kernel<128, 128, 2, 2, 2, 2, HERO_EPI_RAW_I32, HERO_I32, -1, true>), grid, dim3(256), 0, st, g1);
     hero_status s1 = hero_launch_status();
@@ -1310,8 +1310,8 @@ hero_status launch_grid(GemmArgs g, int BM, int BN, int threads, K kernel, hipSt
 // fewer than 192 tiles of 128x128 exist (small problems are latency-bound: more, shorter workgroups).  The
 // persistent kernels need K >= 256, K % 128 == 0 and 32-bit per-lane offsets; otherwise the one-tile-per-workgroup
 // 256x256 kernel or the register-staged 128x128 one take their place.
-// HERO_GEMM_TILE overrides the choice for tuning runs and tests: 0 = 128x128 register-staged, 1 = 256x256 one tile
-// per workgroup, 2 = 64x64, 7 = 256x256 persistent, 8 = 128x128 persistent.
+// The test hook hero_int8_gemm_tile forces a form: 0 = 128x128 register-staged, 1 = 256x256 one tile per workgroup,
+// 2 = 64x64 (and its skinny relatives), 7 = 256x256 persistent, 8 = 128x128 persistent.
 template <int BM, int BN, int WM, int WN, int EPI, int CDT, int RDT>
 hero_status launch_persistent(const GemmArgs& g, int wg_per_cu, hipStream_t st) {
     GemmArgs gp = g;
@@ -1373,6 +1373,17 @@ hero_status launch_epi(const GemmArgs& g, void* ws, size_t ws_bytes, hipStream_t
         // measured: 8-10 % at 128 tiles or fewer, a loss with more tiles or with 2 groups
         const int64_t t64 = (int64_t)((g.M + 63) / 64) * ((g.N + 63) / 64);
         const int kt = g.K / BK;
+        // One row of tiles (M <= 64: a decode step) streams the weight matrix once and is bound by how many of its
+        // bytes are in flight.  Measured inside a layer, i.e. with weights that are NOT in the Infinity Cache (timed
+        // alone and back to back the same kernels look 30 % faster than they are): up to 128 tiles, 64 x 32 tiles
+        // with 8 slabs in flight in registers (64 x 4096 x 4096: 13.1 us against 16.6 for the four-K-group form);
+        // beyond, two K groups per workgroup with 4 slabs each (64 x 12288 x 4096: 17.5 against 23.3 us for the
+        // plain 64 x 64 tile; 64 x 16384 x 4096: 18.8-21.0 against 26.5-27.0; 8 or 16 slabs in flight, four K
+        // groups or 64 x 32 tiles are all slower there).
+        if (g.M <= 64 && kt >= 32) {
+            if (t64 <= 128) return launch_grid(g, 64, 32, 128, int8_gemm_kernel<64, 32, 2, 1, 8, 2, EPI, CDT, RDT>, st);
+            if (kt % 2 == 0) return launch_grid(g, 64, 64, 512, int8_gemm_kernel<64, 64, 2, 2, 4, 1, EPI, CDT, RDT, false, 2>, st);
+        }
         if (t64 <= 128 && kt >= 32 && kt % 4 == 0)
             return launch_grid(g, 64, 64, 1024, int8_gemm_kernel<64, 64, 2, 2, 2, 1, EPI, CDT, RDT, false, 4>, st);
         return launch_grid(g, 64, 64, 256, int8_gemm_kernel<64, 64, 2, 2, 2, 2, EPI, CDT, RDT>, st);

@@ -443,6 +443,40 @@ def test_gemm_skinny_split_k_workspace(hero, M, N, K):
         hero.hero_int8_gemm(dA, dB, workspace=ws[16:])
 
 
+@pytest.mark.parametrize("M,N,K", [(64, 4096, 4096), (37, 1000, 2048), (64, 12288, 4096), (5, 8264, 2176), (64, 8200, 2112), (1, 16384, 4096)])
+def test_gemm_skinny_one_pass_forms(hero, M, N, K):
+    """One row of tiles (M <= 64, a decode step) without a scratch: 64 x 32 tiles with eight slabs in flight up to
+    128 tiles of 64 x 64, two K groups per workgroup beyond (the last shape has an odd slab count and takes the plain
+    tile).  Every epilogue in its class: raw / REQUANT / DEQUANT (+ residual, in place) bit-exact, GELU^quant +-1."""
+    c = synth.gemm_case(900 + M + N % 97, M, K, N)
+    A, Bt, rs, cs, bias = c["A"], c["Bt"], c["a_row_scale"], c["b_col_scale"], c["bias"]
+    dA, dB = dev(A), dev(Bt)
+    assert_exact(to_np(hero.hero_int8_gemm(dA, dB)), O.gemm_i32(A, Bt), "raw")
+    y = O.int8_gemm(A, Bt, a_row_scale=rs, b_col_scale=cs, bias=bias, epi=O.EPI_DEQUANT, c_dt=O.F32)
+    s_out = np.float32(np.abs(y).max() / 127)
+    cs2, b2 = (cs / s_out).astype(np.float32), (bias / s_out).astype(np.float32)
+    ref = O.int8_gemm(A, Bt, a_row_scale=rs, b_col_scale=cs2, bias=b2, epi=O.EPI_REQUANT, c_dt=O.I8)
+    got = hero.hero_int8_gemm(dA, dB, dev(rs), dev(cs2), dev(b2), epi=HB.EPI_REQUANT, out_dtype=torch.int8)
+    assert_exact(to_np(got), ref, "requant")
+    assert np.abs(ref).max() == 127
+    res = O.f32_to_bf16(synth.rng(13).standard_normal((M, N)).astype(np.float32))
+    ref = O.int8_gemm(A, Bt, a_row_scale=rs, b_col_scale=cs, bias=bias, residual=res, res_dt=O.BF16,
+                      epi=O.EPI_DEQUANT, c_dt=O.BF16)
+    dres = dev(res)
+    got = hero.hero_int8_gemm(dA, dB, dev(rs), dev(cs), dev(bias), residual=dres, epi=HB.EPI_DEQUANT, C_out=dres)
+    assert_exact(to_np(got), ref, "dequant + residual in place")
+    ref = O.int8_gemm(A, Bt, a_row_scale=rs, b_col_scale=cs, bias=bias, epi=O.EPI_DEQUANT, c_dt=O.F16)
+    got = hero.hero_int8_gemm(dA, dB, dev(rs), dev(cs), dev(bias), epi=HB.EPI_DEQUANT, out_dtype=torch.float16)
+    assert_exact(to_np(got), ref, "dequant f16")
+    csg = (cs * np.float32(30.0 / np.sqrt(K))).astype(np.float32)
+    g = O.int8_gemm(A, Bt, a_row_scale=rs, b_col_scale=csg, bias=bias, epi=O.EPI_DEQUANT_GELU, c_dt=O.F32)
+    s_a = (np.abs(g).max(axis=0) / 127 + 1e-6).astype(np.float32)
+    ref = O.int8_gemm(A, Bt, a_row_scale=rs, b_col_scale=csg, bias=bias, epi=O.EPI_GELU_REQUANT, out_col_scale=s_a, c_dt=O.I8)
+    got = hero.hero_int8_gemm(dA, dB, dev(rs), dev(csg), dev(bias), epi=HB.EPI_GELU_REQUANT, out_col_scale=dev(s_a),
+                              out_dtype=torch.int8)
+    assert_codes(to_np(got), ref, "gelu requant", max_frac=max(1e-3, 2.5 / ref.size))
+
+
 def test_gemm_strided_operands_and_errors(hero):
     """Leading dimensions larger than the logical width; invalid combinations are refused."""
     M, N, K = 96, 80, 128
