@@ -83,17 +83,31 @@ def calibrate(p, x_calib, arch, H, Dh, eps, mask, B, S, kv_len=None, *, hero, fp
     return sc, t["out"]
 
 
+def check_mode(mode):
+    """The subsets of the per-module switch the layer driver runs (Sec. 2.3): a module can be 8-bit only when the
+    module that produces its codes is (attention needs the QKV GEMM's SQ codes, the attention-output linear the
+    attention's FWQ codes, FC2 the GELU^quant codes of FC1)."""
+    m = mode & ~(HB.M_FP8 | HB.M_F16)
+    if (m & HB.M_ATTN and not m & HB.M_QKV) or (m & HB.M_ATTN_OUT and not m & HB.M_ATTN) or (m & HB.M_FC2 and not m & HB.M_FC1):
+        raise ValueError("this subset of the switch needs a stand-alone quantization kernel, which the method removes")
+    if mode & HB.M_FP8 and (m != HB.MODE_M3 or mode & HB.M_F16):
+        raise ValueError("the FP8 variant runs every module in 8 bits")
+
+
 def prepare(p, sc, arch, d, Dh, mode=HB.MODE_M3, *, hero, fp8=False):
     """Fold the static scales into the weights and quantize.  Returns (tensors, qk_scale,
     p_scale): `tensors` is keyed by the field names of hero_layer_weights.  The fold + column-wise
     quantization runs in hero_weight_fold_quant of the loaded library `hero`, on the weights' device.
+    mode: any admissible subset of the module bits (Table 1's rows, the all-16-bit layer MODE_M0 and what lies
+    between); a 16-bit module gets its unfolded weight, transposed to [N][K], in BF16 or (HB.M_F16) FP16.
     fp8 (mode M3, scales from calibrate(fp8=True)): E4M3 weights for a layer run with M_FP8."""
+    check_mode(mode | (HB.M_FP8 if fp8 else 0))
     P = {k: v.double() for k, v in p.items()}
     post = arch == HB.ARCH_POST_LN
+    hp = torch.float16 if mode & HB.M_F16 else torch.bfloat16
     t = {}
-    if fp8 and mode != HB.MODE_M3:
-        raise ValueError("the FP8 variant runs every module in 8 bits")
     f32 = lambda a: None if a is None else a.float().contiguous()
+    as_hp = lambda name: P[name].t().contiguous().to(hp)             # [in][out] -> [N][K], one rounding from fp64
 
     def quantize_folded(name, rm, cd):
         return hero.hero_weight_fold_quant(p[name].float().contiguous(), f32(rm), f32(cd), fp8=fp8)
@@ -103,7 +117,10 @@ def prepare(p, sc, arch, d, Dh, mode=HB.MODE_M3, *, hero, fp8=False):
     else:
         div = torch.ones(3 * d, dtype=torch.float64, device=P["w_qkv"].device)
         qk_scale = 1.0 / math.sqrt(Dh)
-    t["w_qkv"], t["w_qkv_s"] = quantize_folded("w_qkv", None, div if mode & HB.M_ATTN else None)
+    if mode & HB.M_QKV:
+        t["w_qkv"], t["w_qkv_s"] = quantize_folded("w_qkv", None, div if mode & HB.M_ATTN else None)
+    else:
+        t["w_qkv_hp"] = as_hp("w_qkv")
     t["b_qkv"] = (P["b_qkv"] / div).float()
     pv = sc["S_p"].double() * sc["S_v"].double()
     if mode & HB.M_ATTN_OUT:
@@ -113,16 +130,19 @@ def prepare(p, sc, arch, d, Dh, mode=HB.MODE_M3, *, hero, fp8=False):
         t["b_o"] = bo.float()
     else:
         t["attn_out_scale"] = pv.float().reshape(1)
-        t["w_o_bf16"] = P["w_o"].t().contiguous().to(torch.bfloat16)
+        t["w_o_bf16"] = as_hp("w_o")
         t["b_o"] = P["b_o"].float()
-    t["w_1"], t["w_1_s"] = quantize_folded("w_1", None, None)
+    if mode & HB.M_FC1:
+        t["w_1"], t["w_1_s"] = quantize_folded("w_1", None, None)
+    else:
+        t["w_1_hp"] = as_hp("w_1")
     t["b_1"] = P["b_1"].float()
     if mode & HB.M_FC2:
         b2 = P["b_2"] / sc["S_x2"].double() if post else P["b_2"]
         t["w_2"], t["w_2_s"] = quantize_folded("w_2", sc["S_a"], sc["S_x2"] if post else None)
         t["b_2"] = b2.float()
     else:
-        t["w_2_bf16"] = P["w_2"].t().contiguous().to(torch.bfloat16)
+        t["w_2_bf16"] = as_hp("w_2")
         t["b_2"] = P["b_2"].float()
     for k in ("S_o", "S_x2", "S_a"):
         t[k] = sc[k].float().contiguous()

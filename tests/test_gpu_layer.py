@@ -324,6 +324,40 @@ def test_gpu_preparation_matches_the_oracles(hero, arch, fp8):
         np.testing.assert_allclose(t[g_].cpu().numpy(), np.asarray(w_o[o_]), rtol=1e-6, atol=1e-9, err_msg=g_)
 
 
+@pytest.mark.parametrize("mode,f16", [(HB.MODE_M0, False), (HB.MODE_M0, True), (HB.MODE_M1, True), (HB.M_QKV | HB.M_ATTN | HB.M_ATTN_OUT, False),
+                                      (HB.M_FC1 | HB.M_FC2, True)])
+def test_prep_prepares_every_admissible_mode(hero, mode, f16):
+    """prep.prepare for the modes beyond Table 1's INT8 QKV / FC1: the 16-bit weights (transposed, one rounding from
+    fp64, BF16 or FP16) are the oracle's bit for bit, the 8-bit ones equal up to boundary codes, and a subset that
+    would need a stand-alone quantization kernel is refused."""
+    from paper_2310_17723_amd import prep
+    shape = _shape(synth.POST_LN, synth.MASK_NONE, S=64)
+    B, S, d = shape.B, shape.S, shape.d
+    p = synth.layer_params(63, shape)
+    hc = synth.activations(63, shape, B * S, stream=1).astype(np.float64)
+    sc_o, _ = OL.calibrate(p, hc, shape, B, S)
+    w_o = OL.prepare(p, sc_o, shape, mode, hp_dt=O.F16 if f16 else O.BF16)
+    pt = {k: torch.from_numpy(v).cuda() for k, v in p.items()}
+    sc_g = {k: torch.from_numpy(np.asarray(v, np.float32)).cuda() for k, v in sc_o.items()}
+    t, qk, ps = prep.prepare(pt, sc_g, shape.arch, d, shape.Dh, mode | (HB.M_F16 if f16 else 0), hero=hero)
+    assert abs(qk / float(w_o["qk_scale"] if mode & HB.M_ATTN else w_o["bf16_qk_scale"]) - 1) < 1e-6
+    pairs16 = {"w_qkv_hp": "wb_qkv", "w_o_bf16": "wb_o", "w_1_hp": "wb_1", "w_2_bf16": "wb_2"}
+    pairs8 = {"w_qkv": "wq_qkv", "w_o": "wq_o", "w_1": "wq_1", "w_2": "wq_2"}
+    bits = {"w_qkv": HB.M_QKV, "w_o": HB.M_ATTN_OUT, "w_1": HB.M_FC1, "w_2": HB.M_FC2}
+    for (g16, o16), (g8, o8) in zip(pairs16.items(), pairs8.items()):
+        if mode & bits[g8]:
+            assert g16 not in t and np.mean(to_np(t[g8]) != np.asarray(w_o[o8])) <= 1e-3, g8
+        else:
+            assert g8 not in t and t[g16].dtype == (torch.float16 if f16 else torch.bfloat16)
+            assert np.array_equal(to_np(t[g16]), np.asarray(w_o[o16])), g16
+    for g_ in ("b_qkv", "b_o", "b_1", "b_2"):
+        np.testing.assert_allclose(t[g_].cpu().numpy(), np.asarray(w_o[g_]), rtol=1e-6, atol=1e-9, err_msg=g_)
+    with pytest.raises(ValueError):
+        prep.prepare(pt, sc_g, shape.arch, d, shape.Dh, HB.M_QKV | HB.M_FC1 | HB.M_ATTN_OUT, hero=hero)
+    with pytest.raises(ValueError):
+        prep.prepare(pt, sc_g, shape.arch, d, shape.Dh, HB.MODE_M1, hero=hero, fp8=True)
+
+
 def test_layer_rejects_bad_requests(hero):
     shape = _shape(synth.POST_LN, synth.MASK_NONE)
     desc = _desc(hero, shape, HB.MODE_M3)
