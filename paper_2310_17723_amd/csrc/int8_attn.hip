@@ -572,10 +572,7 @@ __global__ __launch_bounds__(256) void int8_attn_decode_kernel(AttnArgs a) {
     // ---- phase 1: scores ---------------------------------------------------------------------
     constexpr float FMASKED = -3.0e38f;
     ST lmax = F8 ? (ST)FMASKED : (ST)-0x40000000;
-    for (int k0 = 0; k0 < len; k0 += KPI) {
-        const int key = k0 + kg;
-        v4i kv = {0, 0, 0, 0};
-        if (key < len) kv = *reinterpret_cast<const v4i*>(kbase + (int64_t)key * a.ks[1]);
+    auto score = [&](const v4i& kv) {
         ST d = 0;
         if constexpr (F8) {
             float kf[16];
@@ -588,6 +585,27 @@ __global__ __launch_bounds__(256) void int8_attn_decode_kernel(AttnArgs a) {
         }
 #pragma unroll
         for (int o = 1; o < LPK; o <<= 1) d += __shfl_xor(d, o);
+        return d;
+    };
+    // the stream is bound by the bytes in flight: UNR unconditional loads per lane are issued before the first is
+    // used (whole groups of UNR * KPI keys), the ragged rest goes one guarded load at a time
+    constexpr int UNR = 8;
+    int k0 = 0;
+    for (; k0 + UNR * KPI <= len; k0 += UNR * KPI) {
+        v4i kv[UNR];
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) kv[u] = *reinterpret_cast<const v4i*>(kbase + (int64_t)(k0 + u * KPI + kg) * a.ks[1]);
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const ST d = score(kv[u]);
+            if (sub == 0) { sc[k0 + u * KPI + kg] = d; lmax = max(lmax, d); }
+        }
+    }
+    for (; k0 < len; k0 += KPI) {
+        const int key = k0 + kg;
+        v4i kv = {0, 0, 0, 0};
+        if (key < len) kv = *reinterpret_cast<const v4i*>(kbase + (int64_t)key * a.ks[1]);
+        const ST d = score(kv);
         if (sub == 0 && key < len) { sc[key] = d; lmax = max(lmax, d); }
     }
     // block max
@@ -618,21 +636,28 @@ __global__ __launch_bounds__(256) void int8_attn_decode_kernel(AttnArgs a) {
     ST acc[16];
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc[e] = 0;
-    for (int k0 = 0; k0 < len; k0 += KPI) {
-        const int key = k0 + kg;
-        if (key < len) {
-            const v4i vv = *reinterpret_cast<const v4i*>(vbase + (int64_t)key * a.vs[1]);
-            const ST p = sc[key];
-            if constexpr (F8) {
-                float vf[16];
-                decode16(vv, vf);
+    auto pv = [&](const v4i& vv, const ST p) {
+        if constexpr (F8) {
+            float vf[16];
+            decode16(vv, vf);
 #pragma unroll
-                for (int e = 0; e < 16; ++e) acc[e] = fmaf(p, vf[e], acc[e]);
-            } else {
+            for (int e = 0; e < 16; ++e) acc[e] = fmaf(p, vf[e], acc[e]);
+        } else {
 #pragma unroll
-                for (int e = 0; e < 16; ++e) acc[e] += p * (int)(int8_t)(vv[e >> 2] >> (8 * (e & 3)));
-            }
+            for (int e = 0; e < 16; ++e) acc[e] += p * (int)(int8_t)(vv[e >> 2] >> (8 * (e & 3)));
         }
+    };
+    k0 = 0;
+    for (; k0 + UNR * KPI <= len; k0 += UNR * KPI) {
+        v4i vv[UNR];
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) vv[u] = *reinterpret_cast<const v4i*>(vbase + (int64_t)(k0 + u * KPI + kg) * a.vs[1]);
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) pv(vv[u], sc[k0 + u * KPI + kg]);
+    }
+    for (; k0 < len; k0 += KPI) {
+        const int key = k0 + kg;
+        if (key < len) pv(*reinterpret_cast<const v4i*>(vbase + (int64_t)key * a.vs[1]), sc[key]);
     }
 #pragma unroll
     for (int e = 0; e < 16; ++e) racc[kg][sub * 16 + e] = acc[e];
