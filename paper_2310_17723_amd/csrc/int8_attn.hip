@@ -23,6 +23,7 @@
 // the matrix cores, so both passes are written to spend as few vector instructions per score
 // as possible (see the comment in front of pass 1).
 #include "hero_common.h"
+#include <atomic>
 #include <type_traits>
 
 namespace {
@@ -679,6 +680,22 @@ __global__ void zero_rows_kernel(int8_t* out, int64_t bytes) {
     if (i < bytes) *reinterpret_cast<v4i*>(out + i) = v4i{0, 0, 0, 0};
 }
 
+// The decode kernel keeps one score per key in dynamic LDS; beyond 32 KB a kernel must be told once (per device) how
+// much it may ask for.  The attribute is raised to the kernel's maximum the first time a launch needs more than the
+// default, not on every call.
+template <int DH, int ODT, int FMT>
+bool decode_lds_ready(size_t lds) {
+    static std::atomic<bool> raised[64];
+    if (lds <= 32768) return true;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return false;
+    if (raised[dev].load(std::memory_order_acquire)) return true;
+    if (hipFuncSetAttribute((const void*)int8_attn_decode_kernel<DH, ODT, FMT>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            DEC_MAX_KEYS * (int)sizeof(int)) != hipSuccess) return false;
+    raised[dev].store(true, std::memory_order_release);
+    return true;
+}
+
 template <int DH, bool ONLINE = false, int FMT = HERO_I8>
 hero_status launch(const AttnArgs& a, hero_dtype out_dt, hipStream_t st) {
     constexpr int HG = DH >= 128 ? 1 : 128 / DH;               // heads per workgroup group (see the kernel)
@@ -743,8 +760,7 @@ hero_status attn_entry(const int8_t* q, const int64_t q_strides[4],
         dim3 grid((unsigned)H, (unsigned)B), block(256);
         const size_t lds = (size_t)Skv * sizeof(int);
 #define HERO_DEC(DH_, ODT_, FMT_) do { \
-            if (lds > 32768 && hipFuncSetAttribute((const void*)int8_attn_decode_kernel<DH_, ODT_, FMT_>, \
-                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) return HERO_ERR_LAUNCH; \
+            if (!decode_lds_ready<DH_, ODT_, FMT_>(lds)) return HERO_ERR_LAUNCH; \
             hipLaunchKernelGGL((int8_attn_decode_kernel<DH_, ODT_, FMT_>), grid, block, lds, st, a); } while (0)
 #define HERO_DEC_DT(DH_, FMT_) do { \
             if (out_dt == HERO_BF16) HERO_DEC(DH_, HERO_BF16, FMT_); else if (out_dt == HERO_F16) HERO_DEC(DH_, HERO_F16, FMT_); \

@@ -1379,7 +1379,13 @@ hero_status launch_epi(const GemmArgs& g, void* ws, size_t ws_bytes, hipStream_t
         // with 8 slabs in flight in registers (64 x 4096 x 4096: 13.1 us against 16.6 for the four-K-group form);
         // beyond, two K groups per workgroup with 4 slabs each (64 x 12288 x 4096: 17.5 against 23.3 us for the
         // plain 64 x 64 tile; 64 x 16384 x 4096: 18.8-21.0 against 26.5-27.0; 8 or 16 slabs in flight, four K
-        // groups or 64 x 32 tiles are all slower there).
+        // groups or 64 x 32 tiles are all slower there).  More bytes in flight do not help beyond that: a form of
+        // this kernel with two producer waves that kept seven 16 KB stages (112 KB per workgroup) on their way
+        // straight into an LDS ring was correct and no faster (64 x 16384 x 4096: 23.4 us; with 64 workgroups, 64 x
+        // 4096 x 16384: 51 us = 21 GB/s per compute unit).  A compute unit pulls about 21-23 GB/s from HBM whatever
+        // it has outstanding (the decode attention reaches 5.9 TB/s with all 256 of them streaming), so what counts
+        // is that every unit streams its 1/256 of the weights: 64-column tiles do that for N = 16384 and leave a
+        // quarter of the chip idle for N = 12288.
         if (g.M <= 64 && kt >= 32) {
             if (t64 <= 128) return launch_grid(g, 64, 32, 128, int8_gemm_kernel<64, 32, 2, 1, 8, 2, EPI, CDT, RDT>, st);
             if (kt % 2 == 0) return launch_grid(g, 64, 64, 512, int8_gemm_kernel<64, 64, 2, 2, 4, 1, EPI, CDT, RDT, false, 2>, st);

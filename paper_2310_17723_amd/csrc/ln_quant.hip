@@ -25,6 +25,7 @@
 //     reciprocal / reciprocal square root, and v_cvt_pk_u8_f32 of y/s + 128 rounds, saturates
 //     and packs in one instruction (the offset is removed by an XOR of the packed dword).
 #include "hero_common.h"
+#include <atomic>
 #include <type_traits>
 
 namespace {
@@ -378,9 +379,16 @@ hero_status launch_nch(const LnArgs& a, hipStream_t st) {
     const bool has_ln = a.gamma != nullptr;
     const void* fn = GATHER ? (const void*)ln_quant_kernel<XDT, RDT, NCH, true, GATHER>
                    : has_ln ? (const void*)ln_quant_kernel<XDT, RDT, NCH, true> : (const void*)ln_quant_kernel<XDT, RDT, NCH, false>;
-    if (lds > 65536 &&                                    // more than 64 KB of dynamic LDS needs the opt-in
-        hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-        return HERO_ERR_LAUNCH;
+    if (lds > 65536) {                                    // more than 64 KB of dynamic LDS needs the opt-in: once per device
+        static std::atomic<bool> raised[3][64];
+        int dev = -1;
+        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return HERO_ERR_LAUNCH;
+        std::atomic<bool>& done = raised[GATHER ? 2 : (has_ln ? 1 : 0)][dev];
+        if (!done.load(std::memory_order_acquire)) {
+            if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) return HERO_ERR_LAUNCH;
+            done.store(true, std::memory_order_release);
+        }
+    }
     // persistent workgroups: wide ones (one per CU) once every CU has several rows per wave, else
     // 4-wave workgroups, never more than the rows need
     constexpr int MAXW = ln_max_waves(NCH);
