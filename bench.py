@@ -306,6 +306,25 @@ def gemm_sweep(hero, seed, iters=10):
     return rows
 
 
+def gemm_cpu_baseline(seed):
+    """The oracle's GeMM^quant beside the config-1 sweep: M = 512 in full, and 64 seeded output rows of the M = 8192
+    problem (the oracle computes row by row, so the rate of a sample of rows is the rate of the problem)."""
+    import oracle as O
+    from paper_2310_17723_amd import synth
+    out = []
+    K, N = synth.GEMM_KN[0]
+    for M, rows, what in ((512, 512, "in full"), (8192, 64, "64 seeded output rows")):
+        c = synth.gemm_case(seed, M, K, N)
+        sel = np.sort(synth.rng(seed + M).choice(M, rows, replace=False)) if rows < M else np.arange(M)
+        A, rs = np.ascontiguousarray(c["A"][sel]), np.ascontiguousarray(c["a_row_scale"][sel])
+        t0 = time.perf_counter()
+        O.int8_gemm(A, c["Bt"], a_row_scale=rs, b_col_scale=c["b_col_scale"], bias=c["bias"], epi=O.EPI_REQUANT, c_dt=O.I8)
+        dt = time.perf_counter() - t0
+        out.append({"value": round(2.0 * rows * N * K / dt / 1e9, 2), "unit": "GOP/s", "cores": O.num_threads(), "kind": "oracle",
+                    "sample": f"REQUANT {M}x{N}x{K}: {what}", "seconds": round(dt, 3)})
+    return out
+
+
 def fp8_gemm_leg(hero, shape, seed, iters=20):
     """The FP8 variant of the layer's two big GEMMs (Sec. 2.1 names FP8 as the alternative 8-bit format):
     E4M3 operands from Gaussian data under token-wise / column-wise scales, E4M3 outputs."""
@@ -782,6 +801,7 @@ def main():
         rec["ln_quant_large"]["frac_of_best_large_copy"] = round(rec["ln_quant_large"]["gbs"] / mc["hbm_best_copy_gbs"], 4)
         log("[bench] GEMM sweep")
         rec["gemm_sweep"] = gemm_sweep(hero, args.seed)
+        rec["gemm_sweep_cpu_baseline"] = gemm_cpu_baseline(args.seed)
         del st
         torch.cuda.empty_cache()
         log("[bench] CPU oracle baseline")
