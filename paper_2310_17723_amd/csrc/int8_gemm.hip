@@ -1385,7 +1385,11 @@ hero_status launch_epi(const GemmArgs& g, void* ws, size_t ws_bytes, hipStream_t
         // 4096 x 16384: 51 us = 21 GB/s per compute unit).  A compute unit pulls about 21-23 GB/s from HBM whatever
         // it has outstanding (the decode attention reaches 5.9 TB/s with all 256 of them streaming), so what counts
         // is that every unit streams its 1/256 of the weights: 64-column tiles do that for N = 16384 and leave a
-        // quarter of the chip idle for N = 12288.
+        // quarter of the chip idle for N = 12288.  Narrower strips do not fix that either: every workgroup also reads
+        // all of the M x K activations (from the L2, but through the same per-unit path), so 16-column strips (tried
+        // with 32-wide tiles whose upper half repeats the last owned column) move four times the activation bytes per
+        // weight byte: 64 x 4096 x 4096 11.8 us (13.0 with 32 columns), 64 x 12288 x 4096 29-38 us (17.5),
+        // 64 x 4096 x 16384 without a split 35-40 us (28 with the split and its reduction pass).
         if (g.M <= 64 && kt >= 32) {
             if (t64 <= 128) return launch_grid(g, 64, 32, 128, int8_gemm_kernel<64, 32, 2, 1, 8, 2, EPI, CDT, RDT>, st);
             if (kt % 2 == 0) return launch_grid(g, 64, 64, 512, int8_gemm_kernel<64, 64, 2, 2, 4, 1, EPI, CDT, RDT, false, 2>, st);
