@@ -30,8 +30,9 @@ sys.path.insert(0, ROOT)
 # which names the commit and the commands they were taken with (written from the rocprofv3 summaries beside it).
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "measured_traffic.json")
 
-# what SURVEY's roofline gives per workload, in layer-tokens/s (INT8 MFMA peak for the prefill stacks, 8 TB/s
-# for the decode step); bert-base is latency-bound and has none
+# the roofline bound of a whole layer per workload, in layer-tokens/s: its integer operations at the 5.0 POP/s INT8
+# MFMA peak for the prefill stacks (446 GOP / 6.87 TOP per layer), its HBM bytes at 8 TB/s for the decode step
+# (1.3 GB per layer-step); bert-base is latency-bound and has none
 LAYER_BOUND = {"bert-large-32x512": 185e6, "gpt-prefill-8x2048": 12e6, "gpt-decode-64x1": 0.39e6}
 
 PEAK_INT8_TOPS = 5000.0      # MI355X dense INT8 MFMA, TOP/s
