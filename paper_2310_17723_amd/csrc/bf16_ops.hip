@@ -183,15 +183,27 @@ __global__ __launch_bounds__(256) void bf16_attn_kernel(BAttnArgs a) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) o[c][r] = 0.0f;
 
+    // K / V tiles: global -> registers (the next tile's loads are in flight during the current tile's math) -> LDS
+    constexpr int CPRW = DH / 8;                           // 16-byte chunks per K/V row
+    constexpr int UNITS = ABKV * CPRW / 256;               // chunks per thread and tile
+    v4i rk[UNITS], rv[UNITS];
+    auto fetch = [&](int tile) {
+#pragma unroll
+        for (int u = 0; u < UNITS; ++u) {
+            const int idx = tid + u * 256, row = idx / CPRW, ch = idx % CPRW;
+            const int key = min(tile * ABKV + row, a.Skv - 1);
+            rk[u] = *reinterpret_cast<const v4i*>(kbase + (int64_t)key * a.ks[1] + ch * 8);
+            rv[u] = *reinterpret_cast<const v4i*>(vbase + (int64_t)key * a.vs[1] + ch * 8);
+        }
+    };
+    if (ntiles > 0) fetch(0);
     for (int tile = 0; tile < ntiles; ++tile) {
         __syncthreads();
-        constexpr int CPRW = DH / 8;                       // 16-byte chunks per K/V row
-        for (int idx = tid; idx < ABKV * CPRW; idx += 256) {
-            const int row = idx / CPRW, ch = idx % CPRW;
-            const int key = min(tile * ABKV + row, a.Skv - 1);
-            *reinterpret_cast<v4i*>(&sK[row * KLD + ch * 16]) =
-                *reinterpret_cast<const v4i*>(kbase + (int64_t)key * a.ks[1] + ch * 8);
-            v4i w = *reinterpret_cast<const v4i*>(vbase + (int64_t)key * a.vs[1] + ch * 8);
+#pragma unroll
+        for (int u = 0; u < UNITS; ++u) {
+            const int idx = tid + u * 256, row = idx / CPRW, ch = idx % CPRW;
+            *reinterpret_cast<v4i*>(&sK[row * KLD + ch * 16]) = rk[u];
+            const v4i w = rv[u];
             // key row 32kb + 8g + 4h' + t of the tile -> position 32kb + 16(g>>1) + 8h' + 4(g&1) + t:
             // within each 16-key MFMA step, half h' holds its 8 keys (g&1, t) contiguously
             const int r32 = row & 31, g4 = r32 >> 3, hp = (r32 >> 2) & 1, t = r32 & 3;
@@ -201,6 +213,7 @@ __global__ __launch_bounds__(256) void bf16_attn_kernel(BAttnArgs a) {
                 *reinterpret_cast<uint16_t*>(&sVt[(ch * 8 + e) * VLD + pos * 2]) = (uint16_t)((uint32_t)w[e >> 1] >> (16 * (e & 1)));
         }
         __syncthreads();
+        if (tile + 1 < ntiles) fetch(tile + 1);
 #pragma unroll
         for (int s = 0; s < ABKV / 32; ++s) {
             v16f acc;
