@@ -124,6 +124,52 @@ def test_int8_attn_online_full_size_sampled_heads(hero):
         assert_codes(got[b * S:(b + 1) * S, h * Dh:(h + 1) * Dh][valid], ref[valid], f"online (b,h)=({b},{h})")
 
 
+@pytest.mark.parametrize("fp8", [False, True])
+def test_decode_attention_full_size_sampled_heads(hero, fp8):
+    """The cache-streaming one-query kernel at config 4's size (64 sequences x 32 heads x 128 against a 2176-row cache,
+    the launch the decode bench times; lengths 2048 .. 2175 so that whole groups of keys and a ragged rest both
+    occur): sampled (batch, head) pairs against the oracle; INT8 in the +-1 LSB class, E4M3 within what the
+    probabilities next to a rounding boundary allow."""
+    from parity import assert_fp8_attn_codes, fp8_attn_flip_bound
+    shape = synth.CONFIGS[4]
+    B, H, Dh, d = shape.B, shape.H, shape.Dh, shape.d
+    Smax = shape.cache_len + shape.steps
+    g = synth.rng(2700 + fp8)
+    kv_len = g.integers(shape.cache_len, Smax, B).astype(np.int32)
+    kv_len[0], kv_len[B - 1] = shape.cache_len, Smax - 1
+    tg = torch.Generator(device="cuda").manual_seed(2700)
+    if fp8:
+        kc = (torch.randn((B, H, Smax, Dh), device="cuda", generator=tg) * 40).to(torch.float8_e4m3fn)
+        vc = (torch.randn((B, H, Smax, Dh), device="cuda", generator=tg) * 40).to(torch.float8_e4m3fn)
+        q = (torch.randn((B, 1, H, Dh), device="cuda", generator=tg) * 40).to(torch.float8_e4m3fn)
+        qk_scale, sp = float(np.float32(1.5 / (40 * 40 * np.sqrt(Dh)))), float(OL.S_P_FP8)
+        cs = (g.uniform(0.8, 1.2, d) * sp * 4.0).astype(np.float32)
+        got = to_np(hero.hero_fp8_attn(q, kc.permute(0, 2, 1, 3), vc.permute(0, 2, 1, 3), qk_scale, sp, dev(cs),
+                                       mask=HB.MASK_PADDING, kv_len=dev(kv_len)).view(torch.uint8))
+        view = lambda t: to_np(t.view(torch.uint8))
+    else:
+        kc = torch.randint(-127, 128, (B, H, Smax, Dh), dtype=torch.int8, device="cuda", generator=tg)
+        vc = torch.randint(-127, 128, (B, H, Smax, Dh), dtype=torch.int8, device="cuda", generator=tg)
+        q = torch.randint(-127, 128, (B, 1, H, Dh), dtype=torch.int8, device="cuda", generator=tg)
+        qk_scale, sp = float(4.0 / (73.0 * 73.0 * np.sqrt(Dh))), float(OL.S_P)       # logits of std 4: a few dominant keys per row
+        cs = (g.uniform(0.8, 1.2, d) / (255 * 73) * 127 * 0.4).astype(np.float32)
+        got = to_np(hero.hero_int8_attn(q, kc.permute(0, 2, 1, 3), vc.permute(0, 2, 1, 3), qk_scale, sp, dev(cs),
+                                        mask=HB.MASK_PADDING, kv_len=dev(kv_len)))
+        view = to_np
+    for (b, h) in [(0, 0), (B - 1, H - 1), (int(g.integers(0, B)), int(g.integers(0, H))), (int(g.integers(0, B)), int(g.integers(0, H)))]:
+        qb = view(q[b:b + 1, :, h:h + 1])
+        kb, vb = (np.ascontiguousarray(view(t[b:b + 1, h:h + 1]).transpose(0, 2, 1, 3)) for t in (kc, vc))
+        csh = cs[h * Dh:(h + 1) * Dh]
+        if fp8:
+            ref = O.fp8_attn(qb, kb, vb, qk_scale=qk_scale, p_scale=sp, out_col_scale=csh, mask=O.MASK_PADDING, kv_len=kv_len[b:b + 1])
+            D = fp8_attn_flip_bound(qb, kb, vb, qk_scale, sp, csh, mask=1, kv_len=kv_len[b:b + 1])
+            assert_fp8_attn_codes(got[b:b + 1, h * Dh:(h + 1) * Dh], ref, O.e4m3_to_f32, f"fp8 decode (b,h)=({b},{h})", flip_bound=D)
+        else:
+            ref = O.int8_attn(qb, kb, vb, qk_scale=qk_scale, p_scale=sp, out_col_scale=csh, mask=O.MASK_PADDING, kv_len=kv_len[b:b + 1])
+            assert np.abs(ref).max() > 15
+            assert_codes(got[b:b + 1, h * Dh:(h + 1) * Dh], ref, f"decode (b,h)=({b},{h})", max_frac=2.5 / ref.size)
+
+
 def test_fp8_attn_full_size_sampled_heads(hero):
     """hero_fp8_attn at config 2's full size (the launch the bench times): sampled (batch, head) pairs against its
     oracle, within what the probabilities next to an E4M3 rounding boundary can change (parity.fp8_attn_flip_bound)."""
