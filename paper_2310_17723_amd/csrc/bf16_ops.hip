@@ -151,7 +151,15 @@ __global__ __launch_bounds__(256) void bf16_attn_kernel(BAttnArgs a) {
     __shared__ __attribute__((aligned(16))) int8_t sK[ABKV * KLD];
     __shared__ __attribute__((aligned(16))) int8_t sVt[DH * VLD];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hh = lane >> 5, ql = lane & 31;
-    const int b = blockIdx.z, h = blockIdx.y, q0 = blockIdx.x * ABQ;
+    // Workgroups go round-robin to the 8 XCDs: all query blocks of one (batch, head) are sent to the same XCD, back to
+    // back, so its K / V stream hits that XCD's L2 after the first block; their order inside the head rotates with a
+    // hash of the head's number (the blocks of a causal or padded head differ in length, and the hardware places
+    // workgroups on the compute units in launch order: a fixed order hands a unit the same kind of block every time).
+    const int nqb = (a.Sq + ABQ - 1) / ABQ;
+    const int slot = blockIdx.x / 8, bh = (slot / nqb) * 8 + (int)(blockIdx.x % 8);
+    if (bh >= a.B * a.H) return;
+    const uint32_t rot = ((uint32_t)(slot / nqb) * 2654435761u) >> 20;
+    const int b = bh / a.H, h = bh % a.H, q0 = (int)((slot % nqb + rot) % (uint32_t)nqb) * ABQ;
     const int len = a.kv_len ? min(max(a.kv_len[b], 0), a.Skv) : a.Skv;
     const int shift = len - a.Sq;
     const int qi = q0 + wave * 32 + ql;
@@ -183,34 +191,43 @@ __global__ __launch_bounds__(256) void bf16_attn_kernel(BAttnArgs a) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) o[c][r] = 0.0f;
 
-    // K / V tiles: global -> registers (the next tile's loads are in flight during the current tile's math) -> LDS
+    // K / V tiles: global -> registers (the next tile's loads are in flight during the current tile's math) -> LDS.
+    // A thread's unit is one 16-byte chunk (8 channels) of TWO neighbouring key rows 2r, 2r + 1: V is stored transposed
+    // and the two keys sit side by side there, so a channel's pair of values goes out as one 32-bit store.
     constexpr int CPRW = DH / 8;                           // 16-byte chunks per K/V row
-    constexpr int UNITS = ABKV * CPRW / 256;               // chunks per thread and tile
-    v4i rk[UNITS], rv[UNITS];
+    constexpr int PAIRS = (ABKV / 2) * CPRW / 256;         // units per thread and tile
+    v4i rk[PAIRS][2], rv[PAIRS][2];
     auto fetch = [&](int tile) {
 #pragma unroll
-        for (int u = 0; u < UNITS; ++u) {
-            const int idx = tid + u * 256, row = idx / CPRW, ch = idx % CPRW;
-            const int key = min(tile * ABKV + row, a.Skv - 1);
-            rk[u] = *reinterpret_cast<const v4i*>(kbase + (int64_t)key * a.ks[1] + ch * 8);
-            rv[u] = *reinterpret_cast<const v4i*>(vbase + (int64_t)key * a.vs[1] + ch * 8);
+        for (int u = 0; u < PAIRS; ++u) {
+            const int idx = tid + u * 256, rp = idx / CPRW, ch = idx % CPRW;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int key = min(tile * ABKV + 2 * rp + j, a.Skv - 1);
+                rk[u][j] = *reinterpret_cast<const v4i*>(kbase + (int64_t)key * a.ks[1] + ch * 8);
+                rv[u][j] = *reinterpret_cast<const v4i*>(vbase + (int64_t)key * a.vs[1] + ch * 8);
+            }
         }
     };
     if (ntiles > 0) fetch(0);
     for (int tile = 0; tile < ntiles; ++tile) {
         __syncthreads();
 #pragma unroll
-        for (int u = 0; u < UNITS; ++u) {
-            const int idx = tid + u * 256, row = idx / CPRW, ch = idx % CPRW;
-            *reinterpret_cast<v4i*>(&sK[row * KLD + ch * 16]) = rk[u];
-            const v4i w = rv[u];
+        for (int u = 0; u < PAIRS; ++u) {
+            const int idx = tid + u * 256, rp = idx / CPRW, ch = idx % CPRW, row = 2 * rp;
+            *reinterpret_cast<v4i*>(&sK[row * KLD + ch * 16]) = rk[u][0];
+            *reinterpret_cast<v4i*>(&sK[(row + 1) * KLD + ch * 16]) = rk[u][1];
             // key row 32kb + 8g + 4h' + t of the tile -> position 32kb + 16(g>>1) + 8h' + 4(g&1) + t:
-            // within each 16-key MFMA step, half h' holds its 8 keys (g&1, t) contiguously
+            // within each 16-key MFMA step, half h' holds its 8 keys (g&1, t) contiguously; rows 2r and 2r + 1
+            // differ in the lowest bit of t only
             const int r32 = row & 31, g4 = r32 >> 3, hp = (r32 >> 2) & 1, t = r32 & 3;
             const int pos = (row & 32) + (g4 >> 1) * 16 + hp * 8 + (g4 & 1) * 4 + t;
 #pragma unroll
-            for (int e = 0; e < 8; ++e)
-                *reinterpret_cast<uint16_t*>(&sVt[(ch * 8 + e) * VLD + pos * 2]) = (uint16_t)((uint32_t)w[e >> 1] >> (16 * (e & 1)));
+            for (int j = 0; j < 4; ++j) {                   // channels 2j, 2j + 1 of both keys
+                const uint32_t w0 = (uint32_t)rv[u][0][j], w1 = (uint32_t)rv[u][1][j];
+                *reinterpret_cast<uint32_t*>(&sVt[(ch * 8 + 2 * j) * VLD + pos * 2]) = __builtin_amdgcn_perm(w1, w0, 0x05040100u);
+                *reinterpret_cast<uint32_t*>(&sVt[(ch * 8 + 2 * j + 1) * VLD + pos * 2]) = __builtin_amdgcn_perm(w1, w0, 0x07060302u);
+            }
         }
         __syncthreads();
         if (tile + 1 < ntiles) fetch(tile + 1);
@@ -245,11 +262,15 @@ __global__ __launch_bounds__(256) void bf16_attn_kernel(BAttnArgs a) {
                     pb[r >> 1] = pk;
                 }
                 l = fmaf(l, resc, sum);
+                // the accumulators are rescaled only in steps where some query of the wave raises its maximum
+                // (otherwise every factor is exactly 1)
+                if (__builtin_amdgcn_ballot_w64(mn != m2) != 0) {
+#pragma unroll
+                    for (int c = 0; c < CT; ++c)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) o[c][r] *= resc;
+                }
                 m2 = mn;
-#pragma unroll
-                for (int c = 0; c < CT; ++c)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) o[c][r] *= resc;
             } else {
 #pragma unroll
                 for (int r = 0; r < 8; ++r) pb[r] = 0;
@@ -373,7 +394,9 @@ extern "C" hero_status hero_hp_attn(const void* q, const int64_t q_strides[4],
     for (int t = 0; t < 4; ++t) { a.qs[t] = q_strides[t]; a.ks[t] = k_strides[t]; a.vs[t] = v_strides[t]; }
     a.B = (int)B; a.H = (int)H; a.Sq = (int)Sq; a.Skv = (int)Skv; a.scale = scale; a.mask = (int)mask; a.kv_len = kv_len;
     a.out = (uint16_t*)out; a.ldo = ldo;
-    dim3 grid((unsigned)((Sq + ABQ - 1) / ABQ), (unsigned)H, (unsigned)B);
+    const int64_t nblocks = ((B * H + 7) / 8) * 8 * ((Sq + ABQ - 1) / ABQ);   // whole rounds of 8 heads, one per XCD
+    if (nblocks > 0x7fffffffLL) return HERO_ERR_SHAPE;
+    dim3 grid((unsigned)nblocks);
     if (dt == HERO_BF16) {
         if (Dh == 64) hipLaunchKernelGGL((bf16_attn_kernel<64, HERO_BF16>), grid, dim3(256), 0, st, a);
         else hipLaunchKernelGGL((bf16_attn_kernel<128, HERO_BF16>), grid, dim3(256), 0, st, a);
