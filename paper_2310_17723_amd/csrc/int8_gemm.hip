@@ -1467,6 +1467,10 @@ hero_status launch_epi_fp8(GemmArgs g, hipStream_t st, int cfg) {
         // few tiles and a long K: four groups of waves per workgroup split K, as for INT8 operands
         const int64_t t64 = (int64_t)((g.M + 63) / 64) * ((g.N + 63) / 64);
         const int kt = g.K / BK;
+        if (g.M <= 64 && kt >= 32) {                          // one row of tiles: the forms chosen for INT8 operands (cold weights)
+            if (t64 <= 128 && kt < 128) return launch_grid(g, 64, 32, 128, int8_gemm_kernel<64, 32, 2, 1, 8, 2, EPI, CDT, RDT, false, 1, HERO_F8E4M3>, st);
+            if (t64 > 128 && kt % 2 == 0) return launch_grid(g, 64, 64, 512, int8_gemm_kernel<64, 64, 2, 2, 4, 1, EPI, CDT, RDT, false, 2, HERO_F8E4M3>, st);
+        }
         if (t64 <= 128 && kt >= 32 && kt % 4 == 0)
             return launch_grid(g, 64, 64, 1024, int8_gemm_kernel<64, 64, 2, 2, 2, 1, EPI, CDT, RDT, false, 4, HERO_F8E4M3>, st);
         return launch_grid(g, 64, 64, 256, int8_gemm_kernel<64, 64, 2, 2, 2, 2, EPI, CDT, RDT, false, 1, HERO_F8E4M3>, st);
