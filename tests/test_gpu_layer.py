@@ -214,6 +214,67 @@ def test_module_switch_beyond_table1(hero, arch, mode, hp):
         assert e <= 2e-2
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_layer_random_shapes(hero, seed):
+    """A seeded sweep of layer shapes the tile sizes do not divide (1 to 5 heads of 64 or 128 channels, ffn a multiple
+    of 64, 1 to 3 sequences of 5 to 170 tokens), both architectures, the modes M3 / M2 / M1 / M0, padding with a
+    sequence of length 1 and (seed 0) an empty one: the layer driver's buffer arithmetic and every kernel's ragged edges
+    inside one chain.  Bars as in the fixed-shape layer tests."""
+    g = synth.rng(7000 + seed)
+    Dh = int(g.choice([64, 128]))
+    H = int(g.integers(1, 6)) if Dh == 64 else int(g.integers(1, 4))
+    f = 64 * int(g.integers(2, 13))
+    B, S = int(g.integers(1, 4)), int(g.integers(5, 171))
+    if seed == 0:
+        B = max(B, 2)                                         # room for the empty sequence
+    arch = synth.POST_LN if seed % 2 == 0 else synth.PRE_LN
+    mode = [OL.MODE_M3, OL.MODE_M3, OL.MODE_M2, OL.MODE_M1, OL.MODE_M0, OL.MODE_M3, OL.MODE_M1, OL.MODE_M2][seed]
+    mask = synth.MASK_CAUSAL if arch == synth.PRE_LN else synth.MASK_PADDING
+    shape = _shape(arch, mask, d=H * Dh, H=H, Dh=Dh, f=f, B=B, S=S, kv_lo=1, kv_hi=S)
+    T = B * S
+    p = synth.layer_params(70 + seed, shape)
+    emb = synth.embedding_ln_params(70 + seed, shape)
+    hc = synth.activations(70 + seed, shape, 4 * S, stream=1).astype(np.float64)      # four full calibration sequences
+    if arch == synth.POST_LN:
+        hc = OL._ln64(hc, emb["g"].astype(np.float64), emb["b"].astype(np.float64), shape.eps)
+    sc, _ = OL.calibrate(p, hc, synth.small(shape, mask=synth.MASK_NONE if arch == synth.POST_LN else mask), 4, S)
+    w = OL.prepare(p, sc, shape, mode)
+    desc = _desc(hero, shape, mode)
+    W, keep = upload_weights(hero, w)
+    ws = torch.empty(hero.hero_layer_workspace_bytes(desc, B, S), dtype=torch.uint8, device="cuda")
+    assert ws.numel() > 0
+    h0 = synth.activations(70 + seed, shape, T)
+    print(f"[parity] random layer {seed}: arch {arch} mode {mode} d {H}x{Dh} f {f} B {B} S {S}", end=" ")
+    if arch == synth.POST_LN:
+        kv_len = synth.kv_lengths(70 + seed, shape)
+        kv_len[0] = 1
+        if seed == 0 and B > 1:
+            kv_len[1] = 0
+        xq, xs, xf = O.ln_quant(h0, O.F32, None, None, 0, None, emb["g"], emb["b"], shape.eps, y_hp_dt=O.F32)
+        kw_o = dict(x_q=xq, x_s=xs) if mode & OL.M_QKV else dict(x_hp=O.f32_to_hp(xf, O.BF16))
+        oq, os_ = OL.layer_fwd(w, shape, B, S, kv_len=kv_len, **kw_o)
+        out_q = torch.empty((T, shape.d), dtype=torch.int8, device="cuda")
+        out_s = torch.empty((T,), dtype=torch.float32, device="cuda")
+        kw_g = dict(x_q=dev(xq), x_scale=dev(xs)) if mode & OL.M_QKV else dict(x_hp=dev(kw_o["x_hp"]))
+        hero.hero_layer_fwd(desc, W, B, S, ws, out_q=out_q, out_scale=out_s, kv_len=dev(kv_len), **kw_g)
+        valid = (np.arange(S)[None, :] < kv_len[:, None]).ravel()
+        gq, gs = to_np(out_q)[valid], to_np(out_s)[valid]
+        ident = float(np.mean(gq == oq[valid]))
+        dmax = int(np.abs(gq.astype(int) - oq[valid].astype(int)).max())
+        srel = float(np.max(np.abs(gs - os_[valid]) / os_[valid]))
+        print(f"identical {ident:.5f} max diff {dmax} scale rel {srel:.2e}")
+        floor, dlim, slim = (0.999, 1, 1e-3) if mode == OL.MODE_M3 else (0.97, 3, 1e-2)
+        assert ident >= floor and dmax <= dlim and srel <= slim
+    else:
+        hb = O.f32_to_bf16(h0)
+        ref = O.bf16_to_f32(OL.layer_fwd(w, shape, B, S, h=hb))
+        h = dev(hb)
+        hero.hero_layer_fwd(desc, W, B, S, ws, h=h)
+        e = rel_err(O.bf16_to_f32(to_np(h)), ref)
+        print(f"rel_err {e:.2e}")
+        assert e <= 2e-2
+
+
 def test_module_switch_refuses_subsets_that_need_a_quantization_kernel(hero):
     shape = _shape(synth.POST_LN, synth.MASK_NONE)
     for bad in (OL.M_ATTN, OL.M_QKV | OL.M_ATTN_OUT, OL.M_FC2, OL.M_QKV | OL.M_FC2, OL.MODE_M2 | HB.M_FP8, OL.MODE_M3 | HB.M_FP8 | HB.M_F16):
