@@ -1394,6 +1394,19 @@ hero_status launch_epi(const GemmArgs& g, void* ws, size_t ws_bytes, hipStream_t
             if (t64 <= 128) return launch_grid(g, 64, 32, 128, int8_gemm_kernel<64, 32, 2, 1, 8, 2, EPI, CDT, RDT>, st);
             if (kt % 2 == 0) return launch_grid(g, 64, 64, 512, int8_gemm_kernel<64, 64, 2, 2, 4, 1, EPI, CDT, RDT, false, 2>, st);
         }
+        // Small problems (a BERT-base layer: 128 tokens) are bound by how many compute units stream the weights at
+        // all, so the tiles shrink with the problem.  Measured as the layer runs them (weights in the caches): up to 32
+        // tiles of 64 x 64, 32 x 32 tiles with four K groups (128 x 768 x 3072: 5.5 us against 8.4 for 64 x 64 with
+        // four groups) or, with a short K, two (128 x 768 x 768: 3.9 against 4.4); up to 128 tiles, 64 x 32 tiles with
+        // two K groups (128 x 2304 x 768: 4.2 against 4.6; 128 x 3072 x 768 + GELU^quant: 4.7 against 5.1;
+        // 512 x 1024 x 4096: 8.6 against 10.2); beyond, plain 64 x 64 tiles (512 x 3072 x 1024: 7.2, every smaller
+        // tile slower).
+        if (t64 <= 32 && kt >= 32 && kt % 4 == 0)
+            return launch_grid(g, 32, 32, 256, int8_gemm_kernel<32, 32, 1, 1, 4, 1, EPI, CDT, RDT, false, 4>, st);
+        if (t64 <= 32 && kt % 2 == 0)
+            return launch_grid(g, 32, 32, 128, int8_gemm_kernel<32, 32, 1, 1, 8, 2, EPI, CDT, RDT, false, 2>, st);
+        if (t64 <= 128 && kt % 2 == 0)
+            return launch_grid(g, 64, 32, 256, int8_gemm_kernel<64, 32, 2, 1, 4, 2, EPI, CDT, RDT, false, 2>, st);
         if (t64 <= 128 && kt >= 32 && kt % 4 == 0)
             return launch_grid(g, 64, 64, 1024, int8_gemm_kernel<64, 64, 2, 2, 2, 1, EPI, CDT, RDT, false, 4>, st);
         return launch_grid(g, 64, 64, 256, int8_gemm_kernel<64, 64, 2, 2, 2, 2, EPI, CDT, RDT>, st);
