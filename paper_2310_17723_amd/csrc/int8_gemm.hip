@@ -1342,6 +1342,16 @@ hero_status launch_ovl(const GemmArgs& g, hipStream_t st) {
 // workgroup, 2 = 64x64, 7 = 256x256 persistent, 8 = 128x128 persistent, 9 = 256x128 persistent with the overlapped
 // epilogue (forced by the test entry point hero_int8_gemm_tile only; a forced kernel that cannot run the shape falls
 // back to its one-tile-per-workgroup relative).
+// 256 x 256 tiles, one workgroup per CU, or 128 x 128 tiles, two per CU?  Per full round the small tile is 10-15 % slower
+// (twice the L2 -> LDS traffic), but the large one wastes what its last round leaves empty: 384 tiles on 256 CUs are
+// one and a half rounds (8192 x 3072 x 1024, 16-bit output: 47.3 us against 42.0 with the small tile), 512 tiles are
+// two full ones (8192 x 4096 x 1024: 40.7 against 43.6).  Compare the filled fractions, the small tile's scaled by 0.87.
+inline bool small_tile_fills_better(int64_t t256, int64_t t128) {
+    const double e256 = (double)t256 / (double)(((t256 + 255) / 256) * 256);
+    const double e128 = 0.87 * (double)t128 / (double)(((t128 + 511) / 512) * 512);
+    return e128 > e256;
+}
+
 template <int EPI, int CDT, int RDT>
 hero_status launch_epi(const GemmArgs& g, void* ws, size_t ws_bytes, hipStream_t st, int tile) {
     int cfg = tile;
@@ -1356,7 +1366,7 @@ hero_status launch_epi(const GemmArgs& g, void* ws, size_t ws_bytes, hipStream_t
     const bool ovl_ok = pers_ok && g.K >= 16 * BK && RDT < 0;
     if (cfg < 0) {
         const int64_t t256 = (int64_t)((g.M + 255) / 256) * ((g.N + 255) / 256), t128 = (int64_t)((g.M + 127) / 128) * ((g.N + 127) / 128);
-        if (t256 >= 160) cfg = !pers_ok ? 1 : ((t256 > 256 && t256 < 384) ? 8 : 7);
+        if (t256 >= 160) cfg = !pers_ok ? 1 : (small_tile_fills_better(t256, t128) ? 8 : 7);
         else if (g.M <= 64 || t128 < 192) cfg = 2;
         else cfg = pers_ok ? 8 : 0;
     } else if (cfg == 9 && !ovl_ok) {
@@ -1450,7 +1460,7 @@ hero_status hero_hp_gemm_large(const void* A, int64_t lda, const void* Wt, int64
     g.b_col_scale = nullptr; g.bias = bias; g.residual = residual; g.ldr = ldr; g.out_col_scale = nullptr;
     g.C = C; g.ldc = ldc; g.M = (int)M; g.N = (int)N; g.K = (int)(K * 2);
     g.ksplit = 1; g.kslabs = 0;
-    const int cfg = tile >= 0 ? tile : ((t256 < 160 || (t256 > 256 && t256 < 384)) ? 8 : 7);
+    const int cfg = tile >= 0 ? tile : ((t256 < 160 || small_tile_fills_better(t256, t128)) ? 8 : 7);
     if (cfg == 0) return HERO_ERR_UNSUPPORTED;
     if (dt == HERO_BF16) {
         if (cfg == 8) return launch_hp_persistent<128, 128, 2, 2, HERO_BF16>(g, 2, gelu != 0, st);
@@ -1468,7 +1478,7 @@ hero_status launch_epi_fp8(GemmArgs g, hipStream_t st, int cfg) {
     // cfg: -1 = chosen here; 0 / 7 / 8 forced by the test entry point hero_fp8_gemm_tile
     const bool small = g.M <= 64 || t128 < 192;
     if (pers_ok && (cfg == 7 || cfg == 8 || (cfg < 0 && !small))) {
-        const bool tile128 = cfg == 8 || (cfg < 0 && (t256 < 160 || (t256 > 256 && t256 < 384)));
+        const bool tile128 = cfg == 8 || (cfg < 0 && (t256 < 160 || small_tile_fills_better(t256, t128)));
         g.ntm = tile128 ? (g.M + 127) / 128 : (g.M + 255) / 256; g.ntn = tile128 ? (g.N + 127) / 128 : (g.N + 255) / 256;
         g.per_xcd = (int)(((tile128 ? t128 : t256) + NUM_XCD - 1) / NUM_XCD);
         const int cap = tile128 ? 64 : 32, nslot = g.per_xcd < cap ? g.per_xcd : cap;
