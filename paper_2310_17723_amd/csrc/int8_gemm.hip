@@ -1305,8 +1305,9 @@ hero_status launch_grid(GemmArgs g, int BM, int BN, int threads, K kernel, hipSt
 // Tile choice (all measured on MI355X): the persistent 256x256 direct-to-LDS kernel, one workgroup per CU, once
 // the grid has enough tiles (160) to keep most of the 256 CUs busy; the persistent 128x128 form of the same kernel,
 // two workgroups per CU, below that (with 96-128 tiles of 256x256 half of the CUs would idle: 10-30 % faster there)
-// and where the 256x256 tiles would make a second, mostly empty round (257-383 tiles: 15-20 % faster; per full
-// round the small tile is 10-15 % slower, it needs twice the L2 -> LDS traffic); 64x64 register-staged tiles while
+// and where the last round of 256x256 tiles would be so empty that the small tile fills the chip better
+// (small_tile_fills_better below; per full round the small tile is 10-15 % slower, it needs twice the L2 -> LDS
+// traffic); 64x64 register-staged tiles, or smaller ones, while
 // fewer than 192 tiles of 128x128 exist (small problems are latency-bound: more, shorter workgroups).  The
 // persistent kernels need K >= 256, K % 128 == 0 and 32-bit per-lane offsets; otherwise the one-tile-per-workgroup
 // 256x256 kernel or the register-staged 128x128 one take their place.
