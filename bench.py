@@ -798,6 +798,9 @@ def main():
         log("[bench] measured ceilings (MFMA loops, MFMA + VALU co-issue, HBM streams)")
         rec["roofline"]["measured_ceilings"] = measured_ceilings()
         mc = rec["roofline"]["measured_ceilings"]
+        # beside `frac` (against the nameplate peak): against what a register-only loop of the same matrix instruction
+        # sustains on random operand bytes on this machine, right now
+        rec["roofline"]["frac_of_measured_mfma_rate"] = round(rec["roofline"]["achieved"] / mc["mfma_int8_random_operands_tops"], 4)
         rec["ln_quant"]["frac_of_same_size_copy"] = round(rec["ln_quant"]["gbs"] / mc["copy_24MiB_rotating_gbs"], 4)
         rec["ln_quant_large"]["frac_of_best_large_copy"] = round(rec["ln_quant_large"]["gbs"] / mc["hbm_best_copy_gbs"], 4)
         log("[bench] GEMM sweep")
