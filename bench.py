@@ -162,17 +162,19 @@ class Stack:
         """One pass of the whole stack.  Decode: `steps` tokens, each through every layer."""
         hero, sh = self.hero, self.shape
         B, S = sh.B, sh.S
+        # the hint a caller of a stack gives: what the next call reads first (the next layer's QKV weights)
+        nxt = lambda l: self.keep[(l + 1) % self.layers].get("w_qkv")
         if sh.arch == 0:
             xq, xs = self.x0_q, self.x0_s
             for l in range(self.layers):
                 oq, os_ = self.buf[l & 1]
                 hero.hero_layer_fwd(self.desc, self.weights[l], B, S, self.ws, x_q=xq, x_scale=xs, out_q=oq,
-                                    out_scale=os_, kv_len=self.kv_len)
+                                    out_scale=os_, kv_len=self.kv_len, next_read=nxt(l))
                 xq, xs = oq, os_
         elif self.caches is None:
             self.h.copy_(self.h0)
             for l in range(self.layers):
-                hero.hero_layer_fwd(self.desc, self.weights[l], B, S, self.ws, h=self.h)
+                hero.hero_layer_fwd(self.desc, self.weights[l], B, S, self.ws, h=self.h, next_read=nxt(l))
         else:
             for t in range(sh.steps):
                 self.h.copy_(self.h0)

@@ -363,6 +363,11 @@ typedef struct {
        not read).  out_hp (optional, any mode): the 16-bit copy of the layer output, i.e. the x_hp of a successor
        whose QKV module is 16-bit. */
     const void* x_hp; void* out_hp;
+    /* optional hint (may be NULL / 0; never written, changes no result): device memory that the caller's NEXT call
+       reads first, typically the next layer's w_qkv.  The layer's last GeMM^quant requests its lines while it runs, so
+       that they wait in the cache hierarchy instead of in HBM when the next call's first tiles ask for them.  At most
+       next_read_bytes bytes from next_read are read; 4-byte aligned. */
+    const void* next_read; size_t next_read_bytes;
 } hero_layer_io;
 
 /* Bytes of scratch hero_layer_fwd needs for T = B*S rows of this layer. */

@@ -38,7 +38,8 @@ class LayerWeights(C.Structure):
 
 class LayerIO(C.Structure):
     _fields_ = [("B", i64), ("S", i64), ("x_q", vp), ("x_scale", vp), ("out_q", vp), ("out_scale", vp),
-                ("h", vp), ("kv_len", vp), ("k_cache", vp), ("v_cache", vp), ("Smax", i64), ("x_hp", vp), ("out_hp", vp)]
+                ("h", vp), ("kv_len", vp), ("k_cache", vp), ("v_cache", vp), ("Smax", i64), ("x_hp", vp), ("out_hp", vp),
+                ("next_read", vp), ("next_read_bytes", C.c_size_t)]
 
 
 SYMBOLS = {
@@ -345,10 +346,11 @@ class Hero:
         return int(self.lib.hero_layer_workspace_bytes(C.byref(desc), B, S))
 
     def hero_layer_fwd(self, desc, weights, B, S, workspace, *, x_q=None, x_scale=None, out_q=None, out_scale=None,
-                       h=None, kv_len=None, k_cache=None, v_cache=None, x_hp=None, out_hp=None, stream=None):
+                       h=None, kv_len=None, k_cache=None, v_cache=None, x_hp=None, out_hp=None, next_read=None, stream=None):
         ptr = lambda t: None if t is None else t.data_ptr()
         io = LayerIO(B, S, *(ptr(t) for t in (x_q, x_scale, out_q, out_scale, h, kv_len, k_cache, v_cache)),
-                     k_cache.shape[2] if k_cache is not None else 0, ptr(x_hp), ptr(out_hp))
+                     k_cache.shape[2] if k_cache is not None else 0, ptr(x_hp), ptr(out_hp),
+                     ptr(next_read), 0 if next_read is None else next_read.numel() * next_read.element_size())
         st = self.lib.hero_layer_fwd(C.byref(desc), C.byref(weights), C.byref(io), _ptr(workspace),
                                      workspace.numel() * workspace.element_size(), _stream(stream))
         self._check(st)

@@ -44,6 +44,9 @@ struct GemmArgs {
     // split-K (skinny M): blockIdx.y picks a range of kslabs slabs and writes raw int32 partial sums
     // to its own [M][ldc] plane of C (plane stride M * ldc elements); a second kernel adds the planes
     int ksplit, kslabs;
+    // optional (persistent kernels only): memory the NEXT kernel of the caller's chain will read (a layer's next weight
+    // matrix).  Every tile requests pf_lpt of its pf_lines 128-byte lines once, at the start of its epilogue.
+    const int8_t* pf = nullptr; int pf_lines = 0, pf_lpt = 0;
 };
 
 // Operand types of the main loops.  ADT = HERO_I8: INT8 operands, int32 accumulators.  ADT = HERO_BF16: bf16
@@ -628,8 +631,9 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void int8_gemm_persistent_kernel(G
     constexpr int RING = NS * STAGE;
     constexpr int SVF = 4 * BN;                                  // floats per vector set: column scale, bias, S_a, row scale
     static_assert(BM == BN, "the row-scale vector shares the column vectors' length");
-    static_assert(RING + 2 * SVF * 4 <= 160 * 1024, "LDS budget");
-    __shared__ __attribute__((aligned(1024))) int8_t smem[RING + 2 * SVF * 4];
+    constexpr int PF_OFF = RING + 2 * SVF * 4;                   // 256 bytes per wave where the prefetch requests land (never read)
+    static_assert(PF_OFF + NWAVE * 256 <= 160 * 1024, "LDS budget");
+    __shared__ __attribute__((aligned(1024))) int8_t smem[PF_OFF + NWAVE * 256];
     float* const sv0 = reinterpret_cast<float*>(smem + RING);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -823,6 +827,19 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void int8_gemm_persistent_kernel(G
         for (int kt = 0; kt < KT; kt += 2) {
             iteration(std::false_type{});
             iteration(std::true_type{});
+        }
+        // Prefetch for the caller's next kernel: this tile's share of the lines, one dword of each, through the same
+        // direct loads into a scratch corner of the LDS (no register is written, so nothing has to wait for them; the
+        // waits of the next main loop only count loads issued after these, and the epilogue in between is far
+        // longer than a miss).  What the request brings is the line: into this XCD's L2 and, on its way, into the
+        // memory-side cache, where the next kernel's first tiles would otherwise all miss at once.
+        if (g.pf_lines > 0) {
+            const int w0 = __builtin_amdgcn_readfirstlane(wave) * 64;
+            if (w0 < g.pf_lpt) {
+                const uint32_t line = (uint32_t)min(seq * g.pf_lpt + w0 + lane, g.pf_lines - 1);
+                dma4s(line * 128u, reinterpret_cast<const float*>(g.pf),
+                      __builtin_amdgcn_readfirstlane(lds_offset(smem + PF_OFF)) + (uint32_t)w0 * 4u);
+            }
         }
         // epilogue of this tile; the ring keeps filling with the next tile's slabs meanwhile
         const float* sv = sv0 + par * SVF;
@@ -1313,6 +1330,19 @@ hero_status launch_grid(GemmArgs g, int BM, int BN, int threads, K kernel, hipSt
 // 256x256 kernel or the register-staged 128x128 one take their place.
 // The test hook hero_int8_gemm_tile forces a form: 0 = 128x128 register-staged, 1 = 256x256 one tile per workgroup,
 // 2 = 64x64 (and its skinny relatives), 7 = 256x256 persistent, 8 = 128x128 persistent.
+// the prefetch hint's share per tile: at most one request per lane
+inline void share_prefetch(GemmArgs& g, int64_t tiles, int lanes) {
+    if (g.pf_lines <= 0) return;
+    const int64_t lpt = (g.pf_lines + tiles - 1) / tiles;
+    g.pf_lpt = (int)(lpt < lanes ? lpt : lanes);
+}
+inline void set_prefetch(GemmArgs& g, const void* prefetch, size_t prefetch_bytes) {
+    if (prefetch && prefetch_bytes >= 128 && ((uintptr_t)prefetch & 3) == 0) {   // whole lines inside the region, 32-bit byte offsets
+        g.pf = (const int8_t*)prefetch;
+        g.pf_lines = (int)std::min<size_t>(prefetch_bytes / 128, (size_t)1 << 24);
+    }
+}
+
 template <int BM, int BN, int WM, int WN, int EPI, int CDT, int RDT>
 hero_status launch_persistent(const GemmArgs& g, int wg_per_cu, hipStream_t st) {
     GemmArgs gp = g;
@@ -1320,6 +1350,7 @@ hero_status launch_persistent(const GemmArgs& g, int wg_per_cu, hipStream_t st) 
     const int64_t tiles = (int64_t)gp.ntm * gp.ntn;
     if (tiles > 0x7fffff00LL) return HERO_ERR_SHAPE;
     gp.per_xcd = (int)((tiles + NUM_XCD - 1) / NUM_XCD);
+    share_prefetch(gp, tiles, WM * WN * 64);
     const int cap = 32 * wg_per_cu;                                   // 32 CUs per XCD
     const int nslot = gp.per_xcd < cap ? gp.per_xcd : cap;
     hipLaunchKernelGGL((int8_gemm_persistent_kernel<BM, BN, WM, WN, 4, EPI, CDT, RDT>), dim3((unsigned)(nslot * NUM_XCD)), dim3(WM * WN * 64), 0, st, gp);
@@ -1483,6 +1514,7 @@ hero_status launch_epi_fp8(GemmArgs g, hipStream_t st, int cfg) {
         g.ntm = tile128 ? (g.M + 127) / 128 : (g.M + 255) / 256; g.ntn = tile128 ? (g.N + 127) / 128 : (g.N + 255) / 256;
         g.per_xcd = (int)(((tile128 ? t128 : t256) + NUM_XCD - 1) / NUM_XCD);
         const int cap = tile128 ? 64 : 32, nslot = g.per_xcd < cap ? g.per_xcd : cap;
+        share_prefetch(g, tile128 ? t128 : t256, tile128 ? 256 : 512);
         if (tile128) hipLaunchKernelGGL((int8_gemm_persistent_kernel<128, 128, 2, 2, 4, EPI, CDT, RDT, HERO_F8E4M3>), dim3((unsigned)(nslot * NUM_XCD)), dim3(256), 0, st, g);
         else hipLaunchKernelGGL((int8_gemm_persistent_kernel<256, 256, 2, 4, 4, EPI, CDT, RDT, HERO_F8E4M3>), dim3((unsigned)(nslot * NUM_XCD)), dim3(512), 0, st, g);
         return hero_launch_status();
@@ -1507,7 +1539,8 @@ static hero_status run_fp8_gemm(const void* A, int64_t lda, const float* a_row_s
                                 const float* bias, const void* residual, hero_dtype res_dt, int64_t ldr,
                                 hero_epilogue epi, const float* out_col_scale,
                                 void* C, hero_dtype c_dt, int64_t ldc,
-                                int64_t M, int64_t N, int64_t K, void* stream, int tile) {
+                                int64_t M, int64_t N, int64_t K, void* stream, int tile,
+                                const void* prefetch = nullptr, size_t prefetch_bytes = 0) {
     if (M < 0 || N < 0 || K <= 0) return HERO_ERR_SHAPE;
     if (M > 0x7fffffffLL || N > 0x7fffffffLL || K > 0x7fffffffLL) return HERO_ERR_SHAPE;
     if (K % KMULT != 0) return HERO_ERR_UNSUPPORTED;
@@ -1533,6 +1566,7 @@ static hero_status run_fp8_gemm(const void* A, int64_t lda, const float* a_row_s
     g.bias = bias; g.residual = residual; g.ldr = ldr; g.out_col_scale = out_col_scale;
     g.C = C; g.ldc = ldc; g.M = (int)M; g.N = (int)N; g.K = (int)K;
     g.ksplit = 1; g.kslabs = 0;
+    set_prefetch(g, prefetch, prefetch_bytes);
     hipStream_t st = (hipStream_t)stream;
     switch (epi) {
     case HERO_EPI_REQUANT: return launch_epi_fp8<HERO_EPI_REQUANT, HERO_F8E4M3, -1>(g, st, tile);
@@ -1604,7 +1638,8 @@ static hero_status run_int8_gemm(const int8_t* A, int64_t lda, const float* a_ro
                                  hero_epilogue epi, const float* out_col_scale,
                                  void* C, hero_dtype c_dt, int64_t ldc,
                                  int64_t M, int64_t N, int64_t K,
-                                 void* workspace, size_t workspace_bytes, void* stream, int tile) {
+                                 void* workspace, size_t workspace_bytes, void* stream, int tile,
+                                 const void* prefetch = nullptr, size_t prefetch_bytes = 0) {
     if (workspace && ((uintptr_t)workspace & 255)) return HERO_ERR_WORKSPACE;
     bool noop = false;
     const hero_status cs = check_gemm_args(A, lda, Bt, ldb, b_col_scale, residual, res_dt, ldr, epi, out_col_scale,
@@ -1616,6 +1651,7 @@ static hero_status run_int8_gemm(const int8_t* A, int64_t lda, const float* a_ro
     g.bias = bias; g.residual = residual; g.ldr = ldr; g.out_col_scale = out_col_scale;
     g.C = C; g.ldc = ldc; g.M = (int)M; g.N = (int)N; g.K = (int)K;
     g.ksplit = 1; g.kslabs = 0;
+    set_prefetch(g, prefetch, prefetch_bytes);
     hipStream_t st = (hipStream_t)stream;
     switch (epi) {
     case HERO_EPI_RAW_I32: return launch_epi<HERO_EPI_RAW_I32, HERO_I32, -1>(g, workspace, workspace_bytes, st, tile);
@@ -1632,6 +1668,31 @@ static hero_status run_int8_gemm(const int8_t* A, int64_t lda, const float* a_ro
         return launch_epi<HERO_EPI_DEQUANT, HERO_F16, HERO_F16>(g, workspace, workspace_bytes, st, tile);
     default: return HERO_ERR_UNSUPPORTED;
     }
+}
+
+// hero_int8_gemm_ws for a caller that knows what its chain reads next (hero_layer_fwd: the next module's weights):
+// the large-problem kernels request that memory while they run, the others ignore the hint.  Not part of the C ABI.
+hero_status hero_int8_gemm_prefetching(const int8_t* A, int64_t lda, const float* a_row_scale,
+                                       const int8_t* Bt, int64_t ldb, const float* b_col_scale,
+                                       const float* bias, const void* residual, hero_dtype res_dt, int64_t ldr,
+                                       hero_epilogue epi, const float* out_col_scale,
+                                       void* C, hero_dtype c_dt, int64_t ldc,
+                                       int64_t M, int64_t N, int64_t K,
+                                       void* workspace, size_t workspace_bytes, void* stream,
+                                       const void* prefetch, size_t prefetch_bytes) {
+    return run_int8_gemm(A, lda, a_row_scale, Bt, ldb, b_col_scale, bias, residual, res_dt, ldr, epi, out_col_scale,
+                         C, c_dt, ldc, M, N, K, workspace, workspace_bytes, stream, -1, prefetch, prefetch_bytes);
+}
+
+hero_status hero_fp8_gemm_prefetching(const void* A, int64_t lda, const float* a_row_scale,
+                                      const void* Bt, int64_t ldb, const float* b_col_scale,
+                                      const float* bias, const void* residual, hero_dtype res_dt, int64_t ldr,
+                                      hero_epilogue epi, const float* out_col_scale,
+                                      void* C, hero_dtype c_dt, int64_t ldc,
+                                      int64_t M, int64_t N, int64_t K, void* stream,
+                                      const void* prefetch, size_t prefetch_bytes) {
+    return run_fp8_gemm(A, lda, a_row_scale, Bt, ldb, b_col_scale, bias, residual, res_dt, ldr, epi, out_col_scale,
+                        C, c_dt, ldc, M, N, K, stream, -1, prefetch, prefetch_bytes);
 }
 
 extern "C" hero_status hero_int8_gemm_ws(const int8_t* A, int64_t lda, const float* a_row_scale,

@@ -105,6 +105,24 @@ extern "C" const char* hero_strerror(hero_status s) {
     return "unknown status";
 }
 
+// (int8_gemm.hip) hero_int8_gemm_ws with a hint: memory the chain's next kernel reads, requested while this one runs
+hero_status hero_int8_gemm_prefetching(const int8_t* A, int64_t lda, const float* a_row_scale,
+                                       const int8_t* Bt, int64_t ldb, const float* b_col_scale,
+                                       const float* bias, const void* residual, hero_dtype res_dt, int64_t ldr,
+                                       hero_epilogue epi, const float* out_col_scale,
+                                       void* C, hero_dtype c_dt, int64_t ldc,
+                                       int64_t M, int64_t N, int64_t K,
+                                       void* workspace, size_t workspace_bytes, void* stream,
+                                       const void* prefetch, size_t prefetch_bytes);
+
+hero_status hero_fp8_gemm_prefetching(const void* A, int64_t lda, const float* a_row_scale,
+                                      const void* Bt, int64_t ldb, const float* b_col_scale,
+                                      const float* bias, const void* residual, hero_dtype res_dt, int64_t ldr,
+                                      hero_epilogue epi, const float* out_col_scale,
+                                      void* C, hero_dtype c_dt, int64_t ldc,
+                                      int64_t M, int64_t N, int64_t K, void* stream,
+                                      const void* prefetch, size_t prefetch_bytes);
+
 extern "C" const char* hero_build_arch(void) { return HERO_BUILD_ARCH; }
 
 extern "C" size_t hero_layer_workspace_bytes(const hero_layer_desc* desc, int64_t B, int64_t S) {
@@ -177,8 +195,8 @@ extern "C" hero_status hero_layer_fwd(const hero_layer_desc* desc, const hero_la
         if (pre)
             HERO_TRY(hero_ln_quant_fp8(io->h, HERO_BF16, nullptr, nullptr, F8, nullptr, w->ln1_g, w->ln1_b, desc->eps,
                                        T, d, xin_q, xin_s, nullptr, HERO_BF16, stream));
-        HERO_TRY(hero_fp8_gemm(xin_q, d, xin_s, w->w_qkv, d, w->w_qkv_s, w->b_qkv, nullptr, HERO_BF16, 0,
-                               HERO_EPI_REQUANT, nullptr, qkv, F8, 3 * d, T, 3 * d, d, stream));
+        HERO_TRY(hero_fp8_gemm_prefetching(xin_q, d, xin_s, w->w_qkv, d, w->w_qkv_s, w->b_qkv, nullptr, HERO_BF16, 0,
+                                           HERO_EPI_REQUANT, nullptr, qkv, F8, 3 * d, T, 3 * d, d, stream, w->w_o, (size_t)(d * d)));
         const int64_t qs[4] = {S * 3 * d, 3 * d, Dh, 1};
         const int8_t* qp = (const int8_t*)qkv;
         const int8_t *kp = qp + d, *vp = qp + 2 * d;
@@ -195,26 +213,26 @@ extern "C" hero_status hero_layer_fwd(const hero_layer_desc* desc, const hero_la
         HERO_TRY(hero_fp8_attn(qp, qs, kp, ks, vp, ks, B, H, S, Skv, Dh, w->qk_scale, w->p_scale,
                                w->attn_out_scale, 0, (hero_mask)desc->mask, io->kv_len, attn, F8, d, stream));
         if (!pre) {
-            HERO_TRY(hero_fp8_gemm(attn, d, nullptr, w->w_o, d, w->w_o_s, w->b_o, nullptr, HERO_BF16, 0,
-                                   HERO_EPI_REQUANT, nullptr, xo, F8, d, T, d, d, stream));
+            HERO_TRY(hero_fp8_gemm_prefetching(attn, d, nullptr, w->w_o, d, w->w_o_s, w->b_o, nullptr, HERO_BF16, 0,
+                                               HERO_EPI_REQUANT, nullptr, xo, F8, d, T, d, d, stream, w->w_1, (size_t)(f * d)));
             HERO_TRY(hero_ln_quant_fp8(xin_q, F8, xin_s, xo, F8, w->S_o, w->ln1_g, w->ln1_b, desc->eps, T, d,
                                        mid_q, mid_s, nullptr, HERO_BF16, stream));
         } else {
-            HERO_TRY(hero_fp8_gemm(attn, d, nullptr, w->w_o, d, w->w_o_s, w->b_o, io->h, HERO_BF16, d,
-                                   HERO_EPI_DEQUANT, nullptr, io->h, HERO_BF16, d, T, d, d, stream));
+            HERO_TRY(hero_fp8_gemm_prefetching(attn, d, nullptr, w->w_o, d, w->w_o_s, w->b_o, io->h, HERO_BF16, d,
+                                               HERO_EPI_DEQUANT, nullptr, io->h, HERO_BF16, d, T, d, d, stream, w->w_1, (size_t)(f * d)));
             HERO_TRY(hero_ln_quant_fp8(io->h, HERO_BF16, nullptr, nullptr, F8, nullptr, w->ln2_g, w->ln2_b, desc->eps,
                                        T, d, mid_q, mid_s, nullptr, HERO_BF16, stream));
         }
-        HERO_TRY(hero_fp8_gemm(mid_q, d, mid_s, w->w_1, d, w->w_1_s, w->b_1, nullptr, HERO_BF16, 0,
-                               HERO_EPI_GELU_REQUANT, w->S_a, act, F8, f, T, f, d, stream));
+        HERO_TRY(hero_fp8_gemm_prefetching(mid_q, d, mid_s, w->w_1, d, w->w_1_s, w->b_1, nullptr, HERO_BF16, 0,
+                                           HERO_EPI_GELU_REQUANT, w->S_a, act, F8, f, T, f, d, stream, w->w_2, (size_t)(d * f)));
         if (!pre) {
-            HERO_TRY(hero_fp8_gemm(act, f, nullptr, w->w_2, f, w->w_2_s, w->b_2, nullptr, HERO_BF16, 0,
-                                   HERO_EPI_REQUANT, nullptr, x2, F8, d, T, d, f, stream));
+            HERO_TRY(hero_fp8_gemm_prefetching(act, f, nullptr, w->w_2, f, w->w_2_s, w->b_2, nullptr, HERO_BF16, 0,
+                                               HERO_EPI_REQUANT, nullptr, x2, F8, d, T, d, f, stream, io->next_read, io->next_read_bytes));
             HERO_TRY(hero_ln_quant_fp8(mid_q, F8, mid_s, x2, F8, w->S_x2, w->ln2_g, w->ln2_b, desc->eps, T, d,
                                        io->out_q, io->out_scale, nullptr, HERO_BF16, stream));
         } else {
-            HERO_TRY(hero_fp8_gemm(act, f, nullptr, w->w_2, f, w->w_2_s, w->b_2, io->h, HERO_BF16, d,
-                                   HERO_EPI_DEQUANT, nullptr, io->h, HERO_BF16, d, T, d, f, stream));
+            HERO_TRY(hero_fp8_gemm_prefetching(act, f, nullptr, w->w_2, f, w->w_2_s, w->b_2, io->h, HERO_BF16, d,
+                                               HERO_EPI_DEQUANT, nullptr, io->h, HERO_BF16, d, T, d, f, stream, io->next_read, io->next_read_bytes));
         }
         return HERO_OK;
     }
@@ -225,9 +243,10 @@ extern "C" hero_status hero_layer_fwd(const hero_layer_desc* desc, const hero_la
                                T, d, xin_q, xin_s, q_i8 ? nullptr : xin_hp, HP, stream));
     // (2) QKV: SQ codes for an INT8 attention (bare Round), 16-bit values otherwise
     if (q_i8)
-        HERO_TRY(hero_int8_gemm_ws(xin_q, d, xin_s, w->w_qkv, d, w->w_qkv_s, w->b_qkv, nullptr, HP, 0,
-                                attn_i8 ? HERO_EPI_REQUANT : HERO_EPI_DEQUANT, nullptr,
-                                qkv, attn_i8 ? HERO_I8 : HP, 3 * d, T, 3 * d, d, gws, ws.gemm_ws_bytes, stream));
+        HERO_TRY(hero_int8_gemm_prefetching(xin_q, d, xin_s, w->w_qkv, d, w->w_qkv_s, w->b_qkv, nullptr, HP, 0,
+                                            attn_i8 ? HERO_EPI_REQUANT : HERO_EPI_DEQUANT, nullptr,
+                                            qkv, attn_i8 ? HERO_I8 : HP, 3 * d, T, 3 * d, d, gws, ws.gemm_ws_bytes, stream,
+                                            o_i8 ? w->w_o : nullptr, (size_t)(d * d)));
     else
         HERO_TRY(hero_hp_gemm(xin_hp, d, w->w_qkv_hp, d, w->b_qkv, nullptr, 0, 0, qkv, 3 * d, T, 3 * d, d, HP, stream));
     // (3) attention
@@ -259,16 +278,18 @@ extern "C" hero_status hero_layer_fwd(const hero_layer_desc* desc, const hero_la
     const hero_dtype x1_dt = q_i8 ? HERO_I8 : HP;
     if (!pre) {
         if (o_i8)
-            HERO_TRY(hero_int8_gemm_ws((const int8_t*)attn, d, nullptr, w->w_o, d, w->w_o_s, w->b_o, nullptr, HP, 0,
-                                    HERO_EPI_REQUANT, nullptr, xo, HERO_I8, d, T, d, d, gws, ws.gemm_ws_bytes, stream));
+            HERO_TRY(hero_int8_gemm_prefetching((const int8_t*)attn, d, nullptr, w->w_o, d, w->w_o_s, w->b_o, nullptr, HP, 0,
+                                                HERO_EPI_REQUANT, nullptr, xo, HERO_I8, d, T, d, d, gws, ws.gemm_ws_bytes, stream,
+                                                fc1_i8 ? w->w_1 : nullptr, (size_t)(f * d)));
         else
             HERO_TRY(hero_hp_gemm(attn, d, w->w_o_bf16, d, w->b_o, nullptr, 0, 0, xo, d, T, d, d, HP, stream));
         HERO_TRY(hero_ln_quant(x1, x1_dt, q_i8 ? xin_s : nullptr, xo, o_i8 ? HERO_I8 : HP, o_i8 ? w->S_o : nullptr,
                                w->ln1_g, w->ln1_b, desc->eps, T, d, mid_q, mid_s, fc1_i8 ? nullptr : mid_hp, HP, stream));
     } else {
         if (o_i8)
-            HERO_TRY(hero_int8_gemm_ws((const int8_t*)attn, d, nullptr, w->w_o, d, w->w_o_s, w->b_o, io->h, HP, d,
-                                    HERO_EPI_DEQUANT, nullptr, io->h, HP, d, T, d, d, gws, ws.gemm_ws_bytes, stream));
+            HERO_TRY(hero_int8_gemm_prefetching((const int8_t*)attn, d, nullptr, w->w_o, d, w->w_o_s, w->b_o, io->h, HP, d,
+                                                HERO_EPI_DEQUANT, nullptr, io->h, HP, d, T, d, d, gws, ws.gemm_ws_bytes, stream,
+                                                fc1_i8 ? w->w_1 : nullptr, (size_t)(f * d)));
         else
             HERO_TRY(hero_hp_gemm(attn, d, w->w_o_bf16, d, w->b_o, io->h, d, 0, io->h, d, T, d, d, HP, stream));
         HERO_TRY(hero_ln_quant(io->h, HP, nullptr, nullptr, HERO_I8, nullptr, w->ln2_g, w->ln2_b, desc->eps,
@@ -276,16 +297,18 @@ extern "C" hero_status hero_layer_fwd(const hero_layer_desc* desc, const hero_la
     }
     // (5) FC1 + GELU: GELU^quant codes for an INT8 FC2 (X_1 stays in registers), 16-bit values otherwise
     if (fc1_i8)
-        HERO_TRY(hero_int8_gemm_ws(mid_q, d, mid_s, w->w_1, d, w->w_1_s, w->b_1, nullptr, HP, 0,
-                                fc2_i8 ? HERO_EPI_GELU_REQUANT : HERO_EPI_DEQUANT_GELU, w->S_a,
-                                act, fc2_i8 ? HERO_I8 : HP, f, T, f, d, gws, ws.gemm_ws_bytes, stream));
+        HERO_TRY(hero_int8_gemm_prefetching(mid_q, d, mid_s, w->w_1, d, w->w_1_s, w->b_1, nullptr, HP, 0,
+                                            fc2_i8 ? HERO_EPI_GELU_REQUANT : HERO_EPI_DEQUANT_GELU, w->S_a,
+                                            act, fc2_i8 ? HERO_I8 : HP, f, T, f, d, gws, ws.gemm_ws_bytes, stream,
+                                            fc2_i8 ? w->w_2 : nullptr, (size_t)(d * f)));
     else
         HERO_TRY(hero_hp_gemm(mid_hp, d, w->w_1_hp, d, w->b_1, nullptr, 0, 1, act, f, T, f, d, HP, stream));
     // (6) FC2 and the closing LN^quant (POST_LN) or residual add (PRE_LN)
     if (!pre) {
         if (fc2_i8)
-            HERO_TRY(hero_int8_gemm_ws((const int8_t*)act, f, nullptr, w->w_2, f, w->w_2_s, w->b_2, nullptr, HP, 0,
-                                    HERO_EPI_REQUANT, nullptr, x2, HERO_I8, d, T, d, f, gws, ws.gemm_ws_bytes, stream));
+            HERO_TRY(hero_int8_gemm_prefetching((const int8_t*)act, f, nullptr, w->w_2, f, w->w_2_s, w->b_2, nullptr, HP, 0,
+                                                HERO_EPI_REQUANT, nullptr, x2, HERO_I8, d, T, d, f, gws, ws.gemm_ws_bytes, stream,
+                                                io->next_read, io->next_read_bytes));
         else
             HERO_TRY(hero_hp_gemm(act, f, w->w_2_bf16, f, w->b_2, nullptr, 0, 0, x2, d, T, d, f, HP, stream));
         HERO_TRY(hero_ln_quant(fc1_i8 ? (const void*)mid_q : (const void*)mid_hp, fc1_i8 ? HERO_I8 : HP, fc1_i8 ? mid_s : nullptr,
@@ -293,8 +316,9 @@ extern "C" hero_status hero_layer_fwd(const hero_layer_desc* desc, const hero_la
                                io->out_q, io->out_scale, io->out_hp, HP, stream));
     } else {
         if (fc2_i8)
-            HERO_TRY(hero_int8_gemm_ws((const int8_t*)act, f, nullptr, w->w_2, f, w->w_2_s, w->b_2, io->h, HP, d,
-                                    HERO_EPI_DEQUANT, nullptr, io->h, HP, d, T, d, f, gws, ws.gemm_ws_bytes, stream));
+            HERO_TRY(hero_int8_gemm_prefetching((const int8_t*)act, f, nullptr, w->w_2, f, w->w_2_s, w->b_2, io->h, HP, d,
+                                                HERO_EPI_DEQUANT, nullptr, io->h, HP, d, T, d, f, gws, ws.gemm_ws_bytes, stream,
+                                                io->next_read, io->next_read_bytes));
         else
             HERO_TRY(hero_hp_gemm(act, f, w->w_2_bf16, f, w->b_2, io->h, d, 0, io->h, d, T, d, f, HP, stream));
     }

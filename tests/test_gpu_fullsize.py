@@ -251,6 +251,20 @@ def test_bert_large_layer_batch_slice(hero):
     assert np.allclose(gs, os_[valid], rtol=4e-3)
     assert np.abs(gq.astype(int) - oq[valid].astype(int)).max() <= 3
     assert np.mean(gq == oq[valid]) >= 0.999
+    # The same four sequences twice (8 x 512 rows: QKV and FC1 now run the 256 x 256 persistent tiles, the other
+    # two GEMMs the 128 x 128 ones), with the caller's hint about what it reads next: a sequence's result depends on
+    # nothing but the sequence, and the hint changes no value, so every copy equals the first run bit for bit.
+    B2, T2 = 2 * B, 2 * T
+    ws2 = torch.empty(hero.hero_layer_workspace_bytes(desc, B2, S), dtype=torch.uint8, device="cuda")
+    out_q2 = torch.empty((T2, shape.d), dtype=torch.int8, device="cuda")
+    out_s2 = torch.empty((T2,), dtype=torch.float32, device="cuda")
+    nxt = torch.zeros(3 * shape.d * shape.d + 100, dtype=torch.int8, device="cuda")       # (not a whole number of lines)
+    hero.hero_layer_fwd(desc, W, B2, S, ws2, x_q=dev(np.concatenate([xq, xq])), x_scale=dev(np.concatenate([xs, xs])),
+                        out_q=out_q2, out_scale=out_s2, kv_len=dev(np.concatenate([kv_len, kv_len])), next_read=nxt)
+    g2, s2 = to_np(out_q2), to_np(out_s2)
+    for c in range(2):
+        assert np.array_equal(g2[c * T:(c + 1) * T][valid], gq) and np.array_equal(s2[c * T:(c + 1) * T][valid], gs)
+    assert not to_np(nxt).any()                                                            # the hint is only read
 
 
 def test_bert_large_layer_batch_slice_fp8(hero):
@@ -272,7 +286,8 @@ def test_bert_large_layer_batch_slice_fp8(hero):
     ws = torch.empty(hero.hero_layer_workspace_bytes(desc, B, S), dtype=torch.uint8, device="cuda")
     out_q = torch.empty((T, shape.d), dtype=torch.uint8, device="cuda")
     out_s = torch.empty((T,), dtype=torch.float32, device="cuda")
-    hero.hero_layer_fwd(desc, W, B, S, ws, x_q=dev(xq), x_scale=dev(xs), out_q=out_q, out_scale=out_s, kv_len=dev(kv_len))
+    hero.hero_layer_fwd(desc, W, B, S, ws, x_q=dev(xq), x_scale=dev(xs), out_q=out_q, out_scale=out_s, kv_len=dev(kv_len),
+                        next_read=keep["w_qkv"])                     # (with the caller's hint: it changes no value)
     valid = (np.arange(S)[None, :] < kv_len[:, None]).ravel()
     ref = (O.e4m3_to_f32(oq).astype(np.float64) * os_[:, None])[valid]
     got = (O.e4m3_to_f32(to_np(out_q)).astype(np.float64) * to_np(out_s)[:, None])[valid]
