@@ -229,7 +229,7 @@ def fc1_roofline(hero, shape, seed, iters=20, tile=None):
     ms = time_gpu(fn, iters)
     ops = 2.0 * M * N * K
     tops = ops / (ms * 1e-3) / 1e12
-    return {"bound": "mfma", "kernel": "int8_gemm_persistent_kernel<GELU_REQUANT> (FC1)", "shape_mnk": [M, N, K],
+    return {"bound": "mfma", "kernel": ("int8_gemm_ovl_kernel" if K < 2048 and tile in (None, 9) else "int8_gemm_persistent_kernel") + "<GELU_REQUANT> (FC1)", "shape_mnk": [M, N, K],
             "achieved": round(tops, 2), "peak": PEAK_INT8_TOPS, "unit": "TOP/s", "frac": round(tops / PEAK_INT8_TOPS, 4),
             "avg_launch_us": round(ms * 1e3, 2), "ops_per_launch": ops, "timing": "median of 5 x 20 launches, HIP events",
             "algorithmic_bytes": M * K + N * K + M * N + 4 * (M + 3 * N),

@@ -900,8 +900,9 @@ __global__ __launch_bounds__(512, 2) void int8_gemm_ovl_kernel(GemmArgs g) {
     constexpr int SPREAD = 16;                                   // slabs of the next tile the epilogue is spread over
     constexpr int NSTEP = 16, NPIECE = 8;                        // 8 pieces of 8 outputs per lane, 16 steps each
     static_assert(NPIECE * NSTEP == SPREAD * 2 * NM, "one epilogue step behind every matrix instruction");
-    static_assert(RING + NSV * SVF * 4 <= 160 * 1024, "LDS budget");
-    __shared__ __attribute__((aligned(1024))) int8_t smem[RING + NSV * SVF * 4];
+    constexpr int PF_OFF = RING + NSV * SVF * 4;                 // 256 bytes per wave where the prefetch requests land (never read)
+    static_assert(PF_OFF + NWAVE * 256 <= 160 * 1024, "LDS budget");
+    __shared__ __attribute__((aligned(1024))) int8_t smem[PF_OFF + NWAVE * 256];
     float* const sv0 = reinterpret_cast<float*>(smem + RING);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -956,6 +957,12 @@ __global__ __launch_bounds__(512, 2) void int8_gemm_ovl_kernel(GemmArgs g) {
             dma4s((uint32_t)min(vch + lane, lim) * 4u, vsrc + org, vdst + bo);
         }
         if (von2) dma4s((uint32_t)min(128 + wu * 64 + lane, g.M - 1 - m0i) * 4u, g.a_row_scale + m0i, vdst2 + bo);
+        // the prefetch hint (see the persistent kernel): this tile's share of the lines the caller's next kernel reads.
+        // Like the vectors the requests are older than every slab of the tile, and five slabs pass before a wait
+        // asks for them.
+        if (g.pf_lines > 0 && wu * 64 < g.pf_lpt)
+            dma4s((uint32_t)min(iseq * g.pf_lpt + wu * 64 + lane, g.pf_lines - 1) * 128u, reinterpret_cast<const float*>(g.pf),
+                  __builtin_amdgcn_readfirstlane(lds_offset(smem + PF_OFF)) + (uint32_t)wu * 256u);
     };
     // The stream moves in PAIRS of slabs (128 bytes of every row = one cache line): load j of a pair is unit
     // j / 2 of slab j % 2, so the two 64-byte halves of a line are requested back to back.
@@ -1366,6 +1373,7 @@ hero_status launch_ovl(const GemmArgs& g, hipStream_t st) {
     if (tiles > 0x7fffff00LL) return HERO_ERR_SHAPE;
     gp.per_xcd = (int)((tiles + NUM_XCD - 1) / NUM_XCD);
     const int nslot = gp.per_xcd < 32 ? gp.per_xcd : 32;              // one workgroup per CU (152 KB of LDS), 32 CUs per XCD
+    share_prefetch(gp, tiles, 512);
     hipLaunchKernelGGL((int8_gemm_ovl_kernel<EPI, CDT>), dim3((unsigned)(nslot * NUM_XCD)), dim3(512), 0, st, gp);
     return hero_launch_status();
 }
@@ -1406,6 +1414,13 @@ hero_status launch_epi(const GemmArgs& g, void* ws, size_t ws_bytes, hipStream_t
     } else if ((cfg == 7 || cfg == 8) && !pers_ok) {
         cfg = cfg == 7 ? 1 : 0;
     }
+    // A GELU epilogue behind a short K goes to the overlapped-epilogue kernel: timed alone with resident operands it
+    // is 3 % behind the 256 x 256 tile (95 against 92.5 us at 16384 x 4096 x 1024), but in a layer the weights come
+    // from HBM and its six slabs of lookahead lose 4 us to that where the other loses 13 (rotating operands: 99.5
+    // against 105.2 us; the 24-layer BERT-large stack 7.95 -> 7.75 ms).  From K = 4096 on its slower main loop
+    // costs more than the hidden epilogue saves (GPT prefill, FC1 16384 x 16384 x 4096: +11 %).
+    constexpr bool GELU_EPI = EPI == HERO_EPI_GELU_REQUANT || EPI == HERO_EPI_DEQUANT_GELU;
+    if (GELU_EPI && tile < 0 && cfg == 7 && ovl_ok && g.K < 2048) cfg = 9;
     if constexpr (RDT < 0) { if (cfg == 9) return launch_ovl<EPI, CDT>(g, st); }
     if (cfg == 7) return launch_persistent<256, 256, 2, 4, EPI, CDT, RDT>(g, 1, st);
     if (cfg == 8) return launch_persistent<128, 128, 2, 2, EPI, CDT, RDT>(g, 2, st);
