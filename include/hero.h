@@ -366,7 +366,8 @@ typedef struct {
     /* optional hint (may be NULL / 0; never written, changes no result): device memory that the caller's NEXT call
        reads first, typically the next layer's w_qkv.  The layer's last GeMM^quant requests its lines while it runs, so
        that they wait in the cache hierarchy instead of in HBM when the next call's first tiles ask for them.  At most
-       next_read_bytes bytes from next_read are read; 4-byte aligned. */
+       next_read_bytes bytes from next_read are read; 4-byte aligned; a region above 8 MB is ignored (it would not
+       survive in the cache until it is used). */
     const void* next_read; size_t next_read_bytes;
 } hero_layer_io;
 

@@ -1343,10 +1343,13 @@ inline void share_prefetch(GemmArgs& g, int64_t tiles, int lanes) {
     const int64_t lpt = (g.pf_lines + tiles - 1) / tiles;
     g.pf_lpt = (int)(lpt < lanes ? lpt : lanes);
 }
+// Only regions of at most 8 MB are requested: a BERT-large weight matrix (1-4 MB) waits in the memory-side cache until
+// its kernel starts and saves it 5-7 us of simultaneous first misses; GPT's 16-64 MB matrices are pushed out again by
+// the activations written in between (FC1 alone writes 268 MB), and requesting them cost 0.3 % of the layer.
 inline void set_prefetch(GemmArgs& g, const void* prefetch, size_t prefetch_bytes) {
-    if (prefetch && prefetch_bytes >= 128 && ((uintptr_t)prefetch & 3) == 0) {   // whole lines inside the region, 32-bit byte offsets
+    if (prefetch && prefetch_bytes >= 128 && prefetch_bytes <= ((size_t)8 << 20) && ((uintptr_t)prefetch & 3) == 0) {
         g.pf = (const int8_t*)prefetch;
-        g.pf_lines = (int)std::min<size_t>(prefetch_bytes / 128, (size_t)1 << 24);
+        g.pf_lines = (int)(prefetch_bytes / 128);                // whole lines inside the region
     }
 }
 
