@@ -1422,6 +1422,8 @@ hero_status launch_epi(const GemmArgs& g, void* ws, size_t ws_bytes, hipStream_t
     // from HBM and its six slabs of lookahead lose 4 us to that where the other loses 13 (rotating operands: 99.5
     // against 105.2 us; the 24-layer BERT-large stack 7.95 -> 7.75 ms).  From K = 4096 on its slower main loop
     // costs more than the hidden epilogue saves (GPT prefill, FC1 16384 x 16384 x 4096: +11 %).
+    // Forcing each of the layer's other GEMMs (QKV, attention-output, FC2) to this kernel or to the 128 x 128 tiles
+    // inside the stack made every one of them slower (7.46 -> 7.50-7.67 ms per 24 layers).
     constexpr bool GELU_EPI = EPI == HERO_EPI_GELU_REQUANT || EPI == HERO_EPI_DEQUANT_GELU;
     if (GELU_EPI && tile < 0 && cfg == 7 && ovl_ok && g.K < 2048) cfg = 9;
     if constexpr (RDT < 0) { if (cfg == 9) return launch_ovl<EPI, CDT>(g, st); }
