@@ -76,3 +76,32 @@ def test_argument_errors_come_before_any_launch(lib):
                                    128, 4096, 16384, None) == 5
     assert L.hero_int8_gemm_static(None, 64, None, None, 64, None, None, None, 0, 0, 0, None, None, 2, 64, 8, 8, 64, None) == 1
     assert "built-in scratch" in lib.strerror(5)
+
+
+def test_binding_structs_match_the_header_layout(tmp_path):
+    """The three structs of hero_layer_fwd as gcc lays them out from include/hero.h against the binding's ctypes
+    mirrors: size and the offset of every field (a field added to one side only would shift everything behind it)."""
+    import subprocess
+    from paper_2310_17723_amd import binding
+    structs = {"hero_layer_desc": binding.LayerDesc, "hero_layer_weights": binding.LayerWeights, "hero_layer_io": binding.LayerIO}
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "hero.h"', 'int main(void) {']
+    for cname, ct in structs.items():
+        lines.append(f'  printf("{cname} size %zu\\n", sizeof({cname}));')
+        for f, _ in ct._fields_:
+            lines.append(f'  printf("{cname} {f} %zu\\n", offsetof({cname}, {f}));')
+    lines += ['  return 0;', '}']
+    src, exe = tmp_path / "layout.c", tmp_path / "layout"
+    src.write_text("\n".join(lines))
+    subprocess.run(["gcc", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split("\n")
+    seen = {(a, b): int(c) for a, b, c in (l.split() for l in out if l.strip())}
+    for cname, ct in structs.items():
+        assert seen[(cname, "size")] == C.sizeof(ct), cname
+        for f, _ in ct._fields_:
+            assert seen[(cname, f)] == getattr(ct, f).offset, f"{cname}.{f}"
+    # and no field of the header is missing from the binding
+    text = re.sub(r"/\*.*?\*/", "", open(os.path.join(ROOT, "include", "hero.h")).read(), flags=re.S)
+    for cname, ct in structs.items():
+        body = re.search(r"typedef struct \{([^}]*)\}\s*" + cname + ";", text).group(1)
+        fields = re.findall(r"\b([A-Za-z_][A-Za-z0-9_]*)\s*[;,]", body)
+        assert sorted(fields) == sorted(f for f, _ in ct._fields_), cname
