@@ -758,7 +758,9 @@ def main():
     mode = {"M1": HB.MODE_M1, "M2": HB.MODE_M2, "M3": HB.MODE_M3}[args.mode]
     decode = shape.cache_len > 0
     steps = args.steps if args.steps is not None else (1 if decode else 10)
-    warmup = args.warmup if args.warmup is not None else (1 if decode else 3)
+    # default warm-up: long enough (about 45 ms of the BERT-large stack) that the timed steps begin behind the slow
+    # first ~35 ms this GPU shows after every idle period (see time_gpu)
+    warmup = args.warmup if args.warmup is not None else (1 if decode else 6)
 
     log(f"[bench] preparing {shape.name} ({args.mode}) ...")
     if args.fp8 and args.mode != "M3":
