@@ -27,6 +27,27 @@ static inline hero_status hero_launch_status() {
     return hipGetLastError() == hipSuccess ? HERO_OK : HERO_ERR_LAUNCH;
 }
 
+// ---- internal to the library (not part of the C ABI): the GeMM^quant entry points with a hint for callers that know
+// what their chain reads next (hero_layer_fwd: the next module's weight matrix).  The large-problem kernels request
+// that memory while they run, so that it waits in the cache hierarchy when the next kernel starts; the other kernels
+// ignore the hint; no result depends on it.  Defined in int8_gemm.hip.
+hero_status hero_int8_gemm_prefetching(const int8_t* A, int64_t lda, const float* a_row_scale,
+                                       const int8_t* Bt, int64_t ldb, const float* b_col_scale,
+                                       const float* bias, const void* residual, hero_dtype res_dt, int64_t ldr,
+                                       hero_epilogue epi, const float* out_col_scale,
+                                       void* C, hero_dtype c_dt, int64_t ldc,
+                                       int64_t M, int64_t N, int64_t K,
+                                       void* workspace, size_t workspace_bytes, void* stream,
+                                       const void* prefetch, size_t prefetch_bytes);
+
+hero_status hero_fp8_gemm_prefetching(const void* A, int64_t lda, const float* a_row_scale,
+                                      const void* Bt, int64_t ldb, const float* b_col_scale,
+                                      const float* bias, const void* residual, hero_dtype res_dt, int64_t ldr,
+                                      hero_epilogue epi, const float* out_col_scale,
+                                      void* C, hero_dtype c_dt, int64_t ldc,
+                                      int64_t M, int64_t N, int64_t K, void* stream,
+                                      const void* prefetch, size_t prefetch_bytes);
+
 // ---- 16-bit float storage (round to nearest even) -------------------------------------
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
 typedef __bf16 v2bf __attribute__((ext_vector_type(2)));

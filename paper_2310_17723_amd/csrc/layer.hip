@@ -105,24 +105,6 @@ extern "C" const char* hero_strerror(hero_status s) {
     return "unknown status";
 }
 
-// (int8_gemm.hip) hero_int8_gemm_ws with a hint: memory the chain's next kernel reads, requested while this one runs
-hero_status hero_int8_gemm_prefetching(const int8_t* A, int64_t lda, const float* a_row_scale,
-                                       const int8_t* Bt, int64_t ldb, const float* b_col_scale,
-                                       const float* bias, const void* residual, hero_dtype res_dt, int64_t ldr,
-                                       hero_epilogue epi, const float* out_col_scale,
-                                       void* C, hero_dtype c_dt, int64_t ldc,
-                                       int64_t M, int64_t N, int64_t K,
-                                       void* workspace, size_t workspace_bytes, void* stream,
-                                       const void* prefetch, size_t prefetch_bytes);
-
-hero_status hero_fp8_gemm_prefetching(const void* A, int64_t lda, const float* a_row_scale,
-                                      const void* Bt, int64_t ldb, const float* b_col_scale,
-                                      const float* bias, const void* residual, hero_dtype res_dt, int64_t ldr,
-                                      hero_epilogue epi, const float* out_col_scale,
-                                      void* C, hero_dtype c_dt, int64_t ldc,
-                                      int64_t M, int64_t N, int64_t K, void* stream,
-                                      const void* prefetch, size_t prefetch_bytes);
-
 extern "C" const char* hero_build_arch(void) { return HERO_BUILD_ARCH; }
 
 extern "C" size_t hero_layer_workspace_bytes(const hero_layer_desc* desc, int64_t B, int64_t S) {
