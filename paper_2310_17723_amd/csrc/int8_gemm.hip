@@ -871,8 +871,9 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void int8_gemm_persistent_kernel(G
 // where it costs 25 us behind the 256 x 256 tile -- but the main loop of the smaller tile is slower by about as much
 // (92 us against 76 us: 1.33 x the LDS fragment reads per matrix instruction and 1.5 x the direct-load bytes on a
 // load stream that is latency-bound), so the two kernels end within 2 % of each other (99 / 101 us with
-// GELU^quant).  The tile choice therefore keeps the 256 x 256 kernel; this one is reached through the test entry
-// point (tile code 9) and stays as the measured answer to "can the epilogue be hidden".
+// GELU^quant) when both are timed alone with operands that stay in the memory-side cache.  Inside a layer the
+// weights come from HBM, and there the deeper ring decides: this kernel is the tile choice's pick for a GELU epilogue
+// with K < 2048 (the numbers are beside the rule in launch_epi); the test entry point reaches it as tile code 9.
 // =====================================================================================
 // wait for vmcnt <= N and for every LDS access of this wave, then the workgroup barrier.  Inline assembly: the
 // kernel below has global stores inside its main loop, and a __syncthreads() there would make the compiler
