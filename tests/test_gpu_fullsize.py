@@ -269,6 +269,13 @@ def test_bert_large_layer_batch_slice(hero):
     assert np.abs(g2[:T][valid].astype(int) - oq[valid].astype(int)).max() <= 3
     assert np.mean(g2[:T][valid] == oq[valid]) >= 0.999
     assert not to_np(nxt).any()                                                            # the hint is only read
+    # hints the library ignores (less than a line, not 4-byte aligned, more than 8 MB) or takes in part: same output
+    big = torch.zeros(9 << 20, dtype=torch.int8, device="cuda")
+    for hint in (nxt[:100], nxt[1:4097], big, big[: (8 << 20)], nxt[:128]):
+        o3, s3 = torch.empty_like(out_q2), torch.empty_like(out_s2)
+        hero.hero_layer_fwd(desc, W, B2, S, ws2, x_q=dev(np.concatenate([xq, xq])), x_scale=dev(np.concatenate([xs, xs])),
+                            out_q=o3, out_scale=s3, kv_len=dev(np.concatenate([kv_len, kv_len])), next_read=hint)
+        assert np.array_equal(to_np(o3)[:T][valid], g2[:T][valid]) and np.array_equal(to_np(s3)[:T][valid], s2[:T][valid])
 
 
 def test_bert_large_layer_batch_slice_fp8(hero):
